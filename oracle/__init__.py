@@ -1,0 +1,19 @@
+"""fp64 CPU oracle of the TIDE router hot path (test infrastructure only).
+
+Only the tests, the smoke check and the benchmark's cpu_baseline leg may import
+this package; the product library neither imports nor links it.
+"""
+from .tide_oracle import (  # noqa: F401
+    DTYPE_CODES,
+    build,
+    exit_from_fire,
+    fires,
+    max_threads,
+    rmsnorm,
+    router_eval,
+    select_exit,
+    set_threads,
+    sigmoid,
+    silu,
+    widen,
+)
