@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Benchmark of the TIDE router hot path on one MI355X.
+
+One "step" = one pass of the whole path -- RMSNorm, router, threshold and earliest-exit
+selection -- over one batch of the 8B-shaped bf16 prefill workload (C=8 checkpoints x
+T=4096 tokens x d=4096, seeded synthetic hidden states already resident in HBM), through
+the C ABI call tide_select_exit (raw fp32 router weights: the gain fold / weight packing
+pass is inside the timed region).  Prints ONE JSON line.
+
+  value      tokens/s through all C checkpoints (whole job, inputs resident)
+  roofline   the prefill kernel alone (tide_select_exit_packed = exactly one launch per
+             step), algorithmic bytes / HIP-event time per launch, against 8 TB/s
+  cpu_baseline  the fp64 oracle on the same workload on this machine's host cores
+  decode     config-2 latency (fp16, T=1 and T=8), us per call
+
+Input buffers rotate so that consecutive steps never re-read a buffer that could still
+sit in the 256 MB last-level cache.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--buffers", type=int, default=4, help="distinct input batches rotated through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (the router path shards by tokens with no "
+              "exchange; no multi-GPU run exists to measure). Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2603_21365_amd import synth
+    from paper_2603_21365_amd import tide_route as tr
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    tr.load_library()
+    w = synth.config1()
+    C, T, d = w.C, w.T, w.d
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    # ---- inputs: `buffers` independent batches of the same generator (different seed streams)
+    host_batches, batches = [], []
+    for i in range(args.buffers):
+        hb = synth.make_hidden(w.cfg + 100 * i, C, T, d, w.dtype)
+        if i == 0:
+            host_batches.append(hb)
+        batches.append(torch.from_numpy(hb.view(np.int16)).cuda().view(torch.bfloat16))
+    rt = w.routers()
+    g, W1, b1, w2 = dev(rt.gamma), dev(rt.W1), dev(rt.b1), dev(rt.w2)
+
+    # b2 for the ~30 % firing rate, from this implementation's own b2 = 0 logits of batch 0
+    _, z0, _ = tr.select_exit(batches[0], g, w.eps, W1, b1, w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers)
+    torch.cuda.synchronize()
+    rt.b2 = synth.calibrate_b2(z0.cpu().numpy(), w.fire_rate)
+
+    out = (torch.empty(T, dtype=torch.int32, device="cuda"), torch.empty((C, T), dtype=torch.float32, device="cuda"),
+           torch.empty(T, dtype=torch.int32, device="cuda"))
+
+    def step_raw(i):
+        tr.select_exit(batches[i % args.buffers], g, w.eps, W1, b1, w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers,
+                       out=out)
+
+    packed = tr.router_pack(tr.BF16, g, W1)
+
+    def step_packed(i):
+        tr.select_exit_packed(batches[i % args.buffers], packed, w.eps, b1, w2, rt.b2, rt.theta, w.layer_ids, 0,
+                              w.n_layers, d=d, out=out)
+
+    def timed(step, steps, warmup):
+        for i in range(warmup):
+            step(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for i in range(steps):
+            step(i)
+        e1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return wall, e0.elapsed_time(e1) * 1e-3
+
+    wall_raw, ev_raw = timed(step_raw, args.steps, args.warmup)
+    wall_pk, ev_pk = timed(step_packed, args.steps, args.warmup)
+
+    ex = out[0].cpu().numpy()
+    from paper_2603_21365_amd import stats
+    hist = stats.exit_histogram(ex, w.layer_ids, w.n_layers)
+
+    # ---- roofline of the prefill kernel: one launch per packed step
+    esz = 2
+    alg_bytes = C * T * d * esz + C * d * 128 * esz + T * (4 + 4) + C * T * 4
+    t_launch = ev_pk / args.steps
+    achieved = alg_bytes / t_launch / 1e9
+    flops = 2.0 * d * 128 * C * T
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "kernel": "tide_prefill_kernel<bf16>", "us_per_launch": round(t_launch * 1e6, 2),
+                "algorithmic_bytes_per_launch": alg_bytes,
+                "mfma_tflops": round(flops / t_launch / 1e12, 1),
+                "mfma_frac_of_bf16_peak": round(flops / t_launch / 1e12 / MFMA_PEAK_TFLOPS["bf16"], 4)}
+
+    result = {
+        "metric": "tokens/sec + % HBM peak, fused RMSNorm+router d=4096 bf16; decode us/call",
+        "value": round(T * args.steps / wall_raw, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(wall_raw / args.steps * 1e3, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[1]: 8B-shaped prefill, bf16, d=4096, 32 layers, checkpoints every 4 (C=8), "
+                               "T=4096 tokens, ~30% firing per checkpoint", "C": C, "T": T, "d": d,
+                   "entry_point": "tide_select_exit (raw fp32 router weights; gain fold + packing inside the step)",
+                   "input_buffers_rotated": args.buffers},
+        "rows_per_s": round(C * T * args.steps / wall_raw, 1),
+        "packed_weights": {"entry_point": "tide_select_exit_packed", "tokens_per_s": round(T * args.steps / wall_pk, 1),
+                           "ms_per_step": round(wall_pk / args.steps * 1e3, 5)},
+        "exit_histogram": hist,
+        "roofline": roofline,
+    }
+
+    # ---- decode latency (config 2): fp16, T = 1 and 8, raw weights, auto-selected decode variant
+    if not args.no_decode:
+        dec = {}
+        for Td in (1, 8):
+            wd = synth.config2(Td)
+            hd = torch.from_numpy(wd.hidden()).cuda()
+            outd = (torch.empty(Td, dtype=torch.int32, device="cuda"), torch.empty((C, Td), dtype=torch.float32, device="cuda"),
+                    torch.empty(Td, dtype=torch.int32, device="cuda"))
+            call = lambda i: tr.select_exit(hd, g, wd.eps, W1, b1, w2, rt.b2, rt.theta, wd.layer_ids, 0, wd.n_layers, out=outd)
+            wall, ev = timed(call, 2000, 200)
+            dec[f"T{Td}"] = {"us_per_call": round(wall / 2000 * 1e6, 2), "calls_per_s": round(2000 / wall, 1),
+                             "us_per_call_hip_events": round(ev / 2000 * 1e6, 2)}
+        result["decode"] = {"workload": "configs[2]: fp16, d=4096, C=8, back-to-back calls on one stream", **dec}
+
+    # ---- the CPU oracle on the same workload (baseline, not a target)
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        hb = host_batches[0]
+        t0 = time.perf_counter()
+        oracle.select_exit(hb, w.dtype, rt.gamma, w.eps, rt.W1, rt.b1, rt.w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": round(T / dt, 1), "unit": "tokens/s", "cores": oracle.max_threads(),
+                                  "kind": "oracle",
+                                  "sample": f"one full batch of the same workload (C={C} x T={T} rows of d={d}, fp64), "
+                                            f"{dt:.2f} s"}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,138 @@
+/*
+ * tide_route.h -- C ABI of libtide_route: the per-token router hot path of TIDE
+ * (Token-Informed Depth Execution) for AMD MI355X (gfx950).
+ *
+ * What the library computes.  A router phi_k sits at each periodic checkpoint layer
+ * (paper Sec. 3.1: layers c-1, 2c-1, ...).  For one hidden row h in R^d it evaluates
+ * (paper Eq. (2); fused kernel 1 of Sec. 3.4)
+ *
+ *     n   = h / sqrt(mean(h^2) + eps) * gamma               RMSNorm
+ *     a_j = b1_j + sum_i n_i * W1[i][j],   j < 128          down-projection (W1 = W_down^T)
+ *     z   = b2 + sum_j w2_j * a_j * sigmoid(a_j)            SiLU, up-projection: the LOGIT
+ *     p   = sigmoid(z),     fire = (p > threshold)          strict, as in Alg. 1 / Fig. 1
+ *
+ * and, over C checkpoints, picks for every token the earliest eligible checkpoint whose
+ * router fires (paper Fig. 1 inference step 3, Sec. 3.3, Alg. 1 per token).
+ * The paper's router has gamma = 1 and no biases: pass gamma = NULL, b1 = NULL, b2 = 0.
+ * The bottleneck width is fixed at 128 (the paper's default, Sec. 3.1).
+ *
+ * Conventions for every entry point
+ *  - "device" pointers are HIP device memory on the current device; "host" pointers are
+ *    ordinary host memory read before the call returns.  The caller owns every buffer,
+ *    outputs included; the library keeps no pointer after the enqueued work finishes.
+ *  - Work is enqueued on `stream` (a hipStream_t, NULL = the default stream) and the call
+ *    returns without waiting for it.  Outputs are valid once the stream reaches that point.
+ *  - Return value: TIDE_OK (0) or a negative tide_status_t.  On error nothing is enqueued,
+ *    outputs are untouched and tide_last_error() describes the cause.  No call aborts.
+ *  - hidden rows are d elements of `dtype`, row r of checkpoint c starting at element
+ *    c*ckpt_stride + r*row_stride.  Requirements: d % 128 == 0, 128 <= d <= 16384,
+ *    row_stride >= d, base address and both strides (in bytes) multiples of 16.
+ *  - T == 0 is a successful no-op.  1 <= C <= 32.
+ *  - The threshold test is taken on the logit: z > ln(theta/(1-theta)) for 0 < theta < 1,
+ *    never for theta >= 1 (the paper's "1.0 (off)", Table 4), always for theta <= 0.
+ *  - The entry points that take raw router weights, and tide_select_exit_packed, use a
+ *    per-device workspace that the library allocates (hipMalloc) on first use and when a
+ *    larger problem arrives; calls that share it on one device must be ordered on one
+ *    stream.  tide_release() frees it.
+ */
+#ifndef TIDE_ROUTE_H
+#define TIDE_ROUTE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TIDE_BOTTLENECK 128
+#define TIDE_MAX_CHECKPOINTS 32
+
+typedef enum { TIDE_F32 = 0, TIDE_F16 = 1, TIDE_BF16 = 2 } tide_dtype_t;
+
+typedef enum {
+    TIDE_OK = 0,
+    TIDE_ERR_INVALID_ARG = -1, /* NULL where data is required, negative size, bad enum, unsorted layer_ids */
+    TIDE_ERR_UNSUPPORTED = -2, /* d outside the supported set, C > 32 */
+    TIDE_ERR_ALIGNMENT = -3,   /* hidden base or strides not 16-byte aligned */
+    TIDE_ERR_WORKSPACE = -4,   /* workspace allocation failed */
+    TIDE_ERR_HIP = -5          /* a HIP runtime call failed; see tide_last_error() */
+} tide_status_t;
+
+/* Kernel variant selection (tide_set_variant): AUTO picks DECODE when T is small. */
+typedef enum { TIDE_VARIANT_AUTO = 0, TIDE_VARIANT_PREFILL = 1, TIDE_VARIANT_DECODE = 2 } tide_variant_t;
+
+/* Library version as major*10000 + minor*100 + patch. */
+int tide_version(void);
+
+/* Thread-local, NUL-terminated description of the last error on this thread ("" if none). */
+const char* tide_last_error(void);
+
+/* One router over T rows: Eq. (2).
+ *   hidden  device [T rows]            dtype, layout as above (ckpt_stride unused)
+ *   gamma   device [d] fp32 or NULL    RMSNorm gain (NULL = all ones, the paper's form)
+ *   W1      device [d,128] fp32        row-major, W1[i*128+j] = W_down[j][i]
+ *   b1      device [128] fp32 or NULL  bias after the down-projection (NULL = zeros)
+ *   w2      device [128] fp32          = W_up
+ *   b2, eps, threshold                 by value
+ *   prob    device [T] fp32 out, or NULL
+ *   fire    device [T] u8 out (0/1), or NULL
+ *   logit   device [T] fp32 out, or NULL   (z before the sigmoid)                     */
+int tide_router_eval(const void* hidden, int dtype, int64_t T, int64_t d, int64_t row_stride,
+                     const float* gamma, float eps, const float* W1, const float* b1,
+                     const float* w2, float b2, float threshold, float* prob, uint8_t* fire,
+                     float* logit, void* stream);
+
+/* Per-token earliest exit over C checkpoints: Fig. 1 step 3 / Alg. 1 applied per token.
+ *   hidden     device [C,T rows]             router c reads checkpoint c's rows
+ *   gamma      device [C,d] or NULL;  W1 device [C,d,128];  b1 device [C,128] or NULL;
+ *   w2         device [C,128]
+ *   b2         HOST [C];  threshold HOST [C]  (one theta per checkpoint; the paper uses one)
+ *   layer_ids  HOST [C] int32, strictly ascending: the model layer of each checkpoint
+ *   min_layer  checkpoints with layer_ids[c] < min_layer cannot be chosen (k_min of Alg. 1)
+ *   no_exit_layer  value written when no eligible checkpoint fires (e.g. the layer count)
+ *   exit_layer device [T] int32 out:   min{ layer_ids[c] : eligible, fired } or no_exit_layer
+ *   logits     device [C,T] fp32 out, or NULL
+ *   fire_mask  device [T] u32 out, or NULL: bit c set iff checkpoint c fired (eligible or not) */
+int tide_select_exit(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d,
+                     int64_t ckpt_stride, int64_t row_stride, const float* gamma, float eps,
+                     const float* W1, const float* b1, const float* w2, const float* b2,
+                     const float* threshold, const int32_t* layer_ids, int32_t min_layer,
+                     int32_t no_exit_layer, int32_t* exit_layer, float* logits,
+                     uint32_t* fire_mask, void* stream);
+
+/* Router weights do not change between requests (they are trained once, Sec. 3.1), so the
+ * gain can be folded into the projection ahead of time: W1'[i][j] = gamma_i * W1[i][j],
+ * rounded to `dtype` and stored in the order the matrix-core kernel consumes it.
+ * tide_packed_router_bytes: bytes of one checkpoint's packed weights (0 if unsupported).
+ * tide_router_pack: device gamma [C,d] or NULL, device W1 [C,d,128] -> device packed
+ *   [C * tide_packed_router_bytes] (16-byte aligned).  The packed layout is private to the
+ *   library version that wrote it.                                                      */
+size_t tide_packed_router_bytes(int dtype, int64_t d);
+int tide_router_pack(int dtype, int64_t C, int64_t d, const float* gamma, const float* W1,
+                     void* packed, void* stream);
+
+/* The two calls above with pre-packed weights in place of (gamma, W1); `packed` must have
+ * been written by tide_router_pack with the same dtype, C and d.                        */
+int tide_router_eval_packed(const void* hidden, int dtype, int64_t T, int64_t d,
+                            int64_t row_stride, const void* packed, float eps, const float* b1,
+                            const float* w2, float b2, float threshold, float* prob,
+                            uint8_t* fire, float* logit, void* stream);
+int tide_select_exit_packed(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d,
+                            int64_t ckpt_stride, int64_t row_stride, const void* packed,
+                            float eps, const float* b1, const float* w2, const float* b2,
+                            const float* threshold, const int32_t* layer_ids, int32_t min_layer,
+                            int32_t no_exit_layer, int32_t* exit_layer, float* logits,
+                            uint32_t* fire_mask, void* stream);
+
+/* Force a kernel variant for the raw-weight entry points (process-wide; for tests and
+ * benchmarks).  Returns the previous setting, or TIDE_ERR_INVALID_ARG.                  */
+int tide_set_variant(int variant);
+
+/* Free the current device's workspace (synchronises that device).                       */
+int tide_release(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TIDE_ROUTE_H */

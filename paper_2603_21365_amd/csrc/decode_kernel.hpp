@@ -1,0 +1,202 @@
+// Decode kernel: the same fused RMSNorm + router + earliest exit (paper Eq. (2), Sec. 3.3:
+// every decode step evaluates the routers on the new token's checkpoint states) for a
+// handful of rows per call, where the cost is reading C routers' weights and latency.
+//
+// The d-long contraction of each checkpoint is split over S = d/128 workgroups so that the
+// whole chip pulls the weights at once (raw fp32 W1, no packing pass: with so few rows the
+// matrix cores have nothing to amortise).  Each workgroup writes its partial 128-vector and
+// partial sum of squares per token; the last workgroup of a checkpoint (device-scope
+// counter) reduces them in a fixed order, finishes the router, and the last checkpoint to
+// finish selects the earliest exit.  One launch, no host round trip, deterministic sums.
+#pragma once
+#include "device_utils.hpp"
+
+namespace tide {
+
+struct DecodeParams {
+    const char* hidden;
+    int64_t ckpt_stride_bytes, row_stride_bytes;
+    const float* gamma;   // [C][d] or null
+    const float* W1;      // [C][d][128]
+    const float* b1;      // [C][128] or null
+    const float* w2;      // [C][128]
+    int C, T, d, S;       // S = d / kDecodeSlice
+    float eps;
+    int32_t min_layer, no_exit;
+    float* prob; uint8_t* fire; float* logits;   // [C][T], nullable
+    int32_t* exit_layer; uint32_t* fire_mask;    // [T], nullable
+    float* stage;         // [C][T]
+    float* part;          // [C][S][T][129]: 128 partial pre-activations + partial sum of squares
+    uint32_t* counter;    // [C+1], zero on entry, zero on exit
+    CheckpointTable tab;
+};
+
+constexpr int kDecodeThreads = 256;
+constexpr int kDecodeSlice = 128;    // k values per workgroup
+constexpr int kDecodeTB = 8;         // tokens per pass
+constexpr int kPartStride = kBottleneck + 1;
+
+template <int DT> __device__ __forceinline__ void chunk_to_f32(u32x4 c, float* out);
+template <> __device__ __forceinline__ void chunk_to_f32<kF32>(u32x4 c, float* out) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) out[e] = __uint_as_float(c[e]);
+}
+template <> __device__ __forceinline__ void chunk_to_f32<kF16>(u32x4 c, float* out) {
+    f16x8 h = __builtin_bit_cast(f16x8, c);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) out[e] = (float)h[e];
+}
+template <> __device__ __forceinline__ void chunk_to_f32<kBF16>(u32x4 c, float* out) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        out[2 * e] = __uint_as_float(c[e] << 16);
+        out[2 * e + 1] = __uint_as_float(c[e] & 0xffff0000u);
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kDecodeThreads) void tide_decode_kernel(const DecodeParams p) {
+    constexpr int E = Storage<DT>::kElems;
+    constexpr int kChunksPerTok = kDecodeSlice / E;          // 16 or 32 lanes share a token
+    constexpr int kLoads = kDecodeSlice / 8;                 // float4 weight loads per thread
+    __shared__ float xs[kDecodeTB][kDecodeSlice];            // gamma-scaled inputs of this slice
+    __shared__ float ss_lds[kDecodeTB];
+    __shared__ float red[4][kDecodeTB][kBottleneck];
+    __shared__ float zw[4];
+    __shared__ int flag;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // consecutive workgroup ids land on consecutive XCDs: keep one checkpoint's weights on
+    // one XCD (and in its L2 across calls) whenever the counts allow it
+    const int nblk = p.C * p.S;
+    const int per_xcd = (nblk + 7) >> 3;
+    const int work = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (work >= nblk) return;
+    const int c = work / p.S, s = work - c * p.S;
+    const int k0 = s * kDecodeSlice;
+
+    // ---- this thread's weights: rows k0 + kk + 8*i, columns 4*jq .. 4*jq+3 ----
+    const int kk = tid >> 5, jq = tid & 31;
+    const float* w = p.W1 + ((size_t)c * p.d + k0 + kk) * kBottleneck + 4 * jq;
+    f32x4 wreg[kLoads];
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) wreg[i] = *reinterpret_cast<const f32x4*>(w + (size_t)8 * i * kBottleneck);
+
+    const char* base = p.hidden + (int64_t)c * p.ckpt_stride_bytes + (int64_t)k0 * Storage<DT>::kBytes;
+    const float* g = p.gamma ? p.gamma + (size_t)c * p.d + k0 : nullptr;
+
+    for (int t0 = 0; t0 < p.T; t0 += kDecodeTB) {
+        const int nt = min(kDecodeTB, p.T - t0);
+        // ---- stage x * gamma for up to 8 tokens; partial sums of squares of raw x ----
+        for (int q = tid; q < kDecodeTB * kChunksPerTok; q += kDecodeThreads) {
+            const int t = q / kChunksPerTok, ch = q - t * kChunksPerTok;
+            u32x4 v = {0, 0, 0, 0};
+            if (t < nt) v = *reinterpret_cast<const u32x4*>(base + (int64_t)(t0 + t) * p.row_stride_bytes + ch * 16);
+            float f[E];
+            chunk_to_f32<DT>(v, f);
+            float sq = 0.0f;
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                sq = fmaf(f[e], f[e], sq);
+                xs[t][ch * E + e] = f[e] * (g ? g[ch * E + e] : 1.0f);
+            }
+            sq = xor_reduce_sum<(kChunksPerTok == 16 ? 4 : 5)>(sq);
+            if (ch == 0) ss_lds[t] = sq;
+        }
+        __syncthreads();
+
+        // ---- partial products over this thread's 16 k values ----
+        float acc[kDecodeTB][4];
+#pragma unroll
+        for (int t = 0; t < kDecodeTB; ++t)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[t][j] = 0.0f;
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i) {
+#pragma unroll
+            for (int t = 0; t < kDecodeTB; ++t) {
+                const float x = xs[t][kk + 8 * i];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[t][j] = fmaf(x, wreg[i][j], acc[t][j]);
+            }
+        }
+        // lanes l and l^32 hold the two k phases of a wave; then the four waves meet in LDS
+#pragma unroll
+        for (int t = 0; t < kDecodeTB; ++t)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float v = acc[t][j] + __shfl_xor(acc[t][j], 32, kWave);
+                if (lane < 32) red[wave][t][4 * jq + j] = v;
+            }
+        __syncthreads();
+        float* part = p.part + (((size_t)c * p.S + s) * p.T + t0) * kPartStride;
+        for (int q = tid; q < nt * kBottleneck; q += kDecodeThreads) {
+            const int t = q >> 7, col = q & 127;
+            stage_store(part + (size_t)t * kPartStride + col,
+                        (red[0][t][col] + red[1][t][col]) + (red[2][t][col] + red[3][t][col]));
+        }
+        if (tid < nt) stage_store(part + (size_t)tid * kPartStride + kBottleneck, ss_lds[tid]);
+        __syncthreads();
+    }
+
+    // ---- last workgroup of this checkpoint finishes the router ----
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t prev = __hip_atomic_fetch_add(p.counter + c, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        flag = (prev == (uint32_t)p.S - 1);
+    }
+    __syncthreads();
+    if (!flag) return;
+    __threadfence();
+
+    const int col = tid & 127, half = tid >> 7;       // waves 0,1 -> even token of a pair; 2,3 -> odd
+    const float b1c = p.b1 ? p.b1[c * kBottleneck + col] : 0.0f;
+    const float w2c = p.w2[c * kBottleneck + col];
+    const float* pc = p.part + (size_t)c * p.S * p.T * kPartStride;
+    for (int tp = 0; tp < p.T; tp += 2) {
+        const int t = tp + half;
+        float term = 0.0f;
+        if (t < p.T) {
+            float a = 0.0f, ssum = 0.0f;
+            for (int si = 0; si < p.S; ++si) {
+                const float* q = pc + ((size_t)si * p.T + t) * kPartStride;
+                a += stage_load(q + col);
+                ssum += stage_load(q + kBottleneck);
+            }
+            const float r = 1.0f / sqrtf(ssum / (float)p.d + p.eps);
+            term = w2c * silu_f32(fmaf(r, a, b1c));
+        }
+        term = xor_reduce_sum<6>(term);
+        if (lane == 0) zw[wave] = term;
+        __syncthreads();
+        if ((tid == 0 || tid == 128) && t < p.T) {
+            const float z = p.tab.b2[c] + (zw[2 * half] + zw[2 * half + 1]);
+            const int64_t o = (int64_t)c * p.T + t;
+            if (p.logits) p.logits[o] = z;
+            if (p.prob) p.prob[o] = sigmoid_f32(z);
+            if (p.fire) p.fire[o] = z > p.tab.thr_logit[c] ? 1 : 0;
+            if (p.exit_layer) stage_store(p.stage + o, z);
+        }
+        __syncthreads();
+    }
+    if (tid == 0) __hip_atomic_store(p.counter + c, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!p.exit_layer) return;
+
+    // ---- last checkpoint to finish selects the earliest exit of every token ----
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t prev = __hip_atomic_fetch_add(p.counter + p.C, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        flag = (prev == (uint32_t)p.C - 1);
+    }
+    __syncthreads();
+    if (!flag) return;
+    __threadfence();
+    for (int t = tid; t < p.T; t += kDecodeThreads)
+        select_earliest(p.tab, p.C, p.min_layer, p.no_exit, p.stage + t, p.T, p.exit_layer + t,
+                        p.fire_mask ? p.fire_mask + t : nullptr);
+    if (tid == 0) __hip_atomic_store(p.counter + p.C, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+}  // namespace tide

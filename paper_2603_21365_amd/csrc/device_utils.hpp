@@ -1,0 +1,117 @@
+// Device-side building blocks shared by the gfx950 kernels: storage-type traits, 16-byte
+// chunk arithmetic, matrix-core wrappers, wave64 reductions, coherent staging accesses.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tide {
+
+constexpr int kBottleneck = 128;
+constexpr int kWave = 64;
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+enum : int { kF32 = 0, kF16 = 1, kBF16 = 2 };
+
+// One 16-byte chunk of a hidden row holds kElems consecutive elements.  A "k-group" is the
+// pair of chunks that the two lane halves of a wave feed to one 32x32 matrix-core step.
+template <int DT> struct Storage;
+template <> struct Storage<kF32>  { static constexpr int kBytes = 4; static constexpr int kElems = 4; };
+template <> struct Storage<kF16>  { static constexpr int kBytes = 2; static constexpr int kElems = 8; };
+template <> struct Storage<kBF16> { static constexpr int kBytes = 2; static constexpr int kElems = 8; };
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+
+// Sum of squares of the elements of one chunk, accumulated in fp32.
+template <int DT> __device__ __forceinline__ float chunk_sumsq(u32x4 c, float acc);
+template <> __device__ __forceinline__ float chunk_sumsq<kF32>(u32x4 c, float acc) {
+    float x0 = __uint_as_float(c.x), x1 = __uint_as_float(c.y), x2 = __uint_as_float(c.z), x3 = __uint_as_float(c.w);
+    acc = fmaf(x0, x0, acc); acc = fmaf(x1, x1, acc); acc = fmaf(x2, x2, acc); acc = fmaf(x3, x3, acc);
+    return acc;
+}
+template <> __device__ __forceinline__ float chunk_sumsq<kF16>(u32x4 c, float acc) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f16x2 p = __builtin_bit_cast(f16x2, c[i]);
+        acc = __builtin_amdgcn_fdot2(p, p, acc, false);
+    }
+    return acc;
+}
+template <> __device__ __forceinline__ float chunk_sumsq<kBF16>(u32x4 c, float acc) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        bf16x2 p = __builtin_bit_cast(bf16x2, c[i]);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(p, p, acc, false);
+    }
+    return acc;
+}
+
+// acc[32x32] += A[32 x kgroup] * B[kgroup x 32] with A and B chunks laid out as the matrix
+// cores take them: lane l supplies row/column l%32 and the chunk of lane half l/32.
+template <int DT> __device__ __forceinline__ f32x16 mma_kgroup(u32x4 a, u32x4 b, f32x16 acc);
+template <> __device__ __forceinline__ f32x16 mma_kgroup<kBF16>(u32x4 a, u32x4 b, f32x16 acc) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+}
+template <> __device__ __forceinline__ f32x16 mma_kgroup<kF16>(u32x4 a, u32x4 b, f32x16 acc) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), acc, 0, 0, 0);
+}
+template <> __device__ __forceinline__ f32x16 mma_kgroup<kF32>(u32x4 a, u32x4 b, f32x16 acc) {
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[m]), __uint_as_float(b[m]), acc, 0, 0, 0);
+    return acc;
+}
+
+__device__ __forceinline__ float sigmoid_f32(float x) {
+    // 1/(1+e^-x); e^-x overflows to +inf for x < -88 and the quotient is then exactly 0
+    return 1.0f / (1.0f + __expf(-x));
+}
+__device__ __forceinline__ float silu_f32(float x) { return x * sigmoid_f32(x); }
+
+// Butterfly sum over the lanes that differ in the low `kBits` bits of the lane id: every
+// participating lane ends up with the total (no broadcast step to forget).
+template <int kBits> __device__ __forceinline__ float xor_reduce_sum(float v) {
+#pragma unroll
+    for (int s = 1; s < (1 << kBits); s <<= 1) v += __shfl_xor(v, s, kWave);
+    return v;
+}
+
+// Staging values that another workgroup, possibly on another XCD, reads back in the same
+// launch go through device-scope atomics so that they bypass the non-coherent caches.
+__device__ __forceinline__ void stage_store(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float stage_load(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Per-checkpoint scalars that travel by value in the kernel argument block.
+struct CheckpointTable {
+    float b2[32];
+    float thr_logit[32];  // ln(theta/(1-theta)); +inf for theta >= 1, -inf for theta <= 0
+    int32_t layer_id[32];
+};
+
+// Earliest eligible firing checkpoint of one token, given its C logits (ascending layers).
+__device__ __forceinline__ void select_earliest(const CheckpointTable& tab, int C, int32_t min_layer, int32_t no_exit,
+                                                const float* z_of_c, int64_t z_stride, int32_t* exit_out, uint32_t* mask_out) {
+    int32_t chosen = no_exit;
+    bool found = false;
+    uint32_t mask = 0;
+    for (int c = 0; c < C; ++c) {
+        float z = stage_load(z_of_c + c * z_stride);
+        bool f = z > tab.thr_logit[c];
+        if (f) mask |= 1u << c;
+        if (f && !found && tab.layer_id[c] >= min_layer) { chosen = tab.layer_id[c]; found = true; }
+    }
+    *exit_out = chosen;
+    if (mask_out) *mask_out = mask;
+}
+
+}  // namespace tide

@@ -1,0 +1,188 @@
+// Prefill kernel: fused RMSNorm + router + earliest exit for many rows (paper Eq. (2),
+// Sec. 3.4 kernel 1, Fig. 1 inference step 3), designed for gfx950.
+//
+// The RMSNorm scale r = 1/sqrt(mean(h^2)+eps) is one scalar per row and the gain one scalar
+// per input channel, so   sum_i (h_i r gamma_i) W1[i][j]  =  r * sum_i h_i (gamma_i W1[i][j]).
+// The kernel therefore streams each RAW hidden row from HBM exactly once, uses it directly
+// as the matrix-core A operand against the pre-folded W1' = diag(gamma) W1, accumulates the
+// row's sum of squares from the same registers, and applies r to the 128 accumulators in
+// the epilogue.  For 16-bit inputs the A operand is the exact input (no second rounding).
+//
+// Workgroup = 256 threads (4 waves) owning kRows rows of one checkpoint and all 128 router
+// columns; wave w owns columns 32w..32w+31.  Per k-tile (kTileBytes of every row):
+//   global -> registers (coalesced 16-byte chunks, 16 lanes per row segment)
+//   registers -> LDS (padded rows), sum of squares on the way
+//   LDS -> A fragments; W1' fragments straight from L2 in their packed order; MFMA.
+// Epilogue: r, +b1, SiLU, *w2, sum over the 128 columns, +b2, sigmoid, threshold; the
+// last workgroup to finish a token tile (device-scope counter) takes the min over the
+// checkpoints, so one launch yields exit_layer with no host round trip.
+#pragma once
+#include "device_utils.hpp"
+
+namespace tide {
+
+struct PrefillParams {
+    const char* hidden;        // storage-typed rows
+    int64_t ckpt_stride_bytes;
+    int64_t row_stride_bytes;
+    const u32x4* packed;       // [C][d*128 elements] packed W1'
+    const float* b1;           // [C][128] or null
+    const float* w2;           // [C][128]
+    int C, T, d;
+    int tiles_per_ckpt;        // ceil(T / kRows)
+    int total_tiles;           // C * tiles_per_ckpt
+    float eps;
+    int32_t min_layer, no_exit;
+    // outputs (each may be null)
+    float* prob;               // [C][T]
+    uint8_t* fire;             // [C][T]
+    float* logits;             // [C][T] user output
+    int32_t* exit_layer;       // [T]
+    uint32_t* fire_mask;       // [T]
+    // workspace
+    float* stage;              // [C][T] logits read back by the selecting workgroup (may alias logits)
+    uint32_t* tile_counter;    // [tiles_per_ckpt], zero on entry, zero on exit
+    CheckpointTable tab;
+};
+
+constexpr int kPrefillThreads = 256;
+constexpr int kRows = 64;                 // rows per workgroup
+constexpr int kTileBytes = 256;           // bytes of each row per k-tile
+constexpr int kChunksPerRow = kTileBytes / 16;                       // 16
+constexpr int kChunksPerThread = kRows * kChunksPerRow / kPrefillThreads;  // 4
+constexpr int kGroupsPerTile = kChunksPerRow / 2;                    // 8
+constexpr int kPitch = kTileBytes + 16;   // LDS row pitch: 16-byte pad staggers the banks
+
+template <int DT>
+__global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const PrefillParams p) {
+    __shared__ __attribute__((aligned(16))) char a_lds[2][kRows * kPitch];
+    __shared__ float row_ss[kRows];
+    __shared__ float z_part[4][kRows];
+    __shared__ int is_last;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    // XCD-aware tile order: consecutive workgroup ids land on consecutive XCDs, so give XCD x
+    // the x-th contiguous slice of the checkpoint-major tile list; its L2 then holds one W1'.
+    const int per_xcd = (p.total_tiles + 7) >> 3;
+    const int work = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (work >= p.total_tiles) return;
+    const int c = work / p.tiles_per_ckpt;
+    const int tile = work - c * p.tiles_per_ckpt;
+    const int row0 = tile * kRows;
+
+    const char* base = p.hidden + (int64_t)c * p.ckpt_stride_bytes;
+    const u32x4* wp = p.packed + (size_t)c * ((size_t)p.d * kBottleneck / Storage<DT>::kElems);
+
+    // this thread's chunk column and rows within the tile
+    const int cc = tid & (kChunksPerRow - 1);
+    const int lr0 = tid / kChunksPerRow;           // 0..15; rows lr0 + 16*i
+    const char* gptr[kChunksPerThread];
+#pragma unroll
+    for (int i = 0; i < kChunksPerThread; ++i) {
+        int r = row0 + lr0 + 16 * i;
+        r = r < p.T ? r : p.T - 1;                 // ragged tail: re-read the last row, never store it
+        gptr[i] = base + (int64_t)r * p.row_stride_bytes + cc * 16;
+    }
+
+    const int ntile = p.d * Storage<DT>::kBytes / kTileBytes;
+    u32x4 areg[kChunksPerThread];
+    u32x4 bcur[kGroupsPerTile], bnext[kGroupsPerTile];
+    float ss[kChunksPerThread];
+#pragma unroll
+    for (int i = 0; i < kChunksPerThread; ++i) ss[i] = 0.0f;
+    f32x16 acc0 = {0}, acc1 = {0};
+
+#pragma unroll
+    for (int i = 0; i < kChunksPerThread; ++i) areg[i] = *reinterpret_cast<const u32x4*>(gptr[i]);
+    const u32x4* bptr = wp + wave * 64 + lane;     // + G*256 per k-group
+#pragma unroll
+    for (int g = 0; g < kGroupsPerTile; ++g) bcur[g] = bptr[(size_t)g * 256];
+
+    const int a_read_off = (lane & 31) * kPitch + (lane >> 5) * 16;
+    for (int kt = 0; kt < ntile; ++kt) {
+        char* buf = a_lds[kt & 1];
+#pragma unroll
+        for (int i = 0; i < kChunksPerThread; ++i) {
+            ss[i] = chunk_sumsq<DT>(areg[i], ss[i]);
+            *reinterpret_cast<u32x4*>(buf + (lr0 + 16 * i) * kPitch + cc * 16) = areg[i];
+        }
+        __syncthreads();
+        if (kt + 1 < ntile) {
+#pragma unroll
+            for (int i = 0; i < kChunksPerThread; ++i)
+                areg[i] = *reinterpret_cast<const u32x4*>(gptr[i] + (int64_t)(kt + 1) * kTileBytes);
+#pragma unroll
+            for (int g = 0; g < kGroupsPerTile; ++g) bnext[g] = bptr[(size_t)((kt + 1) * kGroupsPerTile + g) * 256];
+        }
+#pragma unroll
+        for (int g = 0; g < kGroupsPerTile; ++g) {
+            u32x4 a0 = *reinterpret_cast<const u32x4*>(buf + a_read_off + g * 32);
+            u32x4 a1 = *reinterpret_cast<const u32x4*>(buf + a_read_off + 32 * kPitch + g * 32);
+            acc0 = mma_kgroup<DT>(a0, bcur[g], acc0);
+            acc1 = mma_kgroup<DT>(a1, bcur[g], acc1);
+        }
+#pragma unroll
+        for (int g = 0; g < kGroupsPerTile; ++g) bcur[g] = bnext[g];
+    }
+
+    // ---- row scale: the 16 lanes that share a row hold its partial sums of squares ----
+#pragma unroll
+    for (int i = 0; i < kChunksPerThread; ++i) {
+        float s = xor_reduce_sum<4>(ss[i]);
+        if (cc == 0) row_ss[lr0 + 16 * i] = s;
+    }
+    __syncthreads();
+
+    // ---- epilogue: a = r*acc + b1; SiLU; dot with w2 over this wave's 32 columns ----
+    const int col = 32 * wave + (lane & 31);
+    const float b1c = p.b1 ? p.b1[c * kBottleneck + col] : 0.0f;
+    const float w2c = p.w2[c * kBottleneck + col];
+    const float inv_d = 1.0f / (float)p.d;
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = mb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            const float r = 1.0f / sqrtf(row_ss[row] * inv_d + p.eps);
+            const float a = fmaf(r, mb == 0 ? acc0[v] : acc1[v], b1c);
+            float term = w2c * silu_f32(a);
+            term = xor_reduce_sum<5>(term);
+            if ((lane & 31) == 0) z_part[wave][row] = term;
+        }
+    }
+    __syncthreads();
+
+    if (tid < kRows) {
+        const int t = row0 + tid;
+        if (t < p.T) {
+            const float z = p.tab.b2[c] + ((z_part[0][tid] + z_part[1][tid]) + (z_part[2][tid] + z_part[3][tid]));
+            const int64_t o = (int64_t)c * p.T + t;
+            if (p.logits) p.logits[o] = z;
+            if (p.prob) p.prob[o] = sigmoid_f32(z);
+            if (p.fire) p.fire[o] = z > p.tab.thr_logit[c] ? 1 : 0;
+            if (p.exit_layer) stage_store(p.stage + o, z);
+        }
+    }
+    if (!p.exit_layer) return;
+
+    // ---- earliest exit: the last workgroup to finish this token tile selects ----
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t prev = __hip_atomic_fetch_add(p.tile_counter + tile, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        is_last = (prev == (uint32_t)p.C - 1);
+    }
+    __syncthreads();
+    if (!is_last) return;
+    __threadfence();
+    if (tid < kRows) {
+        const int t = row0 + tid;
+        if (t < p.T)
+            select_earliest(p.tab, p.C, p.min_layer, p.no_exit, p.stage + t, p.T, p.exit_layer + t,
+                            p.fire_mask ? p.fire_mask + t : nullptr);
+    }
+    if (tid == 0) __hip_atomic_store(p.tile_counter + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+}  // namespace tide

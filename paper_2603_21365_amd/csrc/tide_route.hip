@@ -1,0 +1,400 @@
+// libtide_route: host side of the C ABI declared in include/tide_route.h -- argument
+// checks, the per-device workspace, kernel selection and launches.  No torch types, no
+// host synchronisation on the hot path.
+#include "../../include/tide_route.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <limits>
+#include <mutex>
+
+#include "decode_kernel.hpp"
+#include "pack_kernel.hpp"
+#include "prefill_kernel.hpp"
+
+namespace {
+
+using namespace tide;
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define TIDE_HIP(expr)                                                                         \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess) return fail(TIDE_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+constexpr int kMaxDevices = 16;
+constexpr size_t kCounterSlots = 1 << 16;  // token tiles per checkpoint that one launch may use
+constexpr int kDecodeAutoMaxT = 32;
+constexpr int kDecodeMaxT = 64;
+
+struct Buffer {
+    void* ptr = nullptr;
+    size_t bytes = 0;
+};
+
+struct Workspace {
+    Buffer counters, stage, packed, part;
+};
+
+std::mutex g_mu;
+Workspace g_ws[kMaxDevices];
+int g_variant = TIDE_VARIANT_AUTO;
+
+// Grow-only device buffer.  Re-allocation frees the old block, which waits for the device.
+int reserve(Buffer& b, size_t bytes, bool zero) {
+    if (b.bytes >= bytes && b.ptr) return TIDE_OK;
+    if (b.ptr) {
+        hipError_t e = hipFree(b.ptr);
+        b.ptr = nullptr;
+        b.bytes = 0;
+        if (e != hipSuccess) return fail(TIDE_ERR_HIP, "hipFree: %s", hipGetErrorString(e));
+    }
+    size_t want = (bytes + 255) & ~size_t(255);
+    hipError_t e = hipMalloc(&b.ptr, want);
+    if (e != hipSuccess) {
+        b.ptr = nullptr;
+        return fail(TIDE_ERR_WORKSPACE, "workspace hipMalloc(%zu): %s", want, hipGetErrorString(e));
+    }
+    b.bytes = want;
+    if (zero) {
+        e = hipMemset(b.ptr, 0, want);
+        if (e != hipSuccess) return fail(TIDE_ERR_HIP, "hipMemset: %s", hipGetErrorString(e));
+    }
+    return TIDE_OK;
+}
+
+int current_workspace(Workspace** out) {
+    int dev = 0;
+    TIDE_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(TIDE_ERR_UNSUPPORTED, "device index %d out of range", dev);
+    *out = &g_ws[dev];
+    return TIDE_OK;
+}
+
+size_t elem_bytes(int dtype) { return dtype == TIDE_F32 ? 4 : 2; }
+
+float threshold_logit(float theta) {
+    if (!(theta < 1.0f)) return std::numeric_limits<float>::infinity();   // also NaN: never fire
+    if (theta <= 0.0f) return -std::numeric_limits<float>::infinity();
+    const double t = (double)theta;
+    return (float)std::log(t / (1.0 - t));
+}
+
+// Everything both entry points must check before anything is enqueued.
+int check_common(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t ckpt_stride,
+                 int64_t row_stride, const void* weights, const float* w2, float eps) {
+    if (dtype != TIDE_F32 && dtype != TIDE_F16 && dtype != TIDE_BF16)
+        return fail(TIDE_ERR_INVALID_ARG, "dtype %d is not a tide_dtype_t", dtype);
+    if (C < 1) return fail(TIDE_ERR_INVALID_ARG, "C = %lld must be at least 1", (long long)C);
+    if (C > TIDE_MAX_CHECKPOINTS) return fail(TIDE_ERR_UNSUPPORTED, "C = %lld exceeds %d", (long long)C, TIDE_MAX_CHECKPOINTS);
+    if (T < 0) return fail(TIDE_ERR_INVALID_ARG, "T = %lld is negative", (long long)T);
+    if (d <= 0) return fail(TIDE_ERR_INVALID_ARG, "d = %lld must be positive", (long long)d);
+    if (d % 128 != 0 || d < 128 || d > 16384)
+        return fail(TIDE_ERR_UNSUPPORTED, "d = %lld: supported sizes are multiples of 128 in [128, 16384]", (long long)d);
+    if (T > (int64_t)kCounterSlots * kRows || C * T > (int64_t)1 << 30)
+        return fail(TIDE_ERR_UNSUPPORTED, "T = %lld is too large for one call", (long long)T);
+    if (row_stride < d) return fail(TIDE_ERR_INVALID_ARG, "row_stride %lld < d %lld", (long long)row_stride, (long long)d);
+    if (C > 1 && T > 1 && ckpt_stride < 0) return fail(TIDE_ERR_INVALID_ARG, "negative ckpt_stride");
+    if (!(eps >= 0.0f)) return fail(TIDE_ERR_INVALID_ARG, "eps must be >= 0");
+    if (T == 0) return TIDE_OK;
+    if (!hidden || !weights || !w2) return fail(TIDE_ERR_INVALID_ARG, "hidden, W1/packed and w2 must not be NULL");
+    const size_t eb = elem_bytes(dtype);
+    if (((uintptr_t)hidden & 15) || ((size_t)row_stride * eb & 15) || (C > 1 && ((size_t)ckpt_stride * eb & 15)))
+        return fail(TIDE_ERR_ALIGNMENT, "hidden base and strides must be multiples of 16 bytes");
+    return TIDE_OK;
+}
+
+int fill_table(CheckpointTable& tab, int64_t C, const float* b2, const float* threshold, const int32_t* layer_ids) {
+    if (!b2 || !threshold || !layer_ids) return fail(TIDE_ERR_INVALID_ARG, "b2, threshold and layer_ids (host arrays) must not be NULL");
+    std::memset(&tab, 0, sizeof(tab));
+    for (int64_t c = 0; c < C; ++c) {
+        if (c > 0 && layer_ids[c] <= layer_ids[c - 1])
+            return fail(TIDE_ERR_INVALID_ARG, "layer_ids must be strictly ascending (layer_ids[%lld] = %d after %d)",
+                        (long long)c, layer_ids[c], layer_ids[c - 1]);
+        tab.b2[c] = b2[c];
+        tab.thr_logit[c] = threshold_logit(threshold[c]);
+        tab.layer_id[c] = layer_ids[c];
+    }
+    return TIDE_OK;
+}
+
+template <typename F> int by_dtype(int dtype, F&& f) {
+    switch (dtype) {
+    case TIDE_F32: return f(std::integral_constant<int, kF32>{});
+    case TIDE_F16: return f(std::integral_constant<int, kF16>{});
+    default: return f(std::integral_constant<int, kBF16>{});
+    }
+}
+
+struct Outputs {
+    float* prob;
+    uint8_t* fire;
+    float* logits;
+    int32_t* exit_layer;
+    uint32_t* fire_mask;
+};
+
+int launch_pack(int dtype, int64_t C, int64_t d, const float* gamma, const float* W1, void* packed, hipStream_t st) {
+    const int chunks = (int)(d * kBottleneck * elem_bytes(dtype) / 16);
+    dim3 grid((chunks + 255) / 256, (unsigned)C);
+    by_dtype(dtype, [&](auto dt) {
+        hipLaunchKernelGGL((tide_pack_kernel<decltype(dt)::value>), grid, dim3(256), 0, st, gamma, W1, (u32x4*)packed, (int)d, chunks);
+        return 0;
+    });
+    TIDE_HIP(hipGetLastError());
+    return TIDE_OK;
+}
+
+int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t ckpt_stride,
+                   int64_t row_stride, const void* packed, float eps, const float* b1, const float* w2,
+                   const CheckpointTable& tab, int32_t min_layer, int32_t no_exit, const Outputs& o, hipStream_t st) {
+    PrefillParams p;
+    std::memset(&p, 0, sizeof(p));
+    const size_t eb = elem_bytes(dtype);
+    p.hidden = (const char*)hidden;
+    p.ckpt_stride_bytes = ckpt_stride * (int64_t)eb;
+    p.row_stride_bytes = row_stride * (int64_t)eb;
+    p.packed = (const u32x4*)packed;
+    p.b1 = b1;
+    p.w2 = w2;
+    p.C = (int)C;
+    p.T = (int)T;
+    p.d = (int)d;
+    p.tiles_per_ckpt = (int)((T + kRows - 1) / kRows);
+    p.total_tiles = p.C * p.tiles_per_ckpt;
+    p.eps = eps;
+    p.min_layer = min_layer;
+    p.no_exit = no_exit;
+    p.prob = o.prob;
+    p.fire = o.fire;
+    p.logits = o.logits;
+    p.exit_layer = o.exit_layer;
+    p.fire_mask = o.fire_mask;
+    p.tab = tab;
+    if (o.exit_layer) {
+        int rc = reserve(ws.counters, kCounterSlots * sizeof(uint32_t), true);
+        if (rc) return rc;
+        p.tile_counter = (uint32_t*)ws.counters.ptr;
+        if (o.logits) {
+            p.stage = o.logits;
+        } else {
+            rc = reserve(ws.stage, (size_t)C * T * sizeof(float), false);
+            if (rc) return rc;
+            p.stage = (float*)ws.stage.ptr;
+        }
+    }
+    const unsigned grid = 8u * (unsigned)((p.total_tiles + 7) / 8);
+    by_dtype(dtype, [&](auto dt) {
+        hipLaunchKernelGGL((tide_prefill_kernel<decltype(dt)::value>), dim3(grid), dim3(kPrefillThreads), 0, st, p);
+        return 0;
+    });
+    TIDE_HIP(hipGetLastError());
+    return TIDE_OK;
+}
+
+int launch_decode(Workspace& ws, const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t ckpt_stride,
+                  int64_t row_stride, const float* gamma, const float* W1, float eps, const float* b1, const float* w2,
+                  const CheckpointTable& tab, int32_t min_layer, int32_t no_exit, const Outputs& o, hipStream_t st) {
+    DecodeParams p;
+    std::memset(&p, 0, sizeof(p));
+    const size_t eb = elem_bytes(dtype);
+    p.hidden = (const char*)hidden;
+    p.ckpt_stride_bytes = ckpt_stride * (int64_t)eb;
+    p.row_stride_bytes = row_stride * (int64_t)eb;
+    p.gamma = gamma;
+    p.W1 = W1;
+    p.b1 = b1;
+    p.w2 = w2;
+    p.C = (int)C;
+    p.T = (int)T;
+    p.d = (int)d;
+    p.S = (int)(d / kDecodeSlice);
+    p.eps = eps;
+    p.min_layer = min_layer;
+    p.no_exit = no_exit;
+    p.prob = o.prob;
+    p.fire = o.fire;
+    p.logits = o.logits;
+    p.exit_layer = o.exit_layer;
+    p.fire_mask = o.fire_mask;
+    p.tab = tab;
+    int rc = reserve(ws.counters, kCounterSlots * sizeof(uint32_t), true);
+    if (rc) return rc;
+    p.counter = (uint32_t*)ws.counters.ptr;
+    rc = reserve(ws.part, (size_t)C * p.S * T * kPartStride * sizeof(float), false);
+    if (rc) return rc;
+    p.part = (float*)ws.part.ptr;
+    if (o.exit_layer) {
+        if (o.logits) {
+            p.stage = o.logits;
+        } else {
+            rc = reserve(ws.stage, (size_t)C * T * sizeof(float), false);
+            if (rc) return rc;
+            p.stage = (float*)ws.stage.ptr;
+        }
+    }
+    const int nblk = p.C * p.S;
+    const unsigned grid = 8u * (unsigned)((nblk + 7) / 8);
+    by_dtype(dtype, [&](auto dt) {
+        hipLaunchKernelGGL((tide_decode_kernel<decltype(dt)::value>), dim3(grid), dim3(kDecodeThreads), 0, st, p);
+        return 0;
+    });
+    TIDE_HIP(hipGetLastError());
+    return TIDE_OK;
+}
+
+bool use_decode(int64_t T) {
+    if (g_variant == TIDE_VARIANT_DECODE) return T <= kDecodeMaxT;
+    if (g_variant == TIDE_VARIANT_PREFILL) return false;
+    return T <= kDecodeAutoMaxT;
+}
+
+// Shared body of the four compute entry points.  Exactly one of (W1) / (packed) is given.
+int run(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t ckpt_stride, int64_t row_stride,
+        const float* gamma, const float* W1, const void* packed, float eps, const float* b1, const float* w2,
+        const CheckpointTable& tab, int32_t min_layer, int32_t no_exit, const Outputs& o, void* stream) {
+    if (T == 0) return TIDE_OK;
+    hipStream_t st = (hipStream_t)stream;
+    std::lock_guard<std::mutex> lock(g_mu);
+    Workspace* ws = nullptr;
+    int rc = current_workspace(&ws);
+    if (rc) return rc;
+    if (W1 && use_decode(T))
+        return launch_decode(*ws, hidden, dtype, C, T, d, ckpt_stride, row_stride, gamma, W1, eps, b1, w2, tab,
+                             min_layer, no_exit, o, st);
+    if (W1) {
+        rc = reserve(ws->packed, (size_t)C * tide_packed_router_bytes(dtype, d), false);
+        if (rc) return rc;
+        rc = launch_pack(dtype, C, d, gamma, W1, ws->packed.ptr, st);
+        if (rc) return rc;
+        packed = ws->packed.ptr;
+    }
+    return launch_prefill(*ws, hidden, dtype, C, T, d, ckpt_stride, row_stride, packed, eps, b1, w2, tab, min_layer,
+                          no_exit, o, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+int tide_version(void) { return 100; }
+
+const char* tide_last_error(void) { return g_err; }
+
+size_t tide_packed_router_bytes(int dtype, int64_t d) {
+    if ((dtype != TIDE_F32 && dtype != TIDE_F16 && dtype != TIDE_BF16) || d < 128 || d > 16384 || d % 128) return 0;
+    return (size_t)d * kBottleneck * elem_bytes(dtype);
+}
+
+int tide_router_pack(int dtype, int64_t C, int64_t d, const float* gamma, const float* W1, void* packed, void* stream) {
+    g_err[0] = 0;
+    if (C < 1 || C > TIDE_MAX_CHECKPOINTS) return fail(TIDE_ERR_INVALID_ARG, "C = %lld outside [1, 32]", (long long)C);
+    if (tide_packed_router_bytes(dtype, d) == 0) return fail(TIDE_ERR_UNSUPPORTED, "unsupported dtype %d or d %lld", dtype, (long long)d);
+    if (!W1 || !packed) return fail(TIDE_ERR_INVALID_ARG, "W1 and packed must not be NULL");
+    if ((uintptr_t)packed & 15) return fail(TIDE_ERR_ALIGNMENT, "packed must be 16-byte aligned");
+    return launch_pack(dtype, C, d, gamma, W1, packed, (hipStream_t)stream);
+}
+
+int tide_router_eval(const void* hidden, int dtype, int64_t T, int64_t d, int64_t row_stride, const float* gamma,
+                     float eps, const float* W1, const float* b1, const float* w2, float b2, float threshold,
+                     float* prob, uint8_t* fire, float* logit, void* stream) {
+    g_err[0] = 0;
+    int rc = check_common(hidden, dtype, 1, T, d, 0, row_stride, W1, w2, eps);
+    if (rc) return rc;
+    CheckpointTable tab;
+    const int32_t id0 = 0;
+    rc = fill_table(tab, 1, &b2, &threshold, &id0);
+    if (rc) return rc;
+    Outputs o{prob, fire, logit, nullptr, nullptr};
+    return run(hidden, dtype, 1, T, d, 0, row_stride, gamma, W1, nullptr, eps, b1, w2, tab, 0, 0, o, stream);
+}
+
+int tide_router_eval_packed(const void* hidden, int dtype, int64_t T, int64_t d, int64_t row_stride,
+                            const void* packed, float eps, const float* b1, const float* w2, float b2,
+                            float threshold, float* prob, uint8_t* fire, float* logit, void* stream) {
+    g_err[0] = 0;
+    int rc = check_common(hidden, dtype, 1, T, d, 0, row_stride, packed, w2, eps);
+    if (rc) return rc;
+    if ((uintptr_t)packed & 15) return fail(TIDE_ERR_ALIGNMENT, "packed must be 16-byte aligned");
+    CheckpointTable tab;
+    const int32_t id0 = 0;
+    rc = fill_table(tab, 1, &b2, &threshold, &id0);
+    if (rc) return rc;
+    Outputs o{prob, fire, logit, nullptr, nullptr};
+    return run(hidden, dtype, 1, T, d, 0, row_stride, nullptr, nullptr, packed, eps, b1, w2, tab, 0, 0, o, stream);
+}
+
+int tide_select_exit(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t ckpt_stride,
+                     int64_t row_stride, const float* gamma, float eps, const float* W1, const float* b1,
+                     const float* w2, const float* b2, const float* threshold, const int32_t* layer_ids,
+                     int32_t min_layer, int32_t no_exit_layer, int32_t* exit_layer, float* logits,
+                     uint32_t* fire_mask, void* stream) {
+    g_err[0] = 0;
+    int rc = check_common(hidden, dtype, C, T, d, ckpt_stride, row_stride, W1, w2, eps);
+    if (rc) return rc;
+    CheckpointTable tab;
+    rc = fill_table(tab, C, b2, threshold, layer_ids);
+    if (rc) return rc;
+    if (T > 0 && !exit_layer) return fail(TIDE_ERR_INVALID_ARG, "exit_layer must not be NULL");
+    Outputs o{nullptr, nullptr, logits, exit_layer, fire_mask};
+    return run(hidden, dtype, C, T, d, ckpt_stride, row_stride, gamma, W1, nullptr, eps, b1, w2, tab, min_layer,
+               no_exit_layer, o, stream);
+}
+
+int tide_select_exit_packed(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t ckpt_stride,
+                            int64_t row_stride, const void* packed, float eps, const float* b1, const float* w2,
+                            const float* b2, const float* threshold, const int32_t* layer_ids, int32_t min_layer,
+                            int32_t no_exit_layer, int32_t* exit_layer, float* logits, uint32_t* fire_mask,
+                            void* stream) {
+    g_err[0] = 0;
+    int rc = check_common(hidden, dtype, C, T, d, ckpt_stride, row_stride, packed, w2, eps);
+    if (rc) return rc;
+    if ((uintptr_t)packed & 15) return fail(TIDE_ERR_ALIGNMENT, "packed must be 16-byte aligned");
+    CheckpointTable tab;
+    rc = fill_table(tab, C, b2, threshold, layer_ids);
+    if (rc) return rc;
+    if (T > 0 && !exit_layer) return fail(TIDE_ERR_INVALID_ARG, "exit_layer must not be NULL");
+    Outputs o{nullptr, nullptr, logits, exit_layer, fire_mask};
+    return run(hidden, dtype, C, T, d, ckpt_stride, row_stride, nullptr, nullptr, packed, eps, b1, w2, tab, min_layer,
+               no_exit_layer, o, stream);
+}
+
+int tide_set_variant(int variant) {
+    if (variant != TIDE_VARIANT_AUTO && variant != TIDE_VARIANT_PREFILL && variant != TIDE_VARIANT_DECODE)
+        return fail(TIDE_ERR_INVALID_ARG, "variant %d is not a tide_variant_t", variant);
+    std::lock_guard<std::mutex> lock(g_mu);
+    int prev = g_variant;
+    g_variant = variant;
+    return prev;
+}
+
+int tide_release(void) {
+    g_err[0] = 0;
+    std::lock_guard<std::mutex> lock(g_mu);
+    Workspace* ws = nullptr;
+    int rc = current_workspace(&ws);
+    if (rc) return rc;
+    TIDE_HIP(hipDeviceSynchronize());
+    for (Buffer* b : {&ws->counters, &ws->stage, &ws->packed, &ws->part}) {
+        if (b->ptr) TIDE_HIP(hipFree(b->ptr));
+        b->ptr = nullptr;
+        b->bytes = 0;
+    }
+    return TIDE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,236 @@
+"""Python binding of libtide_route (ctypes): argument marshalling only.
+
+Every function has the name and argument order of its C entry point in
+``include/tide_route.h``; tensors are torch CUDA tensors used for their device memory,
+and work goes onto torch's current stream.  All arithmetic runs in the HIP kernels: if
+the shared library is missing and cannot be built, importing a function fails loudly.
+bf16 hidden states may be given as ``torch.bfloat16`` or as ``torch.uint16``/``int16``
+bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+from .build import LIB_PATH, build_library
+
+F32, F16, BF16 = 0, 1, 2
+VARIANT_AUTO, VARIANT_PREFILL, VARIANT_DECODE = 0, 1, 2
+BOTTLENECK = 128
+DTYPE_CODES = {"f32": F32, "f16": F16, "bf16": BF16}
+
+EXPORTS = (
+    "tide_version", "tide_last_error", "tide_router_eval", "tide_select_exit",
+    "tide_packed_router_bytes", "tide_router_pack", "tide_router_eval_packed",
+    "tide_select_exit_packed", "tide_set_variant", "tide_release",
+)
+
+_lib = None
+
+
+class TideError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"libtide_route status {status}: {message}")
+        self.status = status
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the in-tree libtide_route.so, building it first only if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        build_library()
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, f32, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_int
+    lib.tide_version.restype = ci
+    lib.tide_last_error.restype = ctypes.c_char_p
+    lib.tide_router_eval.argtypes = [vp, ci, i64, i64, i64, vp, f32, vp, vp, vp, f32, f32, vp, vp, vp, vp]
+    lib.tide_router_eval_packed.argtypes = [vp, ci, i64, i64, i64, vp, f32, vp, vp, f32, f32, vp, vp, vp, vp]
+    lib.tide_select_exit.argtypes = [vp, ci, i64, i64, i64, i64, i64, vp, f32, vp, vp, vp, vp, vp, vp, i32, i32,
+                                     vp, vp, vp, vp]
+    lib.tide_select_exit_packed.argtypes = [vp, ci, i64, i64, i64, i64, i64, vp, f32, vp, vp, vp, vp, vp, i32, i32,
+                                            vp, vp, vp, vp]
+    lib.tide_packed_router_bytes.argtypes = [ci, i64]
+    lib.tide_packed_router_bytes.restype = ctypes.c_size_t
+    lib.tide_router_pack.argtypes = [ci, i64, i64, vp, vp, vp, vp]
+    lib.tide_set_variant.argtypes = [ci]
+    for name in ("tide_router_eval", "tide_router_eval_packed", "tide_select_exit", "tide_select_exit_packed",
+                 "tide_router_pack", "tide_set_variant", "tide_release"):
+        getattr(lib, name).restype = ci
+    _lib = lib
+    return lib
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise TideError(status, load_library().tide_last_error().decode())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.float16:
+        return F16
+    if t.dtype in (torch.bfloat16, torch.uint16, torch.int16):
+        return BF16
+    raise TypeError(f"unsupported hidden dtype {t.dtype}")
+
+
+def _ptr(t) -> int | None:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("device tensors are required")
+    return t.data_ptr()
+
+
+def _f32dev(t, shape, name):
+    if t is None:
+        return None
+    if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must be a contiguous CUDA float32 tensor of shape {tuple(shape)}")
+    return t
+
+
+def _host(a, C, np_dtype):
+    a = np.ascontiguousarray(np.broadcast_to(np.asarray(a, dtype=np_dtype), (C,)))
+    return a, a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _rows(hidden: torch.Tensor, ndim: int):
+    """Strides (in elements) of a [.., T, d] tensor whose last dimension is contiguous."""
+    if hidden.dim() != ndim or (hidden.shape[-1] > 1 and hidden.stride(-1) != 1):
+        raise ValueError(f"hidden must be {ndim}-dimensional with a contiguous last dimension")
+    return hidden.shape, hidden.stride()
+
+
+def version() -> int:
+    return int(load_library().tide_version())
+
+
+def last_error() -> str:
+    return load_library().tide_last_error().decode()
+
+
+def set_variant(variant: int) -> int:
+    prev = load_library().tide_set_variant(int(variant))
+    if prev < 0:
+        _check(prev)
+    return prev
+
+
+def release() -> None:
+    _check(load_library().tide_release())
+
+
+def packed_router_bytes(dtype: int, d: int) -> int:
+    return int(load_library().tide_packed_router_bytes(int(dtype), int(d)))
+
+
+def router_pack(dtype: int, gamma, W1) -> torch.Tensor:
+    """gamma [C,d] | None, W1 [C,d,128] (device fp32) -> packed weights (device uint8 buffer)."""
+    C, d, b = W1.shape
+    if b != BOTTLENECK:
+        raise ValueError("bottleneck must be 128")
+    _f32dev(W1, (C, d, b), "W1")
+    _f32dev(gamma, (C, d), "gamma")
+    nbytes = packed_router_bytes(dtype, d)
+    if nbytes == 0:
+        raise TideError(-2, f"unsupported dtype {dtype} or d {d}")
+    packed = torch.empty(C * nbytes, dtype=torch.uint8, device=W1.device)
+    _check(load_library().tide_router_pack(int(dtype), C, d, _ptr(gamma), _ptr(W1), _ptr(packed), _stream()))
+    return packed
+
+
+def _eval_outputs(T, device, want_prob, want_fire, want_logit):
+    prob = torch.empty(T, dtype=torch.float32, device=device) if want_prob else None
+    fire = torch.empty(T, dtype=torch.uint8, device=device) if want_fire else None
+    logit = torch.empty(T, dtype=torch.float32, device=device) if want_logit else None
+    return prob, fire, logit
+
+
+def router_eval(hidden, gamma, eps, W1, b1, w2, b2, threshold, *, d=None, want_prob=True, want_fire=True,
+                want_logit=True):
+    """hidden [T, >=d]; gamma [d] | None; W1 [d,128]; b1 [128] | None; w2 [128] -> (prob, fire, logit)."""
+    (T, width), (rs, _) = _rows(hidden, 2)
+    d = int(W1.shape[0]) if d is None else int(d)
+    _f32dev(W1, (d, BOTTLENECK), "W1"), _f32dev(gamma, (d,), "gamma")
+    _f32dev(b1, (BOTTLENECK,), "b1"), _f32dev(w2, (BOTTLENECK,), "w2")
+    if width < d:
+        raise ValueError("hidden rows are shorter than d")
+    prob, fire, logit = _eval_outputs(T, hidden.device, want_prob, want_fire, want_logit)
+    _check(load_library().tide_router_eval(_ptr(hidden), _dtype_code(hidden), T, d, rs if T > 1 else max(rs, d),
+                                           _ptr(gamma), float(eps), _ptr(W1), _ptr(b1), _ptr(w2), float(b2),
+                                           float(threshold), _ptr(prob), _ptr(fire), _ptr(logit), _stream()))
+    return prob, fire, logit
+
+
+def router_eval_packed(hidden, packed, eps, b1, w2, b2, threshold, *, d, want_prob=True, want_fire=True,
+                       want_logit=True):
+    (T, width), (rs, _) = _rows(hidden, 2)
+    _f32dev(b1, (BOTTLENECK,), "b1"), _f32dev(w2, (BOTTLENECK,), "w2")
+    if width < d:
+        raise ValueError("hidden rows are shorter than d")
+    prob, fire, logit = _eval_outputs(T, hidden.device, want_prob, want_fire, want_logit)
+    _check(load_library().tide_router_eval_packed(_ptr(hidden), _dtype_code(hidden), T, int(d),
+                                                  rs if T > 1 else max(rs, d), _ptr(packed), float(eps), _ptr(b1),
+                                                  _ptr(w2), float(b2), float(threshold), _ptr(prob), _ptr(fire),
+                                                  _ptr(logit), _stream()))
+    return prob, fire, logit
+
+
+def _select_common(hidden, d, b1, w2, b2, threshold, layer_ids, want_logits, want_mask, out):
+    (C, T, width), (cs, rs, _) = _rows(hidden, 3)
+    if width < d:
+        raise ValueError("hidden rows are shorter than d")
+    _f32dev(b1, (C, BOTTLENECK), "b1"), _f32dev(w2, (C, BOTTLENECK), "w2")
+    b2h, b2p = _host(b2, C, np.float32)
+    thh, thp = _host(threshold, C, np.float32)
+    idh, idp = _host(layer_ids, C, np.int32)
+    dev = hidden.device
+    if out is None:
+        exit_layer = torch.empty(T, dtype=torch.int32, device=dev)
+        logits = torch.empty((C, T), dtype=torch.float32, device=dev) if want_logits else None
+        mask = torch.empty(T, dtype=torch.int32, device=dev) if want_mask else None
+    else:
+        exit_layer, logits, mask = out
+    cs = cs if (C > 1 and T > 0) else max(cs, 0)
+    rs = rs if T > 1 else max(rs, d)
+    keep = (b2h, thh, idh)
+    return C, T, cs, rs, b2p, thp, idp, exit_layer, logits, mask, keep
+
+
+def select_exit(hidden, gamma, eps, W1, b1, w2, b2, threshold, layer_ids, min_layer, no_exit_layer, *,
+                want_logits=True, want_mask=True, out=None):
+    """hidden [C,T,>=d]; gamma [C,d] | None; W1 [C,d,128]; b1 [C,128] | None; w2 [C,128]; b2, threshold,
+    layer_ids: host sequences of length C (or scalars) -> (exit_layer i32[T], logits f32[C,T], fire_mask i32[T])."""
+    d = int(W1.shape[1])
+    C, T, cs, rs, b2p, thp, idp, exit_layer, logits, mask, keep = _select_common(
+        hidden, d, b1, w2, b2, threshold, layer_ids, want_logits, want_mask, out)
+    _f32dev(W1, (C, d, BOTTLENECK), "W1"), _f32dev(gamma, (C, d), "gamma")
+    _check(load_library().tide_select_exit(_ptr(hidden), _dtype_code(hidden), C, T, d, cs, rs, _ptr(gamma),
+                                           float(eps), _ptr(W1), _ptr(b1), _ptr(w2), b2p, thp, idp, int(min_layer),
+                                           int(no_exit_layer), _ptr(exit_layer), _ptr(logits), _ptr(mask),
+                                           _stream()))
+    del keep
+    return exit_layer, logits, mask
+
+
+def select_exit_packed(hidden, packed, eps, b1, w2, b2, threshold, layer_ids, min_layer, no_exit_layer, *, d,
+                       want_logits=True, want_mask=True, out=None):
+    C, T, cs, rs, b2p, thp, idp, exit_layer, logits, mask, keep = _select_common(
+        hidden, int(d), b1, w2, b2, threshold, layer_ids, want_logits, want_mask, out)
+    _check(load_library().tide_select_exit_packed(_ptr(hidden), _dtype_code(hidden), C, T, int(d), cs, rs,
+                                                  _ptr(packed), float(eps), _ptr(b1), _ptr(w2), b2p, thp, idp,
+                                                  int(min_layer), int(no_exit_layer), _ptr(exit_layer), _ptr(logits),
+                                                  _ptr(mask), _stream()))
+    del keep
+    return exit_layer, logits, mask

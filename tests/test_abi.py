@@ -1,0 +1,101 @@
+"""CPU-side checks of the boundary: the shared library loads, exports every symbol the
+header declares, and rejects bad arguments before anything is enqueued (no GPU needed:
+none of these calls reaches a kernel launch)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from conftest import ROOT, read_golden
+from paper_2603_21365_amd import stats
+from paper_2603_21365_amd import tide_route as tr
+
+HEADER = os.path.join(ROOT, "include", "tide_route.h")
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tide_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = tr.load_library()
+    names = declared_symbols()
+    assert set(names) == set(tr.EXPORTS), (names, tr.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert tr.version() >= 100
+    assert tr.last_error() == "" or isinstance(tr.last_error(), str)
+
+
+def test_packed_size_query():
+    assert tr.packed_router_bytes(tr.BF16, 4096) == 4096 * 128 * 2
+    assert tr.packed_router_bytes(tr.F32, 768) == 768 * 128 * 4
+    assert tr.packed_router_bytes(tr.F16, 100) == 0
+    assert tr.packed_router_bytes(7, 4096) == 0
+
+
+FAKE = 0x10000  # never dereferenced: every call below fails its checks first
+
+
+def _eval(lib, hidden=FAKE, dtype=2, T=4, d=256, rs=256, W1=FAKE, w2=FAKE, eps=1e-6):
+    return lib.tide_router_eval(hidden, dtype, T, d, rs, None, eps, W1, None, w2, 0.0, 0.5, None, None, None, None)
+
+
+def test_router_eval_rejects_bad_arguments():
+    lib = tr.load_library()
+    assert _eval(lib, dtype=5) == -1 and "dtype" in tr.last_error()
+    assert _eval(lib, T=-1) == -1
+    assert _eval(lib, d=0) == -1
+    assert _eval(lib, d=100, rs=100) == -2 and "128" in tr.last_error()
+    assert _eval(lib, d=32768, rs=32768) == -2
+    assert _eval(lib, rs=128) == -1
+    assert _eval(lib, hidden=None) == -1
+    assert _eval(lib, W1=None) == -1
+    assert _eval(lib, w2=None) == -1
+    assert _eval(lib, eps=-1.0) == -1
+    assert _eval(lib, eps=float("nan")) == -1
+    assert _eval(lib, hidden=FAKE + 2) == -3
+    assert _eval(lib, rs=260) == -3            # 260 bf16 = 520 bytes: not a multiple of 16
+    assert _eval(lib, T=0, hidden=None, W1=None, w2=None) == 0   # empty input: successful no-op
+
+
+def test_select_exit_rejects_bad_arguments():
+    lib = tr.load_library()
+    def call(C=2, T=4, d=256, ids=(3, 7), b2=(0, 0), th=(.5, .5), exit_ptr=FAKE, cs=1024, hidden=FAKE):
+        b2a, tha = np.asarray(b2, np.float32), np.asarray(th, np.float32)
+        ida = np.asarray(ids, np.int32) if ids is not None else None
+        p = lambda a: a.ctypes.data_as(ctypes.c_void_p) if a is not None else None
+        return lib.tide_select_exit(hidden, 2, C, T, d, cs, d, None, 1e-6, FAKE, None, FAKE, p(b2a), p(tha),
+                                    p(ida), 0, 32, exit_ptr, None, None, None)
+
+    assert call(ids=(7, 3)) == -1 and "ascending" in tr.last_error()
+    assert call(ids=(3, 3)) == -1
+    assert call(ids=None) == -1
+    assert call(C=0, ids=(), b2=(), th=()) == -1
+    assert call(C=33, ids=tuple(range(33)), b2=(0,) * 33, th=(.5,) * 33) == -2
+    assert call(exit_ptr=None) == -1
+    assert call(cs=1028) == -3
+    assert call(T=0, hidden=None) == 0
+
+
+def test_set_variant_validates():
+    prev = tr.set_variant(tr.VARIANT_AUTO)
+    assert prev in (0, 1, 2)
+    with pytest.raises(tr.TideError):
+        tr.set_variant(9)
+    tr.set_variant(prev)
+
+
+def test_exit_statistics_reproduce_fig3(golden_dir):
+    g = read_golden(os.path.join(golden_dir, "fig3_exit_example.txt"))
+    ex = [int(x) for x in g["exit_layers"]]
+    used, full, saved = stats.layer_ops(ex, int(g["n_layers"][0]))
+    assert (used, full) == (int(g["layer_ops"][0]), int(g["layer_ops_full"][0]))
+    assert round(100 * saved) == int(g["reduction_percent_rounded"][0])
+    hist = stats.exit_histogram(ex, [int(x) for x in g["router_layers"]], int(g["n_layers"][0]))
+    assert hist == {"L8": 1, "L16": 1, "none": 1}
+    assert stats.exit_rate(ex, 32) == pytest.approx(2 / 3)

@@ -1,0 +1,316 @@
+"""GPU parity: libtide_route (through its C ABI, via the ctypes binding) against the fp64
+oracle on the same seeded bytes -- element by element at sizes the oracle finishes in
+seconds, on sampled tokens plus size-independent properties at the sweep's full sizes."""
+import time
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2603_21365_amd import synth
+from parity import (TOL, check_self_consistent, compare_select, oracle_select, report, routers_to_device,
+                    thr_logits, to_device)
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(f"[gpu-case] {msg}", flush=True)
+
+
+@pytest.fixture(scope="module")
+def tr():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2603_21365_amd import tide_route
+    tide_route.load_library()
+    yield tide_route
+    tide_route.set_variant(tide_route.VARIANT_AUTO)
+
+
+def calibrated(w, hidden_bits):
+    """Routers of workload w with b2 set from the oracle's b2 = 0 logits."""
+    rt = w.routers()
+    if w.fire_rate is not None:
+        _, z0, _ = oracle_select(w, rt, hidden_bits)
+        rt.b2 = synth.calibrate_b2(z0, w.fire_rate)
+    return rt
+
+
+def gpu_select(tr, w, rt, hidden_dev, *, packed=False, min_layer=0, no_exit=None, variant=None, d=None):
+    import torch
+    no_exit = w.n_layers if no_exit is None else no_exit
+    g, W1, b1, w2 = routers_to_device(rt)
+    if variant is not None:
+        tr.set_variant(variant)
+    try:
+        if packed:
+            pk = tr.router_pack(tr.DTYPE_CODES[w.dtype], g, W1)
+            out = tr.select_exit_packed(hidden_dev, pk, w.eps, b1, w2, rt.b2, rt.theta, w.layer_ids, min_layer,
+                                        no_exit, d=w.d if d is None else d)
+        else:
+            out = tr.select_exit(hidden_dev, g, w.eps, W1, b1, w2, rt.b2, rt.theta, w.layer_ids, min_layer, no_exit)
+        torch.cuda.synchronize()
+    finally:
+        tr.set_variant(tr.VARIANT_AUTO)
+    return [o.cpu().numpy() for o in out]
+
+
+def run_and_compare(tr, w, name, *, packed=False, variant=None, min_layer=0, rt=None, hidden_bits=None):
+    say(f"{name}: dtype={w.dtype} C={w.C} T={w.T} d={w.d} packed={packed} variant={variant}")
+    hidden_bits = w.hidden() if hidden_bits is None else hidden_bits
+    rt = calibrated(w, hidden_bits) if rt is None else rt
+    ex_o, z_o, m_o = oracle_select(w, rt, hidden_bits, min_layer=min_layer)
+    ex_g, z_g, m_g = gpu_select(tr, w, rt, to_device(hidden_bits, w.dtype), packed=packed, variant=variant,
+                                min_layer=min_layer)
+    st = compare_select(name, w.dtype, z_g, ex_g, m_g, z_o, ex_o, m_o, rt.theta, w.layer_ids, min_layer, w.n_layers)
+    report(st)
+    return st, (ex_o, z_o, m_o), (ex_g, z_g, m_g)
+
+
+# ------------------------------------------------------------------ config 0: tiny fp32
+
+@pytest.mark.parametrize("variant", ["prefill", "decode"])
+def test_config0_router_eval(tr, variant):
+    import torch
+    w = synth.config0()
+    say(f"config0 router_eval variant={variant}")
+    h = w.hidden()
+    rt = w.routers()
+    z_o, p_o, f_o = oracle.router_eval(h[0], "f32", rt.gamma[0], w.eps, rt.W1[0], rt.b1[0], rt.w2[0], 0.0, 0.5)
+    g, W1, b1, w2 = routers_to_device(rt)
+    tr.set_variant({"prefill": tr.VARIANT_PREFILL, "decode": tr.VARIANT_DECODE}[variant])
+    try:
+        prob, fire, logit = tr.router_eval(to_device(h[0], "f32"), g[0], w.eps, W1[0], b1[0], w2[0], 0.0, 0.5)
+        torch.cuda.synchronize()
+    finally:
+        tr.set_variant(tr.VARIANT_AUTO)
+    z_g, p_g, f_g = logit.cpu().numpy(), prob.cpu().numpy(), fire.cpu().numpy()
+    err = np.abs(z_g - z_o).max()
+    print(f"PARITY name=config0_{variant} rows=64 max_abs_err={err:.3e}", flush=True)
+    assert err <= TOL["f32"]
+    assert np.abs(p_g - p_o).max() <= TOL["f32"]
+    near = np.abs(z_o) <= TOL["f32"]
+    assert np.array_equal(f_g[~near], f_o[~near])
+    assert set(np.unique(f_g)) <= {0, 1}
+
+
+# ------------------------------------------------------------------ config 1: 8B-shaped prefill, bf16, full size
+
+@pytest.mark.parametrize("packed", [False, True])
+def test_config1_full(tr, packed):
+    w = synth.config1()
+    st, (ex_o, _, m_o), _ = run_and_compare(tr, w, f"config1_packed{int(packed)}", packed=packed)
+    fired = [(int(((m_o >> c) & 1).sum())) for c in range(w.C)]
+    assert fired == [round(0.30 * w.T)] * w.C          # the generator's stated firing rate
+    assert st["max_abs_err"] < 1e-2                      # bf16 W1' rounding: well inside the 2e-2 bar
+
+
+# ------------------------------------------------------------------ config 2: decode, fp16
+
+@pytest.mark.parametrize("T", [1, 8])
+def test_config2_decode(tr, T):
+    w = synth.config2(T)
+    # routers and b2 as in config 1 (calibrated on the 4096-token bf16 prefill stream)
+    w1 = synth.config1()
+    rt = calibrated(w1, w1.hidden())
+    hb = w.hidden()
+    st_d, _, (ex_d, z_d, m_d) = run_and_compare(tr, w, f"config2_T{T}_auto", rt=rt, hidden_bits=hb)
+    st_p, _, (ex_p, z_p, m_p) = run_and_compare(tr, w, f"config2_T{T}_prefill", rt=rt, hidden_bits=hb,
+                                                variant=tr.VARIANT_PREFILL)
+    assert st_d["max_abs_err"] < 1e-4                    # the decode variant computes in fp32 on fp32 weights
+    assert np.abs(z_d - z_p).max() < 2e-2
+
+
+# ------------------------------------------------------------------ config 3: 36-layer batched prefill, bf16, full size
+
+def test_config3_full(tr):
+    w = synth.config3()
+    t0 = time.time()
+    st, (ex_o, _, m_o), _ = run_and_compare(tr, w, "config3", packed=True)
+    say(f"config3 done in {time.time() - t0:.1f}s")
+    assert [(int(((m_o >> c) & 1).sum())) for c in range(w.C)] == [round(0.20 * w.T)] * w.C
+
+
+# ------------------------------------------------------------------ config 4: hidden-size x dtype sweep
+
+N_SAMPLE = 2048
+
+
+@pytest.mark.parametrize("d", synth.SWEEP_D)
+def test_config4_sweep(tr, d):
+    """Full T = 16384 on the GPU; the oracle checks a seeded sample of 2048 tokens per point
+    element by element, and the size-independent properties are checked on all tokens."""
+    rng = np.random.default_rng(4000 + d)
+    base = synth.config4(d, "f32")
+    h32 = base.hidden()
+    sample = np.sort(rng.choice(base.T, size=N_SAMPLE, replace=False))
+    for dtype in synth.SWEEP_DTYPES:
+        w = synth.config4(d, dtype)
+        name = f"config4_d{d}_{dtype}"
+        say(f"{name}: C={w.C} T={w.T} layers={w.layer_ids.tolist()}")
+        hb = h32 if dtype == "f32" else synth.to_storage(h32, dtype)
+        hs = np.ascontiguousarray(hb[:, sample, :])
+        rt = w.routers()
+        ws = synth.config4(d, dtype, T=N_SAMPLE)
+        _, z0, _ = oracle_select(ws, rt, hs)
+        rt.b2 = synth.calibrate_b2(z0, w.fire_rate)
+        ex_o, z_o, m_o = oracle_select(ws, rt, hs)
+        ex_g, z_g, m_g = gpu_select(tr, w, rt, to_device(hb, dtype), packed=True)
+        check_self_consistent(name, z_g, ex_g, m_g, rt.theta, w.layer_ids, 0, w.n_layers)
+        st = compare_select(name, dtype, z_g[:, sample], ex_g[sample], m_g[sample], z_o, ex_o, m_o, rt.theta,
+                            w.layer_ids, 0, w.n_layers)
+        report(st)
+        del hb
+
+
+# ------------------------------------------------------------------ edge cases
+
+@pytest.mark.parametrize("T", [1, 63, 64, 65, 130, 257])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_prefill_ragged_tail_and_padded_strides(tr, T, dtype):
+    """Row and checkpoint strides larger than the data, padding filled with NaN: nothing
+    outside the d real elements of the T real rows may influence any output."""
+    import torch
+    d, C, pad_cols, pad_rows = 512, 3, 8, 5
+    w = synth.Workload(f"edge_T{T}_{dtype}", 21, dtype, d, 12, 4, T, None)
+    say(f"{w.name}: prefill variant, row_stride={d + pad_cols}, ckpt_stride=(T+{pad_rows})*row_stride")
+    hb = w.hidden()
+    rt = w.routers()
+    rt.b2[:] = [0.1, -0.1, 0.0]
+    ex_o, z_o, m_o = oracle_select(w, rt, hb)
+    tdt = {"bf16": torch.bfloat16, "f32": torch.float32}[dtype]
+    big = torch.full((C, T + pad_rows, d + pad_cols), float("nan"), dtype=tdt, device="cuda")
+    big[:, :T, :d] = to_device(hb, dtype)
+    view = big[:, :T, :]                       # strides: ((T+5)*(d+8), d+8, 1)
+    g, W1, b1, w2 = routers_to_device(rt)
+    tr.set_variant(tr.VARIANT_PREFILL)
+    try:
+        ex, z, m = tr.select_exit(view, g, w.eps, W1, b1, w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers)
+        torch.cuda.synchronize()
+    finally:
+        tr.set_variant(tr.VARIANT_AUTO)
+    report(compare_select(w.name, dtype, z.cpu().numpy(), ex.cpu().numpy(), m.cpu().numpy(), z_o, ex_o, m_o, rt.theta,
+                          w.layer_ids, 0, w.n_layers))
+
+
+@pytest.mark.parametrize("T", [1, 2, 7, 8, 9, 33, 64])
+@pytest.mark.parametrize("C,dtype", [(1, "f16"), (3, "bf16"), (8, "f32")])
+def test_decode_variant_token_counts(tr, T, C, dtype):
+    w = synth.Workload(f"decode_T{T}_C{C}_{dtype}", 22, dtype, 768, 4 * C, 4, T, None)
+    hb = w.hidden()
+    rt = w.routers()
+    rt.b2[:] = np.linspace(-0.2, 0.2, C)
+    run_and_compare(tr, w, w.name, rt=rt, hidden_bits=hb, variant=tr.VARIANT_DECODE)
+
+
+def test_thresholds_off_and_always_and_min_layer(tr):
+    import torch
+    w = synth.Workload("theta_edges", 23, "bf16", 1024, 16, 4, 200, None)
+    hb = w.hidden()
+    hd = to_device(hb, "bf16")
+    rt = w.routers()
+    for variant in (tr.VARIANT_PREFILL, tr.VARIANT_DECODE):
+        Tuse = 200 if variant == tr.VARIANT_PREFILL else 48
+        wv = synth.Workload("theta_edges", 23, "bf16", 1024, 16, 4, Tuse, None)
+        say(f"theta edges variant={variant} T={Tuse}")
+        h = hd[:, :Tuse].contiguous()
+        rt.theta[:] = 1.0                                    # "1.0 (off)": nothing exits (Table 4)
+        ex, z, m = gpu_select(tr, wv, rt, h, variant=variant)
+        assert np.all(ex == wv.n_layers) and np.all(m == 0)
+        rt.theta[:] = 0.0                                    # everything fires: first eligible checkpoint
+        ex, z, m = gpu_select(tr, wv, rt, h, variant=variant)
+        assert np.all(ex == 3) and np.all(m == 0xF)
+        ex, z, m = gpu_select(tr, wv, rt, h, variant=variant, min_layer=8)
+        assert np.all(ex == 11) and np.all(m == 0xF)
+        ex, z, m = gpu_select(tr, wv, rt, h, variant=variant, min_layer=100, no_exit=-7)
+        assert np.all(ex == -7)
+        rt.theta[:] = [1.0, 0.5, 0.0, 0.5]                   # per-checkpoint thresholds
+        ex_o, z_o, m_o = oracle_select(wv, rt, hb[:, :Tuse], min_layer=0)
+        ex, z, m = gpu_select(tr, wv, rt, h, variant=variant)
+        report(compare_select(f"theta_mixed_v{variant}", "bf16", z, ex, m, z_o, ex_o, m_o, rt.theta, wv.layer_ids, 0,
+                              wv.n_layers))
+        assert np.all(ex <= 11)
+
+
+def test_paper_form_without_gain_and_biases(tr):
+    """gamma = NULL, b1 = NULL, b2 = 0: Eq. (2) exactly as printed."""
+    import torch
+    w = synth.Workload("paper_form", 24, "f16", 2048, 8, 4, 300, None)
+    hb = w.hidden()
+    rt = w.routers()
+    ex_o, z_o, m_o = oracle.select_exit(hb, "f16", None, w.eps, rt.W1, None, rt.w2, rt.b2, rt.theta, w.layer_ids, 0, 8)
+    _, W1, _, w2 = routers_to_device(rt)
+    for variant, T in ((tr.VARIANT_PREFILL, 300), (tr.VARIANT_DECODE, 40)):
+        say(f"paper form variant={variant} T={T}")
+        tr.set_variant(variant)
+        try:
+            ex, z, m = tr.select_exit(to_device(np.ascontiguousarray(hb[:, :T]), "f16"), None, w.eps, W1, None, w2,
+                                      rt.b2, rt.theta, w.layer_ids, 0, 8)
+            torch.cuda.synchronize()
+        finally:
+            tr.set_variant(tr.VARIANT_AUTO)
+        report(compare_select(f"paper_form_v{variant}", "f16", z.cpu().numpy(), ex.cpu().numpy(), m.cpu().numpy(),
+                              z_o[:, :T], ex_o[:T], m_o[:T], rt.theta, w.layer_ids, 0, 8))
+
+
+def test_repeated_and_interleaved_calls_are_deterministic(tr):
+    """The device-side tile counters must return to zero after every call, also when calls
+    with different token counts alternate; results are bit-identical run to run."""
+    import torch
+    wa = synth.Workload("rep_a", 25, "bf16", 1024, 16, 4, 1000, None)
+    wb = synth.Workload("rep_b", 26, "bf16", 1024, 16, 4, 130, None)
+    ha, hb_ = to_device(wa.hidden(), "bf16"), to_device(wb.hidden(), "bf16")
+    ra, rb = wa.routers(), wb.routers()
+    say("repeat/interleave")
+    first_a = gpu_select(tr, wa, ra, ha)
+    first_b = gpu_select(tr, wb, rb, hb_, variant=tr.VARIANT_PREFILL)
+    for i in range(3):
+        again_a = gpu_select(tr, wa, ra, ha)
+        again_b = gpu_select(tr, wb, rb, hb_, variant=tr.VARIANT_PREFILL)
+        for x, y in zip(first_a + first_b, again_a + again_b):
+            assert np.array_equal(x, y)
+    # without the optional outputs the library stages logits in its own workspace
+    g, W1, b1, w2 = routers_to_device(ra)
+    ex, z, m = tr.select_exit(ha, g, wa.eps, W1, b1, w2, ra.b2, ra.theta, wa.layer_ids, 0, 16, want_logits=False,
+                              want_mask=False)
+    torch.cuda.synchronize()
+    assert z is None and m is None and np.array_equal(ex.cpu().numpy(), first_a[0])
+
+
+def test_largest_hidden_size_and_side_stream(tr):
+    import torch
+    w = synth.Workload("d16384", 27, "bf16", 16384, 8, 4, 192, None)
+    hb = w.hidden()
+    rt = w.routers()
+    ex_o, z_o, m_o = oracle_select(w, rt, hb)
+    say("d=16384 on a side stream")
+    s = torch.cuda.Stream()
+    hd = to_device(hb, "bf16")
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        ex, z, m = gpu_select(tr, w, rt, hd, packed=True)
+    report(compare_select("d16384", "bf16", z, ex, m, z_o, ex_o, m_o, rt.theta, w.layer_ids, 0, w.n_layers))
+
+
+def test_router_eval_outputs_are_optional_and_packed_matches_raw(tr):
+    import torch
+    w = synth.Workload("eval_opt", 28, "bf16", 4096, 4, 4, 777, None)
+    hb = w.hidden()
+    rt = w.routers()
+    z_o, p_o, f_o = oracle.router_eval(hb[0], "bf16", rt.gamma[0], w.eps, rt.W1[0], rt.b1[0], rt.w2[0], 0.05, 0.6)
+    g, W1, b1, w2 = routers_to_device(rt)
+    hd = to_device(hb[0], "bf16")
+    say("router_eval raw vs packed, optional outputs")
+    prob, fire, logit = tr.router_eval(hd, g[0], w.eps, W1[0], b1[0], w2[0], 0.05, 0.6)
+    pk = tr.router_pack(tr.BF16, g[:1].contiguous(), W1[:1].contiguous())
+    prob2, fire2, logit2 = tr.router_eval_packed(hd, pk, w.eps, b1[0], w2[0], 0.05, 0.6, d=w.d)
+    only_fire = tr.router_eval(hd, g[0], w.eps, W1[0], b1[0], w2[0], 0.05, 0.6, want_prob=False, want_logit=False)
+    torch.cuda.synchronize()
+    assert torch.equal(logit, logit2) and torch.equal(fire, fire2) and torch.equal(prob, prob2)
+    assert only_fire[0] is None and only_fire[2] is None and torch.equal(only_fire[1], fire)
+    z = logit.cpu().numpy()
+    assert np.abs(z - z_o).max() <= TOL["bf16"]
+    assert np.abs(prob.cpu().numpy() - p_o).max() <= TOL["bf16"]
+    near = np.abs(z_o - thr_logits(0.6)[0]) <= TOL["bf16"]
+    assert np.array_equal(fire.cpu().numpy()[~near], f_o[~near])
