@@ -35,20 +35,18 @@ template <> __device__ __forceinline__ float chunk_sumsq<kF32>(u32x4 c, float ac
     acc = fmaf(x0, x0, acc); acc = fmaf(x1, x1, acc); acc = fmaf(x2, x2, acc); acc = fmaf(x3, x3, acc);
     return acc;
 }
+// The 16-bit forms use the packed dot-product instruction D += a.lo*b.lo + a.hi*b.hi (fp32
+// accumulate).  It is written as inline assembly because this toolchain's
+// __builtin_amdgcn_fdot2* builtins, called with the same value for both operands in an
+// unrolled loop over a vector's elements, emit the first element's register every time.
 template <> __device__ __forceinline__ float chunk_sumsq<kF16>(u32x4 c, float acc) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        f16x2 p = __builtin_bit_cast(f16x2, c[i]);
-        acc = __builtin_amdgcn_fdot2(p, p, acc, false);
-    }
+    for (int i = 0; i < 4; ++i) asm("v_dot2c_f32_f16 %0, %1, %1" : "+v"(acc) : "v"(c[i]));
     return acc;
 }
 template <> __device__ __forceinline__ float chunk_sumsq<kBF16>(u32x4 c, float acc) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        bf16x2 p = __builtin_bit_cast(bf16x2, c[i]);
-        acc = __builtin_amdgcn_fdot2_f32_bf16(p, p, acc, false);
-    }
+    for (int i = 0; i < 4; ++i) asm("v_dot2c_f32_bf16 %0, %1, %1" : "+v"(acc) : "v"(c[i]));
     return acc;
 }
 

@@ -226,7 +226,7 @@ def test_thresholds_off_and_always_and_min_layer(tr):
         ex, z, m = gpu_select(tr, wv, rt, h, variant=variant, min_layer=100, no_exit=-7)
         assert np.all(ex == -7)
         rt.theta[:] = [1.0, 0.5, 0.0, 0.5]                   # per-checkpoint thresholds
-        ex_o, z_o, m_o = oracle_select(wv, rt, hb[:, :Tuse], min_layer=0)
+        ex_o, z_o, m_o = oracle_select(wv, rt, np.ascontiguousarray(hb[:, :Tuse]), min_layer=0)
         ex, z, m = gpu_select(tr, wv, rt, h, variant=variant)
         report(compare_select(f"theta_mixed_v{variant}", "bf16", z, ex, m, z_o, ex_o, m_o, rt.theta, wv.layer_ids, 0,
                               wv.n_layers))
