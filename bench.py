@@ -37,6 +37,10 @@ def main() -> int:
     ap.add_argument("--buffers", type=int, default=4, help="distinct input batches rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-settle", action="store_true", help="skip the untimed settling phase (short profiler runs)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 256 MiB device copy 3 times (known traffic, scales the profiler's "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (the router path shards by tokens with no "
@@ -84,19 +88,45 @@ def main() -> int:
         tr.select_exit_packed(batches[i % args.buffers], packed, w.eps, b1, w2, rt.b2, rt.theta, w.layer_ids, 0,
                               w.n_layers, d=d, out=out)
 
-    def timed(step, steps, warmup):
+    def timed(step, steps, warmup, window=16):
+        """K steps between two synchronisations.  The host keeps at most ~2*window launches
+        queued ahead of the GPU (it waits on an event recorded `window` steps earlier), so the
+        runtime's submission queue never fills and the figure is the GPU's own throughput."""
         for i in range(warmup):
             step(i)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        marks = []
         t0 = time.perf_counter()
         e0.record()
         for i in range(steps):
             step(i)
+            if i % window == window - 1:
+                m = torch.cuda.Event()
+                m.record()
+                marks.append(m)
+                if len(marks) > 2:
+                    marks.pop(0).synchronize()
         e1.record()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         return wall, e0.elapsed_time(e1) * 1e-3
+
+    # Settle: a one-time stall of ~30 ms was observed early in a process's GPU life (the device
+    # idles between two launches; not kernel time).  Run untimed work past it before timing.
+    t_settle = time.perf_counter()
+    if args.copy_probe:
+        src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    while not args.no_settle and time.perf_counter() - t_settle < 0.4:
+        for i in range(32):
+            step_raw(i)
+            step_packed(i)
+        torch.cuda.synchronize()
 
     wall_raw, ev_raw = timed(step_raw, args.steps, args.warmup)
     wall_pk, ev_pk = timed(step_packed, args.steps, args.warmup)

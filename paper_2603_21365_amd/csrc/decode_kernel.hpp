@@ -5,8 +5,8 @@
 // The d-long contraction of each checkpoint is split over S = d/128 workgroups so that the
 // whole chip pulls the weights at once (raw fp32 W1, no packing pass: with so few rows the
 // matrix cores have nothing to amortise).  Each workgroup writes its partial 128-vector and
-// partial sum of squares per token; the last workgroup of a checkpoint (device-scope
-// counter) reduces them in a fixed order, finishes the router, and the last checkpoint to
+// partial sum of squares per token (device-scope stores, no fences); the last workgroup of a
+// checkpoint (device-scope counter) reduces them in a fixed order, finishes the router, and the last checkpoint to
 // finish selects the earliest exit.  One launch, no host round trip, deterministic sums.
 #pragma once
 #include "device_utils.hpp"
@@ -26,7 +26,7 @@ struct DecodeParams {
     float* prob; uint8_t* fire; float* logits;   // [C][T], nullable
     int32_t* exit_layer; uint32_t* fire_mask;    // [T], nullable
     float* stage;         // [C][T]
-    float* part;          // [C][S][T][129]: 128 partial pre-activations + partial sum of squares
+    float* part;          // [C][S][T][kPartStride]
     uint32_t* counter;    // [C+1], zero on entry, zero on exit
     CheckpointTable tab;
 };
@@ -34,7 +34,7 @@ struct DecodeParams {
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeSlice = 128;    // k values per workgroup
 constexpr int kDecodeTB = 8;         // tokens per pass
-constexpr int kPartStride = kBottleneck + 1;
+constexpr int kPartStride = kBottleneck + 4;   // 128 partial pre-activations, the partial sum of squares, pad to 16 bytes
 
 template <int DT> __device__ __forceinline__ void chunk_to_f32(u32x4 c, float* out);
 template <> __device__ __forceinline__ void chunk_to_f32<kF32>(u32x4 c, float* out) {
@@ -62,7 +62,6 @@ __global__ __launch_bounds__(kDecodeThreads) void tide_decode_kernel(const Decod
     __shared__ float xs[kDecodeTB][kDecodeSlice];            // gamma-scaled inputs of this slice
     __shared__ float ss_lds[kDecodeTB];
     __shared__ float red[4][kDecodeTB][kBottleneck];
-    __shared__ float zw[4];
     __shared__ int flag;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -129,70 +128,73 @@ __global__ __launch_bounds__(kDecodeThreads) void tide_decode_kernel(const Decod
                 if (lane < 32) red[wave][t][4 * jq + j] = v;
             }
         __syncthreads();
-        float* part = p.part + (((size_t)c * p.S + s) * p.T + t0) * kPartStride;
-        for (int q = tid; q < nt * kBottleneck; q += kDecodeThreads) {
-            const int t = q >> 7, col = q & 127;
-            stage_store(part + (size_t)t * kPartStride + col,
-                        (red[0][t][col] + red[1][t][col]) + (red[2][t][col] + red[3][t][col]));
+        // thread (tl, q) owns token tl and columns 4q..4q+3 from here on
+        {
+            const int tl = tid >> 5, q = tid & 31;
+            if (tl < nt) {
+                float* dst = p.part + (((size_t)c * p.S + s) * p.T + t0 + tl) * kPartStride;
+                f32x4 v;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    v[j] = (red[0][tl][4 * q + j] + red[1][tl][4 * q + j]) + (red[2][tl][4 * q + j] + red[3][tl][4 * q + j]);
+                stage_store4(dst + 4 * q, v);
+                if (q == 0) stage_store(dst + kBottleneck, ss_lds[tl]);
+            }
         }
-        if (tid < nt) stage_store(part + (size_t)tid * kPartStride + kBottleneck, ss_lds[tid]);
         __syncthreads();
     }
 
     // ---- last workgroup of this checkpoint finishes the router ----
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t prev = __hip_atomic_fetch_add(p.counter + c, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        flag = (prev == (uint32_t)p.S - 1);
-    }
-    __syncthreads();
-    if (!flag) return;
-    __threadfence();
+    stage_writes_done();
+    if (!last_arrival(p.counter + c, (uint32_t)p.S, &flag)) return;
 
-    const int col = tid & 127, half = tid >> 7;       // waves 0,1 -> even token of a pair; 2,3 -> odd
-    const float b1c = p.b1 ? p.b1[c * kBottleneck + col] : 0.0f;
-    const float w2c = p.w2[c * kBottleneck + col];
-    const float* pc = p.part + (size_t)c * p.S * p.T * kPartStride;
-    for (int tp = 0; tp < p.T; tp += 2) {
-        const int t = tp + half;
-        float term = 0.0f;
-        if (t < p.T) {
-            float a = 0.0f, ssum = 0.0f;
-            for (int si = 0; si < p.S; ++si) {
-                const float* q = pc + ((size_t)si * p.T + t) * kPartStride;
-                a += stage_load(q + col);
-                ssum += stage_load(q + kBottleneck);
+    {
+        const int tl = tid >> 5, q = tid & 31;          // 8 tokens x 32 column quads per pass
+        f32x4 b1v = {0, 0, 0, 0};
+        if (p.b1) b1v = *reinterpret_cast<const f32x4*>(p.b1 + c * kBottleneck + 4 * q);
+        const f32x4 w2v = *reinterpret_cast<const f32x4*>(p.w2 + c * kBottleneck + 4 * q);
+        const float* pc = p.part + (size_t)c * p.S * p.T * kPartStride;
+        for (int t0 = 0; t0 < p.T; t0 += kDecodeTB) {
+            const int t = t0 + tl;
+            const bool valid = t < p.T;
+            f32x4 a = {0, 0, 0, 0};
+            float ssum = 0.0f;
+            constexpr int kBatch = 32;                  // partials in flight per thread
+            for (int s0 = 0; s0 < p.S; s0 += kBatch) {
+                f32x4 v[kBatch];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    v[u] = f32x4{0, 0, 0, 0};
+                    if (valid && s0 + u < p.S)
+                        v[u] = stage_load4(pc + ((size_t)(s0 + u) * p.T + t) * kPartStride + 4 * q);
+                }
+                float sv = 0.0f;
+                if (valid && s0 + q < p.S) sv = stage_load(pc + ((size_t)(s0 + q) * p.T + t) * kPartStride + kBottleneck);
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) a += v[u];
+                ssum += xor_reduce_sum<5>(sv);          // fixed order: deterministic
             }
             const float r = 1.0f / sqrtf(ssum / (float)p.d + p.eps);
-            term = w2c * silu_f32(fmaf(r, a, b1c));
+            float term = 0.0f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) term += w2v[j] * silu_f32(fmaf(r, a[j], b1v[j]));
+            term = xor_reduce_sum<5>(term);
+            if (valid && q == 0) {
+                const float z = p.tab.b2[c] + term;
+                const int64_t o = (int64_t)c * p.T + t;
+                if (p.logits && p.logits != p.stage) p.logits[o] = z;
+                if (p.prob) p.prob[o] = sigmoid_f32(z);
+                if (p.fire) p.fire[o] = z > p.tab.thr_logit[c] ? 1 : 0;
+                if (p.exit_layer) stage_store(p.stage + o, z);
+            }
         }
-        term = xor_reduce_sum<6>(term);
-        if (lane == 0) zw[wave] = term;
-        __syncthreads();
-        if ((tid == 0 || tid == 128) && t < p.T) {
-            const float z = p.tab.b2[c] + (zw[2 * half] + zw[2 * half + 1]);
-            const int64_t o = (int64_t)c * p.T + t;
-            if (p.logits) p.logits[o] = z;
-            if (p.prob) p.prob[o] = sigmoid_f32(z);
-            if (p.fire) p.fire[o] = z > p.tab.thr_logit[c] ? 1 : 0;
-            if (p.exit_layer) stage_store(p.stage + o, z);
-        }
-        __syncthreads();
     }
     if (tid == 0) __hip_atomic_store(p.counter + c, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (!p.exit_layer) return;
 
     // ---- last checkpoint to finish selects the earliest exit of every token ----
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t prev = __hip_atomic_fetch_add(p.counter + p.C, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        flag = (prev == (uint32_t)p.C - 1);
-    }
-    __syncthreads();
-    if (!flag) return;
-    __threadfence();
+    stage_writes_done();
+    if (!last_arrival(p.counter + p.C, (uint32_t)p.C, &flag)) return;
     for (int t = tid; t < p.T; t += kDecodeThreads)
         select_earliest(p.tab, p.C, p.min_layer, p.no_exit, p.stage + t, p.T, p.exit_layer + t,
                         p.fire_mask ? p.fire_mask + t : nullptr);

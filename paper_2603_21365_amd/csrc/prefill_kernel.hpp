@@ -10,9 +10,11 @@
 //
 // Workgroup = 256 threads (4 waves) owning kRows rows of one checkpoint and all 128 router
 // columns; wave w owns columns 32w..32w+31.  Per k-tile (kTileBytes of every row):
-//   global -> registers (coalesced 16-byte chunks, 16 lanes per row segment)
+//   global -> registers (coalesced 16-byte chunks, 16 lanes per row segment), kDepth tiles
+//   ahead of their use so that enough bytes are in flight to cover HBM latency
 //   registers -> LDS (padded rows), sum of squares on the way
-//   LDS -> A fragments; W1' fragments straight from L2 in their packed order; MFMA.
+//   LDS -> A fragments; W1' fragments straight from L2 in their packed order (same
+//   kDepth-deep register ring); MFMA.
 // Epilogue: r, +b1, SiLU, *w2, sum over the 128 columns, +b2, sigmoid, threshold; the
 // last workgroup to finish a token tile (device-scope counter) takes the min over the
 // checkpoints, so one launch yields exit_layer with no host round trip.
@@ -52,8 +54,11 @@ constexpr int kChunksPerRow = kTileBytes / 16;                       // 16
 constexpr int kChunksPerThread = kRows * kChunksPerRow / kPrefillThreads;  // 4
 constexpr int kGroupsPerTile = kChunksPerRow / 2;                    // 8
 constexpr int kPitch = kTileBytes + 16;   // LDS row pitch: 16-byte pad staggers the banks
+constexpr int kMaxDepth = 3;              // k-tiles of hidden rows and W1' kept in flight per thread
 
-template <int DT>
+// kDepth = ring depth; the host picks kMaxDepth whenever a row has at least that many k-tiles
+// (the prologue fills the whole ring unconditionally), else 1.
+template <int DT, int kDepth>
 __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const PrefillParams p) {
     __shared__ __attribute__((aligned(16))) char a_lds[2][kRows * kPitch];
     __shared__ float row_ss[kRows];
@@ -84,47 +89,81 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const 
         r = r < p.T ? r : p.T - 1;                 // ragged tail: re-read the last row, never store it
         gptr[i] = base + (int64_t)r * p.row_stride_bytes + cc * 16;
     }
+    const u32x4* bptr = wp + wave * 64 + lane;     // + G*256 per k-group
 
+    // Rows are a power-of-two number of bytes apart and every workgroup starts together, so
+    // walking k from 0 everywhere would make the whole chip hit the same few HBM channels at
+    // once.  Each workgroup starts its k loop at a different tile and wraps (a dot product
+    // does not care about the order of its terms).
     const int ntile = p.d * Storage<DT>::kBytes / kTileBytes;
-    u32x4 areg[kChunksPerThread];
-    u32x4 bcur[kGroupsPerTile], bnext[kGroupsPerTile];
+    int next = (int)(((unsigned)work * 5u) % (unsigned)ntile);
+
+    u32x4 areg[kDepth][kChunksPerThread];
+    u32x4 breg[kDepth][kGroupsPerTile];
     float ss[kChunksPerThread];
 #pragma unroll
     for (int i = 0; i < kChunksPerThread; ++i) ss[i] = 0.0f;
     f32x16 acc0 = {0}, acc1 = {0};
 
+    auto load_a = [&](int j, int kt) {
 #pragma unroll
-    for (int i = 0; i < kChunksPerThread; ++i) areg[i] = *reinterpret_cast<const u32x4*>(gptr[i]);
-    const u32x4* bptr = wp + wave * 64 + lane;     // + G*256 per k-group
+        for (int i = 0; i < kChunksPerThread; ++i)
+            areg[j][i] = *reinterpret_cast<const u32x4*>(gptr[i] + (int64_t)kt * kTileBytes);
+    };
+    auto load_b = [&](int j, int kt) {
 #pragma unroll
-    for (int g = 0; g < kGroupsPerTile; ++g) bcur[g] = bptr[(size_t)g * 256];
+        for (int g = 0; g < kGroupsPerTile; ++g) breg[j][g] = bptr[(size_t)(kt * kGroupsPerTile + g) * 256];
+    };
+
+    // ntile >= kDepth (host-checked): the ring is filled without branches, in the same order
+    // in which the loop refills it, so the wait counts stay exact across the loop entry.
+#pragma unroll
+    for (int j = 0; j < kDepth; ++j) {
+        load_a(j, next);
+        load_b(j, next);
+        next = next + 1 == ntile ? 0 : next + 1;
+    }
 
     const int a_read_off = (lane & 31) * kPitch + (lane >> 5) * 16;
-    for (int kt = 0; kt < ntile; ++kt) {
+    // One k-tile: registers -> LDS, barrier, refill this ring slot (optional), MFMA.
+    auto do_tile = [&](int j, int kt, bool refill) {
         char* buf = a_lds[kt & 1];
 #pragma unroll
         for (int i = 0; i < kChunksPerThread; ++i) {
-            ss[i] = chunk_sumsq<DT>(areg[i], ss[i]);
-            *reinterpret_cast<u32x4*>(buf + (lr0 + 16 * i) * kPitch + cc * 16) = areg[i];
+            ss[i] = chunk_sumsq<DT>(areg[j][i], ss[i]);
+            *reinterpret_cast<u32x4*>(buf + (lr0 + 16 * i) * kPitch + cc * 16) = areg[j][i];
         }
         __syncthreads();
-        if (kt + 1 < ntile) {
-#pragma unroll
-            for (int i = 0; i < kChunksPerThread; ++i)
-                areg[i] = *reinterpret_cast<const u32x4*>(gptr[i] + (int64_t)(kt + 1) * kTileBytes);
-#pragma unroll
-            for (int g = 0; g < kGroupsPerTile; ++g) bnext[g] = bptr[(size_t)((kt + 1) * kGroupsPerTile + g) * 256];
-        }
+        if (refill) load_a(j, next);
 #pragma unroll
         for (int g = 0; g < kGroupsPerTile; ++g) {
             u32x4 a0 = *reinterpret_cast<const u32x4*>(buf + a_read_off + g * 32);
             u32x4 a1 = *reinterpret_cast<const u32x4*>(buf + a_read_off + 32 * kPitch + g * 32);
-            acc0 = mma_kgroup<DT>(a0, bcur[g], acc0);
-            acc1 = mma_kgroup<DT>(a1, bcur[g], acc1);
+            acc0 = mma_kgroup<DT>(a0, breg[j][g], acc0);
+            acc1 = mma_kgroup<DT>(a1, breg[j][g], acc1);
         }
+        if (refill) {
+            load_b(j, next);
+            next = next + 1 == ntile ? 0 : next + 1;
+        }
+    };
+
+    // Steady state: whole ring turns with unconditional refills, so that the compiler's
+    // wait counts see one fixed order of loads and leave kDepth tiles in flight.
+    int kt = 0;
+    const int n_refill = ntile > kDepth ? ntile - kDepth : 0;   // tiles that refill their slot
+    for (; kt + kDepth <= n_refill; kt += kDepth) {
 #pragma unroll
-        for (int g = 0; g < kGroupsPerTile; ++g) bcur[g] = bnext[g];
+        for (int j = 0; j < kDepth; ++j) do_tile(j, kt + j, true);
     }
+    // Tail: the last partial turn with refills, then the tiles already in the ring.
+#pragma unroll
+    for (int j = 0; j < kDepth; ++j)
+        if (kt + j < ntile) do_tile(j, kt + j, kt + j < n_refill);
+    kt += kDepth;
+#pragma unroll
+    for (int j = 0; j < kDepth; ++j)
+        if (kt + j < ntile) do_tile(j, kt + j, false);
 
     // ---- row scale: the 16 lanes that share a row hold its partial sums of squares ----
 #pragma unroll
@@ -158,7 +197,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const 
         if (t < p.T) {
             const float z = p.tab.b2[c] + ((z_part[0][tid] + z_part[1][tid]) + (z_part[2][tid] + z_part[3][tid]));
             const int64_t o = (int64_t)c * p.T + t;
-            if (p.logits) p.logits[o] = z;
+            if (p.logits && p.logits != p.stage) p.logits[o] = z;
             if (p.prob) p.prob[o] = sigmoid_f32(z);
             if (p.fire) p.fire[o] = z > p.tab.thr_logit[c] ? 1 : 0;
             if (p.exit_layer) stage_store(p.stage + o, z);
@@ -167,15 +206,8 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const 
     if (!p.exit_layer) return;
 
     // ---- earliest exit: the last workgroup to finish this token tile selects ----
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t prev = __hip_atomic_fetch_add(p.tile_counter + tile, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        is_last = (prev == (uint32_t)p.C - 1);
-    }
-    __syncthreads();
-    if (!is_last) return;
-    __threadfence();
+    stage_writes_done();
+    if (!last_arrival(p.tile_counter + tile, (uint32_t)p.C, &is_last)) return;
     if (tid < kRows) {
         const int t = row0 + tid;
         if (t < p.T)

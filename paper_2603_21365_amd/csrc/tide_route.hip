@@ -198,8 +198,13 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
         }
     }
     const unsigned grid = 8u * (unsigned)((p.total_tiles + 7) / 8);
+    const int ntile = (int)(d * (int64_t)eb / kTileBytes);
     by_dtype(dtype, [&](auto dt) {
-        hipLaunchKernelGGL((tide_prefill_kernel<decltype(dt)::value>), dim3(grid), dim3(kPrefillThreads), 0, st, p);
+        constexpr int DT = decltype(dt)::value;
+        if (ntile >= kMaxDepth)
+            hipLaunchKernelGGL((tide_prefill_kernel<DT, kMaxDepth>), dim3(grid), dim3(kPrefillThreads), 0, st, p);
+        else
+            hipLaunchKernelGGL((tide_prefill_kernel<DT, 1>), dim3(grid), dim3(kPrefillThreads), 0, st, p);
         return 0;
     });
     TIDE_HIP(hipGetLastError());
