@@ -129,6 +129,11 @@ int tide_select_exit_packed(const void* hidden, int dtype, int64_t C, int64_t T,
  * benchmarks).  Returns the previous setting, or TIDE_ERR_INVALID_ARG.                  */
 int tide_set_variant(int variant);
 
+/* Choose the prefill kernel's form (process-wide; for tests and tuning): 0 = automatic,
+ * 1 / 2 = streaming form with 64 / 128 rows per workgroup, 3 = register-ring form.
+ * All forms compute the same function.  Returns the previous setting, or TIDE_ERR_INVALID_ARG. */
+int tide_set_prefill_form(int form);
+
 /* Free the current device's workspace (synchronises that device).                       */
 int tide_release(void);
 

@@ -6,8 +6,8 @@
 // whole chip pulls the weights at once (raw fp32 W1, no packing pass: with so few rows the
 // matrix cores have nothing to amortise).  Each workgroup writes its partial 128-vector and
 // partial sum of squares per token (device-scope stores, no fences); the last workgroup of a
-// checkpoint (device-scope counter) reduces them in a fixed order, finishes the router, and the last checkpoint to
-// finish selects the earliest exit.  One launch, no host round trip, deterministic sums.
+// checkpoint (device-scope counter) reduces them in a fixed order and finishes the router; the last checkpoint to
+// report a token selects its earliest exit.  One launch, no host round trip, deterministic sums.
 #pragma once
 #include "device_utils.hpp"
 
@@ -25,9 +25,9 @@ struct DecodeParams {
     int32_t min_layer, no_exit;
     float* prob; uint8_t* fire; float* logits;   // [C][T], nullable
     int32_t* exit_layer; uint32_t* fire_mask;    // [T], nullable
-    float* stage;         // [C][T]
+    uint64_t* arrive;     // [T] arrival words (see report_and_select), zero on entry and on exit
     float* part;          // [C][S][T][kPartStride]
-    uint32_t* counter;    // [C+1], zero on entry, zero on exit
+    uint32_t* counter;    // [C], zero on entry, zero on exit
     CheckpointTable tab;
 };
 
@@ -182,23 +182,17 @@ __global__ __launch_bounds__(kDecodeThreads) void tide_decode_kernel(const Decod
             if (valid && q == 0) {
                 const float z = p.tab.b2[c] + term;
                 const int64_t o = (int64_t)c * p.T + t;
-                if (p.logits && p.logits != p.stage) p.logits[o] = z;
+                const bool f = z > p.tab.thr_logit[c];
+                if (p.logits) p.logits[o] = z;
                 if (p.prob) p.prob[o] = sigmoid_f32(z);
-                if (p.fire) p.fire[o] = z > p.tab.thr_logit[c] ? 1 : 0;
-                if (p.exit_layer) stage_store(p.stage + o, z);
+                if (p.fire) p.fire[o] = f ? 1 : 0;
+                if (p.exit_layer)
+                    report_and_select(p.tab, p.C, c, f, p.min_layer, p.no_exit, p.arrive + t, p.exit_layer + t,
+                                      p.fire_mask ? p.fire_mask + t : nullptr);
             }
         }
     }
     if (tid == 0) __hip_atomic_store(p.counter + c, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (!p.exit_layer) return;
-
-    // ---- last checkpoint to finish selects the earliest exit of every token ----
-    stage_writes_done();
-    if (!last_arrival(p.counter + p.C, (uint32_t)p.C, &flag)) return;
-    for (int t = tid; t < p.T; t += kDecodeThreads)
-        select_earliest(p.tab, p.C, p.min_layer, p.no_exit, p.stage + t, p.T, p.exit_layer + t,
-                        p.fire_mask ? p.fire_mask + t : nullptr);
-    if (tid == 0) __hip_atomic_store(p.counter + p.C, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 }  // namespace tide

@@ -66,11 +66,17 @@ template <> __device__ __forceinline__ f32x16 mma_kgroup<kF32>(u32x4 a, u32x4 b,
     return acc;
 }
 
+// sigmoid and SiLU on the hardware exp / reciprocal units (about 1 ulp each): the router's
+// tolerance is 1e-4 absolute on a sum of 128 terms of order 0.1, and IEEE-exact division
+// and square root cost an order of magnitude more instructions in the per-row epilogue.
 __device__ __forceinline__ float sigmoid_f32(float x) {
-    // 1/(1+e^-x); e^-x overflows to +inf for x < -88 and the quotient is then exactly 0
-    return 1.0f / (1.0f + __expf(-x));
+    // e^-x overflows to +inf for x < -88 and the reciprocal is then exactly 0
+    return __builtin_amdgcn_rcpf(1.0f + __expf(-x));
 }
 __device__ __forceinline__ float silu_f32(float x) { return x * sigmoid_f32(x); }
+__device__ __forceinline__ float inv_rms_f32(float sumsq, float inv_d, float eps) {
+    return __builtin_amdgcn_rsqf(fmaf(sumsq, inv_d, eps));
+}
 
 // Butterfly sum over the lanes that differ in the low `kBits` bits of the lane id: every
 // participating lane ends up with the total (no broadcast step to forget).
@@ -78,6 +84,49 @@ template <int kBits> __device__ __forceinline__ float xor_reduce_sum(float v) {
 #pragma unroll
     for (int s = 1; s < (1 << kBits); s <<= 1) v += __shfl_xor(v, s, kWave);
     return v;
+}
+
+// Sum each of 16 per-lane values over the 32 lanes that share lane>>5, leaving every lane
+// with ONE finished total (a reduce-scatter: 8+4+2+1+1 exchanges instead of 16 x 5).
+// The total a lane ends up with is that of index v = bits (4,3,2,1) of its lane id; lanes
+// 2k and 2k+1 hold the same one.
+__device__ __forceinline__ float reduce_scatter16(const float (&x)[16], int lane) {
+    float y8[8], y4[4], y2[2];
+    bool hi = lane & 16;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) y8[i] = (hi ? x[i + 8] : x[i]) + __shfl_xor(hi ? x[i] : x[i + 8], 16, kWave);
+    hi = lane & 8;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) y4[i] = (hi ? y8[i + 4] : y8[i]) + __shfl_xor(hi ? y8[i] : y8[i + 4], 8, kWave);
+    hi = lane & 4;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) y2[i] = (hi ? y4[i + 2] : y4[i]) + __shfl_xor(hi ? y4[i] : y4[i + 2], 4, kWave);
+    hi = lane & 2;
+    float y = (hi ? y2[1] : y2[0]) + __shfl_xor(hi ? y2[0] : y2[1], 2, kWave);
+    return y + __shfl_xor(y, 1, kWave);
+}
+
+// Router epilogue for one consumer wave holding kBlocks 32x32 accumulator blocks (rows
+// 32b..32b+31 of the tile, this wave's 32 columns; matrix-core C layout: lane l has column
+// l%32 and, in register v, row 8*(v/4) + 4*(l/32) + v%4).  Applies the row scale, bias and
+// SiLU, multiplies by w2 and sums over the wave's 32 columns; writes one partial logit per
+// row to z_part_wave[row].  inv_rms[row] comes from LDS.
+template <int kBlocks>
+__device__ __forceinline__ void router_epilogue(const f32x16 (&acc)[kBlocks], const float* inv_rms, float* z_part_wave,
+                                                float b1c, float w2c, int lane) {
+    const int h = lane >> 5;
+    const int vsel = (lane >> 1) & 15;
+#pragma unroll
+    for (int b = 0; b < kBlocks; ++b) {
+        float x[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = b * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+            x[v] = w2c * silu_f32(fmaf(inv_rms[row], acc[b][v], b1c));
+        }
+        const float total = reduce_scatter16(x, lane);
+        if (!(lane & 1)) z_part_wave[b * 32 + 8 * (vsel >> 2) + 4 * h + (vsel & 3)] = total;
+    }
 }
 
 // Values that another workgroup, possibly on another XCD, reads back within the same launch
@@ -132,20 +181,30 @@ struct CheckpointTable {
     int32_t layer_id[32];
 };
 
-// Earliest eligible firing checkpoint of one token, given its C logits (ascending layers).
-__device__ __forceinline__ void select_earliest(const CheckpointTable& tab, int C, int32_t min_layer, int32_t no_exit,
-                                                const float* z_of_c, int64_t z_stride, int32_t* exit_out, uint32_t* mask_out) {
+// Earliest-exit selection without a second pass (paper Fig. 1 inference step 3, Alg. 1 per
+// token).  Every (checkpoint, token) result is reported with ONE 64-bit device-scope atomic
+// add on the token's arrival word: bit c of the low half carries the fire bit of checkpoint c
+// (distinct bits, so the add is an OR) and the high half counts arrivals.  Whoever brings the
+// count to C holds, in the value the atomic returned plus its own bit, the complete fire mask
+// of that token; it writes exit_layer / fire_mask and puts the word back to zero for the next
+// call.  No staging of logits, no workgroup-level handshake, no fences.
+__device__ __forceinline__ void report_and_select(const CheckpointTable& tab, int C, int c, bool fire, int32_t min_layer,
+                                                  int32_t no_exit, uint64_t* arrive_word, int32_t* exit_out,
+                                                  uint32_t* mask_out) {
+    const uint64_t mine = (1ull << 32) | ((uint64_t)(fire ? 1u : 0u) << c);
+    const uint64_t old = __hip_atomic_fetch_add(arrive_word, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((uint32_t)(old >> 32) != (uint32_t)C - 1) return;
+    const uint32_t mask = (uint32_t)old | (uint32_t)mine;
     int32_t chosen = no_exit;
-    bool found = false;
-    uint32_t mask = 0;
-    for (int c = 0; c < C; ++c) {
-        float z = stage_load(z_of_c + c * z_stride);
-        bool f = z > tab.thr_logit[c];
-        if (f) mask |= 1u << c;
-        if (f && !found && tab.layer_id[c] >= min_layer) { chosen = tab.layer_id[c]; found = true; }
+    uint32_t m = mask;
+    while (m) {                                     // ascending checkpoints = ascending layers
+        const int k = __builtin_ctz(m);
+        if (tab.layer_id[k] >= min_layer) { chosen = tab.layer_id[k]; break; }
+        m &= m - 1;
     }
     *exit_out = chosen;
     if (mask_out) *mask_out = mask;
+    __hip_atomic_store(arrive_word, (uint64_t)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 }  // namespace tide

@@ -1,0 +1,187 @@
+// Prefill kernel, streaming form: the same computation as prefill_kernel.hpp (paper Eq. (2),
+// Sec. 3.4 kernel 1, Fig. 1 inference step 3) with the hidden rows brought into LDS by
+// dedicated producer waves.
+//
+// Why a second form.  Loads return to a wave in issue order, so a wave that fetches both the
+// hidden rows (HBM latency) and the W1' fragments (L2 latency) has its quick L2 loads queued
+// behind its slow HBM ones, and deep prefetch of the rows costs registers.  Here
+//   - 2 producer waves do nothing but issue global->LDS transfers (no registers, no LDS
+//     round trip through VGPRs) into a ring of kStages k-tiles, kStages-1 of them in flight;
+//   - 4 consumer waves fetch only W1' (one k-tile ahead, refilled as it is consumed), read
+//     the A fragments from the ring, run the MFMAs and accumulate the rows' sums of squares
+//     from the very fragments they multiply.
+// One s_barrier per k-tile hands a landed stage to the consumers and a drained one back.
+//
+// Workgroup = kRowsM rows x all 128 columns; consumer wave w owns columns 32w..32w+31 of
+// every row (kRowsM/32 accumulator blocks), so each W1' fragment is fetched once per kRowsM
+// rows.  Ring slots are unpadded (the transfer writes a wave's 64 x 16 bytes contiguously);
+// bank conflicts are avoided by a per-row XOR of the chunk index, applied on the global side.
+#pragma once
+#include <type_traits>
+
+#include "device_utils.hpp"
+#include "prefill_kernel.hpp"
+
+namespace tide {
+
+constexpr int kDmaConsumers = 4;
+constexpr int kDmaProducers = 2;
+constexpr int kDmaThreads = (kDmaConsumers + kDmaProducers) * kWave;   // 384
+constexpr int kDmaStages = 4;
+
+template <int kRowsM> constexpr int dma_lds_bytes() {
+    // ring + per-wave row sums of squares + per-wave logit partials + per-row inverse RMS
+    return kDmaStages * kRowsM * kTileBytes + (2 * kDmaConsumers + 1) * kRowsM * (int)sizeof(float);
+}
+
+// s_waitcnt immediate that waits for vmcnt <= n and nothing else (gfx9 encoding).
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+template <int DT, int kRowsM>
+__global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const PrefillParams p) {
+    typedef __attribute__((address_space(3))) char lds_char;
+    typedef __attribute__((address_space(1))) const char glb_char;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int kBlocks = kRowsM / 32;                       // accumulator blocks per consumer wave
+    constexpr int kStageBytes = kRowsM * kTileBytes;
+    constexpr int kInstrPerProducer = kRowsM / 4 / kDmaProducers;   // one transfer = 4 rows x 256 B
+    char* ring = smem;
+    float* ss_part = reinterpret_cast<float*>(smem + kDmaStages * kStageBytes);   // [4][kRowsM]
+    float* z_part = ss_part + kDmaConsumers * kRowsM;                              // [4][kRowsM]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    const int per_xcd = (p.total_tiles + 7) >> 3;
+    const int work = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (work >= p.total_tiles) return;
+    const int c = work / p.tiles_per_ckpt;
+    const int tile = work - c * p.tiles_per_ckpt;
+    const int row0 = tile * kRowsM;
+    const int ntile = p.d * Storage<DT>::kBytes / kTileBytes;
+    const int rot = (int)(((unsigned)work * 5u) % (unsigned)ntile);   // k rotation, see prefill_kernel.hpp
+
+    f32x16 acc[kBlocks];
+    float ssq[kBlocks];
+#pragma unroll
+    for (int b = 0; b < kBlocks; ++b) {
+        acc[b] = f32x16{0};
+        ssq[b] = 0.0f;
+    }
+
+    if (wave >= kDmaConsumers) {
+        // ------------------------------------------------------------------ producers
+        const int pw = wave - kDmaConsumers;
+        const char* base = p.hidden + (int64_t)c * p.ckpt_stride_bytes;
+        // lane -> (row within a 4-row transfer, LDS chunk slot); the global chunk is the slot
+        // XOR the row's low bits, which is what the consumers undo when they read
+        const int rl = lane >> 4, slot = lane & 15;
+        const char* gp[kInstrPerProducer];
+#pragma unroll
+        for (int i = 0; i < kInstrPerProducer; ++i) {
+            const int row = (pw * kInstrPerProducer + i) * 4 + rl;          // row within the tile
+            int r = row0 + row;
+            r = r < p.T ? r : p.T - 1;                                      // ragged tail: re-read the last row
+            gp[i] = base + (int64_t)r * p.row_stride_bytes + ((slot ^ (row & 15)) << 4);
+        }
+        auto issue = [&](int k) {                                           // k-th tile in rotated order
+            int kt = k + rot;
+            kt = kt >= ntile ? kt - ntile : kt;
+            char* dst = ring + (k % kDmaStages) * kStageBytes + pw * kInstrPerProducer * 1024;
+#pragma unroll
+            for (int i = 0; i < kInstrPerProducer; ++i)
+                __builtin_amdgcn_global_load_lds((glb_char*)(gp[i] + (int64_t)kt * kTileBytes), (lds_char*)(dst + i * 1024), 16, 0, 0);
+        };
+        for (int k = 0; k < kDmaStages - 1; ++k)
+            if (k < ntile) issue(k);
+        for (int k = 0; k < ntile; ++k) {
+            // stage k has landed once at most the younger stages' transfers are outstanding
+            if (k + kDmaStages - 2 < ntile)
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm((kDmaStages - 2) * kInstrPerProducer));
+            else
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            __builtin_amdgcn_s_barrier();          // stage k handed over; slot of stage k-1 is free
+            if (k + kDmaStages - 1 < ntile) issue(k + kDmaStages - 1);
+        }
+    } else {
+        // ------------------------------------------------------------------ consumers
+        const u32x4* wp = p.packed + (size_t)c * ((size_t)p.d * kBottleneck / Storage<DT>::kElems);
+        const u32x4* bptr = wp + wave * 64 + lane;
+        u32x4 breg[kGroupsPerTile];
+#pragma unroll
+        for (int g = 0; g < kGroupsPerTile; ++g) breg[g] = bptr[(size_t)(rot * kGroupsPerTile + g) * 256];
+        // A fragment of lane (r = lane%32, h = lane/32), block b, group g: row 32b + r, chunk 2g+h,
+        // stored at slot (2g+h) ^ (r & 15) = (2g) ^ y with y = h ^ (r & 15)
+        const int r = lane & 31;
+        const int a_base = r * kTileBytes;
+        const int y16 = ((lane >> 5) ^ (r & 15)) << 4;
+        int kt = rot;
+        // One k-tile.  `refill` is a compile-time constant at both call sites so that the loop
+        // body is straight-line code and the W1' wait counts stay exact (8 loads in flight).
+        auto consume = [&](int k, auto refill) {
+            __builtin_amdgcn_s_barrier();
+            const char* st = ring + (k % kDmaStages) * kStageBytes + a_base;
+            int kn = kt + 1;
+            kn = kn >= ntile ? 0 : kn;
+#pragma unroll
+            for (int g = 0; g < kGroupsPerTile; ++g) {
+                u32x4 a[kBlocks];
+#pragma unroll
+                for (int b = 0; b < kBlocks; ++b)
+                    a[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + (y16 ^ (g << 5)));
+#pragma unroll
+                for (int b = 0; b < kBlocks; ++b) acc[b] = mma_kgroup<DT>(a[b], breg[g], acc[b]);
+                if ((g & 3) == wave) {             // this wave's share of the sums of squares
+#pragma unroll
+                    for (int b = 0; b < kBlocks; ++b) ssq[b] = chunk_sumsq<DT>(a[b], ssq[b]);
+                }
+                if (decltype(refill)::value) breg[g] = bptr[(size_t)(kn * kGroupsPerTile + g) * 256];
+            }
+            kt = kn;
+        };
+        for (int k = 0; k + 1 < ntile; ++k) consume(k, std::true_type{});
+        consume(ntile - 1, std::false_type{});
+    }
+
+    // ---- row sums of squares: lanes l and l^32 hold the two chunk phases; the 4 waves the rest
+    if (wave < kDmaConsumers) {
+#pragma unroll
+        for (int b = 0; b < kBlocks; ++b) {
+            const float s = ssq[b] + __shfl_xor(ssq[b], 32, kWave);
+            if (lane < 32) ss_part[wave * kRowsM + 32 * b + lane] = s;
+        }
+    }
+    __syncthreads();
+
+    // ---- one inverse RMS per row, computed once ----
+    float* inv_rms = z_part + kDmaConsumers * kRowsM;          // [kRowsM]
+    if (tid < kRowsM) {
+        const float ss = (ss_part[tid] + ss_part[kRowsM + tid]) + (ss_part[2 * kRowsM + tid] + ss_part[3 * kRowsM + tid]);
+        inv_rms[tid] = inv_rms_f32(ss, 1.0f / (float)p.d, p.eps);
+    }
+    __syncthreads();
+
+    // ---- epilogue: a = r*acc + b1; SiLU; dot with w2 over this wave's 32 columns ----
+    if (wave < kDmaConsumers) {
+        const int col = 32 * wave + (lane & 31);
+        router_epilogue<kBlocks>(acc, inv_rms, z_part + wave * kRowsM, p.b1 ? p.b1[c * kBottleneck + col] : 0.0f,
+                                 p.w2[c * kBottleneck + col], lane);
+    }
+    __syncthreads();
+
+    if (tid < kRowsM) {
+        const int t = row0 + tid;
+        if (t < p.T) {
+            const float z = p.tab.b2[c] + ((z_part[tid] + z_part[kRowsM + tid]) + (z_part[2 * kRowsM + tid] + z_part[3 * kRowsM + tid]));
+            const int64_t o = (int64_t)c * p.T + t;
+            const bool f = z > p.tab.thr_logit[c];
+            if (p.logits) p.logits[o] = z;
+            if (p.prob) p.prob[o] = sigmoid_f32(z);
+            if (p.fire) p.fire[o] = f ? 1 : 0;
+            if (p.exit_layer)
+                report_and_select(p.tab, p.C, c, f, p.min_layer, p.no_exit, p.arrive + t, p.exit_layer + t,
+                                  p.fire_mask ? p.fire_mask + t : nullptr);
+        }
+    }
+}
+
+}  // namespace tide

@@ -15,9 +15,9 @@
 //   registers -> LDS (padded rows), sum of squares on the way
 //   LDS -> A fragments; W1' fragments straight from L2 in their packed order (same
 //   kDepth-deep register ring); MFMA.
-// Epilogue: r, +b1, SiLU, *w2, sum over the 128 columns, +b2, sigmoid, threshold; the
-// last workgroup to finish a token tile (device-scope counter) takes the min over the
-// checkpoints, so one launch yields exit_layer with no host round trip.
+// Epilogue: r, +b1, SiLU, *w2, sum over the 128 columns, +b2, sigmoid, threshold; each result
+// is reported on its token's arrival word and the last checkpoint to report selects the
+// earliest exit, so one launch yields exit_layer with no host round trip.
 #pragma once
 #include "device_utils.hpp"
 
@@ -42,8 +42,7 @@ struct PrefillParams {
     int32_t* exit_layer;       // [T]
     uint32_t* fire_mask;       // [T]
     // workspace
-    float* stage;              // [C][T] logits read back by the selecting workgroup (may alias logits)
-    uint32_t* tile_counter;    // [tiles_per_ckpt], zero on entry, zero on exit
+    uint64_t* arrive;          // [T] arrival words (see report_and_select), zero on entry and on exit
     CheckpointTable tab;
 };
 
@@ -63,7 +62,6 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const 
     __shared__ __attribute__((aligned(16))) char a_lds[2][kRows * kPitch];
     __shared__ float row_ss[kRows];
     __shared__ float z_part[4][kRows];
-    __shared__ int is_last;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
@@ -103,7 +101,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const 
     float ss[kChunksPerThread];
 #pragma unroll
     for (int i = 0; i < kChunksPerThread; ++i) ss[i] = 0.0f;
-    f32x16 acc0 = {0}, acc1 = {0};
+    f32x16 acc[2] = {f32x16{0}, f32x16{0}};
 
     auto load_a = [&](int j, int kt) {
 #pragma unroll
@@ -139,8 +137,8 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const 
         for (int g = 0; g < kGroupsPerTile; ++g) {
             u32x4 a0 = *reinterpret_cast<const u32x4*>(buf + a_read_off + g * 32);
             u32x4 a1 = *reinterpret_cast<const u32x4*>(buf + a_read_off + 32 * kPitch + g * 32);
-            acc0 = mma_kgroup<DT>(a0, breg[j][g], acc0);
-            acc1 = mma_kgroup<DT>(a1, breg[j][g], acc1);
+            acc[0] = mma_kgroup<DT>(a0, breg[j][g], acc[0]);
+            acc[1] = mma_kgroup<DT>(a1, breg[j][g], acc[1]);
         }
         if (refill) {
             load_b(j, next);
@@ -166,30 +164,18 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const 
         if (kt + j < ntile) do_tile(j, kt + j, false);
 
     // ---- row scale: the 16 lanes that share a row hold its partial sums of squares ----
+    const float inv_d = 1.0f / (float)p.d;
 #pragma unroll
     for (int i = 0; i < kChunksPerThread; ++i) {
-        float s = xor_reduce_sum<4>(ss[i]);
-        if (cc == 0) row_ss[lr0 + 16 * i] = s;
+        const float s = xor_reduce_sum<4>(ss[i]);
+        if (cc == 0) row_ss[lr0 + 16 * i] = inv_rms_f32(s, inv_d, p.eps);
     }
     __syncthreads();
 
     // ---- epilogue: a = r*acc + b1; SiLU; dot with w2 over this wave's 32 columns ----
     const int col = 32 * wave + (lane & 31);
-    const float b1c = p.b1 ? p.b1[c * kBottleneck + col] : 0.0f;
-    const float w2c = p.w2[c * kBottleneck + col];
-    const float inv_d = 1.0f / (float)p.d;
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = mb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-            const float r = 1.0f / sqrtf(row_ss[row] * inv_d + p.eps);
-            const float a = fmaf(r, mb == 0 ? acc0[v] : acc1[v], b1c);
-            float term = w2c * silu_f32(a);
-            term = xor_reduce_sum<5>(term);
-            if ((lane & 31) == 0) z_part[wave][row] = term;
-        }
-    }
+    router_epilogue<2>(acc, row_ss, z_part[wave], p.b1 ? p.b1[c * kBottleneck + col] : 0.0f,
+                       p.w2[c * kBottleneck + col], lane);
     __syncthreads();
 
     if (tid < kRows) {
@@ -197,24 +183,15 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const 
         if (t < p.T) {
             const float z = p.tab.b2[c] + ((z_part[0][tid] + z_part[1][tid]) + (z_part[2][tid] + z_part[3][tid]));
             const int64_t o = (int64_t)c * p.T + t;
-            if (p.logits && p.logits != p.stage) p.logits[o] = z;
+            const bool f = z > p.tab.thr_logit[c];
+            if (p.logits) p.logits[o] = z;
             if (p.prob) p.prob[o] = sigmoid_f32(z);
-            if (p.fire) p.fire[o] = z > p.tab.thr_logit[c] ? 1 : 0;
-            if (p.exit_layer) stage_store(p.stage + o, z);
+            if (p.fire) p.fire[o] = f ? 1 : 0;
+            if (p.exit_layer)
+                report_and_select(p.tab, p.C, c, f, p.min_layer, p.no_exit, p.arrive + t, p.exit_layer + t,
+                                  p.fire_mask ? p.fire_mask + t : nullptr);
         }
     }
-    if (!p.exit_layer) return;
-
-    // ---- earliest exit: the last workgroup to finish this token tile selects ----
-    stage_writes_done();
-    if (!last_arrival(p.tile_counter + tile, (uint32_t)p.C, &is_last)) return;
-    if (tid < kRows) {
-        const int t = row0 + tid;
-        if (t < p.T)
-            select_earliest(p.tab, p.C, p.min_layer, p.no_exit, p.stage + t, p.T, p.exit_layer + t,
-                            p.fire_mask ? p.fire_mask + t : nullptr);
-    }
-    if (tid == 0) __hip_atomic_store(p.tile_counter + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 }  // namespace tide

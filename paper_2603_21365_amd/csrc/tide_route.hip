@@ -14,6 +14,7 @@
 
 #include "decode_kernel.hpp"
 #include "pack_kernel.hpp"
+#include "prefill_dma_kernel.hpp"
 #include "prefill_kernel.hpp"
 
 namespace {
@@ -37,7 +38,7 @@ int fail(int code, const char* fmt, ...) {
     } while (0)
 
 constexpr int kMaxDevices = 16;
-constexpr size_t kCounterSlots = 1 << 16;  // token tiles per checkpoint that one launch may use
+constexpr size_t kCounterSlots = 64;       // per-checkpoint counters of the decode kernel
 constexpr int kDecodeAutoMaxT = 32;
 constexpr int kDecodeMaxT = 64;
 
@@ -47,12 +48,13 @@ struct Buffer {
 };
 
 struct Workspace {
-    Buffer counters, stage, packed, part;
+    Buffer counters, arrive, packed, part;
 };
 
 std::mutex g_mu;
 Workspace g_ws[kMaxDevices];
 int g_variant = TIDE_VARIANT_AUTO;
+int g_prefill_form = 0;   // 0 auto; 1 / 2: streaming form with 64 / 128 rows per workgroup; 3: register-ring form
 
 // Grow-only device buffer.  Re-allocation frees the old block, which waits for the device.
 int reserve(Buffer& b, size_t bytes, bool zero) {
@@ -105,7 +107,7 @@ int check_common(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d,
     if (d <= 0) return fail(TIDE_ERR_INVALID_ARG, "d = %lld must be positive", (long long)d);
     if (d % 128 != 0 || d < 128 || d > 16384)
         return fail(TIDE_ERR_UNSUPPORTED, "d = %lld: supported sizes are multiples of 128 in [128, 16384]", (long long)d);
-    if (T > (int64_t)kCounterSlots * kRows || C * T > (int64_t)1 << 30)
+    if (C * T > (int64_t)1 << 30)
         return fail(TIDE_ERR_UNSUPPORTED, "T = %lld is too large for one call", (long long)T);
     if (row_stride < d) return fail(TIDE_ERR_INVALID_ARG, "row_stride %lld < d %lld", (long long)row_stride, (long long)d);
     if (C > 1 && T > 1 && ckpt_stride < 0) return fail(TIDE_ERR_INVALID_ARG, "negative ckpt_stride");
@@ -159,6 +161,21 @@ int launch_pack(int dtype, int64_t C, int64_t d, const float* gamma, const float
     return TIDE_OK;
 }
 
+// The streaming kernels use more LDS than the default per-kernel limit: raise it once.
+template <int DT, int M> int launch_dma(unsigned grid, hipStream_t st, const PrefillParams& p) {
+    static bool raised[kMaxDevices] = {};
+    int dev = 0;
+    TIDE_HIP(hipGetDevice(&dev));
+    constexpr int lds = dma_lds_bytes<M>();
+    if (!raised[dev]) {
+        TIDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&tide_prefill_dma_kernel<DT, M>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        raised[dev] = true;
+    }
+    hipLaunchKernelGGL((tide_prefill_dma_kernel<DT, M>), dim3(grid), dim3(kDmaThreads), lds, st, p);
+    return TIDE_OK;
+}
+
 int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t ckpt_stride,
                    int64_t row_stride, const void* packed, float eps, const float* b1, const float* w2,
                    const CheckpointTable& tab, int32_t min_layer, int32_t no_exit, const Outputs& o, hipStream_t st) {
@@ -174,7 +191,15 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
     p.C = (int)C;
     p.T = (int)T;
     p.d = (int)d;
-    p.tiles_per_ckpt = (int)((T + kRows - 1) / kRows);
+    // Rows per workgroup: 128 (each W1' fragment fetched once per 128 rows) when that still
+    // gives every CU a workgroup, else 64; g_prefill_form overrides for tests and tuning.
+    const int64_t tiles128 = C * ((T + 127) / 128);
+    int rows_per_wg = tiles128 >= 192 ? 128 : 64;
+    if (g_prefill_form == 1) rows_per_wg = 64;
+    if (g_prefill_form == 2) rows_per_wg = 128;
+    const bool ring_form = g_prefill_form == 3;
+    if (ring_form) rows_per_wg = kRows;
+    p.tiles_per_ckpt = (int)((T + rows_per_wg - 1) / rows_per_wg);
     p.total_tiles = p.C * p.tiles_per_ckpt;
     p.eps = eps;
     p.min_layer = min_layer;
@@ -186,27 +211,28 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
     p.fire_mask = o.fire_mask;
     p.tab = tab;
     if (o.exit_layer) {
-        int rc = reserve(ws.counters, kCounterSlots * sizeof(uint32_t), true);
-        if (rc) return rc;
-        p.tile_counter = (uint32_t*)ws.counters.ptr;
-        if (o.logits) {
-            p.stage = o.logits;
-        } else {
-            rc = reserve(ws.stage, (size_t)C * T * sizeof(float), false);
-            if (rc) return rc;
-            p.stage = (float*)ws.stage.ptr;
-        }
+        int rc0 = reserve(ws.arrive, (size_t)T * sizeof(uint64_t), true);
+        if (rc0) return rc0;
+        p.arrive = (uint64_t*)ws.arrive.ptr;
     }
     const unsigned grid = 8u * (unsigned)((p.total_tiles + 7) / 8);
     const int ntile = (int)(d * (int64_t)eb / kTileBytes);
+    int rc = TIDE_OK;
     by_dtype(dtype, [&](auto dt) {
         constexpr int DT = decltype(dt)::value;
-        if (ntile >= kMaxDepth)
-            hipLaunchKernelGGL((tide_prefill_kernel<DT, kMaxDepth>), dim3(grid), dim3(kPrefillThreads), 0, st, p);
-        else
-            hipLaunchKernelGGL((tide_prefill_kernel<DT, 1>), dim3(grid), dim3(kPrefillThreads), 0, st, p);
+        if (ring_form) {
+            if (ntile >= kMaxDepth)
+                hipLaunchKernelGGL((tide_prefill_kernel<DT, kMaxDepth>), dim3(grid), dim3(kPrefillThreads), 0, st, p);
+            else
+                hipLaunchKernelGGL((tide_prefill_kernel<DT, 1>), dim3(grid), dim3(kPrefillThreads), 0, st, p);
+        } else if (rows_per_wg == 128) {
+            rc = launch_dma<DT, 128>(grid, st, p);
+        } else {
+            rc = launch_dma<DT, 64>(grid, st, p);
+        }
         return 0;
     });
+    if (rc) return rc;
     TIDE_HIP(hipGetLastError());
     return TIDE_OK;
 }
@@ -244,13 +270,9 @@ int launch_decode(Workspace& ws, const void* hidden, int dtype, int64_t C, int64
     if (rc) return rc;
     p.part = (float*)ws.part.ptr;
     if (o.exit_layer) {
-        if (o.logits) {
-            p.stage = o.logits;
-        } else {
-            rc = reserve(ws.stage, (size_t)C * T * sizeof(float), false);
-            if (rc) return rc;
-            p.stage = (float*)ws.stage.ptr;
-        }
+        rc = reserve(ws.arrive, (size_t)T * sizeof(uint64_t), true);
+        if (rc) return rc;
+        p.arrive = (uint64_t*)ws.arrive.ptr;
     }
     const int nblk = p.C * p.S;
     const unsigned grid = 8u * (unsigned)((nblk + 7) / 8);
@@ -387,6 +409,14 @@ int tide_set_variant(int variant) {
     return prev;
 }
 
+int tide_set_prefill_form(int form) {
+    if (form < 0 || form > 3) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d outside [0, 3]", form);
+    std::lock_guard<std::mutex> lock(g_mu);
+    int prev = g_prefill_form;
+    g_prefill_form = form;
+    return prev;
+}
+
 int tide_release(void) {
     g_err[0] = 0;
     std::lock_guard<std::mutex> lock(g_mu);
@@ -394,7 +424,7 @@ int tide_release(void) {
     int rc = current_workspace(&ws);
     if (rc) return rc;
     TIDE_HIP(hipDeviceSynchronize());
-    for (Buffer* b : {&ws->counters, &ws->stage, &ws->packed, &ws->part}) {
+    for (Buffer* b : {&ws->counters, &ws->arrive, &ws->packed, &ws->part}) {
         if (b->ptr) TIDE_HIP(hipFree(b->ptr));
         b->ptr = nullptr;
         b->bytes = 0;

@@ -25,7 +25,7 @@ DTYPE_CODES = {"f32": F32, "f16": F16, "bf16": BF16}
 EXPORTS = (
     "tide_version", "tide_last_error", "tide_router_eval", "tide_select_exit",
     "tide_packed_router_bytes", "tide_router_pack", "tide_router_eval_packed",
-    "tide_select_exit_packed", "tide_set_variant", "tide_release",
+    "tide_select_exit_packed", "tide_set_variant", "tide_set_prefill_form", "tide_release",
 )
 
 _lib = None
@@ -58,8 +58,9 @@ def load_library() -> ctypes.CDLL:
     lib.tide_packed_router_bytes.restype = ctypes.c_size_t
     lib.tide_router_pack.argtypes = [ci, i64, i64, vp, vp, vp, vp]
     lib.tide_set_variant.argtypes = [ci]
+    lib.tide_set_prefill_form.argtypes = [ci]
     for name in ("tide_router_eval", "tide_router_eval_packed", "tide_select_exit", "tide_select_exit_packed",
-                 "tide_router_pack", "tide_set_variant", "tide_release"):
+                 "tide_router_pack", "tide_set_variant", "tide_set_prefill_form", "tide_release"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -122,6 +123,13 @@ def last_error() -> str:
 
 def set_variant(variant: int) -> int:
     prev = load_library().tide_set_variant(int(variant))
+    if prev < 0:
+        _check(prev)
+    return prev
+
+
+def set_prefill_form(form: int) -> int:
+    prev = load_library().tide_set_prefill_form(int(form))
     if prev < 0:
         _check(prev)
     return prev
@@ -234,3 +242,49 @@ def select_exit_packed(hidden, packed, eps, b1, w2, b2, threshold, layer_ids, mi
                                                   _ptr(mask), _stream()))
     del keep
     return exit_layer, logits, mask
+
+
+class PreparedCall:
+    """A C entry point with its arguments marshalled once.
+
+    For latency-sensitive loops (a decode step calls the router every token): calling the
+    object re-issues exactly the same C call -- same buffers, same stream -- without the
+    per-call Python checks.  It keeps every tensor and host array it points into alive."""
+
+    def __init__(self, fn, cargs, keep, outputs):
+        self._fn, self._cargs, self._keep, self.outputs = fn, cargs, keep, outputs
+
+    def __call__(self):
+        status = self._fn(*self._cargs)
+        if status != 0:
+            _check(status)
+        return self.outputs
+
+
+def _c(argtypes, values):
+    return tuple(t(v) if v is not None else t() for t, v in zip(argtypes, values))
+
+
+def prepare_select_exit(hidden, gamma, eps, W1, b1, w2, b2, threshold, layer_ids, min_layer, no_exit_layer, *,
+                        want_logits=True, want_mask=True, out=None) -> PreparedCall:
+    """select_exit with its arguments frozen; the stream is torch's current stream at preparation."""
+    d = int(W1.shape[1])
+    C, T, cs, rs, b2p, thp, idp, exit_layer, logits, mask, keep = _select_common(
+        hidden, d, b1, w2, b2, threshold, layer_ids, want_logits, want_mask, out)
+    _f32dev(W1, (C, d, BOTTLENECK), "W1"), _f32dev(gamma, (C, d), "gamma")
+    fn = load_library().tide_select_exit
+    vals = (_ptr(hidden), _dtype_code(hidden), C, T, d, cs, rs, _ptr(gamma), float(eps), _ptr(W1), _ptr(b1), _ptr(w2),
+            b2p.value, thp.value, idp.value, int(min_layer), int(no_exit_layer), _ptr(exit_layer), _ptr(logits),
+            _ptr(mask), _stream())
+    return PreparedCall(fn, _c(fn.argtypes, vals), (keep, hidden, gamma, W1, b1, w2), (exit_layer, logits, mask))
+
+
+def prepare_select_exit_packed(hidden, packed, eps, b1, w2, b2, threshold, layer_ids, min_layer, no_exit_layer, *,
+                               d, want_logits=True, want_mask=True, out=None) -> PreparedCall:
+    C, T, cs, rs, b2p, thp, idp, exit_layer, logits, mask, keep = _select_common(
+        hidden, int(d), b1, w2, b2, threshold, layer_ids, want_logits, want_mask, out)
+    fn = load_library().tide_select_exit_packed
+    vals = (_ptr(hidden), _dtype_code(hidden), C, T, int(d), cs, rs, _ptr(packed), float(eps), _ptr(b1), _ptr(w2),
+            b2p.value, thp.value, idp.value, int(min_layer), int(no_exit_layer), _ptr(exit_layer), _ptr(logits),
+            _ptr(mask), _stream())
+    return PreparedCall(fn, _c(fn.argtypes, vals), (keep, hidden, packed, b1, w2), (exit_layer, logits, mask))

@@ -90,6 +90,14 @@ def test_set_variant_validates():
     tr.set_variant(prev)
 
 
+def test_set_prefill_form_validates():
+    prev = tr.set_prefill_form(0)
+    assert prev in (0, 1, 2, 3)
+    with pytest.raises(tr.TideError):
+        tr.set_prefill_form(4)
+    tr.set_prefill_form(prev)
+
+
 def test_exit_statistics_reproduce_fig3(golden_dir):
     g = read_golden(os.path.join(golden_dir, "fig3_exit_example.txt"))
     ex = [int(x) for x in g["exit_layers"]]

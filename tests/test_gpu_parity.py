@@ -26,6 +26,7 @@ def tr():
     tide_route.load_library()
     yield tide_route
     tide_route.set_variant(tide_route.VARIANT_AUTO)
+    tide_route.set_prefill_form(0)
 
 
 def calibrated(w, hidden_bits):
@@ -104,6 +105,32 @@ def test_config1_full(tr, packed):
     fired = [(int(((m_o >> c) & 1).sum())) for c in range(w.C)]
     assert fired == [round(0.30 * w.T)] * w.C          # the generator's stated firing rate
     assert st["max_abs_err"] < 1e-2                      # bf16 W1' rounding: well inside the 2e-2 bar
+
+
+@pytest.mark.parametrize("form", [1, 2, 3])
+@pytest.mark.parametrize("dtype,T,d", [("bf16", 300, 1024), ("f16", 129, 768), ("f32", 257, 512), ("bf16", 64, 128)])
+def test_every_prefill_form_computes_the_same_function(tr, form, dtype, T, d):
+    """Streaming form with 64 / 128 rows per workgroup and the register-ring form, forced in
+    turn, on ragged token counts and on a hidden size with a single k-tile."""
+    w = synth.Workload(f"form{form}_{dtype}_T{T}_d{d}", 29, dtype, d, 12, 4, T, None)
+    rt = w.routers()
+    rt.b2[:] = [0.2, -0.1, 0.0]
+    tr.set_prefill_form(form)
+    try:
+        run_and_compare(tr, w, w.name, rt=rt, packed=True, variant=tr.VARIANT_PREFILL)
+    finally:
+        tr.set_prefill_form(0)
+
+
+@pytest.mark.parametrize("form", [1, 2, 3])
+def test_config1_full_in_every_prefill_form(tr, form):
+    w = synth.config1()
+    tr.set_prefill_form(form)
+    try:
+        st, _, _ = run_and_compare(tr, w, f"config1_form{form}", packed=True)
+    finally:
+        tr.set_prefill_form(0)
+    assert st["max_abs_err"] < 1e-2
 
 
 # ------------------------------------------------------------------ config 2: decode, fp16
