@@ -28,6 +28,7 @@ constexpr int kDmaConsumers = 4;
 constexpr int kDmaProducers = 2;
 constexpr int kDmaThreads = (kDmaConsumers + kDmaProducers) * kWave;   // 384
 constexpr int kDmaStages = 4;
+constexpr int kStreamOnce = 2;   // cache-policy bits of the transfer: "nt" -- every hidden byte is read exactly once
 
 template <int kRowsM> constexpr int dma_lds_bytes() {
     // ring + per-wave row sums of squares + per-wave logit partials + per-row inverse RMS
@@ -89,7 +90,7 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
             char* dst = ring + (k % kDmaStages) * kStageBytes + pw * kInstrPerProducer * 1024;
 #pragma unroll
             for (int i = 0; i < kInstrPerProducer; ++i)
-                __builtin_amdgcn_global_load_lds((glb_char*)(gp[i] + (int64_t)kt * kTileBytes), (lds_char*)(dst + i * 1024), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((glb_char*)(gp[i] + (int64_t)kt * kTileBytes), (lds_char*)(dst + i * 1024), 16, 0, kStreamOnce);
         };
         for (int k = 0; k < kDmaStages - 1; ++k)
             if (k < ntile) issue(k);

@@ -106,7 +106,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const 
     auto load_a = [&](int j, int kt) {
 #pragma unroll
         for (int i = 0; i < kChunksPerThread; ++i)
-            areg[j][i] = *reinterpret_cast<const u32x4*>(gptr[i] + (int64_t)kt * kTileBytes);
+            areg[j][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gptr[i] + (int64_t)kt * kTileBytes));   // read once
     };
     auto load_b = [&](int j, int kt) {
 #pragma unroll
