@@ -86,24 +86,43 @@ template <int kBits> __device__ __forceinline__ float xor_reduce_sum(float v) {
     return v;
 }
 
+// Lane exchanges that stay in the vector ALU (no LDS round trip): DPP permutations within a
+// row of 16 lanes, and the gfx950 row swap between neighbouring rows.
+template <int kCtrl> __device__ __forceinline__ float dpp_f32(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kCtrl, 0xF, 0xF, false));
+}
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i within 8: flips bit 2 (and the bits below)
+constexpr int kDppRor8 = 0x128;       // rotate a row by 8 = lane i <-> i^8
+
 // Sum each of 16 per-lane values over the 32 lanes that share lane>>5, leaving every lane
 // with ONE finished total (a reduce-scatter: 8+4+2+1+1 exchanges instead of 16 x 5).
 // The total a lane ends up with is that of index v = bits (4,3,2,1) of its lane id; lanes
 // 2k and 2k+1 hold the same one.
+// Step 1 swaps rows: v_permlane16_swap exchanges the odd 16-lane rows of its first operand
+// with the even rows of its second, so with (x[i], x[i+8]) the two results add up to "my kept
+// half plus my partner's" in every lane at once.  It is inline assembly because this
+// toolchain's builtin returns the first result twice; the leading s_nop covers the two wait
+// states the instruction needs after a VALU write of its operands (the compiler cannot see
+// into the asm to insert them).
 __device__ __forceinline__ float reduce_scatter16(const float (&x)[16], int lane) {
     float y8[8], y4[4], y2[2];
-    bool hi = lane & 16;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) y8[i] = (hi ? x[i + 8] : x[i]) + __shfl_xor(hi ? x[i] : x[i + 8], 16, kWave);
-    hi = lane & 8;
+    for (int i = 0; i < 8; ++i) {
+        float a = x[i], b = x[i + 8];
+        asm("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+        y8[i] = a + b;
+    }
+    bool hi = lane & 8;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) y4[i] = (hi ? y8[i + 4] : y8[i]) + __shfl_xor(hi ? y8[i] : y8[i + 4], 8, kWave);
+    for (int i = 0; i < 4; ++i) y4[i] = (hi ? y8[i + 4] : y8[i]) + dpp_f32<kDppRor8>(hi ? y8[i] : y8[i + 4]);
     hi = lane & 4;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) y2[i] = (hi ? y4[i + 2] : y4[i]) + __shfl_xor(hi ? y4[i] : y4[i + 2], 4, kWave);
+    for (int i = 0; i < 2; ++i) y2[i] = (hi ? y4[i + 2] : y4[i]) + dpp_f32<kDppHalfMirror>(hi ? y4[i] : y4[i + 2]);
     hi = lane & 2;
-    float y = (hi ? y2[1] : y2[0]) + __shfl_xor(hi ? y2[0] : y2[1], 2, kWave);
-    return y + __shfl_xor(y, 1, kWave);
+    const float y = (hi ? y2[1] : y2[0]) + dpp_f32<kDppXor2>(hi ? y2[0] : y2[1]);
+    return y + dpp_f32<kDppXor1>(y);
 }
 
 // Router epilogue for one consumer wave holding kBlocks 32x32 accumulator blocks (rows
@@ -120,9 +139,10 @@ __device__ __forceinline__ void router_epilogue(const f32x16 (&acc)[kBlocks], co
     for (int b = 0; b < kBlocks; ++b) {
         float x[16];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = b * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-            x[v] = w2c * silu_f32(fmaf(inv_rms[row], acc[b][v], b1c));
+        for (int q = 0; q < 4; ++q) {                      // registers 4q..4q+3 are rows 32b + 8q + 4h + (0..3)
+            const f32x4 rs = *reinterpret_cast<const f32x4*>(inv_rms + b * 32 + 8 * q + 4 * h);   // 16-byte aligned
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[4 * q + e] = w2c * silu_f32(fmaf(rs[e], acc[b][4 * q + e], b1c));
         }
         const float total = reduce_scatter16(x, lane);
         if (!(lane & 1)) z_part_wave[b * 32 + 8 * (vsel >> 2) + 4 * h + (vsel & 3)] = total;

@@ -60,7 +60,7 @@ constexpr int kMaxDepth = 3;              // k-tiles of hidden rows and W1' kept
 template <int DT, int kDepth>
 __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const PrefillParams p) {
     __shared__ __attribute__((aligned(16))) char a_lds[2][kRows * kPitch];
-    __shared__ float row_ss[kRows];
+    __shared__ __attribute__((aligned(16))) float row_ss[kRows];
     __shared__ float z_part[4][kRows];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
