@@ -11,6 +11,8 @@
 //     the A fragments from the ring, run the MFMAs and accumulate the rows' sums of squares
 //     from the very fragments they multiply.
 // One s_barrier per k-tile hands a landed stage to the consumers and a drained one back.
+// Workgroups are persistent: each walks a list of tiles, and the producers keep fetching
+// across tile boundaries, so HBM stays busy while the consumers are in a tile's epilogue.
 //
 // Workgroup = kRowsM rows x all 128 columns; consumer wave w owns columns 32w..32w+31 of
 // every row (kRowsM/32 accumulator blocks), so each W1' fragment is fetched once per kRowsM
@@ -35,8 +37,33 @@ template <int kRowsM> constexpr int dma_lds_bytes() {
     return kDmaStages * kRowsM * kTileBytes + (2 * kDmaConsumers + 1) * kRowsM * (int)sizeof(float);
 }
 
+// The ring hand-off barrier: a bare s_barrier (no wait for this wave's outstanding loads, which
+// is the point), fenced for the compiler only so that no LDS access is moved across it.
+__device__ __forceinline__ void ring_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 // s_waitcnt immediate that waits for vmcnt <= n and nothing else (gfx9 encoding).
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+// Tile schedule of a persistent workgroup.  The checkpoint-major tile list is cut into 8
+// contiguous slices, slice x -> XCD x (workgroup id mod 8), so that an XCD's L2 holds one W1'
+// at a time; the workgroups of an XCD deal its slice out round-robin.
+struct TileWalk {
+    int next, end, step;
+    __device__ TileWalk(int total_tiles) {
+        const int per_xcd = (total_tiles + 7) >> 3;
+        const int xcd = blockIdx.x & 7;
+        next = xcd * per_xcd + (blockIdx.x >> 3);
+        end = min((xcd + 1) * per_xcd, total_tiles);
+        step = gridDim.x >> 3;
+    }
+    __device__ bool valid() const { return next < end; }
+    __device__ bool has_more() const { return next + step < end; }
+    __device__ void advance() { next += step; }
+};
 
 template <int DT, int kRowsM>
 __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const PrefillParams p) {
@@ -49,80 +76,120 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
     char* ring = smem;
     float* ss_part = reinterpret_cast<float*>(smem + kDmaStages * kStageBytes);   // [4][kRowsM]
     float* z_part = ss_part + kDmaConsumers * kRowsM;                              // [4][kRowsM]
+    float* inv_rms = z_part + kDmaConsumers * kRowsM;                              // [kRowsM]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-
-    const int per_xcd = (p.total_tiles + 7) >> 3;
-    const int work = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (work >= p.total_tiles) return;
-    const int c = work / p.tiles_per_ckpt;
-    const int tile = work - c * p.tiles_per_ckpt;
-    const int row0 = tile * kRowsM;
     const int ntile = p.d * Storage<DT>::kBytes / kTileBytes;
-    const int rot = (int)(((unsigned)work * 5u) % (unsigned)ntile);   // k rotation, see prefill_kernel.hpp
+    // Rows are a power-of-two number of bytes apart and all workgroups start together: each
+    // tile starts its k loop at a different k-tile and wraps (see prefill_kernel.hpp).
+    auto rotation = [&](int work) { return (int)(((unsigned)work * 5u) % (unsigned)ntile); };
 
-    f32x16 acc[kBlocks];
-    float ssq[kBlocks];
-#pragma unroll
-    for (int b = 0; b < kBlocks; ++b) {
-        acc[b] = f32x16{0};
-        ssq[b] = 0.0f;
-    }
+    TileWalk walk(p.total_tiles);
+    if (!walk.valid()) return;
 
     if (wave >= kDmaConsumers) {
         // ------------------------------------------------------------------ producers
+        // They run ahead of the consumers by kDmaStages-1 k-tiles, across tile boundaries: while
+        // the consumers are in the epilogue of one tile the ring fills with the next tile's rows.
         const int pw = wave - kDmaConsumers;
-        const char* base = p.hidden + (int64_t)c * p.ckpt_stride_bytes;
         // lane -> (row within a 4-row transfer, LDS chunk slot); the global chunk is the slot
         // XOR the row's low bits, which is what the consumers undo when they read
         const int rl = lane >> 4, slot = lane & 15;
-        const char* gp[kInstrPerProducer];
+        const char* gp[kInstrPerProducer];     // row pointers of the tile being fetched
+        int f_rot = 0, f_k = 0;                // fetch cursor: k-tile within that tile
+        TileWalk fetch = walk;
+        auto aim = [&](int work) {
+            const int c = work / p.tiles_per_ckpt;
+            const int row0 = (work - c * p.tiles_per_ckpt) * kRowsM;
+            const char* base = p.hidden + (int64_t)c * p.ckpt_stride_bytes;
 #pragma unroll
-        for (int i = 0; i < kInstrPerProducer; ++i) {
-            const int row = (pw * kInstrPerProducer + i) * 4 + rl;          // row within the tile
-            int r = row0 + row;
-            r = r < p.T ? r : p.T - 1;                                      // ragged tail: re-read the last row
-            gp[i] = base + (int64_t)r * p.row_stride_bytes + ((slot ^ (row & 15)) << 4);
-        }
-        auto issue = [&](int k) {                                           // k-th tile in rotated order
-            int kt = k + rot;
+            for (int i = 0; i < kInstrPerProducer; ++i) {
+                const int row = (pw * kInstrPerProducer + i) * 4 + rl;      // row within the tile
+                int r = row0 + row;
+                r = r < p.T ? r : p.T - 1;                                  // ragged tail: re-read the last row
+                gp[i] = base + (int64_t)r * p.row_stride_bytes + ((slot ^ (row & 15)) << 4);
+            }
+            f_rot = rotation(work);
+            f_k = 0;
+        };
+        aim(fetch.next);
+        int issued = 0;                        // global stage counter -> ring slot
+        bool fetch_done = false;
+        auto issue_next = [&]() {              // one k-tile of the fetch cursor's tile; moves the cursor
+            if (fetch_done) return;
+            int kt = f_k + f_rot;
             kt = kt >= ntile ? kt - ntile : kt;
-            char* dst = ring + (k % kDmaStages) * kStageBytes + pw * kInstrPerProducer * 1024;
+            char* dst = ring + (issued % kDmaStages) * kStageBytes + pw * kInstrPerProducer * 1024;
 #pragma unroll
             for (int i = 0; i < kInstrPerProducer; ++i)
                 __builtin_amdgcn_global_load_lds((glb_char*)(gp[i] + (int64_t)kt * kTileBytes), (lds_char*)(dst + i * 1024), 16, 0, kStreamOnce);
+            ++issued;
+            if (++f_k == ntile) {
+                if (fetch.has_more()) {
+                    fetch.advance();
+                    aim(fetch.next);
+                } else {
+                    fetch_done = true;
+                }
+            }
         };
-        for (int k = 0; k < kDmaStages - 1; ++k)
-            if (k < ntile) issue(k);
-        for (int k = 0; k < ntile; ++k) {
-            // stage k has landed once at most the younger stages' transfers are outstanding
-            if (k + kDmaStages - 2 < ntile)
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm((kDmaStages - 2) * kInstrPerProducer));
-            else
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-            __builtin_amdgcn_s_barrier();          // stage k handed over; slot of stage k-1 is free
-            if (k + kDmaStages - 1 < ntile) issue(k + kDmaStages - 1);
+        for (int s = 0; s < kDmaStages - 1; ++s) issue_next();
+        int handed = 0;                        // stages handed to the consumers so far
+        for (; walk.valid(); walk.advance()) {
+            for (int k = 0; k < ntile; ++k) {
+                // stage `handed` has landed once at most the kDmaStages-2 younger ones are outstanding
+                if (issued - handed == kDmaStages - 1)
+                    __builtin_amdgcn_s_waitcnt(vmcnt_imm((kDmaStages - 2) * kInstrPerProducer));
+                else
+                    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                ring_barrier();                    // stage handed over; the slot of the one before it is free
+                ++handed;
+                issue_next();
+            }
+            ring_barrier();                        // the three barriers of the consumers' epilogue
+            ring_barrier();
+            ring_barrier();
         }
-    } else {
-        // ------------------------------------------------------------------ consumers
-        const u32x4* wp = p.packed + (size_t)c * ((size_t)p.d * kBottleneck / Storage<DT>::kElems);
-        const u32x4* bptr = wp + wave * 64 + lane;
-        u32x4 breg[kGroupsPerTile];
+        return;
+    }
+
+    // ---------------------------------------------------------------------- consumers
+    const int r = lane & 31;
+    // A fragment of lane (r = lane%32, h = lane/32), block b, group g: row 32b + r, chunk 2g+h,
+    // stored at slot (2g+h) ^ (r & 15) = (2g) ^ y with y = h ^ (r & 15)
+    const int a_base = r * kTileBytes;
+    const int y16 = ((lane >> 5) ^ (r & 15)) << 4;
+    const size_t ckpt_chunks = (size_t)p.d * kBottleneck / Storage<DT>::kElems;
+    auto b_pointer = [&](int work) {
+        return p.packed + (size_t)(work / p.tiles_per_ckpt) * ckpt_chunks + wave * 64 + lane;
+    };
+    u32x4 breg[kGroupsPerTile];
+    {
+        const u32x4* b0 = b_pointer(walk.next);
+        const int rot0 = rotation(walk.next);
 #pragma unroll
-        for (int g = 0; g < kGroupsPerTile; ++g) breg[g] = bptr[(size_t)(rot * kGroupsPerTile + g) * 256];
-        // A fragment of lane (r = lane%32, h = lane/32), block b, group g: row 32b + r, chunk 2g+h,
-        // stored at slot (2g+h) ^ (r & 15) = (2g) ^ y with y = h ^ (r & 15)
-        const int r = lane & 31;
-        const int a_base = r * kTileBytes;
-        const int y16 = ((lane >> 5) ^ (r & 15)) << 4;
-        int kt = rot;
-        // One k-tile.  `refill` is a compile-time constant at both call sites so that the loop
-        // body is straight-line code and the W1' wait counts stay exact (8 loads in flight).
-        auto consume = [&](int k, auto refill) {
-            __builtin_amdgcn_s_barrier();
-            const char* st = ring + (k % kDmaStages) * kStageBytes + a_base;
-            int kn = kt + 1;
-            kn = kn >= ntile ? 0 : kn;
+        for (int g = 0; g < kGroupsPerTile; ++g) breg[g] = b0[(size_t)(rot0 * kGroupsPerTile + g) * 256];
+    }
+    int stage = 0;                                 // global stage counter -> ring slot
+    for (; walk.valid(); walk.advance()) {
+        const int work = walk.next;
+        const int c = work / p.tiles_per_ckpt;
+        const int row0 = (work - c * p.tiles_per_ckpt) * kRowsM;
+        const u32x4* bptr = b_pointer(work);
+        int kt = rotation(work);
+
+        f32x16 acc[kBlocks];
+        float ssq[kBlocks];
+#pragma unroll
+        for (int b = 0; b < kBlocks; ++b) {
+            acc[b] = f32x16{0};
+            ssq[b] = 0.0f;
+        }
+        // One k-tile; afterwards breg holds the fragments of (nb, kn).  Each call site is
+        // straight-line code, so the W1' wait counts stay exact (8 loads in flight).
+        auto consume = [&](const u32x4* nb, int kn, auto refill) {
+            ring_barrier();
+            const char* st = ring + (stage % kDmaStages) * kStageBytes + a_base;
 #pragma unroll
             for (int g = 0; g < kGroupsPerTile; ++g) {
                 u32x4 a[kBlocks];
@@ -135,53 +202,60 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
 #pragma unroll
                     for (int b = 0; b < kBlocks; ++b) ssq[b] = chunk_sumsq<DT>(a[b], ssq[b]);
                 }
-                if (decltype(refill)::value) breg[g] = bptr[(size_t)(kn * kGroupsPerTile + g) * 256];
+                if (decltype(refill)::value) breg[g] = nb[(size_t)(kn * kGroupsPerTile + g) * 256];
             }
-            kt = kn;
+            ++stage;
         };
-        for (int k = 0; k + 1 < ntile; ++k) consume(k, std::true_type{});
-        consume(ntile - 1, std::false_type{});
-    }
+        for (int k = 0; k + 1 < ntile; ++k) {
+            const int kn = kt + 1 >= ntile ? 0 : kt + 1;
+            consume(bptr, kn, std::true_type{});
+            kt = kn;
+        }
+        if (walk.has_more()) {                      // last k-tile: prefetch the next tile's first fragments
+            const int nwork = walk.next + walk.step;
+            consume(b_pointer(nwork), rotation(nwork), std::true_type{});
+        } else {
+            consume(bptr, 0, std::false_type{});
+        }
 
-    // ---- row sums of squares: lanes l and l^32 hold the two chunk phases; the 4 waves the rest
-    if (wave < kDmaConsumers) {
+        // ---- row sums of squares: lanes l and l^32 hold the two chunk phases; the 4 waves the rest
 #pragma unroll
         for (int b = 0; b < kBlocks; ++b) {
-            const float s = ssq[b] + __shfl_xor(ssq[b], 32, kWave);
-            if (lane < 32) ss_part[wave * kRowsM + 32 * b + lane] = s;
+            const float s2 = ssq[b] + __shfl_xor(ssq[b], 32, kWave);
+            if (lane < 32) ss_part[wave * kRowsM + 32 * b + lane] = s2;
         }
-    }
-    __syncthreads();
+        __syncthreads();
 
-    // ---- one inverse RMS per row, computed once ----
-    float* inv_rms = z_part + kDmaConsumers * kRowsM;          // [kRowsM]
-    if (tid < kRowsM) {
-        const float ss = (ss_part[tid] + ss_part[kRowsM + tid]) + (ss_part[2 * kRowsM + tid] + ss_part[3 * kRowsM + tid]);
-        inv_rms[tid] = inv_rms_f32(ss, 1.0f / (float)p.d, p.eps);
-    }
-    __syncthreads();
-
-    // ---- epilogue: a = r*acc + b1; SiLU; dot with w2 over this wave's 32 columns ----
-    if (wave < kDmaConsumers) {
-        const int col = 32 * wave + (lane & 31);
-        router_epilogue<kBlocks>(acc, inv_rms, z_part + wave * kRowsM, p.b1 ? p.b1[c * kBottleneck + col] : 0.0f,
-                                 p.w2[c * kBottleneck + col], lane);
-    }
-    __syncthreads();
-
-    if (tid < kRowsM) {
-        const int t = row0 + tid;
-        if (t < p.T) {
-            const float z = p.tab.b2[c] + ((z_part[tid] + z_part[kRowsM + tid]) + (z_part[2 * kRowsM + tid] + z_part[3 * kRowsM + tid]));
-            const int64_t o = (int64_t)c * p.T + t;
-            const bool f = z > p.tab.thr_logit[c];
-            if (p.logits) p.logits[o] = z;
-            if (p.prob) p.prob[o] = sigmoid_f32(z);
-            if (p.fire) p.fire[o] = f ? 1 : 0;
-            if (p.exit_layer)
-                report_and_select(p.tab, p.C, c, f, p.min_layer, p.no_exit, p.arrive + t, p.exit_layer + t,
-                                  p.fire_mask ? p.fire_mask + t : nullptr);
+        // ---- one inverse RMS per row, computed once ----
+        if (tid < kRowsM) {
+            const float ss = (ss_part[tid] + ss_part[kRowsM + tid]) + (ss_part[2 * kRowsM + tid] + ss_part[3 * kRowsM + tid]);
+            inv_rms[tid] = inv_rms_f32(ss, 1.0f / (float)p.d, p.eps);
         }
+        __syncthreads();
+
+        // ---- epilogue: a = r*acc + b1; SiLU; dot with w2 over this wave's 32 columns ----
+        {
+            const int col = 32 * wave + (lane & 31);
+            router_epilogue<kBlocks>(acc, inv_rms, z_part + wave * kRowsM, p.b1 ? p.b1[c * kBottleneck + col] : 0.0f,
+                                     p.w2[c * kBottleneck + col], lane);
+        }
+        __syncthreads();
+
+        if (tid < kRowsM) {
+            const int t = row0 + tid;
+            if (t < p.T) {
+                const float z = p.tab.b2[c] + ((z_part[tid] + z_part[kRowsM + tid]) + (z_part[2 * kRowsM + tid] + z_part[3 * kRowsM + tid]));
+                const int64_t o = (int64_t)c * p.T + t;
+                const bool f = z > p.tab.thr_logit[c];
+                if (p.logits) p.logits[o] = z;
+                if (p.prob) p.prob[o] = sigmoid_f32(z);
+                if (p.fire) p.fire[o] = f ? 1 : 0;
+                if (p.exit_layer)
+                    report_and_select(p.tab, p.C, c, f, p.min_layer, p.no_exit, p.arrive + t, p.exit_layer + t,
+                                      p.fire_mask ? p.fire_mask + t : nullptr);
+            }
+        }
+        // z_part / ss_part / inv_rms are next written after the first barriers of the next tile's k loop
     }
 }
 

@@ -162,16 +162,22 @@ int launch_pack(int dtype, int64_t C, int64_t d, const float* gamma, const float
 }
 
 // The streaming kernels use more LDS than the default per-kernel limit: raise it once.
+// They are persistent: at most one (128-row) or two (64-row) workgroups per CU, each walking
+// a list of tiles.
 template <int DT, int M> int launch_dma(unsigned grid, hipStream_t st, const PrefillParams& p) {
     static bool raised[kMaxDevices] = {};
+    static int cus[kMaxDevices] = {};
     int dev = 0;
     TIDE_HIP(hipGetDevice(&dev));
     constexpr int lds = dma_lds_bytes<M>();
     if (!raised[dev]) {
         TIDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&tide_prefill_dma_kernel<DT, M>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        TIDE_HIP(hipDeviceGetAttribute(&cus[dev], hipDeviceAttributeMultiprocessorCount, dev));
         raised[dev] = true;
     }
+    const unsigned resident = (unsigned)(cus[dev] > 8 ? cus[dev] & ~7 : 8) * (M == 128 ? 1u : 2u);
+    if (grid > resident) grid = resident;      // both are multiples of 8
     hipLaunchKernelGGL((tide_prefill_dma_kernel<DT, M>), dim3(grid), dim3(kDmaThreads), lds, st, p);
     return TIDE_OK;
 }
