@@ -50,21 +50,42 @@ template <> __device__ __forceinline__ float chunk_sumsq<kBF16>(u32x4 c, float a
     return acc;
 }
 
-// acc[32x32] += A[32 x kgroup] * B[kgroup x 32] with A and B chunks laid out as the matrix
-// cores take them: lane l supplies row/column l%32 and the chunk of lane half l/32.
-template <int DT> __device__ __forceinline__ f32x16 mma_kgroup(u32x4 a, u32x4 b, f32x16 acc);
-template <> __device__ __forceinline__ f32x16 mma_kgroup<kBF16>(u32x4 a, u32x4 b, f32x16 acc) {
+// acc[32x32] += A[32 x 16] * B[16 x 32] with A and B fragments laid out as the matrix cores
+// take them: lane l supplies row/column l%32 and the 8 consecutive-k elements of lane half
+// l/32.
+template <int DT> __device__ __forceinline__ f32x16 mma_k16(u32x4 a, u32x4 b, f32x16 acc);
+template <> __device__ __forceinline__ f32x16 mma_k16<kBF16>(u32x4 a, u32x4 b, f32x16 acc) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
 }
-template <> __device__ __forceinline__ f32x16 mma_kgroup<kF16>(u32x4 a, u32x4 b, f32x16 acc) {
+template <> __device__ __forceinline__ f32x16 mma_k16<kF16>(u32x4 a, u32x4 b, f32x16 acc) {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), acc, 0, 0, 0);
 }
-template <> __device__ __forceinline__ f32x16 mma_kgroup<kF32>(u32x4 a, u32x4 b, f32x16 acc) {
+
+// fp32 storage.  The fp32 matrix-core rate is 1/16 of the bf16 rate, which would make the
+// fp32 path compute-bound at a third of HBM bandwidth.  Instead every fp32 value is split into
+// two bf16 terms, x = hi + mid + O(2^-17 x), for the hidden rows on the fly and for W1' at
+// pack time, and the product is taken as  hi*hi + hi*mid + mid*hi  on the bf16 matrix cores
+// with fp32 accumulation: three bf16 steps instead of eight fp32 ones per 16 k values.  The
+// dropped terms are 2^-17 relative per product; on the router's logits that is 1e-5 at most
+// (measured against the fp64 oracle), against a tolerance of 1e-4.
+__device__ __forceinline__ void split_bf16(const float* x, int n, __bf16* hi, __bf16* mid) {
 #pragma unroll
-    for (int m = 0; m < 4; ++m)
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[m]), __uint_as_float(b[m]), acc, 0, 0, 0);
-    return acc;
+    for (int e = 0; e < n; ++e) {
+        const __bf16 h = static_cast<__bf16>(x[e]);
+        hi[e] = h;
+        mid[e] = static_cast<__bf16>(x[e] - static_cast<float>(h));   // the difference is exact in fp32
+    }
 }
+__device__ __forceinline__ f32x16 mma_k16_split(u32x4 a_hi, u32x4 a_mid, u32x4 b_hi, u32x4 b_mid, f32x16 acc) {
+    acc = mma_k16<kBF16>(a_mid, b_hi, acc);      // small terms first
+    acc = mma_k16<kBF16>(a_hi, b_mid, acc);
+    return mma_k16<kBF16>(a_hi, b_hi, acc);
+}
+
+// How a storage type maps onto matrix-core steps.  A k-tile is 256 bytes of a row; it holds
+// kMmaGroups groups of 16 k values, and each group needs kPlanes W1' fragments.
+template <int DT> struct Compute { static constexpr int kMmaGroups = 8, kPlanes = 1; };
+template <> struct Compute<kF32> { static constexpr int kMmaGroups = 4, kPlanes = 2; };
 
 // sigmoid and SiLU on the hardware exp / reciprocal units (about 1 ulp each): the router's
 // tolerance is 1e-4 absolute on a sum of 128 terms of order 0.1, and IEEE-exact division

@@ -159,16 +159,24 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
     // stored at slot (2g+h) ^ (r & 15) = (2g) ^ y with y = h ^ (r & 15)
     const int a_base = r * kTileBytes;
     const int y16 = ((lane >> 5) ^ (r & 15)) << 4;
+    const int yf16 = (((lane >> 5) << 1) ^ (r & 15)) << 4;     // fp32 rows: see the k loop
     const size_t ckpt_chunks = (size_t)p.d * kBottleneck / Storage<DT>::kElems;
     auto b_pointer = [&](int work) {
         return p.packed + (size_t)(work / p.tiles_per_ckpt) * ckpt_chunks + wave * 64 + lane;
     };
-    u32x4 breg[kGroupsPerTile];
+    constexpr int kMmaGroups = Compute<DT>::kMmaGroups, kPlanes = Compute<DT>::kPlanes;
+    const size_t plane_chunks = (size_t)p.d * 16;
+    u32x4 breg[kMmaGroups * kPlanes];              // [g * kPlanes + plane]: 8 fragments either way
+    auto b_fragment = [&](const u32x4* base, int kt, int g, int pl) {
+        return base[pl * plane_chunks + (size_t)(kt * kMmaGroups + g) * 256];
+    };
     {
         const u32x4* b0 = b_pointer(walk.next);
         const int rot0 = rotation(walk.next);
 #pragma unroll
-        for (int g = 0; g < kGroupsPerTile; ++g) breg[g] = b0[(size_t)(rot0 * kGroupsPerTile + g) * 256];
+        for (int g = 0; g < kMmaGroups; ++g)
+#pragma unroll
+            for (int pl = 0; pl < kPlanes; ++pl) breg[g * kPlanes + pl] = b_fragment(b0, rot0, g, pl);
     }
     int stage = 0;                                 // global stage counter -> ring slot
     for (; walk.valid(); walk.advance()) {
@@ -191,18 +199,50 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
             ring_barrier();
             const char* st = ring + (stage % kDmaStages) * kStageBytes + a_base;
 #pragma unroll
-            for (int g = 0; g < kGroupsPerTile; ++g) {
-                u32x4 a[kBlocks];
+            for (int g = 0; g < kMmaGroups; ++g) {
+                if constexpr (DT == kF32) {
+                    // 16 k values = chunks 4g+2h and 4g+2h+1 of the row (4 fp32 each); their slots are
+                    // ((4g) ^ y) and that ^ 1 with y = (2h) ^ (r & 15)
+                    u32x4 ah[kBlocks], am[kBlocks];
+                    float sq[kBlocks];
 #pragma unroll
-                for (int b = 0; b < kBlocks; ++b)
-                    a[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + (y16 ^ (g << 5)));
+                    for (int b = 0; b < kBlocks; ++b) {
+                        const char* src = st + b * 32 * kTileBytes;
+                        const u32x4 c0 = *reinterpret_cast<const u32x4*>(src + (yf16 ^ (g << 6)));
+                        const u32x4 c1 = *reinterpret_cast<const u32x4*>(src + (yf16 ^ (g << 6) ^ 16));
+                        float x[8] = {__uint_as_float(c0.x), __uint_as_float(c0.y), __uint_as_float(c0.z), __uint_as_float(c0.w),
+                                      __uint_as_float(c1.x), __uint_as_float(c1.y), __uint_as_float(c1.z), __uint_as_float(c1.w)};
+                        __bf16 hi[8], mid[8];
+                        split_bf16(x, 8, hi, mid);
+                        bf16x8 h8, m8;
 #pragma unroll
-                for (int b = 0; b < kBlocks; ++b) acc[b] = mma_kgroup<DT>(a[b], breg[g], acc[b]);
-                if ((g & 3) == wave) {             // this wave's share of the sums of squares
+                        for (int e = 0; e < 8; ++e) { h8[e] = hi[e]; m8[e] = mid[e]; }
+                        ah[b] = __builtin_bit_cast(u32x4, h8);
+                        am[b] = __builtin_bit_cast(u32x4, m8);
+                        sq[b] = chunk_sumsq<kF32>(c1, chunk_sumsq<kF32>(c0, 0.0f));
+                    }
 #pragma unroll
-                    for (int b = 0; b < kBlocks; ++b) ssq[b] = chunk_sumsq<DT>(a[b], ssq[b]);
+                    for (int b = 0; b < kBlocks; ++b) acc[b] = mma_k16_split(ah[b], am[b], breg[2 * g], breg[2 * g + 1], acc[b]);
+                    if (g == wave) {                   // this wave's share of the sums of squares
+#pragma unroll
+                        for (int b = 0; b < kBlocks; ++b) ssq[b] += sq[b];
+                    }
+                } else {
+                    u32x4 a[kBlocks];
+#pragma unroll
+                    for (int b = 0; b < kBlocks; ++b)
+                        a[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + (y16 ^ (g << 5)));
+#pragma unroll
+                    for (int b = 0; b < kBlocks; ++b) acc[b] = mma_k16<DT>(a[b], breg[g], acc[b]);
+                    if ((g & 3) == wave) {             // this wave's share of the sums of squares
+#pragma unroll
+                        for (int b = 0; b < kBlocks; ++b) ssq[b] = chunk_sumsq<DT>(a[b], ssq[b]);
+                    }
                 }
-                if (decltype(refill)::value) breg[g] = nb[(size_t)(kn * kGroupsPerTile + g) * 256];
+                if (decltype(refill)::value) {
+#pragma unroll
+                    for (int pl = 0; pl < kPlanes; ++pl) breg[g * kPlanes + pl] = b_fragment(nb, kn, g, pl);
+                }
             }
             ++stage;
         };

@@ -108,9 +108,14 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const 
         for (int i = 0; i < kChunksPerThread; ++i)
             areg[j][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gptr[i] + (int64_t)kt * kTileBytes));   // read once
     };
-    auto load_b = [&](int j, int kt) {
+    constexpr int kMmaGroups = Compute<DT>::kMmaGroups, kPlanes = Compute<DT>::kPlanes;
+    const size_t plane_chunks = (size_t)p.d * 16;
+    auto load_b = [&](int j, int kt) {            // breg[j][g * kPlanes + plane]
 #pragma unroll
-        for (int g = 0; g < kGroupsPerTile; ++g) breg[j][g] = bptr[(size_t)(kt * kGroupsPerTile + g) * 256];
+        for (int g = 0; g < kMmaGroups; ++g)
+#pragma unroll
+            for (int pl = 0; pl < kPlanes; ++pl)
+                breg[j][g * kPlanes + pl] = bptr[pl * plane_chunks + (size_t)(kt * kMmaGroups + g) * 256];
     };
 
     // ntile >= kDepth (host-checked): the ring is filled without branches, in the same order
@@ -129,16 +134,39 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const 
 #pragma unroll
         for (int i = 0; i < kChunksPerThread; ++i) {
             ss[i] = chunk_sumsq<DT>(areg[j][i], ss[i]);
-            *reinterpret_cast<u32x4*>(buf + (lr0 + 16 * i) * kPitch + cc * 16) = areg[j][i];
+            char* dst = buf + (lr0 + 16 * i) * kPitch;
+            if constexpr (DT == kF32) {
+                // split this chunk's four fp32 values; the row holds its 64 "hi" terms (128 bytes)
+                // followed by its 64 "mid" terms
+                float x[4] = {__uint_as_float(areg[j][i].x), __uint_as_float(areg[j][i].y),
+                              __uint_as_float(areg[j][i].z), __uint_as_float(areg[j][i].w)};
+                __bf16 hi[4], mid[4];
+                split_bf16(x, 4, hi, mid);
+                typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+                typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+                bf16x4 h4 = {hi[0], hi[1], hi[2], hi[3]}, m4 = {mid[0], mid[1], mid[2], mid[3]};
+                *reinterpret_cast<u32x2*>(dst + cc * 8) = __builtin_bit_cast(u32x2, h4);
+                *reinterpret_cast<u32x2*>(dst + 128 + cc * 8) = __builtin_bit_cast(u32x2, m4);
+            } else {
+                *reinterpret_cast<u32x4*>(dst + cc * 16) = areg[j][i];
+            }
         }
         __syncthreads();
         if (refill) load_a(j, next);
 #pragma unroll
-        for (int g = 0; g < kGroupsPerTile; ++g) {
-            u32x4 a0 = *reinterpret_cast<const u32x4*>(buf + a_read_off + g * 32);
-            u32x4 a1 = *reinterpret_cast<const u32x4*>(buf + a_read_off + 32 * kPitch + g * 32);
-            acc[0] = mma_kgroup<DT>(a0, breg[j][g], acc[0]);
-            acc[1] = mma_kgroup<DT>(a1, breg[j][g], acc[1]);
+        for (int g = 0; g < kMmaGroups; ++g) {
+            const char* src = buf + a_read_off + g * 32;
+            if constexpr (DT == kF32) {
+                u32x4 a0h = *reinterpret_cast<const u32x4*>(src), a0m = *reinterpret_cast<const u32x4*>(src + 128);
+                u32x4 a1h = *reinterpret_cast<const u32x4*>(src + 32 * kPitch), a1m = *reinterpret_cast<const u32x4*>(src + 32 * kPitch + 128);
+                acc[0] = mma_k16_split(a0h, a0m, breg[j][2 * g], breg[j][2 * g + 1], acc[0]);
+                acc[1] = mma_k16_split(a1h, a1m, breg[j][2 * g], breg[j][2 * g + 1], acc[1]);
+            } else {
+                u32x4 a0 = *reinterpret_cast<const u32x4*>(src);
+                u32x4 a1 = *reinterpret_cast<const u32x4*>(src + 32 * kPitch);
+                acc[0] = mma_k16<DT>(a0, breg[j][g], acc[0]);
+                acc[1] = mma_k16<DT>(a1, breg[j][g], acc[1]);
+            }
         }
         if (refill) {
             load_b(j, next);
