@@ -7,6 +7,8 @@ from .tide_oracle import (  # noqa: F401
     DTYPE_CODES,
     build,
     exit_from_fire,
+    exit_project,
+    round_to_storage,
     fires,
     max_threads,
     rmsnorm,

@@ -28,6 +28,12 @@
  *     0 < theta < 1; theta >= 1 never fires (the paper's "1.0 (off)" row of
  *     Table 4), theta <= 0 always fires.
  *   - exit is per token (Abstract, Fig. 1, Table 1), not per batch.
+ *   - exit projection (Fig. 1 "LMHead(Norm(h_k))", Alg. 1 "LMHead(RMSNorm(H[k+1]))", Sec. 3.4
+ *     kernels 3 and 4): the row handed to the LM head for token t is the model's final
+ *     RMSNorm applied to the hidden state of the checkpoint the token exits at, written at
+ *     the token's own position; a token that does not exit takes the last layer's hidden
+ *     state (Alg. 1's "no early exit" branch).  The result is stored in the model's own
+ *     type, i.e. the fp64 value is rounded ONCE, to nearest even, to the storage type.
  *
  * All arithmetic is double precision, summed left to right in index order.
  * Inputs are the very bytes the GPU path receives: hidden states in their
@@ -84,6 +90,60 @@ static double widen(const void* p, int dtype, int64_t i) {
     case ORACLE_F32: return widen_f32(p, i);
     case ORACLE_F16: return widen_f16(p, i);
     default:         return widen_bf16(p, i);
+    }
+}
+
+/* ---- exact rounding of a double to a storage type (nearest, ties to even) ---- */
+
+/* p significant bits; emin = frexp exponent of the smallest normal (value = m * 2^e, 0.5 <= |m| < 1);
+ * emax = frexp exponent of the largest finite.  Below the normal range precision shrinks
+ * (gradual underflow).  rint() rounds to nearest even in the default rounding mode.          */
+static double round_to_format(double v, int p, int emin, int emax) {
+    if (v == 0.0 || isnan(v) || isinf(v)) return v;
+    int e;
+    double m = frexp(v, &e);
+    int bits = p;
+    if (e < emin) bits = p - (emin - e);
+    if (bits < 0) return copysign(0.0, v);         /* below half the smallest subnormal */
+    double r = ldexp(rint(ldexp(m, bits)), e - bits);
+    double top = ldexp(1.0 - ldexp(1.0, -p), emax); /* largest finite */
+    if (fabs(r) > top) return copysign(INFINITY, v);
+    return r;
+}
+
+static double round_to_storage(double v, int dtype) {
+    switch (dtype) {
+    case ORACLE_F32: return round_to_format(v, 24, -125, 128);
+    case ORACLE_F16: return round_to_format(v, 11, -13, 16);
+    default:         return round_to_format(v, 8, -125, 128);
+    }
+}
+
+/* bit pattern of a value that is exactly representable in the storage type */
+static void store_exact(void* p, int dtype, int64_t i, double r) {
+    if (dtype == ORACLE_F32) {
+        float f = (float)r;
+        memcpy((char*)p + 4 * i, &f, 4);
+    } else if (dtype == ORACLE_BF16) {
+        float f = (float)r;
+        uint32_t u;
+        memcpy(&u, &f, 4);
+        uint16_t h = (uint16_t)(u >> 16);
+        memcpy((char*)p + 2 * i, &h, 2);
+    } else {
+        uint16_t h;
+        uint16_t sign = signbit(r) ? 0x8000 : 0;
+        double a = fabs(r);
+        if (isnan(r)) h = 0x7e00;
+        else if (isinf(r)) h = sign | 0x7c00;
+        else if (a == 0.0) h = sign;
+        else {
+            int e;
+            double m = frexp(a, &e);               /* a = m * 2^e */
+            if (e < -13) h = sign | (uint16_t)ldexp(a, 24);              /* subnormal: a / 2^-24 */
+            else h = sign | (uint16_t)(((e + 14) << 10) | ((int)ldexp(m, 11) & 0x3ff));
+        }
+        memcpy((char*)p + 2 * i, &h, 2);
     }
 }
 
@@ -256,6 +316,50 @@ int tide_oracle_exit_from_fire(const uint8_t* fire /* [C,T] */, int64_t C, int64
     }
     return 0;
 }
+
+/* ---- exported: exit projection (Fig. 1 output box, Alg. 1 line 5, Sec. 3.4 kernels 3-4) ---- */
+
+/* hidden [C,T,d] (strides in elements), final_hidden [T,d] or NULL, exit_layer [T],
+ * layer_ids [C], gain [d] or NULL (ones).  out [T,d] in the storage type.  A token whose
+ * exit_layer is not a checkpoint layer takes final_hidden's row, or is left untouched when
+ * final_hidden is NULL.  written[t] (optional) = 1 iff row t of out was written.            */
+int tide_oracle_exit_project(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d,
+                             int64_t ckpt_stride, int64_t row_stride, const void* final_hidden,
+                             int64_t final_row_stride, const int32_t* exit_layer,
+                             const int32_t* layer_ids, const float* gain, double eps, void* out,
+                             int64_t out_row_stride, uint8_t* written) {
+    if (C < 1 || T < 0 || d <= 0 || row_stride < d || out_row_stride < d) return -1;
+    for (int64_t t = 0; t < T; ++t) {
+        const void* src = NULL;
+        int64_t off = 0;
+        for (int64_t c = 0; c < C; ++c)
+            if (layer_ids[c] == exit_layer[t]) {
+                src = hidden;
+                off = c * ckpt_stride + t * row_stride;
+                break;
+            }
+        if (!src && final_hidden) {
+            src = final_hidden;
+            off = t * final_row_stride;
+        }
+        if (written) written[t] = src ? 1 : 0;
+        if (!src) continue;
+        double ss = 0.0;
+        for (int64_t i = 0; i < d; ++i) {
+            double x = widen(src, dtype, off + i);
+            ss += x * x;
+        }
+        double r = 1.0 / sqrt(ss / (double)d + eps);
+        for (int64_t i = 0; i < d; ++i) {
+            double g = gain ? (double)gain[i] : 1.0;
+            double y = widen(src, dtype, off + i) * r * g;
+            store_exact(out, dtype, t * out_row_stride + i, round_to_storage(y, dtype));
+        }
+    }
+    return 0;
+}
+
+double tide_oracle_round_to_storage(double v, int dtype) { return round_to_storage(v, dtype); }
 
 /* ---- exported: scalar helpers, so that the pins can probe them directly ---- */
 

@@ -46,6 +46,11 @@ def _load():
         lib.tide_oracle_select_exit.restype = ctypes.c_int
         lib.tide_oracle_exit_from_fire.argtypes = [vp, i64, i64, vp, i32, i32, vp]
         lib.tide_oracle_exit_from_fire.restype = ctypes.c_int
+        lib.tide_oracle_exit_project.argtypes = [vp, ctypes.c_int, i64, i64, i64, i64, i64, vp, i64, vp, vp, vp, dbl,
+                                                 vp, i64, vp]
+        lib.tide_oracle_exit_project.restype = ctypes.c_int
+        lib.tide_oracle_round_to_storage.argtypes = [dbl, ctypes.c_int]
+        lib.tide_oracle_round_to_storage.restype = dbl
         lib.tide_oracle_sigmoid.argtypes = [dbl]
         lib.tide_oracle_sigmoid.restype = dbl
         lib.tide_oracle_silu.argtypes = [dbl]
@@ -182,6 +187,39 @@ def select_exit(hidden, dtype, gamma, eps, W1, b1, w2, b2, theta, layer_ids, min
     if rc:
         raise ValueError(f"tide_oracle_select_exit rejected its arguments ({rc})")
     return exit_layer, logits, mask
+
+
+def round_to_storage(v: float, dtype: str) -> float:
+    """The storage-type value nearest to v (ties to even), as a double."""
+    return float(_load().tide_oracle_round_to_storage(float(v), DTYPE_CODES[dtype]))
+
+
+def exit_project(hidden, dtype, final_hidden, exit_layer, layer_ids, gain, eps, d=None, out=None):
+    """Rows for the LM head: final RMSNorm of each token's exit checkpoint state.
+
+    hidden [C,T,rs] storage bits; final_hidden [T,rs2] storage bits or None; exit_layer [T] i32;
+    gain [d] or None.  Returns (out [T,d] storage bits, written [T] u8).  Rows that are not
+    written keep the contents of `out` (zeros when out is not given).
+    """
+    hidden = _storage(hidden, dtype)
+    C, T, rs = hidden.shape
+    d = rs if d is None else int(d)
+    frs = 0
+    if final_hidden is not None:
+        final_hidden = _storage(final_hidden, dtype)
+        frs = int(final_hidden.shape[1])
+    exit_layer = np.ascontiguousarray(exit_layer, dtype=np.int32)
+    layer_ids = np.ascontiguousarray(layer_ids, dtype=np.int32)
+    gain = _f32(gain, (d,))
+    if out is None:
+        out = np.zeros((T, d), dtype=hidden.dtype)
+    written = np.empty(T, dtype=np.uint8)
+    rc = _load().tide_oracle_exit_project(_p(hidden), DTYPE_CODES[dtype], C, T, d, T * rs, rs, _p(final_hidden), frs,
+                                          _p(exit_layer), _p(layer_ids), _p(gain), float(np.float32(eps)), _p(out),
+                                          int(out.shape[1]), _p(written))
+    if rc:
+        raise ValueError("tide_oracle_exit_project rejected its arguments")
+    return out, written
 
 
 def exit_from_fire(fire, layer_ids, min_layer, no_exit_layer):

@@ -35,6 +35,11 @@ MUTANTS = {
     "bf16_shift": [("(uint32_t)h << 16", "(uint32_t)h << 15")],
     "f16_bias": [("ex - 15)", "ex - 16)")],
     "f16_subnormal": [("ldexp((double)fr, -24)", "ldexp((double)fr, -25)")],
+    "projection_takes_first_checkpoint": [("off = c * ckpt_stride + t * row_stride;\n                break;", "off = t * row_stride;\n                break;")],
+    "projection_drops_gain": [("double y = widen(src, dtype, off + i) * r * g;", "double y = widen(src, dtype, off + i) * r;")],
+    "projection_truncates": [("double r = ldexp(rint(ldexp(m, bits)), e - bits);", "double r = ldexp(trunc(ldexp(m, bits)), e - bits);")],
+    "projection_ignores_final_state": [("if (!src && final_hidden) {", "if (0) {")],
+    "bf16_rounds_to_9_bits": [("default:         return round_to_format(v, 8, -125, 128);", "default:         return round_to_format(v, 9, -125, 128);")],
 }
 
 

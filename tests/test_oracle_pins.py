@@ -360,3 +360,94 @@ def test_calibrated_bias_hits_the_requested_firing_count():
     _, z1, mask = oracle.select_exit(h, "bf16", rt.gamma, w.eps, rt.W1, rt.b1, rt.w2, rt.b2, rt.theta, w.layer_ids, 0, 32)
     for c in range(w.C):
         assert int(((mask >> c) & 1).sum()) == round(0.30 * w.T)
+
+
+# --------------------------------------------------------------------------- exit projection
+
+def test_round_to_storage_against_numpy_and_exact_ties():
+    """double -> fp16 against numpy's correctly rounded cast (random values, every midpoint
+    between consecutive fp16 values, the subnormal range, overflow); double -> bf16 on every
+    representable value, every midpoint (ties to even) and points just off the midpoints."""
+    rng = np.random.default_rng(5)
+    vals = np.concatenate([rng.standard_normal(20000) * 10.0 ** rng.integers(-8, 5, 20000),
+                           rng.standard_normal(2000) * 1e-7, [65504.0, 65519.9, 65520.0, 70000.0, -1e9, 0.0, -0.0]])
+    with np.errstate(over="ignore"):
+        want = vals.astype(np.float16).astype(np.float64)
+    got = np.array([oracle.round_to_storage(v, "f16") for v in vals])
+    assert np.array_equal(got, want)
+    h = np.arange(0, 0x7c00, dtype=np.uint16).view(np.float16).astype(np.float64)   # all finite non-negative
+    mid = (h[:-1] + h[1:]) / 2
+    with np.errstate(over="ignore"):
+        assert np.array_equal(np.array([oracle.round_to_storage(v, "f16") for v in mid]), mid.astype(np.float16).astype(np.float64))
+    b = (np.arange(0x0080, 0x7f80, 7, dtype=np.uint32) << 16).view(np.float32).astype(np.float64)  # normal bf16 values
+    assert np.array_equal(np.array([oracle.round_to_storage(v, "bf16") for v in b]), b)
+    bits = np.arange(0x3f00, 0x4100, dtype=np.uint32)
+    lo, hi = (bits << 16).view(np.float32).astype(np.float64), ((bits + 1) << 16).view(np.float32).astype(np.float64)
+    for l, u, bb in zip(lo, hi, bits):
+        m = (l + u) / 2
+        even = l if bb % 2 == 0 else u
+        assert oracle.round_to_storage(m, "bf16") == even
+        assert oracle.round_to_storage(np.nextafter(m, l), "bf16") == l
+        assert oracle.round_to_storage(np.nextafter(m, u), "bf16") == u
+    assert oracle.round_to_storage(1.0 + 2.0 ** -30, "f32") == 1.0
+    assert oracle.round_to_storage(1.0 + 2.0 ** -24, "f32") == 1.0            # tie -> even
+    assert oracle.round_to_storage(1.0 + 3 * 2.0 ** -24, "f32") == 1.0 + 2.0 ** -22
+
+
+def test_exit_projection_gathers_the_exit_checkpoint_row():
+    """One-hot rows h[c,t,:] = v * e_c make the source identifiable: at eps = 0 the projected row
+    is sqrt(d) * gain[c] * sign(v) at position c and 0 elsewhere (closed form); tokens without an
+    exit take the final hidden state, or stay untouched when none is given."""
+    C, T, d = 4, 9, 16
+    ids = np.array([3, 7, 11, 15], np.int32)
+    h = np.zeros((C, T, d), np.float32)
+    for c in range(C):
+        h[c, :, c] = 2.0 + c
+    fin = np.zeros((T, d), np.float32)
+    fin[:, 9] = -5.0
+    gain = (1 + 0.25 * np.arange(d)).astype(np.float32)
+    exits = np.array([3, 7, 11, 15, 16, 16, 7, 3, 99], np.int32)
+    out, written = oracle.exit_project(h, "f32", fin, exits, ids, gain, 0.0)
+    assert written.all()
+    for t, e in enumerate(exits):
+        want = np.zeros(d)
+        if e in ids:
+            c = int(np.nonzero(ids == e)[0][0])
+            want[c] = math.sqrt(d) * float(gain[c])
+        else:
+            want[9] = -math.sqrt(d) * float(gain[9])
+        assert np.allclose(out[t], want.astype(np.float32), rtol=1e-7, atol=0)
+    sentinel = np.full((T, d), 42.0, np.float32)
+    out2, written2 = oracle.exit_project(h, "f32", None, exits, ids, gain, 0.0, out=sentinel)
+    assert written2.tolist() == [1, 1, 1, 1, 0, 0, 1, 1, 0]
+    assert np.all(out2[written2 == 0] == 42.0) and np.array_equal(out2[written2 == 1], out[written2 == 1])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_exit_projection_matches_rmsnorm_then_numpy_rounding(dtype):
+    """The projected row is the RMSNorm pin-tested above, rounded once to the storage type:
+    fp16 and fp32 against numpy's casts from float64, bf16 against exact neighbour search."""
+    C, T, d = 3, 40, 96
+    w = synth.Workload("proj", 31, dtype, d, 12, 4, T, None)
+    hb = w.hidden()
+    ids = w.layer_ids
+    exits = RNG.choice(np.concatenate([ids, [12]]), size=T).astype(np.int32)
+    fin = synth.make_hidden(32, 1, T, d, dtype)[0]
+    gain = (1 + 0.1 * RNG.standard_normal(d)).astype(np.float32)
+    out, written = oracle.exit_project(hb, dtype, fin, exits, ids, gain, 1e-6)
+    assert written.all()
+    for t in range(T):
+        src = hb[int(np.nonzero(ids == exits[t])[0][0]), t] if exits[t] in ids else fin[t]
+        y = oracle.rmsnorm(src[None, :], dtype, gain, float(np.float32(1e-6)))[0]        # float64
+        if dtype == "f32":
+            want = y.astype(np.float32)
+        elif dtype == "f16":
+            want = y.astype(np.float16)
+        else:
+            f = y.astype(np.float32)
+            b0 = (f.view(np.uint32) >> 16).astype(np.int64)
+            cand = np.stack([synth.bf16_bits_to_f32(np.clip(b0 + k, 0, 0xFFFF).astype(np.uint16)) for k in (-1, 0, 1)]).astype(np.float64)
+            best = np.abs(cand - y[None, :]).argmin(axis=0)          # ties are measure-zero for random data
+            want_f = cand[best, np.arange(d)].astype(np.float32)
+            want = (want_f.view(np.uint32) >> 16).astype(np.uint16)
+        assert np.array_equal(out[t].view(np.uint16) if dtype != "f32" else out[t], want.view(np.uint16) if dtype != "f32" else want)
