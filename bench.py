@@ -176,6 +176,17 @@ def main() -> int:
         "roofline": roofline,
     }
 
+    # ---- exit projection (the step after the path: rows for the LM head), same workload
+    final_h = torch.from_numpy(synth.make_hidden(w.cfg + 7, 1, T, d, w.dtype)[0].view(np.int16)).cuda().view(torch.bfloat16)
+    norm_gain = torch.ones(d, dtype=torch.float32, device="cuda")
+    proj_out = torch.empty((T, d), dtype=torch.bfloat16, device="cuda")
+    pj_calls = [tr.prepare_exit_project(b, final_h, out[0], w.layer_ids, norm_gain, 1e-6, out=proj_out) for b in batches]
+    wall_pj, ev_pj = timed(lambda i: pj_calls[i % args.buffers](), args.steps, args.warmup)
+    pj_bytes = 2 * T * d * esz + 4 * T + 4 * d
+    result["exit_projection"] = {"entry_point": "tide_exit_project", "us_per_call": round(ev_pj / args.steps * 1e6, 2),
+                                 "algorithmic_bytes": pj_bytes, "gbs": round(pj_bytes / (ev_pj / args.steps) / 1e9, 1),
+                                 "frac_of_hbm_peak": round(pj_bytes / (ev_pj / args.steps) / 1e9 / HBM_PEAK_GBS, 4)}
+
     # ---- decode latency (config 2): fp16, T = 1 and 8, raw weights, auto-selected decode variant
     if not args.no_decode:
         dec = {}

@@ -125,6 +125,23 @@ int tide_select_exit_packed(const void* hidden, int dtype, int64_t C, int64_t T,
                             int32_t no_exit_layer, int32_t* exit_layer, float* logits,
                             uint32_t* fire_mask, void* stream);
 
+/* Exit projection: the rows the LM head consumes (Fig. 1 "LMHead(Norm(h_k))", Alg. 1 line 5,
+ * Sec. 3.4 kernels 3-4).  out[t,:] = RMSNorm(src_t) * norm_gain, computed in fp32 and rounded
+ * once to `dtype`, where src_t = hidden[c,t,:] for the checkpoint c with
+ * layer_ids[c] == exit_layer[t], else final_hidden[t,:] (the last layer's state; Alg. 1's
+ * "no early exit" branch); with final_hidden == NULL such tokens' rows of out are left untouched.
+ *   hidden       device [C,T rows], as for tide_select_exit
+ *   final_hidden device [T rows] of `dtype` or NULL;  final_row_stride in elements
+ *   exit_layer   device [T] int32 (e.g. tide_select_exit's output)
+ *   layer_ids    HOST [C] int32, strictly ascending
+ *   norm_gain    device [d] fp32, 16-byte aligned, or NULL (ones);  eps as in the model's final norm
+ *   out          device [T rows] of `dtype`, out_row_stride >= d elements, 16-byte aligned      */
+int tide_exit_project(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d,
+                      int64_t ckpt_stride, int64_t row_stride, const void* final_hidden,
+                      int64_t final_row_stride, const int32_t* exit_layer, const int32_t* layer_ids,
+                      const float* norm_gain, float eps, void* out, int64_t out_row_stride,
+                      void* stream);
+
 /* Force a kernel variant for the raw-weight entry points (process-wide; for tests and
  * benchmarks).  Returns the previous setting, or TIDE_ERR_INVALID_ARG.                  */
 int tide_set_variant(int variant);

@@ -16,6 +16,7 @@
 #include "pack_kernel.hpp"
 #include "prefill_dma_kernel.hpp"
 #include "prefill_kernel.hpp"
+#include "project_kernel.hpp"
 
 namespace {
 
@@ -407,6 +408,64 @@ int tide_select_exit_packed(const void* hidden, int dtype, int64_t C, int64_t T,
     Outputs o{nullptr, nullptr, logits, exit_layer, fire_mask};
     return run(hidden, dtype, C, T, d, ckpt_stride, row_stride, nullptr, nullptr, packed, eps, b1, w2, tab, min_layer,
                no_exit_layer, o, stream);
+}
+
+int tide_exit_project(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t ckpt_stride,
+                      int64_t row_stride, const void* final_hidden, int64_t final_row_stride,
+                      const int32_t* exit_layer, const int32_t* layer_ids, const float* norm_gain, float eps,
+                      void* out, int64_t out_row_stride, void* stream) {
+    g_err[0] = 0;
+    int rc = check_common(hidden, dtype, C, T, d, ckpt_stride, row_stride, hidden, reinterpret_cast<const float*>(hidden), eps);
+    if (rc) return rc;
+    if (T == 0) return TIDE_OK;
+    if (!exit_layer || !layer_ids || !out) return fail(TIDE_ERR_INVALID_ARG, "exit_layer, layer_ids (host) and out must not be NULL");
+    if (out_row_stride < d || (final_hidden && final_row_stride < d))
+        return fail(TIDE_ERR_INVALID_ARG, "row strides of out / final_hidden must be at least d");
+    const size_t eb = elem_bytes(dtype);
+    if (((uintptr_t)out & 15) || ((size_t)out_row_stride * eb & 15) ||
+        (final_hidden && (((uintptr_t)final_hidden & 15) || ((size_t)final_row_stride * eb & 15))) ||
+        ((uintptr_t)norm_gain & 15))
+        return fail(TIDE_ERR_ALIGNMENT, "out, final_hidden and norm_gain bases and the row strides must be multiples of 16 bytes");
+    ProjectParams p;
+    std::memset(&p, 0, sizeof(p));
+    for (int64_t c = 0; c < C; ++c) {
+        if (c > 0 && layer_ids[c] <= layer_ids[c - 1])
+            return fail(TIDE_ERR_INVALID_ARG, "layer_ids must be strictly ascending");
+        p.layer_id[c] = layer_ids[c];
+    }
+    p.hidden = (const char*)hidden;
+    p.ckpt_stride_bytes = ckpt_stride * (int64_t)eb;
+    p.row_stride_bytes = row_stride * (int64_t)eb;
+    p.final_hidden = (const char*)final_hidden;
+    p.final_row_stride_bytes = final_row_stride * (int64_t)eb;
+    p.exit_layer = exit_layer;
+    p.gain = norm_gain;
+    p.out = (char*)out;
+    p.out_row_stride_bytes = out_row_stride * (int64_t)eb;
+    p.C = (int)C;
+    p.T = (int)T;
+    p.d = (int)d;
+    p.eps = eps;
+    const int64_t row_bytes = d * (int64_t)eb;
+    const bool wave_per_row = row_bytes <= (int64_t)kProjectMaxChunks * 16 * kWave;      // 16 KiB
+    if (row_bytes > (int64_t)kProjectMaxChunks * 16 * kProjectThreads)
+        return fail(TIDE_ERR_UNSUPPORTED, "rows of %lld bytes exceed the projection kernel's limit", (long long)row_bytes);
+    hipStream_t st = (hipStream_t)stream;
+    const unsigned grid = wave_per_row ? (unsigned)((T + 3) / 4) : (unsigned)T;
+    by_dtype(dtype, [&](auto dt) {
+        constexpr int DT = decltype(dt)::value;
+        if (wave_per_row && norm_gain)
+            hipLaunchKernelGGL((tide_project_kernel<DT, true, true>), dim3(grid), dim3(kProjectThreads), 0, st, p);
+        else if (wave_per_row)
+            hipLaunchKernelGGL((tide_project_kernel<DT, true, false>), dim3(grid), dim3(kProjectThreads), 0, st, p);
+        else if (norm_gain)
+            hipLaunchKernelGGL((tide_project_kernel<DT, false, true>), dim3(grid), dim3(kProjectThreads), 0, st, p);
+        else
+            hipLaunchKernelGGL((tide_project_kernel<DT, false, false>), dim3(grid), dim3(kProjectThreads), 0, st, p);
+        return 0;
+    });
+    TIDE_HIP(hipGetLastError());
+    return TIDE_OK;
 }
 
 int tide_set_variant(int variant) {

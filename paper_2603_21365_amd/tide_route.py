@@ -25,7 +25,7 @@ DTYPE_CODES = {"f32": F32, "f16": F16, "bf16": BF16}
 EXPORTS = (
     "tide_version", "tide_last_error", "tide_router_eval", "tide_select_exit",
     "tide_packed_router_bytes", "tide_router_pack", "tide_router_eval_packed",
-    "tide_select_exit_packed", "tide_set_variant", "tide_set_prefill_form", "tide_release",
+    "tide_select_exit_packed", "tide_exit_project", "tide_set_variant", "tide_set_prefill_form", "tide_release",
 )
 
 _lib = None
@@ -57,10 +57,11 @@ def load_library() -> ctypes.CDLL:
     lib.tide_packed_router_bytes.argtypes = [ci, i64]
     lib.tide_packed_router_bytes.restype = ctypes.c_size_t
     lib.tide_router_pack.argtypes = [ci, i64, i64, vp, vp, vp, vp]
+    lib.tide_exit_project.argtypes = [vp, ci, i64, i64, i64, i64, i64, vp, i64, vp, vp, vp, f32, vp, i64, vp]
     lib.tide_set_variant.argtypes = [ci]
     lib.tide_set_prefill_form.argtypes = [ci]
     for name in ("tide_router_eval", "tide_router_eval_packed", "tide_select_exit", "tide_select_exit_packed",
-                 "tide_router_pack", "tide_set_variant", "tide_set_prefill_form", "tide_release"):
+                 "tide_router_pack", "tide_exit_project", "tide_set_variant", "tide_set_prefill_form", "tide_release"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -244,6 +245,43 @@ def select_exit_packed(hidden, packed, eps, b1, w2, b2, threshold, layer_ids, mi
     return exit_layer, logits, mask
 
 
+def _project_args(hidden, final_hidden, exit_layer, layer_ids, norm_gain, eps, d, out):
+    (C, T, width), (cs, rs, _) = _rows(hidden, 3)
+    d = width if d is None else int(d)
+    if width < d:
+        raise ValueError("hidden rows are shorter than d")
+    _f32dev(norm_gain, (d,), "norm_gain")
+    if exit_layer.dtype != torch.int32 or not exit_layer.is_cuda or tuple(exit_layer.shape) != (T,) or not exit_layer.is_contiguous():
+        raise ValueError("exit_layer must be a contiguous CUDA int32 tensor of shape [T]")
+    frs = 0
+    if final_hidden is not None:
+        (Tf, wf), (frs, _) = _rows(final_hidden, 2)
+        if Tf != T or wf < d or final_hidden.dtype != hidden.dtype:
+            raise ValueError("final_hidden must be [T, >=d] of hidden's dtype")
+        frs = frs if T > 1 else max(frs, d)
+    if out is None:
+        out = torch.zeros((T, d), dtype=hidden.dtype, device=hidden.device)
+    (To, wo), (ors, _) = _rows(out, 2)
+    if To != T or wo < d or out.dtype != hidden.dtype:
+        raise ValueError("out must be [T, >=d] of hidden's dtype")
+    idh, idp = _host(layer_ids, C, np.int32)
+    cs = cs if (C > 1 and T > 0) else max(cs, 0)
+    vals = (_ptr(hidden), _dtype_code(hidden), C, T, d, cs, rs if T > 1 else max(rs, d), _ptr(final_hidden), frs,
+            _ptr(exit_layer), idp.value, _ptr(norm_gain), float(eps), _ptr(out), ors if T > 1 else max(ors, d), _stream())
+    return vals, idh, out
+
+
+def exit_project(hidden, final_hidden, exit_layer, layer_ids, norm_gain, eps, *, d=None, out=None):
+    """hidden [C,T,>=d]; final_hidden [T,>=d] | None; exit_layer int32 [T] (device); layer_ids host [C];
+    norm_gain [d] | None -> out [T,d] of hidden's dtype (rows of non-exiting tokens untouched when
+    final_hidden is None)."""
+    vals, keep, out = _project_args(hidden, final_hidden, exit_layer, layer_ids, norm_gain, eps, d, out)
+    fn = load_library().tide_exit_project
+    _check(fn(*_c(fn.argtypes, vals)))
+    del keep
+    return out
+
+
 class PreparedCall:
     """A C entry point with its arguments marshalled once.
 
@@ -288,3 +326,9 @@ def prepare_select_exit_packed(hidden, packed, eps, b1, w2, b2, threshold, layer
             b2p.value, thp.value, idp.value, int(min_layer), int(no_exit_layer), _ptr(exit_layer), _ptr(logits),
             _ptr(mask), _stream())
     return PreparedCall(fn, _c(fn.argtypes, vals), (keep, hidden, packed, b1, w2), (exit_layer, logits, mask))
+
+
+def prepare_exit_project(hidden, final_hidden, exit_layer, layer_ids, norm_gain, eps, *, d=None, out=None) -> PreparedCall:
+    vals, keep, out = _project_args(hidden, final_hidden, exit_layer, layer_ids, norm_gain, eps, d, out)
+    fn = load_library().tide_exit_project
+    return PreparedCall(fn, _c(fn.argtypes, vals), (keep, hidden, final_hidden, exit_layer, norm_gain), out)

@@ -82,6 +82,26 @@ def test_select_exit_rejects_bad_arguments():
     assert call(T=0, hidden=None) == 0
 
 
+def test_exit_project_rejects_bad_arguments():
+    lib = tr.load_library()
+    ids = np.asarray([3, 7], np.int32)
+    idp = ids.ctypes.data_as(ctypes.c_void_p)
+
+    def call(T=4, d=256, out=FAKE, out_rs=256, ex=FAKE, fin=None, fin_rs=0, ids_p=idp):
+        return lib.tide_exit_project(FAKE, 2, 2, T, d, 1024, 256, fin, fin_rs, ex, ids_p, None, 1e-6, out, out_rs, None)
+
+    assert call(out=None) == -1
+    assert call(ex=None) == -1
+    assert call(ids_p=None) == -1
+    assert call(out_rs=128) == -1
+    assert call(fin=FAKE, fin_rs=100) == -1
+    assert call(out=FAKE + 4) == -3
+    assert call(d=100, out_rs=100) == -2
+    bad = np.asarray([7, 3], np.int32)
+    assert call(ids_p=bad.ctypes.data_as(ctypes.c_void_p)) == -1
+    assert call(T=0) == 0
+
+
 def test_set_variant_validates():
     prev = tr.set_variant(tr.VARIANT_AUTO)
     assert prev in (0, 1, 2)
