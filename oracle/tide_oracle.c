@@ -317,6 +317,30 @@ int tide_oracle_exit_from_fire(const uint8_t* fire /* [C,T] */, int64_t C, int64
     return 0;
 }
 
+/* ---- exported: whole-batch exit, Alg. 1 read literally ---- */
+
+/* Alg. 1 walks the checkpoints in ascending order, skips those below k_min and returns at the
+ * first one whose score exceeds theta "for all tokens in batch"; otherwise there is no early
+ * exit.  fire [C,T] are the per-token threshold tests.  Also returns, per checkpoint, how many
+ * tokens fired (the numbers behind Table 1's distribution column).                           */
+int tide_oracle_batch_exit(const uint8_t* fire /* [C,T] */, int64_t C, int64_t T,
+                           const int32_t* layer_ids, int32_t min_layer, int32_t no_exit_layer,
+                           int32_t* batch_exit_layer, int64_t* fire_counts /* [C] or NULL */) {
+    if (C < 1 || T < 0) return -1;
+    *batch_exit_layer = no_exit_layer;
+    int decided = 0;
+    for (int64_t c = 0; c < C; ++c) {
+        int64_t n = 0;
+        for (int64_t t = 0; t < T; ++t) n += fire[c * T + t] ? 1 : 0;
+        if (fire_counts) fire_counts[c] = n;
+        if (!decided && layer_ids[c] >= min_layer && n == T && T > 0) {
+            *batch_exit_layer = layer_ids[c];
+            decided = 1;
+        }
+    }
+    return 0;
+}
+
 /* ---- exported: exit projection (Fig. 1 output box, Alg. 1 line 5, Sec. 3.4 kernels 3-4) ---- */
 
 /* hidden [C,T,d] (strides in elements), final_hidden [T,d] or NULL, exit_layer [T],

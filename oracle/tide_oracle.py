@@ -46,6 +46,8 @@ def _load():
         lib.tide_oracle_select_exit.restype = ctypes.c_int
         lib.tide_oracle_exit_from_fire.argtypes = [vp, i64, i64, vp, i32, i32, vp]
         lib.tide_oracle_exit_from_fire.restype = ctypes.c_int
+        lib.tide_oracle_batch_exit.argtypes = [vp, i64, i64, vp, i32, i32, vp, vp]
+        lib.tide_oracle_batch_exit.restype = ctypes.c_int
         lib.tide_oracle_exit_project.argtypes = [vp, ctypes.c_int, i64, i64, i64, i64, i64, vp, i64, vp, vp, vp, dbl,
                                                  vp, i64, vp]
         lib.tide_oracle_exit_project.restype = ctypes.c_int
@@ -187,6 +189,22 @@ def select_exit(hidden, dtype, gamma, eps, W1, b1, w2, b2, theta, layer_ids, min
     if rc:
         raise ValueError(f"tide_oracle_select_exit rejected its arguments ({rc})")
     return exit_layer, logits, mask
+
+
+def batch_exit(fire, layer_ids, min_layer, no_exit_layer):
+    """Alg. 1 literally: the first eligible checkpoint at which every token fires.
+
+    fire [C,T] u8 -> (batch_exit_layer int, fire_counts [C] i64)."""
+    fire = np.ascontiguousarray(fire, dtype=np.uint8)
+    C, T = fire.shape
+    layer_ids = np.ascontiguousarray(layer_ids, dtype=np.int32)
+    out = np.zeros(1, dtype=np.int32)
+    counts = np.zeros(C, dtype=np.int64)
+    rc = _load().tide_oracle_batch_exit(_p(fire), C, T, _p(layer_ids), int(min_layer), int(no_exit_layer), _p(out),
+                                        _p(counts))
+    if rc:
+        raise ValueError("tide_oracle_batch_exit rejected its arguments")
+    return int(out[0]), counts
 
 
 def round_to_storage(v: float, dtype: str) -> float:

@@ -35,6 +35,8 @@ MUTANTS = {
     "bf16_shift": [("(uint32_t)h << 16", "(uint32_t)h << 15")],
     "f16_bias": [("ex - 15)", "ex - 16)")],
     "f16_subnormal": [("ldexp((double)fr, -24)", "ldexp((double)fr, -25)")],
+    "batch_exit_any_instead_of_all": [("n == T && T > 0", "n > 0 && T > 0")],
+    "batch_exit_ignores_k_min": [("if (!decided && layer_ids[c] >= min_layer && n == T && T > 0)", "if (!decided && n == T && T > 0)")],
     "projection_takes_first_checkpoint": [("off = c * ckpt_stride + t * row_stride;\n                break;", "off = t * row_stride;\n                break;")],
     "projection_drops_gain": [("double y = widen(src, dtype, off + i) * r * g;", "double y = widen(src, dtype, off + i) * r;")],
     "projection_truncates": [("double r = ldexp(rint(ldexp(m, bits)), e - bits);", "double r = ldexp(trunc(ldexp(m, bits)), e - bits);")],

@@ -451,3 +451,34 @@ def test_exit_projection_matches_rmsnorm_then_numpy_rounding(dtype):
             want_f = cand[best, np.arange(d)].astype(np.float32)
             want = (want_f.view(np.uint32) >> 16).astype(np.uint16)
         assert np.array_equal(out[t].view(np.uint16) if dtype != "f32" else out[t], want.view(np.uint16) if dtype != "f32" else want)
+
+
+# --------------------------------------------------------------------------- whole-batch exit (Alg. 1)
+
+def test_batch_exit_is_alg1_read_literally(golden_dir):
+    ids = np.array([3, 7, 11, 15], np.int32)
+    rng = np.random.default_rng(8)
+    for trial in range(200):
+        T = int(rng.integers(1, 9))
+        fire = (rng.random((4, T)) < 0.8).astype(np.uint8)
+        kmin = int(rng.choice([0, 4, 8, 12, 16]))
+        got, counts = oracle.batch_exit(fire, ids, kmin, 16)
+        want = 16
+        for c in range(4):                                   # the loop of Alg. 1, in Python
+            if ids[c] < kmin:
+                continue
+            if all(fire[c, t] for t in range(T)):
+                want = int(ids[c])
+                break
+        assert got == want
+        assert counts.tolist() == fire.sum(axis=1).tolist()
+        # never earlier than any token's own earliest exit
+        per_token = oracle.exit_from_fire(fire, ids, kmin, 16)
+        assert got >= per_token.max()
+    # the worked example of Fig. 3 has no checkpoint at which all three tokens have converged
+    g = read_golden(os.path.join(golden_dir, "fig3_exit_example.txt"))
+    fire = np.array([[1, 0, 0], [1, 1, 0]], np.uint8)
+    got, counts = oracle.batch_exit(fire, [int(x) for x in g["router_layers"]], 0, int(g["n_layers"][0]))
+    assert got == int(g["n_layers"][0]) and counts.tolist() == [1, 2]
+    assert oracle.batch_exit(np.ones((2, 5), np.uint8), [8, 16], 0, 32)[0] == 8
+    assert oracle.batch_exit(np.ones((2, 5), np.uint8), [8, 16], 9, 32)[0] == 16
