@@ -142,6 +142,18 @@ int tide_exit_project(const void* hidden, int dtype, int64_t C, int64_t T, int64
                       const float* norm_gain, float eps, void* out, int64_t out_row_stride,
                       void* stream);
 
+/* Whole-batch exit, Alg. 1 read literally: the first checkpoint, in ascending order and not below
+ * min_layer, at which EVERY token of the batch fired; no_exit_layer if there is none.
+ *   fire_mask        device [T] u32 (tide_select_exit's output: bit c = token fired at checkpoint c)
+ *   layer_ids        HOST [C] int32, strictly ascending
+ *   batch_exit_layer device [1] int32 out
+ *   all_fire_mask    device [1] u32 out or NULL: bit c set iff all T tokens fired at checkpoint c
+ *   fire_counts      device [C] u32 out or NULL: tokens that fired at each checkpoint
+ * Uses the library workspace (see the conventions at the top).                              */
+int tide_batch_exit(const uint32_t* fire_mask, int64_t T, int64_t C, const int32_t* layer_ids,
+                    int32_t min_layer, int32_t no_exit_layer, int32_t* batch_exit_layer,
+                    uint32_t* all_fire_mask, uint32_t* fire_counts, void* stream);
+
 /* Force a kernel variant for the raw-weight entry points (process-wide; for tests and
  * benchmarks).  Returns the previous setting, or TIDE_ERR_INVALID_ARG.                  */
 int tide_set_variant(int variant);

@@ -12,6 +12,7 @@
 #include <limits>
 #include <mutex>
 
+#include "batch_kernel.hpp"
 #include "decode_kernel.hpp"
 #include "pack_kernel.hpp"
 #include "prefill_dma_kernel.hpp"
@@ -49,7 +50,7 @@ struct Buffer {
 };
 
 struct Workspace {
-    Buffer counters, arrive, packed, part;
+    Buffer counters, arrive, packed, part, batch;
 };
 
 std::mutex g_mu;
@@ -468,6 +469,46 @@ int tide_exit_project(const void* hidden, int dtype, int64_t C, int64_t T, int64
     return TIDE_OK;
 }
 
+int tide_batch_exit(const uint32_t* fire_mask, int64_t T, int64_t C, const int32_t* layer_ids, int32_t min_layer,
+                    int32_t no_exit_layer, int32_t* batch_exit_layer, uint32_t* all_fire_mask, uint32_t* fire_counts,
+                    void* stream) {
+    g_err[0] = 0;
+    if (C < 1 || C > TIDE_MAX_CHECKPOINTS) return fail(TIDE_ERR_INVALID_ARG, "C = %lld outside [1, 32]", (long long)C);
+    if (T < 0 || T > (int64_t)1 << 30) return fail(TIDE_ERR_INVALID_ARG, "T = %lld outside [0, 2^30]", (long long)T);
+    if (T == 0) return TIDE_OK;
+    if (!fire_mask || !layer_ids || !batch_exit_layer)
+        return fail(TIDE_ERR_INVALID_ARG, "fire_mask, layer_ids (host) and batch_exit_layer must not be NULL");
+    BatchParams p;
+    std::memset(&p, 0, sizeof(p));
+    for (int64_t c = 0; c < C; ++c) {
+        if (c > 0 && layer_ids[c] <= layer_ids[c - 1])
+            return fail(TIDE_ERR_INVALID_ARG, "layer_ids must be strictly ascending");
+        p.layer_id[c] = layer_ids[c];
+    }
+    std::lock_guard<std::mutex> lock(g_mu);
+    Workspace* ws = nullptr;
+    int rc = current_workspace(&ws);
+    if (rc) return rc;
+    constexpr unsigned kMaxBlocks = 256;
+    rc = reserve(ws->batch, (kMaxBlocks * 32 + 1) * sizeof(uint32_t), true);
+    if (rc) return rc;
+    p.fire_mask = fire_mask;
+    p.T = (int)T;
+    p.C = (int)C;
+    p.min_layer = min_layer;
+    p.no_exit = no_exit_layer;
+    p.batch_exit_layer = batch_exit_layer;
+    p.all_fire_mask = all_fire_mask;
+    p.fire_counts = fire_counts;
+    p.counter = (uint32_t*)ws->batch.ptr;
+    p.partial = p.counter + 1;
+    unsigned grid = (unsigned)((T + 4 * kBatchThreads - 1) / (4 * kBatchThreads));
+    grid = grid > kMaxBlocks ? kMaxBlocks : grid;
+    hipLaunchKernelGGL(tide_batch_exit_kernel, dim3(grid), dim3(kBatchThreads), 0, (hipStream_t)stream, p);
+    TIDE_HIP(hipGetLastError());
+    return TIDE_OK;
+}
+
 int tide_set_variant(int variant) {
     if (variant != TIDE_VARIANT_AUTO && variant != TIDE_VARIANT_PREFILL && variant != TIDE_VARIANT_DECODE)
         return fail(TIDE_ERR_INVALID_ARG, "variant %d is not a tide_variant_t", variant);
@@ -492,7 +533,7 @@ int tide_release(void) {
     int rc = current_workspace(&ws);
     if (rc) return rc;
     TIDE_HIP(hipDeviceSynchronize());
-    for (Buffer* b : {&ws->counters, &ws->arrive, &ws->packed, &ws->part}) {
+    for (Buffer* b : {&ws->counters, &ws->arrive, &ws->packed, &ws->part, &ws->batch}) {
         if (b->ptr) TIDE_HIP(hipFree(b->ptr));
         b->ptr = nullptr;
         b->bytes = 0;

@@ -25,7 +25,7 @@ DTYPE_CODES = {"f32": F32, "f16": F16, "bf16": BF16}
 EXPORTS = (
     "tide_version", "tide_last_error", "tide_router_eval", "tide_select_exit",
     "tide_packed_router_bytes", "tide_router_pack", "tide_router_eval_packed",
-    "tide_select_exit_packed", "tide_exit_project", "tide_set_variant", "tide_set_prefill_form", "tide_release",
+    "tide_select_exit_packed", "tide_exit_project", "tide_batch_exit", "tide_set_variant", "tide_set_prefill_form", "tide_release",
 )
 
 _lib = None
@@ -58,10 +58,11 @@ def load_library() -> ctypes.CDLL:
     lib.tide_packed_router_bytes.restype = ctypes.c_size_t
     lib.tide_router_pack.argtypes = [ci, i64, i64, vp, vp, vp, vp]
     lib.tide_exit_project.argtypes = [vp, ci, i64, i64, i64, i64, i64, vp, i64, vp, vp, vp, f32, vp, i64, vp]
+    lib.tide_batch_exit.argtypes = [vp, i64, i64, vp, i32, i32, vp, vp, vp, vp]
     lib.tide_set_variant.argtypes = [ci]
     lib.tide_set_prefill_form.argtypes = [ci]
     for name in ("tide_router_eval", "tide_router_eval_packed", "tide_select_exit", "tide_select_exit_packed",
-                 "tide_router_pack", "tide_exit_project", "tide_set_variant", "tide_set_prefill_form", "tide_release"):
+                 "tide_router_pack", "tide_exit_project", "tide_batch_exit", "tide_set_variant", "tide_set_prefill_form", "tide_release"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -280,6 +281,22 @@ def exit_project(hidden, final_hidden, exit_layer, layer_ids, norm_gain, eps, *,
     _check(fn(*_c(fn.argtypes, vals)))
     del keep
     return out
+
+
+def batch_exit(fire_mask, C, layer_ids, min_layer, no_exit_layer):
+    """fire_mask int32/uint32 [T] (device) -> (batch_exit_layer i32[1], all_fire_mask i32[1], fire_counts i32[C])."""
+    if not fire_mask.is_cuda or fire_mask.dim() != 1 or not fire_mask.is_contiguous() or fire_mask.element_size() != 4:
+        raise ValueError("fire_mask must be a contiguous CUDA 32-bit integer tensor of shape [T]")
+    T = int(fire_mask.shape[0])
+    dev = fire_mask.device
+    layer = torch.zeros(1, dtype=torch.int32, device=dev)
+    allm = torch.zeros(1, dtype=torch.int32, device=dev)
+    counts = torch.zeros(int(C), dtype=torch.int32, device=dev)
+    idh, idp = _host(layer_ids, int(C), np.int32)
+    _check(load_library().tide_batch_exit(_ptr(fire_mask), T, int(C), idp, int(min_layer), int(no_exit_layer),
+                                          _ptr(layer), _ptr(allm), _ptr(counts), _stream()))
+    del idh
+    return layer, allm, counts
 
 
 class PreparedCall:

@@ -102,6 +102,17 @@ def test_exit_project_rejects_bad_arguments():
     assert call(T=0) == 0
 
 
+def test_batch_exit_rejects_bad_arguments():
+    lib = tr.load_library()
+    ids = np.asarray([3, 7], np.int32).ctypes.data_as(ctypes.c_void_p)
+    call = lambda fm=FAKE, T=4, C=2, idp=ids, outp=FAKE: lib.tide_batch_exit(fm, T, C, idp, 0, 8, outp, None, None, None)
+    assert call(fm=None) == -1 and call(outp=None) == -1 and call(idp=None) == -1
+    assert call(C=0) == -1 and call(C=33) == -1 and call(T=-1) == -1
+    bad = np.asarray([7, 3], np.int32)
+    assert call(idp=bad.ctypes.data_as(ctypes.c_void_p)) == -1
+    assert call(T=0, fm=None, outp=None) == 0
+
+
 def test_set_variant_validates():
     prev = tr.set_variant(tr.VARIANT_AUTO)
     assert prev in (0, 1, 2)

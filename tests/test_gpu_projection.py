@@ -110,3 +110,31 @@ def test_select_then_project_end_to_end(tr):
     assert same.mean() > 0.95
     got = out.view(torch.int16).cpu().numpy().view(np.uint16)
     ulp_compare("select_then_project", w.dtype, got, want, same)
+
+
+@pytest.mark.parametrize("T", [1, 7, 1000, 5000, 300000])
+def test_batch_exit_matches_the_oracle(tr, T):
+    """Alg. 1's whole-batch rule on random fire masks, incl. masks in which one checkpoint fires
+    for every token; integer outputs are bit-exact."""
+    import torch
+    C = 9
+    ids = synth.checkpoint_layers(36, 4)
+    rng = np.random.default_rng(T)
+    fire = (rng.random((C, T)) < 0.9).astype(np.uint8)
+    fire[5, :] = 1                                     # checkpoint 5 (layer 23) fires for all
+    fire[2, :] = 1
+    if T > 1:
+        fire[2, T // 2] = 0                            # ... checkpoint 2 for all but one token
+    mask = np.zeros(T, np.uint32)
+    for c in range(C):
+        mask |= fire[c].astype(np.uint32) << c
+    md = torch.from_numpy(mask.view(np.int32)).cuda()
+    for kmin in (0, 12, 24, 99):
+        print(f"[gpu-case] batch_exit T={T} k_min={kmin}", flush=True)
+        want, counts = oracle.batch_exit(fire, ids, kmin, 36)
+        layer, allm, cnt = tr.batch_exit(md, C, ids, kmin, 36)
+        torch.cuda.synchronize()
+        assert int(layer.item()) == want
+        assert cnt.cpu().numpy().tolist() == counts.tolist()
+        want_mask = sum(1 << c for c in range(C) if counts[c] == T)
+        assert int(allm.item()) & 0xFFFFFFFF == want_mask
