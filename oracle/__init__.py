@@ -7,6 +7,7 @@ from .tide_oracle import (  # noqa: F401
     DTYPE_CODES,
     batch_exit,
     build,
+    cosine_labels,
     exit_from_fire,
     exit_project,
     round_to_storage,

@@ -28,6 +28,8 @@
  *     0 < theta < 1; theta >= 1 never fires (the paper's "1.0 (off)" row of
  *     Table 4), theta <= 0 always fires.
  *   - exit is per token (Abstract, Fig. 1, Table 1), not per batch.
+ *   - calibration labels (Sec. 3.1 step 2, Eq. (1)): cosine similarity of a checkpoint's hidden
+ *     state with the last layer's, per token; label 1 iff it exceeds tau, strictly.
  *   - exit projection (Fig. 1 "LMHead(Norm(h_k))", Alg. 1 "LMHead(RMSNorm(H[k+1]))", Sec. 3.4
  *     kernels 3 and 4): the row handed to the LM head for token t is the model's final
  *     RMSNorm applied to the hidden state of the checkpoint the token exits at, written at
@@ -312,6 +314,39 @@ int tide_oracle_exit_from_fire(const uint8_t* fire /* [C,T] */, int64_t C, int64
                 exit_layer[t] = layer_ids[c];
                 break;
             }
+        }
+    }
+    return 0;
+}
+
+/* ---- exported: convergence labels of the calibration stage, Eq. (1) ---- */
+
+/* s_k = (h_k . h_L) / (|h_k| |h_L|) per token and checkpoint; label = 1[s_k > tau] (strict;
+ * tau = 0.98 in the paper).  hidden [C,T,d], final_hidden [T,d] (the last layer's states).
+ * A zero vector gives 0/0 = NaN and the label 0.                                             */
+int tide_oracle_cosine_labels(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d,
+                              int64_t ckpt_stride, int64_t row_stride, const void* final_hidden,
+                              int64_t final_row_stride, double tau, double* sim /* [C,T] */,
+                              uint8_t* label /* [C,T] */) {
+    if (C < 1 || T < 0 || d <= 0 || row_stride < d || final_row_stride < d) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        double nl = 0.0;
+        for (int64_t i = 0; i < d; ++i) {
+            double y = widen(final_hidden, dtype, t * final_row_stride + i);
+            nl += y * y;
+        }
+        for (int64_t c = 0; c < C; ++c) {
+            double dot = 0.0, nk = 0.0;
+            for (int64_t i = 0; i < d; ++i) {
+                double x = widen(hidden, dtype, c * ckpt_stride + t * row_stride + i);
+                double y = widen(final_hidden, dtype, t * final_row_stride + i);
+                dot += x * y;
+                nk += x * x;
+            }
+            double s = dot / (sqrt(nk) * sqrt(nl));
+            if (sim) sim[c * T + t] = s;
+            if (label) label[c * T + t] = (uint8_t)(s > tau);
         }
     }
     return 0;

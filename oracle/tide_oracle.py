@@ -46,6 +46,8 @@ def _load():
         lib.tide_oracle_select_exit.restype = ctypes.c_int
         lib.tide_oracle_exit_from_fire.argtypes = [vp, i64, i64, vp, i32, i32, vp]
         lib.tide_oracle_exit_from_fire.restype = ctypes.c_int
+        lib.tide_oracle_cosine_labels.argtypes = [vp, ctypes.c_int, i64, i64, i64, i64, i64, vp, i64, dbl, vp, vp]
+        lib.tide_oracle_cosine_labels.restype = ctypes.c_int
         lib.tide_oracle_batch_exit.argtypes = [vp, i64, i64, vp, i32, i32, vp, vp]
         lib.tide_oracle_batch_exit.restype = ctypes.c_int
         lib.tide_oracle_exit_project.argtypes = [vp, ctypes.c_int, i64, i64, i64, i64, i64, vp, i64, vp, vp, vp, dbl,
@@ -189,6 +191,21 @@ def select_exit(hidden, dtype, gamma, eps, W1, b1, w2, b2, theta, layer_ids, min
     if rc:
         raise ValueError(f"tide_oracle_select_exit rejected its arguments ({rc})")
     return exit_layer, logits, mask
+
+
+def cosine_labels(hidden, dtype, final_hidden, tau, d=None):
+    """Eq. (1): hidden [C,T,rs], final_hidden [T,rs2] storage bits -> (sim [C,T] f64, label [C,T] u8)."""
+    hidden = _storage(hidden, dtype)
+    final_hidden = _storage(final_hidden, dtype)
+    C, T, rs = hidden.shape
+    d = rs if d is None else int(d)
+    sim = np.empty((C, T), dtype=np.float64)
+    label = np.empty((C, T), dtype=np.uint8)
+    rc = _load().tide_oracle_cosine_labels(_p(hidden), DTYPE_CODES[dtype], C, T, d, T * rs, rs, _p(final_hidden),
+                                           int(final_hidden.shape[1]), float(np.float32(tau)), _p(sim), _p(label))
+    if rc:
+        raise ValueError("tide_oracle_cosine_labels rejected its arguments")
+    return sim, label
 
 
 def batch_exit(fire, layer_ids, min_layer, no_exit_layer):

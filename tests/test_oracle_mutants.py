@@ -35,6 +35,9 @@ MUTANTS = {
     "bf16_shift": [("(uint32_t)h << 16", "(uint32_t)h << 15")],
     "f16_bias": [("ex - 15)", "ex - 16)")],
     "f16_subnormal": [("ldexp((double)fr, -24)", "ldexp((double)fr, -25)")],
+    "cosine_not_normalised_by_final": [("double s = dot / (sqrt(nk) * sqrt(nl));", "double s = dot / (sqrt(nk) * sqrt(nk));")],
+    "cosine_label_not_strict": [("label[c * T + t] = (uint8_t)(s > tau);", "label[c * T + t] = (uint8_t)(s >= tau);")],
+    "cosine_dot_of_squares": [("dot += x * y;", "dot += x * x;")],
     "batch_exit_any_instead_of_all": [("n == T && T > 0", "n > 0 && T > 0")],
     "batch_exit_ignores_k_min": [("if (!decided && layer_ids[c] >= min_layer && n == T && T > 0)", "if (!decided && n == T && T > 0)")],
     "projection_takes_first_checkpoint": [("off = c * ckpt_stride + t * row_stride;\n                break;", "off = t * row_stride;\n                break;")],

@@ -482,3 +482,47 @@ def test_batch_exit_is_alg1_read_literally(golden_dir):
     assert got == int(g["n_layers"][0]) and counts.tolist() == [1, 2]
     assert oracle.batch_exit(np.ones((2, 5), np.uint8), [8, 16], 0, 32)[0] == 8
     assert oracle.batch_exit(np.ones((2, 5), np.uint8), [8, 16], 9, 32)[0] == 16
+
+
+# --------------------------------------------------------------------------- calibration labels (Eq. 1)
+
+def test_cosine_labels_closed_forms_and_library_routine():
+    d, T = 64, 6
+    rng = np.random.default_rng(11)
+    hL = rng.standard_normal((T, d)).astype(np.float32)
+    orth = rng.standard_normal((T, d)).astype(np.float32)
+    orth -= (np.sum(orth.astype(np.float64) * hL, axis=1, keepdims=True) / np.sum(hL.astype(np.float64) ** 2, axis=1, keepdims=True) * hL).astype(np.float32)
+    h = np.stack([hL, -hL, 4.0 * hL, orth, rng.standard_normal((T, d)).astype(np.float32)])
+    sim, lab = oracle.cosine_labels(h, "f32", hL, 0.98)
+    assert np.allclose(sim[0], 1.0, atol=1e-15) and np.allclose(sim[1], -1.0, atol=1e-15)
+    assert np.allclose(sim[2], 1.0, atol=1e-15)                                   # scale invariant
+    assert np.all(np.abs(sim[3]) < 1e-6)                                          # orthogonal (to fp32 rounding of the input)
+    x, y = h[4].astype(np.float64), hL.astype(np.float64)
+    want = np.einsum("td,td->t", x, y) / (np.linalg.norm(x, axis=1) * np.linalg.norm(y, axis=1))
+    assert np.allclose(sim[4], want, rtol=1e-13, atol=1e-15)
+    assert lab[0].all() and lab[2].all() and not lab[1].any() and not lab[3].any()
+    assert np.array_equal(lab[4], (want > float(np.float32(0.98))).astype(np.uint8))
+    # symmetric in its two arguments; strict threshold; zero vector -> label 0
+    sim_t, _ = oracle.cosine_labels(hL[None], "f32", h[4], 0.5)
+    assert np.allclose(sim_t[0], sim[4], rtol=1e-13)
+    two = np.array([[[3.0, 4.0]]], np.float32)
+    ref = np.array([[4.0, 3.0]], np.float32)                                      # cos = 24/25 = 0.96 exactly representable? no: use tau around it
+    s, l_lo = oracle.cosine_labels(two, "f32", ref, 0.95)
+    _, l_hi = oracle.cosine_labels(two, "f32", ref, 0.97)
+    assert abs(s[0, 0] - 0.96) < 1e-15 and l_lo[0, 0] == 1 and l_hi[0, 0] == 0
+    same = np.array([[[1.0, 0.0]]], np.float32)
+    assert oracle.cosine_labels(same, "f32", same[0], 1.0)[1][0, 0] == 0           # s = 1 is not > 1
+    z, lz = oracle.cosine_labels(np.zeros((1, 1, 4), np.float32), "f32", np.ones((1, 4), np.float32), 0.0)
+    assert np.isnan(z[0, 0]) and lz[0, 0] == 0
+
+
+def test_cosine_labels_follow_the_trajectory_generator():
+    """With h_c = h_final + sigma_c * noise the expected cosine is 1/sqrt(1 + sigma_c^2)-like and
+    rises with depth: a sanity check of the generator against Eq. (1), in all storage types."""
+    w = synth.config1(T=64)
+    w.d = 512
+    hb = synth.make_hidden(w.cfg, w.C, w.T, w.d, "bf16")
+    sim, lab = oracle.cosine_labels(hb, "bf16", hb[-1], 0.98)
+    means = sim.mean(axis=1)
+    assert np.all(np.diff(means) > 0) and means[-1] == 1.0
+    assert lab[-1].all() and not lab[0].any()
