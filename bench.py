@@ -187,6 +187,18 @@ def main() -> int:
                                  "algorithmic_bytes": pj_bytes, "gbs": round(pj_bytes / (ev_pj / args.steps) / 1e9, 1),
                                  "frac_of_hbm_peak": round(pj_bytes / (ev_pj / args.steps) / 1e9 / HBM_PEAK_GBS, 4)}
 
+    # ---- calibration labels (the step before the path: Eq. 1), same shapes
+    cos_out = (torch.empty((C, T), dtype=torch.float32, device="cuda"), torch.empty((C, T), dtype=torch.uint8, device="cuda"))
+
+    def cos_call(i):
+        tr.cosine_labels(batches[i % args.buffers], final_h, 0.98, out=cos_out)
+    n_cos = max(20, args.steps // 4)
+    wall_cs, ev_cs = timed(cos_call, n_cos, 5)
+    cs_bytes = (C + 1) * T * d * esz + 5 * C * T
+    result["calibration_labels"] = {"entry_point": "tide_cosine_labels", "us_per_call": round(ev_cs / n_cos * 1e6, 2),
+                                    "algorithmic_bytes": cs_bytes, "gbs": round(cs_bytes / (ev_cs / n_cos) / 1e9, 1),
+                                    "frac_of_hbm_peak": round(cs_bytes / (ev_cs / n_cos) / 1e9 / HBM_PEAK_GBS, 4)}
+
     # ---- decode latency (config 2): fp16, T = 1 and 8, raw weights, auto-selected decode variant
     if not args.no_decode:
         dec = {}

@@ -142,6 +142,15 @@ int tide_exit_project(const void* hidden, int dtype, int64_t C, int64_t T, int64
                       const float* norm_gain, float eps, void* out, int64_t out_row_stride,
                       void* stream);
 
+/* Calibration labels (Sec. 3.1 step 2, Eq. (1)): sim[c,t] = cos(hidden[c,t,:], final_hidden[t,:]),
+ * label[c,t] = (sim > tau), strictly; tau = 0.98 in the paper.  fp32 accumulation.
+ *   hidden device [C,T rows], final_hidden device [T rows] (the last layer's states), as above
+ *   sim    device [C,T] fp32 out or NULL;   label device [C,T] u8 out or NULL                 */
+int tide_cosine_labels(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d,
+                       int64_t ckpt_stride, int64_t row_stride, const void* final_hidden,
+                       int64_t final_row_stride, float tau, float* sim, uint8_t* label,
+                       void* stream);
+
 /* Whole-batch exit, Alg. 1 read literally: the first checkpoint, in ascending order and not below
  * min_layer, at which EVERY token of the batch fired; no_exit_layer if there is none.
  *   fire_mask        device [T] u32 (tide_select_exit's output: bit c = token fired at checkpoint c)

@@ -67,8 +67,9 @@ template <int DT, bool kGain> __device__ __forceinline__ u32x4 scale_round_chunk
     }
 }
 
-// kWavePerRow: 4 rows per workgroup (one per wave), else 1 row per workgroup.
-template <int DT, bool kWavePerRow, bool kGain>
+// kWavePerRow: 4 rows per workgroup (one per wave), else 1 row per workgroup.  kChunks = 16-byte
+// chunks of the row held per thread (the host picks the smallest of 4, 8, 16 that covers it).
+template <int DT, bool kWavePerRow, bool kGain, int kChunks>
 __global__ __launch_bounds__(kProjectThreads) void tide_project_kernel(const ProjectParams p) {
     __shared__ float part[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -89,21 +90,17 @@ __global__ __launch_bounds__(kProjectThreads) void tide_project_kernel(const Pro
 
     // Every thread's share of the row sits in registers between the read and the write.  Chunk
     // indices past the row's end are clamped for the load (in bounds, branch-free) and zeroed.
-    u32x4 v[kProjectMaxChunks];
+    u32x4 v[kChunks];
     float ss = 0.0f;
     if (src) {
 #pragma unroll
-        for (int j = 0; j < kProjectMaxChunks; ++j) {
+        for (int j = 0; j < kChunks; ++j) {
             const int q = first + j * stride;
-            if (j * stride < nchunk) {             // uniform across the row's threads
-                const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src) + min(q, nchunk - 1));
-                v[j] = q < nchunk ? x : u32x4{0, 0, 0, 0};
-            } else {
-                v[j] = u32x4{0, 0, 0, 0};
-            }
+            const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src) + min(q, nchunk - 1));
+            v[j] = q < nchunk ? x : u32x4{0, 0, 0, 0};
         }
 #pragma unroll
-        for (int j = 0; j < kProjectMaxChunks; ++j) ss = chunk_sumsq<DT>(v[j], ss);
+        for (int j = 0; j < kChunks; ++j) ss = chunk_sumsq<DT>(v[j], ss);
     }
     ss = xor_reduce_sum<6>(ss);
     if (!kWavePerRow) {
@@ -115,7 +112,7 @@ __global__ __launch_bounds__(kProjectThreads) void tide_project_kernel(const Pro
     const float r = inv_rms_f32(ss, 1.0f / (float)p.d, p.eps);
     char* dst = p.out + (int64_t)t * p.out_row_stride_bytes;
 #pragma unroll
-    for (int j = 0; j < kProjectMaxChunks; ++j) {
+    for (int j = 0; j < kChunks; ++j) {
         const int q = first + j * stride;
         if (q < nchunk) {
             const u32x4 o = scale_round_chunk<DT, kGain>(v[j], r, kGain ? p.gain + q * Storage<DT>::kElems : nullptr);

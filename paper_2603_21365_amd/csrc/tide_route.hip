@@ -13,6 +13,7 @@
 #include <mutex>
 
 #include "batch_kernel.hpp"
+#include "cosine_kernel.hpp"
 #include "decode_kernel.hpp"
 #include "pack_kernel.hpp"
 #include "prefill_dma_kernel.hpp"
@@ -453,16 +454,75 @@ int tide_exit_project(const void* hidden, int dtype, int64_t C, int64_t T, int64
         return fail(TIDE_ERR_UNSUPPORTED, "rows of %lld bytes exceed the projection kernel's limit", (long long)row_bytes);
     hipStream_t st = (hipStream_t)stream;
     const unsigned grid = wave_per_row ? (unsigned)((T + 3) / 4) : (unsigned)T;
+    const int64_t per_thread = (row_bytes / 16 + (wave_per_row ? kWave : kProjectThreads) - 1) / (wave_per_row ? kWave : kProjectThreads);
     by_dtype(dtype, [&](auto dt) {
         constexpr int DT = decltype(dt)::value;
-        if (wave_per_row && norm_gain)
-            hipLaunchKernelGGL((tide_project_kernel<DT, true, true>), dim3(grid), dim3(kProjectThreads), 0, st, p);
-        else if (wave_per_row)
-            hipLaunchKernelGGL((tide_project_kernel<DT, true, false>), dim3(grid), dim3(kProjectThreads), 0, st, p);
-        else if (norm_gain)
-            hipLaunchKernelGGL((tide_project_kernel<DT, false, true>), dim3(grid), dim3(kProjectThreads), 0, st, p);
-        else
-            hipLaunchKernelGGL((tide_project_kernel<DT, false, false>), dim3(grid), dim3(kProjectThreads), 0, st, p);
+        auto go = [&](auto wpr, auto gain, auto chunks) {
+            hipLaunchKernelGGL((tide_project_kernel<DT, decltype(wpr)::value, decltype(gain)::value, decltype(chunks)::value>),
+                               dim3(grid), dim3(kProjectThreads), 0, st, p);
+        };
+        auto pick_chunks = [&](auto wpr, auto gain) {
+            if (per_thread <= 4) go(wpr, gain, std::integral_constant<int, 4>{});
+            else if (per_thread <= 8) go(wpr, gain, std::integral_constant<int, 8>{});
+            else go(wpr, gain, std::integral_constant<int, 16>{});
+        };
+        auto pick_gain = [&](auto wpr) {
+            if (norm_gain) pick_chunks(wpr, std::true_type{});
+            else pick_chunks(wpr, std::false_type{});
+        };
+        if (wave_per_row) pick_gain(std::true_type{});
+        else pick_gain(std::false_type{});
+        return 0;
+    });
+    TIDE_HIP(hipGetLastError());
+    return TIDE_OK;
+}
+
+int tide_cosine_labels(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t ckpt_stride,
+                       int64_t row_stride, const void* final_hidden, int64_t final_row_stride, float tau, float* sim,
+                       uint8_t* label, void* stream) {
+    g_err[0] = 0;
+    int rc = check_common(hidden, dtype, C, T, d, ckpt_stride, row_stride, hidden, reinterpret_cast<const float*>(hidden), 0.0f);
+    if (rc) return rc;
+    if (T == 0) return TIDE_OK;
+    if (!final_hidden) return fail(TIDE_ERR_INVALID_ARG, "final_hidden must not be NULL");
+    if (final_row_stride < d) return fail(TIDE_ERR_INVALID_ARG, "final_row_stride %lld < d", (long long)final_row_stride);
+    const size_t eb = elem_bytes(dtype);
+    if (((uintptr_t)final_hidden & 15) || ((size_t)final_row_stride * eb & 15))
+        return fail(TIDE_ERR_ALIGNMENT, "final_hidden base and stride must be multiples of 16 bytes");
+    const int64_t row_bytes = d * (int64_t)eb;
+    if (row_bytes > (int64_t)kCosineMaxChunks * 16 * kCosineThreads)
+        return fail(TIDE_ERR_UNSUPPORTED, "rows of %lld bytes exceed the labeler's limit", (long long)row_bytes);
+    CosineParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.hidden = (const char*)hidden;
+    p.ckpt_stride_bytes = ckpt_stride * (int64_t)eb;
+    p.row_stride_bytes = row_stride * (int64_t)eb;
+    p.final_hidden = (const char*)final_hidden;
+    p.final_row_stride_bytes = final_row_stride * (int64_t)eb;
+    p.C = (int)C;
+    p.T = (int)T;
+    p.d = (int)d;
+    p.tau = tau;
+    p.sim = sim;
+    p.label = label;
+    const bool wave_per_row = row_bytes <= (int64_t)kCosineMaxChunks * 16 * kWave;
+    const unsigned grid = wave_per_row ? (unsigned)((T + 3) / 4) : (unsigned)T;
+    const int64_t per_thread = (row_bytes / 16 + (wave_per_row ? kWave : kCosineThreads) - 1) / (wave_per_row ? kWave : kCosineThreads);
+    hipStream_t st = (hipStream_t)stream;
+    by_dtype(dtype, [&](auto dt) {
+        constexpr int DT = decltype(dt)::value;
+        auto go = [&](auto wpr, auto chunks) {
+            hipLaunchKernelGGL((tide_cosine_kernel<DT, decltype(wpr)::value, decltype(chunks)::value>), dim3(grid),
+                               dim3(kCosineThreads), 0, st, p);
+        };
+        auto pick = [&](auto wpr) {
+            if (per_thread <= 4) go(wpr, std::integral_constant<int, 4>{});
+            else if (per_thread <= 8) go(wpr, std::integral_constant<int, 8>{});
+            else go(wpr, std::integral_constant<int, 16>{});
+        };
+        if (wave_per_row) pick(std::true_type{});
+        else pick(std::false_type{});
         return 0;
     });
     TIDE_HIP(hipGetLastError());

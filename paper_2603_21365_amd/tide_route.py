@@ -25,7 +25,7 @@ DTYPE_CODES = {"f32": F32, "f16": F16, "bf16": BF16}
 EXPORTS = (
     "tide_version", "tide_last_error", "tide_router_eval", "tide_select_exit",
     "tide_packed_router_bytes", "tide_router_pack", "tide_router_eval_packed",
-    "tide_select_exit_packed", "tide_exit_project", "tide_batch_exit", "tide_set_variant", "tide_set_prefill_form", "tide_release",
+    "tide_select_exit_packed", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_set_variant", "tide_set_prefill_form", "tide_release",
 )
 
 _lib = None
@@ -58,11 +58,12 @@ def load_library() -> ctypes.CDLL:
     lib.tide_packed_router_bytes.restype = ctypes.c_size_t
     lib.tide_router_pack.argtypes = [ci, i64, i64, vp, vp, vp, vp]
     lib.tide_exit_project.argtypes = [vp, ci, i64, i64, i64, i64, i64, vp, i64, vp, vp, vp, f32, vp, i64, vp]
+    lib.tide_cosine_labels.argtypes = [vp, ci, i64, i64, i64, i64, i64, vp, i64, f32, vp, vp, vp]
     lib.tide_batch_exit.argtypes = [vp, i64, i64, vp, i32, i32, vp, vp, vp, vp]
     lib.tide_set_variant.argtypes = [ci]
     lib.tide_set_prefill_form.argtypes = [ci]
     for name in ("tide_router_eval", "tide_router_eval_packed", "tide_select_exit", "tide_select_exit_packed",
-                 "tide_router_pack", "tide_exit_project", "tide_batch_exit", "tide_set_variant", "tide_set_prefill_form", "tide_release"):
+                 "tide_router_pack", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_set_variant", "tide_set_prefill_form", "tide_release"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -281,6 +282,25 @@ def exit_project(hidden, final_hidden, exit_layer, layer_ids, norm_gain, eps, *,
     _check(fn(*_c(fn.argtypes, vals)))
     del keep
     return out
+
+
+def cosine_labels(hidden, final_hidden, tau, *, d=None, out=None):
+    """hidden [C,T,>=d], final_hidden [T,>=d] -> (sim f32 [C,T], label u8 [C,T]) per Eq. (1)."""
+    (C, T, width), (cs, rs, _) = _rows(hidden, 3)
+    d = width if d is None else int(d)
+    (Tf, wf), (frs, _) = _rows(final_hidden, 2)
+    if Tf != T or wf < d or width < d or final_hidden.dtype != hidden.dtype:
+        raise ValueError("final_hidden must be [T, >=d] of hidden's dtype")
+    if out is None:
+        sim = torch.empty((C, T), dtype=torch.float32, device=hidden.device)
+        label = torch.empty((C, T), dtype=torch.uint8, device=hidden.device)
+    else:
+        sim, label = out
+    cs = cs if (C > 1 and T > 0) else max(cs, 0)
+    _check(load_library().tide_cosine_labels(_ptr(hidden), _dtype_code(hidden), C, T, d, cs, rs if T > 1 else max(rs, d),
+                                             _ptr(final_hidden), frs if T > 1 else max(frs, d), float(tau), _ptr(sim),
+                                             _ptr(label), _stream()))
+    return sim, label
 
 
 def batch_exit(fire_mask, C, layer_ids, min_layer, no_exit_layer):

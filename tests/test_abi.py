@@ -102,6 +102,14 @@ def test_exit_project_rejects_bad_arguments():
     assert call(T=0) == 0
 
 
+def test_cosine_labels_rejects_bad_arguments():
+    lib = tr.load_library()
+    call = lambda T=4, d=256, fin=FAKE, frs=256, dtype=2: lib.tide_cosine_labels(FAKE, dtype, 2, T, d, 1024, 256, fin, frs, 0.98,
+                                                                                  None, None, None)
+    assert call(fin=None) == -1 and call(frs=128) == -1 and call(dtype=9) == -1
+    assert call(fin=FAKE + 8) == -3 and call(d=100, frs=100) == -2 and call(T=0) == 0
+
+
 def test_batch_exit_rejects_bad_arguments():
     lib = tr.load_library()
     ids = np.asarray([3, 7], np.int32).ctypes.data_as(ctypes.c_void_p)

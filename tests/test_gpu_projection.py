@@ -138,3 +138,27 @@ def test_batch_exit_matches_the_oracle(tr, T):
         assert cnt.cpu().numpy().tolist() == counts.tolist()
         want_mask = sum(1 << c for c in range(C) if counts[c] == T)
         assert int(allm.item()) & 0xFFFFFFFF == want_mask
+
+
+@pytest.mark.parametrize("dtype,d,T,C", [("bf16", 4096, 300, 8), ("f16", 768, 65, 3), ("f32", 2048, 17, 2), ("f32", 8192, 5, 2),
+                                          ("bf16", 16384, 3, 2)])
+def test_cosine_labels_match_the_oracle(tr, dtype, d, T, C):
+    """Eq. (1) on the trajectory generator (similarities rise towards 1 with depth, so labels of
+    both kinds occur).  Similarities within 2e-5 (fp32 accumulation of d terms); labels exact
+    except where the oracle's similarity lies within that of tau, which are counted."""
+    import torch
+    w = synth.Workload(f"cos_{dtype}_d{d}", 51, dtype, d, 4 * C, 4, T, 0.3)
+    hb = w.hidden()
+    fin = np.ascontiguousarray(hb[-1])
+    tau = 0.98
+    sim_o, lab_o = oracle.cosine_labels(hb, dtype, fin, tau)
+    print(f"[gpu-case] cosine {w.name} T={T} C={C}", flush=True)
+    sim, lab = tr.cosine_labels(to_device(hb, dtype), to_device(fin, dtype), tau)
+    torch.cuda.synchronize()
+    sim, lab = sim.cpu().numpy(), lab.cpu().numpy()
+    err = np.abs(sim - sim_o).max()
+    near = np.abs(sim_o - float(np.float32(tau))) <= 2e-5
+    print(f"PARITY name={w.name} rows={C * T} max_abs_err={err:.3e} near_tau={int(near.sum())} positives={int(lab_o.sum())}", flush=True)
+    assert err <= 2e-5
+    assert np.array_equal(lab[~near], lab_o[~near])
+    assert lab_o.any() and not lab_o.all()
