@@ -5,6 +5,7 @@ this package; the product library neither imports nor links it.
 """
 from .tide_oracle import (  # noqa: F401
     DTYPE_CODES,
+    batch_compact,
     batch_exit,
     build,
     cosine_labels,

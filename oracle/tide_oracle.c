@@ -28,6 +28,8 @@
  *     0 < theta < 1; theta >= 1 never fires (the paper's "1.0 (off)" row of
  *     Table 4), theta <= 0 always fires.
  *   - exit is per token (Abstract, Fig. 1, Table 1), not per batch.
+ *   - batch compaction (Sec. 3.4 kernel 2): at a checkpoint layer k the tokens split into those
+ *     whose exit layer is <= k and those that continue; both lists keep the token order.
  *   - calibration labels (Sec. 3.1 step 2, Eq. (1)): cosine similarity of a checkpoint's hidden
  *     state with the last layer's, per token; label 1 iff it exceeds tau, strictly.
  *   - exit projection (Fig. 1 "LMHead(Norm(h_k))", Alg. 1 "LMHead(RMSNorm(H[k+1]))", Sec. 3.4
@@ -316,6 +318,25 @@ int tide_oracle_exit_from_fire(const uint8_t* fire /* [C,T] */, int64_t C, int64
             }
         }
     }
+    return 0;
+}
+
+/* ---- exported: batch compaction (Sec. 3.4 kernel 2) ---- */
+
+/* Separates the tokens that have exited at or before `layer` (exit_layer[t] <= layer) from those
+ * that continue, as two index lists in ascending token order.  counts[0] = exited, counts[1] =
+ * continuing.  exit_idx and cont_idx have room for T entries each; entries past the counts are
+ * left untouched.                                                                             */
+int tide_oracle_batch_compact(const int32_t* exit_layer, int64_t T, int32_t layer, int32_t* exit_idx,
+                              int32_t* cont_idx, int32_t* counts) {
+    if (T < 0) return -1;
+    int32_t ne = 0, nc = 0;
+    for (int64_t t = 0; t < T; ++t) {
+        if (exit_layer[t] <= layer) exit_idx[ne++] = (int32_t)t;
+        else cont_idx[nc++] = (int32_t)t;
+    }
+    counts[0] = ne;
+    counts[1] = nc;
     return 0;
 }
 

@@ -46,6 +46,8 @@ def _load():
         lib.tide_oracle_select_exit.restype = ctypes.c_int
         lib.tide_oracle_exit_from_fire.argtypes = [vp, i64, i64, vp, i32, i32, vp]
         lib.tide_oracle_exit_from_fire.restype = ctypes.c_int
+        lib.tide_oracle_batch_compact.argtypes = [vp, i64, i32, vp, vp, vp]
+        lib.tide_oracle_batch_compact.restype = ctypes.c_int
         lib.tide_oracle_cosine_labels.argtypes = [vp, ctypes.c_int, i64, i64, i64, i64, i64, vp, i64, dbl, vp, vp]
         lib.tide_oracle_cosine_labels.restype = ctypes.c_int
         lib.tide_oracle_batch_exit.argtypes = [vp, i64, i64, vp, i32, i32, vp, vp]
@@ -191,6 +193,19 @@ def select_exit(hidden, dtype, gamma, eps, W1, b1, w2, b2, theta, layer_ids, min
     if rc:
         raise ValueError(f"tide_oracle_select_exit rejected its arguments ({rc})")
     return exit_layer, logits, mask
+
+
+def batch_compact(exit_layer, layer):
+    """Sec. 3.4 kernel 2: (exit_idx, cont_idx) -- tokens with exit_layer <= layer, and the rest, in order."""
+    exit_layer = np.ascontiguousarray(exit_layer, dtype=np.int32)
+    T = exit_layer.shape[0]
+    e = np.full(T, -1, np.int32)
+    c = np.full(T, -1, np.int32)
+    n = np.zeros(2, np.int32)
+    rc = _load().tide_oracle_batch_compact(_p(exit_layer), T, int(layer), _p(e), _p(c), _p(n))
+    if rc:
+        raise ValueError("tide_oracle_batch_compact rejected its arguments")
+    return e[:n[0]].copy(), c[:n[1]].copy()
 
 
 def cosine_labels(hidden, dtype, final_hidden, tau, d=None):

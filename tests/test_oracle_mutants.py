@@ -35,6 +35,7 @@ MUTANTS = {
     "bf16_shift": [("(uint32_t)h << 16", "(uint32_t)h << 15")],
     "f16_bias": [("ex - 15)", "ex - 16)")],
     "f16_subnormal": [("ldexp((double)fr, -24)", "ldexp((double)fr, -25)")],
+    "compact_strict_comparison": [("if (exit_layer[t] <= layer) exit_idx[ne++] = (int32_t)t;", "if (exit_layer[t] < layer) exit_idx[ne++] = (int32_t)t;")],
     "cosine_not_normalised_by_final": [("double s = dot / (sqrt(nk) * sqrt(nl));", "double s = dot / (sqrt(nk) * sqrt(nk));")],
     "cosine_label_not_strict": [("label[c * T + t] = (uint8_t)(s > tau);", "label[c * T + t] = (uint8_t)(s >= tau);")],
     "cosine_dot_of_squares": [("dot += x * y;", "dot += x * x;")],

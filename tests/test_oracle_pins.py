@@ -526,3 +526,18 @@ def test_cosine_labels_follow_the_trajectory_generator():
     means = sim.mean(axis=1)
     assert np.all(np.diff(means) > 0) and means[-1] == 1.0
     assert lab[-1].all() and not lab[0].any()
+
+
+# --------------------------------------------------------------------------- batch compaction (Sec. 3.4 kernel 2)
+
+def test_batch_compact_is_a_stable_partition():
+    rng = np.random.default_rng(21)
+    for T in (0, 1, 5, 64, 1000):
+        ex = rng.choice([3, 7, 11, 15, 16], size=T).astype(np.int32)
+        for layer in (2, 3, 7, 11, 15, 16, 100):
+            e, c = oracle.batch_compact(ex, layer)
+            assert e.tolist() == [t for t in range(T) if ex[t] <= layer]          # Python's own filter
+            assert c.tolist() == [t for t in range(T) if ex[t] > layer]
+            assert len(e) + len(c) == T and set(e) | set(c) == set(range(T))
+    # Fig. 3's example: after the router at layer 8 one token has left, after layer 16 two
+    assert [len(oracle.batch_compact(np.array([8, 16, 32], np.int32), k)[0]) for k in (8, 16, 31, 32)] == [1, 2, 2, 3]
