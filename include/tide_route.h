@@ -142,6 +142,15 @@ int tide_exit_project(const void* hidden, int dtype, int64_t C, int64_t T, int64
                       const float* norm_gain, float eps, void* out, int64_t out_row_stride,
                       void* stream);
 
+/* Batch compaction (Sec. 3.4 kernel 2): the tokens that have exited at or before `layer`
+ * (exit_layer[t] <= layer) and those that continue, as two index lists in ascending token order --
+ * what a layer-skipping runtime needs to gather the continuing tokens after a checkpoint.
+ *   exit_layer device [T] int32;  exit_idx, cont_idx device [T] int32 out (entries past the
+ *   counts are left untouched);  counts device [2] int32 out: {exited, continuing}, also for T == 0.
+ * Uses the library workspace.                                                                */
+int tide_batch_compact(const int32_t* exit_layer, int64_t T, int32_t layer, int32_t* exit_idx,
+                       int32_t* cont_idx, int32_t* counts, void* stream);
+
 /* Calibration labels (Sec. 3.1 step 2, Eq. (1)): sim[c,t] = cos(hidden[c,t,:], final_hidden[t,:]),
  * label[c,t] = (sim > tau), strictly; tau = 0.98 in the paper.  fp32 accumulation.
  *   hidden device [C,T rows], final_hidden device [T rows] (the last layer's states), as above

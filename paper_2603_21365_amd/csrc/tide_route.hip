@@ -13,6 +13,7 @@
 #include <mutex>
 
 #include "batch_kernel.hpp"
+#include "compact_kernel.hpp"
 #include "cosine_kernel.hpp"
 #include "decode_kernel.hpp"
 #include "pack_kernel.hpp"
@@ -51,7 +52,7 @@ struct Buffer {
 };
 
 struct Workspace {
-    Buffer counters, arrive, packed, part, batch;
+    Buffer counters, arrive, packed, part, batch, compact;
 };
 
 std::mutex g_mu;
@@ -478,6 +479,40 @@ int tide_exit_project(const void* hidden, int dtype, int64_t C, int64_t T, int64
     return TIDE_OK;
 }
 
+int tide_batch_compact(const int32_t* exit_layer, int64_t T, int32_t layer, int32_t* exit_idx, int32_t* cont_idx,
+                       int32_t* counts, void* stream) {
+    g_err[0] = 0;
+    if (T < 0 || T > (int64_t)1 << 30) return fail(TIDE_ERR_INVALID_ARG, "T = %lld outside [0, 2^30]", (long long)T);
+    if (!counts) return fail(TIDE_ERR_INVALID_ARG, "counts must not be NULL");
+    if (T > 0 && (!exit_layer || !exit_idx || !cont_idx))
+        return fail(TIDE_ERR_INVALID_ARG, "exit_layer, exit_idx and cont_idx must not be NULL");
+    hipStream_t st = (hipStream_t)stream;
+    std::lock_guard<std::mutex> lock(g_mu);
+    Workspace* ws = nullptr;
+    int rc = current_workspace(&ws);
+    if (rc) return rc;
+    constexpr int kMaxBlocks = 1024;
+    rc = reserve(ws->compact, kMaxBlocks * sizeof(uint32_t), true);
+    if (rc) return rc;
+    CompactParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.exit_layer = exit_layer;
+    p.T = (int)T;
+    p.layer = layer;
+    p.exit_idx = exit_idx;
+    p.cont_idx = cont_idx;
+    p.counts = counts;
+    p.block_counts = (uint32_t*)ws->compact.ptr;
+    int64_t slice = 16 * kCompactThreads;                               // 4096 tokens per workgroup ...
+    while ((T + slice - 1) / slice > kMaxBlocks) slice *= 2;            // ... more for very large batches
+    p.slice = (int)slice;
+    const unsigned grid = T > 0 ? (unsigned)((T + slice - 1) / slice) : 1u;   // T == 0 still writes counts = {0, 0}
+    if (grid > 1) hipLaunchKernelGGL(tide_compact_count_kernel, dim3(grid), dim3(kCompactThreads), 0, st, p);
+    hipLaunchKernelGGL(tide_compact_scatter_kernel, dim3(grid), dim3(kCompactThreads), 0, st, p);
+    TIDE_HIP(hipGetLastError());
+    return TIDE_OK;
+}
+
 int tide_cosine_labels(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t ckpt_stride,
                        int64_t row_stride, const void* final_hidden, int64_t final_row_stride, float tau, float* sim,
                        uint8_t* label, void* stream) {
@@ -593,7 +628,7 @@ int tide_release(void) {
     int rc = current_workspace(&ws);
     if (rc) return rc;
     TIDE_HIP(hipDeviceSynchronize());
-    for (Buffer* b : {&ws->counters, &ws->arrive, &ws->packed, &ws->part, &ws->batch}) {
+    for (Buffer* b : {&ws->counters, &ws->arrive, &ws->packed, &ws->part, &ws->batch, &ws->compact}) {
         if (b->ptr) TIDE_HIP(hipFree(b->ptr));
         b->ptr = nullptr;
         b->bytes = 0;

@@ -25,7 +25,7 @@ DTYPE_CODES = {"f32": F32, "f16": F16, "bf16": BF16}
 EXPORTS = (
     "tide_version", "tide_last_error", "tide_router_eval", "tide_select_exit",
     "tide_packed_router_bytes", "tide_router_pack", "tide_router_eval_packed",
-    "tide_select_exit_packed", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_set_variant", "tide_set_prefill_form", "tide_release",
+    "tide_select_exit_packed", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_batch_compact", "tide_set_variant", "tide_set_prefill_form", "tide_release",
 )
 
 _lib = None
@@ -58,12 +58,13 @@ def load_library() -> ctypes.CDLL:
     lib.tide_packed_router_bytes.restype = ctypes.c_size_t
     lib.tide_router_pack.argtypes = [ci, i64, i64, vp, vp, vp, vp]
     lib.tide_exit_project.argtypes = [vp, ci, i64, i64, i64, i64, i64, vp, i64, vp, vp, vp, f32, vp, i64, vp]
+    lib.tide_batch_compact.argtypes = [vp, i64, i32, vp, vp, vp, vp]
     lib.tide_cosine_labels.argtypes = [vp, ci, i64, i64, i64, i64, i64, vp, i64, f32, vp, vp, vp]
     lib.tide_batch_exit.argtypes = [vp, i64, i64, vp, i32, i32, vp, vp, vp, vp]
     lib.tide_set_variant.argtypes = [ci]
     lib.tide_set_prefill_form.argtypes = [ci]
     for name in ("tide_router_eval", "tide_router_eval_packed", "tide_select_exit", "tide_select_exit_packed",
-                 "tide_router_pack", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_set_variant", "tide_set_prefill_form", "tide_release"):
+                 "tide_router_pack", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_batch_compact", "tide_set_variant", "tide_set_prefill_form", "tide_release"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -282,6 +283,21 @@ def exit_project(hidden, final_hidden, exit_layer, layer_ids, norm_gain, eps, *,
     _check(fn(*_c(fn.argtypes, vals)))
     del keep
     return out
+
+
+def batch_compact(exit_layer, layer):
+    """exit_layer int32 [T] (device) -> (exit_idx i32[T], cont_idx i32[T], counts i32[2]); the lists are
+    valid up to counts[0] / counts[1] entries."""
+    if exit_layer.dtype != torch.int32 or not exit_layer.is_cuda or exit_layer.dim() != 1 or not exit_layer.is_contiguous():
+        raise ValueError("exit_layer must be a contiguous CUDA int32 tensor of shape [T]")
+    T = int(exit_layer.shape[0])
+    dev = exit_layer.device
+    e = torch.full((T,), -1, dtype=torch.int32, device=dev)
+    c = torch.full((T,), -1, dtype=torch.int32, device=dev)
+    n = torch.zeros(2, dtype=torch.int32, device=dev)
+    _check(load_library().tide_batch_compact(_ptr(exit_layer) if T else None, T, int(layer), _ptr(e) if T else None,
+                                             _ptr(c) if T else None, _ptr(n), _stream()))
+    return e, c, n
 
 
 def cosine_labels(hidden, final_hidden, tau, *, d=None, out=None):

@@ -110,6 +110,12 @@ def test_cosine_labels_rejects_bad_arguments():
     assert call(fin=FAKE + 8) == -3 and call(d=100, frs=100) == -2 and call(T=0) == 0
 
 
+def test_batch_compact_rejects_bad_arguments():
+    lib = tr.load_library()
+    call = lambda ex=FAKE, T=4, e=FAKE, c=FAKE, n=FAKE: lib.tide_batch_compact(ex, T, 7, e, c, n, None)
+    assert call(n=None) == -1 and call(ex=None) == -1 and call(e=None) == -1 and call(c=None) == -1 and call(T=-2) == -1
+
+
 def test_batch_exit_rejects_bad_arguments():
     lib = tr.load_library()
     ids = np.asarray([3, 7], np.int32).ctypes.data_as(ctypes.c_void_p)

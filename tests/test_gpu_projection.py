@@ -162,3 +162,21 @@ def test_cosine_labels_match_the_oracle(tr, dtype, d, T, C):
     assert err <= 2e-5
     assert np.array_equal(lab[~near], lab_o[~near])
     assert lab_o.any() and not lab_o.all()
+
+
+@pytest.mark.parametrize("T", [0, 1, 63, 64, 65, 255, 257, 4096, 4097, 20000, 5000000])
+def test_batch_compact_matches_the_oracle(tr, T):
+    """Index lists and counts are integers: bit-exact, including the order."""
+    import torch
+    rng = np.random.default_rng(T + 1)
+    ex = rng.choice(np.array([3, 7, 11, 15, 16], np.int32), size=T, p=[0.3, 0.2, 0.1, 0.1, 0.3]).astype(np.int32)
+    exd = torch.from_numpy(ex).cuda()
+    for layer in (2, 7, 16):
+        print(f"[gpu-case] batch_compact T={T} layer={layer}", flush=True)
+        e_o, c_o = oracle.batch_compact(ex, layer)
+        e, c, n = tr.batch_compact(exd, layer)
+        torch.cuda.synchronize()
+        n = n.cpu().numpy()
+        assert n.tolist() == [len(e_o), len(c_o)]
+        assert np.array_equal(e.cpu().numpy()[:n[0]], e_o) and np.array_equal(c.cpu().numpy()[:n[1]], c_o)
+        assert np.all(e.cpu().numpy()[n[0]:] == -1) and np.all(c.cpu().numpy()[n[1]:] == -1)
