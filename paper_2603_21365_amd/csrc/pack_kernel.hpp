@@ -13,48 +13,53 @@
 
 namespace tide {
 
-// One thread per output chunk; grid.y = checkpoint.
+// One workgroup per 16-k group: the group's 16 x 128 weights are one contiguous 8 KiB of W1,
+// read with coalesced 16-byte loads, scaled by gamma and transposed through LDS so that every
+// thread then assembles one output chunk (two for fp32: hi and mid plane).  grid = (d/16, C).
+constexpr int kPackThreads = 256;
+
 template <int DT>
-__global__ __launch_bounds__(256) void tide_pack_kernel(const float* __restrict__ gamma, const float* __restrict__ W1,
-                                                        u32x4* __restrict__ packed, int d, int chunks_per_ckpt) {
-    const int c = blockIdx.y;
-    const int q = blockIdx.x * blockDim.x + threadIdx.x;
-    if (q >= chunks_per_ckpt) return;
-    const int plane_chunks = d * 16;
-    const int plane = q >= plane_chunks ? 1 : 0;             // only fp32 has a second plane
-    const int qq = q - plane * plane_chunks;
-    const int lane = qq & 63, nb = (qq >> 6) & 3, G = qq >> 8;
-    const int h = lane >> 5, j = lane & 31;
-    const int k0 = 16 * G + 8 * h;
-    const int col = 32 * nb + j;
-    const float* w = W1 + (size_t)c * d * kBottleneck;
-    const float* g = gamma ? gamma + (size_t)c * d : nullptr;
+__global__ __launch_bounds__(kPackThreads) void tide_pack_kernel(const float* __restrict__ gamma, const float* __restrict__ W1,
+                                                                 u32x4* __restrict__ packed, int d, int chunks_per_ckpt) {
+    __shared__ float tile[16][kBottleneck + 4];            // +4: rows land on different banks
+    const int c = blockIdx.y, G = blockIdx.x, tid = threadIdx.x;
+    const float* w = W1 + ((size_t)c * d + 16 * G) * kBottleneck;
+    const float* g = gamma ? gamma + (size_t)c * d + 16 * G : nullptr;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int q = tid + i * kPackThreads;              // float4 index within the 16 x 128 tile
+        const int k = q >> 5, col4 = (q & 31) * 4;
+        f32x4 v = reinterpret_cast<const f32x4*>(w)[q];
+        const float gk = g ? g[k] : 1.0f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) tile[k][col4 + e] = v[e] * gk;
+    }
+    __syncthreads();
+    const int lane = tid & 63, nb = tid >> 6;
+    const int h = lane >> 5, col = 32 * nb + (lane & 31);
     float v[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const int k = k0 + e;
-        v[e] = w[(size_t)k * kBottleneck + col] * (g ? g[k] : 1.0f);
-    }
-    u32x4 out;
+    for (int e = 0; e < 8; ++e) v[e] = tile[8 * h + e][col];
+    u32x4* out = packed + (size_t)c * chunks_per_ckpt + (size_t)G * 256 + tid;
     if constexpr (DT == kF16) {
         f16x8 o;
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = static_cast<_Float16>(v[e]);
-        out = __builtin_bit_cast(u32x4, o);
+        *out = __builtin_bit_cast(u32x4, o);
     } else if constexpr (DT == kBF16) {
         bf16x8 o;
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = static_cast<__bf16>(v[e]);
-        out = __builtin_bit_cast(u32x4, o);
+        *out = __builtin_bit_cast(u32x4, o);
     } else {
         __bf16 hi[8], mid[8];
         split_bf16(v, 8, hi, mid);
-        bf16x8 o;
+        bf16x8 oh, om;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = plane ? mid[e] : hi[e];
-        out = __builtin_bit_cast(u32x4, o);
+        for (int e = 0; e < 8; ++e) { oh[e] = hi[e]; om[e] = mid[e]; }
+        out[0] = __builtin_bit_cast(u32x4, oh);
+        out[(size_t)d * 16] = __builtin_bit_cast(u32x4, om);        // the mid plane follows the hi plane
     }
-    packed[(size_t)c * chunks_per_ckpt + q] = out;
 }
 
 }  // namespace tide

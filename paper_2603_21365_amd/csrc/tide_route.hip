@@ -156,9 +156,9 @@ struct Outputs {
 
 int launch_pack(int dtype, int64_t C, int64_t d, const float* gamma, const float* W1, void* packed, hipStream_t st) {
     const int chunks = (int)(d * kBottleneck * elem_bytes(dtype) / 16);
-    dim3 grid((chunks + 255) / 256, (unsigned)C);
+    dim3 grid((unsigned)(d / 16), (unsigned)C);
     by_dtype(dtype, [&](auto dt) {
-        hipLaunchKernelGGL((tide_pack_kernel<decltype(dt)::value>), grid, dim3(256), 0, st, gamma, W1, (u32x4*)packed, (int)d, chunks);
+        hipLaunchKernelGGL((tide_pack_kernel<decltype(dt)::value>), grid, dim3(kPackThreads), 0, st, gamma, W1, (u32x4*)packed, (int)d, chunks);
         return 0;
     });
     TIDE_HIP(hipGetLastError());
