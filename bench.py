@@ -105,15 +105,30 @@ def main() -> int:
         for i in range(steps):
             step(i)
             if i % window == window - 1:
-                m = torch.cuda.Event()
+                m = torch.cuda.Event(enable_timing=True)
                 m.record()
                 marks.append(m)
                 if len(marks) > 2:
-                    marks.pop(0).synchronize()
+                    marks[-3].synchronize()
         e1.record()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
+        # per-step time of every full window of `window` steps (spread of the measurement)
+        edges = [e0] + marks
+        per_window = sorted(edges[k].elapsed_time(edges[k + 1]) * 1e-3 / window for k in range(len(edges) - 1))
+        timed.windows = per_window
         return wall, e0.elapsed_time(e1) * 1e-3
+
+    def sp_pct(ws, q):
+        return ws[min(len(ws) - 1, int(q * len(ws)))]
+
+    def spread(us_scale=1e6):
+        ws = timed.windows
+        if not ws:
+            return {}
+        return {"median": round(ws[len(ws) // 2] * us_scale, 2), "best": round(ws[0] * us_scale, 2),
+                "p90": round(ws[min(len(ws) - 1, (9 * len(ws)) // 10)] * us_scale, 2), "windows": len(ws),
+                "steps_per_window": 16}
 
     # Settle: a one-time stall of ~30 ms was observed early in a process's GPU life (the device
     # idles between two launches; not kernel time).  Run untimed work past it before timing.
@@ -132,7 +147,17 @@ def main() -> int:
         torch.cuda.synchronize()
 
     wall_raw, ev_raw = timed(step_raw, args.steps, args.warmup)
+    spread_raw = spread()
     wall_pk, ev_pk = timed(step_packed, args.steps, args.warmup)
+    spread_pk = spread()
+
+    # what this machine's memory system gives a plain device-to-device copy of one batch (256 MiB read
+    # + 256 MiB written), source and destination rotated like the inputs: the "achievable" figure
+    copy_dst = [torch.empty_like(batches[0]) for _ in range(2)]
+    n_copy = max(20, args.steps // 4)
+    _, ev_cp = timed(lambda i: copy_dst[i & 1].copy_(batches[i % args.buffers]), n_copy, 5)
+    copy_gbs = 2.0 * batches[0].numel() * 2 / (ev_cp / n_copy) / 1e9
+    del copy_dst
 
     ex = out[0].cpu().numpy()
     from paper_2603_21365_amd import stats
@@ -156,6 +181,8 @@ def main() -> int:
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "kernel": "tide_prefill_dma_kernel<bf16, 128 rows/workgroup>", "us_per_launch": round(t_launch * 1e6, 2),
+                "us_per_launch_spread": spread_pk,
+                "device_copy_gbs": round(copy_gbs, 1), "frac_of_device_copy": round(achieved / copy_gbs, 4),
                 "algorithmic_bytes_per_launch": alg_bytes,
                 "mfma_tflops": round(flops / t_launch / 1e12, 1),
                 "mfma_frac_of_bf16_peak": round(flops / t_launch / 1e12 / MFMA_PEAK_TFLOPS["bf16"], 4)}
@@ -163,7 +190,8 @@ def main() -> int:
     result = {
         "metric": "tokens/sec + % HBM peak, fused RMSNorm+router d=4096 bf16; decode us/call",
         "value": round(T * args.steps / wall_raw, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(wall_raw / args.steps * 1e3, 5), "higher_is_better": True,
+        "warmup": args.warmup, "ms_per_step": round(wall_raw / args.steps * 1e3, 5),
+        "us_per_step_spread": spread_raw, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "configs[1]: 8B-shaped prefill, bf16, d=4096, 32 layers, checkpoints every 4 (C=8), "
                                "T=4096 tokens, ~30% firing per checkpoint", "C": C, "T": T, "d": d,
@@ -210,9 +238,23 @@ def main() -> int:
             prepared = tr.prepare_select_exit(hd, g, wd.eps, W1, b1, w2, rt.b2, rt.theta, wd.layer_ids, 0, wd.n_layers,
                                               out=outd)
             wall, ev = timed(lambda i: prepared(), 2000, 200)
+            sp = spread()
+            # latency of a single call as a caller that needs the answer sees it: call, then wait
+            lat = []
+            for _ in range(1000):
+                t0 = time.perf_counter()
+                prepared()
+                torch.cuda.synchronize()
+                lat.append(time.perf_counter() - t0)
+            lat.sort()
             dec[f"T{Td}"] = {"us_per_call": round(wall / 2000 * 1e6, 2), "calls_per_s": round(2000 / wall, 1),
-                             "us_per_call_hip_events": round(ev / 2000 * 1e6, 2)}
-        result["decode"] = {"workload": "configs[2]: fp16, d=4096, C=8, back-to-back calls on one stream", **dec}
+                             "us_per_call_hip_events": round(ev / 2000 * 1e6, 2),
+                             "us_per_call_spread": {"p10": round(sp_pct(timed.windows, 0.1) * 1e6, 2), "median": sp["median"],
+                                                    "p90": sp["p90"], "windows": sp["windows"], "calls_per_window": 16},
+                             "us_call_plus_sync": {"p10": round(lat[100] * 1e6, 2), "median": round(lat[500] * 1e6, 2),
+                                                   "p90": round(lat[900] * 1e6, 2), "calls": 1000}}
+        result["decode"] = {"workload": "configs[2]: fp16, d=4096, C=8, back-to-back calls on one stream "
+                                        "(us_per_call) and one call then a stream synchronisation (us_call_plus_sync)", **dec}
 
     # ---- the CPU oracle on the same workload (baseline, not a target)
     if not args.no_cpu_baseline:
@@ -222,10 +264,30 @@ def main() -> int:
         t0 = time.perf_counter()
         oracle.select_exit(hb, w.dtype, rt.gamma, w.eps, rt.W1, rt.b1, rt.w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers)
         dt = time.perf_counter() - t0
-        result["cpu_baseline"] = {"value": round(T / dt, 1), "unit": "tokens/s", "cores": oracle.max_threads(),
+        cores = oracle.max_threads()
+        # one thread, on the first 256 tokens of the same batch
+        n1 = 256
+        oracle.set_threads(1)
+        t1 = time.perf_counter()
+        oracle.select_exit(np.ascontiguousarray(hb[:, :n1]), w.dtype, rt.gamma, w.eps, rt.W1, rt.b1, rt.w2, rt.b2, rt.theta,
+                           w.layer_ids, 0, w.n_layers)
+        dt1 = time.perf_counter() - t1
+        oracle.set_threads(cores)
+        cpu_model = ""
+        try:
+            for line in open("/proc/cpuinfo"):
+                if line.startswith("model name"):
+                    cpu_model = line.split(":", 1)[1].strip()
+                    break
+        except OSError:
+            pass
+        result["cpu_baseline"] = {"value": round(T / dt, 1), "unit": "tokens/s", "cores": cores,
                                   "kind": "oracle",
                                   "sample": f"one full batch of the same workload (C={C} x T={T} rows of d={d}, fp64), "
-                                            f"{dt:.2f} s"}
+                                            f"{dt:.2f} s",
+                                  "single_thread_tokens_per_s": round(n1 / dt1, 1),
+                                  "single_thread_sample": f"first {n1} tokens of the same batch, {dt1:.2f} s",
+                                  "cpu": cpu_model, "os_cpu_count": os.cpu_count()}
     print(json.dumps(result))
     return 0
 
