@@ -13,6 +13,13 @@
 // One s_barrier per k-tile hands a landed stage to the consumers and a drained one back.
 // Workgroups are persistent: each walks a list of tiles, and the producers keep fetching
 // across tile boundaries, so HBM stays busy while the consumers are in a tile's epilogue.
+// When the tiles do not divide evenly among the workgroups, the tiles of the last, partly
+// filled round are cut into 2 or 4 pieces of fewer rows, so that the round costs a half or a
+// quarter of a full one instead of leaving most of the chip idle for a whole tile.  A piece of
+// 1/s of the rows takes s k-tiles per ring stage: every stage is the same number of bytes and
+// of transfers whatever the item, so the bytes in flight and the time per barrier stay those
+// of a full tile; its W1' fragments are fetched two k-tiles ahead instead of one, because a
+// k-tile of a piece is too little matrix work to cover the L2 round trip.
 //
 // Workgroup = kRowsM rows x all 128 columns; consumer wave w owns columns 32w..32w+31 of
 // every row (kRowsM/32 accumulator blocks), so each W1' fragment is fetched once per kRowsM
@@ -48,21 +55,45 @@ __device__ __forceinline__ void ring_barrier() {
 // s_waitcnt immediate that waits for vmcnt <= n and nothing else (gfx9 encoding).
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
-// Tile schedule of a persistent workgroup.  The checkpoint-major tile list is cut into 8
+// One unit of work of a persistent workgroup: `blocks` 32-row blocks of tile `tile`, starting
+// `row_off` rows into it.
+struct WorkItem {
+    int tile, row_off, blocks;
+};
+
+// Work schedule of a persistent workgroup.  The checkpoint-major tile list is cut into 8
 // contiguous slices, slice x -> XCD x (workgroup id mod 8), so that an XCD's L2 holds one W1'
-// at a time; the workgroups of an XCD deal its slice out round-robin.
+// at a time.  The g workgroups of an XCD deal its slice out round-robin: q full rounds, then the
+// r < g tiles left over, each cut into s pieces (s = 4 if 4r <= g, 2 if 2r <= g, else 1; s must
+// also divide the number of k-tiles of a row), one piece per workgroup.
+template <int kBlocks>
 struct TileWalk {
-    int next, end, step;
-    __device__ TileWalk(int total_tiles) {
+    int lo, j, g, q, s, count, i;
+    __device__ TileWalk(int total_tiles, int ntile) {
         const int per_xcd = (total_tiles + 7) >> 3;
         const int xcd = blockIdx.x & 7;
-        next = xcd * per_xcd + (blockIdx.x >> 3);
-        end = min((xcd + 1) * per_xcd, total_tiles);
-        step = gridDim.x >> 3;
+        lo = xcd * per_xcd;
+        const int n = max(min(lo + per_xcd, total_tiles) - lo, 0);
+        g = gridDim.x >> 3;
+        j = blockIdx.x >> 3;
+        q = n / g;
+        const int r = n - q * g;
+        s = 1;
+        if (r > 0 && 2 * r <= g && kBlocks >= 2 && ntile % 2 == 0) s = 2;
+        if (r > 0 && 4 * r <= g && kBlocks >= 4 && ntile % 4 == 0) s = 4;
+        count = q + (j < r * s ? 1 : 0);
+        i = 0;
     }
-    __device__ bool valid() const { return next < end; }
-    __device__ bool has_more() const { return next + step < end; }
-    __device__ void advance() { next += step; }
+    __device__ bool valid() const { return i < count; }
+    __device__ bool has_more() const { return i + 1 < count; }
+    __device__ void advance() { ++i; }
+    __device__ WorkItem item(int k) const {
+        if (k < q) return WorkItem{lo + j + k * g, 0, kBlocks};
+        const int piece = j % s;
+        return WorkItem{lo + q * g + j / s, piece * (kBlocks * 32 / s), kBlocks / s};
+    }
+    __device__ WorkItem current() const { return item(i); }
+    __device__ WorkItem following() const { return item(i + 1); }
 };
 
 template <int DT, int kRowsM>
@@ -80,54 +111,67 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ntile = p.d * Storage<DT>::kBytes / kTileBytes;
+    // An item of 1/s of the rows takes s k-tiles per stage: ntile / s stages.
+    auto split_of = [&](const WorkItem& it) { return kBlocks / it.blocks; };
     // Rows are a power-of-two number of bytes apart and all workgroups start together: each
-    // tile starts its k loop at a different k-tile and wraps (see prefill_kernel.hpp).
-    auto rotation = [&](int work) { return (int)(((unsigned)work * 5u) % (unsigned)ntile); };
+    // item starts its k loop at a different stage and wraps (see prefill_kernel.hpp).
+    auto first_stage = [&](const WorkItem& it) {
+        return (int)(((unsigned)it.tile * 5u + (unsigned)it.row_off) % (unsigned)(ntile / split_of(it)));
+    };
 
-    TileWalk walk(p.total_tiles);
+    TileWalk<kBlocks> walk(p.total_tiles, ntile);
     if (!walk.valid()) return;
 
     if (wave >= kDmaConsumers) {
         // ------------------------------------------------------------------ producers
-        // They run ahead of the consumers by kDmaStages-1 k-tiles, across tile boundaries: while
-        // the consumers are in the epilogue of one tile the ring fills with the next tile's rows.
+        // They run ahead of the consumers by kDmaStages-1 stages, across item boundaries: while
+        // the consumers are in the epilogue of one item the ring fills with the next one's rows.
         const int pw = wave - kDmaConsumers;
         // lane -> (row within a 4-row transfer, LDS chunk slot); the global chunk is the slot
         // XOR the row's low bits, which is what the consumers undo when they read
         const int rl = lane >> 4, slot = lane & 15;
-        const char* gp[kInstrPerProducer];     // row pointers of the tile being fetched
-        int f_rot = 0, f_k = 0;                // fetch cursor: k-tile within that tile
-        TileWalk fetch = walk;
-        auto aim = [&](int work) {
-            const int c = work / p.tiles_per_ckpt;
-            const int row0 = (work - c * p.tiles_per_ckpt) * kRowsM;
+        // Transfer i of a stage: k-tile (i / per_sub) of the stage, row group (i % per_sub) of this
+        // producer's half of the item's rows; per_sub = kInstrPerProducer / s.
+        const char* gp[kInstrPerProducer];     // source of transfer i at stage 0
+        int doff[kInstrPerProducer];           // its place in the ring slot
+        int f_rot = 0, f_k = 0, f_stages = 0, f_stage_bytes = 0;   // fetch cursor within its item
+        TileWalk<kBlocks> fetch = walk;
+        auto aim = [&](const WorkItem& it) {
+            const int c = it.tile / p.tiles_per_ckpt;
+            const int row0 = (it.tile - c * p.tiles_per_ckpt) * kRowsM + it.row_off;
             const char* base = p.hidden + (int64_t)c * p.ckpt_stride_bytes;
+            const int s = split_of(it);
+            const int per_sub = kInstrPerProducer / s;
 #pragma unroll
             for (int i = 0; i < kInstrPerProducer; ++i) {
-                const int row = (pw * kInstrPerProducer + i) * 4 + rl;      // row within the tile
+                const int sub = i / per_sub, group = pw * per_sub + (i - sub * per_sub);
+                const int row = group * 4 + rl;                             // row within the item
                 int r = row0 + row;
                 r = r < p.T ? r : p.T - 1;                                  // ragged tail: re-read the last row
-                gp[i] = base + (int64_t)r * p.row_stride_bytes + ((slot ^ (row & 15)) << 4);
+                gp[i] = base + (int64_t)r * p.row_stride_bytes + ((slot ^ (row & 15)) << 4) + sub * kTileBytes;
+                doff[i] = sub * (kStageBytes / s) + group * 1024;
             }
-            f_rot = rotation(work);
+            f_stages = ntile / s;
+            f_stage_bytes = s * kTileBytes;
+            f_rot = first_stage(it);
             f_k = 0;
         };
-        aim(fetch.next);
+        aim(fetch.current());
         int issued = 0;                        // global stage counter -> ring slot
         bool fetch_done = false;
-        auto issue_next = [&]() {              // one k-tile of the fetch cursor's tile; moves the cursor
+        auto issue_next = [&]() {              // one stage of the fetch cursor's item; moves the cursor
             if (fetch_done) return;
-            int kt = f_k + f_rot;
-            kt = kt >= ntile ? kt - ntile : kt;
-            char* dst = ring + (issued % kDmaStages) * kStageBytes + pw * kInstrPerProducer * 1024;
+            int ks = f_k + f_rot;
+            ks = ks >= f_stages ? ks - f_stages : ks;
+            char* dst = ring + (issued % kDmaStages) * kStageBytes;
 #pragma unroll
             for (int i = 0; i < kInstrPerProducer; ++i)
-                __builtin_amdgcn_global_load_lds((glb_char*)(gp[i] + (int64_t)kt * kTileBytes), (lds_char*)(dst + i * 1024), 16, 0, kStreamOnce);
+                __builtin_amdgcn_global_load_lds((glb_char*)(gp[i] + (int64_t)ks * f_stage_bytes), (lds_char*)(dst + doff[i]), 16, 0, kStreamOnce);
             ++issued;
-            if (++f_k == ntile) {
+            if (++f_k == f_stages) {
                 if (fetch.has_more()) {
                     fetch.advance();
-                    aim(fetch.next);
+                    aim(fetch.current());
                 } else {
                     fetch_done = true;
                 }
@@ -136,8 +180,10 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
         for (int s = 0; s < kDmaStages - 1; ++s) issue_next();
         int handed = 0;                        // stages handed to the consumers so far
         for (; walk.valid(); walk.advance()) {
-            for (int k = 0; k < ntile; ++k) {
+            const int stages = ntile / split_of(walk.current());
+            for (int k = 0; k < stages; ++k) {
                 // stage `handed` has landed once at most the kDmaStages-2 younger ones are outstanding
+                // (every stage is kInstrPerProducer transfers; loads complete in issue order)
                 if (issued - handed == kDmaStages - 1)
                     __builtin_amdgcn_s_waitcnt(vmcnt_imm((kDmaStages - 2) * kInstrPerProducer));
                 else
@@ -161,52 +207,57 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
     const int y16 = ((lane >> 5) ^ (r & 15)) << 4;
     const int yf16 = (((lane >> 5) << 1) ^ (r & 15)) << 4;     // fp32 rows: see the k loop
     const size_t ckpt_chunks = (size_t)p.d * kBottleneck / Storage<DT>::kElems;
-    auto b_pointer = [&](int work) {
-        return p.packed + (size_t)(work / p.tiles_per_ckpt) * ckpt_chunks + wave * 64 + lane;
+    auto b_pointer = [&](const WorkItem& it) {
+        return p.packed + (size_t)(it.tile / p.tiles_per_ckpt) * ckpt_chunks + wave * 64 + lane;
     };
     constexpr int kMmaGroups = Compute<DT>::kMmaGroups, kPlanes = Compute<DT>::kPlanes;
+    constexpr int kFrags = kMmaGroups * kPlanes;   // W1' fragments of one k-tile: 8 either way
     const size_t plane_chunks = (size_t)p.d * 16;
-    u32x4 breg[kMmaGroups * kPlanes];              // [g * kPlanes + plane]: 8 fragments either way
+    u32x4 breg[kFrags];                            // [g * kPlanes + plane]
     auto b_fragment = [&](const u32x4* base, int kt, int g, int pl) {
         return base[pl * plane_chunks + (size_t)(kt * kMmaGroups + g) * 256];
     };
     {
-        const u32x4* b0 = b_pointer(walk.next);
-        const int rot0 = rotation(walk.next);
+        // the first k-tile of the first item
+        const WorkItem first = walk.current();
+        const u32x4* b0 = b_pointer(first);
+        const int kt0 = first_stage(first) * split_of(first);
 #pragma unroll
         for (int g = 0; g < kMmaGroups; ++g)
 #pragma unroll
-            for (int pl = 0; pl < kPlanes; ++pl) breg[g * kPlanes + pl] = b_fragment(b0, rot0, g, pl);
+            for (int pl = 0; pl < kPlanes; ++pl) breg[g * kPlanes + pl] = b_fragment(b0, kt0, g, pl);
     }
     int stage = 0;                                 // global stage counter -> ring slot
-    for (; walk.valid(); walk.advance()) {
-        const int work = walk.next;
-        const int c = work / p.tiles_per_ckpt;
-        const int row0 = (work - c * p.tiles_per_ckpt) * kRowsM;
-        const u32x4* bptr = b_pointer(work);
-        int kt = rotation(work);
 
-        f32x16 acc[kBlocks];
-        float ssq[kBlocks];
+    // One item of kActive 32-row blocks.  kActive is a compile-time value so that the k loop of
+    // every item size is straight-line code.
+    auto run_item = [&](auto active_tag, const WorkItem& it) {
+        constexpr int kActive = decltype(active_tag)::value;
+        constexpr int kSub = kBlocks / kActive;     // k-tiles per stage
+        constexpr int kSubBytes = kStageBytes / kSub;
+        const int c = it.tile / p.tiles_per_ckpt;
+        const int row0 = (it.tile - c * p.tiles_per_ckpt) * kRowsM + it.row_off;
+        const u32x4* bptr = b_pointer(it);
+
+        f32x16 acc[kActive];
+        float ssq[kActive];
 #pragma unroll
-        for (int b = 0; b < kBlocks; ++b) {
+        for (int b = 0; b < kActive; ++b) {
             acc[b] = f32x16{0};
             ssq[b] = 0.0f;
         }
-        // One k-tile; afterwards breg holds the fragments of (nb, kn).  Each call site is
-        // straight-line code, so the W1' wait counts stay exact (8 loads in flight).
-        auto consume = [&](const u32x4* nb, int kn, auto refill) {
-            ring_barrier();
-            const char* st = ring + (stage % kDmaStages) * kStageBytes + a_base;
+        // The matrix work of one k-tile: A fragments of the kActive blocks from `st`, W1' fragments
+        // from bf; after group g is used, bf's fragment g is refilled from (nb, kn) if refill is set.
+        auto k_tile = [&](const char* st, u32x4 (&bf)[kFrags], const u32x4* nb, int kn, auto refill) {
 #pragma unroll
             for (int g = 0; g < kMmaGroups; ++g) {
                 if constexpr (DT == kF32) {
                     // 16 k values = chunks 4g+2h and 4g+2h+1 of the row (4 fp32 each); their slots are
                     // ((4g) ^ y) and that ^ 1 with y = (2h) ^ (r & 15)
-                    u32x4 ah[kBlocks], am[kBlocks];
-                    float sq[kBlocks];
+                    u32x4 ah[kActive], am[kActive];
+                    float sq[kActive];
 #pragma unroll
-                    for (int b = 0; b < kBlocks; ++b) {
+                    for (int b = 0; b < kActive; ++b) {
                         const char* src = st + b * 32 * kTileBytes;
                         const u32x4 c0 = *reinterpret_cast<const u32x4*>(src + (yf16 ^ (g << 6)));
                         const u32x4 c1 = *reinterpret_cast<const u32x4*>(src + (yf16 ^ (g << 6) ^ 16));
@@ -222,52 +273,95 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
                         sq[b] = chunk_sumsq<kF32>(c1, chunk_sumsq<kF32>(c0, 0.0f));
                     }
 #pragma unroll
-                    for (int b = 0; b < kBlocks; ++b) acc[b] = mma_k16_split(ah[b], am[b], breg[2 * g], breg[2 * g + 1], acc[b]);
+                    for (int b = 0; b < kActive; ++b) acc[b] = mma_k16_split(ah[b], am[b], bf[2 * g], bf[2 * g + 1], acc[b]);
                     if (g == wave) {                   // this wave's share of the sums of squares
 #pragma unroll
-                        for (int b = 0; b < kBlocks; ++b) ssq[b] += sq[b];
+                        for (int b = 0; b < kActive; ++b) ssq[b] += sq[b];
                     }
                 } else {
-                    u32x4 a[kBlocks];
+                    u32x4 a[kActive];
 #pragma unroll
-                    for (int b = 0; b < kBlocks; ++b)
+                    for (int b = 0; b < kActive; ++b)
                         a[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + (y16 ^ (g << 5)));
 #pragma unroll
-                    for (int b = 0; b < kBlocks; ++b) acc[b] = mma_k16<DT>(a[b], breg[g], acc[b]);
+                    for (int b = 0; b < kActive; ++b) acc[b] = mma_k16<DT>(a[b], bf[g], acc[b]);
                     if ((g & 3) == wave) {             // this wave's share of the sums of squares
 #pragma unroll
-                        for (int b = 0; b < kBlocks; ++b) ssq[b] = chunk_sumsq<DT>(a[b], ssq[b]);
+                        for (int b = 0; b < kActive; ++b) ssq[b] = chunk_sumsq<DT>(a[b], ssq[b]);
                     }
                 }
                 if (decltype(refill)::value) {
 #pragma unroll
-                    for (int pl = 0; pl < kPlanes; ++pl) breg[g * kPlanes + pl] = b_fragment(nb, kn, g, pl);
+                    for (int pl = 0; pl < kPlanes; ++pl) bf[g * kPlanes + pl] = b_fragment(nb, kn, g, pl);
                 }
             }
-            ++stage;
         };
-        for (int k = 0; k + 1 < ntile; ++k) {
-            const int kn = kt + 1 >= ntile ? 0 : kt + 1;
-            consume(bptr, kn, std::true_type{});
-            kt = kn;
-        }
-        if (walk.has_more()) {                      // last k-tile: prefetch the next tile's first fragments
-            const int nwork = walk.next + walk.step;
-            consume(b_pointer(nwork), rotation(nwork), std::true_type{});
+
+        if constexpr (kSub == 1) {
+            // ---- full tile: one k-tile per stage, W1' one k-tile ahead.  Each call site is
+            // straight-line code, so the W1' wait counts stay exact (8 loads in flight).
+            int kt = first_stage(it);
+            auto consume = [&](const u32x4* nb, int kn, auto refill) {
+                ring_barrier();
+                k_tile(ring + (stage % kDmaStages) * kStageBytes + a_base, breg, nb, kn, refill);
+                ++stage;
+            };
+            for (int k = 0; k + 1 < ntile; ++k) {
+                const int kn = kt + 1 >= ntile ? 0 : kt + 1;
+                consume(bptr, kn, std::true_type{});
+                kt = kn;
+            }
+            if (walk.has_more()) {                  // last k-tile: prefetch the next item's first fragments
+                const WorkItem nxt = walk.following();
+                consume(b_pointer(nxt), first_stage(nxt) * split_of(nxt), std::true_type{});
+            } else {
+                consume(bptr, 0, std::false_type{});
+            }
         } else {
-            consume(bptr, 0, std::false_type{});
+            // ---- piece (always the last item of its workgroup): kSub k-tiles per stage, W1' two
+            // k-tiles ahead in two fragment sets used alternately (kSub is even).
+            const int stages = ntile / kSub;
+            int ks = first_stage(it);
+            u32x4 bnext[kFrags];                    // breg: k-tile j even of a stage, bnext: j odd
+#pragma unroll
+            for (int g = 0; g < kMmaGroups; ++g)
+#pragma unroll
+                for (int pl = 0; pl < kPlanes; ++pl) bnext[g * kPlanes + pl] = b_fragment(bptr, ks * kSub + 1, g, pl);
+            auto consume = [&](int ks_next, auto last) {
+                ring_barrier();
+                const char* st = ring + (stage % kDmaStages) * kStageBytes + a_base;
+#pragma unroll
+                for (int j = 0; j < kSub; ++j) {
+                    // the set used by k-tile j is refilled with the k-tile two steps later
+                    const int kn = j + 2 < kSub ? ks * kSub + j + 2 : ks_next * kSub + (j + 2 - kSub);
+                    if (decltype(last)::value && j + 2 >= kSub) {
+                        if (j & 1) k_tile(st + j * kSubBytes, bnext, bptr, 0, std::false_type{});
+                        else k_tile(st + j * kSubBytes, breg, bptr, 0, std::false_type{});
+                    } else {
+                        if (j & 1) k_tile(st + j * kSubBytes, bnext, bptr, kn, std::true_type{});
+                        else k_tile(st + j * kSubBytes, breg, bptr, kn, std::true_type{});
+                    }
+                }
+                ++stage;
+            };
+            for (int k = 0; k + 1 < stages; ++k) {
+                const int kn = ks + 1 >= stages ? 0 : ks + 1;
+                consume(kn, std::false_type{});
+                ks = kn;
+            }
+            consume(0, std::true_type{});
         }
 
         // ---- row sums of squares: lanes l and l^32 hold the two chunk phases; the 4 waves the rest
 #pragma unroll
-        for (int b = 0; b < kBlocks; ++b) {
+        for (int b = 0; b < kActive; ++b) {
             const float s2 = ssq[b] + __shfl_xor(ssq[b], 32, kWave);
             if (lane < 32) ss_part[wave * kRowsM + 32 * b + lane] = s2;
         }
         __syncthreads();
 
         // ---- one inverse RMS per row, computed once ----
-        if (tid < kRowsM) {
+        if (tid < kActive * 32) {
             const float ss = (ss_part[tid] + ss_part[kRowsM + tid]) + (ss_part[2 * kRowsM + tid] + ss_part[3 * kRowsM + tid]);
             inv_rms[tid] = inv_rms_f32(ss, 1.0f / (float)p.d, p.eps);
         }
@@ -276,12 +370,12 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
         // ---- epilogue: a = r*acc + b1; SiLU; dot with w2 over this wave's 32 columns ----
         {
             const int col = 32 * wave + (lane & 31);
-            router_epilogue<kBlocks>(acc, inv_rms, z_part + wave * kRowsM, p.b1 ? p.b1[c * kBottleneck + col] : 0.0f,
+            router_epilogue<kActive>(acc, inv_rms, z_part + wave * kRowsM, p.b1 ? p.b1[c * kBottleneck + col] : 0.0f,
                                      p.w2[c * kBottleneck + col], lane);
         }
         __syncthreads();
 
-        if (tid < kRowsM) {
+        if (tid < kActive * 32) {
             const int t = row0 + tid;
             if (t < p.T) {
                 const float z = p.tab.b2[c] + ((z_part[tid] + z_part[kRowsM + tid]) + (z_part[2 * kRowsM + tid] + z_part[3 * kRowsM + tid]));
@@ -295,7 +389,18 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
                                       p.fire_mask ? p.fire_mask + t : nullptr);
             }
         }
-        // z_part / ss_part / inv_rms are next written after the first barriers of the next tile's k loop
+        // z_part / ss_part / inv_rms are next written after the first barriers of the next item's k loop
+    };
+
+    for (; walk.valid(); walk.advance()) {
+        const WorkItem it = walk.current();
+        if (it.blocks == kBlocks) {
+            run_item(std::integral_constant<int, kBlocks>{}, it);
+        } else if (kBlocks == 4 && it.blocks == 2) {
+            run_item(std::integral_constant<int, (kBlocks == 4 ? 2 : 1)>{}, it);
+        } else {
+            run_item(std::integral_constant<int, 1>{}, it);
+        }
     }
 }
 

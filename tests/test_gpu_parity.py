@@ -122,6 +122,27 @@ def test_every_prefill_form_computes_the_same_function(tr, form, dtype, T, d):
         tr.set_prefill_form(0)
 
 
+@pytest.mark.parametrize("form,dtype,layers,T,d,what", [
+    (2, "bf16", 20, 8155, 256, "320 tiles of 128 rows on 256 workgroups: 8 left per XCD, cut into 32-row quarters; ragged"),
+    (2, "f16", 12, 16384, 512, "384 tiles: 16 left per XCD, cut into 64-row halves"),
+    (2, "f32", 12, 16384 - 70, 256, "halves, fp32 rows, ragged last tile"),
+    (2, "bf16", 28, 8192, 128, "448 tiles: 24 left per XCD, too many to cut; single k-tile"),
+    (1, "bf16", 12, 16384, 256, "768 tiles of 64 rows on 512 workgroups: 32 left per XCD, cut into 32-row halves"),
+])
+def test_uneven_tile_counts_split_the_last_round(tr, form, dtype, layers, T, d, what):
+    """Tile counts that do not divide among the persistent workgroups: the tiles of the last
+    round are processed as pieces of fewer rows (a 256-CU device is assumed for the counts)."""
+    w = synth.Workload(f"uneven_form{form}_{dtype}_L{layers}_T{T}_d{d}", 31, dtype, d, layers, 4, T, None)
+    say(what)
+    rt = w.routers()
+    rt.b2[:] = np.linspace(-0.2, 0.2, w.C)
+    tr.set_prefill_form(form)
+    try:
+        run_and_compare(tr, w, w.name, rt=rt, packed=True, variant=tr.VARIANT_PREFILL)
+    finally:
+        tr.set_prefill_form(0)
+
+
 @pytest.mark.parametrize("form", [1, 2, 3])
 def test_config1_full_in_every_prefill_form(tr, form):
     w = synth.config1()
