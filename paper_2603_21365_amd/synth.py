@@ -210,6 +210,7 @@ class Workload:
     theta: float = 0.5
     eps: float = 1e-6
     layer_ids: np.ndarray = field(default=None)
+    b: int = BOTTLENECK       # router bottleneck width
 
     def __post_init__(self):
         if self.layer_ids is None:
@@ -224,7 +225,7 @@ class Workload:
                            trajectory=self.trajectory, **kw)
 
     def routers(self) -> Routers:
-        return make_routers(self.cfg, self.C, self.d, theta=self.theta)
+        return make_routers(self.cfg, self.C, self.d, b=self.b, theta=self.theta)
 
 
 def config0() -> Workload:
@@ -245,6 +246,15 @@ def config2(T: int) -> Workload:
 def config3(T: int = 16384) -> Workload:
     """36-layer batched prefill, bf16: C=9, batch 8 x 2048 tokens, ~20 % fire."""
     return Workload("cfg3_prefill_36l_bf16", 3, "bf16", 4096, 36, 4, T, 0.20)
+
+
+# The (hidden size, bottleneck width) pairs the paper compiles dedicated kernels for (Table 2).
+TABLE2_PAIRS = ((2048, 64), (2048, 128), (3072, 128), (4096, 128), (4096, 256), (5120, 128), (8192, 128), (8192, 256))
+
+
+def table2(d: int, b: int, dtype: str = "bf16", T: int = 4096) -> Workload:
+    """One hidden-size / bottleneck pair of Table 2: 32 layers, checkpoints every 4 (C=8), ~30 % fire."""
+    return Workload(f"table2_d{d}_b{b}_{dtype}", 5, dtype, d, 32, 4, T, 0.30, b=b)
 
 
 SWEEP_D = (768, 1024, 2048, 2560, 3072, 4096, 5120, 8192)

@@ -167,10 +167,11 @@ def test_constant_row_gives_column_sums():
         assert abs(z[0] - want) < 1e-13
 
 
-def test_paper_form_against_numpy_and_scipy_routines():
+@pytest.mark.parametrize("b", [128, 64, 256])
+def test_paper_form_against_numpy_and_scipy_routines(b):
     """Eq. (2) exactly as printed (no gain, no biases, W_down [b,d], W_up [1,b]) composed from
-    library routines: 2-norm, matmul, expit."""
-    d, b, T = 96, 128, 11
+    library routines: 2-norm, matmul, expit -- at the three bottleneck widths of Table 2."""
+    d, T = 96, 11
     W_down = (RNG.standard_normal((b, d)) / math.sqrt(d)).astype(np.float32)
     W_up = (RNG.standard_normal((1, b)) / math.sqrt(b)).astype(np.float32)
     h = RNG.standard_normal((T, d)).astype(np.float32)
@@ -182,6 +183,33 @@ def test_paper_form_against_numpy_and_scipy_routines():
     assert np.allclose(p, want_p, rtol=1e-12, atol=0)
     assert np.allclose(z, scipy.special.logit(want_p), rtol=1e-9, atol=1e-12)
     assert np.array_equal(fire.astype(bool), want_p > 0.5)
+
+
+def test_bottleneck_widths_pad_with_zeros_and_split_into_halves():
+    """What ties the bottleneck widths of Table 2 together: a router of width 64 is the width-128
+    router whose other 64 columns have zero W1 and zero w2 (whatever their b1), and a router of
+    width 256 is the sum of the two width-128 routers made of its column halves (b2 counted once)."""
+    d, T = 48, 9
+    h = RNG.standard_normal((T, d)).astype(np.float32)
+    gamma, W1, b1, w2 = rand_router(d, 64)
+    z64, _, _ = oracle.router_eval(h, "f32", gamma, 1e-6, W1, b1, w2, 0.2, 0.5)
+    W1p = np.zeros((d, 128), np.float32); W1p[:, :64] = W1
+    b1p = RNG.standard_normal(128).astype(np.float32); b1p[:64] = b1
+    w2p = np.zeros(128, np.float32); w2p[:64] = w2
+    zp, _, _ = oracle.router_eval(h, "f32", gamma, 1e-6, W1p, b1p, w2p, 0.2, 0.5)
+    assert np.allclose(z64, zp, rtol=0, atol=1e-14)
+    gamma, W1, b1, w2 = rand_router(d, 256)
+    z256, _, _ = oracle.router_eval(h, "f32", gamma, 1e-6, W1, b1, w2, 0.2, 0.5)
+    za, _, _ = oracle.router_eval(h, "f32", gamma, 1e-6, np.ascontiguousarray(W1[:, :128]), b1[:128], w2[:128], 0.2, 0.5)
+    zb, _, _ = oracle.router_eval(h, "f32", gamma, 1e-6, np.ascontiguousarray(W1[:, 128:]), b1[128:], w2[128:], 0.0, 0.5)
+    assert np.allclose(z256, za + zb, rtol=0, atol=1e-13)
+    # a single live column beyond the first 128: z = b2 + w2_j silu(a_j), a_j from one row of W1
+    W1s = np.zeros((d, 256), np.float32); W1s[5, 200] = 0.75
+    w2s = np.zeros(256, np.float32); w2s[200] = -1.5
+    hs = np.zeros((1, d), np.float32); hs[0, 5] = 2.0
+    z, _, _ = oracle.router_eval(hs, "f32", None, 0.0, W1s, None, w2s, 0.1, 0.5)
+    a = math.sqrt(d) * 0.75
+    assert abs(z[0] - (float(np.float32(0.1)) - 1.5 * a / (1 + math.exp(-a)))) < 1e-13
 
 
 def test_brute_force_tiny_d_with_exact_rationals():
