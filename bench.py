@@ -227,6 +227,26 @@ def main() -> int:
                                     "algorithmic_bytes": cs_bytes, "gbs": round(cs_bytes / (ev_cs / n_cos) / 1e9, 1),
                                     "frac_of_hbm_peak": round(cs_bytes / (ev_cs / n_cos) / 1e9 / HBM_PEAK_GBS, 4)}
 
+    # ---- the other bottleneck widths of the paper's kernel specialisations (Table 2), same token count
+    widths = {}
+    gen = torch.Generator(device="cuda").manual_seed(0x71DE)
+    for dd, bb in ((2048, 64), (4096, 256), (8192, 256)):
+        nb = 3
+        hbs = [torch.randn((C, T, dd), generator=gen, device="cuda").to(torch.bfloat16) for _ in range(nb)]
+        Wb = torch.randn((C, dd, bb), generator=gen, device="cuda") / dd ** 0.5
+        w2b = torch.randn((C, bb), generator=gen, device="cuda") / bb ** 0.5
+        pkb = tr.router_pack(tr.BF16, None, Wb)
+        cb = [tr.prepare_select_exit_packed(h, pkb, w.eps, None, w2b, 0.0, 0.5, w.layer_ids, 0, w.n_layers, d=dd, out=out)
+              for h in hbs]
+        n_w = max(20, args.steps // 4)
+        _, ev_w = timed(lambda i: cb[i % nb](), n_w, 5)
+        by = C * T * dd * esz + C * dd * bb * esz + T * 8 + C * T * 4
+        widths[f"d{dd}_b{bb}"] = {"us_per_call": round(ev_w / n_w * 1e6, 2), "algorithmic_bytes": by,
+                                  "gbs": round(by / (ev_w / n_w) / 1e9, 1),
+                                  "frac_of_hbm_peak": round(by / (ev_w / n_w) / 1e9 / HBM_PEAK_GBS, 4)}
+        del hbs, cb, pkb, Wb
+    result["bottleneck_widths"] = {"workload": f"Table 2 pairs with b != 128: bf16, C={C}, T={T}, packed weights", **widths}
+
     # ---- decode latency (config 2): fp16, T = 1 and 8, raw weights, auto-selected decode variant
     if not args.no_decode:
         dec = {}

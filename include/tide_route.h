@@ -7,14 +7,15 @@
  * (paper Eq. (2); fused kernel 1 of Sec. 3.4)
  *
  *     n   = h / sqrt(mean(h^2) + eps) * gamma               RMSNorm
- *     a_j = b1_j + sum_i n_i * W1[i][j],   j < 128          down-projection (W1 = W_down^T)
+ *     a_j = b1_j + sum_i n_i * W1[i][j],   j < b            down-projection (W1 = W_down^T)
  *     z   = b2 + sum_j w2_j * a_j * sigmoid(a_j)            SiLU, up-projection: the LOGIT
  *     p   = sigmoid(z),     fire = (p > threshold)          strict, as in Alg. 1 / Fig. 1
  *
  * and, over C checkpoints, picks for every token the earliest eligible checkpoint whose
  * router fires (paper Fig. 1 inference step 3, Sec. 3.3, Alg. 1 per token).
  * The paper's router has gamma = 1 and no biases: pass gamma = NULL, b1 = NULL, b2 = 0.
- * The bottleneck width is fixed at 128 (the paper's default, Sec. 3.1).
+ * The bottleneck width b is 128 (the paper's default, Sec. 3.1), 64 or 256: the widths of the
+ * paper's kernel specialisations (Sec. 3.4, Table 2).
  *
  * Conventions for every entry point
  *  - "device" pointers are HIP device memory on the current device; "host" pointers are
@@ -45,7 +46,7 @@
 extern "C" {
 #endif
 
-#define TIDE_BOTTLENECK 128
+#define TIDE_BOTTLENECK 128 /* the default width; 64 and 256 are accepted too */
 #define TIDE_MAX_CHECKPOINTS 32
 
 typedef enum { TIDE_F32 = 0, TIDE_F16 = 1, TIDE_BF16 = 2 } tide_dtype_t;
@@ -71,22 +72,23 @@ const char* tide_last_error(void);
 /* One router over T rows: Eq. (2).
  *   hidden  device [T rows]            dtype, layout as above (ckpt_stride unused)
  *   gamma   device [d] fp32 or NULL    RMSNorm gain (NULL = all ones, the paper's form)
- *   W1      device [d,128] fp32        row-major, W1[i*128+j] = W_down[j][i]
- *   b1      device [128] fp32 or NULL  bias after the down-projection (NULL = zeros)
- *   w2      device [128] fp32          = W_up
+ *   b       bottleneck width: 64, 128 or 256 (anything else: TIDE_ERR_UNSUPPORTED)
+ *   W1      device [d,b] fp32          row-major, W1[i*b+j] = W_down[j][i], 16-byte aligned
+ *   b1      device [b] fp32 or NULL    bias after the down-projection (NULL = zeros)
+ *   w2      device [b] fp32            = W_up
  *   b2, eps, threshold                 by value
  *   prob    device [T] fp32 out, or NULL
  *   fire    device [T] u8 out (0/1), or NULL
  *   logit   device [T] fp32 out, or NULL   (z before the sigmoid)                     */
-int tide_router_eval(const void* hidden, int dtype, int64_t T, int64_t d, int64_t row_stride,
-                     const float* gamma, float eps, const float* W1, const float* b1,
+int tide_router_eval(const void* hidden, int dtype, int64_t T, int64_t d, int64_t b,
+                     int64_t row_stride, const float* gamma, float eps, const float* W1, const float* b1,
                      const float* w2, float b2, float threshold, float* prob, uint8_t* fire,
                      float* logit, void* stream);
 
 /* Per-token earliest exit over C checkpoints: Fig. 1 step 3 / Alg. 1 applied per token.
  *   hidden     device [C,T rows]             router c reads checkpoint c's rows
- *   gamma      device [C,d] or NULL;  W1 device [C,d,128];  b1 device [C,128] or NULL;
- *   w2         device [C,128]
+ *   gamma      device [C,d] or NULL;  W1 device [C,d,b];  b1 device [C,b] or NULL;
+ *   w2         device [C,b]
  *   b2         HOST [C];  threshold HOST [C]  (one theta per checkpoint; the paper uses one)
  *   layer_ids  HOST [C] int32, strictly ascending: the model layer of each checkpoint
  *   min_layer  checkpoints with layer_ids[c] < min_layer cannot be chosen (k_min of Alg. 1)
@@ -94,7 +96,7 @@ int tide_router_eval(const void* hidden, int dtype, int64_t T, int64_t d, int64_
  *   exit_layer device [T] int32 out:   min{ layer_ids[c] : eligible, fired } or no_exit_layer
  *   logits     device [C,T] fp32 out, or NULL
  *   fire_mask  device [T] u32 out, or NULL: bit c set iff checkpoint c fired (eligible or not) */
-int tide_select_exit(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d,
+int tide_select_exit(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b,
                      int64_t ckpt_stride, int64_t row_stride, const float* gamma, float eps,
                      const float* W1, const float* b1, const float* w2, const float* b2,
                      const float* threshold, const int32_t* layer_ids, int32_t min_layer,
@@ -104,22 +106,23 @@ int tide_select_exit(const void* hidden, int dtype, int64_t C, int64_t T, int64_
 /* Router weights do not change between requests (they are trained once, Sec. 3.1), so the
  * gain can be folded into the projection ahead of time: W1'[i][j] = gamma_i * W1[i][j],
  * rounded to `dtype` and stored in the order the matrix-core kernel consumes it.
- * tide_packed_router_bytes: bytes of one checkpoint's packed weights (0 if unsupported).
- * tide_router_pack: device gamma [C,d] or NULL, device W1 [C,d,128] -> device packed
+ * tide_packed_router_bytes: bytes of one checkpoint's packed weights (0 if unsupported; width 64
+ *   is stored padded to 128 columns, width 256 as two 128-column halves).
+ * tide_router_pack: device gamma [C,d] or NULL, device W1 [C,d,b] -> device packed
  *   [C * tide_packed_router_bytes] (16-byte aligned).  The packed layout is private to the
  *   library version that wrote it.                                                      */
-size_t tide_packed_router_bytes(int dtype, int64_t d);
-int tide_router_pack(int dtype, int64_t C, int64_t d, const float* gamma, const float* W1,
-                     void* packed, void* stream);
+size_t tide_packed_router_bytes(int dtype, int64_t d, int64_t b);
+int tide_router_pack(int dtype, int64_t C, int64_t d, int64_t b, const float* gamma,
+                     const float* W1, void* packed, void* stream);
 
 /* The two calls above with pre-packed weights in place of (gamma, W1); `packed` must have
- * been written by tide_router_pack with the same dtype, C and d.                        */
-int tide_router_eval_packed(const void* hidden, int dtype, int64_t T, int64_t d,
+ * been written by tide_router_pack with the same dtype, C, d and b.                     */
+int tide_router_eval_packed(const void* hidden, int dtype, int64_t T, int64_t d, int64_t b,
                             int64_t row_stride, const void* packed, float eps, const float* b1,
                             const float* w2, float b2, float threshold, float* prob,
                             uint8_t* fire, float* logit, void* stream);
 int tide_select_exit_packed(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d,
-                            int64_t ckpt_stride, int64_t row_stride, const void* packed,
+                            int64_t b, int64_t ckpt_stride, int64_t row_stride, const void* packed,
                             float eps, const float* b1, const float* w2, const float* b2,
                             const float* threshold, const int32_t* layer_ids, int32_t min_layer,
                             int32_t no_exit_layer, int32_t* exit_layer, float* logits,

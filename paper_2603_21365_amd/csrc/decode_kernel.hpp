@@ -2,7 +2,8 @@
 // every decode step evaluates the routers on the new token's checkpoint states) for a
 // handful of rows per call, where the cost is reading C routers' weights and latency.
 //
-// The d-long contraction of each checkpoint is split over S = d/128 workgroups so that the
+// The d-long contraction of each checkpoint is split over S = d/128 workgroups (times the
+// 128-column halves of the bottleneck: one for widths 64 and 128, two for 256) so that the
 // whole chip pulls the weights at once (raw fp32 W1, no packing pass: with so few rows the
 // matrix cores have nothing to amortise).  Each workgroup writes its partial 128-vector and
 // partial sum of squares per token (device-scope stores, no fences); the last workgroup of a
@@ -17,16 +18,17 @@ struct DecodeParams {
     const char* hidden;
     int64_t ckpt_stride_bytes, row_stride_bytes;
     const float* gamma;   // [C][d] or null
-    const float* W1;      // [C][d][128]
-    const float* b1;      // [C][128] or null
-    const float* w2;      // [C][128]
+    const float* W1;      // [C][d][b]
+    const float* b1;      // [C][b] or null
+    const float* w2;      // [C][b]
     int C, T, d, S;       // S = d / kDecodeSlice
+    int b, halves;        // bottleneck width (64, 128, 256) and its 128-column halves
     float eps;
     int32_t min_layer, no_exit;
     float* prob; uint8_t* fire; float* logits;   // [C][T], nullable
     int32_t* exit_layer; uint32_t* fire_mask;    // [T], nullable
     uint64_t* arrive;     // [T] arrival words (see report_and_select), zero on entry and on exit
-    float* part;          // [C][S][T][kPartStride]
+    float* part;          // [C][S][T][halves*128 + 4]: partial pre-activations, then the partial sum of squares
     uint32_t* counter;    // [C], zero on entry, zero on exit
     CheckpointTable tab;
 };
@@ -34,7 +36,7 @@ struct DecodeParams {
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeSlice = 128;    // k values per workgroup
 constexpr int kDecodeTB = 8;         // tokens per pass
-constexpr int kPartStride = kBottleneck + 4;   // 128 partial pre-activations, the partial sum of squares, pad to 16 bytes
+constexpr int kPartPad = 4;          // the partial sum of squares, padded to 16 bytes
 
 template <int DT> __device__ __forceinline__ void chunk_to_f32(u32x4 c, float* out);
 template <> __device__ __forceinline__ void chunk_to_f32<kF32>(u32x4 c, float* out) {
@@ -54,7 +56,9 @@ template <> __device__ __forceinline__ void chunk_to_f32<kBF16>(u32x4 c, float* 
     }
 }
 
-template <int DT>
+// kHalves = p.halves as a compile-time value (1 or 2): the width-128 kernel carries no code or
+// registers for a second column half.
+template <int DT, int kHalves>
 __global__ __launch_bounds__(kDecodeThreads) void tide_decode_kernel(const DecodeParams p) {
     constexpr int E = Storage<DT>::kElems;
     constexpr int kChunksPerTok = kDecodeSlice / E;          // 16 or 32 lanes share a token
@@ -67,19 +71,26 @@ __global__ __launch_bounds__(kDecodeThreads) void tide_decode_kernel(const Decod
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // consecutive workgroup ids land on consecutive XCDs: keep one checkpoint's weights on
     // one XCD (and in its L2 across calls) whenever the counts allow it
-    const int nblk = p.C * p.S;
+    const int nblk = p.C * p.S * kHalves;
     const int per_xcd = (nblk + 7) >> 3;
     const int work = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (work >= nblk) return;
-    const int c = work / p.S, s = work - c * p.S;
+    const int c = work / (p.S * kHalves);
+    const int rest = work - c * p.S * kHalves;
+    const int s = rest / kHalves, half = rest - s * kHalves;
     const int k0 = s * kDecodeSlice;
+    constexpr int part_stride = kHalves * kBottleneck + kPartPad;
 
-    // ---- this thread's weights: rows k0 + kk + 8*i, columns 4*jq .. 4*jq+3 ----
+    // ---- this thread's weights: rows k0 + kk + 8*i, columns 4*jq .. 4*jq+3 of this half ----
     const int kk = tid >> 5, jq = tid & 31;
-    const float* w = p.W1 + ((size_t)c * p.d + k0 + kk) * kBottleneck + 4 * jq;
+    const bool live = half * kBottleneck + 4 * jq < p.b;       // columns beyond the width: zeros
+    const float* w = p.W1 + ((size_t)c * p.d + k0 + kk) * p.b + half * kBottleneck + 4 * jq;
     f32x4 wreg[kLoads];
 #pragma unroll
-    for (int i = 0; i < kLoads; ++i) wreg[i] = *reinterpret_cast<const f32x4*>(w + (size_t)8 * i * kBottleneck);
+    for (int i = 0; i < kLoads; ++i) {
+        wreg[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (live) wreg[i] = *reinterpret_cast<const f32x4*>(w + (size_t)8 * i * p.b);
+    }
 
     const char* base = p.hidden + (int64_t)c * p.ckpt_stride_bytes + (int64_t)k0 * Storage<DT>::kBytes;
     const float* g = p.gamma ? p.gamma + (size_t)c * p.d + k0 : nullptr;
@@ -132,13 +143,13 @@ __global__ __launch_bounds__(kDecodeThreads) void tide_decode_kernel(const Decod
         {
             const int tl = tid >> 5, q = tid & 31;
             if (tl < nt) {
-                float* dst = p.part + (((size_t)c * p.S + s) * p.T + t0 + tl) * kPartStride;
+                float* dst = p.part + (((size_t)c * p.S + s) * p.T + t0 + tl) * part_stride;
                 f32x4 v;
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     v[j] = (red[0][tl][4 * q + j] + red[1][tl][4 * q + j]) + (red[2][tl][4 * q + j] + red[3][tl][4 * q + j]);
-                stage_store4(dst + 4 * q, v);
-                if (q == 0) stage_store(dst + kBottleneck, ss_lds[tl]);
+                stage_store4(dst + half * kBottleneck + 4 * q, v);
+                if (q == 0 && half == 0) stage_store(dst + kHalves * kBottleneck, ss_lds[tl]);
             }
         }
         __syncthreads();
@@ -146,38 +157,53 @@ __global__ __launch_bounds__(kDecodeThreads) void tide_decode_kernel(const Decod
 
     // ---- last workgroup of this checkpoint finishes the router ----
     stage_writes_done();
-    if (!last_arrival(p.counter + c, (uint32_t)p.S, &flag)) return;
+    if (!last_arrival(p.counter + c, (uint32_t)(p.S * kHalves), &flag)) return;
 
     {
-        const int tl = tid >> 5, q = tid & 31;          // 8 tokens x 32 column quads per pass
-        f32x4 b1v = {0, 0, 0, 0};
-        if (p.b1) b1v = *reinterpret_cast<const f32x4*>(p.b1 + c * kBottleneck + 4 * q);
-        const f32x4 w2v = *reinterpret_cast<const f32x4*>(p.w2 + c * kBottleneck + 4 * q);
-        const float* pc = p.part + (size_t)c * p.S * p.T * kPartStride;
+        const int tl = tid >> 5, q = tid & 31;          // 8 tokens x 32 column quads (per half) per pass
+        f32x4 b1v[kHalves], w2v[kHalves];
+#pragma unroll
+        for (int hf = 0; hf < kHalves; ++hf) {
+            const int col = hf * kBottleneck + 4 * q;
+            b1v[hf] = f32x4{0, 0, 0, 0};
+            w2v[hf] = f32x4{0, 0, 0, 0};
+            if (col < p.b) {
+                if (p.b1) b1v[hf] = *reinterpret_cast<const f32x4*>(p.b1 + c * p.b + col);
+                w2v[hf] = *reinterpret_cast<const f32x4*>(p.w2 + c * p.b + col);
+            }
+        }
+        const float* pc = p.part + (size_t)c * p.S * p.T * part_stride;
         for (int t0 = 0; t0 < p.T; t0 += kDecodeTB) {
             const int t = t0 + tl;
             const bool valid = t < p.T;
-            f32x4 a = {0, 0, 0, 0};
+            f32x4 a[kHalves];
             float ssum = 0.0f;
             constexpr int kBatch = 32;                  // partials in flight per thread
-            for (int s0 = 0; s0 < p.S; s0 += kBatch) {
-                f32x4 v[kBatch];
 #pragma unroll
-                for (int u = 0; u < kBatch; ++u) {
-                    v[u] = f32x4{0, 0, 0, 0};
-                    if (valid && s0 + u < p.S)
-                        v[u] = stage_load4(pc + ((size_t)(s0 + u) * p.T + t) * kPartStride + 4 * q);
+            for (int hf = 0; hf < kHalves; ++hf) {
+                a[hf] = f32x4{0, 0, 0, 0};
+                for (int s0 = 0; s0 < p.S; s0 += kBatch) {
+                    f32x4 v[kBatch];
+#pragma unroll
+                    for (int u = 0; u < kBatch; ++u) {
+                        v[u] = f32x4{0, 0, 0, 0};
+                        if (valid && s0 + u < p.S)
+                            v[u] = stage_load4(pc + ((size_t)(s0 + u) * p.T + t) * part_stride + hf * kBottleneck + 4 * q);
+                    }
+                    float sv = 0.0f;
+                    if (hf == 0 && valid && s0 + q < p.S)
+                        sv = stage_load(pc + ((size_t)(s0 + q) * p.T + t) * part_stride + kHalves * kBottleneck);
+#pragma unroll
+                    for (int u = 0; u < kBatch; ++u) a[hf] += v[u];
+                    if (hf == 0) ssum += xor_reduce_sum<5>(sv);          // fixed order: deterministic
                 }
-                float sv = 0.0f;
-                if (valid && s0 + q < p.S) sv = stage_load(pc + ((size_t)(s0 + q) * p.T + t) * kPartStride + kBottleneck);
-#pragma unroll
-                for (int u = 0; u < kBatch; ++u) a += v[u];
-                ssum += xor_reduce_sum<5>(sv);          // fixed order: deterministic
             }
             const float r = 1.0f / sqrtf(ssum / (float)p.d + p.eps);
             float term = 0.0f;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) term += w2v[j] * silu_f32(fmaf(r, a[j], b1v[j]));
+            for (int hf = 0; hf < kHalves; ++hf)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) term += w2v[hf][j] * silu_f32(fmaf(r, a[hf][j], b1v[hf][j]));
             term = xor_reduce_sum<5>(term);
             if (valid && q == 0) {
                 const float z = p.tab.b2[c] + term;

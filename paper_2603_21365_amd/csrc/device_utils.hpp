@@ -170,6 +170,30 @@ __device__ __forceinline__ void router_epilogue(const f32x16 (&acc)[kBlocks], co
     }
 }
 
+// The same for a wave that owns two column blocks (bottleneck width 256: columns 32w + l%32 of
+// each 128-column half): the two blocks' terms are added per element before the one reduction.
+template <int kBlocks>
+__device__ __forceinline__ void router_epilogue2(const f32x16 (&acc0)[kBlocks], const f32x16 (&acc1)[kBlocks],
+                                                 const float* inv_rms, float* z_part_wave, float b1c0, float w2c0,
+                                                 float b1c1, float w2c1, int lane) {
+    const int h = lane >> 5;
+    const int vsel = (lane >> 1) & 15;
+#pragma unroll
+    for (int b = 0; b < kBlocks; ++b) {
+        float x[16];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 rs = *reinterpret_cast<const f32x4*>(inv_rms + b * 32 + 8 * q + 4 * h);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                x[4 * q + e] = w2c0 * silu_f32(fmaf(rs[e], acc0[b][4 * q + e], b1c0)) +
+                               w2c1 * silu_f32(fmaf(rs[e], acc1[b][4 * q + e], b1c1));
+        }
+        const float total = reduce_scatter16(x, lane);
+        if (!(lane & 1)) z_part_wave[b * 32 + 8 * (vsel >> 2) + 4 * h + (vsel & 3)] = total;
+    }
+}
+
 // Values that another workgroup, possibly on another XCD, reads back within the same launch
 // are written and read with device-scope relaxed atomics: such accesses go straight to the
 // level where all XCDs agree, so no cache write-back or invalidate is needed.  (A device-scope

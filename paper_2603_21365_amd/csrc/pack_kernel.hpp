@@ -8,6 +8,8 @@
 // B operand of one matrix-core step as one contiguous KiB.  fp32: two such planes of bf16, the
 // "hi" plane (d*16 chunks) followed by the "mid" plane, with W1' = hi + mid + O(2^-17)
 // (see split_bf16) -- the same number of bytes as fp32 weights.
+// A bottleneck of width b is packed as ceil(b/128) such 128-column halves, one after the
+// other; columns at and beyond b (width 64) are zeros.
 #pragma once
 #include "device_utils.hpp"
 
@@ -15,21 +17,24 @@ namespace tide {
 
 // One workgroup per 16-k group: the group's 16 x 128 weights are one contiguous 8 KiB of W1,
 // read with coalesced 16-byte loads, scaled by gamma and transposed through LDS so that every
-// thread then assembles one output chunk (two for fp32: hi and mid plane).  grid = (d/16, C).
+// thread then assembles one output chunk (two for fp32: hi and mid plane).
+// grid = (d/16, C * halves); chunks_per_half = 16-byte chunks of one packed 128-column half.
 constexpr int kPackThreads = 256;
 
 template <int DT>
 __global__ __launch_bounds__(kPackThreads) void tide_pack_kernel(const float* __restrict__ gamma, const float* __restrict__ W1,
-                                                                 u32x4* __restrict__ packed, int d, int chunks_per_ckpt) {
+                                                                 u32x4* __restrict__ packed, int d, int chunks_per_half,
+                                                                 int b, int halves) {
     __shared__ float tile[16][kBottleneck + 4];            // +4: rows land on different banks
-    const int c = blockIdx.y, G = blockIdx.x, tid = threadIdx.x;
-    const float* w = W1 + ((size_t)c * d + 16 * G) * kBottleneck;
+    const int c = blockIdx.y / halves, half = blockIdx.y - c * halves, G = blockIdx.x, tid = threadIdx.x;
+    const float* w = W1 + ((size_t)c * d + 16 * G) * b + half * kBottleneck;
     const float* g = gamma ? gamma + (size_t)c * d + 16 * G : nullptr;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int q = tid + i * kPackThreads;              // float4 index within the 16 x 128 tile
         const int k = q >> 5, col4 = (q & 31) * 4;
-        f32x4 v = reinterpret_cast<const f32x4*>(w)[q];
+        f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (half * kBottleneck + col4 < b) v = *reinterpret_cast<const f32x4*>(w + (size_t)k * b + col4);
         const float gk = g ? g[k] : 1.0f;
 #pragma unroll
         for (int e = 0; e < 4; ++e) tile[k][col4 + e] = v[e] * gk;
@@ -40,7 +45,7 @@ __global__ __launch_bounds__(kPackThreads) void tide_pack_kernel(const float* __
     float v[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = tile[8 * h + e][col];
-    u32x4* out = packed + (size_t)c * chunks_per_ckpt + (size_t)G * 256 + tid;
+    u32x4* out = packed + (size_t)blockIdx.y * chunks_per_half + (size_t)G * 256 + tid;
     if constexpr (DT == kF16) {
         f16x8 o;
 #pragma unroll

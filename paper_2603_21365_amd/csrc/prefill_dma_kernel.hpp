@@ -96,7 +96,9 @@ struct TileWalk {
     __device__ WorkItem following() const { return item(i + 1); }
 };
 
-template <int DT, int kRowsM>
+// kCB = 128-column halves of the bottleneck each consumer wave covers: 1 (width 64 or 128) or 2
+// (width 256: wave w owns columns 32w..32w+31 of both halves, twice the accumulators).
+template <int DT, int kRowsM, int kCB>
 __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const PrefillParams p) {
     typedef __attribute__((address_space(3))) char lds_char;
     typedef __attribute__((address_space(1))) const char glb_char;
@@ -119,7 +121,8 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
         return (int)(((unsigned)it.tile * 5u + (unsigned)it.row_off) % (unsigned)(ntile / split_of(it)));
     };
 
-    TileWalk<kBlocks> walk(p.total_tiles, ntile);
+    // (two column halves: the tiles of the last round are not cut -- passing one k-tile rules it out)
+    TileWalk<kBlocks> walk(p.total_tiles, kCB == 1 ? ntile : 1);
     if (!walk.valid()) return;
 
     if (wave >= kDmaConsumers) {
@@ -207,13 +210,17 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
     const int y16 = ((lane >> 5) ^ (r & 15)) << 4;
     const int yf16 = (((lane >> 5) << 1) ^ (r & 15)) << 4;     // fp32 rows: see the k loop
     const size_t ckpt_chunks = (size_t)p.d * kBottleneck / Storage<DT>::kElems;
-    auto b_pointer = [&](const WorkItem& it) {
-        return p.packed + (size_t)(it.tile / p.tiles_per_ckpt) * ckpt_chunks + wave * 64 + lane;
+    auto b_pointer = [&](const WorkItem& it) {           // first (or only) column half of the item's checkpoint
+        return p.packed + (size_t)(it.tile / p.tiles_per_ckpt) * kCB * ckpt_chunks + wave * 64 + lane;
     };
     constexpr int kMmaGroups = Compute<DT>::kMmaGroups, kPlanes = Compute<DT>::kPlanes;
     constexpr int kFrags = kMmaGroups * kPlanes;   // W1' fragments of one k-tile: 8 either way
     const size_t plane_chunks = (size_t)p.d * 16;
     u32x4 breg[kFrags];                            // [g * kPlanes + plane]
+    // Two column halves: half a k-tile of fragments per column half, refilled half a k-tile
+    // ahead (the same number of matrix instructions between fetch and use as with one half).
+    constexpr int kHalfG = kMmaGroups / 2;
+    u32x4 bh0[kCB == 2 ? kHalfG * kPlanes : 1], bh1[kCB == 2 ? kHalfG * kPlanes : 1];
     auto b_fragment = [&](const u32x4* base, int kt, int g, int pl) {
         return base[pl * plane_chunks + (size_t)(kt * kMmaGroups + g) * 256];
     };
@@ -222,10 +229,20 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
         const WorkItem first = walk.current();
         const u32x4* b0 = b_pointer(first);
         const int kt0 = first_stage(first) * split_of(first);
+        if constexpr (kCB == 1) {
 #pragma unroll
-        for (int g = 0; g < kMmaGroups; ++g)
+            for (int g = 0; g < kMmaGroups; ++g)
 #pragma unroll
-            for (int pl = 0; pl < kPlanes; ++pl) breg[g * kPlanes + pl] = b_fragment(b0, kt0, g, pl);
+                for (int pl = 0; pl < kPlanes; ++pl) breg[g * kPlanes + pl] = b_fragment(b0, kt0, g, pl);
+        } else {
+#pragma unroll
+            for (int g = 0; g < kHalfG; ++g)
+#pragma unroll
+                for (int pl = 0; pl < kPlanes; ++pl) {
+                    bh0[g * kPlanes + pl] = b_fragment(b0, kt0, g, pl);
+                    bh1[g * kPlanes + pl] = b_fragment(b0 + ckpt_chunks, kt0, g, pl);
+                }
+        }
     }
     int stage = 0;                                 // global stage counter -> ring slot
 
@@ -240,10 +257,12 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
         const u32x4* bptr = b_pointer(it);
 
         f32x16 acc[kActive];
+        f32x16 acc1[kCB == 2 ? kActive : 1];        // second column half
         float ssq[kActive];
 #pragma unroll
         for (int b = 0; b < kActive; ++b) {
             acc[b] = f32x16{0};
+            if constexpr (kCB == 2) acc1[b] = f32x16{0};
             ssq[b] = 0.0f;
         }
         // The matrix work of one k-tile: A fragments of the kActive blocks from `st`, W1' fragments
@@ -297,7 +316,93 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
             }
         };
 
-        if constexpr (kSub == 1) {
+        // The same with two column halves: k-tile kt of this item (fragments at cur), then the
+        // fragment slot of group g is refilled with group g + kHalfG of the same k-tile, or
+        // group g - kHalfG of (nb, kn) if refill is set.
+        auto k_tile2 = [&](const char* st, const u32x4* cur, int kt, const u32x4* nb, int kn, auto refill) {
+#pragma unroll
+            for (int g = 0; g < kMmaGroups; ++g) {
+                constexpr int kSlotStride = kPlanes;
+                const int slot = (g % kHalfG) * kSlotStride;
+                if constexpr (DT == kF32) {
+                    u32x4 ah[kActive], am[kActive];
+                    float sq[kActive];
+#pragma unroll
+                    for (int b = 0; b < kActive; ++b) {
+                        const char* src = st + b * 32 * kTileBytes;
+                        const u32x4 c0 = *reinterpret_cast<const u32x4*>(src + (yf16 ^ (g << 6)));
+                        const u32x4 c1 = *reinterpret_cast<const u32x4*>(src + (yf16 ^ (g << 6) ^ 16));
+                        float x[8] = {__uint_as_float(c0.x), __uint_as_float(c0.y), __uint_as_float(c0.z), __uint_as_float(c0.w),
+                                      __uint_as_float(c1.x), __uint_as_float(c1.y), __uint_as_float(c1.z), __uint_as_float(c1.w)};
+                        __bf16 hi[8], mid[8];
+                        split_bf16(x, 8, hi, mid);
+                        bf16x8 h8, m8;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) { h8[e] = hi[e]; m8[e] = mid[e]; }
+                        ah[b] = __builtin_bit_cast(u32x4, h8);
+                        am[b] = __builtin_bit_cast(u32x4, m8);
+                        sq[b] = chunk_sumsq<kF32>(c1, chunk_sumsq<kF32>(c0, 0.0f));
+                    }
+#pragma unroll
+                    for (int b = 0; b < kActive; ++b) {
+                        acc[b] = mma_k16_split(ah[b], am[b], bh0[slot], bh0[slot + 1], acc[b]);
+                        acc1[b] = mma_k16_split(ah[b], am[b], bh1[slot], bh1[slot + 1], acc1[b]);
+                    }
+                    if (g == wave) {
+#pragma unroll
+                        for (int b = 0; b < kActive; ++b) ssq[b] += sq[b];
+                    }
+                } else {
+                    u32x4 a[kActive];
+#pragma unroll
+                    for (int b = 0; b < kActive; ++b)
+                        a[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + (y16 ^ (g << 5)));
+#pragma unroll
+                    for (int b = 0; b < kActive; ++b) {
+                        acc[b] = mma_k16<DT>(a[b], bh0[slot], acc[b]);
+                        acc1[b] = mma_k16<DT>(a[b], bh1[slot], acc1[b]);
+                    }
+                    if ((g & 3) == wave) {
+#pragma unroll
+                        for (int b = 0; b < kActive; ++b) ssq[b] = chunk_sumsq<DT>(a[b], ssq[b]);
+                    }
+                }
+                if (g < kHalfG) {
+#pragma unroll
+                    for (int pl = 0; pl < kPlanes; ++pl) {
+                        bh0[slot + pl] = b_fragment(cur, kt, g + kHalfG, pl);
+                        bh1[slot + pl] = b_fragment(cur + ckpt_chunks, kt, g + kHalfG, pl);
+                    }
+                } else if (decltype(refill)::value) {
+#pragma unroll
+                    for (int pl = 0; pl < kPlanes; ++pl) {
+                        bh0[slot + pl] = b_fragment(nb, kn, g - kHalfG, pl);
+                        bh1[slot + pl] = b_fragment(nb + ckpt_chunks, kn, g - kHalfG, pl);
+                    }
+                }
+            }
+        };
+
+        if constexpr (kCB == 2) {
+            // ---- full tile, two column halves (items are never cut here)
+            int kt = first_stage(it);
+            auto consume = [&](const u32x4* nb, int kn, auto refill) {
+                ring_barrier();
+                k_tile2(ring + (stage % kDmaStages) * kStageBytes + a_base, bptr, kt, nb, kn, refill);
+                ++stage;
+            };
+            for (int k = 0; k + 1 < ntile; ++k) {
+                const int kn = kt + 1 >= ntile ? 0 : kt + 1;
+                consume(bptr, kn, std::true_type{});
+                kt = kn;
+            }
+            if (walk.has_more()) {
+                const WorkItem nxt = walk.following();
+                consume(b_pointer(nxt), first_stage(nxt), std::true_type{});
+            } else {
+                consume(bptr, 0, std::false_type{});
+            }
+        } else if constexpr (kSub == 1) {
             // ---- full tile: one k-tile per stage, W1' one k-tile ahead.  Each call site is
             // straight-line code, so the W1' wait counts stay exact (8 loads in flight).
             int kt = first_stage(it);
@@ -368,10 +473,19 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
         __syncthreads();
 
         // ---- epilogue: a = r*acc + b1; SiLU; dot with w2 over this wave's 32 columns ----
+        // (columns at and beyond the bottleneck width are zero padding: their w2 is zero)
         {
             const int col = 32 * wave + (lane & 31);
-            router_epilogue<kActive>(acc, inv_rms, z_part + wave * kRowsM, p.b1 ? p.b1[c * kBottleneck + col] : 0.0f,
-                                     p.w2[c * kBottleneck + col], lane);
+            const float b1c = (p.b1 && col < p.b) ? p.b1[c * p.b + col] : 0.0f;
+            const float w2c = col < p.b ? p.w2[c * p.b + col] : 0.0f;
+            if constexpr (kCB == 2) {
+                const int col1 = col + kBottleneck;
+                router_epilogue2<kActive>(acc, acc1, inv_rms, z_part + wave * kRowsM, b1c, w2c,
+                                          (p.b1 && col1 < p.b) ? p.b1[c * p.b + col1] : 0.0f,
+                                          col1 < p.b ? p.w2[c * p.b + col1] : 0.0f, lane);
+            } else {
+                router_epilogue<kActive>(acc, inv_rms, z_part + wave * kRowsM, b1c, w2c, lane);
+            }
         }
         __syncthreads();
 

@@ -27,10 +27,11 @@ struct PrefillParams {
     const char* hidden;        // storage-typed rows
     int64_t ckpt_stride_bytes;
     int64_t row_stride_bytes;
-    const u32x4* packed;       // [C][d*128 elements] packed W1'
-    const float* b1;           // [C][128] or null
-    const float* w2;           // [C][128]
+    const u32x4* packed;       // [C][halves][d*128 elements] packed W1' (halves = ceil(b/128))
+    const float* b1;           // [C][b] or null
+    const float* w2;           // [C][b]
     int C, T, d;
+    int b;                     // bottleneck width: 64, 128 or 256 (columns >= b of the last half are zero padding)
     int tiles_per_ckpt;        // ceil(T / kRows)
     int total_tiles;           // C * tiles_per_ckpt
     float eps;
@@ -202,8 +203,9 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const 
 
     // ---- epilogue: a = r*acc + b1; SiLU; dot with w2 over this wave's 32 columns ----
     const int col = 32 * wave + (lane & 31);
-    router_epilogue<2>(acc, row_ss, z_part[wave], p.b1 ? p.b1[c * kBottleneck + col] : 0.0f,
-                       p.w2[c * kBottleneck + col], lane);
+    // columns at and beyond the bottleneck width (64) are zero padding: their w2 is zero
+    router_epilogue<2>(acc, row_ss, z_part[wave], (p.b1 && col < p.b) ? p.b1[c * p.b + col] : 0.0f,
+                       col < p.b ? p.w2[c * p.b + col] : 0.0f, lane);
     __syncthreads();
 
     if (tid < kRows) {

@@ -101,7 +101,9 @@ float threshold_logit(float theta) {
 }
 
 // Everything both entry points must check before anything is enqueued.
-int check_common(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t ckpt_stride,
+bool supported_bottleneck(int64_t b) { return b == 64 || b == 128 || b == 256; }
+
+int check_common(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int64_t ckpt_stride,
                  int64_t row_stride, const void* weights, const float* w2, float eps) {
     if (dtype != TIDE_F32 && dtype != TIDE_F16 && dtype != TIDE_BF16)
         return fail(TIDE_ERR_INVALID_ARG, "dtype %d is not a tide_dtype_t", dtype);
@@ -111,6 +113,8 @@ int check_common(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d,
     if (d <= 0) return fail(TIDE_ERR_INVALID_ARG, "d = %lld must be positive", (long long)d);
     if (d % 128 != 0 || d < 128 || d > 16384)
         return fail(TIDE_ERR_UNSUPPORTED, "d = %lld: supported sizes are multiples of 128 in [128, 16384]", (long long)d);
+    if (!supported_bottleneck(b))
+        return fail(TIDE_ERR_UNSUPPORTED, "bottleneck width b = %lld: supported widths are 64, 128 and 256", (long long)b);
     if (C * T > (int64_t)1 << 30)
         return fail(TIDE_ERR_UNSUPPORTED, "T = %lld is too large for one call", (long long)T);
     if (row_stride < d) return fail(TIDE_ERR_INVALID_ARG, "row_stride %lld < d %lld", (long long)row_stride, (long long)d);
@@ -154,11 +158,15 @@ struct Outputs {
     uint32_t* fire_mask;
 };
 
-int launch_pack(int dtype, int64_t C, int64_t d, const float* gamma, const float* W1, void* packed, hipStream_t st) {
-    const int chunks = (int)(d * kBottleneck * elem_bytes(dtype) / 16);
-    dim3 grid((unsigned)(d / 16), (unsigned)C);
+int halves_of(int64_t b) { return (int)((b + kBottleneck - 1) / kBottleneck); }
+
+int launch_pack(int dtype, int64_t C, int64_t d, int64_t b, const float* gamma, const float* W1, void* packed, hipStream_t st) {
+    const int chunks = (int)(d * kBottleneck * elem_bytes(dtype) / 16);      // of one 128-column half
+    const int halves = halves_of(b);
+    dim3 grid((unsigned)(d / 16), (unsigned)(C * halves));
     by_dtype(dtype, [&](auto dt) {
-        hipLaunchKernelGGL((tide_pack_kernel<decltype(dt)::value>), grid, dim3(kPackThreads), 0, st, gamma, W1, (u32x4*)packed, (int)d, chunks);
+        hipLaunchKernelGGL((tide_pack_kernel<decltype(dt)::value>), grid, dim3(kPackThreads), 0, st, gamma, W1, (u32x4*)packed, (int)d,
+                           chunks, (int)b, halves);
         return 0;
     });
     TIDE_HIP(hipGetLastError());
@@ -168,25 +176,26 @@ int launch_pack(int dtype, int64_t C, int64_t d, const float* gamma, const float
 // The streaming kernels use more LDS than the default per-kernel limit: raise it once.
 // They are persistent: at most one (128-row) or two (64-row) workgroups per CU, each walking
 // a list of tiles.
-template <int DT, int M> int launch_dma(unsigned grid, hipStream_t st, const PrefillParams& p) {
+template <int DT, int M, int CB> int launch_dma(unsigned grid, hipStream_t st, const PrefillParams& p) {
     static bool raised[kMaxDevices] = {};
     static int cus[kMaxDevices] = {};
     int dev = 0;
     TIDE_HIP(hipGetDevice(&dev));
     constexpr int lds = dma_lds_bytes<M>();
     if (!raised[dev]) {
-        TIDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&tide_prefill_dma_kernel<DT, M>),
+        TIDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&tide_prefill_dma_kernel<DT, M, CB>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds));
         TIDE_HIP(hipDeviceGetAttribute(&cus[dev], hipDeviceAttributeMultiprocessorCount, dev));
         raised[dev] = true;
     }
-    const unsigned resident = (unsigned)(cus[dev] > 8 ? cus[dev] & ~7 : 8) * (M == 128 ? 1u : 2u);
+    // (the two-halves kernel needs more than the 168 registers that let three waves share a SIMD)
+    const unsigned resident = (unsigned)(cus[dev] > 8 ? cus[dev] & ~7 : 8) * ((M == 128 || CB == 2) ? 1u : 2u);
     if (grid > resident) grid = resident;      // both are multiples of 8
-    hipLaunchKernelGGL((tide_prefill_dma_kernel<DT, M>), dim3(grid), dim3(kDmaThreads), lds, st, p);
+    hipLaunchKernelGGL((tide_prefill_dma_kernel<DT, M, CB>), dim3(grid), dim3(kDmaThreads), lds, st, p);
     return TIDE_OK;
 }
 
-int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t ckpt_stride,
+int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int64_t ckpt_stride,
                    int64_t row_stride, const void* packed, float eps, const float* b1, const float* w2,
                    const CheckpointTable& tab, int32_t min_layer, int32_t no_exit, const Outputs& o, hipStream_t st) {
     PrefillParams p;
@@ -201,6 +210,8 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
     p.C = (int)C;
     p.T = (int)T;
     p.d = (int)d;
+    p.b = (int)b;
+    const bool two_halves = halves_of(b) == 2;
     // Rows per workgroup: 128 (each W1' fragment fetched once per 128 rows) when that still
     // gives every CU a workgroup, else 64; g_prefill_form overrides for tests and tuning.
     const int64_t tiles128 = C * ((T + 127) / 128);
@@ -210,8 +221,12 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
     // fp32 rows are split into bf16 terms before the matrix cores: the register-ring form does
     // that once per workgroup on the way into LDS, the streaming form once per consumer wave,
     // so the ring form is the faster one for fp32 (measured 4.1 vs 3.6 TB/s).
-    const bool ring_form = g_prefill_form == 3 || (g_prefill_form == 0 && dtype == TIDE_F32);
+    // Width 256 (two column halves per wave) exists in the streaming form with 64 rows per
+    // workgroup only.  With 128 rows the accumulators (256 values per lane) leave room for half a
+    // k-tile of W1' in flight, too little to cover the L2 round trip: measured slower.
+    const bool ring_form = !two_halves && (g_prefill_form == 3 || (g_prefill_form == 0 && dtype == TIDE_F32));
     if (ring_form) rows_per_wg = kRows;
+    if (two_halves) rows_per_wg = 64;
     p.tiles_per_ckpt = (int)((T + rows_per_wg - 1) / rows_per_wg);
     p.total_tiles = p.C * p.tiles_per_ckpt;
     p.eps = eps;
@@ -238,10 +253,12 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
                 hipLaunchKernelGGL((tide_prefill_kernel<DT, kMaxDepth>), dim3(grid), dim3(kPrefillThreads), 0, st, p);
             else
                 hipLaunchKernelGGL((tide_prefill_kernel<DT, 1>), dim3(grid), dim3(kPrefillThreads), 0, st, p);
+        } else if (two_halves) {
+            rc = launch_dma<DT, 64, 2>(grid, st, p);
         } else if (rows_per_wg == 128) {
-            rc = launch_dma<DT, 128>(grid, st, p);
+            rc = launch_dma<DT, 128, 1>(grid, st, p);
         } else {
-            rc = launch_dma<DT, 64>(grid, st, p);
+            rc = launch_dma<DT, 64, 1>(grid, st, p);
         }
         return 0;
     });
@@ -250,7 +267,7 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
     return TIDE_OK;
 }
 
-int launch_decode(Workspace& ws, const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t ckpt_stride,
+int launch_decode(Workspace& ws, const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int64_t ckpt_stride,
                   int64_t row_stride, const float* gamma, const float* W1, float eps, const float* b1, const float* w2,
                   const CheckpointTable& tab, int32_t min_layer, int32_t no_exit, const Outputs& o, hipStream_t st) {
     DecodeParams p;
@@ -267,6 +284,8 @@ int launch_decode(Workspace& ws, const void* hidden, int dtype, int64_t C, int64
     p.T = (int)T;
     p.d = (int)d;
     p.S = (int)(d / kDecodeSlice);
+    p.b = (int)b;
+    p.halves = halves_of(b);
     p.eps = eps;
     p.min_layer = min_layer;
     p.no_exit = no_exit;
@@ -279,7 +298,7 @@ int launch_decode(Workspace& ws, const void* hidden, int dtype, int64_t C, int64
     int rc = reserve(ws.counters, kCounterSlots * sizeof(uint32_t), true);
     if (rc) return rc;
     p.counter = (uint32_t*)ws.counters.ptr;
-    rc = reserve(ws.part, (size_t)C * p.S * T * kPartStride * sizeof(float), false);
+    rc = reserve(ws.part, (size_t)C * p.S * T * (p.halves * kBottleneck + kPartPad) * sizeof(float), false);
     if (rc) return rc;
     p.part = (float*)ws.part.ptr;
     if (o.exit_layer) {
@@ -287,10 +306,13 @@ int launch_decode(Workspace& ws, const void* hidden, int dtype, int64_t C, int64
         if (rc) return rc;
         p.arrive = (uint64_t*)ws.arrive.ptr;
     }
-    const int nblk = p.C * p.S;
+    const int nblk = p.C * p.S * p.halves;
     const unsigned grid = 8u * (unsigned)((nblk + 7) / 8);
     by_dtype(dtype, [&](auto dt) {
-        hipLaunchKernelGGL((tide_decode_kernel<decltype(dt)::value>), dim3(grid), dim3(kDecodeThreads), 0, st, p);
+        if (p.halves == 2)
+            hipLaunchKernelGGL((tide_decode_kernel<decltype(dt)::value, 2>), dim3(grid), dim3(kDecodeThreads), 0, st, p);
+        else
+            hipLaunchKernelGGL((tide_decode_kernel<decltype(dt)::value, 1>), dim3(grid), dim3(kDecodeThreads), 0, st, p);
         return 0;
     });
     TIDE_HIP(hipGetLastError());
@@ -304,7 +326,7 @@ bool use_decode(int64_t T) {
 }
 
 // Shared body of the four compute entry points.  Exactly one of (W1) / (packed) is given.
-int run(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t ckpt_stride, int64_t row_stride,
+int run(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int64_t ckpt_stride, int64_t row_stride,
         const float* gamma, const float* W1, const void* packed, float eps, const float* b1, const float* w2,
         const CheckpointTable& tab, int32_t min_layer, int32_t no_exit, const Outputs& o, void* stream) {
     if (T == 0) return TIDE_OK;
@@ -314,16 +336,16 @@ int run(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t 
     int rc = current_workspace(&ws);
     if (rc) return rc;
     if (W1 && use_decode(T))
-        return launch_decode(*ws, hidden, dtype, C, T, d, ckpt_stride, row_stride, gamma, W1, eps, b1, w2, tab,
+        return launch_decode(*ws, hidden, dtype, C, T, d, b, ckpt_stride, row_stride, gamma, W1, eps, b1, w2, tab,
                              min_layer, no_exit, o, st);
     if (W1) {
-        rc = reserve(ws->packed, (size_t)C * tide_packed_router_bytes(dtype, d), false);
+        rc = reserve(ws->packed, (size_t)C * tide_packed_router_bytes(dtype, d, b), false);
         if (rc) return rc;
-        rc = launch_pack(dtype, C, d, gamma, W1, ws->packed.ptr, st);
+        rc = launch_pack(dtype, C, d, b, gamma, W1, ws->packed.ptr, st);
         if (rc) return rc;
         packed = ws->packed.ptr;
     }
-    return launch_prefill(*ws, hidden, dtype, C, T, d, ckpt_stride, row_stride, packed, eps, b1, w2, tab, min_layer,
+    return launch_prefill(*ws, hidden, dtype, C, T, d, b, ckpt_stride, row_stride, packed, eps, b1, w2, tab, min_layer,
                           no_exit, o, st);
 }
 
@@ -335,39 +357,41 @@ int tide_version(void) { return 100; }
 
 const char* tide_last_error(void) { return g_err; }
 
-size_t tide_packed_router_bytes(int dtype, int64_t d) {
+size_t tide_packed_router_bytes(int dtype, int64_t d, int64_t b) {
     if ((dtype != TIDE_F32 && dtype != TIDE_F16 && dtype != TIDE_BF16) || d < 128 || d > 16384 || d % 128) return 0;
-    return (size_t)d * kBottleneck * elem_bytes(dtype);
+    if (!supported_bottleneck(b)) return 0;
+    return (size_t)halves_of(b) * (size_t)d * kBottleneck * elem_bytes(dtype);
 }
 
-int tide_router_pack(int dtype, int64_t C, int64_t d, const float* gamma, const float* W1, void* packed, void* stream) {
+int tide_router_pack(int dtype, int64_t C, int64_t d, int64_t b, const float* gamma, const float* W1, void* packed, void* stream) {
     g_err[0] = 0;
     if (C < 1 || C > TIDE_MAX_CHECKPOINTS) return fail(TIDE_ERR_INVALID_ARG, "C = %lld outside [1, 32]", (long long)C);
-    if (tide_packed_router_bytes(dtype, d) == 0) return fail(TIDE_ERR_UNSUPPORTED, "unsupported dtype %d or d %lld", dtype, (long long)d);
+    if (tide_packed_router_bytes(dtype, d, b) == 0)
+        return fail(TIDE_ERR_UNSUPPORTED, "unsupported dtype %d, d %lld or bottleneck width %lld", dtype, (long long)d, (long long)b);
     if (!W1 || !packed) return fail(TIDE_ERR_INVALID_ARG, "W1 and packed must not be NULL");
     if ((uintptr_t)packed & 15) return fail(TIDE_ERR_ALIGNMENT, "packed must be 16-byte aligned");
-    return launch_pack(dtype, C, d, gamma, W1, packed, (hipStream_t)stream);
+    return launch_pack(dtype, C, d, b, gamma, W1, packed, (hipStream_t)stream);
 }
 
-int tide_router_eval(const void* hidden, int dtype, int64_t T, int64_t d, int64_t row_stride, const float* gamma,
+int tide_router_eval(const void* hidden, int dtype, int64_t T, int64_t d, int64_t b, int64_t row_stride, const float* gamma,
                      float eps, const float* W1, const float* b1, const float* w2, float b2, float threshold,
                      float* prob, uint8_t* fire, float* logit, void* stream) {
     g_err[0] = 0;
-    int rc = check_common(hidden, dtype, 1, T, d, 0, row_stride, W1, w2, eps);
+    int rc = check_common(hidden, dtype, 1, T, d, b, 0, row_stride, W1, w2, eps);
     if (rc) return rc;
     CheckpointTable tab;
     const int32_t id0 = 0;
     rc = fill_table(tab, 1, &b2, &threshold, &id0);
     if (rc) return rc;
     Outputs o{prob, fire, logit, nullptr, nullptr};
-    return run(hidden, dtype, 1, T, d, 0, row_stride, gamma, W1, nullptr, eps, b1, w2, tab, 0, 0, o, stream);
+    return run(hidden, dtype, 1, T, d, b, 0, row_stride, gamma, W1, nullptr, eps, b1, w2, tab, 0, 0, o, stream);
 }
 
-int tide_router_eval_packed(const void* hidden, int dtype, int64_t T, int64_t d, int64_t row_stride,
+int tide_router_eval_packed(const void* hidden, int dtype, int64_t T, int64_t d, int64_t b, int64_t row_stride,
                             const void* packed, float eps, const float* b1, const float* w2, float b2,
                             float threshold, float* prob, uint8_t* fire, float* logit, void* stream) {
     g_err[0] = 0;
-    int rc = check_common(hidden, dtype, 1, T, d, 0, row_stride, packed, w2, eps);
+    int rc = check_common(hidden, dtype, 1, T, d, b, 0, row_stride, packed, w2, eps);
     if (rc) return rc;
     if ((uintptr_t)packed & 15) return fail(TIDE_ERR_ALIGNMENT, "packed must be 16-byte aligned");
     CheckpointTable tab;
@@ -375,33 +399,33 @@ int tide_router_eval_packed(const void* hidden, int dtype, int64_t T, int64_t d,
     rc = fill_table(tab, 1, &b2, &threshold, &id0);
     if (rc) return rc;
     Outputs o{prob, fire, logit, nullptr, nullptr};
-    return run(hidden, dtype, 1, T, d, 0, row_stride, nullptr, nullptr, packed, eps, b1, w2, tab, 0, 0, o, stream);
+    return run(hidden, dtype, 1, T, d, b, 0, row_stride, nullptr, nullptr, packed, eps, b1, w2, tab, 0, 0, o, stream);
 }
 
-int tide_select_exit(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t ckpt_stride,
+int tide_select_exit(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int64_t ckpt_stride,
                      int64_t row_stride, const float* gamma, float eps, const float* W1, const float* b1,
                      const float* w2, const float* b2, const float* threshold, const int32_t* layer_ids,
                      int32_t min_layer, int32_t no_exit_layer, int32_t* exit_layer, float* logits,
                      uint32_t* fire_mask, void* stream) {
     g_err[0] = 0;
-    int rc = check_common(hidden, dtype, C, T, d, ckpt_stride, row_stride, W1, w2, eps);
+    int rc = check_common(hidden, dtype, C, T, d, b, ckpt_stride, row_stride, W1, w2, eps);
     if (rc) return rc;
     CheckpointTable tab;
     rc = fill_table(tab, C, b2, threshold, layer_ids);
     if (rc) return rc;
     if (T > 0 && !exit_layer) return fail(TIDE_ERR_INVALID_ARG, "exit_layer must not be NULL");
     Outputs o{nullptr, nullptr, logits, exit_layer, fire_mask};
-    return run(hidden, dtype, C, T, d, ckpt_stride, row_stride, gamma, W1, nullptr, eps, b1, w2, tab, min_layer,
+    return run(hidden, dtype, C, T, d, b, ckpt_stride, row_stride, gamma, W1, nullptr, eps, b1, w2, tab, min_layer,
                no_exit_layer, o, stream);
 }
 
-int tide_select_exit_packed(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t ckpt_stride,
+int tide_select_exit_packed(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int64_t ckpt_stride,
                             int64_t row_stride, const void* packed, float eps, const float* b1, const float* w2,
                             const float* b2, const float* threshold, const int32_t* layer_ids, int32_t min_layer,
                             int32_t no_exit_layer, int32_t* exit_layer, float* logits, uint32_t* fire_mask,
                             void* stream) {
     g_err[0] = 0;
-    int rc = check_common(hidden, dtype, C, T, d, ckpt_stride, row_stride, packed, w2, eps);
+    int rc = check_common(hidden, dtype, C, T, d, b, ckpt_stride, row_stride, packed, w2, eps);
     if (rc) return rc;
     if ((uintptr_t)packed & 15) return fail(TIDE_ERR_ALIGNMENT, "packed must be 16-byte aligned");
     CheckpointTable tab;
@@ -409,7 +433,7 @@ int tide_select_exit_packed(const void* hidden, int dtype, int64_t C, int64_t T,
     if (rc) return rc;
     if (T > 0 && !exit_layer) return fail(TIDE_ERR_INVALID_ARG, "exit_layer must not be NULL");
     Outputs o{nullptr, nullptr, logits, exit_layer, fire_mask};
-    return run(hidden, dtype, C, T, d, ckpt_stride, row_stride, nullptr, nullptr, packed, eps, b1, w2, tab, min_layer,
+    return run(hidden, dtype, C, T, d, b, ckpt_stride, row_stride, nullptr, nullptr, packed, eps, b1, w2, tab, min_layer,
                no_exit_layer, o, stream);
 }
 
@@ -418,7 +442,7 @@ int tide_exit_project(const void* hidden, int dtype, int64_t C, int64_t T, int64
                       const int32_t* exit_layer, const int32_t* layer_ids, const float* norm_gain, float eps,
                       void* out, int64_t out_row_stride, void* stream) {
     g_err[0] = 0;
-    int rc = check_common(hidden, dtype, C, T, d, ckpt_stride, row_stride, hidden, reinterpret_cast<const float*>(hidden), eps);
+    int rc = check_common(hidden, dtype, C, T, d, kBottleneck, ckpt_stride, row_stride, hidden, reinterpret_cast<const float*>(hidden), eps);
     if (rc) return rc;
     if (T == 0) return TIDE_OK;
     if (!exit_layer || !layer_ids || !out) return fail(TIDE_ERR_INVALID_ARG, "exit_layer, layer_ids (host) and out must not be NULL");
@@ -517,7 +541,7 @@ int tide_cosine_labels(const void* hidden, int dtype, int64_t C, int64_t T, int6
                        int64_t row_stride, const void* final_hidden, int64_t final_row_stride, float tau, float* sim,
                        uint8_t* label, void* stream) {
     g_err[0] = 0;
-    int rc = check_common(hidden, dtype, C, T, d, ckpt_stride, row_stride, hidden, reinterpret_cast<const float*>(hidden), 0.0f);
+    int rc = check_common(hidden, dtype, C, T, d, kBottleneck, ckpt_stride, row_stride, hidden, reinterpret_cast<const float*>(hidden), 0.0f);
     if (rc) return rc;
     if (T == 0) return TIDE_OK;
     if (!final_hidden) return fail(TIDE_ERR_INVALID_ARG, "final_hidden must not be NULL");

@@ -48,15 +48,15 @@ def load_library() -> ctypes.CDLL:
     vp, i64, i32, f32, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_int
     lib.tide_version.restype = ci
     lib.tide_last_error.restype = ctypes.c_char_p
-    lib.tide_router_eval.argtypes = [vp, ci, i64, i64, i64, vp, f32, vp, vp, vp, f32, f32, vp, vp, vp, vp]
-    lib.tide_router_eval_packed.argtypes = [vp, ci, i64, i64, i64, vp, f32, vp, vp, f32, f32, vp, vp, vp, vp]
-    lib.tide_select_exit.argtypes = [vp, ci, i64, i64, i64, i64, i64, vp, f32, vp, vp, vp, vp, vp, vp, i32, i32,
+    lib.tide_router_eval.argtypes = [vp, ci, i64, i64, i64, i64, vp, f32, vp, vp, vp, f32, f32, vp, vp, vp, vp]
+    lib.tide_router_eval_packed.argtypes = [vp, ci, i64, i64, i64, i64, vp, f32, vp, vp, f32, f32, vp, vp, vp, vp]
+    lib.tide_select_exit.argtypes = [vp, ci, i64, i64, i64, i64, i64, i64, vp, f32, vp, vp, vp, vp, vp, vp, i32, i32,
                                      vp, vp, vp, vp]
-    lib.tide_select_exit_packed.argtypes = [vp, ci, i64, i64, i64, i64, i64, vp, f32, vp, vp, vp, vp, vp, i32, i32,
+    lib.tide_select_exit_packed.argtypes = [vp, ci, i64, i64, i64, i64, i64, i64, vp, f32, vp, vp, vp, vp, vp, i32, i32,
                                             vp, vp, vp, vp]
-    lib.tide_packed_router_bytes.argtypes = [ci, i64]
+    lib.tide_packed_router_bytes.argtypes = [ci, i64, i64]
     lib.tide_packed_router_bytes.restype = ctypes.c_size_t
-    lib.tide_router_pack.argtypes = [ci, i64, i64, vp, vp, vp, vp]
+    lib.tide_router_pack.argtypes = [ci, i64, i64, i64, vp, vp, vp, vp]
     lib.tide_exit_project.argtypes = [vp, ci, i64, i64, i64, i64, i64, vp, i64, vp, vp, vp, f32, vp, i64, vp]
     lib.tide_batch_compact.argtypes = [vp, i64, i32, vp, vp, vp, vp]
     lib.tide_cosine_labels.argtypes = [vp, ci, i64, i64, i64, i64, i64, vp, i64, f32, vp, vp, vp]
@@ -143,22 +143,20 @@ def release() -> None:
     _check(load_library().tide_release())
 
 
-def packed_router_bytes(dtype: int, d: int) -> int:
-    return int(load_library().tide_packed_router_bytes(int(dtype), int(d)))
+def packed_router_bytes(dtype: int, d: int, b: int = BOTTLENECK) -> int:
+    return int(load_library().tide_packed_router_bytes(int(dtype), int(d), int(b)))
 
 
 def router_pack(dtype: int, gamma, W1) -> torch.Tensor:
-    """gamma [C,d] | None, W1 [C,d,128] (device fp32) -> packed weights (device uint8 buffer)."""
+    """gamma [C,d] | None, W1 [C,d,b] (device fp32; b = 64, 128 or 256) -> packed weights (device uint8 buffer)."""
     C, d, b = W1.shape
-    if b != BOTTLENECK:
-        raise ValueError("bottleneck must be 128")
     _f32dev(W1, (C, d, b), "W1")
     _f32dev(gamma, (C, d), "gamma")
-    nbytes = packed_router_bytes(dtype, d)
+    nbytes = packed_router_bytes(dtype, d, b)
     if nbytes == 0:
-        raise TideError(-2, f"unsupported dtype {dtype} or d {d}")
+        raise TideError(-2, f"unsupported dtype {dtype}, d {d} or bottleneck width {b}")
     packed = torch.empty(C * nbytes, dtype=torch.uint8, device=W1.device)
-    _check(load_library().tide_router_pack(int(dtype), C, d, _ptr(gamma), _ptr(W1), _ptr(packed), _stream()))
+    _check(load_library().tide_router_pack(int(dtype), C, d, b, _ptr(gamma), _ptr(W1), _ptr(packed), _stream()))
     return packed
 
 
@@ -171,15 +169,16 @@ def _eval_outputs(T, device, want_prob, want_fire, want_logit):
 
 def router_eval(hidden, gamma, eps, W1, b1, w2, b2, threshold, *, d=None, want_prob=True, want_fire=True,
                 want_logit=True):
-    """hidden [T, >=d]; gamma [d] | None; W1 [d,128]; b1 [128] | None; w2 [128] -> (prob, fire, logit)."""
+    """hidden [T, >=d]; gamma [d] | None; W1 [d,b]; b1 [b] | None; w2 [b] -> (prob, fire, logit)."""
     (T, width), (rs, _) = _rows(hidden, 2)
     d = int(W1.shape[0]) if d is None else int(d)
-    _f32dev(W1, (d, BOTTLENECK), "W1"), _f32dev(gamma, (d,), "gamma")
-    _f32dev(b1, (BOTTLENECK,), "b1"), _f32dev(w2, (BOTTLENECK,), "w2")
+    b = int(W1.shape[1])
+    _f32dev(W1, (d, b), "W1"), _f32dev(gamma, (d,), "gamma")
+    _f32dev(b1, (b,), "b1"), _f32dev(w2, (b,), "w2")
     if width < d:
         raise ValueError("hidden rows are shorter than d")
     prob, fire, logit = _eval_outputs(T, hidden.device, want_prob, want_fire, want_logit)
-    _check(load_library().tide_router_eval(_ptr(hidden), _dtype_code(hidden), T, d, rs if T > 1 else max(rs, d),
+    _check(load_library().tide_router_eval(_ptr(hidden), _dtype_code(hidden), T, d, b, rs if T > 1 else max(rs, d),
                                            _ptr(gamma), float(eps), _ptr(W1), _ptr(b1), _ptr(w2), float(b2),
                                            float(threshold), _ptr(prob), _ptr(fire), _ptr(logit), _stream()))
     return prob, fire, logit
@@ -188,11 +187,12 @@ def router_eval(hidden, gamma, eps, W1, b1, w2, b2, threshold, *, d=None, want_p
 def router_eval_packed(hidden, packed, eps, b1, w2, b2, threshold, *, d, want_prob=True, want_fire=True,
                        want_logit=True):
     (T, width), (rs, _) = _rows(hidden, 2)
-    _f32dev(b1, (BOTTLENECK,), "b1"), _f32dev(w2, (BOTTLENECK,), "w2")
+    b = int(w2.shape[0])
+    _f32dev(b1, (b,), "b1"), _f32dev(w2, (b,), "w2")
     if width < d:
         raise ValueError("hidden rows are shorter than d")
     prob, fire, logit = _eval_outputs(T, hidden.device, want_prob, want_fire, want_logit)
-    _check(load_library().tide_router_eval_packed(_ptr(hidden), _dtype_code(hidden), T, int(d),
+    _check(load_library().tide_router_eval_packed(_ptr(hidden), _dtype_code(hidden), T, int(d), b,
                                                   rs if T > 1 else max(rs, d), _ptr(packed), float(eps), _ptr(b1),
                                                   _ptr(w2), float(b2), float(threshold), _ptr(prob), _ptr(fire),
                                                   _ptr(logit), _stream()))
@@ -203,7 +203,8 @@ def _select_common(hidden, d, b1, w2, b2, threshold, layer_ids, want_logits, wan
     (C, T, width), (cs, rs, _) = _rows(hidden, 3)
     if width < d:
         raise ValueError("hidden rows are shorter than d")
-    _f32dev(b1, (C, BOTTLENECK), "b1"), _f32dev(w2, (C, BOTTLENECK), "w2")
+    b = int(w2.shape[-1])
+    _f32dev(b1, (C, b), "b1"), _f32dev(w2, (C, b), "w2")
     b2h, b2p = _host(b2, C, np.float32)
     thh, thp = _host(threshold, C, np.float32)
     idh, idp = _host(layer_ids, C, np.int32)
@@ -216,19 +217,19 @@ def _select_common(hidden, d, b1, w2, b2, threshold, layer_ids, want_logits, wan
         exit_layer, logits, mask = out
     cs = cs if (C > 1 and T > 0) else max(cs, 0)
     rs = rs if T > 1 else max(rs, d)
-    keep = (b2h, thh, idh)
+    keep = (b2h, thh, idh, b)
     return C, T, cs, rs, b2p, thp, idp, exit_layer, logits, mask, keep
 
 
 def select_exit(hidden, gamma, eps, W1, b1, w2, b2, threshold, layer_ids, min_layer, no_exit_layer, *,
                 want_logits=True, want_mask=True, out=None):
-    """hidden [C,T,>=d]; gamma [C,d] | None; W1 [C,d,128]; b1 [C,128] | None; w2 [C,128]; b2, threshold,
+    """hidden [C,T,>=d]; gamma [C,d] | None; W1 [C,d,b]; b1 [C,b] | None; w2 [C,b]; b2, threshold,
     layer_ids: host sequences of length C (or scalars) -> (exit_layer i32[T], logits f32[C,T], fire_mask i32[T])."""
     d = int(W1.shape[1])
     C, T, cs, rs, b2p, thp, idp, exit_layer, logits, mask, keep = _select_common(
         hidden, d, b1, w2, b2, threshold, layer_ids, want_logits, want_mask, out)
-    _f32dev(W1, (C, d, BOTTLENECK), "W1"), _f32dev(gamma, (C, d), "gamma")
-    _check(load_library().tide_select_exit(_ptr(hidden), _dtype_code(hidden), C, T, d, cs, rs, _ptr(gamma),
+    _f32dev(W1, (C, d, keep[3]), "W1"), _f32dev(gamma, (C, d), "gamma")
+    _check(load_library().tide_select_exit(_ptr(hidden), _dtype_code(hidden), C, T, d, keep[3], cs, rs, _ptr(gamma),
                                            float(eps), _ptr(W1), _ptr(b1), _ptr(w2), b2p, thp, idp, int(min_layer),
                                            int(no_exit_layer), _ptr(exit_layer), _ptr(logits), _ptr(mask),
                                            _stream()))
@@ -240,7 +241,7 @@ def select_exit_packed(hidden, packed, eps, b1, w2, b2, threshold, layer_ids, mi
                        want_logits=True, want_mask=True, out=None):
     C, T, cs, rs, b2p, thp, idp, exit_layer, logits, mask, keep = _select_common(
         hidden, int(d), b1, w2, b2, threshold, layer_ids, want_logits, want_mask, out)
-    _check(load_library().tide_select_exit_packed(_ptr(hidden), _dtype_code(hidden), C, T, int(d), cs, rs,
+    _check(load_library().tide_select_exit_packed(_ptr(hidden), _dtype_code(hidden), C, T, int(d), keep[3], cs, rs,
                                                   _ptr(packed), float(eps), _ptr(b1), _ptr(w2), b2p, thp, idp,
                                                   int(min_layer), int(no_exit_layer), _ptr(exit_layer), _ptr(logits),
                                                   _ptr(mask), _stream()))
@@ -362,9 +363,9 @@ def prepare_select_exit(hidden, gamma, eps, W1, b1, w2, b2, threshold, layer_ids
     d = int(W1.shape[1])
     C, T, cs, rs, b2p, thp, idp, exit_layer, logits, mask, keep = _select_common(
         hidden, d, b1, w2, b2, threshold, layer_ids, want_logits, want_mask, out)
-    _f32dev(W1, (C, d, BOTTLENECK), "W1"), _f32dev(gamma, (C, d), "gamma")
+    _f32dev(W1, (C, d, keep[3]), "W1"), _f32dev(gamma, (C, d), "gamma")
     fn = load_library().tide_select_exit
-    vals = (_ptr(hidden), _dtype_code(hidden), C, T, d, cs, rs, _ptr(gamma), float(eps), _ptr(W1), _ptr(b1), _ptr(w2),
+    vals = (_ptr(hidden), _dtype_code(hidden), C, T, d, keep[3], cs, rs, _ptr(gamma), float(eps), _ptr(W1), _ptr(b1), _ptr(w2),
             b2p.value, thp.value, idp.value, int(min_layer), int(no_exit_layer), _ptr(exit_layer), _ptr(logits),
             _ptr(mask), _stream())
     return PreparedCall(fn, _c(fn.argtypes, vals), (keep, hidden, gamma, W1, b1, w2), (exit_layer, logits, mask))
@@ -375,7 +376,7 @@ def prepare_select_exit_packed(hidden, packed, eps, b1, w2, b2, threshold, layer
     C, T, cs, rs, b2p, thp, idp, exit_layer, logits, mask, keep = _select_common(
         hidden, int(d), b1, w2, b2, threshold, layer_ids, want_logits, want_mask, out)
     fn = load_library().tide_select_exit_packed
-    vals = (_ptr(hidden), _dtype_code(hidden), C, T, int(d), cs, rs, _ptr(packed), float(eps), _ptr(b1), _ptr(w2),
+    vals = (_ptr(hidden), _dtype_code(hidden), C, T, int(d), keep[3], cs, rs, _ptr(packed), float(eps), _ptr(b1), _ptr(w2),
             b2p.value, thp.value, idp.value, int(min_layer), int(no_exit_layer), _ptr(exit_layer), _ptr(logits),
             _ptr(mask), _stream())
     return PreparedCall(fn, _c(fn.argtypes, vals), (keep, hidden, packed, b1, w2), (exit_layer, logits, mask))

@@ -36,13 +36,17 @@ def test_packed_size_query():
     assert tr.packed_router_bytes(tr.F32, 768) == 768 * 128 * 4
     assert tr.packed_router_bytes(tr.F16, 100) == 0
     assert tr.packed_router_bytes(7, 4096) == 0
+    # width 64 is stored padded to 128 columns, width 256 as two 128-column halves (Table 2's widths)
+    assert tr.packed_router_bytes(tr.BF16, 2048, 64) == 2048 * 128 * 2
+    assert tr.packed_router_bytes(tr.BF16, 8192, 256) == 8192 * 256 * 2
+    assert tr.packed_router_bytes(tr.BF16, 4096, 96) == 0 and tr.packed_router_bytes(tr.BF16, 4096, 512) == 0
 
 
 FAKE = 0x10000  # never dereferenced: every call below fails its checks first
 
 
-def _eval(lib, hidden=FAKE, dtype=2, T=4, d=256, rs=256, W1=FAKE, w2=FAKE, eps=1e-6):
-    return lib.tide_router_eval(hidden, dtype, T, d, rs, None, eps, W1, None, w2, 0.0, 0.5, None, None, None, None)
+def _eval(lib, hidden=FAKE, dtype=2, T=4, d=256, rs=256, W1=FAKE, w2=FAKE, eps=1e-6, b=128):
+    return lib.tide_router_eval(hidden, dtype, T, d, b, rs, None, eps, W1, None, w2, 0.0, 0.5, None, None, None, None)
 
 
 def test_router_eval_rejects_bad_arguments():
@@ -52,6 +56,8 @@ def test_router_eval_rejects_bad_arguments():
     assert _eval(lib, d=0) == -1
     assert _eval(lib, d=100, rs=100) == -2 and "128" in tr.last_error()
     assert _eval(lib, d=32768, rs=32768) == -2
+    assert _eval(lib, b=96) == -2 and "bottleneck" in tr.last_error()
+    assert _eval(lib, b=0) == -2 and _eval(lib, b=512) == -2
     assert _eval(lib, rs=128) == -1
     assert _eval(lib, hidden=None) == -1
     assert _eval(lib, W1=None) == -1
@@ -65,11 +71,11 @@ def test_router_eval_rejects_bad_arguments():
 
 def test_select_exit_rejects_bad_arguments():
     lib = tr.load_library()
-    def call(C=2, T=4, d=256, ids=(3, 7), b2=(0, 0), th=(.5, .5), exit_ptr=FAKE, cs=1024, hidden=FAKE):
+    def call(C=2, T=4, d=256, ids=(3, 7), b2=(0, 0), th=(.5, .5), exit_ptr=FAKE, cs=1024, hidden=FAKE, b=128):
         b2a, tha = np.asarray(b2, np.float32), np.asarray(th, np.float32)
         ida = np.asarray(ids, np.int32) if ids is not None else None
         p = lambda a: a.ctypes.data_as(ctypes.c_void_p) if a is not None else None
-        return lib.tide_select_exit(hidden, 2, C, T, d, cs, d, None, 1e-6, FAKE, None, FAKE, p(b2a), p(tha),
+        return lib.tide_select_exit(hidden, 2, C, T, d, b, cs, d, None, 1e-6, FAKE, None, FAKE, p(b2a), p(tha),
                                     p(ida), 0, 32, exit_ptr, None, None, None)
 
     assert call(ids=(7, 3)) == -1 and "ascending" in tr.last_error()
@@ -78,6 +84,7 @@ def test_select_exit_rejects_bad_arguments():
     assert call(C=0, ids=(), b2=(), th=()) == -1
     assert call(C=33, ids=tuple(range(33)), b2=(0,) * 33, th=(.5,) * 33) == -2
     assert call(exit_ptr=None) == -1
+    assert call(b=100) == -2
     assert call(cs=1028) == -3
     assert call(T=0, hidden=None) == 0
 

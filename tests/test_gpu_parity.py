@@ -212,6 +212,45 @@ def test_config4_sweep(tr, d):
         del hb
 
 
+# ------------------------------------------------------------------ bottleneck widths (Sec. 3.4, Table 2)
+
+@pytest.mark.parametrize("d,b", synth.TABLE2_PAIRS)
+def test_table2_pairs_prefill(tr, d, b):
+    """Every (hidden size, bottleneck width) pair of Table 2, bf16, 8 checkpoints x 2048 tokens."""
+    w = synth.table2(d, b, "bf16", T=2048)
+    st, _, _ = run_and_compare(tr, w, w.name, packed=True)
+    assert st["max_abs_err"] < 1e-2
+
+
+@pytest.mark.parametrize("b", [64, 256])
+@pytest.mark.parametrize("dtype,T,d", [("bf16", 300, 1024), ("f16", 129, 768), ("f32", 257, 512), ("bf16", 4100, 256)])
+def test_bottleneck_widths_every_dtype_and_form(tr, b, dtype, T, d):
+    """Widths 64 (padded to 128 columns) and 256 (two column halves) on ragged token counts, raw and
+    packed weights, and in every prefill form that supports the width."""
+    w = synth.Workload(f"width{b}_{dtype}_T{T}_d{d}", 37, dtype, d, 12, 4, T, None, b=b)
+    rt = w.routers()
+    rt.b2[:] = [0.2, -0.1, 0.0]
+    hb = w.hidden()
+    run_and_compare(tr, w, w.name + "_raw", rt=rt, hidden_bits=hb, variant=tr.VARIANT_PREFILL)
+    for form in (1, 2, 3):
+        tr.set_prefill_form(form)
+        try:
+            run_and_compare(tr, w, f"{w.name}_form{form}", rt=rt, hidden_bits=hb, packed=True, variant=tr.VARIANT_PREFILL)
+        finally:
+            tr.set_prefill_form(0)
+
+
+@pytest.mark.parametrize("b", [64, 256])
+@pytest.mark.parametrize("T", [1, 8, 19])
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_bottleneck_widths_decode(tr, b, T, dtype):
+    w = synth.Workload(f"decode_width{b}_{dtype}_T{T}", 41, dtype, 2048, 32, 4, T, None, b=b)
+    rt = w.routers()
+    rt.b2[:] = np.linspace(-0.3, 0.3, w.C)
+    st, _, _ = run_and_compare(tr, w, w.name, rt=rt, variant=tr.VARIANT_DECODE)
+    assert st["max_abs_err"] < 1e-4
+
+
 # ------------------------------------------------------------------ edge cases
 
 @pytest.mark.parametrize("T", [1, 63, 64, 65, 130, 257])
