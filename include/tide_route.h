@@ -26,8 +26,10 @@
  *  - Return value: TIDE_OK (0) or a negative tide_status_t.  On error nothing is enqueued,
  *    outputs are untouched and tide_last_error() describes the cause.  No call aborts.
  *  - hidden rows are d elements of `dtype`, row r of checkpoint c starting at element
- *    c*ckpt_stride + r*row_stride.  Requirements: d % 128 == 0, 128 <= d <= 16384,
- *    row_stride >= d, base address and both strides (in bytes) multiples of 16.
+ *    c*ckpt_stride + r*row_stride.  Requirements: 16 <= d <= 16384 with d*sizeof(dtype) a
+ *    multiple of 16, row_stride >= d, base address and both strides (in bytes) multiples of 16.
+ *    Hidden sizes that are multiples of 128 (every model of the paper's Table 2) run on the
+ *    tuned kernels; any other size on a generic fallback (Sec. 3.4), bottleneck 64 or 128 only.
  *  - T == 0 is a successful no-op.  1 <= C <= 32.
  *  - The threshold test is taken on the logit: z > ln(theta/(1-theta)) for 0 < theta < 1,
  *    never for theta >= 1 (the paper's "1.0 (off)", Table 4), always for theta <= 0.
@@ -54,7 +56,7 @@ typedef enum { TIDE_F32 = 0, TIDE_F16 = 1, TIDE_BF16 = 2 } tide_dtype_t;
 typedef enum {
     TIDE_OK = 0,
     TIDE_ERR_INVALID_ARG = -1, /* NULL where data is required, negative size, bad enum, unsorted layer_ids */
-    TIDE_ERR_UNSUPPORTED = -2, /* d outside the supported set, C > 32 */
+    TIDE_ERR_UNSUPPORTED = -2, /* d or b outside the supported set, C > 32 */
     TIDE_ERR_ALIGNMENT = -3,   /* hidden base or strides not 16-byte aligned */
     TIDE_ERR_WORKSPACE = -4,   /* workspace allocation failed */
     TIDE_ERR_HIP = -5          /* a HIP runtime call failed; see tide_last_error() */

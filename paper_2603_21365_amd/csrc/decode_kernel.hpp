@@ -21,7 +21,7 @@ struct DecodeParams {
     const float* W1;      // [C][d][b]
     const float* b1;      // [C][b] or null
     const float* w2;      // [C][b]
-    int C, T, d, S;       // S = d / kDecodeSlice
+    int C, T, d, S;       // S = ceil(d / kDecodeSlice); the last slice may be partial (any d with 16-byte rows)
     int b, halves;        // bottleneck width (64, 128, 256) and its 128-column halves
     float eps;
     int32_t min_layer, no_exit;
@@ -83,13 +83,17 @@ __global__ __launch_bounds__(kDecodeThreads) void tide_decode_kernel(const Decod
 
     // ---- this thread's weights: rows k0 + kk + 8*i, columns 4*jq .. 4*jq+3 of this half ----
     const int kk = tid >> 5, jq = tid & 31;
-    const bool live = half * kBottleneck + 4 * jq < p.b;       // columns beyond the width: zeros
-    const float* w = p.W1 + ((size_t)c * p.d + k0 + kk) * p.b + half * kBottleneck + 4 * jq;
+    // columns beyond the width and rows beyond d read as zeros: branch-free (the load goes to a
+    // clamped address and the value is dropped), so that all loads stay in flight together
+    const bool live = half * kBottleneck + 4 * jq < p.b;
+    const float* w = p.W1 + (size_t)c * p.d * p.b + (live ? half * kBottleneck + 4 * jq : 0);
     f32x4 wreg[kLoads];
 #pragma unroll
     for (int i = 0; i < kLoads; ++i) {
-        wreg[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-        if (live) wreg[i] = *reinterpret_cast<const f32x4*>(w + (size_t)8 * i * p.b);
+        const int k = k0 + kk + 8 * i;
+        const bool ok = live && k < p.d;
+        const f32x4 v = *reinterpret_cast<const f32x4*>(w + (size_t)(k < p.d ? k : p.d - 1) * p.b);
+        wreg[i] = ok ? v : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     }
 
     const char* base = p.hidden + (int64_t)c * p.ckpt_stride_bytes + (int64_t)k0 * Storage<DT>::kBytes;
@@ -101,14 +105,15 @@ __global__ __launch_bounds__(kDecodeThreads) void tide_decode_kernel(const Decod
         for (int q = tid; q < kDecodeTB * kChunksPerTok; q += kDecodeThreads) {
             const int t = q / kChunksPerTok, ch = q - t * kChunksPerTok;
             u32x4 v = {0, 0, 0, 0};
-            if (t < nt) v = *reinterpret_cast<const u32x4*>(base + (int64_t)(t0 + t) * p.row_stride_bytes + ch * 16);
+            const bool inside = k0 + ch * E < p.d;              // the last slice of a ragged d is partial
+            if (t < nt && inside) v = *reinterpret_cast<const u32x4*>(base + (int64_t)(t0 + t) * p.row_stride_bytes + ch * 16);
             float f[E];
             chunk_to_f32<DT>(v, f);
             float sq = 0.0f;
 #pragma unroll
             for (int e = 0; e < E; ++e) {
                 sq = fmaf(f[e], f[e], sq);
-                xs[t][ch * E + e] = f[e] * (g ? g[ch * E + e] : 1.0f);
+                xs[t][ch * E + e] = f[e] * ((g && inside) ? g[ch * E + e] : 1.0f);
             }
             sq = xor_reduce_sum<(kChunksPerTok == 16 ? 4 : 5)>(sq);
             if (ch == 0) ss_lds[t] = sq;

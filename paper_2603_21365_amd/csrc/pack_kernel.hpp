@@ -18,12 +18,13 @@ namespace tide {
 // One workgroup per 16-k group: the group's 16 x 128 weights are one contiguous 8 KiB of W1,
 // read with coalesced 16-byte loads, scaled by gamma and transposed through LDS so that every
 // thread then assembles one output chunk (two for fp32: hi and mid plane).
-// grid = (d/16, C * halves); chunks_per_half = 16-byte chunks of one packed 128-column half.
+// grid = (dpad/16, C * halves); chunks_per_half = 16-byte chunks of one packed 128-column half.
+// dpad >= d is the number of packed rows (whole k-tiles); rows at and beyond d are zeros.
 constexpr int kPackThreads = 256;
 
 template <int DT>
 __global__ __launch_bounds__(kPackThreads) void tide_pack_kernel(const float* __restrict__ gamma, const float* __restrict__ W1,
-                                                                 u32x4* __restrict__ packed, int d, int chunks_per_half,
+                                                                 u32x4* __restrict__ packed, int d, int dpad, int chunks_per_half,
                                                                  int b, int halves) {
     __shared__ float tile[16][kBottleneck + 4];            // +4: rows land on different banks
     const int c = blockIdx.y / halves, half = blockIdx.y - c * halves, G = blockIdx.x, tid = threadIdx.x;
@@ -34,8 +35,9 @@ __global__ __launch_bounds__(kPackThreads) void tide_pack_kernel(const float* __
         const int q = tid + i * kPackThreads;              // float4 index within the 16 x 128 tile
         const int k = q >> 5, col4 = (q & 31) * 4;
         f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (half * kBottleneck + col4 < b) v = *reinterpret_cast<const f32x4*>(w + (size_t)k * b + col4);
-        const float gk = g ? g[k] : 1.0f;
+        const bool row_ok = 16 * G + k < d;
+        if (row_ok && half * kBottleneck + col4 < b) v = *reinterpret_cast<const f32x4*>(w + (size_t)k * b + col4);
+        const float gk = (g && row_ok) ? g[k] : 1.0f;
 #pragma unroll
         for (int e = 0; e < 4; ++e) tile[k][col4 + e] = v[e] * gk;
     }
@@ -63,7 +65,7 @@ __global__ __launch_bounds__(kPackThreads) void tide_pack_kernel(const float* __
 #pragma unroll
         for (int e = 0; e < 8; ++e) { oh[e] = hi[e]; om[e] = mid[e]; }
         out[0] = __builtin_bit_cast(u32x4, oh);
-        out[(size_t)d * 16] = __builtin_bit_cast(u32x4, om);        // the mid plane follows the hi plane
+        out[(size_t)dpad * 16] = __builtin_bit_cast(u32x4, om);     // the mid plane follows the hi plane
     }
 }
 

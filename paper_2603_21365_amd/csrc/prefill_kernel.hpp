@@ -31,6 +31,8 @@ struct PrefillParams {
     const float* b1;           // [C][b] or null
     const float* w2;           // [C][b]
     int C, T, d;
+    int dpad;                  // d rounded up to whole k-tiles (128 elements of 16 bits, 64 of fp32): the packed
+                               // weights have dpad rows, zero beyond d; equal to d in the streaming form
     int b;                     // bottleneck width: 64, 128 or 256 (columns >= b of the last half are zero padding)
     int tiles_per_ckpt;        // ceil(T / kRows)
     int total_tiles;           // C * tiles_per_ckpt
@@ -58,7 +60,9 @@ constexpr int kMaxDepth = 3;              // k-tiles of hidden rows and W1' kept
 
 // kDepth = ring depth; the host picks kMaxDepth whenever a row has at least that many k-tiles
 // (the prologue fills the whole ring unconditionally), else 1.
-template <int DT, int kDepth>
+// kRagged: d is not a whole number of k-tiles (the generic fallback for hidden sizes that are
+// not multiples of 128): chunks beyond the end of a row read as zeros.
+template <int DT, int kDepth, bool kRagged = false>
 __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const PrefillParams p) {
     __shared__ __attribute__((aligned(16))) char a_lds[2][kRows * kPitch];
     __shared__ __attribute__((aligned(16))) float row_ss[kRows];
@@ -76,7 +80,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const 
     const int row0 = tile * kRows;
 
     const char* base = p.hidden + (int64_t)c * p.ckpt_stride_bytes;
-    const u32x4* wp = p.packed + (size_t)c * ((size_t)p.d * kBottleneck / Storage<DT>::kElems);
+    const u32x4* wp = p.packed + (size_t)c * ((size_t)p.dpad * kBottleneck / Storage<DT>::kElems);
 
     // this thread's chunk column and rows within the tile
     const int cc = tid & (kChunksPerRow - 1);
@@ -86,15 +90,16 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const 
     for (int i = 0; i < kChunksPerThread; ++i) {
         int r = row0 + lr0 + 16 * i;
         r = r < p.T ? r : p.T - 1;                 // ragged tail: re-read the last row, never store it
-        gptr[i] = base + (int64_t)r * p.row_stride_bytes + cc * 16;
+        gptr[i] = base + (int64_t)r * p.row_stride_bytes;      // start of the row
     }
+    const int row_bytes = p.d * Storage<DT>::kBytes;
     const u32x4* bptr = wp + wave * 64 + lane;     // + G*256 per k-group
 
     // Rows are a power-of-two number of bytes apart and every workgroup starts together, so
     // walking k from 0 everywhere would make the whole chip hit the same few HBM channels at
     // once.  Each workgroup starts its k loop at a different tile and wraps (a dot product
     // does not care about the order of its terms).
-    const int ntile = p.d * Storage<DT>::kBytes / kTileBytes;
+    const int ntile = p.dpad * Storage<DT>::kBytes / kTileBytes;
     int next = (int)(((unsigned)work * 5u) % (unsigned)ntile);
 
     u32x4 areg[kDepth][kChunksPerThread];
@@ -105,12 +110,24 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const 
     f32x16 acc[2] = {f32x16{0}, f32x16{0}};
 
     auto load_a = [&](int j, int kt) {
+        const int off = kt * kTileBytes + cc * 16;            // this thread's chunk within the row
+        if constexpr (kRagged) {
+            // branch-free: a chunk past the end of the row is fetched from the row's start and zeroed
+            const bool inside = off < row_bytes;
+            const int safe = inside ? off : 0;
 #pragma unroll
-        for (int i = 0; i < kChunksPerThread; ++i)
-            areg[j][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gptr[i] + (int64_t)kt * kTileBytes));   // read once
+            for (int i = 0; i < kChunksPerThread; ++i) {
+                const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gptr[i] + safe));
+                areg[j][i] = inside ? v : u32x4{0, 0, 0, 0};
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kChunksPerThread; ++i)
+                areg[j][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gptr[i] + off));   // read once
+        }
     };
     constexpr int kMmaGroups = Compute<DT>::kMmaGroups, kPlanes = Compute<DT>::kPlanes;
-    const size_t plane_chunks = (size_t)p.d * 16;
+    const size_t plane_chunks = (size_t)p.dpad * 16;
     auto load_b = [&](int j, int kt) {            // breg[j][g * kPlanes + plane]
 #pragma unroll
         for (int g = 0; g < kMmaGroups; ++g)

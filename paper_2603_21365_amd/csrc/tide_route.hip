@@ -103,6 +103,19 @@ float threshold_logit(float theta) {
 // Everything both entry points must check before anything is enqueued.
 bool supported_bottleneck(int64_t b) { return b == 64 || b == 128 || b == 256; }
 
+// Hidden sizes: rows of whole 16-byte chunks.  Multiples of 128 run on the streaming kernels; any
+// other size on the generic fallback (register-ring prefill form with a zero-filled last k-tile,
+// decode kernel with a partial last slice).
+bool supported_hidden(int dtype, int64_t d) {
+    return d >= 16 && d <= 16384 && (d * (int64_t)(dtype == TIDE_F32 ? 4 : 2)) % 16 == 0;
+}
+
+// d rounded up to whole k-tiles of the prefill kernels (256 bytes of a row).
+int64_t padded_hidden(int dtype, int64_t d) {
+    const int64_t tile = 256 / (dtype == TIDE_F32 ? 4 : 2);
+    return (d + tile - 1) / tile * tile;
+}
+
 int check_common(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int64_t ckpt_stride,
                  int64_t row_stride, const void* weights, const float* w2, float eps) {
     if (dtype != TIDE_F32 && dtype != TIDE_F16 && dtype != TIDE_BF16)
@@ -111,8 +124,11 @@ int check_common(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d,
     if (C > TIDE_MAX_CHECKPOINTS) return fail(TIDE_ERR_UNSUPPORTED, "C = %lld exceeds %d", (long long)C, TIDE_MAX_CHECKPOINTS);
     if (T < 0) return fail(TIDE_ERR_INVALID_ARG, "T = %lld is negative", (long long)T);
     if (d <= 0) return fail(TIDE_ERR_INVALID_ARG, "d = %lld must be positive", (long long)d);
-    if (d % 128 != 0 || d < 128 || d > 16384)
-        return fail(TIDE_ERR_UNSUPPORTED, "d = %lld: supported sizes are multiples of 128 in [128, 16384]", (long long)d);
+    if (!supported_hidden(dtype, d))
+        return fail(TIDE_ERR_UNSUPPORTED, "d = %lld: rows must be a multiple of 16 bytes and d in [16, 16384] "
+                    "(multiples of 128 take the fast kernels)", (long long)d);
+    if (d % 128 != 0 && b == 256)
+        return fail(TIDE_ERR_UNSUPPORTED, "bottleneck width 256 needs d %% 128 == 0 (d = %lld)", (long long)d);
     if (!supported_bottleneck(b))
         return fail(TIDE_ERR_UNSUPPORTED, "bottleneck width b = %lld: supported widths are 64, 128 and 256", (long long)b);
     if (C * T > (int64_t)1 << 30)
@@ -161,12 +177,13 @@ struct Outputs {
 int halves_of(int64_t b) { return (int)((b + kBottleneck - 1) / kBottleneck); }
 
 int launch_pack(int dtype, int64_t C, int64_t d, int64_t b, const float* gamma, const float* W1, void* packed, hipStream_t st) {
-    const int chunks = (int)(d * kBottleneck * elem_bytes(dtype) / 16);      // of one 128-column half
+    const int64_t dpad = padded_hidden(dtype, d);
+    const int chunks = (int)(dpad * kBottleneck * elem_bytes(dtype) / 16);   // of one 128-column half
     const int halves = halves_of(b);
-    dim3 grid((unsigned)(d / 16), (unsigned)(C * halves));
+    dim3 grid((unsigned)(dpad / 16), (unsigned)(C * halves));
     by_dtype(dtype, [&](auto dt) {
         hipLaunchKernelGGL((tide_pack_kernel<decltype(dt)::value>), grid, dim3(kPackThreads), 0, st, gamma, W1, (u32x4*)packed, (int)d,
-                           chunks, (int)b, halves);
+                           (int)dpad, chunks, (int)b, halves);
         return 0;
     });
     TIDE_HIP(hipGetLastError());
@@ -210,8 +227,10 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
     p.C = (int)C;
     p.T = (int)T;
     p.d = (int)d;
+    p.dpad = (int)padded_hidden(dtype, d);
     p.b = (int)b;
     const bool two_halves = halves_of(b) == 2;
+    const bool generic_d = d % 128 != 0;           // the fallback: register-ring form, whatever form is forced
     // Rows per workgroup: 128 (each W1' fragment fetched once per 128 rows) when that still
     // gives every CU a workgroup, else 64; g_prefill_form overrides for tests and tuning.
     const int64_t tiles128 = C * ((T + 127) / 128);
@@ -224,7 +243,7 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
     // Width 256 (two column halves per wave) exists in the streaming form with 64 rows per
     // workgroup only.  With 128 rows the accumulators (256 values per lane) leave room for half a
     // k-tile of W1' in flight, too little to cover the L2 round trip: measured slower.
-    const bool ring_form = !two_halves && (g_prefill_form == 3 || (g_prefill_form == 0 && dtype == TIDE_F32));
+    const bool ring_form = generic_d || (!two_halves && (g_prefill_form == 3 || (g_prefill_form == 0 && dtype == TIDE_F32)));
     if (ring_form) rows_per_wg = kRows;
     if (two_halves) rows_per_wg = 64;
     p.tiles_per_ckpt = (int)((T + rows_per_wg - 1) / rows_per_wg);
@@ -244,11 +263,17 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
         p.arrive = (uint64_t*)ws.arrive.ptr;
     }
     const unsigned grid = 8u * (unsigned)((p.total_tiles + 7) / 8);
-    const int ntile = (int)(d * (int64_t)eb / kTileBytes);
+    const int ntile = (int)(p.dpad * (int64_t)eb / kTileBytes);
+    const bool ragged = p.dpad != p.d;
     int rc = TIDE_OK;
     by_dtype(dtype, [&](auto dt) {
         constexpr int DT = decltype(dt)::value;
-        if (ring_form) {
+        if (ring_form && ragged) {
+            if (ntile >= kMaxDepth)
+                hipLaunchKernelGGL((tide_prefill_kernel<DT, kMaxDepth, true>), dim3(grid), dim3(kPrefillThreads), 0, st, p);
+            else
+                hipLaunchKernelGGL((tide_prefill_kernel<DT, 1, true>), dim3(grid), dim3(kPrefillThreads), 0, st, p);
+        } else if (ring_form) {
             if (ntile >= kMaxDepth)
                 hipLaunchKernelGGL((tide_prefill_kernel<DT, kMaxDepth>), dim3(grid), dim3(kPrefillThreads), 0, st, p);
             else
@@ -283,7 +308,7 @@ int launch_decode(Workspace& ws, const void* hidden, int dtype, int64_t C, int64
     p.C = (int)C;
     p.T = (int)T;
     p.d = (int)d;
-    p.S = (int)(d / kDecodeSlice);
+    p.S = (int)((d + kDecodeSlice - 1) / kDecodeSlice);
     p.b = (int)b;
     p.halves = halves_of(b);
     p.eps = eps;
@@ -358,9 +383,9 @@ int tide_version(void) { return 100; }
 const char* tide_last_error(void) { return g_err; }
 
 size_t tide_packed_router_bytes(int dtype, int64_t d, int64_t b) {
-    if ((dtype != TIDE_F32 && dtype != TIDE_F16 && dtype != TIDE_BF16) || d < 128 || d > 16384 || d % 128) return 0;
-    if (!supported_bottleneck(b)) return 0;
-    return (size_t)halves_of(b) * (size_t)d * kBottleneck * elem_bytes(dtype);
+    if ((dtype != TIDE_F32 && dtype != TIDE_F16 && dtype != TIDE_BF16) || !supported_hidden(dtype, d)) return 0;
+    if (!supported_bottleneck(b) || (d % 128 != 0 && b == 256)) return 0;
+    return (size_t)halves_of(b) * (size_t)padded_hidden(dtype, d) * kBottleneck * elem_bytes(dtype);
 }
 
 int tide_router_pack(int dtype, int64_t C, int64_t d, int64_t b, const float* gamma, const float* W1, void* packed, void* stream) {

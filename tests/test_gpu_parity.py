@@ -251,6 +251,50 @@ def test_bottleneck_widths_decode(tr, b, T, dtype):
     assert st["max_abs_err"] < 1e-4
 
 
+# ------------------------------------------------------------------ hidden sizes that are not multiples of 128
+
+@pytest.mark.parametrize("b", [128, 64])
+@pytest.mark.parametrize("dtype,d", [("bf16", 200), ("bf16", 1000), ("f16", 72), ("f16", 4104), ("f32", 100), ("f32", 708),
+                                     ("f32", 192), ("bf16", 16)])
+def test_generic_fallback_for_other_hidden_sizes(tr, dtype, d, b):
+    """The generic fallback (Sec. 3.4): any d whose rows are whole 16-byte chunks -- a partial last
+    k-tile in the prefill kernel, a partial last slice in the decode kernel -- with padded strides
+    whose padding holds NaN."""
+    import torch
+    C, T = 3, 333
+    w = synth.Workload(f"generic_{dtype}_d{d}_b{b}", 43, dtype, d, 12, 4, T, None, b=b)
+    rt = w.routers()
+    rt.b2[:] = [0.1, -0.2, 0.0]
+    hb = w.hidden()
+    ex_o, z_o, m_o = oracle_select(w, rt, hb)
+    pad = 24 if dtype == "f32" else 40                       # keeps rows 16-byte aligned
+    store = np.float32 if dtype == "f32" else (np.float16 if dtype == "f16" else np.uint16)
+    nan = np.array(np.nan, dtype=np.float32).astype(store) if dtype != "bf16" else np.uint16(0x7FC0)
+    wide = np.full((C, T + 3, d + pad), nan, dtype=store)
+    wide[:, :T, :d] = hb
+    dev = to_device(wide, dtype)
+    g, W1, b1, w2 = routers_to_device(rt)
+    for variant, Tn in ((tr.VARIANT_PREFILL, T), (tr.VARIANT_DECODE, 21)):
+        tr.set_variant(variant)
+        try:
+            ex, z, m = tr.select_exit(dev[:, :Tn, :], g, w.eps, W1, b1, w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers)
+            torch.cuda.synchronize()
+        finally:
+            tr.set_variant(tr.VARIANT_AUTO)
+        st = compare_select(f"{w.name}_v{variant}", dtype, z.cpu().numpy(), ex.cpu().numpy(), m.cpu().numpy(),
+                            z_o[:, :Tn], ex_o[:Tn], m_o[:Tn], rt.theta, w.layer_ids, 0, w.n_layers)
+        report(st)
+
+
+def test_generic_hidden_size_rejects_width_256(tr):
+    import torch
+    h = torch.zeros((1, 4, 200), dtype=torch.bfloat16, device="cuda")
+    W1 = torch.zeros((1, 200, 256), device="cuda")
+    w2 = torch.zeros((1, 256), device="cuda")
+    with pytest.raises(tr.TideError):
+        tr.select_exit(h, None, 1e-6, W1, None, w2, 0.0, 0.5, [3], 0, 4)
+
+
 # ------------------------------------------------------------------ edge cases
 
 @pytest.mark.parametrize("T", [1, 63, 64, 65, 130, 257])

@@ -43,7 +43,8 @@ def ulp_compare(name, dtype, got_bits, want_bits, mask_rows=None):
 
 
 @pytest.mark.parametrize("dtype,d,T", [("bf16", 4096, 333), ("f16", 512, 130), ("f32", 4096, 65), ("f32", 8192, 9),
-                                        ("bf16", 16384, 5), ("f32", 16384, 3), ("bf16", 128, 1)])
+                                        ("bf16", 16384, 5), ("f32", 16384, 3), ("bf16", 128, 1),
+                                        ("bf16", 200, 77), ("f16", 4104, 33), ("f32", 100, 50)])   # not multiples of 128
 @pytest.mark.parametrize("with_final", [True, False])
 def test_projection_matches_the_oracle(tr, dtype, d, T, with_final):
     import torch
@@ -141,7 +142,7 @@ def test_batch_exit_matches_the_oracle(tr, T):
 
 
 @pytest.mark.parametrize("dtype,d,T,C", [("bf16", 4096, 300, 8), ("f16", 768, 65, 3), ("f32", 2048, 17, 2), ("f32", 8192, 5, 2),
-                                          ("bf16", 16384, 3, 2)])
+                                          ("bf16", 16384, 3, 2), ("bf16", 1000, 70, 3), ("f32", 708, 33, 2)])
 def test_cosine_labels_match_the_oracle(tr, dtype, d, T, C):
     """Eq. (1) on the trajectory generator (similarities rise towards 1 with depth, so labels of
     both kinds occur).  Similarities within 2e-5 (fp32 accumulation of d terms); labels exact
