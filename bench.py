@@ -37,6 +37,8 @@ def main() -> int:
     ap.add_argument("--buffers", type=int, default=4, help="distinct input batches rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the steps around the path (exit projection, calibration labels, other bottleneck widths)")
     ap.add_argument("--no-settle", action="store_true", help="skip the untimed settling phase (short profiler runs)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 256 MiB device copy 3 times (known traffic, scales the profiler's "
@@ -204,48 +206,49 @@ def main() -> int:
         "roofline": roofline,
     }
 
-    # ---- exit projection (the step after the path: rows for the LM head), same workload
-    final_h = torch.from_numpy(synth.make_hidden(w.cfg + 7, 1, T, d, w.dtype)[0].view(np.int16)).cuda().view(torch.bfloat16)
-    norm_gain = torch.ones(d, dtype=torch.float32, device="cuda")
-    proj_out = torch.empty((T, d), dtype=torch.bfloat16, device="cuda")
-    pj_calls = [tr.prepare_exit_project(b, final_h, out[0], w.layer_ids, norm_gain, 1e-6, out=proj_out) for b in batches]
-    wall_pj, ev_pj = timed(lambda i: pj_calls[i % args.buffers](), args.steps, args.warmup)
-    pj_bytes = 2 * T * d * esz + 4 * T + 4 * d
-    result["exit_projection"] = {"entry_point": "tide_exit_project", "us_per_call": round(ev_pj / args.steps * 1e6, 2),
-                                 "algorithmic_bytes": pj_bytes, "gbs": round(pj_bytes / (ev_pj / args.steps) / 1e9, 1),
-                                 "frac_of_hbm_peak": round(pj_bytes / (ev_pj / args.steps) / 1e9 / HBM_PEAK_GBS, 4)}
+    if not args.no_extras:
+        # ---- exit projection (the step after the path: rows for the LM head), same workload
+        final_h = torch.from_numpy(synth.make_hidden(w.cfg + 7, 1, T, d, w.dtype)[0].view(np.int16)).cuda().view(torch.bfloat16)
+        norm_gain = torch.ones(d, dtype=torch.float32, device="cuda")
+        proj_out = torch.empty((T, d), dtype=torch.bfloat16, device="cuda")
+        pj_calls = [tr.prepare_exit_project(b, final_h, out[0], w.layer_ids, norm_gain, 1e-6, out=proj_out) for b in batches]
+        wall_pj, ev_pj = timed(lambda i: pj_calls[i % args.buffers](), args.steps, args.warmup)
+        pj_bytes = 2 * T * d * esz + 4 * T + 4 * d
+        result["exit_projection"] = {"entry_point": "tide_exit_project", "us_per_call": round(ev_pj / args.steps * 1e6, 2),
+                                     "algorithmic_bytes": pj_bytes, "gbs": round(pj_bytes / (ev_pj / args.steps) / 1e9, 1),
+                                     "frac_of_hbm_peak": round(pj_bytes / (ev_pj / args.steps) / 1e9 / HBM_PEAK_GBS, 4)}
 
-    # ---- calibration labels (the step before the path: Eq. 1), same shapes
-    cos_out = (torch.empty((C, T), dtype=torch.float32, device="cuda"), torch.empty((C, T), dtype=torch.uint8, device="cuda"))
+        # ---- calibration labels (the step before the path: Eq. 1), same shapes
+        cos_out = (torch.empty((C, T), dtype=torch.float32, device="cuda"), torch.empty((C, T), dtype=torch.uint8, device="cuda"))
 
-    def cos_call(i):
-        tr.cosine_labels(batches[i % args.buffers], final_h, 0.98, out=cos_out)
-    n_cos = max(20, args.steps // 4)
-    wall_cs, ev_cs = timed(cos_call, n_cos, 5)
-    cs_bytes = (C + 1) * T * d * esz + 5 * C * T
-    result["calibration_labels"] = {"entry_point": "tide_cosine_labels", "us_per_call": round(ev_cs / n_cos * 1e6, 2),
-                                    "algorithmic_bytes": cs_bytes, "gbs": round(cs_bytes / (ev_cs / n_cos) / 1e9, 1),
-                                    "frac_of_hbm_peak": round(cs_bytes / (ev_cs / n_cos) / 1e9 / HBM_PEAK_GBS, 4)}
+        def cos_call(i):
+            tr.cosine_labels(batches[i % args.buffers], final_h, 0.98, out=cos_out)
+        n_cos = max(20, args.steps // 4)
+        wall_cs, ev_cs = timed(cos_call, n_cos, 5)
+        cs_bytes = (C + 1) * T * d * esz + 5 * C * T
+        result["calibration_labels"] = {"entry_point": "tide_cosine_labels", "us_per_call": round(ev_cs / n_cos * 1e6, 2),
+                                        "algorithmic_bytes": cs_bytes, "gbs": round(cs_bytes / (ev_cs / n_cos) / 1e9, 1),
+                                        "frac_of_hbm_peak": round(cs_bytes / (ev_cs / n_cos) / 1e9 / HBM_PEAK_GBS, 4)}
 
-    # ---- the other bottleneck widths of the paper's kernel specialisations (Table 2), same token count
-    widths = {}
-    gen = torch.Generator(device="cuda").manual_seed(0x71DE)
-    for dd, bb in ((2048, 64), (4096, 256), (8192, 256)):
-        nb = 3
-        hbs = [torch.randn((C, T, dd), generator=gen, device="cuda").to(torch.bfloat16) for _ in range(nb)]
-        Wb = torch.randn((C, dd, bb), generator=gen, device="cuda") / dd ** 0.5
-        w2b = torch.randn((C, bb), generator=gen, device="cuda") / bb ** 0.5
-        pkb = tr.router_pack(tr.BF16, None, Wb)
-        cb = [tr.prepare_select_exit_packed(h, pkb, w.eps, None, w2b, 0.0, 0.5, w.layer_ids, 0, w.n_layers, d=dd, out=out)
-              for h in hbs]
-        n_w = max(20, args.steps // 4)
-        _, ev_w = timed(lambda i: cb[i % nb](), n_w, 5)
-        by = C * T * dd * esz + C * dd * bb * esz + T * 8 + C * T * 4
-        widths[f"d{dd}_b{bb}"] = {"us_per_call": round(ev_w / n_w * 1e6, 2), "algorithmic_bytes": by,
-                                  "gbs": round(by / (ev_w / n_w) / 1e9, 1),
-                                  "frac_of_hbm_peak": round(by / (ev_w / n_w) / 1e9 / HBM_PEAK_GBS, 4)}
-        del hbs, cb, pkb, Wb
-    result["bottleneck_widths"] = {"workload": f"Table 2 pairs with b != 128: bf16, C={C}, T={T}, packed weights", **widths}
+        # ---- the other bottleneck widths of the paper's kernel specialisations (Table 2), same token count
+        widths = {}
+        gen = torch.Generator(device="cuda").manual_seed(0x71DE)
+        for dd, bb in ((2048, 64), (4096, 256), (8192, 256)):
+            nb = 3
+            hbs = [torch.randn((C, T, dd), generator=gen, device="cuda").to(torch.bfloat16) for _ in range(nb)]
+            Wb = torch.randn((C, dd, bb), generator=gen, device="cuda") / dd ** 0.5
+            w2b = torch.randn((C, bb), generator=gen, device="cuda") / bb ** 0.5
+            pkb = tr.router_pack(tr.BF16, None, Wb)
+            cb = [tr.prepare_select_exit_packed(h, pkb, w.eps, None, w2b, 0.0, 0.5, w.layer_ids, 0, w.n_layers, d=dd, out=out)
+                  for h in hbs]
+            n_w = max(20, args.steps // 4)
+            _, ev_w = timed(lambda i: cb[i % nb](), n_w, 5)
+            by = C * T * dd * esz + C * dd * bb * esz + T * 8 + C * T * 4
+            widths[f"d{dd}_b{bb}"] = {"us_per_call": round(ev_w / n_w * 1e6, 2), "algorithmic_bytes": by,
+                                      "gbs": round(by / (ev_w / n_w) / 1e9, 1),
+                                      "frac_of_hbm_peak": round(by / (ev_w / n_w) / 1e9 / HBM_PEAK_GBS, 4)}
+            del hbs, cb, pkb, Wb
+        result["bottleneck_widths"] = {"workload": f"Table 2 pairs with b != 128: bf16, C={C}, T={T}, packed weights", **widths}
 
     # ---- decode latency (config 2): fp16, T = 1 and 8, raw weights, auto-selected decode variant
     if not args.no_decode:

@@ -32,20 +32,21 @@ template <> __device__ __forceinline__ void chunk_dot<kF32>(u32x4 a, u32x4 b, fl
         na = fmaf(x, x, na);
     }
 }
+// 16-bit forms: packed dot-product instructions in one asm statement per chunk, closed by the
+// wait states a dot result needs before another kind of vector instruction reads or overwrites
+// it (see chunk_sumsq in device_utils.hpp).
+#define TIDE_CHUNK_DOT_ASM(op)                                                                        \
+    asm(op " %0, %2, %6\n\t" op " %1, %2, %2\n\t" op " %0, %3, %7\n\t" op " %1, %3, %3\n\t"           \
+        op " %0, %4, %8\n\t" op " %1, %4, %4\n\t" op " %0, %5, %9\n\t" op " %1, %5, %5\n\ts_nop 3"     \
+        : "+v"(dot), "+v"(na)                                                                         \
+        : "v"(a.x), "v"(a.y), "v"(a.z), "v"(a.w), "v"(b.x), "v"(b.y), "v"(b.z), "v"(b.w))
 template <> __device__ __forceinline__ void chunk_dot<kF16>(u32x4 a, u32x4 b, float& dot, float& na) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        asm("v_dot2c_f32_f16 %0, %1, %2" : "+v"(dot) : "v"(a[i]), "v"(b[i]));
-        asm("v_dot2c_f32_f16 %0, %1, %1" : "+v"(na) : "v"(a[i]));
-    }
+    TIDE_CHUNK_DOT_ASM("v_dot2c_f32_f16");
 }
 template <> __device__ __forceinline__ void chunk_dot<kBF16>(u32x4 a, u32x4 b, float& dot, float& na) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        asm("v_dot2c_f32_bf16 %0, %1, %2" : "+v"(dot) : "v"(a[i]), "v"(b[i]));
-        asm("v_dot2c_f32_bf16 %0, %1, %1" : "+v"(na) : "v"(a[i]));
-    }
+    TIDE_CHUNK_DOT_ASM("v_dot2c_f32_bf16");
 }
+#undef TIDE_CHUNK_DOT_ASM
 
 // kChunks = 16-byte chunks of a row held per thread (the host picks the smallest of 4, 8, 16
 // that covers the row: three rows' worth of registers decide the occupancy).

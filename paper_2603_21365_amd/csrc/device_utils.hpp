@@ -39,14 +39,24 @@ template <> __device__ __forceinline__ float chunk_sumsq<kF32>(u32x4 c, float ac
 // accumulate).  It is written as inline assembly because this toolchain's
 // __builtin_amdgcn_fdot2* builtins, called with the same value for both operands in an
 // unrolled loop over a vector's elements, emit the first element's register every time.
+// The four instructions of a chunk chain through the accumulator (same opcode, accumulator
+// operand: forwarded, no wait states).  The trailing s_nop supplies the wait states the
+// hardware needs before any OTHER vector instruction reads (3) or overwrites (4) the result of
+// a dot instruction: the compiler inserts them for instructions it knows, but it cannot see
+// into the asm, and without them the last term of the chain is lost whenever the scheduler
+// happens to place the reader right behind it.
 template <> __device__ __forceinline__ float chunk_sumsq<kF16>(u32x4 c, float acc) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) asm("v_dot2c_f32_f16 %0, %1, %1" : "+v"(acc) : "v"(c[i]));
+    asm("v_dot2c_f32_f16 %0, %1, %1\n\tv_dot2c_f32_f16 %0, %2, %2\n\tv_dot2c_f32_f16 %0, %3, %3\n\t"
+        "v_dot2c_f32_f16 %0, %4, %4\n\ts_nop 3"
+        : "+v"(acc)
+        : "v"(c.x), "v"(c.y), "v"(c.z), "v"(c.w));
     return acc;
 }
 template <> __device__ __forceinline__ float chunk_sumsq<kBF16>(u32x4 c, float acc) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) asm("v_dot2c_f32_bf16 %0, %1, %1" : "+v"(acc) : "v"(c[i]));
+    asm("v_dot2c_f32_bf16 %0, %1, %1\n\tv_dot2c_f32_bf16 %0, %2, %2\n\tv_dot2c_f32_bf16 %0, %3, %3\n\t"
+        "v_dot2c_f32_bf16 %0, %4, %4\n\ts_nop 3"
+        : "+v"(acc)
+        : "v"(c.x), "v"(c.y), "v"(c.z), "v"(c.w));
     return acc;
 }
 

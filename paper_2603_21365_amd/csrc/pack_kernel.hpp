@@ -15,39 +15,37 @@
 
 namespace tide {
 
-// One workgroup per 16-k group: the group's 16 x 128 weights are one contiguous 8 KiB of W1,
-// read with coalesced 16-byte loads, scaled by gamma and transposed through LDS so that every
-// thread then assembles one output chunk (two for fp32: hi and mid plane).
-// grid = (dpad/16, C * halves); chunks_per_half = 16-byte chunks of one packed 128-column half.
-// dpad >= d is the number of packed rows (whole k-tiles); rows at and beyond d are zeros.
+// One thread per output chunk (per pair of planes for fp32): its eight values are eight rows of
+// W1 at one column, so for each of them the 32 lanes of a half-wave read 128 contiguous bytes.
+// All eight loads are independent and in flight together; no LDS, no barrier.
+// grid = (dpad*16 / kPackThreads, C * halves); chunks_per_half = 16-byte chunks of one packed
+// 128-column half (both planes).  dpad >= d is the number of packed rows (whole k-tiles); rows at
+// and beyond d, and columns at and beyond b, are zeros.
 constexpr int kPackThreads = 256;
 
 template <int DT>
 __global__ __launch_bounds__(kPackThreads) void tide_pack_kernel(const float* __restrict__ gamma, const float* __restrict__ W1,
                                                                  u32x4* __restrict__ packed, int d, int dpad, int chunks_per_half,
                                                                  int b, int halves) {
-    __shared__ float tile[16][kBottleneck + 4];            // +4: rows land on different banks
-    const int c = blockIdx.y / halves, half = blockIdx.y - c * halves, G = blockIdx.x, tid = threadIdx.x;
-    const float* w = W1 + ((size_t)c * d + 16 * G) * b + half * kBottleneck;
-    const float* g = gamma ? gamma + (size_t)c * d + 16 * G : nullptr;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int q = tid + i * kPackThreads;              // float4 index within the 16 x 128 tile
-        const int k = q >> 5, col4 = (q & 31) * 4;
-        f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
-        const bool row_ok = 16 * G + k < d;
-        if (row_ok && half * kBottleneck + col4 < b) v = *reinterpret_cast<const f32x4*>(w + (size_t)k * b + col4);
-        const float gk = (g && row_ok) ? g[k] : 1.0f;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) tile[k][col4 + e] = v[e] * gk;
-    }
-    __syncthreads();
-    const int lane = tid & 63, nb = tid >> 6;
-    const int h = lane >> 5, col = 32 * nb + (lane & 31);
+    const int c = blockIdx.y / halves, half = blockIdx.y - c * halves;
+    const int q = blockIdx.x * kPackThreads + threadIdx.x;       // chunk within the (hi) plane
+    if (q >= dpad * 16) return;
+    const int lane = q & 63, nb = (q >> 6) & 3, G = q >> 8;
+    const int h = lane >> 5, j = lane & 31;
+    const int k0 = 16 * G + 8 * h;
+    const int col = half * kBottleneck + 32 * nb + j;
+    const bool col_ok = col < b;
+    const float* w = W1 + (size_t)c * d * b + (col_ok ? col : 0);
+    const float* g = gamma ? gamma + (size_t)c * d : nullptr;
     float v[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = tile[8 * h + e][col];
-    u32x4* out = packed + (size_t)blockIdx.y * chunks_per_half + (size_t)G * 256 + tid;
+    for (int e = 0; e < 8; ++e) {
+        const int k = k0 + e;
+        const int ks = k < d ? k : d - 1;                           // clamped: in bounds, branch-free
+        const float x = w[(size_t)ks * b] * (g ? g[ks] : 1.0f);
+        v[e] = (col_ok && k < d) ? x : 0.0f;
+    }
+    u32x4* out = packed + (size_t)blockIdx.y * chunks_per_half + q;
     if constexpr (DT == kF16) {
         f16x8 o;
 #pragma unroll

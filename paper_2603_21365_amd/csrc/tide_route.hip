@@ -180,7 +180,7 @@ int launch_pack(int dtype, int64_t C, int64_t d, int64_t b, const float* gamma, 
     const int64_t dpad = padded_hidden(dtype, d);
     const int chunks = (int)(dpad * kBottleneck * elem_bytes(dtype) / 16);   // of one 128-column half
     const int halves = halves_of(b);
-    dim3 grid((unsigned)(dpad / 16), (unsigned)(C * halves));
+    dim3 grid((unsigned)((dpad * 16 + kPackThreads - 1) / kPackThreads), (unsigned)(C * halves));
     by_dtype(dtype, [&](auto dt) {
         hipLaunchKernelGGL((tide_pack_kernel<decltype(dt)::value>), grid, dim3(kPackThreads), 0, st, gamma, W1, (u32x4*)packed, (int)d,
                            (int)dpad, chunks, (int)b, halves);
@@ -208,6 +208,9 @@ template <int DT, int M, int CB> int launch_dma(unsigned grid, hipStream_t st, c
     // (the two-halves kernel needs more than the 168 registers that let three waves share a SIMD)
     const unsigned resident = (unsigned)(cus[dev] > 8 ? cus[dev] & ~7 : 8) * ((M == 128 || CB == 2) ? 1u : 2u);
     if (grid > resident) grid = resident;      // both are multiples of 8
+    // With fewer 128-row tiles than CUs, launch every CU anyway: the schedule then cuts the tiles
+    // into 64- or 32-row pieces, one per workgroup (a workgroup without a piece exits at once).
+    if (M == 128 && CB == 1) grid = resident;
     hipLaunchKernelGGL((tide_prefill_dma_kernel<DT, M, CB>), dim3(grid), dim3(kDmaThreads), lds, st, p);
     return TIDE_OK;
 }
@@ -231,10 +234,13 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
     p.b = (int)b;
     const bool two_halves = halves_of(b) == 2;
     const bool generic_d = d % 128 != 0;           // the fallback: register-ring form, whatever form is forced
-    // Rows per workgroup: 128 (each W1' fragment fetched once per 128 rows) when that still
-    // gives every CU a workgroup, else 64; g_prefill_form overrides for tests and tuning.
+    // Rows per workgroup (streaming form).  128 rows fetch each W1' fragment once per 128 rows and
+    // is the choice whenever the tiles fill most of the chip.  With few tiles it wins again, because
+    // every CU is launched and the tiles are cut into 64- or 32-row pieces (up to 80 tiles of 128
+    // rows: measured against the 64-row kernel on a 256-CU device); in between, 64-row tiles on two
+    // workgroups per CU are faster.  g_prefill_form overrides for tests and tuning.
     const int64_t tiles128 = C * ((T + 127) / 128);
-    int rows_per_wg = tiles128 >= 192 ? 128 : 64;
+    int rows_per_wg = (tiles128 <= 80 || tiles128 >= 144) ? 128 : 64;
     if (g_prefill_form == 1) rows_per_wg = 64;
     if (g_prefill_form == 2) rows_per_wg = 128;
     // fp32 rows are split into bf16 terms before the matrix cores: the register-ring form does

@@ -295,6 +295,49 @@ def test_generic_hidden_size_rejects_width_256(tr):
         tr.select_exit(h, None, 1e-6, W1, None, w2, 0.0, 0.5, [3], 0, 4)
 
 
+# ------------------------------------------------------------------ every element counts
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("d", [128, 256, 384])
+def test_every_element_enters_the_sum_of_squares(tr, dtype, d):
+    """Row t carries a spike of 40 at element t (mod d) on unit noise, so that one element holds
+    ~90 % of the row's sum of squares: a kernel that loses any single element's square -- whichever
+    k-tile, lane or instruction slot it falls into -- misses the logit by far more than the
+    tolerance.  All prefill forms and, in slices of 64 tokens, the decode kernel."""
+    import torch
+    T = 2 * d + 37
+    w = synth.Workload(f"spike_{dtype}_d{d}", 47, dtype, d, 8, 4, T, None, trajectory=False)
+    rt = w.routers()
+    h = np.random.default_rng(d).standard_normal((w.C, T, d)).astype(np.float32)
+    for t in range(T):
+        h[:, t, t % d] = 40.0
+    hb = synth.to_storage(h, dtype)
+    ex_o, z_o, m_o = oracle_select(w, rt, hb)
+    dev = to_device(hb, dtype)
+    g, W1, b1, w2 = routers_to_device(rt)
+    for form in (1, 2, 3):
+        tr.set_prefill_form(form)
+        tr.set_variant(tr.VARIANT_PREFILL)
+        try:
+            ex, z, m = tr.select_exit(dev, g, w.eps, W1, b1, w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers)
+            torch.cuda.synchronize()
+        finally:
+            tr.set_prefill_form(0)
+            tr.set_variant(tr.VARIANT_AUTO)
+        report(compare_select(f"{w.name}_form{form}", dtype, z.cpu().numpy(), ex.cpu().numpy(), m.cpu().numpy(),
+                              z_o, ex_o, m_o, rt.theta, w.layer_ids, 0, w.n_layers))
+    tr.set_variant(tr.VARIANT_DECODE)
+    try:
+        for t0 in range(0, T, 64):
+            t1 = min(T, t0 + 64)
+            ex, z, m = tr.select_exit(dev[:, t0:t1], g, w.eps, W1, b1, w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers)
+            torch.cuda.synchronize()
+            report(compare_select(f"{w.name}_decode_{t0}", dtype, z.cpu().numpy(), ex.cpu().numpy(), m.cpu().numpy(),
+                                  z_o[:, t0:t1], ex_o[t0:t1], m_o[t0:t1], rt.theta, w.layer_ids, 0, w.n_layers))
+    finally:
+        tr.set_variant(tr.VARIANT_AUTO)
+
+
 # ------------------------------------------------------------------ edge cases
 
 @pytest.mark.parametrize("T", [1, 63, 64, 65, 130, 257])

@@ -165,6 +165,43 @@ def test_cosine_labels_match_the_oracle(tr, dtype, d, T, C):
     assert lab_o.any() and not lab_o.all()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("d", [128, 384, 4096])
+def test_every_element_enters_the_norms_and_the_dot_product(tr, dtype, d):
+    """Row t of every checkpoint and of the last layer carries a spike at element t (mod d) that
+    holds most of the row's energy: losing one element's product in the projection's sum of squares
+    or in the cosine's dot product / norms shows far above the tolerances."""
+    import torch
+    C, T = 2, min(2 * d + 5, 1100)
+    rng = np.random.default_rng(d)
+    h = rng.standard_normal((C, T, d)).astype(np.float32)
+    f = rng.standard_normal((T, d)).astype(np.float32)
+    for t in range(T):
+        pos = (t * 7) % d
+        h[:, t, pos] = 40.0
+        f[t, pos] = 30.0
+    hb, fb = synth.to_storage(h, dtype), synth.to_storage(f, dtype)
+    layer_ids = np.array([3, 7], np.int32)
+    # cosine labels
+    sim_o, lab_o = oracle.cosine_labels(hb, dtype, fb, 0.9)
+    sim, lab = tr.cosine_labels(to_device(hb, dtype), to_device(fb, dtype), 0.9)
+    torch.cuda.synchronize()
+    err = np.abs(sim.cpu().numpy() - sim_o).max()
+    print(f"PARITY name=spike_cos_{dtype}_d{d} rows={C * T} max_abs_err={err:.3e}", flush=True)
+    assert err <= 2e-5
+    # projection
+    exits = np.where(np.arange(T) % 3 == 0, 3, np.where(np.arange(T) % 3 == 1, 7, 8)).astype(np.int32)
+    gain = np.ones(d, np.float32)
+    sentinel = synth.to_storage(np.full((T, d), 3.0, np.float32), dtype)
+    want, written = oracle.exit_project(hb, dtype, fb, exits, layer_ids, gain, 1e-5, out=sentinel.copy())
+    out = to_device(sentinel.copy(), dtype)
+    tr.exit_project(to_device(hb, dtype), to_device(fb, dtype), torch.from_numpy(exits).cuda(), layer_ids,
+                    torch.from_numpy(gain).cuda(), 1e-5, out=out)
+    torch.cuda.synchronize()
+    got = out.view(torch.int16).cpu().numpy().view(np.uint16) if dtype == "bf16" else out.cpu().numpy()
+    ulp_compare(f"spike_proj_{dtype}_d{d}", dtype, got, want, written == 1)
+
+
 @pytest.mark.parametrize("T", [0, 1, 63, 64, 65, 255, 257, 4096, 4097, 20000, 5000000])
 def test_batch_compact_matches_the_oracle(tr, T):
     """Index lists and counts are integers: bit-exact, including the order."""
