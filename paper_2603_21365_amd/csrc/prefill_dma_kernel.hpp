@@ -18,8 +18,8 @@
 // quarter of a full one instead of leaving most of the chip idle for a whole tile.  A piece of
 // 1/s of the rows takes s k-tiles per ring stage: every stage is the same number of bytes and
 // of transfers whatever the item, so the bytes in flight and the time per barrier stay those
-// of a full tile; its W1' fragments are fetched two k-tiles ahead instead of one, because a
-// k-tile of a piece is too little matrix work to cover the L2 round trip.
+// of a full tile; its W1' fragments are fetched a whole stage (s k-tiles) ahead instead of one
+// k-tile, because a k-tile of a piece is too little matrix work to cover the L2 round trip.
 //
 // Workgroup = kRowsM rows x all 128 columns; consumer wave w owns columns 32w..32w+31 of
 // every row (kRowsM/32 accumulator blocks), so each W1' fragment is fetched once per kRowsM
@@ -258,10 +258,13 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
 
         f32x16 acc[kActive];
         f32x16 acc1[kCB == 2 ? kActive : 1];        // second column half
+        f32x16 acc_odd[kActive];                    // pieces of one block: the odd groups' accumulator
+        u32x4 a_pipe[kActive];                      // pieces: the next group's A fragments
         float ssq[kActive];
 #pragma unroll
         for (int b = 0; b < kActive; ++b) {
             acc[b] = f32x16{0};
+            acc_odd[b] = f32x16{0};
             if constexpr (kCB == 2) acc1[b] = f32x16{0};
             ssq[b] = 0.0f;
         }
@@ -296,6 +299,35 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
                     if (g == wave) {                   // this wave's share of the sums of squares
 #pragma unroll
                         for (int b = 0; b < kActive; ++b) ssq[b] += sq[b];
+                    }
+                } else if constexpr (kActive < kBlocks && kBlocks == 4) {
+                    // (128-row kernel only: the 64-row kernel must stay within the registers that let
+                    // two workgroups share a CU.)  A piece has one or two matrix instructions per group: too few to hide the LDS
+                    // read of the next group's fragments behind them, and with a single block each
+                    // one would wait for the one before it (same accumulator).  So the next group's
+                    // fragments are read before this group's instructions are issued, and a single
+                    // block alternates between two accumulators.
+                    if (g == 0) {
+#pragma unroll
+                        for (int b = 0; b < kActive; ++b)
+                            a_pipe[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + y16);
+                    }
+                    u32x4 a[kActive];
+#pragma unroll
+                    for (int b = 0; b < kActive; ++b) a[b] = a_pipe[b];
+                    if (g + 1 < kMmaGroups) {
+#pragma unroll
+                        for (int b = 0; b < kActive; ++b)
+                            a_pipe[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + (y16 ^ ((g + 1) << 5)));
+                    }
+#pragma unroll
+                    for (int b = 0; b < kActive; ++b) {
+                        if (kActive == 1 && (g & 1)) acc_odd[b] = mma_k16<DT>(a[b], bf[g], acc_odd[b]);
+                        else acc[b] = mma_k16<DT>(a[b], bf[g], acc[b]);
+                    }
+                    if ((g & 3) == wave) {             // this wave's share of the sums of squares
+#pragma unroll
+                        for (int b = 0; b < kActive; ++b) ssq[b] = chunk_sumsq<DT>(a[b], ssq[b]);
                     }
                 } else {
                     u32x4 a[kActive];
@@ -423,39 +455,38 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
                 consume(bptr, 0, std::false_type{});
             }
         } else {
-            // ---- piece (always the last item of its workgroup): kSub k-tiles per stage, W1' two
-            // k-tiles ahead in two fragment sets used alternately (kSub is even).
+            // ---- piece (always the last item of its workgroup): kSub k-tiles per stage, one
+            // fragment set per k-tile of a stage, each refilled for the same k-tile of the next
+            // stage: W1' runs a whole stage (kSub k-tiles) ahead, which a piece can afford because
+            // its few accumulators leave the registers free.
             const int stages = ntile / kSub;
             int ks = first_stage(it);
-            u32x4 bnext[kFrags];                    // breg: k-tile j even of a stage, bnext: j odd
+            u32x4 bx[kSub - 1][kFrags];             // k-tile j of a stage: breg for j = 0, bx[j-1] otherwise
 #pragma unroll
-            for (int g = 0; g < kMmaGroups; ++g)
+            for (int j = 1; j < kSub; ++j)
 #pragma unroll
-                for (int pl = 0; pl < kPlanes; ++pl) bnext[g * kPlanes + pl] = b_fragment(bptr, ks * kSub + 1, g, pl);
-            auto consume = [&](int ks_next, auto last) {
+                for (int g = 0; g < kMmaGroups; ++g)
+#pragma unroll
+                    for (int pl = 0; pl < kPlanes; ++pl) bx[j - 1][g * kPlanes + pl] = b_fragment(bptr, ks * kSub + j, g, pl);
+            auto consume = [&](int ks_next, auto refill) {
                 ring_barrier();
                 const char* st = ring + (stage % kDmaStages) * kStageBytes + a_base;
 #pragma unroll
                 for (int j = 0; j < kSub; ++j) {
-                    // the set used by k-tile j is refilled with the k-tile two steps later
-                    const int kn = j + 2 < kSub ? ks * kSub + j + 2 : ks_next * kSub + (j + 2 - kSub);
-                    if (decltype(last)::value && j + 2 >= kSub) {
-                        if (j & 1) k_tile(st + j * kSubBytes, bnext, bptr, 0, std::false_type{});
-                        else k_tile(st + j * kSubBytes, breg, bptr, 0, std::false_type{});
-                    } else {
-                        if (j & 1) k_tile(st + j * kSubBytes, bnext, bptr, kn, std::true_type{});
-                        else k_tile(st + j * kSubBytes, breg, bptr, kn, std::true_type{});
-                    }
+                    if (j == 0) k_tile(st, breg, bptr, ks_next * kSub, refill);
+                    else k_tile(st + j * kSubBytes, bx[j > 0 ? j - 1 : 0], bptr, ks_next * kSub + j, refill);
                 }
                 ++stage;
             };
             for (int k = 0; k + 1 < stages; ++k) {
                 const int kn = ks + 1 >= stages ? 0 : ks + 1;
-                consume(kn, std::false_type{});
+                consume(kn, std::true_type{});
                 ks = kn;
             }
-            consume(0, std::true_type{});
+            consume(0, std::false_type{});
         }
+
+        if constexpr (kActive == 1 && kBlocks == 4 && DT != kF32 && kCB == 1) acc[0] += acc_odd[0];
 
         // ---- row sums of squares: lanes l and l^32 hold the two chunk phases; the 4 waves the rest
 #pragma unroll
