@@ -262,6 +262,7 @@ def main() -> int:
                                               out=outd)
             wall, ev = timed(lambda i: prepared(), 2000, 200)
             sp = spread()
+            p10 = round(sp_pct(timed.windows, 0.1) * 1e6, 2)
             # latency of a single call as a caller that needs the answer sees it: call, then wait
             lat = []
             for _ in range(1000):
@@ -270,9 +271,33 @@ def main() -> int:
                 torch.cuda.synchronize()
                 lat.append(time.perf_counter() - t0)
             lat.sort()
+            # the same call captured in a HIP graph (what a decode loop would replay every step)
+            cap_stream = torch.cuda.Stream()
+            graph = torch.cuda.CUDAGraph()
+            cap_stream.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(cap_stream):
+                prep_g = tr.prepare_select_exit(hd, g, wd.eps, W1, b1, w2, rt.b2, rt.theta, wd.layer_ids, 0, wd.n_layers,
+                                                out=outd)
+                prep_g()
+                cap_stream.synchronize()
+                with torch.cuda.graph(graph, stream=cap_stream):
+                    prep_g()
+            torch.cuda.synchronize()
+            wall_g, _ = timed(lambda i: graph.replay(), 2000, 200)
+            lat_g = []
+            for _ in range(1000):
+                t0 = time.perf_counter()
+                graph.replay()
+                torch.cuda.synchronize()
+                lat_g.append(time.perf_counter() - t0)
+            lat_g.sort()
             dec[f"T{Td}"] = {"us_per_call": round(wall / 2000 * 1e6, 2), "calls_per_s": round(2000 / wall, 1),
+                             "hip_graph": {"us_per_replay": round(wall_g / 2000 * 1e6, 2),
+                                           "us_replay_plus_sync_median": round(lat_g[500] * 1e6, 2),
+                                           "note": "the call is one kernel: a graph replay costs more than the direct "
+                                                   "launch; capture pays off only when it spans several calls"},
                              "us_per_call_hip_events": round(ev / 2000 * 1e6, 2),
-                             "us_per_call_spread": {"p10": round(sp_pct(timed.windows, 0.1) * 1e6, 2), "median": sp["median"],
+                             "us_per_call_spread": {"p10": p10, "median": sp["median"],
                                                     "p90": sp["p90"], "windows": sp["windows"], "calls_per_window": 16},
                              "us_call_plus_sync": {"p10": round(lat[100] * 1e6, 2), "median": round(lat[500] * 1e6, 2),
                                                    "p90": round(lat[900] * 1e6, 2), "calls": 1000}}
