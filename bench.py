@@ -271,6 +271,11 @@ def main() -> int:
                 torch.cuda.synchronize()
                 lat.append(time.perf_counter() - t0)
             lat.sort()
+            # the same step on pre-packed fp16 weights (the serving loop's form)
+            pk16 = tr.router_pack(tr.F16, g, W1)
+            prep_pk = tr.prepare_select_exit_packed(hd, pk16, wd.eps, b1, w2, rt.b2, rt.theta, wd.layer_ids, 0, wd.n_layers,
+                                                    d=d, out=outd)
+            wall_k, _ = timed(lambda i: prep_pk(), 2000, 200)
             # the same call captured in a HIP graph (what a decode loop would replay every step)
             cap_stream = torch.cuda.Stream()
             graph = torch.cuda.CUDAGraph()
@@ -292,6 +297,7 @@ def main() -> int:
                 lat_g.append(time.perf_counter() - t0)
             lat_g.sort()
             dec[f"T{Td}"] = {"us_per_call": round(wall / 2000 * 1e6, 2), "calls_per_s": round(2000 / wall, 1),
+                             "packed_weights_us_per_call": round(wall_k / 2000 * 1e6, 2),
                              "hip_graph": {"us_per_replay": round(wall_g / 2000 * 1e6, 2),
                                            "us_replay_plus_sync_median": round(lat_g[500] * 1e6, 2),
                                            "note": "the call is one kernel: a graph replay costs more than the direct "

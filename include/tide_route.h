@@ -33,10 +33,11 @@
  *  - T == 0 is a successful no-op.  1 <= C <= 32.
  *  - The threshold test is taken on the logit: z > ln(theta/(1-theta)) for 0 < theta < 1,
  *    never for theta >= 1 (the paper's "1.0 (off)", Table 4), always for theta <= 0.
- *  - The entry points that take raw router weights, and tide_select_exit_packed, use a
- *    per-device workspace that the library allocates (hipMalloc) on first use and when a
- *    larger problem arrives; calls that share it on one device must be ordered on one
- *    stream.  tide_release() frees it.
+ *  - The router entry points (raw or packed weights) use a per-device workspace that the
+ *    library allocates (hipMalloc) on first use and when a larger problem arrives; calls that
+ *    share it on one device must be ordered on one stream.  tide_release() frees it.
+ *  - Up to 32 rows per checkpoint (a decode step) run on a latency kernel that splits each
+ *    router's contraction over the whole chip; larger T on the streaming kernels.
  */
 #ifndef TIDE_ROUTE_H
 #define TIDE_ROUTE_H
@@ -177,7 +178,7 @@ int tide_batch_exit(const uint32_t* fire_mask, int64_t T, int64_t C, const int32
                     int32_t min_layer, int32_t no_exit_layer, int32_t* batch_exit_layer,
                     uint32_t* all_fire_mask, uint32_t* fire_counts, void* stream);
 
-/* Force a kernel variant for the raw-weight entry points (process-wide; for tests and
+/* Force a kernel variant for the router entry points (process-wide; for tests and
  * benchmarks).  Returns the previous setting, or TIDE_ERR_INVALID_ARG.                  */
 int tide_set_variant(int variant);
 

@@ -18,7 +18,9 @@ struct DecodeParams {
     const char* hidden;
     int64_t ckpt_stride_bytes, row_stride_bytes;
     const float* gamma;   // [C][d] or null
-    const float* W1;      // [C][d][b]
+    const float* W1;      // [C][d][b] raw weights, or null when `packed` is given
+    const u32x4* packed;  // [C][halves][planes][dpad*16 chunks] packed W1' (gamma folded in), or null
+    int dpad;             // rows of the packed weights (d rounded up to whole k-tiles)
     const float* b1;      // [C][b] or null
     const float* w2;      // [C][b]
     int C, T, d, S;       // S = ceil(d / kDecodeSlice); the last slice may be partial (any d with 16-byte rows)
@@ -54,6 +56,78 @@ template <> __device__ __forceinline__ void chunk_to_f32<kBF16>(u32x4 c, float* 
         out[2 * e] = __uint_as_float(c[e] << 16);
         out[2 * e + 1] = __uint_as_float(c[e] & 0xffff0000u);
     }
+}
+
+// The tail of both decode kernels.  Every workgroup of checkpoint c has written its partial
+// pre-activations (and, for column half 0, its partial sum of squares) to p.part; the last one to
+// arrive reduces them in a fixed order, finishes the router and reports on the arrival words.
+template <int kHalves>
+__device__ __forceinline__ void decode_finish(const DecodeParams& p, int c, int* flag) {
+    constexpr int part_stride = kHalves * kBottleneck + kPartPad;
+    const int tid = threadIdx.x;
+    stage_writes_done();
+    if (!last_arrival(p.counter + c, (uint32_t)(p.S * kHalves), flag)) return;
+
+    {
+        const int tl = tid >> 5, q = tid & 31;          // 8 tokens x 32 column quads (per half) per pass
+        f32x4 b1v[kHalves], w2v[kHalves];
+#pragma unroll
+        for (int hf = 0; hf < kHalves; ++hf) {
+            const int col = hf * kBottleneck + 4 * q;
+            b1v[hf] = f32x4{0, 0, 0, 0};
+            w2v[hf] = f32x4{0, 0, 0, 0};
+            if (col < p.b) {
+                if (p.b1) b1v[hf] = *reinterpret_cast<const f32x4*>(p.b1 + c * p.b + col);
+                w2v[hf] = *reinterpret_cast<const f32x4*>(p.w2 + c * p.b + col);
+            }
+        }
+        const float* pc = p.part + (size_t)c * p.S * p.T * part_stride;
+        for (int t0 = 0; t0 < p.T; t0 += kDecodeTB) {
+            const int t = t0 + tl;
+            const bool valid = t < p.T;
+            f32x4 a[kHalves];
+            float ssum = 0.0f;
+            constexpr int kBatch = 32;                  // partials in flight per thread
+#pragma unroll
+            for (int hf = 0; hf < kHalves; ++hf) {
+                a[hf] = f32x4{0, 0, 0, 0};
+                for (int s0 = 0; s0 < p.S; s0 += kBatch) {
+                    f32x4 v[kBatch];
+#pragma unroll
+                    for (int u = 0; u < kBatch; ++u) {
+                        v[u] = f32x4{0, 0, 0, 0};
+                        if (valid && s0 + u < p.S)
+                            v[u] = stage_load4(pc + ((size_t)(s0 + u) * p.T + t) * part_stride + hf * kBottleneck + 4 * q);
+                    }
+                    float sv = 0.0f;
+                    if (hf == 0 && valid && s0 + q < p.S)
+                        sv = stage_load(pc + ((size_t)(s0 + q) * p.T + t) * part_stride + kHalves * kBottleneck);
+#pragma unroll
+                    for (int u = 0; u < kBatch; ++u) a[hf] += v[u];
+                    if (hf == 0) ssum += xor_reduce_sum<5>(sv);          // fixed order: deterministic
+                }
+            }
+            const float r = 1.0f / sqrtf(ssum / (float)p.d + p.eps);
+            float term = 0.0f;
+#pragma unroll
+            for (int hf = 0; hf < kHalves; ++hf)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) term += w2v[hf][j] * silu_f32(fmaf(r, a[hf][j], b1v[hf][j]));
+            term = xor_reduce_sum<5>(term);
+            if (valid && q == 0) {
+                const float z = p.tab.b2[c] + term;
+                const int64_t o = (int64_t)c * p.T + t;
+                const bool f = z > p.tab.thr_logit[c];
+                if (p.logits) p.logits[o] = z;
+                if (p.prob) p.prob[o] = sigmoid_f32(z);
+                if (p.fire) p.fire[o] = f ? 1 : 0;
+                if (p.exit_layer)
+                    report_and_select(p.tab, p.C, c, f, p.min_layer, p.no_exit, p.arrive + t, p.exit_layer + t,
+                                      p.fire_mask ? p.fire_mask + t : nullptr);
+            }
+        }
+    }
+    if (tid == 0) __hip_atomic_store(p.counter + c, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // kHalves = p.halves as a compile-time value (1 or 2): the width-128 kernel carries no code or
@@ -160,70 +234,121 @@ __global__ __launch_bounds__(kDecodeThreads) void tide_decode_kernel(const Decod
         __syncthreads();
     }
 
-    // ---- last workgroup of this checkpoint finishes the router ----
-    stage_writes_done();
-    if (!last_arrival(p.counter + c, (uint32_t)(p.S * kHalves), &flag)) return;
+    decode_finish<kHalves>(p, c, &flag);
+}
 
-    {
-        const int tl = tid >> 5, q = tid & 31;          // 8 tokens x 32 column quads (per half) per pass
-        f32x4 b1v[kHalves], w2v[kHalves];
+// The same with pre-packed weights (the serving loop's form: gamma already folded in, half the
+// bytes of fp32 weights).  A packed chunk holds, for lane = 32h + j of column block nb and 16-k
+// group G, the eight values W1'[16G + 8h + e][32 nb + j]; thread (nb = tid / 64, lane) therefore
+// owns ONE column and walks the slice's eight groups, so the four waves split the columns, not k:
+// no cross-wave reduction, only lanes l and l^32 (the two k halves of a group) meet.
+template <int DT, int kHalves>
+__global__ __launch_bounds__(kDecodeThreads) void tide_decode_packed_kernel(const DecodeParams p) {
+    constexpr int E = Storage<DT>::kElems;
+    constexpr int kChunksPerTok = kDecodeSlice / E;
+    constexpr int kGroups = kDecodeSlice / 16;               // 16-k groups per slice
+    constexpr int kPlanes = Compute<DT>::kPlanes;            // fp32: W1' = hi plane + mid plane
+    __shared__ float xs[kDecodeTB][kDecodeSlice];            // raw inputs of this slice (gamma is in the weights)
+    __shared__ float ss_lds[kDecodeTB];
+    __shared__ int flag;
+
+    const int tid = threadIdx.x, lane = tid & 63, nb = tid >> 6;
+    const int nblk = p.C * p.S * kHalves;
+    const int per_xcd = (nblk + 7) >> 3;
+    const int work = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (work >= nblk) return;
+    const int c = work / (p.S * kHalves);
+    const int rest = work - c * p.S * kHalves;
+    const int s = rest / kHalves, half = rest - s * kHalves;
+    const int k0 = s * kDecodeSlice;
+    constexpr int part_stride = kHalves * kBottleneck + kPartPad;
+
+    // ---- this thread's weights: 8 groups x 8 consecutive k of one column, as fp32 ----
+    const size_t plane_chunks = (size_t)p.dpad * 16;
+    const u32x4* pk = p.packed + ((size_t)c * kHalves + half) * kPlanes * plane_chunks + (size_t)(k0 / 16) * 256 + tid;
+    float wv[kGroups][8];
 #pragma unroll
-        for (int hf = 0; hf < kHalves; ++hf) {
-            const int col = hf * kBottleneck + 4 * q;
-            b1v[hf] = f32x4{0, 0, 0, 0};
-            w2v[hf] = f32x4{0, 0, 0, 0};
-            if (col < p.b) {
-                if (p.b1) b1v[hf] = *reinterpret_cast<const f32x4*>(p.b1 + c * p.b + col);
-                w2v[hf] = *reinterpret_cast<const f32x4*>(p.w2 + c * p.b + col);
+    for (int G = 0; G < kGroups; ++G) {
+        // groups at and beyond the packed rows (a partial last slice) read as zeros, branch-free
+        const bool gok = k0 + 16 * G < p.dpad;
+        const size_t goff = gok ? (size_t)G * 256 : 0;
+        u32x4 hi = pk[goff];
+        if (!gok) hi = u32x4{0, 0, 0, 0};
+        if constexpr (DT == kF16) {
+            const f16x8 h8 = __builtin_bit_cast(f16x8, hi);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) wv[G][e] = (float)h8[e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                wv[G][2 * e] = __uint_as_float(hi[e] << 16);
+                wv[G][2 * e + 1] = __uint_as_float(hi[e] & 0xffff0000u);
             }
-        }
-        const float* pc = p.part + (size_t)c * p.S * p.T * part_stride;
-        for (int t0 = 0; t0 < p.T; t0 += kDecodeTB) {
-            const int t = t0 + tl;
-            const bool valid = t < p.T;
-            f32x4 a[kHalves];
-            float ssum = 0.0f;
-            constexpr int kBatch = 32;                  // partials in flight per thread
+            if constexpr (DT == kF32) {
+                u32x4 mid = pk[plane_chunks + goff];
+                if (!gok) mid = u32x4{0, 0, 0, 0};
 #pragma unroll
-            for (int hf = 0; hf < kHalves; ++hf) {
-                a[hf] = f32x4{0, 0, 0, 0};
-                for (int s0 = 0; s0 < p.S; s0 += kBatch) {
-                    f32x4 v[kBatch];
-#pragma unroll
-                    for (int u = 0; u < kBatch; ++u) {
-                        v[u] = f32x4{0, 0, 0, 0};
-                        if (valid && s0 + u < p.S)
-                            v[u] = stage_load4(pc + ((size_t)(s0 + u) * p.T + t) * part_stride + hf * kBottleneck + 4 * q);
-                    }
-                    float sv = 0.0f;
-                    if (hf == 0 && valid && s0 + q < p.S)
-                        sv = stage_load(pc + ((size_t)(s0 + q) * p.T + t) * part_stride + kHalves * kBottleneck);
-#pragma unroll
-                    for (int u = 0; u < kBatch; ++u) a[hf] += v[u];
-                    if (hf == 0) ssum += xor_reduce_sum<5>(sv);          // fixed order: deterministic
+                for (int e = 0; e < 4; ++e) {
+                    wv[G][2 * e] += __uint_as_float(mid[e] << 16);
+                    wv[G][2 * e + 1] += __uint_as_float(mid[e] & 0xffff0000u);
                 }
-            }
-            const float r = 1.0f / sqrtf(ssum / (float)p.d + p.eps);
-            float term = 0.0f;
-#pragma unroll
-            for (int hf = 0; hf < kHalves; ++hf)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) term += w2v[hf][j] * silu_f32(fmaf(r, a[hf][j], b1v[hf][j]));
-            term = xor_reduce_sum<5>(term);
-            if (valid && q == 0) {
-                const float z = p.tab.b2[c] + term;
-                const int64_t o = (int64_t)c * p.T + t;
-                const bool f = z > p.tab.thr_logit[c];
-                if (p.logits) p.logits[o] = z;
-                if (p.prob) p.prob[o] = sigmoid_f32(z);
-                if (p.fire) p.fire[o] = f ? 1 : 0;
-                if (p.exit_layer)
-                    report_and_select(p.tab, p.C, c, f, p.min_layer, p.no_exit, p.arrive + t, p.exit_layer + t,
-                                      p.fire_mask ? p.fire_mask + t : nullptr);
             }
         }
     }
-    if (tid == 0) __hip_atomic_store(p.counter + c, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+    const char* base = p.hidden + (int64_t)c * p.ckpt_stride_bytes + (int64_t)k0 * Storage<DT>::kBytes;
+    const int h8 = (lane >> 5) * 8;                          // this lane's k offset within a group
+    for (int t0 = 0; t0 < p.T; t0 += kDecodeTB) {
+        const int nt = min(kDecodeTB, p.T - t0);
+        for (int q = tid; q < kDecodeTB * kChunksPerTok; q += kDecodeThreads) {
+            const int t = q / kChunksPerTok, ch = q - t * kChunksPerTok;
+            u32x4 v = {0, 0, 0, 0};
+            const bool inside = k0 + ch * E < p.d;
+            if (t < nt && inside) v = *reinterpret_cast<const u32x4*>(base + (int64_t)(t0 + t) * p.row_stride_bytes + ch * 16);
+            float f[E];
+            chunk_to_f32<DT>(v, f);
+            float sq = 0.0f;
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                sq = fmaf(f[e], f[e], sq);
+                xs[t][ch * E + e] = f[e];
+            }
+            sq = xor_reduce_sum<(kChunksPerTok == 16 ? 4 : 5)>(sq);
+            if (ch == 0) ss_lds[t] = sq;
+        }
+        __syncthreads();
+
+        float acc[kDecodeTB];
+#pragma unroll
+        for (int t = 0; t < kDecodeTB; ++t) acc[t] = 0.0f;
+#pragma unroll
+        for (int G = 0; G < kGroups; ++G) {
+#pragma unroll
+            for (int t = 0; t < kDecodeTB; ++t) {
+                const f32x4 x0 = *reinterpret_cast<const f32x4*>(&xs[t][16 * G + h8]);
+                const f32x4 x1 = *reinterpret_cast<const f32x4*>(&xs[t][16 * G + h8 + 4]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    acc[t] = fmaf(x0[e], wv[G][e], acc[t]);
+                    acc[t] = fmaf(x1[e], wv[G][4 + e], acc[t]);
+                }
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < kDecodeTB; ++t) {
+            const float v = acc[t] + __shfl_xor(acc[t], 32, kWave);
+            if (lane < 32 && t < nt) {
+                float* dst = p.part + (((size_t)c * p.S + s) * p.T + t0 + t) * part_stride;
+                stage_store(dst + half * kBottleneck + 32 * nb + lane, v);
+            }
+        }
+        if (tid < nt && half == 0) {
+            float* dst = p.part + (((size_t)c * p.S + s) * p.T + t0 + tid) * part_stride;
+            stage_store(dst + kHalves * kBottleneck, ss_lds[tid]);
+        }
+        __syncthreads();
+    }
+    decode_finish<kHalves>(p, c, &flag);
 }
 
 }  // namespace tide

@@ -299,7 +299,7 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
 }
 
 int launch_decode(Workspace& ws, const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int64_t ckpt_stride,
-                  int64_t row_stride, const float* gamma, const float* W1, float eps, const float* b1, const float* w2,
+                  int64_t row_stride, const float* gamma, const float* W1, const void* packed, float eps, const float* b1, const float* w2,
                   const CheckpointTable& tab, int32_t min_layer, int32_t no_exit, const Outputs& o, hipStream_t st) {
     DecodeParams p;
     std::memset(&p, 0, sizeof(p));
@@ -309,6 +309,8 @@ int launch_decode(Workspace& ws, const void* hidden, int dtype, int64_t C, int64
     p.row_stride_bytes = row_stride * (int64_t)eb;
     p.gamma = gamma;
     p.W1 = W1;
+    p.packed = (const u32x4*)packed;
+    p.dpad = (int)padded_hidden(dtype, d);
     p.b1 = b1;
     p.w2 = w2;
     p.C = (int)C;
@@ -340,10 +342,15 @@ int launch_decode(Workspace& ws, const void* hidden, int dtype, int64_t C, int64
     const int nblk = p.C * p.S * p.halves;
     const unsigned grid = 8u * (unsigned)((nblk + 7) / 8);
     by_dtype(dtype, [&](auto dt) {
-        if (p.halves == 2)
-            hipLaunchKernelGGL((tide_decode_kernel<decltype(dt)::value, 2>), dim3(grid), dim3(kDecodeThreads), 0, st, p);
+        constexpr int DT = decltype(dt)::value;
+        if (p.packed && p.halves == 2)
+            hipLaunchKernelGGL((tide_decode_packed_kernel<DT, 2>), dim3(grid), dim3(kDecodeThreads), 0, st, p);
+        else if (p.packed)
+            hipLaunchKernelGGL((tide_decode_packed_kernel<DT, 1>), dim3(grid), dim3(kDecodeThreads), 0, st, p);
+        else if (p.halves == 2)
+            hipLaunchKernelGGL((tide_decode_kernel<DT, 2>), dim3(grid), dim3(kDecodeThreads), 0, st, p);
         else
-            hipLaunchKernelGGL((tide_decode_kernel<decltype(dt)::value, 1>), dim3(grid), dim3(kDecodeThreads), 0, st, p);
+            hipLaunchKernelGGL((tide_decode_kernel<DT, 1>), dim3(grid), dim3(kDecodeThreads), 0, st, p);
         return 0;
     });
     TIDE_HIP(hipGetLastError());
@@ -366,8 +373,8 @@ int run(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t 
     Workspace* ws = nullptr;
     int rc = current_workspace(&ws);
     if (rc) return rc;
-    if (W1 && use_decode(T))
-        return launch_decode(*ws, hidden, dtype, C, T, d, b, ckpt_stride, row_stride, gamma, W1, eps, b1, w2, tab,
+    if (use_decode(T))
+        return launch_decode(*ws, hidden, dtype, C, T, d, b, ckpt_stride, row_stride, gamma, W1, packed, eps, b1, w2, tab,
                              min_layer, no_exit, o, st);
     if (W1) {
         rc = reserve(ws->packed, (size_t)C * tide_packed_router_bytes(dtype, d, b), false);

@@ -168,6 +168,9 @@ def test_config2_decode(tr, T):
                                                 variant=tr.VARIANT_PREFILL)
     assert st_d["max_abs_err"] < 1e-4                    # the decode variant computes in fp32 on fp32 weights
     assert np.abs(z_d - z_p).max() < 2e-2
+    # packed weights, small T: the decode kernel's packed form (fp16 weights, fp32 arithmetic)
+    st_k, _, (ex_k, z_k, m_k) = run_and_compare(tr, w, f"config2_T{T}_packed", rt=rt, hidden_bits=hb, packed=True)
+    assert st_k["max_abs_err"] < 5e-3
 
 
 # ------------------------------------------------------------------ config 3: 36-layer batched prefill, bf16, full size
@@ -249,6 +252,7 @@ def test_bottleneck_widths_decode(tr, b, T, dtype):
     rt.b2[:] = np.linspace(-0.3, 0.3, w.C)
     st, _, _ = run_and_compare(tr, w, w.name, rt=rt, variant=tr.VARIANT_DECODE)
     assert st["max_abs_err"] < 1e-4
+    run_and_compare(tr, w, w.name + "_packed", rt=rt, variant=tr.VARIANT_DECODE, packed=True)
 
 
 # ------------------------------------------------------------------ hidden sizes that are not multiples of 128
@@ -274,14 +278,19 @@ def test_generic_fallback_for_other_hidden_sizes(tr, dtype, d, b):
     wide[:, :T, :d] = hb
     dev = to_device(wide, dtype)
     g, W1, b1, w2 = routers_to_device(rt)
-    for variant, Tn in ((tr.VARIANT_PREFILL, T), (tr.VARIANT_DECODE, 21)):
+    pk = tr.router_pack(tr.DTYPE_CODES[dtype], g, W1)
+    for variant, Tn, use_packed in ((tr.VARIANT_PREFILL, T, False), (tr.VARIANT_DECODE, 21, False), (tr.VARIANT_DECODE, 21, True)):
         tr.set_variant(variant)
         try:
-            ex, z, m = tr.select_exit(dev[:, :Tn, :], g, w.eps, W1, b1, w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers)
+            if use_packed:
+                ex, z, m = tr.select_exit_packed(dev[:, :Tn, :], pk, w.eps, b1, w2, rt.b2, rt.theta, w.layer_ids, 0,
+                                                 w.n_layers, d=d)
+            else:
+                ex, z, m = tr.select_exit(dev[:, :Tn, :], g, w.eps, W1, b1, w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers)
             torch.cuda.synchronize()
         finally:
             tr.set_variant(tr.VARIANT_AUTO)
-        st = compare_select(f"{w.name}_v{variant}", dtype, z.cpu().numpy(), ex.cpu().numpy(), m.cpu().numpy(),
+        st = compare_select(f"{w.name}_v{variant}{'_packed' if use_packed else ''}", dtype, z.cpu().numpy(), ex.cpu().numpy(), m.cpu().numpy(),
                             z_o[:, :Tn], ex_o[:Tn], m_o[:Tn], rt.theta, w.layer_ids, 0, w.n_layers)
         report(st)
 
@@ -376,6 +385,8 @@ def test_decode_variant_token_counts(tr, T, C, dtype):
     rt = w.routers()
     rt.b2[:] = np.linspace(-0.2, 0.2, C)
     run_and_compare(tr, w, w.name, rt=rt, hidden_bits=hb, variant=tr.VARIANT_DECODE)
+    # the same on pre-packed weights (bf16 / fp16 weights, or hi + mid bf16 planes for fp32 rows)
+    run_and_compare(tr, w, w.name + "_packed", rt=rt, hidden_bits=hb, variant=tr.VARIANT_DECODE, packed=True)
 
 
 def test_thresholds_off_and_always_and_min_layer(tr):
