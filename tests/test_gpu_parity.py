@@ -478,6 +478,32 @@ def test_largest_hidden_size_and_side_stream(tr):
     report(compare_select("d16384", "bf16", z, ex, m, z_o, ex_o, m_o, rt.theta, w.layer_ids, 0, w.n_layers))
 
 
+@pytest.mark.parametrize("T,variant", [(300, "prefill"), (5, "decode")])
+def test_the_maximum_of_32_checkpoints(tr, T, variant):
+    """C = 32 fills the 32-bit fire mask (bit 31 included) and the arrival word's count."""
+    w = synth.Workload(f"C32_T{T}", 59, "bf16", 256, 32, 1, T, None)
+    assert w.C == 32
+    rt = w.routers()
+    rt.b2[:] = np.linspace(-0.3, 0.5, 32)            # the last checkpoints fire more often
+    v = tr.VARIANT_PREFILL if variant == "prefill" else tr.VARIANT_DECODE
+    _, (ex_o, z_o, m_o), _ = run_and_compare(tr, w, w.name, rt=rt, variant=v)
+    assert (m_o >> 31).any() and not (m_o >> 31).all()
+    run_and_compare(tr, w, w.name + "_packed_min_layer", rt=rt, variant=v, packed=True, min_layer=17)
+
+
+def test_empty_batch_is_a_no_op(tr):
+    import torch
+    w = synth.Workload("empty", 61, "bf16", 256, 8, 4, 0, None)
+    rt = w.routers()
+    g, W1, b1, w2 = routers_to_device(rt)
+    hidden = torch.empty((w.C, 0, w.d), dtype=torch.bfloat16, device="cuda")
+    ex, z, m = tr.select_exit(hidden, g, w.eps, W1, b1, w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers)
+    torch.cuda.synchronize()
+    assert ex.shape == (0,) and z.shape == (w.C, 0) and m.shape == (0,)
+    prob, fire, logit = tr.router_eval(hidden[0], g[0], w.eps, W1[0], b1[0], w2[0], 0.0, 0.5)
+    assert prob.shape == (0,) and fire.shape == (0,) and logit.shape == (0,)
+
+
 def test_router_eval_outputs_are_optional_and_packed_matches_raw(tr):
     import torch
     w = synth.Workload("eval_opt", 28, "bf16", 4096, 4, 4, 777, None)
