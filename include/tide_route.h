@@ -183,7 +183,8 @@ int tide_batch_exit(const uint32_t* fire_mask, int64_t T, int64_t C, const int32
 int tide_set_variant(int variant);
 
 /* Choose the prefill kernel's form (process-wide; for tests and tuning): 0 = automatic,
- * 1 / 2 = streaming form with 64 / 128 rows per workgroup, 3 = register-ring form.
+ * 1 / 2 = streaming form with 64 / 128 rows per workgroup, 3 = register-ring form, 4 = wide-tile
+ * form (256 rows per workgroup, 16-bit types) for as many whole tiles as there are workgroups.
  * All forms compute the same function.  Returns the previous setting, or TIDE_ERR_INVALID_ARG. */
 int tide_set_prefill_form(int form);
 

@@ -61,7 +61,7 @@ struct WorkItem {
     int tile, row_off, blocks;
 };
 
-// Work schedule of a persistent workgroup.  The checkpoint-major tile list is cut into 8
+// Work schedule of a persistent workgroup.  The checkpoint-major tile list (from tile_begin on) is cut into 8
 // contiguous slices, slice x -> XCD x (workgroup id mod 8), so that an XCD's L2 holds one W1'
 // at a time.  The g workgroups of an XCD deal its slice out round-robin: q full rounds, then the
 // r < g tiles left over, each cut into s pieces (s = 4 if 4r <= g, 2 if 2r <= g, else 1; s must
@@ -69,10 +69,10 @@ struct WorkItem {
 template <int kBlocks>
 struct TileWalk {
     int lo, j, g, q, s, count, i;
-    __device__ TileWalk(int total_tiles, int ntile) {
-        const int per_xcd = (total_tiles + 7) >> 3;
+    __device__ TileWalk(int tile_begin, int total_tiles, int ntile) {
+        const int per_xcd = (total_tiles - tile_begin + 7) >> 3;
         const int xcd = blockIdx.x & 7;
-        lo = xcd * per_xcd;
+        lo = tile_begin + xcd * per_xcd;
         const int n = max(min(lo + per_xcd, total_tiles) - lo, 0);
         g = gridDim.x >> 3;
         j = blockIdx.x >> 3;
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
     };
 
     // (two column halves: the tiles of the last round are not cut -- passing one k-tile rules it out)
-    TileWalk<kBlocks> walk(p.total_tiles, kCB == 1 ? ntile : 1);
+    TileWalk<kBlocks> walk(p.tile_begin, p.total_tiles, kCB == 1 ? ntile : 1);
     if (!walk.valid()) return;
 
     if (wave >= kDmaConsumers) {

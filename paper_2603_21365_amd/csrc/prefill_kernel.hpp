@@ -34,8 +34,10 @@ struct PrefillParams {
     int dpad;                  // d rounded up to whole k-tiles (128 elements of 16 bits, 64 of fp32): the packed
                                // weights have dpad rows, zero beyond d; equal to d in the streaming form
     int b;                     // bottleneck width: 64, 128 or 256 (columns >= b of the last half are zero padding)
-    int tiles_per_ckpt;        // ceil(T / kRows)
+    int tiles_per_ckpt;        // ceil(T / rows per tile)
     int total_tiles;           // C * tiles_per_ckpt
+    int tile_begin;            // first tile of the checkpoint-major list this launch covers (the streaming
+                               // kernels: the tiles before it went to the wide-tile kernel), else 0
     float eps;
     int32_t min_layer, no_exit;
     // outputs (each may be null)

@@ -1,0 +1,204 @@
+// Prefill kernel, wide-tile form: the streaming computation of prefill_dma_kernel.hpp (paper
+// Eq. (2), Sec. 3.4 kernel 1, Fig. 1 inference step 3) on tiles of 256 rows, for batches large
+// enough to give every CU whole 256-row tiles.
+//
+// Why another form.  What bounds the 128-row kernel is not HBM but the L2 -> CU path: every
+// hidden byte crosses it once and, because a 128-row tile needs its checkpoint's whole W1',
+// so does one byte of W1' per hidden byte.  Twice the rows per fetch of W1' halves that second
+// stream.  256 rows of accumulators do not fit one wave, so
+//   - W1' goes through LDS as well: the producer waves transfer the k-tile's fragments (one
+//     contiguous 16 KiB of the packed weights) into the ring next to the rows, ONCE per
+//     workgroup, and
+//   - 8 consumer waves read them from there: wave cw owns rows 128 (cw / 4) .. +127 and columns
+//     32 (cw % 4) .. +31, four 32x32 accumulator blocks like a consumer of the 128-row kernel.
+// Consumers issue no global loads at all.  A k-tile is 64 elements (128 bytes of a row) so that a
+// ring of three stages (32 KiB of rows + 16 KiB of W1' each) fits the 160 KiB of LDS.
+// 16-bit storage types, bottleneck widths 64 and 128, d a multiple of 128.
+#pragma once
+#include "device_utils.hpp"
+#include "prefill_dma_kernel.hpp"
+
+namespace tide {
+
+constexpr int kWideRows = 256;
+constexpr int kWideTileBytes = 128;                 // bytes of each row per stage (64 elements)
+constexpr int kWideStages = 3;
+constexpr int kWideConsumers = 8;
+constexpr int kWideThreads = (kWideConsumers + kDmaProducers) * kWave;        // 640
+constexpr int kWideABytes = kWideRows * kWideTileBytes;                      // 32 KiB of rows per stage
+constexpr int kWideBBytes = (kWideTileBytes / 2) * kBottleneck * 2;           // 16 KiB of W1' per stage
+constexpr int kWideStageBytes = kWideABytes + kWideBBytes;
+constexpr int kWideAInstr = kWideABytes / 1024 / kDmaProducers;               // 16 transfers of rows per producer and stage
+constexpr int kWideBInstr = kWideBBytes / 1024 / kDmaProducers;               // 8 transfers of W1'
+constexpr int kWideLdsBytes = kWideStages * kWideStageBytes + (4 + 4 + 1) * kWideRows * (int)sizeof(float);
+
+// p.total_tiles counts 256-row tiles here and is a multiple of the grid size (the host hands the
+// rest of the batch to the 128-row kernel); p.tiles_per_ckpt = ceil(T / 256).
+template <int DT>
+__global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(const PrefillParams p) {
+    static_assert(DT != kF32, "16-bit storage types only");
+    typedef __attribute__((address_space(3))) char lds_char;
+    typedef __attribute__((address_space(1))) const char glb_char;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* ring = smem;
+    float* ss_part = reinterpret_cast<float*>(smem + kWideStages * kWideStageBytes);   // [4][256]
+    float* z_part = ss_part + 4 * kWideRows;                                           // [4][256]
+    float* inv_rms = z_part + 4 * kWideRows;                                           // [256]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nstage = p.d * Storage<DT>::kBytes / kWideTileBytes;      // k-tiles of a row
+    // XCD x (workgroup id mod 8) walks the x-th eighth of the checkpoint-major tile list, its
+    // workgroups round-robin: an XCD's L2 holds one W1' at a time.
+    const int per_xcd = p.total_tiles >> 3, g = gridDim.x >> 3;
+    const int lo = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    const int count = per_xcd / g;                                       // tiles of this workgroup
+    auto tile_of = [&](int i) { return lo + i * g; };
+    auto first_stage = [&](int tile) { return (int)(((unsigned)tile * 5u) % (unsigned)nstage); };
+    const size_t ckpt_chunks = (size_t)p.d * kBottleneck / Storage<DT>::kElems;
+
+    if (wave >= kWideConsumers) {
+        // ------------------------------------------------------------------ producers
+        const int pw = wave - kWideConsumers;
+        // rows: one transfer = 8 rows x 128 bytes; lane -> (row within the transfer, LDS chunk slot),
+        // the global chunk is the slot XOR bits 1..3 of the row (what the consumers undo)
+        const int rl = lane >> 3, slot = lane & 7;
+        const char* gp[kWideAInstr];
+        const char* bp = nullptr;              // this producer's half of the k-tile's 16 KiB of W1', stage 0
+        int f_rot = 0, f_k = 0, f_item = 0;
+        auto aim = [&](int tile) {
+            const int c = tile / p.tiles_per_ckpt;
+            const int row0 = (tile - c * p.tiles_per_ckpt) * kWideRows;
+            const char* base = p.hidden + (int64_t)c * p.ckpt_stride_bytes;
+#pragma unroll
+            for (int i = 0; i < kWideAInstr; ++i) {
+                const int row = (pw * kWideAInstr + i) * 8 + rl;
+                int r = row0 + row;
+                r = r < p.T ? r : p.T - 1;                                  // ragged tail: re-read the last row
+                gp[i] = base + (int64_t)r * p.row_stride_bytes + ((slot ^ ((row >> 1) & 7)) << 4);
+            }
+            bp = reinterpret_cast<const char*>(p.packed + (size_t)c * ckpt_chunks) + pw * (kWideBBytes / kDmaProducers) + lane * 16;
+            f_rot = first_stage(tile);
+            f_k = 0;
+        };
+        aim(tile_of(0));
+        int issued = 0;
+        bool fetch_done = false;
+        auto issue_next = [&]() {
+            if (fetch_done) return;
+            int ks = f_k + f_rot;
+            ks = ks >= nstage ? ks - nstage : ks;
+            char* dst = ring + (issued % kWideStages) * kWideStageBytes;
+#pragma unroll
+            for (int i = 0; i < kWideAInstr; ++i)
+                __builtin_amdgcn_global_load_lds((glb_char*)(gp[i] + (int64_t)ks * kWideTileBytes),
+                                                 (lds_char*)(dst + (pw * kWideAInstr + i) * 1024), 16, 0, kStreamOnce);
+#pragma unroll
+            for (int i = 0; i < kWideBInstr; ++i)
+                __builtin_amdgcn_global_load_lds((glb_char*)(bp + (int64_t)ks * kWideBBytes + i * 1024),
+                                                 (lds_char*)(dst + kWideABytes + (pw * kWideBInstr + i) * 1024), 16, 0, 0);
+            ++issued;
+            if (++f_k == nstage) {
+                if (++f_item < count) aim(tile_of(f_item));
+                else fetch_done = true;
+            }
+        };
+        for (int s = 0; s < kWideStages - 1; ++s) issue_next();
+        int handed = 0;
+        for (int it = 0; it < count; ++it) {
+            for (int k = 0; k < nstage; ++k) {
+                // stage `handed` has landed once at most the younger stages' transfers are outstanding
+                if (issued - handed == kWideStages - 1)
+                    __builtin_amdgcn_s_waitcnt(vmcnt_imm((kWideStages - 2) * (kWideAInstr + kWideBInstr)));
+                else
+                    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                ring_barrier();
+                ++handed;
+                issue_next();
+            }
+            ring_barrier();                        // the three barriers of the consumers' epilogue
+            ring_barrier();
+            ring_barrier();
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------------- consumers
+    const int colblk = wave & 3, rh = wave >> 2;
+    const int r = lane & 31, h = lane >> 5;
+    // A fragment of block b, group g: row 128 rh + 32 b + r, chunk 2g + h, stored at chunk slot
+    // (2g + h) XOR ((r >> 1) & 7) of its 128-byte row
+    const int a_row = (kWideRows / 2 * rh + r) * kWideTileBytes;
+    const int a_swz = (r >> 1) & 7;
+    // W1' fragment of group g: the packed order, 1 KiB per (group, column block)
+    const int b_off = kWideABytes + colblk * 1024 + lane * 16;
+    constexpr int kGroups = kWideTileBytes / 32;            // 16-k groups per stage: 4
+    int stage = 0;
+    for (int it = 0; it < count; ++it) {
+        const int tile = tile_of(it);
+        const int c = tile / p.tiles_per_ckpt;
+        const int row0 = (tile - c * p.tiles_per_ckpt) * kWideRows;
+        f32x16 acc[4];
+        float ssq[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            acc[b] = f32x16{0};
+            ssq[b] = 0.0f;
+        }
+        for (int k = 0; k < nstage; ++k) {
+            ring_barrier();
+            const char* st = ring + (stage % kWideStages) * kWideStageBytes;
+#pragma unroll
+            for (int g = 0; g < kGroups; ++g) {
+                const u32x4 bf = *reinterpret_cast<const u32x4*>(st + b_off + g * 4096);
+                u32x4 a[4];
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    a[b] = *reinterpret_cast<const u32x4*>(st + a_row + b * 32 * kWideTileBytes + (((2 * g + h) ^ a_swz) << 4));
+#pragma unroll
+                for (int b = 0; b < 4; ++b) acc[b] = mma_k16<DT>(a[b], bf, acc[b]);
+                if (g == colblk) {                 // this wave's share of its rows' sums of squares
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) ssq[b] = chunk_sumsq<DT>(a[b], ssq[b]);
+                }
+            }
+            ++stage;
+        }
+
+        // ---- row sums of squares: lanes l and l^32 hold the two chunk phases; the 4 column waves the rest
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const float s2 = ssq[b] + __shfl_xor(ssq[b], 32, kWave);
+            if (lane < 32) ss_part[colblk * kWideRows + kWideRows / 2 * rh + 32 * b + lane] = s2;
+        }
+        __syncthreads();
+        if (tid < kWideRows) {
+            const float ss = (ss_part[tid] + ss_part[kWideRows + tid]) + (ss_part[2 * kWideRows + tid] + ss_part[3 * kWideRows + tid]);
+            inv_rms[tid] = inv_rms_f32(ss, 1.0f / (float)p.d, p.eps);
+        }
+        __syncthreads();
+        {
+            const int col = 32 * colblk + (lane & 31);
+            const float b1c = (p.b1 && col < p.b) ? p.b1[c * p.b + col] : 0.0f;
+            const float w2c = col < p.b ? p.w2[c * p.b + col] : 0.0f;
+            router_epilogue<4>(acc, inv_rms + kWideRows / 2 * rh, z_part + colblk * kWideRows + kWideRows / 2 * rh, b1c, w2c, lane);
+        }
+        __syncthreads();
+        if (tid < kWideRows) {
+            const int t = row0 + tid;
+            if (t < p.T) {
+                const float z = p.tab.b2[c] + ((z_part[tid] + z_part[kWideRows + tid]) + (z_part[2 * kWideRows + tid] + z_part[3 * kWideRows + tid]));
+                const int64_t o = (int64_t)c * p.T + t;
+                const bool f = z > p.tab.thr_logit[c];
+                if (p.logits) p.logits[o] = z;
+                if (p.prob) p.prob[o] = sigmoid_f32(z);
+                if (p.fire) p.fire[o] = f ? 1 : 0;
+                if (p.exit_layer)
+                    report_and_select(p.tab, p.C, c, f, p.min_layer, p.no_exit, p.arrive + t, p.exit_layer + t,
+                                      p.fire_mask ? p.fire_mask + t : nullptr);
+            }
+        }
+        // the scratch arrays are next written after the first barriers of the next tile's k loop
+    }
+}
+
+}  // namespace tide

@@ -19,6 +19,7 @@
 #include "pack_kernel.hpp"
 #include "prefill_dma_kernel.hpp"
 #include "prefill_kernel.hpp"
+#include "prefill_wide_kernel.hpp"
 #include "project_kernel.hpp"
 
 namespace {
@@ -58,7 +59,8 @@ struct Workspace {
 std::mutex g_mu;
 Workspace g_ws[kMaxDevices];
 int g_variant = TIDE_VARIANT_AUTO;
-int g_prefill_form = 0;   // 0 auto; 1 / 2: streaming form with 64 / 128 rows per workgroup; 3: register-ring form
+int g_prefill_form = 0;   // 0 auto; 1 / 2: streaming form with 64 / 128 rows per workgroup; 3: register-ring form;
+                          // 4: wide-tile form (256 rows) wherever it applies, on as many workgroups as there are whole tiles
 
 // Grow-only device buffer.  Re-allocation frees the old block, which waits for the device.
 int reserve(Buffer& b, size_t bytes, bool zero) {
@@ -190,23 +192,48 @@ int launch_pack(int dtype, int64_t C, int64_t d, int64_t b, const float* gamma, 
     return TIDE_OK;
 }
 
+// CUs of the current device, rounded down to a multiple of 8 (one slice of the tile list per XCD).
+int resident_cus(unsigned* out) {
+    static int cus[kMaxDevices] = {};
+    int dev = 0;
+    TIDE_HIP(hipGetDevice(&dev));
+    if (!cus[dev]) TIDE_HIP(hipDeviceGetAttribute(&cus[dev], hipDeviceAttributeMultiprocessorCount, dev));
+    *out = (unsigned)(cus[dev] > 8 ? cus[dev] & ~7 : 8);
+    return TIDE_OK;
+}
+
+// The wide-tile kernel: one persistent workgroup per CU, `grid` of them, p.total_tiles a multiple of grid.
+template <int DT> int launch_wide(unsigned grid, hipStream_t st, const PrefillParams& p) {
+    static bool raised[kMaxDevices] = {};
+    int dev = 0;
+    TIDE_HIP(hipGetDevice(&dev));
+    if (!raised[dev]) {
+        TIDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&tide_prefill_wide_kernel<DT>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, kWideLdsBytes));
+        raised[dev] = true;
+    }
+    hipLaunchKernelGGL((tide_prefill_wide_kernel<DT>), dim3(grid), dim3(kWideThreads), kWideLdsBytes, st, p);
+    return TIDE_OK;
+}
+
 // The streaming kernels use more LDS than the default per-kernel limit: raise it once.
 // They are persistent: at most one (128-row) or two (64-row) workgroups per CU, each walking
 // a list of tiles.
 template <int DT, int M, int CB> int launch_dma(unsigned grid, hipStream_t st, const PrefillParams& p) {
     static bool raised[kMaxDevices] = {};
-    static int cus[kMaxDevices] = {};
     int dev = 0;
     TIDE_HIP(hipGetDevice(&dev));
     constexpr int lds = dma_lds_bytes<M>();
     if (!raised[dev]) {
         TIDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&tide_prefill_dma_kernel<DT, M, CB>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-        TIDE_HIP(hipDeviceGetAttribute(&cus[dev], hipDeviceAttributeMultiprocessorCount, dev));
         raised[dev] = true;
     }
+    unsigned cus = 0;
+    int rc_cus = resident_cus(&cus);
+    if (rc_cus) return rc_cus;
     // (the two-halves kernel needs more than the 168 registers that let three waves share a SIMD)
-    const unsigned resident = (unsigned)(cus[dev] > 8 ? cus[dev] & ~7 : 8) * ((M == 128 || CB == 2) ? 1u : 2u);
+    const unsigned resident = cus * ((M == 128 || CB == 2) ? 1u : 2u);
     if (grid > resident) grid = resident;      // both are multiples of 8
     // With fewer 128-row tiles than CUs, launch every CU anyway: the schedule then cuts the tiles
     // into 64- or 32-row pieces, one per workgroup (a workgroup without a piece exits at once).
@@ -268,10 +295,41 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
         if (rc0) return rc0;
         p.arrive = (uint64_t*)ws.arrive.ptr;
     }
-    const unsigned grid = 8u * (unsigned)((p.total_tiles + 7) / 8);
+    int rc = TIDE_OK;
+    // Wide-tile form: whole rounds of 256-row tiles (one per CU and round) go to the wide kernel,
+    // what is left of the checkpoint-major row list to the 128-row streaming kernel behind it on
+    // the same stream (the arrival words carry the per-token state across the two launches).
+    if (!ring_form && !two_halves && dtype != TIDE_F32 && (g_prefill_form == 0 || g_prefill_form == 4)) {
+        unsigned cus = 0;
+        rc = resident_cus(&cus);
+        if (rc) return rc;
+        const int64_t tpc256 = (T + kWideRows - 1) / kWideRows, tiles256 = C * tpc256;
+        unsigned wgrid = cus;
+        if (g_prefill_form == 4 && tiles256 < (int64_t)cus) wgrid = (unsigned)(tiles256 & ~(int64_t)7);
+        const int64_t wide_tiles = wgrid >= 8 ? tiles256 / wgrid * wgrid : 0;
+        if (wide_tiles > 0) {
+            PrefillParams pw = p;
+            pw.tiles_per_ckpt = (int)tpc256;
+            pw.total_tiles = (int)wide_tiles;
+            pw.tile_begin = 0;
+            by_dtype(dtype, [&](auto dt) {
+                constexpr int DT = decltype(dt)::value;
+                if constexpr (DT != kF32) rc = launch_wide<DT>(wgrid, st, pw);
+                return 0;
+            });
+            if (rc) return rc;
+            TIDE_HIP(hipGetLastError());
+            if (wide_tiles == tiles256) return TIDE_OK;
+            const int64_t c0 = wide_tiles / tpc256, j0 = wide_tiles % tpc256;      // first row left: 256 j0 of checkpoint c0
+            rows_per_wg = 128;
+            p.tiles_per_ckpt = (int)((T + 127) / 128);
+            p.total_tiles = p.C * p.tiles_per_ckpt;
+            p.tile_begin = (int)(c0 * p.tiles_per_ckpt + 2 * j0);
+        }
+    }
+    const unsigned grid = 8u * (unsigned)((p.total_tiles - p.tile_begin + 7) / 8);
     const int ntile = (int)(p.dpad * (int64_t)eb / kTileBytes);
     const bool ragged = p.dpad != p.d;
-    int rc = TIDE_OK;
     by_dtype(dtype, [&](auto dt) {
         constexpr int DT = decltype(dt)::value;
         if (ring_form && ragged) {
@@ -676,7 +734,7 @@ int tide_set_variant(int variant) {
 }
 
 int tide_set_prefill_form(int form) {
-    if (form < 0 || form > 3) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d outside [0, 3]", form);
+    if (form < 0 || form > 4) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d outside [0, 4]", form);
     std::lock_guard<std::mutex> lock(g_mu);
     int prev = g_prefill_form;
     g_prefill_form = form;

@@ -107,8 +107,8 @@ def test_config1_full(tr, packed):
     assert st["max_abs_err"] < 1e-2                      # bf16 W1' rounding: well inside the 2e-2 bar
 
 
-@pytest.mark.parametrize("form", [1, 2, 3])
-@pytest.mark.parametrize("dtype,T,d", [("bf16", 300, 1024), ("f16", 129, 768), ("f32", 257, 512), ("bf16", 64, 128)])
+@pytest.mark.parametrize("form", [1, 2, 3, 4])
+@pytest.mark.parametrize("dtype,T,d", [("bf16", 300, 1024), ("f16", 129, 768), ("f32", 257, 512), ("bf16", 64, 128), ("f16", 1100, 384)])
 def test_every_prefill_form_computes_the_same_function(tr, form, dtype, T, d):
     """Streaming form with 64 / 128 rows per workgroup and the register-ring form, forced in
     turn, on ragged token counts and on a hidden size with a single k-tile."""
@@ -128,6 +128,11 @@ def test_every_prefill_form_computes_the_same_function(tr, form, dtype, T, d):
     (2, "f32", 12, 16384 - 70, 256, "halves, fp32 rows, ragged last tile"),
     (2, "bf16", 28, 8192, 128, "448 tiles: 24 left per XCD, too many to cut; single k-tile"),
     (1, "bf16", 12, 16384, 256, "768 tiles of 64 rows on 512 workgroups: 32 left per XCD, cut into 32-row halves"),
+    (4, "bf16", 12, 1300, 256, "wide-tile form: 18 tiles of 256 rows, 16 on 16 workgroups, the rest (from row 1024 of the last "
+                               "checkpoint, ragged) to the 128-row kernel"),
+    (4, "f16", 12, 2048, 512, "wide-tile form: 24 tiles on 24 workgroups, nothing left"),
+    (4, "bf16", 20, 16384 + 77, 128, "wide-tile form: 325 tiles, one full round on 256 workgroups, 69 left; single 128-byte k-tile pair"),
+    (0, "bf16", 36, 8192, 256, "automatic choice at 288 tiles of 256 rows: one wide round, 32 tiles left"),
 ])
 def test_uneven_tile_counts_split_the_last_round(tr, form, dtype, layers, T, d, what):
     """Tile counts that do not divide among the persistent workgroups: the tiles of the last
@@ -324,7 +329,7 @@ def test_every_element_enters_the_sum_of_squares(tr, dtype, d):
     ex_o, z_o, m_o = oracle_select(w, rt, hb)
     dev = to_device(hb, dtype)
     g, W1, b1, w2 = routers_to_device(rt)
-    for form in (1, 2, 3):
+    for form in (1, 2, 3, 4):
         tr.set_prefill_form(form)
         tr.set_variant(tr.VARIANT_PREFILL)
         try:
