@@ -21,8 +21,14 @@
 namespace tide {
 
 constexpr int kWideRows = 256;
-constexpr int kWideTileBytes = 128;                 // bytes of each row per stage (64 elements)
+// 128 bytes of each row per stage (64 elements) in a ring of 3 stages.  (64 bytes in 6 stages
+// was measured too: 52 % of HBM peak instead of 68 % -- the row segments become too short.)
+constexpr int kWideTileBytes = 128;
 constexpr int kWideStages = 3;
+constexpr int kWideChunksPerRow = kWideTileBytes / 16;                       // 8 (or 4)
+constexpr int kWideRowsPerTransfer = 64 / kWideChunksPerRow;                 // 8 (or 16)
+// bank-conflict-free placement: the chunk slot of a row is its chunk index XOR these bits of the row
+__device__ __forceinline__ int wide_swizzle(int row) { return (row / (16 / kWideChunksPerRow)) & (kWideChunksPerRow - 1); }
 constexpr int kWideConsumers = 8;
 constexpr int kWideThreads = (kWideConsumers + kDmaProducers) * kWave;        // 640
 constexpr int kWideABytes = kWideRows * kWideTileBytes;                      // 32 KiB of rows per stage
@@ -61,7 +67,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
         const int pw = wave - kWideConsumers;
         // rows: one transfer = 8 rows x 128 bytes; lane -> (row within the transfer, LDS chunk slot),
         // the global chunk is the slot XOR bits 1..3 of the row (what the consumers undo)
-        const int rl = lane >> 3, slot = lane & 7;
+        const int rl = lane / kWideChunksPerRow, slot = lane % kWideChunksPerRow;
         const char* gp[kWideAInstr];
         const char* bp = nullptr;              // this producer's half of the k-tile's 16 KiB of W1', stage 0
         int f_rot = 0, f_k = 0, f_item = 0;
@@ -71,10 +77,10 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
             const char* base = p.hidden + (int64_t)c * p.ckpt_stride_bytes;
 #pragma unroll
             for (int i = 0; i < kWideAInstr; ++i) {
-                const int row = (pw * kWideAInstr + i) * 8 + rl;
+                const int row = (pw * kWideAInstr + i) * kWideRowsPerTransfer + rl;
                 int r = row0 + row;
                 r = r < p.T ? r : p.T - 1;                                  // ragged tail: re-read the last row
-                gp[i] = base + (int64_t)r * p.row_stride_bytes + ((slot ^ ((row >> 1) & 7)) << 4);
+                gp[i] = base + (int64_t)r * p.row_stride_bytes + ((slot ^ wide_swizzle(row)) << 4);
             }
             bp = reinterpret_cast<const char*>(p.packed + (size_t)c * ckpt_chunks) + pw * (kWideBBytes / kDmaProducers) + lane * 16;
             f_rot = first_stage(tile);
@@ -128,7 +134,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
     // A fragment of block b, group g: row 128 rh + 32 b + r, chunk 2g + h, stored at chunk slot
     // (2g + h) XOR ((r >> 1) & 7) of its 128-byte row
     const int a_row = (kWideRows / 2 * rh + r) * kWideTileBytes;
-    const int a_swz = (r >> 1) & 7;
+    const int a_swz = wide_swizzle(r);
     // W1' fragment of group g: the packed order, 1 KiB per (group, column block)
     const int b_off = kWideABytes + colblk * 1024 + lane * 16;
     constexpr int kGroups = kWideTileBytes / 32;            // 16-k groups per stage: 4
