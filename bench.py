@@ -250,6 +250,27 @@ def main() -> int:
             del hbs, cb, pkb, Wb
         result["bottleneck_widths"] = {"workload": f"Table 2 pairs with b != 128: bf16, C={C}, T={T}, packed weights", **widths}
 
+        # ---- configs[3]: the 36-layer batched prefill (C=9, T=8x2048), where whole rounds of 256-row tiles exist
+        w3 = synth.config3()
+        gen3 = torch.Generator(device="cuda").manual_seed(0x71DE + 3)
+        hb3 = [torch.randn((w3.C, w3.T, d), generator=gen3, device="cuda").to(torch.bfloat16) for _ in range(2)]
+        W3 = torch.randn((w3.C, d, 128), generator=gen3, device="cuda") / d ** 0.5
+        w23 = torch.randn((w3.C, 128), generator=gen3, device="cuda") / 128 ** 0.5
+        pk3 = tr.router_pack(tr.BF16, None, W3)
+        out3 = (torch.empty(w3.T, dtype=torch.int32, device="cuda"), torch.empty((w3.C, w3.T), dtype=torch.float32, device="cuda"),
+                torch.empty(w3.T, dtype=torch.int32, device="cuda"))
+        c3 = [tr.prepare_select_exit_packed(h, pk3, w3.eps, None, w23, 0.0, 0.5, w3.layer_ids, 0, w3.n_layers, d=d, out=out3)
+              for h in hb3]
+        n3 = max(20, args.steps // 5)
+        _, ev3 = timed(lambda i: c3[i & 1](), n3, 5)
+        by3 = w3.C * w3.T * d * esz + w3.C * d * 128 * esz + w3.T * 8 + w3.C * w3.T * 4
+        result["large_batch"] = {"workload": "configs[3]: bf16, d=4096, 36 layers, C=9, T=16384 (8 x 2048), packed weights; "
+                                             "wide-tile kernel for two rounds of 256-row tiles + 128-row kernel for the rest",
+                                 "us_per_call": round(ev3 / n3 * 1e6, 2), "tokens_per_s": round(w3.T / (ev3 / n3), 1),
+                                 "algorithmic_bytes": by3, "gbs": round(by3 / (ev3 / n3) / 1e9, 1),
+                                 "frac_of_hbm_peak": round(by3 / (ev3 / n3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del hb3, c3
+
     # ---- decode latency (config 2): fp16, T = 1 and 8, raw weights, auto-selected decode variant
     if not args.no_decode:
         dec = {}
