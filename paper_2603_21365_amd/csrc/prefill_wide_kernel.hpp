@@ -13,43 +13,51 @@
 //     32 (cw % 4) .. +31, four 32x32 accumulator blocks like a consumer of the 128-row kernel.
 // Consumers issue no global loads at all.  A k-tile is 64 elements (128 bytes of a row) so that a
 // ring of three stages (32 KiB of rows + 16 KiB of W1' each) fits the 160 KiB of LDS.
-// 16-bit storage types, bottleneck widths 64 and 128, d a multiple of 128.
+// The same structure serves bottleneck width 256 (kHalves = 2): 128 rows x 256 columns per
+// workgroup, wave cw owning column block cw % 4 of column half cw / 4 -- the stage is then 16 KiB
+// of rows + 32 KiB of W1' (both halves), the same 48 KiB.
+// 16-bit storage types, d a multiple of 128.
 #pragma once
 #include "device_utils.hpp"
 #include "prefill_dma_kernel.hpp"
 
 namespace tide {
 
-constexpr int kWideRows = 256;
 // 128 bytes of each row per stage (64 elements) in a ring of 3 stages.  (64 bytes in 6 stages
 // was measured too: 52 % of HBM peak instead of 68 % -- the row segments become too short.)
 constexpr int kWideTileBytes = 128;
 constexpr int kWideStages = 3;
-constexpr int kWideChunksPerRow = kWideTileBytes / 16;                       // 8 (or 4)
-constexpr int kWideRowsPerTransfer = 64 / kWideChunksPerRow;                 // 8 (or 16)
+constexpr int kWideChunksPerRow = kWideTileBytes / 16;                       // 8
+constexpr int kWideRowsPerTransfer = 64 / kWideChunksPerRow;                 // 8
 // bank-conflict-free placement: the chunk slot of a row is its chunk index XOR these bits of the row
 __device__ __forceinline__ int wide_swizzle(int row) { return (row / (16 / kWideChunksPerRow)) & (kWideChunksPerRow - 1); }
 constexpr int kWideConsumers = 8;
 constexpr int kWideThreads = (kWideConsumers + kDmaProducers) * kWave;        // 640
-constexpr int kWideABytes = kWideRows * kWideTileBytes;                      // 32 KiB of rows per stage
-constexpr int kWideBBytes = (kWideTileBytes / 2) * kBottleneck * 2;           // 16 KiB of W1' per stage
-constexpr int kWideStageBytes = kWideABytes + kWideBBytes;
-constexpr int kWideAInstr = kWideABytes / 1024 / kDmaProducers;               // 16 transfers of rows per producer and stage
-constexpr int kWideBInstr = kWideBBytes / 1024 / kDmaProducers;               // 8 transfers of W1'
+constexpr int kWideRows = 256;                                               // rows per tile at widths 64 / 128
+constexpr int wide_rows(int kHalves) { return kWideRows / kHalves; }         // 256, or 128 at width 256
+constexpr int wide_a_bytes(int kHalves) { return wide_rows(kHalves) * kWideTileBytes; }                 // 32 / 16 KiB of rows per stage
+constexpr int wide_b_bytes(int kHalves) { return kHalves * (kWideTileBytes / 2) * kBottleneck * 2; }    // 16 / 32 KiB of W1'
+constexpr int kWideStageBytes = wide_a_bytes(1) + wide_b_bytes(1);                                      // 48 KiB either way
+constexpr int kWideInstr = kWideStageBytes / 1024 / kDmaProducers;            // 24 transfers per producer and stage
 constexpr int kWideLdsBytes = kWideStages * kWideStageBytes + (4 + 4 + 1) * kWideRows * (int)sizeof(float);
 
-// p.total_tiles counts 256-row tiles here and is a multiple of the grid size (the host hands the
-// rest of the batch to the 128-row kernel); p.tiles_per_ckpt = ceil(T / 256).
-template <int DT>
+// p.total_tiles counts tiles of wide_rows(kHalves) rows here and is a multiple of the grid size (the
+// host hands the rest of the batch to the streaming kernel); p.tiles_per_ckpt = ceil(T / rows).
+template <int DT, int kHalves>
 __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(const PrefillParams p) {
     static_assert(DT != kF32, "16-bit storage types only");
     typedef __attribute__((address_space(3))) char lds_char;
     typedef __attribute__((address_space(1))) const char glb_char;
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int kRowsW = wide_rows(kHalves);                   // rows per tile
+    constexpr int kABytes = wide_a_bytes(kHalves), kBHalfBytes = wide_b_bytes(1);
+    constexpr int kAInstr = kABytes / 1024 / kDmaProducers;      // transfers of rows per producer and stage: 16 / 8
+    constexpr int kBInstr = kBHalfBytes / 1024 / kDmaProducers;  // transfers of one column half of W1': 8
+    constexpr int kColWaves = 4 * kHalves;                       // consumer waves that share a row: 4 / 8
     char* ring = smem;
-    float* ss_part = reinterpret_cast<float*>(smem + kWideStages * kWideStageBytes);   // [4][256]
-    float* z_part = ss_part + 4 * kWideRows;                                           // [4][256]
-    float* inv_rms = z_part + 4 * kWideRows;                                           // [256]
+    float* ss_part = reinterpret_cast<float*>(smem + kWideStages * kWideStageBytes);   // [4][rows]
+    float* z_part = ss_part + 4 * kWideRows;                                           // [kColWaves][rows]
+    float* inv_rms = z_part + 4 * kWideRows;                                           // [rows]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nstage = p.d * Storage<DT>::kBytes / kWideTileBytes;      // k-tiles of a row
@@ -60,7 +68,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
     const int count = per_xcd / g;                                       // tiles of this workgroup
     auto tile_of = [&](int i) { return lo + i * g; };
     auto first_stage = [&](int tile) { return (int)(((unsigned)tile * 5u) % (unsigned)nstage); };
-    const size_t ckpt_chunks = (size_t)p.d * kBottleneck / Storage<DT>::kElems;
+    const size_t ckpt_chunks = (size_t)p.d * kBottleneck / Storage<DT>::kElems;   // of one column half
 
     if (wave >= kWideConsumers) {
         // ------------------------------------------------------------------ producers
@@ -68,21 +76,21 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
         // rows: one transfer = 8 rows x 128 bytes; lane -> (row within the transfer, LDS chunk slot),
         // the global chunk is the slot XOR bits 1..3 of the row (what the consumers undo)
         const int rl = lane / kWideChunksPerRow, slot = lane % kWideChunksPerRow;
-        const char* gp[kWideAInstr];
-        const char* bp = nullptr;              // this producer's half of the k-tile's 16 KiB of W1', stage 0
+        const char* gp[kAInstr];
+        const char* bp = nullptr;              // this producer's half of a k-tile's 16 KiB of one column half, stage 0
         int f_rot = 0, f_k = 0, f_item = 0;
         auto aim = [&](int tile) {
             const int c = tile / p.tiles_per_ckpt;
-            const int row0 = (tile - c * p.tiles_per_ckpt) * kWideRows;
+            const int row0 = (tile - c * p.tiles_per_ckpt) * kRowsW;
             const char* base = p.hidden + (int64_t)c * p.ckpt_stride_bytes;
 #pragma unroll
-            for (int i = 0; i < kWideAInstr; ++i) {
-                const int row = (pw * kWideAInstr + i) * kWideRowsPerTransfer + rl;
+            for (int i = 0; i < kAInstr; ++i) {
+                const int row = (pw * kAInstr + i) * kWideRowsPerTransfer + rl;
                 int r = row0 + row;
                 r = r < p.T ? r : p.T - 1;                                  // ragged tail: re-read the last row
                 gp[i] = base + (int64_t)r * p.row_stride_bytes + ((slot ^ wide_swizzle(row)) << 4);
             }
-            bp = reinterpret_cast<const char*>(p.packed + (size_t)c * ckpt_chunks) + pw * (kWideBBytes / kDmaProducers) + lane * 16;
+            bp = reinterpret_cast<const char*>(p.packed + (size_t)c * kHalves * ckpt_chunks) + pw * (kBHalfBytes / kDmaProducers) + lane * 16;
             f_rot = first_stage(tile);
             f_k = 0;
         };
@@ -95,13 +103,15 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
             ks = ks >= nstage ? ks - nstage : ks;
             char* dst = ring + (issued % kWideStages) * kWideStageBytes;
 #pragma unroll
-            for (int i = 0; i < kWideAInstr; ++i)
+            for (int i = 0; i < kAInstr; ++i)
                 __builtin_amdgcn_global_load_lds((glb_char*)(gp[i] + (int64_t)ks * kWideTileBytes),
-                                                 (lds_char*)(dst + (pw * kWideAInstr + i) * 1024), 16, 0, kStreamOnce);
+                                                 (lds_char*)(dst + (pw * kAInstr + i) * 1024), 16, 0, kStreamOnce);
 #pragma unroll
-            for (int i = 0; i < kWideBInstr; ++i)
-                __builtin_amdgcn_global_load_lds((glb_char*)(bp + (int64_t)ks * kWideBBytes + i * 1024),
-                                                 (lds_char*)(dst + kWideABytes + (pw * kWideBInstr + i) * 1024), 16, 0, 0);
+            for (int hf = 0; hf < kHalves; ++hf)
+#pragma unroll
+                for (int i = 0; i < kBInstr; ++i)
+                    __builtin_amdgcn_global_load_lds((glb_char*)(bp + (int64_t)hf * ckpt_chunks * 16 + (int64_t)ks * kBHalfBytes + i * 1024),
+                                                     (lds_char*)(dst + kABytes + hf * kBHalfBytes + (pw * kBInstr + i) * 1024), 16, 0, 0);
             ++issued;
             if (++f_k == nstage) {
                 if (++f_item < count) aim(tile_of(f_item));
@@ -114,7 +124,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
             for (int k = 0; k < nstage; ++k) {
                 // stage `handed` has landed once at most the younger stages' transfers are outstanding
                 if (issued - handed == kWideStages - 1)
-                    __builtin_amdgcn_s_waitcnt(vmcnt_imm((kWideStages - 2) * (kWideAInstr + kWideBInstr)));
+                    __builtin_amdgcn_s_waitcnt(vmcnt_imm((kWideStages - 2) * kWideInstr));
                 else
                     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
                 ring_barrier();
@@ -129,20 +139,24 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
     }
 
     // ---------------------------------------------------------------------- consumers
-    const int colblk = wave & 3, rh = wave >> 2;
+    // wave cw: column block cw % 4; cw / 4 is the row half (widths 64 / 128) or the column half (width 256)
+    const int colblk = wave & 3, hi = wave >> 2;
+    const int rh = kHalves == 1 ? hi : 0, half = kHalves == 1 ? 0 : hi;
     const int r = lane & 31, h = lane >> 5;
     // A fragment of block b, group g: row 128 rh + 32 b + r, chunk 2g + h, stored at chunk slot
     // (2g + h) XOR ((r >> 1) & 7) of its 128-byte row
-    const int a_row = (kWideRows / 2 * rh + r) * kWideTileBytes;
+    const int a_row = (128 * rh + r) * kWideTileBytes;
     const int a_swz = wide_swizzle(r);
-    // W1' fragment of group g: the packed order, 1 KiB per (group, column block)
-    const int b_off = kWideABytes + colblk * 1024 + lane * 16;
+    // W1' fragment of group g: the packed order, 1 KiB per (group, column block), column halves apart
+    const int b_off = kABytes + half * kBHalfBytes + colblk * 1024 + lane * 16;
+    const int zrow = 128 * rh;                              // this wave's first row within the tile
+    const int zcol = kHalves == 1 ? colblk : wave;          // its slot among the waves that share a row
     constexpr int kGroups = kWideTileBytes / 32;            // 16-k groups per stage: 4
     int stage = 0;
     for (int it = 0; it < count; ++it) {
         const int tile = tile_of(it);
         const int c = tile / p.tiles_per_ckpt;
-        const int row0 = (tile - c * p.tiles_per_ckpt) * kWideRows;
+        const int row0 = (tile - c * p.tiles_per_ckpt) * kRowsW;
         f32x16 acc[4];
         float ssq[4];
 #pragma unroll
@@ -162,7 +176,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
                     a[b] = *reinterpret_cast<const u32x4*>(st + a_row + b * 32 * kWideTileBytes + (((2 * g + h) ^ a_swz) << 4));
 #pragma unroll
                 for (int b = 0; b < 4; ++b) acc[b] = mma_k16<DT>(a[b], bf, acc[b]);
-                if (g == colblk) {                 // this wave's share of its rows' sums of squares
+                if (g == colblk && half == 0) {    // this wave's share of its rows' sums of squares
 #pragma unroll
                     for (int b = 0; b < 4; ++b) ssq[b] = chunk_sumsq<DT>(a[b], ssq[b]);
                 }
@@ -171,28 +185,33 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
         }
 
         // ---- row sums of squares: lanes l and l^32 hold the two chunk phases; the 4 column waves the rest
+        if (half == 0) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const float s2 = ssq[b] + __shfl_xor(ssq[b], 32, kWave);
-            if (lane < 32) ss_part[colblk * kWideRows + kWideRows / 2 * rh + 32 * b + lane] = s2;
+            for (int b = 0; b < 4; ++b) {
+                const float s2 = ssq[b] + __shfl_xor(ssq[b], 32, kWave);
+                if (lane < 32) ss_part[colblk * kRowsW + zrow + 32 * b + lane] = s2;
+            }
         }
         __syncthreads();
-        if (tid < kWideRows) {
-            const float ss = (ss_part[tid] + ss_part[kWideRows + tid]) + (ss_part[2 * kWideRows + tid] + ss_part[3 * kWideRows + tid]);
+        if (tid < kRowsW) {
+            const float ss = (ss_part[tid] + ss_part[kRowsW + tid]) + (ss_part[2 * kRowsW + tid] + ss_part[3 * kRowsW + tid]);
             inv_rms[tid] = inv_rms_f32(ss, 1.0f / (float)p.d, p.eps);
         }
         __syncthreads();
         {
-            const int col = 32 * colblk + (lane & 31);
+            const int col = kBottleneck * half + 32 * colblk + (lane & 31);
             const float b1c = (p.b1 && col < p.b) ? p.b1[c * p.b + col] : 0.0f;
             const float w2c = col < p.b ? p.w2[c * p.b + col] : 0.0f;
-            router_epilogue<4>(acc, inv_rms + kWideRows / 2 * rh, z_part + colblk * kWideRows + kWideRows / 2 * rh, b1c, w2c, lane);
+            router_epilogue<4>(acc, inv_rms + zrow, z_part + zcol * kRowsW + zrow, b1c, w2c, lane);
         }
         __syncthreads();
-        if (tid < kWideRows) {
+        if (tid < kRowsW) {
             const int t = row0 + tid;
             if (t < p.T) {
-                const float z = p.tab.b2[c] + ((z_part[tid] + z_part[kWideRows + tid]) + (z_part[2 * kWideRows + tid] + z_part[3 * kWideRows + tid]));
+                float zsum = (z_part[tid] + z_part[kRowsW + tid]) + (z_part[2 * kRowsW + tid] + z_part[3 * kRowsW + tid]);
+                if constexpr (kColWaves == 8)
+                    zsum += (z_part[4 * kRowsW + tid] + z_part[5 * kRowsW + tid]) + (z_part[6 * kRowsW + tid] + z_part[7 * kRowsW + tid]);
+                const float z = p.tab.b2[c] + zsum;
                 const int64_t o = (int64_t)c * p.T + t;
                 const bool f = z > p.tab.thr_logit[c];
                 if (p.logits) p.logits[o] = z;

@@ -203,16 +203,16 @@ int resident_cus(unsigned* out) {
 }
 
 // The wide-tile kernel: one persistent workgroup per CU, `grid` of them, p.total_tiles a multiple of grid.
-template <int DT> int launch_wide(unsigned grid, hipStream_t st, const PrefillParams& p) {
+template <int DT, int kHalves> int launch_wide(unsigned grid, hipStream_t st, const PrefillParams& p) {
     static bool raised[kMaxDevices] = {};
     int dev = 0;
     TIDE_HIP(hipGetDevice(&dev));
     if (!raised[dev]) {
-        TIDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&tide_prefill_wide_kernel<DT>),
+        TIDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&tide_prefill_wide_kernel<DT, kHalves>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, kWideLdsBytes));
         raised[dev] = true;
     }
-    hipLaunchKernelGGL((tide_prefill_wide_kernel<DT>), dim3(grid), dim3(kWideThreads), kWideLdsBytes, st, p);
+    hipLaunchKernelGGL((tide_prefill_wide_kernel<DT, kHalves>), dim3(grid), dim3(kWideThreads), kWideLdsBytes, st, p);
     return TIDE_OK;
 }
 
@@ -296,33 +296,35 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
         p.arrive = (uint64_t*)ws.arrive.ptr;
     }
     int rc = TIDE_OK;
-    // Wide-tile form: whole rounds of 256-row tiles (one per CU and round) go to the wide kernel,
-    // what is left of the checkpoint-major row list to the 128-row streaming kernel behind it on
-    // the same stream (the arrival words carry the per-token state across the two launches).
-    if (!ring_form && !two_halves && dtype != TIDE_F32 && (g_prefill_form == 0 || g_prefill_form == 4)) {
+    // Wide-tile form: whole rounds of wide tiles (256 rows, or 128 rows at width 256; one per CU and
+    // round) go to the wide kernel, what is left of the checkpoint-major row list to the streaming
+    // kernel with half as many rows per tile behind it on the same stream (the arrival words carry
+    // the per-token state across the two launches).
+    if (!ring_form && dtype != TIDE_F32 && (g_prefill_form == 0 || g_prefill_form == 4)) {
         unsigned cus = 0;
         rc = resident_cus(&cus);
         if (rc) return rc;
-        const int64_t tpc256 = (T + kWideRows - 1) / kWideRows, tiles256 = C * tpc256;
+        const int64_t wrows = two_halves ? kWideRows / 2 : kWideRows;
+        const int64_t tpcw = (T + wrows - 1) / wrows, tilesw = C * tpcw;
         unsigned wgrid = cus;
-        if (g_prefill_form == 4 && tiles256 < (int64_t)cus) wgrid = (unsigned)(tiles256 & ~(int64_t)7);
-        const int64_t wide_tiles = wgrid >= 8 ? tiles256 / wgrid * wgrid : 0;
+        if (g_prefill_form == 4 && tilesw < (int64_t)cus) wgrid = (unsigned)(tilesw & ~(int64_t)7);
+        const int64_t wide_tiles = wgrid >= 8 ? tilesw / wgrid * wgrid : 0;
         if (wide_tiles > 0) {
             PrefillParams pw = p;
-            pw.tiles_per_ckpt = (int)tpc256;
+            pw.tiles_per_ckpt = (int)tpcw;
             pw.total_tiles = (int)wide_tiles;
             pw.tile_begin = 0;
             by_dtype(dtype, [&](auto dt) {
                 constexpr int DT = decltype(dt)::value;
-                if constexpr (DT != kF32) rc = launch_wide<DT>(wgrid, st, pw);
+                if constexpr (DT != kF32) rc = two_halves ? launch_wide<DT, 2>(wgrid, st, pw) : launch_wide<DT, 1>(wgrid, st, pw);
                 return 0;
             });
             if (rc) return rc;
             TIDE_HIP(hipGetLastError());
-            if (wide_tiles == tiles256) return TIDE_OK;
-            const int64_t c0 = wide_tiles / tpc256, j0 = wide_tiles % tpc256;      // first row left: 256 j0 of checkpoint c0
-            rows_per_wg = 128;
-            p.tiles_per_ckpt = (int)((T + 127) / 128);
+            if (wide_tiles == tilesw) return TIDE_OK;
+            const int64_t c0 = wide_tiles / tpcw, j0 = wide_tiles % tpcw;      // first row left: wrows * j0 of checkpoint c0
+            rows_per_wg = (int)(wrows / 2);
+            p.tiles_per_ckpt = (int)((T + rows_per_wg - 1) / rows_per_wg);
             p.total_tiles = p.C * p.tiles_per_ckpt;
             p.tile_begin = (int)(c0 * p.tiles_per_ckpt + 2 * j0);
         }

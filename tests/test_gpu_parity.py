@@ -231,7 +231,8 @@ def test_table2_pairs_prefill(tr, d, b):
 
 
 @pytest.mark.parametrize("b", [64, 256])
-@pytest.mark.parametrize("dtype,T,d", [("bf16", 300, 1024), ("f16", 129, 768), ("f32", 257, 512), ("bf16", 4100, 256)])
+@pytest.mark.parametrize("dtype,T,d", [("bf16", 300, 1024), ("f16", 129, 768), ("f32", 257, 512), ("bf16", 4100, 256),
+                                       ("f16", 1100, 384)])
 def test_bottleneck_widths_every_dtype_and_form(tr, b, dtype, T, d):
     """Widths 64 (padded to 128 columns) and 256 (two column halves) on ragged token counts, raw and
     packed weights, and in every prefill form that supports the width."""
@@ -240,7 +241,7 @@ def test_bottleneck_widths_every_dtype_and_form(tr, b, dtype, T, d):
     rt.b2[:] = [0.2, -0.1, 0.0]
     hb = w.hidden()
     run_and_compare(tr, w, w.name + "_raw", rt=rt, hidden_bits=hb, variant=tr.VARIANT_PREFILL)
-    for form in (1, 2, 3):
+    for form in (1, 2, 3, 4):
         tr.set_prefill_form(form)
         try:
             run_and_compare(tr, w, f"{w.name}_form{form}", rt=rt, hidden_bits=hb, packed=True, variant=tr.VARIANT_PREFILL)
