@@ -182,7 +182,7 @@ int launch_pack(int dtype, int64_t C, int64_t d, int64_t b, const float* gamma, 
     const int64_t dpad = padded_hidden(dtype, d);
     const int chunks = (int)(dpad * kBottleneck * elem_bytes(dtype) / 16);   // of one 128-column half
     const int halves = halves_of(b);
-    dim3 grid((unsigned)((dpad * 4 + kPackThreads - 1) / kPackThreads), (unsigned)(C * halves));
+    dim3 grid((unsigned)((dpad * 16 + kPackThreads - 1) / kPackThreads), (unsigned)(C * halves));
     by_dtype(dtype, [&](auto dt) {
         hipLaunchKernelGGL((tide_pack_kernel<decltype(dt)::value>), grid, dim3(kPackThreads), 0, st, gamma, W1, (u32x4*)packed, (int)d,
                            (int)dpad, chunks, (int)b, halves);
