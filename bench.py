@@ -271,7 +271,9 @@ def main() -> int:
                                  "frac_of_hbm_peak": round(by3 / (ev3 / n3) / 1e9 / HBM_PEAK_GBS, 4)}
         del hb3, c3
 
-    # ---- decode latency (config 2): fp16, T = 1 and 8, raw weights, auto-selected decode variant
+    # ---- decode latency (config 2): fp16, T = 1 and 8.  Router weights are static at inference, so the
+    # serving loop's call is the one on pre-packed weights (automatic choice: the split-k pair on the
+    # matrix cores); the raw-weight call (fp32 W1, latency kernel, no packing pass) is timed beside it.
     if not args.no_decode:
         dec = {}
         for Td in (1, 8):
@@ -279,31 +281,31 @@ def main() -> int:
             hd = torch.from_numpy(wd.hidden()).cuda()
             outd = (torch.empty(Td, dtype=torch.int32, device="cuda"), torch.empty((C, Td), dtype=torch.float32, device="cuda"),
                     torch.empty(Td, dtype=torch.int32, device="cuda"))
-            prepared = tr.prepare_select_exit(hd, g, wd.eps, W1, b1, w2, rt.b2, rt.theta, wd.layer_ids, 0, wd.n_layers,
-                                              out=outd)
-            wall, ev = timed(lambda i: prepared(), 2000, 200)
+            pk16 = tr.router_pack(tr.F16, g, W1)
+            prep_pk = tr.prepare_select_exit_packed(hd, pk16, wd.eps, b1, w2, rt.b2, rt.theta, wd.layer_ids, 0, wd.n_layers,
+                                                    d=d, out=outd)
+            wall, ev = timed(lambda i: prep_pk(), 2000, 200)
             sp = spread()
             p10 = round(sp_pct(timed.windows, 0.1) * 1e6, 2)
             # latency of a single call as a caller that needs the answer sees it: call, then wait
             lat = []
             for _ in range(1000):
                 t0 = time.perf_counter()
-                prepared()
+                prep_pk()
                 torch.cuda.synchronize()
                 lat.append(time.perf_counter() - t0)
             lat.sort()
-            # the same step on pre-packed fp16 weights (the serving loop's form)
-            pk16 = tr.router_pack(tr.F16, g, W1)
-            prep_pk = tr.prepare_select_exit_packed(hd, pk16, wd.eps, b1, w2, rt.b2, rt.theta, wd.layer_ids, 0, wd.n_layers,
-                                                    d=d, out=outd)
-            wall_k, _ = timed(lambda i: prep_pk(), 2000, 200)
-            # the same call captured in a HIP graph (what a decode loop would replay every step)
+            # the raw-weight call
+            prepared = tr.prepare_select_exit(hd, g, wd.eps, W1, b1, w2, rt.b2, rt.theta, wd.layer_ids, 0, wd.n_layers,
+                                              out=outd)
+            wall_r, _ = timed(lambda i: prepared(), 2000, 200)
+            # the packed call captured in a HIP graph (what a decode loop would replay every step)
             cap_stream = torch.cuda.Stream()
             graph = torch.cuda.CUDAGraph()
             cap_stream.wait_stream(torch.cuda.current_stream())
             with torch.cuda.stream(cap_stream):
-                prep_g = tr.prepare_select_exit(hd, g, wd.eps, W1, b1, w2, rt.b2, rt.theta, wd.layer_ids, 0, wd.n_layers,
-                                                out=outd)
+                prep_g = tr.prepare_select_exit_packed(hd, pk16, wd.eps, b1, w2, rt.b2, rt.theta, wd.layer_ids, 0,
+                                                       wd.n_layers, d=d, out=outd)
                 prep_g()
                 cap_stream.synchronize()
                 with torch.cuda.graph(graph, stream=cap_stream):
@@ -318,18 +320,37 @@ def main() -> int:
                 lat_g.append(time.perf_counter() - t0)
             lat_g.sort()
             dec[f"T{Td}"] = {"us_per_call": round(wall / 2000 * 1e6, 2), "calls_per_s": round(2000 / wall, 1),
-                             "packed_weights_us_per_call": round(wall_k / 2000 * 1e6, 2),
-                             "hip_graph": {"us_per_replay": round(wall_g / 2000 * 1e6, 2),
-                                           "us_replay_plus_sync_median": round(lat_g[500] * 1e6, 2),
-                                           "note": "the call is one kernel: a graph replay costs more than the direct "
-                                                   "launch; capture pays off only when it spans several calls"},
+                             "entry_point": "tide_select_exit_packed (fp16 packed weights; split-k pair, two launches)",
                              "us_per_call_hip_events": round(ev / 2000 * 1e6, 2),
                              "us_per_call_spread": {"p10": p10, "median": sp["median"],
                                                     "p90": sp["p90"], "windows": sp["windows"], "calls_per_window": 16},
                              "us_call_plus_sync": {"p10": round(lat[100] * 1e6, 2), "median": round(lat[500] * 1e6, 2),
-                                                   "p90": round(lat[900] * 1e6, 2), "calls": 1000}}
+                                                   "p90": round(lat[900] * 1e6, 2), "calls": 1000},
+                             "raw_weights": {"entry_point": "tide_select_exit (fp32 W1; latency kernel, one launch)",
+                                             "us_per_call": round(wall_r / 2000 * 1e6, 2)},
+                             "hip_graph": {"us_per_replay": round(wall_g / 2000 * 1e6, 2),
+                                           "us_replay_plus_sync_median": round(lat_g[500] * 1e6, 2),
+                                           "note": "the packed call captured as a graph of its two kernels"}}
         result["decode"] = {"workload": "configs[2]: fp16, d=4096, C=8, back-to-back calls on one stream "
                                         "(us_per_call) and one call then a stream synchronisation (us_call_plus_sync)", **dec}
+
+    # ---- the call a serving loop makes at ONE checkpoint layer (C = 1) on batches of several sizes
+    if not args.no_extras:
+        per = {}
+        for Tp in (64, 256, 1024, 4096, 16384):
+            nb1 = max(3, min(8, int((600 << 20) // (Tp * d * 2))))
+            hb1 = [torch.randn(1, Tp, d, device="cuda").to(torch.bfloat16) for _ in range(nb1)]
+            out1 = (torch.empty(Tp, dtype=torch.int32, device="cuda"), torch.empty((1, Tp), dtype=torch.float32, device="cuda"),
+                    torch.empty(Tp, dtype=torch.int32, device="cuda"))
+            c1 = [tr.prepare_select_exit_packed(h, packed, w.eps, b1[:1], w2[:1], rt.b2[:1], rt.theta[:1], w.layer_ids[:1], 0,
+                                                w.n_layers, d=d, out=out1) for h in hb1]
+            n1c = 400
+            _, ev1 = timed(lambda i: c1[i % nb1](), n1c, 40)
+            by1 = Tp * d * 2 + d * 128 * 2
+            per[f"T{Tp}"] = {"us_per_call": round(ev1 / n1c * 1e6, 2), "gbs": round(by1 / (ev1 / n1c) / 1e9, 1)}
+            del hb1, c1
+        result["per_checkpoint_call"] = {"workload": "one checkpoint (C=1) of the 8B shape: bf16, d=4096, packed weights, "
+                                                     "random rows, back-to-back calls on rotating inputs", **per}
 
     # ---- the CPU oracle on the same workload (baseline, not a target)
     if not args.no_cpu_baseline:

@@ -36,8 +36,11 @@
  *  - The router entry points (raw or packed weights) use a per-device workspace that the
  *    library allocates (hipMalloc) on first use and when a larger problem arrives; calls that
  *    share it on one device must be ordered on one stream.  tide_release() frees it.
- *  - Up to 32 rows per checkpoint (a decode step) run on a latency kernel that splits each
- *    router's contraction over the whole chip; larger T on the streaming kernels.
+ *  - Small batches (a decode step, or one checkpoint's call on a few hundred rows) run on kernels
+ *    that split each router's contraction over the whole chip: a matrix-core split-k pair for
+ *    packed weights of a 16-bit type, an fp32 latency kernel for raw weights up to 8 rows per
+ *    checkpoint and for the shapes the pair does not cover up to 32; larger batches on the
+ *    streaming kernels.  All of them compute the same function.
  */
 #ifndef TIDE_ROUTE_H
 #define TIDE_ROUTE_H
@@ -184,7 +187,10 @@ int tide_set_variant(int variant);
 
 /* Choose the prefill kernel's form (process-wide; for tests and tuning): 0 = automatic,
  * 1 / 2 = streaming form with 64 / 128 rows per workgroup, 3 = register-ring form, 4 = wide-tile
- * form (256 rows per workgroup, 16-bit types) for as many whole tiles as there are workgroups.
+ * form (256 rows per workgroup, 16-bit types) for as many whole tiles as there are workgroups,
+ * 5 = split-k form (several workgroups share a tile's hidden dimension and a second launch adds
+ * their partial results; 16-bit types, widths 64 / 128) with at least two slices.  A form that does
+ * not apply to a call (storage type, width, hidden size) falls back to one that does.
  * All forms compute the same function.  Returns the previous setting, or TIDE_ERR_INVALID_ARG. */
 int tide_set_prefill_form(int form);
 

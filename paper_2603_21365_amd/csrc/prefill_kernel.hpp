@@ -48,6 +48,10 @@ struct PrefillParams {
     uint32_t* fire_mask;       // [T]
     // workspace
     uint64_t* arrive;          // [T] arrival words (see report_and_select), zero on entry and on exit
+    // split-k form only (prefill_splitk_kernel.hpp)
+    int k_slices;              // workgroups that share a tile's k range
+    float* zpart;              // [total_tiles][k_slices][rows per tile * 128] partial accumulators
+    float* sspart;             // [total_tiles][k_slices][4 waves][rows per tile] partial sums of squares
     CheckpointTable tab;
 };
 

@@ -1,0 +1,252 @@
+// Prefill kernels, split-k form: the streaming computation of prefill_dma_kernel.hpp (paper
+// Eq. (2), Sec. 3.4 kernel 1, Fig. 1 inference step 3) for batches with far fewer row tiles
+// than the chip has CUs -- a decode step (Sec. 3.3: one or a few tokens per sequence), or the
+// router call a serving loop makes at ONE checkpoint layer on a small batch.
+//
+// Why another form.  With fewer tiles than CUs the streaming kernel cuts tiles into pieces of
+// fewer rows, but every piece still walks the whole hidden dimension against the whole W1' of
+// its checkpoint: the call takes as long as one wave needs for d/16 dependent matrix steps
+// (about 20 us at d = 4096, whatever the batch).  Here the k range of a tile is cut instead:
+// workgroup (tile, slice) multiplies the tile's rows by 1/S of W1' and leaves its 128 partial
+// sums per row, and its share of the rows' sums of squares, in the workspace; a second, small
+// launch adds the S partial results of every 32-row block in a fixed order and runs the router
+// epilogue and the earliest-exit report on them.  The dependent chain is S times shorter, and the
+// matrix cores do the contraction, so the same pair serves 1 row and 2,000.
+// Two launches, not one with a "last workgroup finishes" hand-over: that was built and measured
+// -- the finishing workgroup has to read the partial results with device-scope loads (they come
+// from other XCDs within the same launch), 8 bytes at a time past every cache, and at 128 rows and
+// 8 slices that alone took longer (24 us a call) than the second launch costs (13 us a call).
+// The price of the form is the partial results -- 16 KiB per workgroup and 32-row block, written
+// once and read once -- which is why it stops where the tiles are many.
+// 16-bit storage types, bottleneck widths 64 / 128, d a multiple of 128.
+#pragma once
+#include <type_traits>
+
+#include "device_utils.hpp"
+#include "prefill_dma_kernel.hpp"
+
+namespace tide {
+
+constexpr int kFinishThreads = 256;
+
+template <int kBlocks> constexpr int splitk_lds_bytes() { return kDmaStages * kBlocks * 32 * kTileBytes; }   // the ring
+// floats a workgroup leaves in p.zpart: kBlocks*32 rows x 128 columns, in the order
+// [consumer wave][block][register quad][lane][4] -- every store instruction of a wave is 1 KiB
+// contiguous, and a lane of the second launch reads back the registers of its own position.
+template <int kBlocks> constexpr int splitk_part_floats() { return kBlocks * 32 * kBottleneck; }
+
+// First launch: blockIdx.x = tile * p.k_slices + slice; tiles of kBlocks*32 rows, checkpoint-major
+// (p.tiles_per_ckpt per checkpoint); slice s covers k-tiles [s*n/S, (s+1)*n/S) of the n = d/128
+// k-tiles of a row (S <= n, so every slice has at least one).
+template <int DT, int kBlocks>
+__global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_splitk_kernel(const PrefillParams p) {
+    static_assert(DT != kF32, "16-bit storage types only");
+    typedef __attribute__((address_space(3))) char lds_char;
+    typedef __attribute__((address_space(1))) const char glb_char;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int kRowsM = kBlocks * 32;
+    constexpr int kStageBytes = kRowsM * kTileBytes;
+    constexpr int kInstrPerProducer = kRowsM / 4 / kDmaProducers;   // one transfer = 4 rows x 256 B
+    constexpr int kPre = 2;                                         // k-tiles of W1' a consumer keeps in flight
+    constexpr int kPartFloats = splitk_part_floats<kBlocks>();
+    char* ring = smem;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int S = p.k_slices;
+    const int item = blockIdx.x;
+    const int tile = item / S, slice = item - tile * S;
+    const int ntile = p.d * Storage<DT>::kBytes / kTileBytes;
+    const int kt0 = slice * ntile / S, nk = (slice + 1) * ntile / S - kt0;
+    const int c = tile / p.tiles_per_ckpt;
+    const int row0 = (tile - c * p.tiles_per_ckpt) * kRowsM;
+    float* zmine = p.zpart + (size_t)item * kPartFloats + (size_t)(wave * kBlocks) * 1024 + lane * 4;
+
+    if (wave >= kDmaConsumers) {
+        // ------------------------------------------------------------------ producers
+        const int pw = wave - kDmaConsumers;
+        const int rl = lane >> 4, slot = lane & 15;
+        const char* base = p.hidden + (int64_t)c * p.ckpt_stride_bytes + (int64_t)kt0 * kTileBytes;
+        const char* gp[kInstrPerProducer];
+#pragma unroll
+        for (int i = 0; i < kInstrPerProducer; ++i) {
+            const int row = (pw * kInstrPerProducer + i) * 4 + rl;          // row within the tile
+            int r = row0 + row;
+            r = r < p.T ? r : p.T - 1;                                      // ragged tail: re-read the last row
+            gp[i] = base + (int64_t)r * p.row_stride_bytes + ((slot ^ (row & 15)) << 4);
+        }
+        int issued = 0;
+        auto issue_next = [&]() {
+            if (issued >= nk) return;
+            char* dst = ring + (issued % kDmaStages) * kStageBytes;
+#pragma unroll
+            for (int i = 0; i < kInstrPerProducer; ++i)
+                __builtin_amdgcn_global_load_lds((glb_char*)(gp[i] + (int64_t)issued * kTileBytes),
+                                                 (lds_char*)(dst + (pw * kInstrPerProducer + i) * 1024), 16, 0, kStreamOnce);
+            ++issued;
+        };
+        // every ring slot is free at the start: fill them all
+        for (int s = 0; s < kDmaStages; ++s) issue_next();
+        for (int k = 0; k < nk; ++k) {
+            // stage k has landed once only the transfers of the younger stages are outstanding
+            // (every stage is kInstrPerProducer transfers; loads complete in issue order)
+            const int younger = issued - k - 1;
+            if (younger >= 3) __builtin_amdgcn_s_waitcnt(vmcnt_imm(3 * kInstrPerProducer));
+            else if (younger == 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * kInstrPerProducer));
+            else if (younger == 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kInstrPerProducer));
+            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            ring_barrier();                        // stage k handed over; the consumers are done with stage k-1
+            if (k > 0) issue_next();               // ... whose slot takes stage k+3
+        }
+    } else {
+        // ------------------------------------------------------------------ consumers
+        const int r = lane & 31;
+        const int a_base = r * kTileBytes;
+        const int y16 = ((lane >> 5) ^ (r & 15)) << 4;               // see prefill_dma_kernel.hpp
+        const size_t ckpt_chunks = (size_t)p.d * kBottleneck / Storage<DT>::kElems;
+        const u32x4* bptr = p.packed + (size_t)c * ckpt_chunks + wave * 64 + lane;
+        constexpr int kGroups = Compute<DT>::kMmaGroups;             // 8
+        // W1' fragments of kPre k-tiles in flight: with few k-tiles per workgroup nothing else hides
+        // the L2 round trip.  Slot j holds k-tile k with k % kPre == j.
+        u32x4 breg[kPre][kGroups];
+#pragma unroll
+        for (int j = 0; j < kPre; ++j) {
+            const int kt = kt0 + (j < nk ? j : nk - 1);
+#pragma unroll
+            for (int g = 0; g < kGroups; ++g) breg[j][g] = bptr[(size_t)(kt * kGroups + g) * 256];
+        }
+        f32x16 acc[kBlocks];
+        float ssq[kBlocks];
+#pragma unroll
+        for (int b = 0; b < kBlocks; ++b) {
+            acc[b] = f32x16{0};
+            ssq[b] = 0.0f;
+        }
+        auto k_tile = [&](const char* st, u32x4 (&bf)[kGroups], int kn, auto refill) {
+#pragma unroll
+            for (int g = 0; g < kGroups; ++g) {
+                u32x4 a[kBlocks];
+#pragma unroll
+                for (int b = 0; b < kBlocks; ++b)
+                    a[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + (y16 ^ (g << 5)));
+#pragma unroll
+                for (int b = 0; b < kBlocks; ++b) acc[b] = mma_k16<DT>(a[b], bf[g], acc[b]);
+                if ((g & 3) == wave) {             // this wave's share of the sums of squares
+#pragma unroll
+                    for (int b = 0; b < kBlocks; ++b) ssq[b] = chunk_sumsq<DT>(a[b], ssq[b]);
+                }
+                if (decltype(refill)::value) bf[g] = bptr[(size_t)(kn * kGroups + g) * 256];
+            }
+        };
+        int k = 0;
+        for (; k + 2 * kPre <= nk; k += kPre) {    // steady state: every k-tile refills its slot
+#pragma unroll
+            for (int j = 0; j < kPre; ++j) {
+                ring_barrier();
+                k_tile(ring + ((k + j) % kDmaStages) * kStageBytes + a_base, breg[j], kt0 + k + j + kPre, std::true_type{});
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 2 * kPre - 1; ++j) {   // fewer than 2 kPre k-tiles left (k is a multiple of kPre)
+            if (k + j < nk) {
+                ring_barrier();
+                const char* st = ring + ((k + j) % kDmaStages) * kStageBytes + a_base;
+                if (k + j + kPre < nk) k_tile(st, breg[j % kPre], kt0 + k + j + kPre, std::true_type{});
+                else k_tile(st, breg[j % kPre], 0, std::false_type{});
+            }
+        }
+
+        // ---- what this workgroup leaves behind: its accumulators as they are, and per wave one
+        // partial sum of squares per row (lanes l and l^32 hold the two chunk phases)
+#pragma unroll
+        for (int b = 0; b < kBlocks; ++b) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<f32x4*>(zmine + (b * 4 + q) * 256) = f32x4{acc[b][4 * q], acc[b][4 * q + 1], acc[b][4 * q + 2], acc[b][4 * q + 3]};
+            const float s2 = ssq[b] + __shfl_xor(ssq[b], 32, kWave);
+            if (lane < 32) p.sspart[((size_t)item * kDmaConsumers + wave) * kRowsM + 32 * b + lane] = s2;
+        }
+    }
+}
+
+// Second launch: one workgroup of 4 waves per 32-row block (blockIdx.x = tile * kBlocks + block);
+// wave w owns columns 32w..32w+31 as consumer wave w of the first launch did.  Slices are added
+// in ascending order: the result does not depend on timing.
+template <int kBlocks>
+__global__ __launch_bounds__(kFinishThreads) void tide_splitk_finish_kernel(const PrefillParams p) {
+    __shared__ __attribute__((aligned(16))) float inv_rms[32];
+    __shared__ float z_part[4][32];
+    __shared__ float ss_part[8][32];
+    constexpr int kRowsM = kBlocks * 32;
+    constexpr int kPartFloats = splitk_part_floats<kBlocks>();
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tile = blockIdx.x / kBlocks, blk = blockIdx.x - tile * kBlocks;
+    const int c = tile / p.tiles_per_ckpt;
+    const int row0 = (tile - c * p.tiles_per_ckpt) * kRowsM + 32 * blk;
+    if (row0 >= p.T) return;                       // a block of padding rows only
+    const int S = p.k_slices;
+
+    // partial sums of squares: thread (row, j) adds the four waves' values of slices j, j+8, ...; the
+    // eight results per row are added in a fixed order below
+    float ss_mine = 0.0f;
+    {
+        const float* sp = p.sspart + (size_t)tile * S * kDmaConsumers * kRowsM + 32 * blk + (tid & 31);
+        for (int s = tid >> 5; s < S; s += 8) {
+            const float* q = sp + (size_t)s * kDmaConsumers * kRowsM;
+            ss_mine += (q[0] + q[kRowsM]) + (q[2 * kRowsM] + q[3 * kRowsM]);
+        }
+    }
+    // partial accumulators: eight slices' loads in flight at a time
+    const float* zp = p.zpart + (size_t)tile * S * kPartFloats + (size_t)(wave * kBlocks + blk) * 1024 + lane * 4;
+    f32x4 sum[4] = {f32x4{0}, f32x4{0}, f32x4{0}, f32x4{0}};
+    for (int s = 0; s < S; s += 8) {
+        f32x4 v[8][4];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int sj = s + j < S ? s + j : S - 1;              // clamped: a surplus load re-reads the last slice
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[j][q] = *reinterpret_cast<const f32x4*>(zp + (size_t)sj * kPartFloats + q * 256);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const bool keep = s + j < S;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) sum[q] += keep ? v[j][q] : f32x4{0};
+        }
+    }
+    ss_part[tid >> 5][tid & 31] = ss_mine;
+    __syncthreads();
+    if (tid < 32) {
+        const float ss = ((ss_part[0][tid] + ss_part[1][tid]) + (ss_part[2][tid] + ss_part[3][tid])) +
+                         ((ss_part[4][tid] + ss_part[5][tid]) + (ss_part[6][tid] + ss_part[7][tid]));
+        inv_rms[tid] = inv_rms_f32(ss, 1.0f / (float)p.d, p.eps);
+    }
+    __syncthreads();
+    {
+        f32x16 acc[1];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[0][4 * q + e] = sum[q][e];
+        const int col = 32 * wave + (lane & 31);
+        const float b1c = (p.b1 && col < p.b) ? p.b1[c * p.b + col] : 0.0f;
+        const float w2c = col < p.b ? p.w2[c * p.b + col] : 0.0f;
+        router_epilogue<1>(acc, inv_rms, z_part[wave], b1c, w2c, lane);
+    }
+    __syncthreads();
+    if (tid < 32) {
+        const int t = row0 + tid;
+        if (t < p.T) {
+            const float z = p.tab.b2[c] + ((z_part[0][tid] + z_part[1][tid]) + (z_part[2][tid] + z_part[3][tid]));
+            const int64_t o = (int64_t)c * p.T + t;
+            const bool f = z > p.tab.thr_logit[c];
+            if (p.logits) p.logits[o] = z;
+            if (p.prob) p.prob[o] = sigmoid_f32(z);
+            if (p.fire) p.fire[o] = f ? 1 : 0;
+            if (p.exit_layer)
+                report_and_select(p.tab, p.C, c, f, p.min_layer, p.no_exit, p.arrive + t, p.exit_layer + t,
+                                  p.fire_mask ? p.fire_mask + t : nullptr);
+        }
+    }
+}
+
+}  // namespace tide

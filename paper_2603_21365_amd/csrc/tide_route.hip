@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -19,6 +20,7 @@
 #include "pack_kernel.hpp"
 #include "prefill_dma_kernel.hpp"
 #include "prefill_kernel.hpp"
+#include "prefill_splitk_kernel.hpp"
 #include "prefill_wide_kernel.hpp"
 #include "project_kernel.hpp"
 
@@ -45,7 +47,11 @@ int fail(int code, const char* fmt, ...) {
 constexpr int kMaxDevices = 16;
 constexpr size_t kCounterSlots = 64;       // per-checkpoint counters of the decode kernel
 constexpr int kDecodeAutoMaxT = 32;
+constexpr int kDecodeRawMaxT = 8;          // raw weights where the split-k prefill form applies
 constexpr int kDecodeMaxT = 64;
+constexpr int kSplitkMaxSlices = 8;        // workgroups that share a tile's k range in the split-k prefill form
+constexpr int kSplitkMaxTiles = 24;        // most tiles for which that form is chosen automatically ...
+constexpr int kSplitkForcedMaxTiles = 1024;   // ... and when it is forced (tide_set_prefill_form(5))
 
 struct Buffer {
     void* ptr = nullptr;
@@ -216,6 +222,29 @@ template <int DT, int kHalves> int launch_wide(unsigned grid, hipStream_t st, co
     return TIDE_OK;
 }
 
+// The split-k pair: `tiles` tiles of kBlocks*32 rows times p.k_slices workgroups leave their partial
+// results in the workspace, then one small workgroup per 32-row block adds them and finishes the router.
+template <int DT, int kBlocks> int launch_splitk(Workspace& ws, int64_t tiles, hipStream_t st, PrefillParams& p) {
+    static bool raised[kMaxDevices] = {};
+    int dev = 0;
+    TIDE_HIP(hipGetDevice(&dev));
+    constexpr int lds = splitk_lds_bytes<kBlocks>();
+    if (!raised[dev]) {
+        TIDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&tide_prefill_splitk_kernel<DT, kBlocks>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        raised[dev] = true;
+    }
+    const size_t items = (size_t)tiles * p.k_slices;
+    const size_t z_bytes = items * splitk_part_floats<kBlocks>() * sizeof(float);
+    int rc = reserve(ws.part, z_bytes + items * kDmaConsumers * kBlocks * 32 * sizeof(float), false);
+    if (rc) return rc;
+    p.zpart = (float*)ws.part.ptr;
+    p.sspart = (float*)((char*)ws.part.ptr + z_bytes);
+    hipLaunchKernelGGL((tide_prefill_splitk_kernel<DT, kBlocks>), dim3((unsigned)items), dim3(kDmaThreads), lds, st, p);
+    hipLaunchKernelGGL((tide_splitk_finish_kernel<kBlocks>), dim3((unsigned)(tiles * kBlocks)), dim3(kFinishThreads), 0, st, p);
+    return TIDE_OK;
+}
+
 // The streaming kernels use more LDS than the default per-kernel limit: raise it once.
 // They are persistent: at most one (128-row) or two (64-row) workgroups per CU, each walking
 // a list of tiles.
@@ -296,6 +325,32 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
         p.arrive = (uint64_t*)ws.arrive.ptr;
     }
     int rc = TIDE_OK;
+    // Split-k form: with few tiles (of 32, 64 or 128 rows, whatever holds a checkpoint's rows), up to
+    // 8 workgroups share a tile's k range and a second launch adds their results.  Measured against
+    // the streaming kernel on a 256-CU device at d = 4096: 9.5-18 us instead of 19-21 us up to 16
+    // tiles of 128 rows, even at 32, slower beyond (the partial results are 64 KiB per workgroup).
+    if (!ring_form && !two_halves && dtype != TIDE_F32 && (g_prefill_form == 0 || g_prefill_form == 5)) {
+        const int rows = T <= 32 ? 32 : T <= 64 ? 64 : 128;
+        const int64_t tpc = (T + rows - 1) / rows, tiles = C * tpc;
+        const int64_t ntile = d * (int64_t)eb / kTileBytes;
+        int64_t S = std::min<int64_t>(ntile, kSplitkMaxSlices);
+        if (tiles > (g_prefill_form == 5 ? kSplitkForcedMaxTiles : kSplitkMaxTiles)) S = 1;
+        if (S >= 2) {
+            p.tiles_per_ckpt = (int)tpc;
+            p.total_tiles = (int)tiles;
+            p.k_slices = (int)S;
+            by_dtype(dtype, [&](auto dt) {
+                constexpr int DT = decltype(dt)::value;
+                if constexpr (DT != kF32)
+                    rc = rows == 32 ? launch_splitk<DT, 1>(ws, tiles, st, p)
+                       : rows == 64 ? launch_splitk<DT, 2>(ws, tiles, st, p) : launch_splitk<DT, 4>(ws, tiles, st, p);
+                return 0;
+            });
+            if (rc) return rc;
+            TIDE_HIP(hipGetLastError());
+            return TIDE_OK;
+        }
+    }
     // Wide-tile form: whole rounds of wide tiles (256 rows, or 128 rows at width 256; one per CU and
     // round) go to the wide kernel, what is left of the checkpoint-major row list to the streaming
     // kernel with half as many rows per tile behind it on the same stream (the arrival words carry
@@ -417,10 +472,19 @@ int launch_decode(Workspace& ws, const void* hidden, int dtype, int64_t C, int64
     return TIDE_OK;
 }
 
-bool use_decode(int64_t T) {
+// The latency kernel (fp32 FMAs, raw or packed weights, k split over workgroups) or the prefill path?
+// With packed weights of a 16-bit type the split-k prefill form is the faster one at every T
+// (measured, d = 4096, C = 1 / 8: 9.5 / 10.6 us against 10.8 / 13.9 us at T = 1, 13.5 / 15.9 us at
+// T = 8 and 40 us at T = 32).  With raw weights that form needs the packing pass first (7.5 us at
+// C = 8), so the latency kernel, which reads W1 as it is, keeps T <= 8 (11-15 us against 17 us);
+// it also keeps, up to T = 32, what the split-k form does not cover.
+bool use_decode(int64_t T, int dtype, int64_t d, int64_t b, bool packed_given) {
     if (g_variant == TIDE_VARIANT_DECODE) return T <= kDecodeMaxT;
     if (g_variant == TIDE_VARIANT_PREFILL) return false;
-    return T <= kDecodeAutoMaxT;
+    const bool split_k = dtype != TIDE_F32 && d % 128 == 0 && d >= 256 && b <= kBottleneck &&
+                         (g_prefill_form == 0 || g_prefill_form == 5);
+    if (!split_k) return T <= kDecodeAutoMaxT;
+    return !packed_given && T <= kDecodeRawMaxT;
 }
 
 // Shared body of the four compute entry points.  Exactly one of (W1) / (packed) is given.
@@ -433,7 +497,7 @@ int run(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t 
     Workspace* ws = nullptr;
     int rc = current_workspace(&ws);
     if (rc) return rc;
-    if (use_decode(T))
+    if (use_decode(T, dtype, d, b, packed != nullptr))
         return launch_decode(*ws, hidden, dtype, C, T, d, b, ckpt_stride, row_stride, gamma, W1, packed, eps, b1, w2, tab,
                              min_layer, no_exit, o, st);
     if (W1) {
@@ -736,7 +800,7 @@ int tide_set_variant(int variant) {
 }
 
 int tide_set_prefill_form(int form) {
-    if (form < 0 || form > 4) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d outside [0, 4]", form);
+    if (form < 0 || form > 5) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d outside [0, 5]", form);
     std::lock_guard<std::mutex> lock(g_mu);
     int prev = g_prefill_form;
     g_prefill_form = form;

@@ -107,11 +107,12 @@ def test_config1_full(tr, packed):
     assert st["max_abs_err"] < 1e-2                      # bf16 W1' rounding: well inside the 2e-2 bar
 
 
-@pytest.mark.parametrize("form", [1, 2, 3, 4])
+@pytest.mark.parametrize("form", [1, 2, 3, 4, 5, 0])
 @pytest.mark.parametrize("dtype,T,d", [("bf16", 300, 1024), ("f16", 129, 768), ("f32", 257, 512), ("bf16", 64, 128), ("f16", 1100, 384)])
 def test_every_prefill_form_computes_the_same_function(tr, form, dtype, T, d):
-    """Streaming form with 64 / 128 rows per workgroup and the register-ring form, forced in
-    turn, on ragged token counts and on a hidden size with a single k-tile."""
+    """Streaming form with 64 / 128 rows per workgroup, the register-ring form, the wide-tile form,
+    the split-k form and the automatic choice, in turn, on ragged token counts and on a hidden
+    size with a single k-tile (forms that do not apply to a case fall back to one that does)."""
     w = synth.Workload(f"form{form}_{dtype}_T{T}_d{d}", 29, dtype, d, 12, 4, T, None)
     rt = w.routers()
     rt.b2[:] = [0.2, -0.1, 0.0]
@@ -148,6 +149,29 @@ def test_uneven_tile_counts_split_the_last_round(tr, form, dtype, layers, T, d, 
         tr.set_prefill_form(0)
 
 
+@pytest.mark.parametrize("C,dtype,T,d,b,what", [
+    (1, "bf16", 4096, 4096, 128, "one checkpoint of the 8B-shaped prefill: 32 tiles x 8 slices of 4 k-tiles"),
+    (1, "f16", 4000, 4096, 128, "ragged last tile"),
+    (8, "bf16", 64, 4096, 128, "batched decode step: 8 tiles of 64 rows x 32 slices of one k-tile"),
+    (8, "bf16", 50, 2048, 64, "64-row tiles with 14 padding rows, width 64"),
+    (8, "f16", 1000, 4096, 128, "64 tiles x 4 slices, ragged"),
+    (3, "bf16", 640, 1408, 128, "15 tiles x 11 slices of the 11 k-tiles"),
+    (5, "bf16", 700, 1920, 128, "30 tiles x 8 slices of 15 k-tiles: uneven slices"),
+    (1, "f16", 16384, 512, 128, "128 tiles x 2 slices of 2 k-tiles"),
+    (2, "bf16", 33, 16384, 128, "the largest hidden size: 2 tiles x 128 slices"),
+])
+def test_split_k_form_for_batches_with_few_tiles(tr, C, dtype, T, d, b, what):
+    """The automatic choice for 16-bit rows and at most half as many 128-row tiles as CUs (a
+    256-CU device is assumed for the counts): workgroups share a tile's k range, a second launch
+    adds their partial results."""
+    w = synth.Workload(f"splitk_{dtype}_C{C}_T{T}_d{d}_b{b}", 37, dtype, d, 4 * C, 4, T, None, b=b)
+    say(what)
+    rt = w.routers()
+    rt.b2[:] = np.linspace(-0.2, 0.2, w.C)
+    run_and_compare(tr, w, w.name, rt=rt, packed=True, variant=tr.VARIANT_PREFILL)
+    run_and_compare(tr, w, w.name + "_raw", rt=rt, packed=False, variant=tr.VARIANT_PREFILL)
+
+
 @pytest.mark.parametrize("form", [1, 2, 3])
 def test_config1_full_in_every_prefill_form(tr, form):
     w = synth.config1()
@@ -173,9 +197,13 @@ def test_config2_decode(tr, T):
                                                 variant=tr.VARIANT_PREFILL)
     assert st_d["max_abs_err"] < 1e-4                    # the decode variant computes in fp32 on fp32 weights
     assert np.abs(z_d - z_p).max() < 2e-2
-    # packed weights, small T: the decode kernel's packed form (fp16 weights, fp32 arithmetic)
+    # packed weights, small T: the automatic choice is the split-k pair on the matrix cores (fp16 weights) ...
     st_k, _, (ex_k, z_k, m_k) = run_and_compare(tr, w, f"config2_T{T}_packed", rt=rt, hidden_bits=hb, packed=True)
     assert st_k["max_abs_err"] < 5e-3
+    # ... and, forced, the latency kernel's packed form (fp16 weights, fp32 arithmetic)
+    st_l, _, _ = run_and_compare(tr, w, f"config2_T{T}_packed_latency_kernel", rt=rt, hidden_bits=hb, packed=True,
+                                 variant=tr.VARIANT_DECODE)
+    assert st_l["max_abs_err"] < 5e-3
 
 
 # ------------------------------------------------------------------ config 3: 36-layer batched prefill, bf16, full size
@@ -393,6 +421,17 @@ def test_decode_variant_token_counts(tr, T, C, dtype):
     run_and_compare(tr, w, w.name, rt=rt, hidden_bits=hb, variant=tr.VARIANT_DECODE)
     # the same on pre-packed weights (bf16 / fp16 weights, or hi + mid bf16 planes for fp32 rows)
     run_and_compare(tr, w, w.name + "_packed", rt=rt, hidden_bits=hb, variant=tr.VARIANT_DECODE, packed=True)
+
+
+@pytest.mark.parametrize("T", [1, 2, 7, 8, 9, 31, 32, 33, 63, 64, 65, 127, 129])
+@pytest.mark.parametrize("C,dtype,d", [(1, "f16", 768), (3, "bf16", 256), (8, "bf16", 2048)])
+def test_split_k_pair_on_decode_sized_batches(tr, T, C, dtype, d):
+    """Packed weights of a 16-bit type, automatic choice: tiles of 32, 64 or 128 rows (whatever holds
+    the T rows of a checkpoint), up to 8 workgroups per tile along the hidden dimension."""
+    w = synth.Workload(f"splitk_small_T{T}_C{C}_{dtype}_d{d}", 41, dtype, d, 4 * C, 4, T, None)
+    rt = w.routers()
+    rt.b2[:] = np.linspace(-0.2, 0.2, C)
+    run_and_compare(tr, w, w.name, rt=rt, packed=True)
 
 
 def test_thresholds_off_and_always_and_min_layer(tr):
