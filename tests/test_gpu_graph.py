@@ -21,7 +21,7 @@ def tr():
     tide_route.set_variant(tide_route.VARIANT_AUTO)
 
 
-@pytest.mark.parametrize("case", ["decode_T8_raw", "prefill_T600_packed_then_project"])
+@pytest.mark.parametrize("case", ["decode_T8_raw", "decode_T8_packed", "prefill_T600_packed_then_project"])
 def test_captured_calls_replay_like_eager_calls(tr, case):
     import torch
     decode = case.startswith("decode")
@@ -37,11 +37,14 @@ def test_captured_calls_replay_like_eager_calls(tr, case):
     out = (torch.empty(T, dtype=torch.int32, device="cuda"), torch.empty((w.C, T), dtype=torch.float32, device="cuda"),
            torch.empty(T, dtype=torch.int32, device="cuda"))
     proj = torch.empty((T, w.d), dtype=hidden.dtype, device="cuda")
-    packed = None if decode else tr.router_pack(tr.DTYPE_CODES[dtype], g, W1)
+    raw = case.endswith("raw")
+    packed = None if raw else tr.router_pack(tr.DTYPE_CODES[dtype], g, W1)
 
     def step():
-        if decode:
+        if raw:                                                # the latency kernel
             tr.select_exit(hidden, g, w.eps, W1, b1, w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers, out=out)
+        elif decode:                                           # the split-k pair: two kernels, partial results in the workspace
+            tr.select_exit_packed(hidden, packed, w.eps, b1, w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers, d=w.d, out=out)
         else:
             tr.select_exit_packed(hidden, packed, w.eps, b1, w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers, d=w.d, out=out)
             tr.exit_project(hidden, final, out[0], w.layer_ids, None, 1e-6, out=proj)
