@@ -18,7 +18,8 @@
 // 8 slices that alone took longer (24 us a call) than the second launch costs (13 us a call).
 // The price of the form is the partial results -- 16 KiB per workgroup and 32-row block, written
 // once and read once -- which is why it stops where the tiles are many.
-// 16-bit storage types, bottleneck widths 64 / 128, d a multiple of 128.
+// 16-bit storage types, d a multiple of 128; at bottleneck width 256 each 128-column half of a
+// tile is a workgroup of its own in the first launch.
 #pragma once
 #include <type_traits>
 
@@ -35,8 +36,9 @@ template <int kBlocks> constexpr int splitk_lds_bytes() { return kDmaStages * kB
 // contiguous, and a lane of the second launch reads back the registers of its own position.
 template <int kBlocks> constexpr int splitk_part_floats() { return kBlocks * 32 * kBottleneck; }
 
-// First launch: blockIdx.x = tile * p.k_slices + slice; tiles of kBlocks*32 rows, checkpoint-major
-// (p.tiles_per_ckpt per checkpoint); slice s covers k-tiles [s*n/S, (s+1)*n/S) of the n = d/128
+// First launch: blockIdx.x = (tile * halves + half) * p.k_slices + slice; tiles of kBlocks*32 rows,
+// checkpoint-major (p.tiles_per_ckpt per checkpoint); half = which 128 columns of the bottleneck
+// (halves = 2 at width 256, else 1); slice s covers k-tiles [s*n/S, (s+1)*n/S) of the n = d/128
 // k-tiles of a row (S <= n, so every slice has at least one).
 template <int DT, int kBlocks>
 __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_splitk_kernel(const PrefillParams p) {
@@ -53,8 +55,10 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_splitk_kernel(con
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int S = p.k_slices;
+    const int halves = (p.b + kBottleneck - 1) / kBottleneck;
     const int item = blockIdx.x;
-    const int tile = item / S, slice = item - tile * S;
+    const int th = item / S, slice = item - th * S;
+    const int tile = th / halves, half = th - tile * halves;
     const int ntile = p.d * Storage<DT>::kBytes / kTileBytes;
     const int kt0 = slice * ntile / S, nk = (slice + 1) * ntile / S - kt0;
     const int c = tile / p.tiles_per_ckpt;
@@ -103,7 +107,7 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_splitk_kernel(con
         const int a_base = r * kTileBytes;
         const int y16 = ((lane >> 5) ^ (r & 15)) << 4;               // see prefill_dma_kernel.hpp
         const size_t ckpt_chunks = (size_t)p.d * kBottleneck / Storage<DT>::kElems;
-        const u32x4* bptr = p.packed + (size_t)c * ckpt_chunks + wave * 64 + lane;
+        const u32x4* bptr = p.packed + ((size_t)c * halves + half) * ckpt_chunks + wave * 64 + lane;
         constexpr int kGroups = Compute<DT>::kMmaGroups;             // 8
         // W1' fragments of kPre k-tiles in flight: with few k-tiles per workgroup nothing else hides
         // the L2 round trip.  Slot j holds k-tile k with k % kPre == j.
@@ -168,35 +172,37 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_splitk_kernel(con
     }
 }
 
-// Second launch: one workgroup of 4 waves per 32-row block (blockIdx.x = tile * kBlocks + block);
-// wave w owns columns 32w..32w+31 as consumer wave w of the first launch did.  Slices are added
-// in ascending order: the result does not depend on timing.
-template <int kBlocks>
-__global__ __launch_bounds__(kFinishThreads) void tide_splitk_finish_kernel(const PrefillParams p) {
+// Second launch: one workgroup per 32-row block (blockIdx.x = tile * kBlocks + block) with 4 waves
+// per column half; wave w of a half owns its columns 32w..32w+31 as consumer wave w of the first
+// launch did.  Slices are added in ascending order: the result does not depend on timing.
+template <int kBlocks, int kHalves>
+__global__ __launch_bounds__(kFinishThreads * kHalves) void tide_splitk_finish_kernel(const PrefillParams p) {
     __shared__ __attribute__((aligned(16))) float inv_rms[32];
-    __shared__ float z_part[4][32];
+    __shared__ float z_part[4 * kHalves][32];
     __shared__ float ss_part[8][32];
     constexpr int kRowsM = kBlocks * 32;
     constexpr int kPartFloats = splitk_part_floats<kBlocks>();
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = wave >> 2, w = wave & 3;
     const int tile = blockIdx.x / kBlocks, blk = blockIdx.x - tile * kBlocks;
     const int c = tile / p.tiles_per_ckpt;
     const int row0 = (tile - c * p.tiles_per_ckpt) * kRowsM + 32 * blk;
     if (row0 >= p.T) return;                       // a block of padding rows only
     const int S = p.k_slices;
 
-    // partial sums of squares: thread (row, j) adds the four waves' values of slices j, j+8, ...; the
-    // eight results per row are added in a fixed order below
+    // partial sums of squares (those of column half 0; every half computed the same ones): thread
+    // (row, j) adds the four waves' values of slices j, j+8, ...; the eight results per row are
+    // added in a fixed order below
     float ss_mine = 0.0f;
-    {
-        const float* sp = p.sspart + (size_t)tile * S * kDmaConsumers * kRowsM + 32 * blk + (tid & 31);
+    if (tid < kFinishThreads) {
+        const float* sp = p.sspart + (size_t)tile * kHalves * S * kDmaConsumers * kRowsM + 32 * blk + (tid & 31);
         for (int s = tid >> 5; s < S; s += 8) {
             const float* q = sp + (size_t)s * kDmaConsumers * kRowsM;
             ss_mine += (q[0] + q[kRowsM]) + (q[2 * kRowsM] + q[3 * kRowsM]);
         }
     }
     // partial accumulators: eight slices' loads in flight at a time
-    const float* zp = p.zpart + (size_t)tile * S * kPartFloats + (size_t)(wave * kBlocks + blk) * 1024 + lane * 4;
+    const float* zp = p.zpart + (size_t)(tile * kHalves + half) * S * kPartFloats + (size_t)(w * kBlocks + blk) * 1024 + lane * 4;
     f32x4 sum[4] = {f32x4{0}, f32x4{0}, f32x4{0}, f32x4{0}};
     for (int s = 0; s < S; s += 8) {
         f32x4 v[8][4];
@@ -213,7 +219,7 @@ __global__ __launch_bounds__(kFinishThreads) void tide_splitk_finish_kernel(cons
             for (int q = 0; q < 4; ++q) sum[q] += keep ? v[j][q] : f32x4{0};
         }
     }
-    ss_part[tid >> 5][tid & 31] = ss_mine;
+    if (tid < kFinishThreads) ss_part[tid >> 5][tid & 31] = ss_mine;
     __syncthreads();
     if (tid < 32) {
         const float ss = ((ss_part[0][tid] + ss_part[1][tid]) + (ss_part[2][tid] + ss_part[3][tid])) +
@@ -227,7 +233,8 @@ __global__ __launch_bounds__(kFinishThreads) void tide_splitk_finish_kernel(cons
         for (int q = 0; q < 4; ++q)
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc[0][4 * q + e] = sum[q][e];
-        const int col = 32 * wave + (lane & 31);
+        // (columns at and beyond the bottleneck width are zero padding: their w2 is zero)
+        const int col = kBottleneck * half + 32 * w + (lane & 31);
         const float b1c = (p.b1 && col < p.b) ? p.b1[c * p.b + col] : 0.0f;
         const float w2c = col < p.b ? p.w2[c * p.b + col] : 0.0f;
         router_epilogue<1>(acc, inv_rms, z_part[wave], b1c, w2c, lane);
@@ -236,7 +243,9 @@ __global__ __launch_bounds__(kFinishThreads) void tide_splitk_finish_kernel(cons
     if (tid < 32) {
         const int t = row0 + tid;
         if (t < p.T) {
-            const float z = p.tab.b2[c] + ((z_part[0][tid] + z_part[1][tid]) + (z_part[2][tid] + z_part[3][tid]));
+            float zsum = (z_part[0][tid] + z_part[1][tid]) + (z_part[2][tid] + z_part[3][tid]);
+            if constexpr (kHalves == 2) zsum += (z_part[4][tid] + z_part[5][tid]) + (z_part[6][tid] + z_part[7][tid]);
+            const float z = p.tab.b2[c] + zsum;
             const int64_t o = (int64_t)c * p.T + t;
             const bool f = z > p.tab.thr_logit[c];
             if (p.logits) p.logits[o] = z;

@@ -50,7 +50,7 @@ constexpr int kDecodeAutoMaxT = 32;
 constexpr int kDecodeRawMaxT = 8;          // raw weights where the split-k prefill form applies
 constexpr int kDecodeMaxT = 64;
 constexpr int kSplitkMaxSlices = 8;        // workgroups that share a tile's k range in the split-k prefill form
-constexpr int kSplitkMaxTiles = 24;        // most tiles for which that form is chosen automatically ...
+constexpr int kSplitkMaxTiles = 128;       // most tiles (x column halves) for which that form can be chosen automatically ...
 constexpr int kSplitkForcedMaxTiles = 1024;   // ... and when it is forced (tide_set_prefill_form(5))
 
 struct Buffer {
@@ -234,14 +234,18 @@ template <int DT, int kBlocks> int launch_splitk(Workspace& ws, int64_t tiles, h
                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds));
         raised[dev] = true;
     }
-    const size_t items = (size_t)tiles * p.k_slices;
+    const int halves = halves_of(p.b);
+    const size_t items = (size_t)tiles * halves * p.k_slices;
     const size_t z_bytes = items * splitk_part_floats<kBlocks>() * sizeof(float);
     int rc = reserve(ws.part, z_bytes + items * kDmaConsumers * kBlocks * 32 * sizeof(float), false);
     if (rc) return rc;
     p.zpart = (float*)ws.part.ptr;
     p.sspart = (float*)((char*)ws.part.ptr + z_bytes);
     hipLaunchKernelGGL((tide_prefill_splitk_kernel<DT, kBlocks>), dim3((unsigned)items), dim3(kDmaThreads), lds, st, p);
-    hipLaunchKernelGGL((tide_splitk_finish_kernel<kBlocks>), dim3((unsigned)(tiles * kBlocks)), dim3(kFinishThreads), 0, st, p);
+    if (halves == 2)
+        hipLaunchKernelGGL((tide_splitk_finish_kernel<kBlocks, 2>), dim3((unsigned)(tiles * kBlocks)), dim3(2 * kFinishThreads), 0, st, p);
+    else
+        hipLaunchKernelGGL((tide_splitk_finish_kernel<kBlocks, 1>), dim3((unsigned)(tiles * kBlocks)), dim3(kFinishThreads), 0, st, p);
     return TIDE_OK;
 }
 
@@ -326,15 +330,24 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
     }
     int rc = TIDE_OK;
     // Split-k form: with few tiles (of 32, 64 or 128 rows, whatever holds a checkpoint's rows), up to
-    // 8 workgroups share a tile's k range and a second launch adds their results.  Measured against
-    // the streaming kernel on a 256-CU device at d = 4096: 9.5-18 us instead of 19-21 us up to 16
-    // tiles of 128 rows, even at 32, slower beyond (the partial results are 64 KiB per workgroup).
-    if (!ring_form && !two_halves && dtype != TIDE_F32 && (g_prefill_form == 0 || g_prefill_form == 5)) {
+    // 8 workgroups share a tile's k range and a second launch adds their results.  Whether that beats
+    // the streaming kernel depends on how long a row is (the streaming kernel's dependent chain) and
+    // on how many tiles there are (the partial results: 16 KiB per workgroup and 32-row block), so the
+    // choice compares two cost estimates, in microseconds, fitted to measurements on a 256-CU device
+    // (d = 1024 ... 8192, 1 ... 128 tiles, widths 128 and 256):
+    //   streaming, few tiles:  5.7 + 0.48 n   (n = k-tiles of a row; width 256: 7.0 + 1.17 n)
+    //   split-k pair:          8.2 + 0.3 (n / S)(rows / 32) + 0.08 (rows / 32) tiles
+    if (!ring_form && dtype != TIDE_F32 && (g_prefill_form == 0 || g_prefill_form == 5)) {
         const int rows = T <= 32 ? 32 : T <= 64 ? 64 : 128;
+        const int halves = halves_of(b);
         const int64_t tpc = (T + rows - 1) / rows, tiles = C * tpc;
         const int64_t ntile = d * (int64_t)eb / kTileBytes;
         int64_t S = std::min<int64_t>(ntile, kSplitkMaxSlices);
-        if (tiles > (g_prefill_form == 5 ? kSplitkForcedMaxTiles : kSplitkMaxTiles)) S = 1;
+        const double blocks = rows / 32, col_tiles = (double)(tiles * halves);
+        const double t_split = 8.2 + 0.3 * (double)((ntile + S - 1) / S) * blocks + 0.08 * blocks * col_tiles;
+        const double t_stream = halves == 1 ? 5.7 + 0.48 * (double)ntile : 7.0 + 1.17 * (double)ntile;
+        if (g_prefill_form == 5 ? tiles * halves > kSplitkForcedMaxTiles
+                                : (tiles * halves > kSplitkMaxTiles || t_split + 0.3 >= t_stream)) S = 1;
         if (S >= 2) {
             p.tiles_per_ckpt = (int)tpc;
             p.total_tiles = (int)tiles;
@@ -481,7 +494,7 @@ int launch_decode(Workspace& ws, const void* hidden, int dtype, int64_t C, int64
 bool use_decode(int64_t T, int dtype, int64_t d, int64_t b, bool packed_given) {
     if (g_variant == TIDE_VARIANT_DECODE) return T <= kDecodeMaxT;
     if (g_variant == TIDE_VARIANT_PREFILL) return false;
-    const bool split_k = dtype != TIDE_F32 && d % 128 == 0 && d >= 256 && b <= kBottleneck &&
+    const bool split_k = dtype != TIDE_F32 && d % 128 == 0 && d >= 256 &&
                          (g_prefill_form == 0 || g_prefill_form == 5);
     if (!split_k) return T <= kDecodeAutoMaxT;
     return !packed_given && T <= kDecodeRawMaxT;

@@ -150,26 +150,33 @@ def test_uneven_tile_counts_split_the_last_round(tr, form, dtype, layers, T, d, 
 
 
 @pytest.mark.parametrize("C,dtype,T,d,b,what", [
-    (1, "bf16", 4096, 4096, 128, "one checkpoint of the 8B-shaped prefill: 32 tiles x 8 slices of 4 k-tiles"),
-    (1, "f16", 4000, 4096, 128, "ragged last tile"),
-    (8, "bf16", 64, 4096, 128, "batched decode step: 8 tiles of 64 rows x 32 slices of one k-tile"),
+    (1, "bf16", 2048, 4096, 128, "one checkpoint of an 8B-shaped prefill: 16 tiles x 8 slices of 4 k-tiles"),
+    (1, "f16", 3000, 4096, 128, "24 tiles, ragged last tile"),
+    (8, "bf16", 64, 4096, 128, "batched decode step: 8 tiles of 64 rows x 8 slices of 4 k-tiles"),
     (8, "bf16", 50, 2048, 64, "64-row tiles with 14 padding rows, width 64"),
-    (8, "f16", 1000, 4096, 128, "64 tiles x 4 slices, ragged"),
-    (3, "bf16", 640, 1408, 128, "15 tiles x 11 slices of the 11 k-tiles"),
-    (5, "bf16", 700, 1920, 128, "30 tiles x 8 slices of 15 k-tiles: uneven slices"),
-    (1, "f16", 16384, 512, 128, "128 tiles x 2 slices of 2 k-tiles"),
-    (2, "bf16", 33, 16384, 128, "the largest hidden size: 2 tiles x 128 slices"),
+    (8, "f16", 1000, 4096, 128, "64 tiles: more than the automatic choice takes, forced"),
+    (3, "bf16", 640, 1408, 128, "15 tiles x 8 slices of the 11 k-tiles: slices of 1 and 2 k-tiles"),
+    (4, "bf16", 700, 1920, 128, "24 tiles x 8 slices of 15 k-tiles: uneven slices"),
+    (1, "f16", 16384, 512, 128, "128 tiles x 4 slices of one k-tile, forced"),
+    (2, "bf16", 33, 16384, 128, "the largest hidden size: 2 tiles of 64 rows x 8 slices of 16 k-tiles"),
+    (8, "f16", 8, 4096, 256, "width 256, decode step: each 128-column half of a tile is a workgroup of its own"),
+    (2, "bf16", 300, 2048, 256, "width 256: 6 tiles x 2 halves x 8 slices, ragged"),
+    (1, "bf16", 1, 8192, 256, "width 256 at the 70B shape, a single row"),
 ])
 def test_split_k_form_for_batches_with_few_tiles(tr, C, dtype, T, d, b, what):
-    """The automatic choice for 16-bit rows and at most half as many 128-row tiles as CUs (a
-    256-CU device is assumed for the counts): workgroups share a tile's k range, a second launch
-    adds their partial results."""
+    """The split-k form (the automatic choice for 16-bit rows and at most 24 tiles; forced here so
+    that larger cases run on it too): up to 8 workgroups share a tile's k range, a second launch adds
+    their partial results."""
     w = synth.Workload(f"splitk_{dtype}_C{C}_T{T}_d{d}_b{b}", 37, dtype, d, 4 * C, 4, T, None, b=b)
     say(what)
     rt = w.routers()
     rt.b2[:] = np.linspace(-0.2, 0.2, w.C)
-    run_and_compare(tr, w, w.name, rt=rt, packed=True, variant=tr.VARIANT_PREFILL)
-    run_and_compare(tr, w, w.name + "_raw", rt=rt, packed=False, variant=tr.VARIANT_PREFILL)
+    tr.set_prefill_form(5)
+    try:
+        run_and_compare(tr, w, w.name, rt=rt, packed=True, variant=tr.VARIANT_PREFILL)
+        run_and_compare(tr, w, w.name + "_raw", rt=rt, packed=False, variant=tr.VARIANT_PREFILL)
+    finally:
+        tr.set_prefill_form(0)
 
 
 @pytest.mark.parametrize("form", [1, 2, 3])
