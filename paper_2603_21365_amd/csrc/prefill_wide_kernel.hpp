@@ -6,16 +6,20 @@
 // hidden byte crosses it once and, because a 128-row tile needs its checkpoint's whole W1',
 // so does one byte of W1' per hidden byte.  Twice the rows per fetch of W1' halves that second
 // stream.  256 rows of accumulators do not fit one wave, so
-//   - W1' goes through LDS as well: the producer waves transfer the k-tile's fragments (one
-//     contiguous 16 KiB of the packed weights) into the ring next to the rows, ONCE per
-//     workgroup, and
+//   - W1' goes through LDS as well: a producer wave transfers the k-tile's fragments (one
+//     contiguous 16 KiB of the packed weights) into LDS, ONCE per workgroup, and
 //   - 8 consumer waves read them from there: wave cw owns rows 128 (cw / 4) .. +127 and columns
 //     32 (cw % 4) .. +31, four 32x32 accumulator blocks like a consumer of the 128-row kernel.
-// Consumers issue no global loads at all.  A k-tile is 64 elements (128 bytes of a row) so that a
-// ring of three stages (32 KiB of rows + 16 KiB of W1' each) fits the 160 KiB of LDS.
+// Consumers issue no global loads at all.  A k-tile is 64 elements (128 bytes of a row).
+// Rows and W1' have rings and producer waves of their own (two waves fetch rows, a third W1'):
+// they come from different distances -- the rows from HBM, W1' from L2 -- and loads return to a
+// wave in issue order, so a wave that fetches both has its quick loads queued behind its slow
+// ones.  Both rings hold three stages, two in flight.  The epilogue's scratch arrays live in the
+// W1' slot that the tile's last stage has just vacated (the other slots already hold the next
+// tile's first fragments).
 // The same structure serves bottleneck width 256 (kHalves = 2): 128 rows x 256 columns per
-// workgroup, wave cw owning column block cw % 4 of column half cw / 4 -- the stage is then 16 KiB
-// of rows + 32 KiB of W1' (both halves), the same 48 KiB.
+// workgroup, wave cw owning column block cw % 4 of column half cw / 4 -- a stage is then 16 KiB
+// of rows + 32 KiB of W1' (both halves).
 // 16-bit storage types, d a multiple of 128.
 #pragma once
 #include "device_utils.hpp"
@@ -23,23 +27,40 @@
 
 namespace tide {
 
-// 128 bytes of each row per stage (64 elements) in a ring of 3 stages.  (64 bytes in 6 stages
-// was measured too: 52 % of HBM peak instead of 68 % -- the row segments become too short.)
+#ifndef TIDE_WIDE_ASTAGES
+#define TIDE_WIDE_ASTAGES 3
+#endif
+#ifndef TIDE_WIDE_BSTAGES
+#define TIDE_WIDE_BSTAGES 3
+#endif
+#ifndef TIDE_WIDE_ASTAGES2
+#define TIDE_WIDE_ASTAGES2 3
+#endif
+#ifndef TIDE_WIDE_BSTAGES2
+#define TIDE_WIDE_BSTAGES2 3
+#endif
+
+// 128 bytes of each row per stage (64 elements).  (64 bytes per stage in a ring twice as deep was
+// measured too: 52 % of HBM peak instead of 68 % -- the row segments become too short.)
 constexpr int kWideTileBytes = 128;
-constexpr int kWideStages = 3;
 constexpr int kWideChunksPerRow = kWideTileBytes / 16;                       // 8
 constexpr int kWideRowsPerTransfer = 64 / kWideChunksPerRow;                 // 8
 // bank-conflict-free placement: the chunk slot of a row is its chunk index XOR these bits of the row
 __device__ __forceinline__ int wide_swizzle(int row) { return (row / (16 / kWideChunksPerRow)) & (kWideChunksPerRow - 1); }
 constexpr int kWideConsumers = 8;
-constexpr int kWideThreads = (kWideConsumers + kDmaProducers) * kWave;        // 640
+constexpr int kWideRowProducers = 2;                                         // waves that fetch rows
+constexpr int kWideProducers = kWideRowProducers + 1;                        // ... and the one that fetches W1'
+constexpr int kWideThreads = (kWideConsumers + kWideProducers) * kWave;      // 704
 constexpr int kWideRows = 256;                                               // rows per tile at widths 64 / 128
 constexpr int wide_rows(int kHalves) { return kWideRows / kHalves; }         // 256, or 128 at width 256
 constexpr int wide_a_bytes(int kHalves) { return wide_rows(kHalves) * kWideTileBytes; }                 // 32 / 16 KiB of rows per stage
-constexpr int wide_b_bytes(int kHalves) { return kHalves * (kWideTileBytes / 2) * kBottleneck * 2; }    // 16 / 32 KiB of W1'
-constexpr int kWideStageBytes = wide_a_bytes(1) + wide_b_bytes(1);                                      // 48 KiB either way
-constexpr int kWideInstr = kWideStageBytes / 1024 / kDmaProducers;            // 24 transfers per producer and stage
-constexpr int kWideLdsBytes = kWideStages * kWideStageBytes + (4 + 4 + 1) * kWideRows * (int)sizeof(float);
+constexpr int wide_b_bytes(int kHalves) { return kHalves * (kWideTileBytes / 2) * kBottleneck * 2; }    // 16 / 32 KiB of W1' per stage
+constexpr int wide_a_stages(int kHalves) { return kHalves == 1 ? TIDE_WIDE_ASTAGES : TIDE_WIDE_ASTAGES2; }
+constexpr int wide_b_stages(int kHalves) { return kHalves == 1 ? TIDE_WIDE_BSTAGES : TIDE_WIDE_BSTAGES2; }
+constexpr int wide_lds_bytes(int kHalves) { return wide_a_stages(kHalves) * wide_a_bytes(kHalves) + wide_b_stages(kHalves) * wide_b_bytes(kHalves); }
+constexpr int wide_scratch_bytes(int kHalves) { return (4 + 4 * kHalves + 1) * wide_rows(kHalves) * (int)sizeof(float); }
+static_assert(wide_lds_bytes(1) <= 160 * 1024 && wide_lds_bytes(2) <= 160 * 1024, "LDS of a CU");
+static_assert(wide_scratch_bytes(1) <= wide_b_bytes(1) && wide_scratch_bytes(2) <= wide_b_bytes(2), "the scratch arrays fit a W1' slot");
 
 // p.total_tiles counts tiles of wide_rows(kHalves) rows here and is a multiple of the grid size (the
 // host hands the rest of the batch to the streaming kernel); p.tiles_per_ckpt = ceil(T / rows).
@@ -50,14 +71,16 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
     typedef __attribute__((address_space(1))) const char glb_char;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int kRowsW = wide_rows(kHalves);                   // rows per tile
-    constexpr int kABytes = wide_a_bytes(kHalves), kBHalfBytes = wide_b_bytes(1);
-    constexpr int kAInstr = kABytes / 1024 / kDmaProducers;      // transfers of rows per producer and stage: 16 / 8
-    constexpr int kBInstr = kBHalfBytes / 1024 / kDmaProducers;  // transfers of one column half of W1': 8
+    constexpr int kAStages = wide_a_stages(kHalves), kBStages = wide_b_stages(kHalves);
+    constexpr int kABytes = wide_a_bytes(kHalves), kBBytes = wide_b_bytes(kHalves), kBHalfBytes = wide_b_bytes(1);
+    constexpr int kAInstr = kABytes / 1024 / kWideRowProducers;  // transfers of rows per row producer and stage: 16 / 8
+    constexpr int kBInstr = kBBytes / 1024;                      // transfers of W1' per stage: 16 / 32
     constexpr int kColWaves = 4 * kHalves;                       // consumer waves that share a row: 4 / 8
-    char* ring = smem;
-    float* ss_part = reinterpret_cast<float*>(smem + kWideStages * kWideStageBytes);   // [4][rows]
-    float* z_part = ss_part + 4 * kWideRows;                                           // [kColWaves][rows]
-    float* inv_rms = z_part + 4 * kWideRows;                                           // [rows]
+    static_assert((kAStages - 1) * kAInstr < 64 && (kBStages - 1) * kBInstr < 64, "outstanding transfers of a producer wave");
+    char* a_ring = smem;
+    char* b_ring = smem + kAStages * kABytes;
+    // the scratch arrays of a tile's epilogue, in the W1' slot `slot`
+    auto scratch = [&](int slot) { return reinterpret_cast<float*>(b_ring + slot * kBBytes); };
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nstage = p.d * Storage<DT>::kBytes / kWideTileBytes;      // k-tiles of a row
@@ -70,14 +93,67 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
     auto first_stage = [&](int tile) { return (int)(((unsigned)tile * 5u) % (unsigned)nstage); };
     const size_t ckpt_chunks = (size_t)p.d * kBottleneck / Storage<DT>::kElems;   // of one column half
 
+    if (wave >= kWideConsumers + kWideRowProducers) {
+        // ------------------------------------------------------------------ the W1' producer
+        // Stage s (counted over all tiles of this workgroup) goes to slot s % kBStages, kBStages-1
+        // stages ahead of its use: it is issued at the hand-over of the stage that follows the slot's
+        // previous tenant.  Between two tiles that is after the epilogue, whose scratch arrays sit in
+        // the slot of the tile's last stage.
+        int f_item = 0, f_k = 0, issued = 0;
+        const char* bp = nullptr;
+        int f_rot = 0;
+        auto aim = [&](int tile) {
+            const int c = tile / p.tiles_per_ckpt;
+            bp = reinterpret_cast<const char*>(p.packed + (size_t)c * kHalves * ckpt_chunks) + lane * 16;
+            f_rot = first_stage(tile);
+            f_k = 0;
+        };
+        aim(tile_of(0));
+        bool fetch_done = false;
+        auto issue_next = [&]() {
+            if (fetch_done) return;
+            int ks = f_k + f_rot;
+            ks = ks >= nstage ? ks - nstage : ks;
+            char* dst = b_ring + (issued % kBStages) * kBBytes;
+#pragma unroll
+            for (int hf = 0; hf < kHalves; ++hf)
+#pragma unroll
+                for (int i = 0; i < kBInstr / kHalves; ++i)
+                    __builtin_amdgcn_global_load_lds((glb_char*)(bp + (int64_t)hf * ckpt_chunks * 16 + (int64_t)ks * kBHalfBytes + i * 1024),
+                                                     (lds_char*)(dst + hf * kBHalfBytes + i * 1024), 16, 0, 0);
+            ++issued;
+            if (++f_k == nstage) {
+                if (++f_item < count) aim(tile_of(f_item));
+                else fetch_done = true;
+            }
+        };
+        for (int s = 0; s < kBStages - 1; ++s) issue_next();
+        int handed = 0;
+        for (int it = 0; it < count; ++it) {
+            for (int k = 0; k < nstage; ++k) {
+                // stage `handed` has landed once at most the younger stages' transfers are outstanding
+                if (issued - handed == kBStages - 1)
+                    __builtin_amdgcn_s_waitcnt(vmcnt_imm((kBStages - 2) * kBInstr));
+                else
+                    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                ring_barrier();
+                ++handed;
+                issue_next();
+            }
+            ring_barrier();                        // the four barriers of the consumers' epilogue
+            ring_barrier();
+            ring_barrier();
+            ring_barrier();
+        }
+        return;
+    }
     if (wave >= kWideConsumers) {
-        // ------------------------------------------------------------------ producers
+        // ------------------------------------------------------------------ row producers
         const int pw = wave - kWideConsumers;
-        // rows: one transfer = 8 rows x 128 bytes; lane -> (row within the transfer, LDS chunk slot),
+        // one transfer = 8 rows x 128 bytes; lane -> (row within the transfer, LDS chunk slot),
         // the global chunk is the slot XOR bits 1..3 of the row (what the consumers undo)
         const int rl = lane / kWideChunksPerRow, slot = lane % kWideChunksPerRow;
         const char* gp[kAInstr];
-        const char* bp = nullptr;              // this producer's half of a k-tile's 16 KiB of one column half, stage 0
         int f_rot = 0, f_k = 0, f_item = 0;
         auto aim = [&](int tile) {
             const int c = tile / p.tiles_per_ckpt;
@@ -90,7 +166,6 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
                 r = r < p.T ? r : p.T - 1;                                  // ragged tail: re-read the last row
                 gp[i] = base + (int64_t)r * p.row_stride_bytes + ((slot ^ wide_swizzle(row)) << 4);
             }
-            bp = reinterpret_cast<const char*>(p.packed + (size_t)c * kHalves * ckpt_chunks) + pw * (kBHalfBytes / kDmaProducers) + lane * 16;
             f_rot = first_stage(tile);
             f_k = 0;
         };
@@ -101,37 +176,32 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
             if (fetch_done) return;
             int ks = f_k + f_rot;
             ks = ks >= nstage ? ks - nstage : ks;
-            char* dst = ring + (issued % kWideStages) * kWideStageBytes;
+            char* dst = a_ring + (issued % kAStages) * kABytes;
 #pragma unroll
             for (int i = 0; i < kAInstr; ++i)
                 __builtin_amdgcn_global_load_lds((glb_char*)(gp[i] + (int64_t)ks * kWideTileBytes),
                                                  (lds_char*)(dst + (pw * kAInstr + i) * 1024), 16, 0, kStreamOnce);
-#pragma unroll
-            for (int hf = 0; hf < kHalves; ++hf)
-#pragma unroll
-                for (int i = 0; i < kBInstr; ++i)
-                    __builtin_amdgcn_global_load_lds((glb_char*)(bp + (int64_t)hf * ckpt_chunks * 16 + (int64_t)ks * kBHalfBytes + i * 1024),
-                                                     (lds_char*)(dst + kABytes + hf * kBHalfBytes + (pw * kBInstr + i) * 1024), 16, 0, 0);
             ++issued;
             if (++f_k == nstage) {
                 if (++f_item < count) aim(tile_of(f_item));
                 else fetch_done = true;
             }
         };
-        for (int s = 0; s < kWideStages - 1; ++s) issue_next();
+        for (int s = 0; s < kAStages - 1; ++s) issue_next();
         int handed = 0;
         for (int it = 0; it < count; ++it) {
             for (int k = 0; k < nstage; ++k) {
                 // stage `handed` has landed once at most the younger stages' transfers are outstanding
-                if (issued - handed == kWideStages - 1)
-                    __builtin_amdgcn_s_waitcnt(vmcnt_imm((kWideStages - 2) * kWideInstr));
+                if (issued - handed == kAStages - 1)
+                    __builtin_amdgcn_s_waitcnt(vmcnt_imm((kAStages - 2) * kAInstr));
                 else
                     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
                 ring_barrier();
                 ++handed;
                 issue_next();
             }
-            ring_barrier();                        // the three barriers of the consumers' epilogue
+            ring_barrier();                        // the four barriers of the consumers' epilogue
+            ring_barrier();
             ring_barrier();
             ring_barrier();
         }
@@ -148,7 +218,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
     const int a_row = (128 * rh + r) * kWideTileBytes;
     const int a_swz = wide_swizzle(r);
     // W1' fragment of group g: the packed order, 1 KiB per (group, column block), column halves apart
-    const int b_off = kABytes + half * kBHalfBytes + colblk * 1024 + lane * 16;
+    const int b_off = half * kBHalfBytes + colblk * 1024 + lane * 16;
     const int zrow = 128 * rh;                              // this wave's first row within the tile
     const int zcol = kHalves == 1 ? colblk : wave;          // its slot among the waves that share a row
     constexpr int kGroups = kWideTileBytes / 32;            // 16-k groups per stage: 4
@@ -166,14 +236,15 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
         }
         for (int k = 0; k < nstage; ++k) {
             ring_barrier();
-            const char* st = ring + (stage % kWideStages) * kWideStageBytes;
+            const char* sa = a_ring + (stage % kAStages) * kABytes;
+            const char* sb = b_ring + (stage % kBStages) * kBBytes;
 #pragma unroll
             for (int g = 0; g < kGroups; ++g) {
-                const u32x4 bf = *reinterpret_cast<const u32x4*>(st + b_off + g * 4096);
+                const u32x4 bf = *reinterpret_cast<const u32x4*>(sb + b_off + g * 4096);
                 u32x4 a[4];
 #pragma unroll
                 for (int b = 0; b < 4; ++b)
-                    a[b] = *reinterpret_cast<const u32x4*>(st + a_row + b * 32 * kWideTileBytes + (((2 * g + h) ^ a_swz) << 4));
+                    a[b] = *reinterpret_cast<const u32x4*>(sa + a_row + b * 32 * kWideTileBytes + (((2 * g + h) ^ a_swz) << 4));
 #pragma unroll
                 for (int b = 0; b < 4; ++b) acc[b] = mma_k16<DT>(a[b], bf, acc[b]);
                 if (g == colblk && half == 0) {    // this wave's share of its rows' sums of squares
@@ -184,6 +255,12 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
             ++stage;
         }
 
+        // ---- the epilogue's scratch arrays take the W1' slot of the stage just consumed, once every
+        // consumer is done reading it
+        float* ss_part = scratch((stage - 1) % kBStages);       // [4][rows]
+        float* z_part = ss_part + 4 * kRowsW;                   // [kColWaves][rows]
+        float* inv_rms = z_part + kColWaves * kRowsW;           // [rows]
+        __syncthreads();
         // ---- row sums of squares: lanes l and l^32 hold the two chunk phases; the 4 column waves the rest
         if (half == 0) {
 #pragma unroll
@@ -222,7 +299,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
                                       p.fire_mask ? p.fire_mask + t : nullptr);
             }
         }
-        // the scratch arrays are next written after the first barriers of the next tile's k loop
+        // the slot is refilled (with a stage of the next tile) only after the next tile's first hand-over
     }
 }
 

@@ -215,10 +215,10 @@ template <int DT, int kHalves> int launch_wide(unsigned grid, hipStream_t st, co
     TIDE_HIP(hipGetDevice(&dev));
     if (!raised[dev]) {
         TIDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&tide_prefill_wide_kernel<DT, kHalves>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, kWideLdsBytes));
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, wide_lds_bytes(kHalves)));
         raised[dev] = true;
     }
-    hipLaunchKernelGGL((tide_prefill_wide_kernel<DT, kHalves>), dim3(grid), dim3(kWideThreads), kWideLdsBytes, st, p);
+    hipLaunchKernelGGL((tide_prefill_wide_kernel<DT, kHalves>), dim3(grid), dim3(kWideThreads), wide_lds_bytes(kHalves), st, p);
     return TIDE_OK;
 }
 
