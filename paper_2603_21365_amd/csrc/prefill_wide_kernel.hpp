@@ -7,11 +7,12 @@
 // so does one byte of W1' per hidden byte.  Twice the rows per fetch of W1' halves that second
 // stream.  256 rows of accumulators do not fit one wave, so
 //   - W1' goes through LDS as well: a producer wave transfers the k-tile's fragments (one
-//     contiguous 16 KiB of the packed weights) into LDS, ONCE per workgroup, and
+//     contiguous 16 KiB of the packed weights per column half) into LDS, ONCE per workgroup, and
 //   - 8 consumer waves read them from there: wave cw owns rows 128 (cw / 4) .. +127 and columns
 //     32 (cw % 4) .. +31, four 32x32 accumulator blocks like a consumer of the 128-row kernel.
 // Consumers issue no global loads at all.  A k-tile is 64 elements (128 bytes of a row).
-// Rows and W1' have rings and producer waves of their own (two waves fetch rows, a third W1'):
+// Rows and W1' have rings and producer waves of their own (two waves fetch rows, a third W1';
+// at width 256 one fetches rows and two a column half of W1' each):
 // they come from different distances -- the rows from HBM, W1' from L2 -- and loads return to a
 // wave in issue order, so a wave that fetches both has its quick loads queued behind its slow
 // ones.  Both rings hold three stages, two in flight.  The epilogue's scratch arrays live in the
@@ -27,19 +28,6 @@
 
 namespace tide {
 
-#ifndef TIDE_WIDE_ASTAGES
-#define TIDE_WIDE_ASTAGES 3
-#endif
-#ifndef TIDE_WIDE_BSTAGES
-#define TIDE_WIDE_BSTAGES 3
-#endif
-#ifndef TIDE_WIDE_ASTAGES2
-#define TIDE_WIDE_ASTAGES2 3
-#endif
-#ifndef TIDE_WIDE_BSTAGES2
-#define TIDE_WIDE_BSTAGES2 3
-#endif
-
 // 128 bytes of each row per stage (64 elements).  (64 bytes per stage in a ring twice as deep was
 // measured too: 52 % of HBM peak instead of 68 % -- the row segments become too short.)
 constexpr int kWideTileBytes = 128;
@@ -48,15 +36,18 @@ constexpr int kWideRowsPerTransfer = 64 / kWideChunksPerRow;                 // 
 // bank-conflict-free placement: the chunk slot of a row is its chunk index XOR these bits of the row
 __device__ __forceinline__ int wide_swizzle(int row) { return (row / (16 / kWideChunksPerRow)) & (kWideChunksPerRow - 1); }
 constexpr int kWideConsumers = 8;
-constexpr int kWideRowProducers = 2;                                         // waves that fetch rows
-constexpr int kWideProducers = kWideRowProducers + 1;                        // ... and the one that fetches W1'
+constexpr int kWideProducers = 3;                                            // waves that fetch: 2 rows + 1 W1', or 1 row + 2 W1' (width 256)
+constexpr int wide_row_producers(int kHalves) { return kWideProducers - kHalves; }
 constexpr int kWideThreads = (kWideConsumers + kWideProducers) * kWave;      // 704
 constexpr int kWideRows = 256;                                               // rows per tile at widths 64 / 128
 constexpr int wide_rows(int kHalves) { return kWideRows / kHalves; }         // 256, or 128 at width 256
 constexpr int wide_a_bytes(int kHalves) { return wide_rows(kHalves) * kWideTileBytes; }                 // 32 / 16 KiB of rows per stage
 constexpr int wide_b_bytes(int kHalves) { return kHalves * (kWideTileBytes / 2) * kBottleneck * 2; }    // 16 / 32 KiB of W1' per stage
-constexpr int wide_a_stages(int kHalves) { return kHalves == 1 ? TIDE_WIDE_ASTAGES : TIDE_WIDE_ASTAGES2; }
-constexpr int wide_b_stages(int kHalves) { return kHalves == 1 ? TIDE_WIDE_BSTAGES : TIDE_WIDE_BSTAGES2; }
+// Ring depths, measured: rows 3 / W1' 3 (two stages of each in flight).  Rows 4 / W1' 2 -- all of the
+// LDS, but W1' only one stage ahead -- is 15-20 % slower: a stage is consumed in less time than an L2
+// round trip under load takes.  W1' 4 deep, or rows 4 deep at width 256, change nothing.
+constexpr int wide_a_stages(int) { return 3; }
+constexpr int wide_b_stages(int) { return 3; }
 constexpr int wide_lds_bytes(int kHalves) { return wide_a_stages(kHalves) * wide_a_bytes(kHalves) + wide_b_stages(kHalves) * wide_b_bytes(kHalves); }
 constexpr int wide_scratch_bytes(int kHalves) { return (4 + 4 * kHalves + 1) * wide_rows(kHalves) * (int)sizeof(float); }
 static_assert(wide_lds_bytes(1) <= 160 * 1024 && wide_lds_bytes(2) <= 160 * 1024, "LDS of a CU");
@@ -73,8 +64,9 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
     constexpr int kRowsW = wide_rows(kHalves);                   // rows per tile
     constexpr int kAStages = wide_a_stages(kHalves), kBStages = wide_b_stages(kHalves);
     constexpr int kABytes = wide_a_bytes(kHalves), kBBytes = wide_b_bytes(kHalves), kBHalfBytes = wide_b_bytes(1);
-    constexpr int kAInstr = kABytes / 1024 / kWideRowProducers;  // transfers of rows per row producer and stage: 16 / 8
-    constexpr int kBInstr = kBBytes / 1024;                      // transfers of W1' per stage: 16 / 32
+    constexpr int kRowProducers = wide_row_producers(kHalves);   // 2 / 1; the other producer waves fetch one column half of W1' each
+    constexpr int kAInstr = kABytes / 1024 / kRowProducers;      // transfers of rows per row producer and stage: 16
+    constexpr int kBInstr = kBHalfBytes / 1024;                  // transfers of W1' per W1' producer and stage: 16
     constexpr int kColWaves = 4 * kHalves;                       // consumer waves that share a row: 4 / 8
     static_assert((kAStages - 1) * kAInstr < 64 && (kBStages - 1) * kBInstr < 64, "outstanding transfers of a producer wave");
     char* a_ring = smem;
@@ -93,8 +85,9 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
     auto first_stage = [&](int tile) { return (int)(((unsigned)tile * 5u) % (unsigned)nstage); };
     const size_t ckpt_chunks = (size_t)p.d * kBottleneck / Storage<DT>::kElems;   // of one column half
 
-    if (wave >= kWideConsumers + kWideRowProducers) {
-        // ------------------------------------------------------------------ the W1' producer
+    if (wave >= kWideConsumers + kRowProducers) {
+        // ------------------------------------------------------------------ the W1' producer(s), one per column half
+        const int hf = wave - kWideConsumers - kRowProducers;
         // Stage s (counted over all tiles of this workgroup) goes to slot s % kBStages, kBStages-1
         // stages ahead of its use: it is issued at the hand-over of the stage that follows the slot's
         // previous tenant.  Between two tiles that is after the epilogue, whose scratch arrays sit in
@@ -104,7 +97,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
         int f_rot = 0;
         auto aim = [&](int tile) {
             const int c = tile / p.tiles_per_ckpt;
-            bp = reinterpret_cast<const char*>(p.packed + (size_t)c * kHalves * ckpt_chunks) + lane * 16;
+            bp = reinterpret_cast<const char*>(p.packed + ((size_t)c * kHalves + hf) * ckpt_chunks) + lane * 16;
             f_rot = first_stage(tile);
             f_k = 0;
         };
@@ -116,11 +109,9 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
             ks = ks >= nstage ? ks - nstage : ks;
             char* dst = b_ring + (issued % kBStages) * kBBytes;
 #pragma unroll
-            for (int hf = 0; hf < kHalves; ++hf)
-#pragma unroll
-                for (int i = 0; i < kBInstr / kHalves; ++i)
-                    __builtin_amdgcn_global_load_lds((glb_char*)(bp + (int64_t)hf * ckpt_chunks * 16 + (int64_t)ks * kBHalfBytes + i * 1024),
-                                                     (lds_char*)(dst + hf * kBHalfBytes + i * 1024), 16, 0, 0);
+            for (int i = 0; i < kBInstr; ++i)
+                __builtin_amdgcn_global_load_lds((glb_char*)(bp + (int64_t)ks * kBHalfBytes + i * 1024),
+                                                 (lds_char*)(dst + hf * kBHalfBytes + i * 1024), 16, 0, 0);
             ++issued;
             if (++f_k == nstage) {
                 if (++f_item < count) aim(tile_of(f_item));
