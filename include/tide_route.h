@@ -36,6 +36,9 @@
  *  - The router entry points (raw or packed weights) use a per-device workspace that the
  *    library allocates (hipMalloc) on first use and when a larger problem arrives; calls that
  *    share it on one device must be ordered on one stream.  tide_release() frees it.
+ *    Once the workspace is large enough a call only enqueues kernels, so it can be captured in
+ *    a HIP graph; the graph holds the workspace's addresses, so make one eager call of the
+ *    largest shape first and neither outgrow nor release the workspace while the graph lives.
  *  - Small batches (a decode step, or one checkpoint's call on a few hundred rows) run on kernels
  *    that split each router's contraction over the whole chip: a matrix-core split-k pair for
  *    packed weights of a 16-bit type, an fp32 latency kernel for raw weights up to 8 rows per
