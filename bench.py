@@ -182,7 +182,7 @@ def main() -> int:
     flops = 2.0 * d * 128 * C * T
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "kernel": "tide_prefill_dma_kernel<bf16, 128 rows/workgroup>", "us_per_launch": round(t_launch * 1e6, 2),
+                "kernel": "tide_prefill_tile_kernel<bf16> (one 128-row tile per workgroup)", "us_per_launch": round(t_launch * 1e6, 2),
                 "us_per_launch_spread": spread_pk,
                 "device_copy_gbs": round(copy_gbs, 1), "frac_of_device_copy": round(achieved / copy_gbs, 4),
                 "algorithmic_bytes_per_launch": alg_bytes,

@@ -192,7 +192,8 @@ int tide_set_variant(int variant);
  * 1 / 2 = streaming form with 64 / 128 rows per workgroup, 3 = register-ring form, 4 = wide-tile
  * form (256 rows per workgroup, 16-bit types) for as many whole tiles as there are workgroups,
  * 5 = split-k form (several workgroups share a tile's hidden dimension and a second launch adds
- * their partial results; 16-bit types) with at least two slices.  A form that does
+ * their partial results; 16-bit types) with at least two slices, 6 = one 128-row tile per workgroup
+ * without the persistent schedule (16-bit types, widths 64 / 128).  A form that does
  * not apply to a call (storage type, width, hidden size) falls back to one that does.
  * All forms compute the same function.  Returns the previous setting, or TIDE_ERR_INVALID_ARG. */
 int tide_set_prefill_form(int form);

@@ -1,0 +1,168 @@
+// Prefill kernel, one-tile form: the full-tile path of prefill_dma_kernel.hpp (paper Eq. (2),
+// Sec. 3.4 kernel 1, Fig. 1 inference step 3) and nothing else -- one 128-row tile per
+// workgroup, no persistent schedule, no pieces.
+//
+// Why another form.  When a batch gives every CU one whole tile or none (between half as many
+// tiles as CUs and as many), the streaming kernel's schedule has nothing to decide, but its
+// code for walking tile lists and for 64- and 32-row pieces still costs registers (243 against
+// 139 here) and set-up time: this form is 1-3 % faster on such batches (measured at d = 2048,
+// 4096 and 8192 on the same box; the 8B-shaped prefill of 8 x 4096 rows is one).  Keeping W1' two
+// k-tiles ahead instead of one, or filling all four ring slots at the start, changes nothing.
+// 16-bit storage types, bottleneck widths 64 / 128, d a multiple of 128.
+#pragma once
+#include <type_traits>
+
+#include "device_utils.hpp"
+#include "prefill_dma_kernel.hpp"
+
+namespace tide {
+
+constexpr int kTileRows = 128;
+constexpr int kTileLdsBytes = dma_lds_bytes<kTileRows>();
+
+// blockIdx.x -> tile as in the other forms: XCD x (workgroup id mod 8) takes the x-th eighth of the
+// checkpoint-major tile list from p.tile_begin on, so that an XCD's L2 holds one W1' at a time.
+template <int DT>
+__global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const PrefillParams p) {
+    static_assert(DT != kF32, "16-bit storage types only");
+    typedef __attribute__((address_space(3))) char lds_char;
+    typedef __attribute__((address_space(1))) const char glb_char;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int kBlocks = kTileRows / 32, kRowsM = kTileRows;
+    constexpr int kStageBytes = kRowsM * kTileBytes;
+    constexpr int kInstrPerProducer = kRowsM / 4 / kDmaProducers;   // one transfer = 4 rows x 256 B
+    char* ring = smem;
+    float* ss_part = reinterpret_cast<float*>(smem + kDmaStages * kStageBytes);   // [4][kRowsM]
+    float* z_part = ss_part + kDmaConsumers * kRowsM;                              // [4][kRowsM]
+    float* inv_rms = z_part + kDmaConsumers * kRowsM;                              // [kRowsM]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int per_xcd = (p.total_tiles - p.tile_begin + 7) >> 3;
+    const int tile = p.tile_begin + (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per_xcd || tile >= p.total_tiles) return;
+    const int ntile = p.d * Storage<DT>::kBytes / kTileBytes;
+    // Rows are a power-of-two number of bytes apart and all workgroups start together: each tile
+    // starts its k loop at a different k-tile and wraps (see prefill_kernel.hpp).
+    const int rot = (int)(((unsigned)tile * 5u) % (unsigned)ntile);
+    auto kt_of = [&](int k) { const int x = k + rot; return x >= ntile ? x - ntile : x; };
+    const int c = tile / p.tiles_per_ckpt;
+    const int row0 = (tile - c * p.tiles_per_ckpt) * kRowsM;
+
+    if (wave >= kDmaConsumers) {
+        // ------------------------------------------------------------------ producers
+        const int pw = wave - kDmaConsumers;
+        const int rl = lane >> 4, slot = lane & 15;
+        const char* base = p.hidden + (int64_t)c * p.ckpt_stride_bytes;
+        const char* gp[kInstrPerProducer];
+#pragma unroll
+        for (int i = 0; i < kInstrPerProducer; ++i) {
+            const int row = (pw * kInstrPerProducer + i) * 4 + rl;          // row within the tile
+            int r = row0 + row;
+            r = r < p.T ? r : p.T - 1;                                      // ragged tail: re-read the last row
+            gp[i] = base + (int64_t)r * p.row_stride_bytes + ((slot ^ (row & 15)) << 4);
+        }
+        int issued = 0;
+        auto issue_next = [&]() {
+            if (issued >= ntile) return;
+            char* dst = ring + (issued % kDmaStages) * kStageBytes;
+            const int kt = kt_of(issued);
+#pragma unroll
+            for (int i = 0; i < kInstrPerProducer; ++i)
+                __builtin_amdgcn_global_load_lds((glb_char*)(gp[i] + (int64_t)kt * kTileBytes),
+                                                 (lds_char*)(dst + (pw * kInstrPerProducer + i) * 1024), 16, 0, kStreamOnce);
+            ++issued;
+        };
+        for (int s = 0; s < kDmaStages - 1; ++s) issue_next();
+        for (int k = 0; k < ntile; ++k) {
+            // stage k has landed once only the transfers of the younger stages are outstanding
+            // (every stage is kInstrPerProducer transfers; loads complete in issue order)
+            const int younger = issued - k - 1;
+            if (younger >= 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * kInstrPerProducer));
+            else if (younger == 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kInstrPerProducer));
+            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            ring_barrier();                        // stage k handed over; the slot of stage k-1 is free
+            issue_next();
+        }
+        ring_barrier();                            // the three barriers of the consumers' epilogue
+        ring_barrier();
+        ring_barrier();
+        return;
+    }
+
+    // ---------------------------------------------------------------------- consumers
+    const int r = lane & 31;
+    const int a_base = r * kTileBytes;
+    const int y16 = ((lane >> 5) ^ (r & 15)) << 4;               // see prefill_dma_kernel.hpp
+    const size_t ckpt_chunks = (size_t)p.d * kBottleneck / Storage<DT>::kElems;
+    const u32x4* bptr = p.packed + (size_t)c * ckpt_chunks + wave * 64 + lane;
+    constexpr int kGroups = Compute<DT>::kMmaGroups;             // 8
+    u32x4 breg[kGroups];                                         // W1' fragments, one k-tile ahead
+#pragma unroll
+    for (int g = 0; g < kGroups; ++g) breg[g] = bptr[(size_t)(rot * kGroups + g) * 256];
+    f32x16 acc[kBlocks];
+    float ssq[kBlocks];
+#pragma unroll
+    for (int b = 0; b < kBlocks; ++b) {
+        acc[b] = f32x16{0};
+        ssq[b] = 0.0f;
+    }
+    auto k_tile = [&](const char* st, int kn, auto refill) {
+#pragma unroll
+        for (int g = 0; g < kGroups; ++g) {
+            u32x4 a[kBlocks];
+#pragma unroll
+            for (int b = 0; b < kBlocks; ++b)
+                a[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + (y16 ^ (g << 5)));
+#pragma unroll
+            for (int b = 0; b < kBlocks; ++b) acc[b] = mma_k16<DT>(a[b], breg[g], acc[b]);
+            if ((g & 3) == wave) {                 // this wave's share of the sums of squares
+#pragma unroll
+                for (int b = 0; b < kBlocks; ++b) ssq[b] = chunk_sumsq<DT>(a[b], ssq[b]);
+            }
+            if (decltype(refill)::value) breg[g] = bptr[(size_t)(kn * kGroups + g) * 256];
+        }
+    };
+    for (int k = 0; k + 1 < ntile; ++k) {
+        ring_barrier();
+        k_tile(ring + (k % kDmaStages) * kStageBytes + a_base, kt_of(k + 1), std::true_type{});
+    }
+    ring_barrier();
+    k_tile(ring + ((ntile - 1) % kDmaStages) * kStageBytes + a_base, 0, std::false_type{});
+
+    // ---- row sums of squares: lanes l and l^32 hold the two chunk phases; the 4 waves the rest
+#pragma unroll
+    for (int b = 0; b < kBlocks; ++b) {
+        const float s2 = ssq[b] + __shfl_xor(ssq[b], 32, kWave);
+        if (lane < 32) ss_part[wave * kRowsM + 32 * b + lane] = s2;
+    }
+    __syncthreads();
+    if (tid < kRowsM) {
+        const float ss = (ss_part[tid] + ss_part[kRowsM + tid]) + (ss_part[2 * kRowsM + tid] + ss_part[3 * kRowsM + tid]);
+        inv_rms[tid] = inv_rms_f32(ss, 1.0f / (float)p.d, p.eps);
+    }
+    __syncthreads();
+    {
+        // (columns at and beyond the bottleneck width are zero padding: their w2 is zero)
+        const int col = 32 * wave + (lane & 31);
+        const float b1c = (p.b1 && col < p.b) ? p.b1[c * p.b + col] : 0.0f;
+        const float w2c = col < p.b ? p.w2[c * p.b + col] : 0.0f;
+        router_epilogue<kBlocks>(acc, inv_rms, z_part + wave * kRowsM, b1c, w2c, lane);
+    }
+    __syncthreads();
+    if (tid < kRowsM) {
+        const int t = row0 + tid;
+        if (t < p.T) {
+            const float z = p.tab.b2[c] + ((z_part[tid] + z_part[kRowsM + tid]) + (z_part[2 * kRowsM + tid] + z_part[3 * kRowsM + tid]));
+            const int64_t o = (int64_t)c * p.T + t;
+            const bool f = z > p.tab.thr_logit[c];
+            if (p.logits) p.logits[o] = z;
+            if (p.prob) p.prob[o] = sigmoid_f32(z);
+            if (p.fire) p.fire[o] = f ? 1 : 0;
+            if (p.exit_layer)
+                report_and_select(p.tab, p.C, c, f, p.min_layer, p.no_exit, p.arrive + t, p.exit_layer + t,
+                                  p.fire_mask ? p.fire_mask + t : nullptr);
+        }
+    }
+}
+
+}  // namespace tide

@@ -21,6 +21,7 @@
 #include "prefill_dma_kernel.hpp"
 #include "prefill_kernel.hpp"
 #include "prefill_splitk_kernel.hpp"
+#include "prefill_tile_kernel.hpp"
 #include "prefill_wide_kernel.hpp"
 #include "project_kernel.hpp"
 
@@ -249,6 +250,21 @@ template <int DT, int kBlocks> int launch_splitk(Workspace& ws, int64_t tiles, h
     return TIDE_OK;
 }
 
+// The one-tile kernel: a workgroup per 128-row tile from p.tile_begin on.
+template <int DT> int launch_tile(hipStream_t st, const PrefillParams& p) {
+    static bool raised[kMaxDevices] = {};
+    int dev = 0;
+    TIDE_HIP(hipGetDevice(&dev));
+    if (!raised[dev]) {
+        TIDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&tide_prefill_tile_kernel<DT>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, kTileLdsBytes));
+        raised[dev] = true;
+    }
+    const unsigned grid = 8u * (unsigned)((p.total_tiles - p.tile_begin + 7) / 8);
+    hipLaunchKernelGGL((tide_prefill_tile_kernel<DT>), dim3(grid), dim3(kDmaThreads), kTileLdsBytes, st, p);
+    return TIDE_OK;
+}
+
 // The streaming kernels use more LDS than the default per-kernel limit: raise it once.
 // They are persistent: at most one (128-row) or two (64-row) workgroups per CU, each walking
 // a list of tiles.
@@ -302,7 +318,7 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
     const int64_t tiles128 = C * ((T + 127) / 128);
     int rows_per_wg = (tiles128 <= 80 || tiles128 >= 144) ? 128 : 64;
     if (g_prefill_form == 1) rows_per_wg = 64;
-    if (g_prefill_form == 2) rows_per_wg = 128;
+    if (g_prefill_form == 2 || g_prefill_form == 6) rows_per_wg = 128;
     // fp32 rows are split into bf16 terms before the matrix cores: the register-ring form does
     // that once per workgroup on the way into LDS, the streaming form once per consumer wave,
     // so the ring form is the faster one for fp32 (measured 4.1 vs 3.6 TB/s).
@@ -400,6 +416,16 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
     const unsigned grid = 8u * (unsigned)((p.total_tiles - p.tile_begin + 7) / 8);
     const int ntile = (int)(p.dpad * (int64_t)eb / kTileBytes);
     const bool ragged = p.dpad != p.d;
+    // One whole 128-row tile for every CU or none (more than half as many tiles as CUs, at most as
+    // many): the one-tile kernel, 1-3 % faster than the persistent one on such batches.
+    bool one_tile_each = false;
+    if (!ring_form && !two_halves && dtype != TIDE_F32 && rows_per_wg == 128) {
+        unsigned cus = 0;
+        rc = resident_cus(&cus);
+        if (rc) return rc;
+        const int64_t left = (int64_t)p.total_tiles - p.tile_begin;
+        one_tile_each = g_prefill_form == 6 || (g_prefill_form == 0 && 2 * left > (int64_t)cus && left <= (int64_t)cus);
+    }
     by_dtype(dtype, [&](auto dt) {
         constexpr int DT = decltype(dt)::value;
         if (ring_form && ragged) {
@@ -414,6 +440,8 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
                 hipLaunchKernelGGL((tide_prefill_kernel<DT, 1>), dim3(grid), dim3(kPrefillThreads), 0, st, p);
         } else if (two_halves) {
             rc = launch_dma<DT, 64, 2>(grid, st, p);
+        } else if (rows_per_wg == 128 && one_tile_each) {
+            if constexpr (DT != kF32) rc = launch_tile<DT>(st, p);
         } else if (rows_per_wg == 128) {
             rc = launch_dma<DT, 128, 1>(grid, st, p);
         } else {
@@ -813,7 +841,7 @@ int tide_set_variant(int variant) {
 }
 
 int tide_set_prefill_form(int form) {
-    if (form < 0 || form > 5) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d outside [0, 5]", form);
+    if (form < 0 || form > 6) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d outside [0, 6]", form);
     std::lock_guard<std::mutex> lock(g_mu);
     int prev = g_prefill_form;
     g_prefill_form = form;

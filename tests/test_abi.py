@@ -144,9 +144,9 @@ def test_set_variant_validates():
 
 def test_set_prefill_form_validates():
     prev = tr.set_prefill_form(0)
-    assert prev in (0, 1, 2, 3, 4, 5)
+    assert prev in (0, 1, 2, 3, 4, 5, 6)
     with pytest.raises(tr.TideError):
-        tr.set_prefill_form(6)
+        tr.set_prefill_form(7)
     tr.set_prefill_form(prev)
 
 

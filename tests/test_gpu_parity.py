@@ -107,11 +107,11 @@ def test_config1_full(tr, packed):
     assert st["max_abs_err"] < 1e-2                      # bf16 W1' rounding: well inside the 2e-2 bar
 
 
-@pytest.mark.parametrize("form", [1, 2, 3, 4, 5, 0])
+@pytest.mark.parametrize("form", [1, 2, 3, 4, 5, 6, 0])
 @pytest.mark.parametrize("dtype,T,d", [("bf16", 300, 1024), ("f16", 129, 768), ("f32", 257, 512), ("bf16", 64, 128), ("f16", 1100, 384)])
 def test_every_prefill_form_computes_the_same_function(tr, form, dtype, T, d):
     """Streaming form with 64 / 128 rows per workgroup, the register-ring form, the wide-tile form,
-    the split-k form and the automatic choice, in turn, on ragged token counts and on a hidden
+    the split-k form, the one-tile form and the automatic choice, in turn, on ragged token counts and on a hidden
     size with a single k-tile (forms that do not apply to a case fall back to one that does)."""
     w = synth.Workload(f"form{form}_{dtype}_T{T}_d{d}", 29, dtype, d, 12, 4, T, None)
     rt = w.routers()
@@ -134,6 +134,8 @@ def test_every_prefill_form_computes_the_same_function(tr, form, dtype, T, d):
     (4, "f16", 12, 2048, 512, "wide-tile form: 24 tiles on 24 workgroups, nothing left"),
     (4, "bf16", 20, 16384 + 77, 128, "wide-tile form: 325 tiles, one full round on 256 workgroups, 69 left; single 128-byte k-tile pair"),
     (0, "bf16", 36, 8192, 256, "automatic choice at 288 tiles of 256 rows: one wide round, 32 tiles left"),
+    (6, "bf16", 20, 8155, 256, "one-tile form: 320 tiles of 128 rows, a workgroup each (more than the CUs hold at once); ragged"),
+    (0, "f16", 24, 4000, 384, "automatic choice at 192 tiles of 128 rows: the one-tile form; ragged"),
 ])
 def test_uneven_tile_counts_split_the_last_round(tr, form, dtype, layers, T, d, what):
     """Tile counts that do not divide among the persistent workgroups: the tiles of the last
@@ -179,7 +181,7 @@ def test_split_k_form_for_batches_with_few_tiles(tr, C, dtype, T, d, b, what):
         tr.set_prefill_form(0)
 
 
-@pytest.mark.parametrize("form", [1, 2, 3])
+@pytest.mark.parametrize("form", [1, 2, 3, 6])
 def test_config1_full_in_every_prefill_form(tr, form):
     w = synth.config1()
     tr.set_prefill_form(form)
