@@ -352,6 +352,35 @@ def main() -> int:
         result["per_checkpoint_call"] = {"workload": "one checkpoint (C=1) of the 8B shape: bf16, d=4096, packed weights, "
                                                      "random rows, back-to-back calls on rotating inputs", **per}
 
+        # ---- earliest-exit semantics need fewer rows than the dense call reads: a token's rows beyond its first
+        # firing checkpoint are never needed.  A layer-skipping runtime gets that by calling the router at each
+        # checkpoint on the tokens still running (C = 1, a compacted batch).  The same schedule, back to back:
+        # checkpoint c on T * 0.7^c rows (30 % of the running tokens exit at every checkpoint, as in this
+        # workload); in a model these calls are a layer stack apart, so what matters there is each call's latency.
+        nbytes_pk = tr.packed_router_bytes(tr.BF16, d)
+        sched, rows_sc = [], 0
+        for c in range(C):
+            Tc = max(1, int(round(T * 0.7 ** c)))
+            rows_sc += Tc
+            outc = (torch.empty(Tc, dtype=torch.int32, device="cuda"), torch.empty((1, Tc), dtype=torch.float32, device="cuda"),
+                    torch.empty(Tc, dtype=torch.int32, device="cuda"))
+            sched.append(tr.prepare_select_exit_packed(batches[c % len(batches)][c:c + 1, :Tc], packed[c * nbytes_pk:(c + 1) * nbytes_pk],
+                                                       w.eps, b1[c:c + 1], w2[c:c + 1], rt.b2[c:c + 1], rt.theta[c:c + 1],
+                                                       w.layer_ids[c:c + 1], 0, w.n_layers, d=d, out=outc))
+        def run_schedule(i):
+            for call in sched:
+                call()
+        n_sc = 200
+        _, ev_sc = timed(run_schedule, n_sc, 20)
+        result["short_circuit_schedule"] = {
+            "workload": f"C={C} calls of tide_select_exit_packed with C=1 on T*0.7^c rows (c = 0..{C - 1}), back to back; "
+                        "no compaction pass in the timed region",
+            "us_per_schedule": round(ev_sc / n_sc * 1e6, 2), "rows_evaluated": rows_sc, "rows_dense": C * T,
+            "algorithmic_bytes": rows_sc * d * 2 + C * d * 128 * 2,
+            "tokens_per_s": round(T / (ev_sc / n_sc), 1),
+            "note": "fewer bytes, more launches: on resident data the dense single launch is faster; the schedule is what "
+                    "true layer skipping calls, one call per checkpoint layer"}
+
     # ---- the CPU oracle on the same workload (baseline, not a target)
     if not args.no_cpu_baseline:
         import oracle
