@@ -41,9 +41,9 @@
  *    largest shape first and neither outgrow nor release the workspace while the graph lives.
  *  - Small batches (a decode step, or one checkpoint's call on a few hundred rows) run on kernels
  *    that split each router's contraction over the whole chip: a matrix-core split-k pair for
- *    packed weights of a 16-bit type, an fp32 latency kernel for raw weights up to 8 rows per
- *    checkpoint and for the shapes the pair does not cover up to 32; larger batches on the
- *    streaming kernels.  All of them compute the same function.
+ *    packed weights, an fp32 latency kernel for raw weights up to 8 rows per checkpoint and, up
+ *    to 32, for hidden sizes the pair does not cover; larger batches on the streaming kernels.
+ *    All of them compute the same function.
  */
 #ifndef TIDE_ROUTE_H
 #define TIDE_ROUTE_H
@@ -192,7 +192,7 @@ int tide_set_variant(int variant);
  * 1 / 2 = streaming form with 64 / 128 rows per workgroup, 3 = register-ring form, 4 = wide-tile
  * form (256 rows per workgroup, 16-bit types) for as many whole tiles as there are workgroups,
  * 5 = split-k form (several workgroups share a tile's hidden dimension and a second launch adds
- * their partial results; 16-bit types) with at least two slices, 6 = one 128-row tile per workgroup
+ * their partial results) with at least two slices, 6 = one 128-row tile per workgroup
  * without the persistent schedule (16-bit types, widths 64 / 128).  A form that does
  * not apply to a call (storage type, width, hidden size) falls back to one that does.
  * All forms compute the same function.  Returns the previous setting, or TIDE_ERR_INVALID_ARG. */

@@ -18,8 +18,9 @@
 // 8 slices that alone took longer (24 us a call) than the second launch costs (13 us a call).
 // The price of the form is the partial results -- 16 KiB per workgroup and 32-row block, written
 // once and read once -- which is why it stops where the tiles are many.
-// 16-bit storage types, d a multiple of 128; at bottleneck width 256 each 128-column half of a
-// tile is a workgroup of its own in the first launch.
+// Every storage type (fp32 rows as two bf16 terms, as in the streaming kernel), d a multiple of
+// 128 for 16-bit and of 64 for fp32 rows (whole k-tiles); at bottleneck width 256 each 128-column
+// half of a tile is a workgroup of its own in the first launch.
 #pragma once
 #include <type_traits>
 
@@ -42,14 +43,13 @@ template <int kBlocks> constexpr int splitk_part_floats() { return kBlocks * 32 
 // k-tiles of a row (S <= n, so every slice has at least one).
 template <int DT, int kBlocks>
 __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_splitk_kernel(const PrefillParams p) {
-    static_assert(DT != kF32, "16-bit storage types only");
     typedef __attribute__((address_space(3))) char lds_char;
     typedef __attribute__((address_space(1))) const char glb_char;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int kRowsM = kBlocks * 32;
     constexpr int kStageBytes = kRowsM * kTileBytes;
     constexpr int kInstrPerProducer = kRowsM / 4 / kDmaProducers;   // one transfer = 4 rows x 256 B
-    constexpr int kPre = 2;                                         // k-tiles of W1' a consumer keeps in flight
+    constexpr int kPre = (DT == kF32 && kBlocks == 4) ? 1 : 2;     // k-tiles of W1' a consumer keeps in flight (registers permitting)
     constexpr int kPartFloats = splitk_part_floats<kBlocks>();
     char* ring = smem;
 
@@ -108,15 +108,21 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_splitk_kernel(con
         const int y16 = ((lane >> 5) ^ (r & 15)) << 4;               // see prefill_dma_kernel.hpp
         const size_t ckpt_chunks = (size_t)p.d * kBottleneck / Storage<DT>::kElems;
         const u32x4* bptr = p.packed + ((size_t)c * halves + half) * ckpt_chunks + wave * 64 + lane;
-        constexpr int kGroups = Compute<DT>::kMmaGroups;             // 8
+        constexpr int kGroups = Compute<DT>::kMmaGroups, kPlanes = Compute<DT>::kPlanes;
+        constexpr int kFrags = kGroups * kPlanes;                    // W1' fragments of one k-tile: 8 either way
+        const size_t plane_chunks = (size_t)p.d * 16;                // fp32 rows: the hi and the mid plane of W1'
+        const int yf16 = (((lane >> 5) << 1) ^ (r & 15)) << 4;       // fp32 rows: see prefill_dma_kernel.hpp
+        auto b_fragment = [&](int kt, int g, int pl) { return bptr[pl * plane_chunks + (size_t)(kt * kGroups + g) * 256]; };
         // W1' fragments of kPre k-tiles in flight: with few k-tiles per workgroup nothing else hides
         // the L2 round trip.  Slot j holds k-tile k with k % kPre == j.
-        u32x4 breg[kPre][kGroups];
+        u32x4 breg[kPre][kFrags];                                    // [g * kPlanes + plane]
 #pragma unroll
         for (int j = 0; j < kPre; ++j) {
             const int kt = kt0 + (j < nk ? j : nk - 1);
 #pragma unroll
-            for (int g = 0; g < kGroups; ++g) breg[j][g] = bptr[(size_t)(kt * kGroups + g) * 256];
+            for (int g = 0; g < kGroups; ++g)
+#pragma unroll
+                for (int pl = 0; pl < kPlanes; ++pl) breg[j][g * kPlanes + pl] = b_fragment(kt, g, pl);
         }
         f32x16 acc[kBlocks];
         float ssq[kBlocks];
@@ -125,20 +131,52 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_splitk_kernel(con
             acc[b] = f32x16{0};
             ssq[b] = 0.0f;
         }
-        auto k_tile = [&](const char* st, u32x4 (&bf)[kGroups], int kn, auto refill) {
+        auto k_tile = [&](const char* st, u32x4 (&bf)[kFrags], int kn, auto refill) {
 #pragma unroll
             for (int g = 0; g < kGroups; ++g) {
-                u32x4 a[kBlocks];
+                if constexpr (DT == kF32) {
+                    // 16 k values = chunks 4g+2h and 4g+2h+1 of the row (4 fp32 each), each value split
+                    // into two bf16 terms (device_utils.hpp); three matrix steps per group
+                    u32x4 ah[kBlocks], am[kBlocks];
+                    float sq[kBlocks];
 #pragma unroll
-                for (int b = 0; b < kBlocks; ++b)
-                    a[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + (y16 ^ (g << 5)));
+                    for (int b = 0; b < kBlocks; ++b) {
+                        const char* src = st + b * 32 * kTileBytes;
+                        const u32x4 c0 = *reinterpret_cast<const u32x4*>(src + (yf16 ^ (g << 6)));
+                        const u32x4 c1 = *reinterpret_cast<const u32x4*>(src + (yf16 ^ (g << 6) ^ 16));
+                        float x[8] = {__uint_as_float(c0.x), __uint_as_float(c0.y), __uint_as_float(c0.z), __uint_as_float(c0.w),
+                                      __uint_as_float(c1.x), __uint_as_float(c1.y), __uint_as_float(c1.z), __uint_as_float(c1.w)};
+                        __bf16 hi[8], mid[8];
+                        split_bf16(x, 8, hi, mid);
+                        bf16x8 h8, m8;
 #pragma unroll
-                for (int b = 0; b < kBlocks; ++b) acc[b] = mma_k16<DT>(a[b], bf[g], acc[b]);
-                if ((g & 3) == wave) {             // this wave's share of the sums of squares
+                        for (int e = 0; e < 8; ++e) { h8[e] = hi[e]; m8[e] = mid[e]; }
+                        ah[b] = __builtin_bit_cast(u32x4, h8);
+                        am[b] = __builtin_bit_cast(u32x4, m8);
+                        sq[b] = chunk_sumsq<kF32>(c1, chunk_sumsq<kF32>(c0, 0.0f));
+                    }
 #pragma unroll
-                    for (int b = 0; b < kBlocks; ++b) ssq[b] = chunk_sumsq<DT>(a[b], ssq[b]);
+                    for (int b = 0; b < kBlocks; ++b) acc[b] = mma_k16_split(ah[b], am[b], bf[2 * g], bf[2 * g + 1], acc[b]);
+                    if (g == wave) {                   // this wave's share of the sums of squares
+#pragma unroll
+                        for (int b = 0; b < kBlocks; ++b) ssq[b] += sq[b];
+                    }
+                } else {
+                    u32x4 a[kBlocks];
+#pragma unroll
+                    for (int b = 0; b < kBlocks; ++b)
+                        a[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + (y16 ^ (g << 5)));
+#pragma unroll
+                    for (int b = 0; b < kBlocks; ++b) acc[b] = mma_k16<DT>(a[b], bf[g], acc[b]);
+                    if ((g & 3) == wave) {             // this wave's share of the sums of squares
+#pragma unroll
+                        for (int b = 0; b < kBlocks; ++b) ssq[b] = chunk_sumsq<DT>(a[b], ssq[b]);
+                    }
                 }
-                if (decltype(refill)::value) bf[g] = bptr[(size_t)(kn * kGroups + g) * 256];
+                if (decltype(refill)::value) {
+#pragma unroll
+                    for (int pl = 0; pl < kPlanes; ++pl) bf[g * kPlanes + pl] = b_fragment(kn, g, pl);
+                }
             }
         };
         int k = 0;

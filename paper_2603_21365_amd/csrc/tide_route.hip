@@ -351,9 +351,9 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
     // on how many tiles there are (the partial results: 16 KiB per workgroup and 32-row block), so the
     // choice compares two cost estimates, in microseconds, fitted to measurements on a 256-CU device
     // (d = 1024 ... 8192, 1 ... 128 tiles, widths 128 and 256):
-    //   streaming, few tiles:  5.7 + 0.48 n   (n = k-tiles of a row; width 256: 7.0 + 1.17 n)
+    //   streaming, few tiles:  5.7 + 0.48 n   (n = k-tiles of a row; width 256: 7.0 + 1.17 n; fp32 rows: 5.7 + 0.7 n)
     //   split-k pair:          8.2 + 0.3 (n / S)(rows / 32) + 0.08 (rows / 32) tiles
-    if (!ring_form && dtype != TIDE_F32 && (g_prefill_form == 0 || g_prefill_form == 5)) {
+    if (!generic_d && (g_prefill_form == 0 || g_prefill_form == 5)) {
         const int rows = T <= 32 ? 32 : T <= 64 ? 64 : 128;
         const int halves = halves_of(b);
         const int64_t tpc = (T + rows - 1) / rows, tiles = C * tpc;
@@ -361,7 +361,8 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
         int64_t S = std::min<int64_t>(ntile, kSplitkMaxSlices);
         const double blocks = rows / 32, col_tiles = (double)(tiles * halves);
         const double t_split = 8.2 + 0.3 * (double)((ntile + S - 1) / S) * blocks + 0.08 * blocks * col_tiles;
-        const double t_stream = halves == 1 ? 5.7 + 0.48 * (double)ntile : 7.0 + 1.17 * (double)ntile;
+        const double t_stream = dtype == TIDE_F32 ? 5.7 + 0.7 * (double)ntile      // the register-ring form
+                              : halves == 1 ? 5.7 + 0.48 * (double)ntile : 7.0 + 1.17 * (double)ntile;
         if (g_prefill_form == 5 ? tiles * halves > kSplitkForcedMaxTiles
                                 : (tiles * halves > kSplitkMaxTiles || t_split + 0.3 >= t_stream)) S = 1;
         if (S >= 2) {
@@ -370,9 +371,8 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
             p.k_slices = (int)S;
             by_dtype(dtype, [&](auto dt) {
                 constexpr int DT = decltype(dt)::value;
-                if constexpr (DT != kF32)
-                    rc = rows == 32 ? launch_splitk<DT, 1>(ws, tiles, st, p)
-                       : rows == 64 ? launch_splitk<DT, 2>(ws, tiles, st, p) : launch_splitk<DT, 4>(ws, tiles, st, p);
+                rc = rows == 32 ? launch_splitk<DT, 1>(ws, tiles, st, p)
+                   : rows == 64 ? launch_splitk<DT, 2>(ws, tiles, st, p) : launch_splitk<DT, 4>(ws, tiles, st, p);
                 return 0;
             });
             if (rc) return rc;
@@ -514,15 +514,16 @@ int launch_decode(Workspace& ws, const void* hidden, int dtype, int64_t C, int64
 }
 
 // The latency kernel (fp32 FMAs, raw or packed weights, k split over workgroups) or the prefill path?
-// With packed weights of a 16-bit type the split-k prefill form is the faster one at every T
-// (measured, d = 4096, C = 1 / 8: 9.5 / 10.6 us against 10.8 / 13.9 us at T = 1, 13.5 / 15.9 us at
-// T = 8 and 40 us at T = 32).  With raw weights that form needs the packing pass first (7.5 us at
-// C = 8), so the latency kernel, which reads W1 as it is, keeps T <= 8 (11-15 us against 17 us);
-// it also keeps, up to T = 32, what the split-k form does not cover.
+// With packed weights the split-k prefill form is the faster one at almost every T (measured,
+// d = 4096, C = 1 / 8, fp16: 9.5 / 10.6 us against 10.8 / 13.9 us at T = 1, 13.5 / 15.9 us at T = 8
+// and 40 us at T = 32; fp32 rows: 13.3 / 14.7 us against 11.3 / 14.4 us at T = 1 and 13.6 / 16.4 us at
+// T = 8).  With raw weights that form needs the packing pass first (7.5 us at C = 8), so the latency
+// kernel, which reads W1 as it is, keeps T <= 8 (11-15 us against 17 us); it also keeps, up to
+// T = 32, what the split-k form does not cover (hidden sizes that are not multiples of 128).
 bool use_decode(int64_t T, int dtype, int64_t d, int64_t b, bool packed_given) {
     if (g_variant == TIDE_VARIANT_DECODE) return T <= kDecodeMaxT;
     if (g_variant == TIDE_VARIANT_PREFILL) return false;
-    const bool split_k = dtype != TIDE_F32 && d % 128 == 0 && d >= 256 &&
+    const bool split_k = d % 128 == 0 && d >= 256 &&
                          (g_prefill_form == 0 || g_prefill_form == 5);
     if (!split_k) return T <= kDecodeAutoMaxT;
     return !packed_given && T <= kDecodeRawMaxT;

@@ -164,6 +164,10 @@ def test_uneven_tile_counts_split_the_last_round(tr, form, dtype, layers, T, d, 
     (8, "f16", 8, 4096, 256, "width 256, decode step: each 128-column half of a tile is a workgroup of its own"),
     (2, "bf16", 300, 2048, 256, "width 256: 6 tiles x 2 halves x 8 slices, ragged"),
     (1, "bf16", 1, 8192, 256, "width 256 at the 70B shape, a single row"),
+    (4, "f32", 8, 4096, 128, "fp32 rows (two bf16 terms per value), decode step"),
+    (2, "f32", 700, 1024, 128, "fp32 rows: 12 tiles of 128 rows x 8 slices of 2 k-tiles, ragged"),
+    (3, "f32", 50, 2048, 256, "fp32 rows, width 256, 64-row tiles"),
+    (1, "f32", 300, 256, 64, "fp32 rows, width 64: 3 tiles x 4 slices of one k-tile"),
 ])
 def test_split_k_form_for_batches_with_few_tiles(tr, C, dtype, T, d, b, what):
     """The split-k form (the automatic choice for 16-bit rows and at most 24 tiles; forced here so
@@ -433,9 +437,9 @@ def test_decode_variant_token_counts(tr, T, C, dtype):
 
 
 @pytest.mark.parametrize("T", [1, 2, 7, 8, 9, 31, 32, 33, 63, 64, 65, 127, 129])
-@pytest.mark.parametrize("C,dtype,d", [(1, "f16", 768), (3, "bf16", 256), (8, "bf16", 2048)])
+@pytest.mark.parametrize("C,dtype,d", [(1, "f16", 768), (3, "bf16", 256), (8, "bf16", 2048), (2, "f32", 1024)])
 def test_split_k_pair_on_decode_sized_batches(tr, T, C, dtype, d):
-    """Packed weights of a 16-bit type, automatic choice: tiles of 32, 64 or 128 rows (whatever holds
+    """Packed weights, automatic choice: tiles of 32, 64 or 128 rows (whatever holds
     the T rows of a checkpoint), up to 8 workgroups per tile along the hidden dimension."""
     w = synth.Workload(f"splitk_small_T{T}_C{C}_{dtype}_d{d}", 41, dtype, d, 4 * C, 4, T, None)
     rt = w.routers()
@@ -508,6 +512,20 @@ def test_repeated_and_interleaved_calls_are_deterministic(tr):
         again_a = gpu_select(tr, wa, ra, ha)
         again_b = gpu_select(tr, wb, rb, hb_, variant=tr.VARIANT_PREFILL)
         for x, y in zip(first_a + first_b, again_a + again_b):
+            assert np.array_equal(x, y)
+    # the split-k pair (packed weights) and the latency kernel (raw weights) share one partial-result buffer
+    # in the workspace: alternate them, with different token counts
+    wc = synth.Workload("rep_c", 28, "f16", 2048, 16, 4, 40, None)
+    wd = synth.Workload("rep_d", 29, "f16", 2048, 16, 4, 5, None)
+    hc, hd_ = to_device(wc.hidden(), "f16"), to_device(wd.hidden(), "f16")
+    rc, rd = wc.routers(), wd.routers()
+    first_c = gpu_select(tr, wc, rc, hc, packed=True)
+    first_d = gpu_select(tr, wd, rd, hd_)
+    for i in range(3):
+        again_c = gpu_select(tr, wc, rc, hc, packed=True)
+        again_d = gpu_select(tr, wd, rd, hd_)
+        again_a = gpu_select(tr, wa, ra, ha)
+        for x, y in zip(first_c + first_d + first_a, again_c + again_d + again_a):
             assert np.array_equal(x, y)
     # without the optional outputs the library stages logits in its own workspace
     g, W1, b1, w2 = routers_to_device(ra)
