@@ -36,8 +36,8 @@ struct PrefillParams {
     int b;                     // bottleneck width: 64, 128 or 256 (columns >= b of the last half are zero padding)
     int tiles_per_ckpt;        // ceil(T / rows per tile)
     int total_tiles;           // C * tiles_per_ckpt
-    int tile_begin;            // first tile of the checkpoint-major list this launch covers (the streaming
-                               // kernels: the tiles before it went to the wide-tile kernel), else 0
+    int tile_begin;            // first tile of the checkpoint-major list this launch covers (the tiles before it
+                               // went to a wide-tile kernel), else 0
     float eps;
     int32_t min_layer, no_exit;
     // outputs (each may be null)
@@ -78,9 +78,9 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const 
 
     // XCD-aware tile order: consecutive workgroup ids land on consecutive XCDs, so give XCD x
     // the x-th contiguous slice of the checkpoint-major tile list; its L2 then holds one W1'.
-    const int per_xcd = (p.total_tiles + 7) >> 3;
-    const int work = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (work >= p.total_tiles) return;
+    const int per_xcd = (p.total_tiles - p.tile_begin + 7) >> 3;
+    const int work = p.tile_begin + (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per_xcd || work >= p.total_tiles) return;
     const int c = work / p.tiles_per_ckpt;
     const int tile = work - c * p.tiles_per_ckpt;
     const int row0 = tile * kRows;

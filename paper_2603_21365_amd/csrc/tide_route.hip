@@ -23,6 +23,7 @@
 #include "prefill_splitk_kernel.hpp"
 #include "prefill_tile_kernel.hpp"
 #include "prefill_wide_kernel.hpp"
+#include "prefill_wide32_kernel.hpp"
 #include "project_kernel.hpp"
 
 namespace {
@@ -250,6 +251,20 @@ template <int DT, int kBlocks> int launch_splitk(Workspace& ws, int64_t tiles, h
     return TIDE_OK;
 }
 
+// The wide-tile kernel for fp32 rows: as launch_wide.
+int launch_wide_f32(unsigned grid, hipStream_t st, const PrefillParams& p) {
+    static bool raised[kMaxDevices] = {};
+    int dev = 0;
+    TIDE_HIP(hipGetDevice(&dev));
+    if (!raised[dev]) {
+        TIDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&tide_prefill_wide_f32_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, kWide32LdsBytes));
+        raised[dev] = true;
+    }
+    hipLaunchKernelGGL(tide_prefill_wide_f32_kernel, dim3(grid), dim3(kWideThreads), kWide32LdsBytes, st, p);
+    return TIDE_OK;
+}
+
 // The one-tile kernel: a workgroup per 128-row tile from p.tile_begin on.
 template <int DT> int launch_tile(hipStream_t st, const PrefillParams& p) {
     static bool raised[kMaxDevices] = {};
@@ -321,7 +336,8 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
     if (g_prefill_form == 2 || g_prefill_form == 6) rows_per_wg = 128;
     // fp32 rows are split into bf16 terms before the matrix cores: the register-ring form does
     // that once per workgroup on the way into LDS, the streaming form once per consumer wave,
-    // so the ring form is the faster one for fp32 (measured 4.1 vs 3.6 TB/s).
+    // so of these two the ring form is the faster one for fp32 (measured 4.1 vs 3.6 TB/s); whole rounds
+    // of 256-row tiles go to the fp32 wide-tile kernel further down (4.7 TB/s).
     // Width 256 (two column halves per wave) exists in the streaming form with 64 rows per
     // workgroup only.  With 128 rows the accumulators (256 values per lane) leave room for half a
     // k-tile of W1' in flight, too little to cover the L2 round trip: measured slower.
@@ -411,6 +427,29 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
             p.tiles_per_ckpt = (int)((T + rows_per_wg - 1) / rows_per_wg);
             p.total_tiles = p.C * p.tiles_per_ckpt;
             p.tile_begin = (int)(c0 * p.tiles_per_ckpt + 2 * j0);
+        }
+    }
+    // fp32 rows: whole rounds of 256-row tiles go to the fp32 wide-tile kernel, what is left to the
+    // register-ring kernel (64-row tiles) behind it.
+    if (dtype == TIDE_F32 && !generic_d && !two_halves && (g_prefill_form == 0 || g_prefill_form == 4)) {
+        unsigned cus = 0;
+        rc = resident_cus(&cus);
+        if (rc) return rc;
+        const int64_t tpcw = (T + kWideRows - 1) / kWideRows, tilesw = C * tpcw;
+        unsigned wgrid = cus;
+        if (g_prefill_form == 4 && tilesw < (int64_t)cus) wgrid = (unsigned)(tilesw & ~(int64_t)7);
+        const int64_t wide_tiles = wgrid >= 8 ? tilesw / wgrid * wgrid : 0;
+        if (wide_tiles > 0) {
+            PrefillParams pw = p;
+            pw.tiles_per_ckpt = (int)tpcw;
+            pw.total_tiles = (int)wide_tiles;
+            pw.tile_begin = 0;
+            rc = launch_wide_f32(wgrid, st, pw);
+            if (rc) return rc;
+            TIDE_HIP(hipGetLastError());
+            if (wide_tiles == tilesw) return TIDE_OK;
+            const int64_t c0 = wide_tiles / tpcw, j0 = wide_tiles % tpcw;      // first row left: 256 * j0 of checkpoint c0
+            p.tile_begin = (int)(c0 * p.tiles_per_ckpt + (kWideRows / rows_per_wg) * j0);
         }
     }
     const unsigned grid = 8u * (unsigned)((p.total_tiles - p.tile_begin + 7) / 8);

@@ -134,6 +134,9 @@ def test_every_prefill_form_computes_the_same_function(tr, form, dtype, T, d):
     (4, "f16", 12, 2048, 512, "wide-tile form: 24 tiles on 24 workgroups, nothing left"),
     (4, "bf16", 20, 16384 + 77, 128, "wide-tile form: 325 tiles, one full round on 256 workgroups, 69 left; single 128-byte k-tile pair"),
     (0, "bf16", 36, 8192, 256, "automatic choice at 288 tiles of 256 rows: one wide round, 32 tiles left"),
+    (4, "f32", 12, 1300, 256, "fp32 wide-tile form: 18 tiles of 256 rows, 16 on 16 workgroups, the rest (ragged) to the streaming kernel"),
+    (0, "f32", 36, 8192, 256, "fp32 rows, automatic choice at 288 tiles of 256 rows: one wide round, the rest to the register-ring kernel"),
+    (0, "f32", 20, 16384 + 77, 128, "fp32 rows, 325 tiles: one wide round, 69 left; two k-tiles of the ring kernel, four stages of the wide one"),
     (6, "bf16", 20, 8155, 256, "one-tile form: 320 tiles of 128 rows, a workgroup each (more than the CUs hold at once); ragged"),
     (0, "f16", 24, 4000, 384, "automatic choice at 192 tiles of 128 rows: the one-tile form; ragged"),
 ])
