@@ -55,6 +55,19 @@ struct PrefillParams {
     CheckpointTable tab;
 };
 
+// One router result: logit z of (checkpoint c, token t) -> the optional outputs, and its report on
+// the token's arrival word (Eq. (2)'s sigmoid and threshold; Fig. 1 step 3's earliest exit).
+__device__ __forceinline__ void emit_router_result(const PrefillParams& p, int c, int t, float z) {
+    const int64_t o = (int64_t)c * p.T + t;
+    const bool f = z > p.tab.thr_logit[c];
+    if (p.logits) p.logits[o] = z;
+    if (p.prob) p.prob[o] = sigmoid_f32(z);
+    if (p.fire) p.fire[o] = f ? 1 : 0;
+    if (p.exit_layer)
+        report_and_select(p.tab, p.C, c, f, p.min_layer, p.no_exit, p.arrive + t, p.exit_layer + t,
+                          p.fire_mask ? p.fire_mask + t : nullptr);
+}
+
 constexpr int kPrefillThreads = 256;
 constexpr int kRows = 64;                 // rows per workgroup
 constexpr int kTileBytes = 256;           // bytes of each row per k-tile
@@ -235,14 +248,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const 
         const int t = row0 + tid;
         if (t < p.T) {
             const float z = p.tab.b2[c] + ((z_part[0][tid] + z_part[1][tid]) + (z_part[2][tid] + z_part[3][tid]));
-            const int64_t o = (int64_t)c * p.T + t;
-            const bool f = z > p.tab.thr_logit[c];
-            if (p.logits) p.logits[o] = z;
-            if (p.prob) p.prob[o] = sigmoid_f32(z);
-            if (p.fire) p.fire[o] = f ? 1 : 0;
-            if (p.exit_layer)
-                report_and_select(p.tab, p.C, c, f, p.min_layer, p.no_exit, p.arrive + t, p.exit_layer + t,
-                                  p.fire_mask ? p.fire_mask + t : nullptr);
+            emit_router_result(p, c, t, z);
         }
     }
 }

@@ -284,14 +284,7 @@ __global__ __launch_bounds__(kFinishThreads * kHalves) void tide_splitk_finish_k
             float zsum = (z_part[0][tid] + z_part[1][tid]) + (z_part[2][tid] + z_part[3][tid]);
             if constexpr (kHalves == 2) zsum += (z_part[4][tid] + z_part[5][tid]) + (z_part[6][tid] + z_part[7][tid]);
             const float z = p.tab.b2[c] + zsum;
-            const int64_t o = (int64_t)c * p.T + t;
-            const bool f = z > p.tab.thr_logit[c];
-            if (p.logits) p.logits[o] = z;
-            if (p.prob) p.prob[o] = sigmoid_f32(z);
-            if (p.fire) p.fire[o] = f ? 1 : 0;
-            if (p.exit_layer)
-                report_and_select(p.tab, p.C, c, f, p.min_layer, p.no_exit, p.arrive + t, p.exit_layer + t,
-                                  p.fire_mask ? p.fire_mask + t : nullptr);
+            emit_router_result(p, c, t, z);
         }
     }
 }

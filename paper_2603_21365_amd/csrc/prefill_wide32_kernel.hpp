@@ -214,14 +214,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_f32_kernel(
             const int t = row0 + my_row;
             if (t < p.T) {
                 const float z = p.tab.b2[c] + total;
-                const int64_t o = (int64_t)c * p.T + t;
-                const bool f = z > p.tab.thr_logit[c];
-                if (p.logits) p.logits[o] = z;
-                if (p.prob) p.prob[o] = sigmoid_f32(z);
-                if (p.fire) p.fire[o] = f ? 1 : 0;
-                if (p.exit_layer)
-                    report_and_select(p.tab, p.C, c, f, p.min_layer, p.no_exit, p.arrive + t, p.exit_layer + t,
-                                      p.fire_mask ? p.fire_mask + t : nullptr);
+                emit_router_result(p, c, t, z);
             }
         }
     }
