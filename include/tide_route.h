@@ -198,6 +198,18 @@ int tide_set_variant(int variant);
  * All forms compute the same function.  Returns the previous setting, or TIDE_ERR_INVALID_ARG. */
 int tide_set_prefill_form(int form);
 
+/* The launches a prefill-path call would make for this shape on a device with `cus` compute units
+ * (a positive multiple of 8) under prefill form `form`: host arithmetic only, no GPU needed; for
+ * tests of the tiling (every row of every checkpoint must belong to exactly one tile of exactly one
+ * launch).  out: HOST int32 [2][7], per launch {kernel, rows_per_tile, tiles_per_ckpt, total_tiles,
+ * tile_begin, k_slices, workgroups}: the launch covers tiles tile_begin .. total_tiles-1 of the
+ * checkpoint-major list of tiles of rows_per_tile rows (tiles_per_ckpt per checkpoint, the last one
+ * of a checkpoint possibly ragged).  kernel: 1 split-k pair, 2 wide-tile, 3 wide-tile fp32, 4 one-tile,
+ * 5 / 6 streaming with 128 / 64 rows, 7 register-ring.  Returns the number of launches (1 or 2) or a
+ * negative tide_status_t.  Calls with at most 32 rows per checkpoint may take the latency kernel
+ * instead (see the conventions); this function describes the prefill path only.              */
+int tide_prefill_plan(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int cus, int form, int32_t* out);
+
 /* Free the current device's workspace (synchronises that device).                       */
 int tide_release(void);
 

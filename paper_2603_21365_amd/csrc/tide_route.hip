@@ -281,8 +281,7 @@ template <int DT> int launch_tile(hipStream_t st, const PrefillParams& p) {
 }
 
 // The streaming kernels use more LDS than the default per-kernel limit: raise it once.
-// They are persistent: at most one (128-row) or two (64-row) workgroups per CU, each walking
-// a list of tiles.
+// `grid` is the plan's (persistent workgroups, see plan_prefill).
 template <int DT, int M, int CB> int launch_dma(unsigned grid, hipStream_t st, const PrefillParams& p) {
     static bool raised[kMaxDevices] = {};
     int dev = 0;
@@ -293,17 +292,133 @@ template <int DT, int M, int CB> int launch_dma(unsigned grid, hipStream_t st, c
                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds));
         raised[dev] = true;
     }
-    unsigned cus = 0;
-    int rc_cus = resident_cus(&cus);
-    if (rc_cus) return rc_cus;
-    // (the two-halves kernel needs more than the 168 registers that let three waves share a SIMD)
-    const unsigned resident = cus * ((M == 128 || CB == 2) ? 1u : 2u);
-    if (grid > resident) grid = resident;      // both are multiples of 8
-    // With fewer 128-row tiles than CUs, launch every CU anyway: the schedule then cuts the tiles
-    // into 64- or 32-row pieces, one per workgroup (a workgroup without a piece exits at once).
-    if (M == 128 && CB == 1) grid = resident;
     hipLaunchKernelGGL((tide_prefill_dma_kernel<DT, M, CB>), dim3(grid), dim3(kDmaThreads), lds, st, p);
     return TIDE_OK;
+}
+
+// ---- What a prefill call launches.  Pure host arithmetic (no HIP calls), so that tests can check it
+// for any shape without a GPU (tide_prefill_plan): every row of every checkpoint must fall into
+// exactly one tile of exactly one launch.
+enum PrefillKernel : int {
+    kKernelSplitK = 1,     // prefill_splitk_kernel.hpp: the pair
+    kKernelWide = 2,       // prefill_wide_kernel.hpp (16-bit rows; width 256: 128-row tiles)
+    kKernelWideF32 = 3,    // prefill_wide32_kernel.hpp
+    kKernelTile = 4,       // prefill_tile_kernel.hpp
+    kKernelStream128 = 5,  // prefill_dma_kernel.hpp, 128 rows per workgroup
+    kKernelStream64 = 6,   // prefill_dma_kernel.hpp, 64 rows per workgroup (width 256: both column halves per wave)
+    kKernelRing = 7        // prefill_kernel.hpp
+};
+struct PlannedLaunch {
+    int kernel;            // PrefillKernel
+    int rows_per_tile;
+    int tiles_per_ckpt;    // ceil(T / rows_per_tile)
+    int total_tiles;       // end of the checkpoint-major tile range this launch covers ...
+    int tile_begin;        // ... and its beginning
+    int k_slices;          // split-k form: workgroups per tile and column half; else 1
+    unsigned grid;         // workgroups
+};
+struct PrefillPlan {
+    int count = 0;
+    PlannedLaunch launch[2];
+};
+
+PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, unsigned cus, int form) {
+    PrefillPlan plan;
+    const int64_t eb = (int64_t)elem_bytes(dtype);
+    const int halves = halves_of(b);
+    const bool two_halves = halves == 2;
+    const bool generic_d = d % 128 != 0;           // the fallback: register-ring form, whatever form is forced
+    // Rows per workgroup (streaming form).  128 rows fetch each W1' fragment once per 128 rows and
+    // is the choice whenever the tiles fill most of the chip.  With few tiles it wins again, because
+    // every CU is launched and the tiles are cut into 64- or 32-row pieces (up to 80 tiles of 128
+    // rows: measured against the 64-row kernel on a 256-CU device); in between, 64-row tiles on two
+    // workgroups per CU are faster.  `form` overrides for tests and tuning.
+    const int64_t tiles128 = C * ((T + 127) / 128);
+    int rows_per_wg = (tiles128 <= 80 || tiles128 >= 144) ? 128 : 64;
+    if (form == 1) rows_per_wg = 64;
+    if (form == 2 || form == 6) rows_per_wg = 128;
+    // fp32 rows are split into bf16 terms before the matrix cores: the register-ring form does
+    // that once per workgroup on the way into LDS, the streaming form once per consumer wave,
+    // so of these two the ring form is the faster one for fp32 (measured 4.1 vs 3.6 TB/s); whole rounds
+    // of 256-row tiles go to the fp32 wide-tile kernel further down (4.7 TB/s).
+    // Width 256 (two column halves per wave) exists in the streaming form with 64 rows per
+    // workgroup only.  With 128 rows the accumulators (256 values per lane) leave room for half a
+    // k-tile of W1' in flight, too little to cover the L2 round trip: measured slower.
+    const bool ring_form = generic_d || (!two_halves && (form == 3 || (form == 0 && dtype == TIDE_F32)));
+    if (ring_form) rows_per_wg = kRows;
+    if (two_halves) rows_per_wg = 64;
+    int64_t tiles_per_ckpt = (T + rows_per_wg - 1) / rows_per_wg;
+    int64_t total_tiles = C * tiles_per_ckpt, tile_begin = 0;
+
+    // Split-k form: with few tiles (of 32, 64 or 128 rows, whatever holds a checkpoint's rows), up to
+    // 8 workgroups share a tile's k range and a second launch adds their results.  Whether that beats
+    // the streaming kernel depends on how long a row is (the streaming kernel's dependent chain) and
+    // on how many tiles there are (the partial results: 16 KiB per workgroup and 32-row block), so the
+    // choice compares two cost estimates, in microseconds, fitted to measurements on a 256-CU device
+    // (d = 1024 ... 8192, 1 ... 128 tiles, widths 128 and 256):
+    //   streaming, few tiles:  5.7 + 0.48 n   (n = k-tiles of a row; width 256: 7.0 + 1.17 n; fp32 rows: 5.7 + 0.7 n)
+    //   split-k pair:          8.2 + 0.3 (n / S)(rows / 32) + 0.08 (rows / 32) tiles
+    if (!generic_d && (form == 0 || form == 5)) {
+        const int rows = T <= 32 ? 32 : T <= 64 ? 64 : 128;
+        const int64_t tpc = (T + rows - 1) / rows, tiles = C * tpc;
+        const int64_t ntile = d * eb / kTileBytes;
+        int64_t S = std::min<int64_t>(ntile, kSplitkMaxSlices);
+        const double blocks = rows / 32, col_tiles = (double)(tiles * halves);
+        const double t_split = 8.2 + 0.3 * (double)((ntile + S - 1) / S) * blocks + 0.08 * blocks * col_tiles;
+        const double t_stream = dtype == TIDE_F32 ? 5.7 + 0.7 * (double)ntile      // the register-ring form
+                              : halves == 1 ? 5.7 + 0.48 * (double)ntile : 7.0 + 1.17 * (double)ntile;
+        if (form == 5 ? tiles * halves > kSplitkForcedMaxTiles
+                      : (tiles * halves > kSplitkMaxTiles || t_split + 0.3 >= t_stream)) S = 1;
+        if (S >= 2) {
+            plan.launch[plan.count++] = PlannedLaunch{kKernelSplitK, rows, (int)tpc, (int)tiles, 0, (int)S, (unsigned)(tiles * halves * S)};
+            return plan;
+        }
+    }
+    // Wide-tile forms: whole rounds of wide tiles (256 rows, or 128 rows at width 256; one per CU and
+    // round) go to a wide kernel, what is left of the checkpoint-major row list to a kernel with
+    // smaller tiles behind it on the same stream (the arrival words carry the per-token state across
+    // the two launches): 16-bit rows to the streaming kernel with half as many rows per tile, fp32
+    // rows to the register-ring kernel.
+    const bool wide16 = !ring_form && dtype != TIDE_F32 && (form == 0 || form == 4);
+    const bool wide32 = dtype == TIDE_F32 && !generic_d && !two_halves && (form == 0 || form == 4);
+    if (wide16 || wide32) {
+        const int64_t wrows = two_halves ? kWideRows / 2 : kWideRows;
+        const int64_t tpcw = (T + wrows - 1) / wrows, tilesw = C * tpcw;
+        unsigned wgrid = cus;
+        if (form == 4 && tilesw < (int64_t)cus) wgrid = (unsigned)(tilesw & ~(int64_t)7);
+        const int64_t wide_tiles = wgrid >= 8 ? tilesw / wgrid * wgrid : 0;
+        if (wide_tiles > 0) {
+            plan.launch[plan.count++] = PlannedLaunch{wide16 ? kKernelWide : kKernelWideF32, (int)wrows, (int)tpcw, (int)wide_tiles, 0, 1, wgrid};
+            if (wide_tiles == tilesw) return plan;
+            const int64_t c0 = wide_tiles / tpcw, j0 = wide_tiles % tpcw;      // first row left: wrows * j0 of checkpoint c0
+            if (wide16) rows_per_wg = (int)(wrows / 2);
+            tiles_per_ckpt = (T + rows_per_wg - 1) / rows_per_wg;
+            total_tiles = C * tiles_per_ckpt;
+            tile_begin = c0 * tiles_per_ckpt + (wrows / rows_per_wg) * j0;
+        }
+    }
+    const int64_t left = total_tiles - tile_begin;
+    unsigned grid = 8u * (unsigned)((left + 7) / 8);
+    int kernel = kKernelRing;
+    if (!ring_form) {
+        // One whole 128-row tile for every CU or none (more than half as many tiles as CUs, at most as
+        // many): the one-tile kernel, 1-3 % faster than the persistent one on such batches.
+        const bool one_tile_each = !two_halves && dtype != TIDE_F32 && rows_per_wg == 128 &&
+                                   (form == 6 || (form == 0 && 2 * left > (int64_t)cus && left <= (int64_t)cus));
+        kernel = one_tile_each ? kKernelTile : rows_per_wg == 128 ? kKernelStream128 : kKernelStream64;
+        if (!one_tile_each) {
+            // The streaming kernels are persistent: at most one (128-row; width 256: the two-halves
+            // kernel needs more than the 168 registers that let three waves share a SIMD) or two (64-row)
+            // workgroups per CU, each walking a list of tiles.  With fewer 128-row tiles than CUs every CU
+            // is launched anyway: the schedule then cuts the tiles into 64- or 32-row pieces, one per
+            // workgroup (a workgroup without a piece exits at once).
+            const unsigned resident = cus * ((rows_per_wg == 128 || two_halves) ? 1u : 2u);
+            if (grid > resident) grid = resident;      // both are multiples of 8
+            if (rows_per_wg == 128) grid = resident;
+        }
+    }
+    plan.launch[plan.count++] = PlannedLaunch{kernel, rows_per_wg, (int)tiles_per_ckpt, (int)total_tiles, (int)tile_begin, 1, grid};
+    return plan;
 }
 
 int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int64_t ckpt_stride,
@@ -323,29 +438,6 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
     p.d = (int)d;
     p.dpad = (int)padded_hidden(dtype, d);
     p.b = (int)b;
-    const bool two_halves = halves_of(b) == 2;
-    const bool generic_d = d % 128 != 0;           // the fallback: register-ring form, whatever form is forced
-    // Rows per workgroup (streaming form).  128 rows fetch each W1' fragment once per 128 rows and
-    // is the choice whenever the tiles fill most of the chip.  With few tiles it wins again, because
-    // every CU is launched and the tiles are cut into 64- or 32-row pieces (up to 80 tiles of 128
-    // rows: measured against the 64-row kernel on a 256-CU device); in between, 64-row tiles on two
-    // workgroups per CU are faster.  g_prefill_form overrides for tests and tuning.
-    const int64_t tiles128 = C * ((T + 127) / 128);
-    int rows_per_wg = (tiles128 <= 80 || tiles128 >= 144) ? 128 : 64;
-    if (g_prefill_form == 1) rows_per_wg = 64;
-    if (g_prefill_form == 2 || g_prefill_form == 6) rows_per_wg = 128;
-    // fp32 rows are split into bf16 terms before the matrix cores: the register-ring form does
-    // that once per workgroup on the way into LDS, the streaming form once per consumer wave,
-    // so of these two the ring form is the faster one for fp32 (measured 4.1 vs 3.6 TB/s); whole rounds
-    // of 256-row tiles go to the fp32 wide-tile kernel further down (4.7 TB/s).
-    // Width 256 (two column halves per wave) exists in the streaming form with 64 rows per
-    // workgroup only.  With 128 rows the accumulators (256 values per lane) leave room for half a
-    // k-tile of W1' in flight, too little to cover the L2 round trip: measured slower.
-    const bool ring_form = generic_d || (!two_halves && (g_prefill_form == 3 || (g_prefill_form == 0 && dtype == TIDE_F32)));
-    if (ring_form) rows_per_wg = kRows;
-    if (two_halves) rows_per_wg = 64;
-    p.tiles_per_ckpt = (int)((T + rows_per_wg - 1) / rows_per_wg);
-    p.total_tiles = p.C * p.tiles_per_ckpt;
     p.eps = eps;
     p.min_layer = min_layer;
     p.no_exit = no_exit;
@@ -360,136 +452,60 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
         if (rc0) return rc0;
         p.arrive = (uint64_t*)ws.arrive.ptr;
     }
-    int rc = TIDE_OK;
-    // Split-k form: with few tiles (of 32, 64 or 128 rows, whatever holds a checkpoint's rows), up to
-    // 8 workgroups share a tile's k range and a second launch adds their results.  Whether that beats
-    // the streaming kernel depends on how long a row is (the streaming kernel's dependent chain) and
-    // on how many tiles there are (the partial results: 16 KiB per workgroup and 32-row block), so the
-    // choice compares two cost estimates, in microseconds, fitted to measurements on a 256-CU device
-    // (d = 1024 ... 8192, 1 ... 128 tiles, widths 128 and 256):
-    //   streaming, few tiles:  5.7 + 0.48 n   (n = k-tiles of a row; width 256: 7.0 + 1.17 n; fp32 rows: 5.7 + 0.7 n)
-    //   split-k pair:          8.2 + 0.3 (n / S)(rows / 32) + 0.08 (rows / 32) tiles
-    if (!generic_d && (g_prefill_form == 0 || g_prefill_form == 5)) {
-        const int rows = T <= 32 ? 32 : T <= 64 ? 64 : 128;
-        const int halves = halves_of(b);
-        const int64_t tpc = (T + rows - 1) / rows, tiles = C * tpc;
-        const int64_t ntile = d * (int64_t)eb / kTileBytes;
-        int64_t S = std::min<int64_t>(ntile, kSplitkMaxSlices);
-        const double blocks = rows / 32, col_tiles = (double)(tiles * halves);
-        const double t_split = 8.2 + 0.3 * (double)((ntile + S - 1) / S) * blocks + 0.08 * blocks * col_tiles;
-        const double t_stream = dtype == TIDE_F32 ? 5.7 + 0.7 * (double)ntile      // the register-ring form
-                              : halves == 1 ? 5.7 + 0.48 * (double)ntile : 7.0 + 1.17 * (double)ntile;
-        if (g_prefill_form == 5 ? tiles * halves > kSplitkForcedMaxTiles
-                                : (tiles * halves > kSplitkMaxTiles || t_split + 0.3 >= t_stream)) S = 1;
-        if (S >= 2) {
-            p.tiles_per_ckpt = (int)tpc;
-            p.total_tiles = (int)tiles;
-            p.k_slices = (int)S;
-            by_dtype(dtype, [&](auto dt) {
-                constexpr int DT = decltype(dt)::value;
-                rc = rows == 32 ? launch_splitk<DT, 1>(ws, tiles, st, p)
-                   : rows == 64 ? launch_splitk<DT, 2>(ws, tiles, st, p) : launch_splitk<DT, 4>(ws, tiles, st, p);
-                return 0;
-            });
-            if (rc) return rc;
-            TIDE_HIP(hipGetLastError());
-            return TIDE_OK;
-        }
-    }
-    // Wide-tile form: whole rounds of wide tiles (256 rows, or 128 rows at width 256; one per CU and
-    // round) go to the wide kernel, what is left of the checkpoint-major row list to the streaming
-    // kernel with half as many rows per tile behind it on the same stream (the arrival words carry
-    // the per-token state across the two launches).
-    if (!ring_form && dtype != TIDE_F32 && (g_prefill_form == 0 || g_prefill_form == 4)) {
-        unsigned cus = 0;
-        rc = resident_cus(&cus);
-        if (rc) return rc;
-        const int64_t wrows = two_halves ? kWideRows / 2 : kWideRows;
-        const int64_t tpcw = (T + wrows - 1) / wrows, tilesw = C * tpcw;
-        unsigned wgrid = cus;
-        if (g_prefill_form == 4 && tilesw < (int64_t)cus) wgrid = (unsigned)(tilesw & ~(int64_t)7);
-        const int64_t wide_tiles = wgrid >= 8 ? tilesw / wgrid * wgrid : 0;
-        if (wide_tiles > 0) {
-            PrefillParams pw = p;
-            pw.tiles_per_ckpt = (int)tpcw;
-            pw.total_tiles = (int)wide_tiles;
-            pw.tile_begin = 0;
-            by_dtype(dtype, [&](auto dt) {
-                constexpr int DT = decltype(dt)::value;
-                if constexpr (DT != kF32) rc = two_halves ? launch_wide<DT, 2>(wgrid, st, pw) : launch_wide<DT, 1>(wgrid, st, pw);
-                return 0;
-            });
-            if (rc) return rc;
-            TIDE_HIP(hipGetLastError());
-            if (wide_tiles == tilesw) return TIDE_OK;
-            const int64_t c0 = wide_tiles / tpcw, j0 = wide_tiles % tpcw;      // first row left: wrows * j0 of checkpoint c0
-            rows_per_wg = (int)(wrows / 2);
-            p.tiles_per_ckpt = (int)((T + rows_per_wg - 1) / rows_per_wg);
-            p.total_tiles = p.C * p.tiles_per_ckpt;
-            p.tile_begin = (int)(c0 * p.tiles_per_ckpt + 2 * j0);
-        }
-    }
-    // fp32 rows: whole rounds of 256-row tiles go to the fp32 wide-tile kernel, what is left to the
-    // register-ring kernel (64-row tiles) behind it.
-    if (dtype == TIDE_F32 && !generic_d && !two_halves && (g_prefill_form == 0 || g_prefill_form == 4)) {
-        unsigned cus = 0;
-        rc = resident_cus(&cus);
-        if (rc) return rc;
-        const int64_t tpcw = (T + kWideRows - 1) / kWideRows, tilesw = C * tpcw;
-        unsigned wgrid = cus;
-        if (g_prefill_form == 4 && tilesw < (int64_t)cus) wgrid = (unsigned)(tilesw & ~(int64_t)7);
-        const int64_t wide_tiles = wgrid >= 8 ? tilesw / wgrid * wgrid : 0;
-        if (wide_tiles > 0) {
-            PrefillParams pw = p;
-            pw.tiles_per_ckpt = (int)tpcw;
-            pw.total_tiles = (int)wide_tiles;
-            pw.tile_begin = 0;
-            rc = launch_wide_f32(wgrid, st, pw);
-            if (rc) return rc;
-            TIDE_HIP(hipGetLastError());
-            if (wide_tiles == tilesw) return TIDE_OK;
-            const int64_t c0 = wide_tiles / tpcw, j0 = wide_tiles % tpcw;      // first row left: 256 * j0 of checkpoint c0
-            p.tile_begin = (int)(c0 * p.tiles_per_ckpt + (kWideRows / rows_per_wg) * j0);
-        }
-    }
-    const unsigned grid = 8u * (unsigned)((p.total_tiles - p.tile_begin + 7) / 8);
+    unsigned cus = 0;
+    int rc = resident_cus(&cus);
+    if (rc) return rc;
+    const bool two_halves = halves_of(b) == 2;
     const int ntile = (int)(p.dpad * (int64_t)eb / kTileBytes);
     const bool ragged = p.dpad != p.d;
-    // One whole 128-row tile for every CU or none (more than half as many tiles as CUs, at most as
-    // many): the one-tile kernel, 1-3 % faster than the persistent one on such batches.
-    bool one_tile_each = false;
-    if (!ring_form && !two_halves && dtype != TIDE_F32 && rows_per_wg == 128) {
-        unsigned cus = 0;
-        rc = resident_cus(&cus);
+    const PrefillPlan plan = plan_prefill(dtype, C, T, d, b, cus, g_prefill_form);
+    for (int i = 0; i < plan.count; ++i) {
+        const PlannedLaunch& L = plan.launch[i];
+        p.tiles_per_ckpt = L.tiles_per_ckpt;
+        p.total_tiles = L.total_tiles;
+        p.tile_begin = L.tile_begin;
+        p.k_slices = L.k_slices;
+        by_dtype(dtype, [&](auto dt) {
+            constexpr int DT = decltype(dt)::value;
+            switch (L.kernel) {
+            case kKernelSplitK:
+                rc = L.rows_per_tile == 32 ? launch_splitk<DT, 1>(ws, L.total_tiles, st, p)
+                   : L.rows_per_tile == 64 ? launch_splitk<DT, 2>(ws, L.total_tiles, st, p) : launch_splitk<DT, 4>(ws, L.total_tiles, st, p);
+                break;
+            case kKernelWide:
+                if constexpr (DT != kF32) rc = two_halves ? launch_wide<DT, 2>(L.grid, st, p) : launch_wide<DT, 1>(L.grid, st, p);
+                break;
+            case kKernelWideF32:
+                rc = launch_wide_f32(L.grid, st, p);
+                break;
+            case kKernelTile:
+                if constexpr (DT != kF32) rc = launch_tile<DT>(st, p);
+                break;
+            case kKernelStream128:
+                rc = launch_dma<DT, 128, 1>(L.grid, st, p);
+                break;
+            case kKernelStream64:
+                rc = two_halves ? launch_dma<DT, 64, 2>(L.grid, st, p) : launch_dma<DT, 64, 1>(L.grid, st, p);
+                break;
+            default:
+                if (ragged) {
+                    if (ntile >= kMaxDepth)
+                        hipLaunchKernelGGL((tide_prefill_kernel<DT, kMaxDepth, true>), dim3(L.grid), dim3(kPrefillThreads), 0, st, p);
+                    else
+                        hipLaunchKernelGGL((tide_prefill_kernel<DT, 1, true>), dim3(L.grid), dim3(kPrefillThreads), 0, st, p);
+                } else {
+                    if (ntile >= kMaxDepth)
+                        hipLaunchKernelGGL((tide_prefill_kernel<DT, kMaxDepth>), dim3(L.grid), dim3(kPrefillThreads), 0, st, p);
+                    else
+                        hipLaunchKernelGGL((tide_prefill_kernel<DT, 1>), dim3(L.grid), dim3(kPrefillThreads), 0, st, p);
+                }
+                break;
+            }
+            return 0;
+        });
         if (rc) return rc;
-        const int64_t left = (int64_t)p.total_tiles - p.tile_begin;
-        one_tile_each = g_prefill_form == 6 || (g_prefill_form == 0 && 2 * left > (int64_t)cus && left <= (int64_t)cus);
+        TIDE_HIP(hipGetLastError());
     }
-    by_dtype(dtype, [&](auto dt) {
-        constexpr int DT = decltype(dt)::value;
-        if (ring_form && ragged) {
-            if (ntile >= kMaxDepth)
-                hipLaunchKernelGGL((tide_prefill_kernel<DT, kMaxDepth, true>), dim3(grid), dim3(kPrefillThreads), 0, st, p);
-            else
-                hipLaunchKernelGGL((tide_prefill_kernel<DT, 1, true>), dim3(grid), dim3(kPrefillThreads), 0, st, p);
-        } else if (ring_form) {
-            if (ntile >= kMaxDepth)
-                hipLaunchKernelGGL((tide_prefill_kernel<DT, kMaxDepth>), dim3(grid), dim3(kPrefillThreads), 0, st, p);
-            else
-                hipLaunchKernelGGL((tide_prefill_kernel<DT, 1>), dim3(grid), dim3(kPrefillThreads), 0, st, p);
-        } else if (two_halves) {
-            rc = launch_dma<DT, 64, 2>(grid, st, p);
-        } else if (rows_per_wg == 128 && one_tile_each) {
-            if constexpr (DT != kF32) rc = launch_tile<DT>(st, p);
-        } else if (rows_per_wg == 128) {
-            rc = launch_dma<DT, 128, 1>(grid, st, p);
-        } else {
-            rc = launch_dma<DT, 64, 1>(grid, st, p);
-        }
-        return 0;
-    });
-    if (rc) return rc;
-    TIDE_HIP(hipGetLastError());
     return TIDE_OK;
 }
 
@@ -878,6 +894,23 @@ int tide_set_variant(int variant) {
     int prev = g_variant;
     g_variant = variant;
     return prev;
+}
+
+int tide_prefill_plan(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int cus, int form, int32_t* out) {
+    if (dtype != TIDE_F32 && dtype != TIDE_F16 && dtype != TIDE_BF16) return fail(TIDE_ERR_INVALID_ARG, "dtype %d is not a tide_dtype_t", dtype);
+    if (C < 1 || C > TIDE_MAX_CHECKPOINTS || T < 1 || C * T > (int64_t)1 << 30) return fail(TIDE_ERR_INVALID_ARG, "C = %lld, T = %lld out of range", (long long)C, (long long)T);
+    if (!supported_hidden(dtype, d) || !supported_bottleneck(b) || (d % 128 != 0 && b == 256)) return fail(TIDE_ERR_UNSUPPORTED, "d = %lld, b = %lld unsupported", (long long)d, (long long)b);
+    if (cus < 8 || cus % 8 != 0) return fail(TIDE_ERR_INVALID_ARG, "cus = %d must be a positive multiple of 8", cus);
+    if (form < 0 || form > 6) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d outside [0, 6]", form);
+    if (!out) return fail(TIDE_ERR_INVALID_ARG, "out must not be NULL");
+    const PrefillPlan plan = plan_prefill(dtype, C, T, d, b, (unsigned)cus, form);
+    for (int i = 0; i < plan.count; ++i) {
+        const PlannedLaunch& L = plan.launch[i];
+        int32_t* o = out + 7 * i;
+        o[0] = L.kernel; o[1] = L.rows_per_tile; o[2] = L.tiles_per_ckpt; o[3] = L.total_tiles; o[4] = L.tile_begin; o[5] = L.k_slices;
+        o[6] = (int32_t)L.grid;
+    }
+    return plan.count;
 }
 
 int tide_set_prefill_form(int form) {

@@ -25,7 +25,7 @@ DTYPE_CODES = {"f32": F32, "f16": F16, "bf16": BF16}
 EXPORTS = (
     "tide_version", "tide_last_error", "tide_router_eval", "tide_select_exit",
     "tide_packed_router_bytes", "tide_router_pack", "tide_router_eval_packed",
-    "tide_select_exit_packed", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_batch_compact", "tide_set_variant", "tide_set_prefill_form", "tide_release",
+    "tide_select_exit_packed", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_batch_compact", "tide_set_variant", "tide_set_prefill_form", "tide_prefill_plan", "tide_release",
 )
 
 _lib = None
@@ -63,6 +63,7 @@ def load_library() -> ctypes.CDLL:
     lib.tide_batch_exit.argtypes = [vp, i64, i64, vp, i32, i32, vp, vp, vp, vp]
     lib.tide_set_variant.argtypes = [ci]
     lib.tide_set_prefill_form.argtypes = [ci]
+    lib.tide_prefill_plan.argtypes = [ci, i64, i64, i64, i64, ci, ci, vp]
     for name in ("tide_router_eval", "tide_router_eval_packed", "tide_select_exit", "tide_select_exit_packed",
                  "tide_router_pack", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_batch_compact", "tide_set_variant", "tide_set_prefill_form", "tide_release"):
         getattr(lib, name).restype = ci
@@ -137,6 +138,18 @@ def set_prefill_form(form: int) -> int:
     if prev < 0:
         _check(prev)
     return prev
+
+
+PLAN_FIELDS = ("kernel", "rows_per_tile", "tiles_per_ckpt", "total_tiles", "tile_begin", "k_slices", "workgroups")
+
+
+def prefill_plan(dtype: int, C: int, T: int, d: int, b: int = BOTTLENECK, *, cus: int = 256, form: int = 0) -> list:
+    """The launches a prefill-path call would make (host arithmetic only; no GPU needed): a list of dicts."""
+    out = (ctypes.c_int32 * 14)()
+    n = load_library().tide_prefill_plan(int(dtype), int(C), int(T), int(d), int(b), int(cus), int(form), out)
+    if n < 0:
+        _check(n)
+    return [dict(zip(PLAN_FIELDS, out[7 * i:7 * i + 7])) for i in range(n)]
 
 
 def release() -> None:

@@ -1,0 +1,133 @@
+"""CPU: the host-side tiling of the prefill path (tide_prefill_plan).  Which kernels a call launches,
+with which tile height, over which part of the checkpoint-major tile list, is plain arithmetic on
+(dtype, C, T, d, b, compute units, form); it needs no GPU, and a slip in it would silently skip or
+double-count rows on shapes the GPU parity tests do not happen to visit.  The property that matters:
+every row of every checkpoint belongs to exactly one tile of exactly one launch."""
+import numpy as np
+import pytest
+
+from paper_2603_21365_amd import tide_route as tr
+
+SPLITK, WIDE, WIDE_F32, TILE, STREAM128, STREAM64, RING = 1, 2, 3, 4, 5, 6, 7
+ELEM = {tr.F32: 4, tr.F16: 2, tr.BF16: 2}
+
+
+def covered_rows(plan, C, T):
+    """Row ranges [(checkpoint, first, last+1)] of every tile of every launch."""
+    out = []
+    for L in plan:
+        R, tpc = L["rows_per_tile"], L["tiles_per_ckpt"]
+        assert tpc == -(-T // R), "tiles per checkpoint = ceil(T / rows per tile)"
+        assert 0 <= L["tile_begin"] < L["total_tiles"] <= C * tpc
+        for t in range(L["tile_begin"], L["total_tiles"]):
+            c, j = divmod(t, tpc)
+            out.append((c, j * R, min((j + 1) * R, T)))
+    return out
+
+
+def check_plan(dtype, C, T, d, b, cus, form):
+    plan = tr.prefill_plan(dtype, C, T, d, b, cus=cus, form=form)
+    what = f"dtype={dtype} C={C} T={T} d={d} b={b} cus={cus} form={form}: {plan}"
+    assert 1 <= len(plan) <= 2, what
+    # ---- every row exactly once
+    seen = np.zeros((C, T), np.uint8)
+    for c, lo, hi in covered_rows(plan, C, T):
+        assert lo < hi, what                      # no tile made of padding only
+        seen[c, lo:hi] += 1
+    assert seen.min() == 1 and seen.max() == 1, what
+    assert plan[-1]["total_tiles"] == C * plan[-1]["tiles_per_ckpt"], what   # the last launch runs to the end of the list
+    halves = (b + 127) // 128
+    ntile = d * ELEM[dtype] // 256
+    for i, L in enumerate(plan):
+        k, R, wg = L["kernel"], L["rows_per_tile"], L["workgroups"]
+        assert wg >= 1, what
+        if k == SPLITK:
+            assert len(plan) == 1 and d % 128 == 0, what
+            assert R in (32, 64, 128) and (R == 128 or T <= R) and (R == 32 or T > R // 2), what
+            assert 2 <= L["k_slices"] <= min(8, ntile), what
+            assert wg == L["total_tiles"] * halves * L["k_slices"], what
+        else:
+            assert L["k_slices"] == 1, what
+        if k in (WIDE, WIDE_F32):
+            assert i == 0 and L["tile_begin"] == 0 and d % 128 == 0, what
+            assert R == (128 if halves == 2 else 256), what
+            assert wg % 8 == 0 and wg <= cus and L["total_tiles"] % wg == 0, what   # whole rounds, one slice per XCD
+            assert (dtype == tr.F32) == (k == WIDE_F32), what
+            assert not (k == WIDE_F32 and halves == 2), what
+        if k == TILE:
+            assert R == 128 and dtype != tr.F32 and halves == 1 and d % 128 == 0, what
+            assert wg == 8 * -(-(L["total_tiles"] - L["tile_begin"]) // 8), what
+        if k in (STREAM128, STREAM64):
+            assert R == (128 if k == STREAM128 else 64) and d % 128 == 0, what
+            assert wg % 8 == 0 and wg <= cus * (1 if (R == 128 or halves == 2) else 2), what
+            assert halves == 1 or k == STREAM64, what
+        if k == RING:
+            assert R == 64 and halves == 1, what
+        if d % 128 != 0:
+            assert k == RING and len(plan) == 1, what
+    if len(plan) == 2:
+        assert plan[0]["kernel"] in (WIDE, WIDE_F32) and plan[1]["kernel"] not in (WIDE, WIDE_F32, SPLITK), what
+    return plan
+
+
+SHAPES = [(8, 4096, 4096), (9, 16384, 4096), (10, 16384, 768), (10, 16384, 8192), (1, 1, 4096), (8, 8, 4096), (1, 64, 256),
+          (8, 33, 2048), (3, 1000, 1024), (5, 8155, 256), (12, 16384 + 77, 128), (1, 300000, 128), (32, 513, 512),
+          (7, 2049, 3072), (2, 12345, 5120), (8, 2048, 4096), (8, 3072, 4096), (8, 1536, 4096), (1, 16384, 4096)]
+
+
+@pytest.mark.parametrize("form", [0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("dtype", [tr.BF16, tr.F16, tr.F32])
+def test_every_row_is_in_exactly_one_tile(dtype, form):
+    for C, T, d in SHAPES:
+        for b in (64, 128, 256):
+            for cus in (256, 304, 64, 8):
+                check_plan(dtype, C, T, d, b, cus, form)
+
+
+def test_every_row_is_in_exactly_one_tile_on_random_shapes():
+    rng = np.random.default_rng(0x71DE)
+    for _ in range(3000):
+        dtype = int(rng.choice([tr.BF16, tr.F16, tr.F32]))
+        C = int(rng.integers(1, 33))
+        T = int(rng.choice([rng.integers(1, 70), rng.integers(1, 3000), rng.integers(1, 40000)]))
+        if C * T > 600000:
+            T = 600000 // C
+        d = int(rng.choice([128, 256, 384, 768, 1024, 2048, 2560, 4096, 5120, 8192, 16384]))
+        b = int(rng.choice([64, 128, 256]))
+        cus = int(rng.choice([8, 64, 128, 256, 304]))
+        form = int(rng.integers(0, 7))
+        check_plan(dtype, C, T, d, b, cus, form)
+
+
+def test_generic_hidden_sizes_take_the_register_ring_kernel():
+    for dtype, d in ((tr.BF16, 200), (tr.F16, 72), (tr.F32, 100), (tr.BF16, 4104), (tr.F32, 708)):
+        for form in range(7):
+            for C, T in ((1, 1), (4, 300), (10, 16384)):
+                plan = check_plan(dtype, C, T, d, 128, 256, form)
+                assert [L["kernel"] for L in plan] == [RING]
+
+
+def test_the_choices_on_the_named_workloads():
+    """What the automatic choice is on a 256-CU device for the workloads the measurements quote."""
+    kinds = lambda plan: [(L["kernel"], L["rows_per_tile"]) for L in plan]
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 4096, 4096)) == [(TILE, 128)]                       # one tile per CU
+    assert kinds(tr.prefill_plan(tr.BF16, 9, 16384, 4096)) == [(WIDE, 256), (STREAM128, 128)]    # two wide rounds + the rest
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 8192, 4096)) == [(WIDE, 256)]                        # exactly one wide round
+    assert kinds(tr.prefill_plan(tr.F32, 10, 16384, 4096)) == [(WIDE_F32, 256), (RING, 64)]
+    assert kinds(tr.prefill_plan(tr.F16, 8, 8, 4096)) == [(SPLITK, 32)]                           # a decode step on packed weights
+    assert tr.prefill_plan(tr.F16, 8, 8, 4096)[0]["k_slices"] == 8
+    assert kinds(tr.prefill_plan(tr.BF16, 1, 1024, 4096)) == [(SPLITK, 128)]                      # one checkpoint's call
+    assert kinds(tr.prefill_plan(tr.BF16, 1, 4096, 4096)) == [(STREAM128, 128)]                   # 32 tiles: pieces of the persistent kernel
+    assert kinds(tr.prefill_plan(tr.BF16, 1, 1024, 1024)) == [(STREAM128, 128)]                   # short rows: the chain is short already
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 4096, 4096, 256)) == [(WIDE, 128)]                   # width 256: one round of 128-row tiles
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 2048, 4096)) == [(STREAM64, 64)]                     # 128 tiles of 128 rows: two 64-row workgroups per CU
+
+
+def test_plan_rejects_bad_arguments():
+    bad = [dict(dtype=9), dict(C=0), dict(C=33), dict(T=0), dict(d=100000), dict(d=130), dict(b=96), dict(cus=100), dict(cus=0), dict(form=7),
+           dict(d=200, b=256)]
+    for kw in bad:
+        args = dict(dtype=tr.BF16, C=4, T=100, d=1024, b=128, cus=256, form=0)
+        args.update(kw)
+        with pytest.raises(tr.TideError):
+            tr.prefill_plan(args["dtype"], args["C"], args["T"], args["d"], args["b"], cus=args["cus"], form=args["form"])
