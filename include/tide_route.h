@@ -210,6 +210,16 @@ int tide_set_prefill_form(int form);
  * instead (see the conventions); this function describes the prefill path only.              */
 int tide_prefill_plan(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int cus, int form, int32_t* out);
 
+/* The persistent streaming kernels' schedule, for tests (host arithmetic, no GPU needed; the very
+ * code the kernels run): the work items of workgroup `block` of a launch of `grid` workgroups over
+ * tiles tile_begin .. total_tiles-1 (as in a tide_prefill_plan launch of kernel 5 or 6);
+ * k_tiles = d * sizeof(dtype) / 256.  out: HOST int32 [max_items][3] = {tile, first row within the
+ * tile, rows}: whole tiles, or the 64- / 32-row pieces that the tiles of the last, partly filled
+ * round are cut into.  Returns the number of items (only the first max_items are written) or a
+ * negative tide_status_t.                                                                      */
+int tide_stream_schedule(int rows_per_tile, int64_t b, int64_t k_tiles, int grid, int block, int tile_begin,
+                         int total_tiles, int32_t* out, int max_items);
+
 /* Free the current device's workspace (synchronises that device).                       */
 int tide_release(void);
 

@@ -69,13 +69,15 @@ struct WorkItem {
 template <int kBlocks>
 struct TileWalk {
     int lo, j, g, q, s, count, i;
-    __device__ TileWalk(int tile_begin, int total_tiles, int ntile) {
+    // (host and device: the host side exists so that tests can enumerate the schedule without a GPU)
+    __host__ __device__ TileWalk(int block, int grid, int tile_begin, int total_tiles, int ntile) {
         const int per_xcd = (total_tiles - tile_begin + 7) >> 3;
-        const int xcd = blockIdx.x & 7;
+        const int xcd = block & 7;
         lo = tile_begin + xcd * per_xcd;
-        const int n = max(min(lo + per_xcd, total_tiles) - lo, 0);
-        g = gridDim.x >> 3;
-        j = blockIdx.x >> 3;
+        const int hi = lo + per_xcd < total_tiles ? lo + per_xcd : total_tiles;
+        const int n = hi > lo ? hi - lo : 0;
+        g = grid >> 3;
+        j = block >> 3;
         q = n / g;
         const int r = n - q * g;
         s = 1;
@@ -84,16 +86,16 @@ struct TileWalk {
         count = q + (j < r * s ? 1 : 0);
         i = 0;
     }
-    __device__ bool valid() const { return i < count; }
-    __device__ bool has_more() const { return i + 1 < count; }
-    __device__ void advance() { ++i; }
-    __device__ WorkItem item(int k) const {
+    __host__ __device__ bool valid() const { return i < count; }
+    __host__ __device__ bool has_more() const { return i + 1 < count; }
+    __host__ __device__ void advance() { ++i; }
+    __host__ __device__ WorkItem item(int k) const {
         if (k < q) return WorkItem{lo + j + k * g, 0, kBlocks};
         const int piece = j % s;
         return WorkItem{lo + q * g + j / s, piece * (kBlocks * 32 / s), kBlocks / s};
     }
-    __device__ WorkItem current() const { return item(i); }
-    __device__ WorkItem following() const { return item(i + 1); }
+    __host__ __device__ WorkItem current() const { return item(i); }
+    __host__ __device__ WorkItem following() const { return item(i + 1); }
 };
 
 // kCB = 128-column halves of the bottleneck each consumer wave covers: 1 (width 64 or 128) or 2
@@ -122,7 +124,7 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
     };
 
     // (two column halves: the tiles of the last round are not cut -- passing one k-tile rules it out)
-    TileWalk<kBlocks> walk(p.tile_begin, p.total_tiles, kCB == 1 ? ntile : 1);
+    TileWalk<kBlocks> walk((int)blockIdx.x, (int)gridDim.x, p.tile_begin, p.total_tiles, kCB == 1 ? ntile : 1);
     if (!walk.valid()) return;
 
     if (wave >= kDmaConsumers) {

@@ -913,6 +913,26 @@ int tide_prefill_plan(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int
     return plan.count;
 }
 
+int tide_stream_schedule(int rows_per_tile, int64_t b, int64_t k_tiles, int grid, int block, int tile_begin, int total_tiles,
+                         int32_t* out, int max_items) {
+    if (rows_per_tile != 64 && rows_per_tile != 128) return fail(TIDE_ERR_INVALID_ARG, "rows_per_tile = %d: 64 or 128", rows_per_tile);
+    if (!supported_bottleneck(b) || k_tiles < 1) return fail(TIDE_ERR_INVALID_ARG, "b = %lld, k_tiles = %lld", (long long)b, (long long)k_tiles);
+    if (grid < 8 || grid % 8 != 0 || block < 0 || block >= grid) return fail(TIDE_ERR_INVALID_ARG, "grid = %d (a multiple of 8), block = %d", grid, block);
+    if (tile_begin < 0 || tile_begin > total_tiles || !out || max_items < 0) return fail(TIDE_ERR_INVALID_ARG, "tile range / out");
+    const int ntile = halves_of(b) == 2 ? 1 : (int)k_tiles;          // the two-halves kernel never cuts tiles
+    int n = 0;
+    auto emit = [&](const WorkItem& it) {
+        if (n < max_items) { out[3 * n] = it.tile; out[3 * n + 1] = it.row_off; out[3 * n + 2] = it.blocks * 32; }
+        ++n;
+    };
+    if (rows_per_tile == 128) {
+        for (TileWalk<4> w(block, grid, tile_begin, total_tiles, ntile); w.valid(); w.advance()) emit(w.current());
+    } else {
+        for (TileWalk<2> w(block, grid, tile_begin, total_tiles, ntile); w.valid(); w.advance()) emit(w.current());
+    }
+    return n;
+}
+
 int tide_set_prefill_form(int form) {
     if (form < 0 || form > 6) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d outside [0, 6]", form);
     std::lock_guard<std::mutex> lock(g_mu);

@@ -25,7 +25,7 @@ DTYPE_CODES = {"f32": F32, "f16": F16, "bf16": BF16}
 EXPORTS = (
     "tide_version", "tide_last_error", "tide_router_eval", "tide_select_exit",
     "tide_packed_router_bytes", "tide_router_pack", "tide_router_eval_packed",
-    "tide_select_exit_packed", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_batch_compact", "tide_set_variant", "tide_set_prefill_form", "tide_prefill_plan", "tide_release",
+    "tide_select_exit_packed", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_batch_compact", "tide_set_variant", "tide_set_prefill_form", "tide_prefill_plan", "tide_stream_schedule", "tide_release",
 )
 
 _lib = None
@@ -64,6 +64,7 @@ def load_library() -> ctypes.CDLL:
     lib.tide_set_variant.argtypes = [ci]
     lib.tide_set_prefill_form.argtypes = [ci]
     lib.tide_prefill_plan.argtypes = [ci, i64, i64, i64, i64, ci, ci, vp]
+    lib.tide_stream_schedule.argtypes = [ci, i64, i64, ci, ci, ci, ci, vp, ci]
     for name in ("tide_router_eval", "tide_router_eval_packed", "tide_select_exit", "tide_select_exit_packed",
                  "tide_router_pack", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_batch_compact", "tide_set_variant", "tide_set_prefill_form", "tide_release"):
         getattr(lib, name).restype = ci
@@ -150,6 +151,20 @@ def prefill_plan(dtype: int, C: int, T: int, d: int, b: int = BOTTLENECK, *, cus
     if n < 0:
         _check(n)
     return [dict(zip(PLAN_FIELDS, out[7 * i:7 * i + 7])) for i in range(n)]
+
+
+def stream_schedule(rows_per_tile: int, b: int, k_tiles: int, grid: int, block: int, tile_begin: int, total_tiles: int) -> list:
+    """Work items (tile, first row, rows) of one persistent workgroup of a streaming-kernel launch (host arithmetic)."""
+    cap = 64
+    while True:
+        out = (ctypes.c_int32 * (3 * cap))()
+        n = load_library().tide_stream_schedule(int(rows_per_tile), int(b), int(k_tiles), int(grid), int(block), int(tile_begin),
+                                                int(total_tiles), out, cap)
+        if n < 0:
+            _check(n)
+        if n <= cap:
+            return [tuple(out[3 * i:3 * i + 3]) for i in range(n)]
+        cap = n
 
 
 def release() -> None:

@@ -99,6 +99,44 @@ def test_every_row_is_in_exactly_one_tile_on_random_shapes():
         check_plan(dtype, C, T, d, b, cus, form)
 
 
+def check_schedule(L, b, k_tiles):
+    """Every tile of a streaming-kernel launch is processed exactly once, whole or as pieces that add up."""
+    R, grid, lo, hi = L["rows_per_tile"], L["workgroups"], L["tile_begin"], L["total_tiles"]
+    rows = np.zeros((hi - lo, R), np.uint8)
+    busy = 0
+    for block in range(grid):
+        items = tr.stream_schedule(R, b, k_tiles, grid, block, lo, hi)
+        busy += bool(items)
+        for n, (tile, row_off, nrows) in enumerate(items):
+            assert lo <= tile < hi and nrows in (32, 64, 128) and nrows <= R and row_off % nrows == 0 and row_off + nrows <= R
+            assert nrows == R or (n == len(items) - 1 and b <= 128 and k_tiles % (R // nrows) == 0)   # a piece is a workgroup's last item
+            rows[tile - lo, row_off:row_off + nrows] += 1
+    assert rows.min() == 1 and rows.max() == 1, (L, b, k_tiles)
+    return busy
+
+
+def test_the_persistent_schedule_covers_every_tile_once():
+    """The streaming kernels' own schedule (the code they run, executed on the host), on the launches the
+    plan produces: whole tiles round-robin within an XCD's slice, then the tiles of the last round cut into pieces."""
+    rng = np.random.default_rng(7)
+    cases = [(tr.BF16, 5, 8155, 256, 128, 256, 2), (tr.F16, 3, 16384, 512, 128, 256, 2), (tr.BF16, 7, 8192, 128, 128, 256, 2),
+             (tr.BF16, 3, 16384, 256, 128, 256, 1), (tr.BF16, 1, 4096, 4096, 128, 256, 2), (tr.BF16, 8, 2048, 4096, 128, 256, 0),
+             (tr.BF16, 8, 4096, 4096, 256, 256, 1), (tr.BF16, 9, 16384, 4096, 128, 256, 0), (tr.F32, 3, 16384 - 70, 256, 128, 256, 2)]
+    for _ in range(150):
+        cases.append((int(rng.choice([tr.BF16, tr.F16, tr.F32])), int(rng.integers(1, 13)), int(rng.integers(33, 20000)),
+                      int(rng.choice([128, 256, 384, 1024, 4096])), int(rng.choice([64, 128, 256])), int(rng.choice([8, 64, 256, 304])),
+                      int(rng.choice([0, 1, 2, 4]))))
+    checked = 0
+    for dtype, C, T, d, b, cus, form in cases:
+        for L in tr.prefill_plan(dtype, C, T, d, b, cus=cus, form=form):
+            if L["kernel"] in (STREAM128, STREAM64):
+                busy = check_schedule(L, b, d * ELEM[dtype] // 256)
+                # no workgroup idles while tiles wait (the last XCD's slice of the list may be up to 7 tiles short)
+                assert busy >= min(L["workgroups"], L["total_tiles"] - L["tile_begin"]) - 7
+                checked += 1
+    assert checked > 60
+
+
 def test_generic_hidden_sizes_take_the_register_ring_kernel():
     for dtype, d in ((tr.BF16, 200), (tr.F16, 72), (tr.F32, 100), (tr.BF16, 4104), (tr.F32, 708)):
         for form in range(7):
