@@ -19,8 +19,8 @@
 // The price of the form is the partial results -- 16 KiB per workgroup and 32-row block, written
 // once and read once -- which is why it stops where the tiles are many.
 // Every storage type (fp32 rows as two bf16 terms, as in the streaming kernel), d a multiple of
-// 128 for 16-bit and of 64 for fp32 rows (whole k-tiles); at bottleneck width 256 each 128-column
-// half of a tile is a workgroup of its own in the first launch.
+// 128; at bottleneck width 256 each 128-column half of a tile is a workgroup of its own in the
+// first launch.
 #pragma once
 #include <type_traits>
 
