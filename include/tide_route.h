@@ -193,7 +193,9 @@ int tide_set_variant(int variant);
  * form (256 rows per workgroup, 16-bit types) for as many whole tiles as there are workgroups,
  * 5 = split-k form (several workgroups share a tile's hidden dimension and a second launch adds
  * their partial results) with at least two slices, 6 = one 128-row tile per workgroup
- * without the persistent schedule (16-bit types, widths 64 / 128).  A form that does
+ * without the persistent schedule (16-bit types, widths 64 / 128).  With form 5 the word may also
+ * fix the split-k tile height and slice count: 5 | rows << 8 | slices << 16 with rows in {0, 32, 64,
+ * 128} and slices in {0, 2, 4, 8}, 0 = chosen by the library.  A form that does
  * not apply to a call (storage type, width, hidden size) falls back to one that does.
  * All forms compute the same function.  Returns the previous setting, or TIDE_ERR_INVALID_ARG. */
 int tide_set_prefill_form(int form);

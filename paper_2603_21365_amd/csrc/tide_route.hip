@@ -322,8 +322,9 @@ struct PrefillPlan {
     PlannedLaunch launch[2];
 };
 
-PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, unsigned cus, int form) {
+PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, unsigned cus, int form_word) {
     PrefillPlan plan;
+    const int form = form_word & 0xff, force_rows = (form_word >> 8) & 0xff, force_slices = (form_word >> 16) & 0xff;
     const int64_t eb = (int64_t)elem_bytes(dtype);
     const int halves = halves_of(b);
     const bool two_halves = halves == 2;
@@ -350,27 +351,46 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
     int64_t tiles_per_ckpt = (T + rows_per_wg - 1) / rows_per_wg;
     int64_t total_tiles = C * tiles_per_ckpt, tile_begin = 0;
 
-    // Split-k form: with few tiles (of 32, 64 or 128 rows, whatever holds a checkpoint's rows), up to
-    // 8 workgroups share a tile's k range and a second launch adds their results.  Whether that beats
-    // the streaming kernel depends on how long a row is (the streaming kernel's dependent chain) and
-    // on how many tiles there are (the partial results: 16 KiB per workgroup and 32-row block), so the
-    // choice compares two cost estimates, in microseconds, fitted to measurements on a 256-CU device
-    // (d = 1024 ... 8192, 1 ... 128 tiles, widths 128 and 256):
-    //   streaming, few tiles:  5.7 + 0.48 n   (n = k-tiles of a row; width 256: 7.0 + 1.17 n; fp32 rows: 5.7 + 0.7 n)
-    //   split-k pair:          8.2 + 0.3 (n / S)(rows / 32) + 0.08 (rows / 32) tiles
+    // Split-k form: with few rows, 2, 4 or 8 workgroups share the k range of a tile of 32, 64 or 128
+    // rows and a second launch adds their results.  Which tile height and slice count is best, and
+    // whether the pair beats the streaming kernel at all, depends on how long a row is (a workgroup's
+    // dependent chain of k-tiles, longer per k-tile the taller the tile), on how many workgroups that
+    // makes (beyond one per CU they run in rounds) and on the volume of partial results (16 KiB per
+    // workgroup and 32-row block), so the choice compares cost estimates, in microseconds, fitted to
+    // measurements on a 256-CU device (d = 1024 ... 8192, 32 ... 8192 rows, widths 128 and 256), with
+    // n = k-tiles of a row, B = 32-row blocks per tile, S = slices, R = 32-row blocks of the whole call
+    // (x 2 at width 256), W = workgroups:
+    //   streaming, few tiles:  5.7 + 0.48 n   (width 256: 7.0 + 1.17 n; fp32 rows: 5.7 + 0.7 n)
+    //   split-k pair:          a_B + c_B ceil(n / S) ceil(W / CUs) + (0.011 + 0.009 S) R
+    //                          with (a_B, c_B) = (8.5, 0.50), (8.9, 0.60), (9.6, 0.92) for B = 1, 2, 4
+    // Forced (form 5) the cheapest shape is taken whatever the streaming estimate says, and the form
+    // word may fix the tile height (bits 8-15) and the slice count (bits 16-23).
     if (!generic_d && (form == 0 || form == 5)) {
-        const int rows = T <= 32 ? 32 : T <= 64 ? 64 : 128;
-        const int64_t tpc = (T + rows - 1) / rows, tiles = C * tpc;
         const int64_t ntile = d * eb / kTileBytes;
-        int64_t S = std::min<int64_t>(ntile, kSplitkMaxSlices);
-        const double blocks = rows / 32, col_tiles = (double)(tiles * halves);
-        const double t_split = 8.2 + 0.3 * (double)((ntile + S - 1) / S) * blocks + 0.08 * blocks * col_tiles;
+        const int64_t max_blocks = form == 5 ? (int64_t)kSplitkForcedMaxTiles * 4 : (int64_t)kSplitkMaxTiles * 4;
+        double best = 1e30;
+        int best_rows = 0;
+        int64_t best_S = 0;
+        for (int rows = 32; rows <= 128; rows *= 2) {
+            if (force_rows ? rows != force_rows : (rows > 32 && 2 * T <= rows)) continue;   // never a tile that is mostly padding
+            const int64_t tiles = C * ((T + rows - 1) / rows);
+            const double B = rows / 32, R = (double)(tiles * halves) * B;
+            const double launch_cost = rows == 32 ? 8.5 : rows == 64 ? 8.9 : 9.6, chain_cost = rows == 32 ? 0.50 : rows == 64 ? 0.60 : 0.92;
+            if (tiles * halves * (rows / 32) > max_blocks) continue;
+            for (int64_t s = kSplitkMaxSlices; s >= 2; s /= 2) {
+                const int64_t S = std::min<int64_t>(ntile, s);
+                if (S < 2 || (force_slices && s != force_slices)) continue;
+                const int64_t W = tiles * halves * S;
+                const double t = launch_cost + chain_cost * (double)((ntile + S - 1) / S) * (double)((W + cus - 1) / cus) +
+                                 (0.011 + 0.009 * (double)S) * R;
+                if (t < best) { best = t; best_rows = rows; best_S = S; }
+            }
+        }
         const double t_stream = dtype == TIDE_F32 ? 5.7 + 0.7 * (double)ntile      // the register-ring form
                               : halves == 1 ? 5.7 + 0.48 * (double)ntile : 7.0 + 1.17 * (double)ntile;
-        if (form == 5 ? tiles * halves > kSplitkForcedMaxTiles
-                      : (tiles * halves > kSplitkMaxTiles || t_split + 0.3 >= t_stream)) S = 1;
-        if (S >= 2) {
-            plan.launch[plan.count++] = PlannedLaunch{kKernelSplitK, rows, (int)tpc, (int)tiles, 0, (int)S, (unsigned)(tiles * halves * S)};
+        if (best_rows && (form == 5 || best + 0.3 < t_stream)) {
+            const int64_t tpc = (T + best_rows - 1) / best_rows, tiles = C * tpc;
+            plan.launch[plan.count++] = PlannedLaunch{kKernelSplitK, best_rows, (int)tpc, (int)tiles, 0, (int)best_S, (unsigned)(tiles * halves * best_S)};
             return plan;
         }
     }
@@ -579,7 +599,7 @@ bool use_decode(int64_t T, int dtype, int64_t d, int64_t b, bool packed_given) {
     if (g_variant == TIDE_VARIANT_DECODE) return T <= kDecodeMaxT;
     if (g_variant == TIDE_VARIANT_PREFILL) return false;
     const bool split_k = d % 128 == 0 && d >= 256 &&
-                         (g_prefill_form == 0 || g_prefill_form == 5);
+                         ((g_prefill_form & 0xff) == 0 || (g_prefill_form & 0xff) == 5);
     if (!split_k) return T <= kDecodeAutoMaxT;
     return !packed_given && T <= kDecodeRawMaxT;
 }
@@ -896,12 +916,23 @@ int tide_set_variant(int variant) {
     return prev;
 }
 
+namespace {
+// A prefill form word: the form in bits 0-7; with form 5, optionally a forced split-k tile height
+// (bits 8-15: 0, 32, 64 or 128) and slice count (bits 16-23: 0, 2, 4 or 8).
+bool valid_form_word(int w) {
+    const int form = w & 0xff, rows = (w >> 8) & 0xff, slices = (w >> 16) & 0xff;
+    if (w < 0 || (w >> 24) != 0 || form > 6) return false;
+    if ((rows || slices) && form != 5) return false;
+    return (rows == 0 || rows == 32 || rows == 64 || rows == 128) && (slices == 0 || slices == 2 || slices == 4 || slices == 8);
+}
+}  // namespace
+
 int tide_prefill_plan(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int cus, int form, int32_t* out) {
     if (dtype != TIDE_F32 && dtype != TIDE_F16 && dtype != TIDE_BF16) return fail(TIDE_ERR_INVALID_ARG, "dtype %d is not a tide_dtype_t", dtype);
     if (C < 1 || C > TIDE_MAX_CHECKPOINTS || T < 1 || C * T > (int64_t)1 << 30) return fail(TIDE_ERR_INVALID_ARG, "C = %lld, T = %lld out of range", (long long)C, (long long)T);
     if (!supported_hidden(dtype, d) || !supported_bottleneck(b) || (d % 128 != 0 && b == 256)) return fail(TIDE_ERR_UNSUPPORTED, "d = %lld, b = %lld unsupported", (long long)d, (long long)b);
     if (cus < 8 || cus % 8 != 0) return fail(TIDE_ERR_INVALID_ARG, "cus = %d must be a positive multiple of 8", cus);
-    if (form < 0 || form > 6) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d outside [0, 6]", form);
+    if (!valid_form_word(form)) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d: a form in [0, 6], with form 5 optionally rows << 8 | slices << 16", form);
     if (!out) return fail(TIDE_ERR_INVALID_ARG, "out must not be NULL");
     const PrefillPlan plan = plan_prefill(dtype, C, T, d, b, (unsigned)cus, form);
     for (int i = 0; i < plan.count; ++i) {
@@ -934,7 +965,7 @@ int tide_stream_schedule(int rows_per_tile, int64_t b, int64_t k_tiles, int grid
 }
 
 int tide_set_prefill_form(int form) {
-    if (form < 0 || form > 6) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d outside [0, 6]", form);
+    if (!valid_form_word(form)) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d: a form in [0, 6], with form 5 optionally rows << 8 | slices << 16", form);
     std::lock_guard<std::mutex> lock(g_mu);
     int prev = g_prefill_form;
     g_prefill_form = form;

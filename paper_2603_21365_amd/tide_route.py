@@ -134,6 +134,11 @@ def set_variant(variant: int) -> int:
     return prev
 
 
+def splitk_form(rows: int = 0, slices: int = 0) -> int:
+    """The form word that forces the split-k pair with this tile height (32 / 64 / 128) and slice count (2 / 4 / 8); 0 = the library's choice."""
+    return 5 | int(rows) << 8 | int(slices) << 16
+
+
 def set_prefill_form(form: int) -> int:
     prev = load_library().tide_set_prefill_form(int(form))
     if prev < 0:

@@ -173,17 +173,39 @@ def test_uneven_tile_counts_split_the_last_round(tr, form, dtype, layers, T, d, 
     (1, "f32", 300, 256, 64, "fp32 rows, width 64: 3 tiles x 4 slices of one k-tile"),
 ])
 def test_split_k_form_for_batches_with_few_tiles(tr, C, dtype, T, d, b, what):
-    """The split-k form (the automatic choice for 16-bit rows and at most 24 tiles; forced here so
-    that larger cases run on it too): up to 8 workgroups share a tile's k range, a second launch adds
-    their partial results."""
+    """The split-k form (the automatic choice for calls of few rows; forced here so that larger cases
+    run on it too): up to 8 workgroups share a tile's k range, a second launch adds their partial
+    results.  Each case runs with the smallest tile height that holds a checkpoint's rows and 8 slices
+    (what the descriptions count), then with the shape the library picks itself."""
     w = synth.Workload(f"splitk_{dtype}_C{C}_T{T}_d{d}_b{b}", 37, dtype, d, 4 * C, 4, T, None, b=b)
     say(what)
     rt = w.routers()
     rt.b2[:] = np.linspace(-0.2, 0.2, w.C)
-    tr.set_prefill_form(5)
+    tr.set_prefill_form(tr.splitk_form(32 if T <= 32 else 64 if T <= 64 else 128, 8))
     try:
         run_and_compare(tr, w, w.name, rt=rt, packed=True, variant=tr.VARIANT_PREFILL)
         run_and_compare(tr, w, w.name + "_raw", rt=rt, packed=False, variant=tr.VARIANT_PREFILL)
+        tr.set_prefill_form(5)
+        run_and_compare(tr, w, w.name + "_own_shape", rt=rt, packed=True, variant=tr.VARIANT_PREFILL)
+    finally:
+        tr.set_prefill_form(0)
+
+
+@pytest.mark.parametrize("slices", [2, 4, 8])
+@pytest.mark.parametrize("rows", [32, 64, 128])
+@pytest.mark.parametrize("C,dtype,T,d,b", [(3, "bf16", 333, 1408, 128), (2, "f16", 200, 1024, 256), (2, "f32", 150, 512, 128),
+                                           (1, "bf16", 1100, 4096, 64)])
+def test_split_k_tile_heights_and_slice_counts(tr, rows, slices, C, dtype, T, d, b):
+    """Every tile height x slice count of the split-k pair on calls of several tiles per checkpoint with
+    a ragged last tile: 11 k-tiles (uneven slices), width 256 (two column halves), fp32 rows, width 64."""
+    w = synth.Workload(f"splitk_r{rows}_s{slices}_{dtype}_C{C}_T{T}_d{d}_b{b}", 41, dtype, d, 4 * C, 4, T, None, b=b)
+    plan = tr.prefill_plan(tr.DTYPE_CODES[dtype], C, T, d, b, form=tr.splitk_form(rows, slices))
+    assert [(L["kernel"], L["rows_per_tile"], L["k_slices"]) for L in plan] == [(1, rows, slices)]
+    rt = w.routers()
+    rt.b2[:] = np.linspace(-0.2, 0.2, w.C)
+    tr.set_prefill_form(tr.splitk_form(rows, slices))
+    try:
+        run_and_compare(tr, w, w.name, rt=rt, packed=True, variant=tr.VARIANT_PREFILL)
     finally:
         tr.set_prefill_form(0)
 

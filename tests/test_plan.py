@@ -43,8 +43,8 @@ def check_plan(dtype, C, T, d, b, cus, form):
         assert wg >= 1, what
         if k == SPLITK:
             assert len(plan) == 1 and d % 128 == 0, what
-            assert R in (32, 64, 128) and (R == 128 or T <= R) and (R == 32 or T > R // 2), what
-            assert 2 <= L["k_slices"] <= min(8, ntile), what
+            assert R in (32, 64, 128) and (form >> 8 or R == 32 or T > R // 2), what   # its own choice: never a tile that is mostly padding
+            assert L["k_slices"] in (2, 4, 8, ntile) and 2 <= L["k_slices"] <= min(8, ntile), what
             assert wg == L["total_tiles"] * halves * L["k_slices"], what
         else:
             assert L["k_slices"] == 1, what
@@ -154,11 +154,26 @@ def test_the_choices_on_the_named_workloads():
     assert kinds(tr.prefill_plan(tr.F32, 10, 16384, 4096)) == [(WIDE_F32, 256), (RING, 64)]
     assert kinds(tr.prefill_plan(tr.F16, 8, 8, 4096)) == [(SPLITK, 32)]                           # a decode step on packed weights
     assert tr.prefill_plan(tr.F16, 8, 8, 4096)[0]["k_slices"] == 8
-    assert kinds(tr.prefill_plan(tr.BF16, 1, 1024, 4096)) == [(SPLITK, 128)]                      # one checkpoint's call
-    assert kinds(tr.prefill_plan(tr.BF16, 1, 4096, 4096)) == [(STREAM128, 128)]                   # 32 tiles: pieces of the persistent kernel
+    assert kinds(tr.prefill_plan(tr.BF16, 1, 1024, 4096)) == [(SPLITK, 32)]                       # one checkpoint's call: 32 tiles x 8 slices
+    assert tr.prefill_plan(tr.BF16, 1, 1024, 4096)[0]["workgroups"] == 256
+    p4096 = tr.prefill_plan(tr.BF16, 1, 4096, 4096)[0]                                            # 64 tiles x 4 slices: still one workgroup per CU
+    assert (p4096["kernel"], p4096["rows_per_tile"], p4096["k_slices"], p4096["workgroups"]) == (SPLITK, 64, 4, 256)
+    assert kinds(tr.prefill_plan(tr.BF16, 1, 6144, 4096)) == [(STREAM128, 128)]                   # 48 tiles: pieces of the persistent kernel
     assert kinds(tr.prefill_plan(tr.BF16, 1, 1024, 1024)) == [(STREAM128, 128)]                   # short rows: the chain is short already
     assert kinds(tr.prefill_plan(tr.BF16, 8, 4096, 4096, 256)) == [(WIDE, 128)]                   # width 256: one round of 128-row tiles
     assert kinds(tr.prefill_plan(tr.BF16, 8, 2048, 4096)) == [(STREAM64, 64)]                     # 128 tiles of 128 rows: two 64-row workgroups per CU
+
+
+def test_a_forced_split_k_shape_is_taken_as_given():
+    for dtype, C, T, d, b in ((tr.BF16, 3, 333, 1408, 128), (tr.F16, 2, 200, 1024, 256), (tr.F32, 2, 150, 512, 128), (tr.BF16, 8, 1, 4096, 128)):
+        for rows in (32, 64, 128):
+            for slices in (2, 4, 8):
+                plan = check_plan(dtype, C, T, d, b, 256, tr.splitk_form(rows, slices))
+                assert [(L["kernel"], L["rows_per_tile"], L["k_slices"]) for L in plan] == [(SPLITK, rows, slices)]
+    assert tr.prefill_plan(tr.BF16, 1, 100, 512, form=tr.splitk_form(64, 8))[0]["k_slices"] == 4     # 4 k-tiles: at most 4 slices
+    for word in (2 | 64 << 8, 5 | 48 << 8, 5 | 3 << 16, 5 | 1 << 24, 0 | 8 << 16):
+        with pytest.raises(tr.TideError):
+            tr.prefill_plan(tr.BF16, 1, 100, 512, form=word)
 
 
 def test_plan_rejects_bad_arguments():
