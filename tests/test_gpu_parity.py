@@ -449,6 +449,36 @@ def test_prefill_ragged_tail_and_padded_strides(tr, T, dtype):
                           w.layer_ids, 0, w.n_layers))
 
 
+@pytest.mark.parametrize("rows,slices", [(32, 8), (64, 4), (128, 2)])
+@pytest.mark.parametrize("T,dtype", [(1, "f16"), (97, "bf16"), (300, "f32")])
+def test_split_k_pair_on_padded_strides(tr, rows, slices, T, dtype):
+    """The split-k pair on row and checkpoint strides larger than the data, padding filled with NaN:
+    the clamped re-reads of a ragged tile's missing rows and the partial results of padding rows
+    must not reach any output."""
+    import torch
+    d, C, pad_cols, pad_rows = 1024, 3, 8, 5
+    w = synth.Workload(f"splitk_pad_T{T}_{dtype}_r{rows}_s{slices}", 53, dtype, d, 12, 4, T, None)
+    say(f"{w.name}: row_stride={d + pad_cols}, ckpt_stride=(T+{pad_rows})*row_stride")
+    hb = w.hidden()
+    rt = w.routers()
+    rt.b2[:] = [0.1, -0.1, 0.0]
+    ex_o, z_o, m_o = oracle_select(w, rt, hb)
+    tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[dtype]
+    big = torch.full((C, T + pad_rows, d + pad_cols), float("nan"), dtype=tdt, device="cuda")
+    big[:, :T, :d] = to_device(hb, dtype)
+    g, W1, b1, w2 = routers_to_device(rt)
+    tr.set_variant(tr.VARIANT_PREFILL)
+    tr.set_prefill_form(tr.splitk_form(rows, slices))
+    try:
+        ex, z, m = tr.select_exit(big[:, :T, :], g, w.eps, W1, b1, w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers)
+        torch.cuda.synchronize()
+    finally:
+        tr.set_prefill_form(0)
+        tr.set_variant(tr.VARIANT_AUTO)
+    report(compare_select(w.name, dtype, z.cpu().numpy(), ex.cpu().numpy(), m.cpu().numpy(), z_o, ex_o, m_o, rt.theta,
+                          w.layer_ids, 0, w.n_layers))
+
+
 @pytest.mark.parametrize("T", [1, 2, 7, 8, 9, 33, 64])
 @pytest.mark.parametrize("C,dtype", [(1, "f16"), (3, "bf16"), (8, "f32")])
 def test_decode_variant_token_counts(tr, T, C, dtype):
@@ -464,8 +494,8 @@ def test_decode_variant_token_counts(tr, T, C, dtype):
 @pytest.mark.parametrize("T", [1, 2, 7, 8, 9, 31, 32, 33, 63, 64, 65, 127, 129])
 @pytest.mark.parametrize("C,dtype,d", [(1, "f16", 768), (3, "bf16", 256), (8, "bf16", 2048), (2, "f32", 1024)])
 def test_split_k_pair_on_decode_sized_batches(tr, T, C, dtype, d):
-    """Packed weights, automatic choice: tiles of 32, 64 or 128 rows (whatever holds
-    the T rows of a checkpoint), up to 8 workgroups per tile along the hidden dimension."""
+    """Packed weights, automatic choice: the split-k pair with the tile height and slice count the
+    library picks for the call (short rows may go to the streaming kernel instead)."""
     w = synth.Workload(f"splitk_small_T{T}_C{C}_{dtype}_d{d}", 41, dtype, d, 4 * C, 4, T, None)
     rt = w.routers()
     rt.b2[:] = np.linspace(-0.2, 0.2, C)
