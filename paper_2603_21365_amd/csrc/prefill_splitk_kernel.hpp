@@ -17,7 +17,9 @@
 // from other XCDs within the same launch), 8 bytes at a time past every cache, and at 128 rows and
 // 8 slices that alone took longer (24 us a call) than the second launch costs (13 us a call).
 // The price of the form is the partial results -- 16 KiB per workgroup and 32-row block, written
-// once and read once -- which is why it stops where the tiles are many.
+// once and read once -- which is why it stops where the tiles are many.  Tile height (32, 64 or
+// 128 rows) and S (2, 4 or 8) are the host's choice per call: short tiles and many slices while
+// the workgroups fit the chip once, fewer slices and taller tiles beyond.
 // Every storage type (fp32 rows as two bf16 terms, as in the streaming kernel), d a multiple of
 // 128; at bottleneck width 256 each 128-column half of a tile is a workgroup of its own in the
 // first launch.

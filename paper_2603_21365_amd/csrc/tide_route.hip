@@ -52,8 +52,8 @@ constexpr int kDecodeAutoMaxT = 32;
 constexpr int kDecodeRawMaxT = 8;          // raw weights where the split-k prefill form applies
 constexpr int kDecodeMaxT = 64;
 constexpr int kSplitkMaxSlices = 8;        // workgroups that share a tile's k range in the split-k prefill form
-constexpr int kSplitkMaxTiles = 128;       // most tiles (x column halves) for which that form can be chosen automatically ...
-constexpr int kSplitkForcedMaxTiles = 1024;   // ... and when it is forced (tide_set_prefill_form(5))
+constexpr int kSplitkMaxTiles = 128;       // most 128-row tiles' worth of rows (x column halves) the split-k form is considered for ...
+constexpr int kSplitkForcedMaxTiles = 1024;   // ... and when it is forced (tide_set_prefill_form(5)): bounds the partial results at 512 MiB
 
 struct Buffer {
     void* ptr = nullptr;
