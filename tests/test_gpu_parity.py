@@ -502,6 +502,21 @@ def test_split_k_pair_on_decode_sized_batches(tr, T, C, dtype, d):
     run_and_compare(tr, w, w.name, rt=rt, packed=True)
 
 
+@pytest.mark.parametrize("C,T,dtype,d,b,shape", [
+    (1, 1024, "bf16", 4096, 128, (32, 8)), (1, 2048, "f16", 4096, 128, (32, 4)), (1, 4096, "bf16", 4096, 128, (64, 4)),
+    (8, 400, "bf16", 4096, 128, (64, 4)), (1, 4096, "bf16", 4096, 256, (64, 2)), (1, 2000, "f32", 4096, 128, (64, 8)),
+    (1, 1000, "f16", 8192, 128, (32, 8))])
+def test_one_checkpoint_calls_take_the_shape_the_plan_names(tr, C, T, dtype, d, b, shape):
+    """The calls a serving loop makes at one checkpoint layer (and a small all-checkpoint call), automatic
+    choice on a 256-CU device: the split-k shape (tile height, slices) that the measurements quote, and parity on it."""
+    plan = tr.prefill_plan(tr.DTYPE_CODES[dtype], C, T, d, b)
+    assert [(L["kernel"], L["rows_per_tile"], L["k_slices"]) for L in plan] == [(1,) + shape]
+    w = synth.Workload(f"one_ckpt_C{C}_T{T}_{dtype}_d{d}_b{b}", 59, dtype, d, 4 * C, 4, T, None, b=b)
+    rt = w.routers()
+    rt.b2[:] = np.linspace(-0.2, 0.2, C) if C > 1 else 0.1
+    run_and_compare(tr, w, w.name, rt=rt, packed=True)
+
+
 def test_thresholds_off_and_always_and_min_layer(tr):
     import torch
     w = synth.Workload("theta_edges", 23, "bf16", 1024, 16, 4, 200, None)
