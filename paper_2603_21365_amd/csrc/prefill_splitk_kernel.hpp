@@ -105,6 +105,7 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_splitk_kernel(con
         }
     } else {
         // ------------------------------------------------------------------ consumers
+        const int wave_u = __builtin_amdgcn_readfirstlane(wave);     // uniform: branches on it are scalar
         const int r = lane & 31;
         const int a_base = r * kTileBytes;
         const int y16 = ((lane >> 5) ^ (r & 15)) << 4;               // see prefill_dma_kernel.hpp
@@ -133,7 +134,18 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_splitk_kernel(con
             acc[b] = f32x16{0};
             ssq[b] = 0.0f;
         }
+        // 16-bit rows: the A fragments of a group are read from LDS kAhead groups before its matrix steps
+        // are issued (a wave is alone on its SIMD, so nothing else would cover the LDS round trip, and
+        // the fewer blocks a tile has the fewer matrix steps there are per group to cover it with).
+        // Not at 128 rows: with two k-tiles of W1' in registers there are none left for it.
+        constexpr int kAhead = kBlocks >= 4 ? 0 : kBlocks == 2 ? 2 : 4;
+        auto read_a = [&](const char* st, int g, u32x4* dst) {
+#pragma unroll
+            for (int b = 0; b < kBlocks; ++b)
+                dst[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + (y16 ^ (g << 5)));
+        };
         auto k_tile = [&](const char* st, u32x4 (&bf)[kFrags], int kn, auto refill) {
+            [[maybe_unused]] u32x4 a16[kAhead + 1][kBlocks];
 #pragma unroll
             for (int g = 0; g < kGroups; ++g) {
                 if constexpr (DT == kF32) {
@@ -159,18 +171,18 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_splitk_kernel(con
                     }
 #pragma unroll
                     for (int b = 0; b < kBlocks; ++b) acc[b] = mma_k16_split(ah[b], am[b], bf[2 * g], bf[2 * g + 1], acc[b]);
-                    if (g == wave) {                   // this wave's share of the sums of squares
 #pragma unroll
-                        for (int b = 0; b < kBlocks; ++b) ssq[b] += sq[b];
-                    }
+                    for (int b = 0; b < kBlocks; ++b) ssq[b] += g == wave_u ? sq[b] : 0.0f;   // this wave's share of the sums of squares
                 } else {
-                    u32x4 a[kBlocks];
+                    if (g == 0) {
 #pragma unroll
-                    for (int b = 0; b < kBlocks; ++b)
-                        a[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + (y16 ^ (g << 5)));
+                        for (int j = 0; j < kAhead; ++j) read_a(st, j, a16[j]);
+                    }
+                    u32x4* a = a16[g % (kAhead + 1)];
+                    if (g + kAhead < kGroups) read_a(st, g + kAhead, a16[(g + kAhead) % (kAhead + 1)]);
 #pragma unroll
                     for (int b = 0; b < kBlocks; ++b) acc[b] = mma_k16<DT>(a[b], bf[g], acc[b]);
-                    if ((g & 3) == wave) {             // this wave's share of the sums of squares
+                    if ((g & 3) == wave_u) {           // this wave's share of the sums of squares
 #pragma unroll
                         for (int b = 0; b < kBlocks; ++b) ssq[b] = chunk_sumsq<DT>(a[b], ssq[b]);
                     }

@@ -90,6 +90,7 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
     }
 
     // ---------------------------------------------------------------------- consumers
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);     // uniform: branches on it are scalar
     const int r = lane & 31;
     const int a_base = r * kTileBytes;
     const int y16 = ((lane >> 5) ^ (r & 15)) << 4;               // see prefill_dma_kernel.hpp
@@ -106,18 +107,25 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
         acc[b] = f32x16{0};
         ssq[b] = 0.0f;
     }
+    // The A fragments of group g+1 are read from LDS before the matrix steps of group g are issued:
+    // a wave is alone on its SIMD, so nothing else would cover the LDS round trip of each group.
     auto k_tile = [&](const char* st, int kn, auto refill) {
-#pragma unroll
-        for (int g = 0; g < kGroups; ++g) {
-            u32x4 a[kBlocks];
+        u32x4 a[2][kBlocks];
+        auto read_a = [&](int g, u32x4* dst) {
 #pragma unroll
             for (int b = 0; b < kBlocks; ++b)
-                a[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + (y16 ^ (g << 5)));
+                dst[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + (y16 ^ (g << 5)));
+        };
+        read_a(0, a[0]);
 #pragma unroll
-            for (int b = 0; b < kBlocks; ++b) acc[b] = mma_k16<DT>(a[b], breg[g], acc[b]);
-            if ((g & 3) == wave) {                 // this wave's share of the sums of squares
+        for (int g = 0; g < kGroups; ++g) {
+            u32x4* cur = a[g & 1];
+            if (g + 1 < kGroups) read_a(g + 1, a[(g + 1) & 1]);      // (two groups ahead: measured, no further gain)
 #pragma unroll
-                for (int b = 0; b < kBlocks; ++b) ssq[b] = chunk_sumsq<DT>(a[b], ssq[b]);
+            for (int b = 0; b < kBlocks; ++b) acc[b] = mma_k16<DT>(cur[b], breg[g], acc[b]);
+            if ((g & 3) == wave_u) {               // this wave's share of the sums of squares
+#pragma unroll
+                for (int b = 0; b < kBlocks; ++b) ssq[b] = chunk_sumsq<DT>(cur[b], ssq[b]);
             }
             if (decltype(refill)::value) breg[g] = bptr[(size_t)(kn * kGroups + g) * 256];
         }

@@ -203,6 +203,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
     // wave cw: column block cw % 4; cw / 4 is the row half (widths 64 / 128) or the column half (width 256)
     const int colblk = wave & 3, hi = wave >> 2;
     const int rh = kHalves == 1 ? hi : 0, half = kHalves == 1 ? 0 : hi;
+    const int colblk_u = __builtin_amdgcn_readfirstlane(colblk), half_u = __builtin_amdgcn_readfirstlane(half);   // uniform: scalar branches
     const int r = lane & 31, h = lane >> 5;
     // A fragment of block b, group g: row 128 rh + 32 b + r, chunk 2g + h, stored at chunk slot
     // (2g + h) XOR ((r >> 1) & 7) of its 128-byte row
@@ -229,18 +230,25 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
             ring_barrier();
             const char* sa = a_ring + (stage % kAStages) * kABytes;
             const char* sb = b_ring + (stage % kBStages) * kBBytes;
-#pragma unroll
-            for (int g = 0; g < kGroups; ++g) {
-                const u32x4 bf = *reinterpret_cast<const u32x4*>(sb + b_off + g * 4096);
-                u32x4 a[4];
+            // the fragments of group g+1 are read before the matrix steps of group g are issued: the
+            // LDS round trip of a group is longer than the other wave of the SIMD keeps the matrix core busy
+            u32x4 a[2][4], bf[2];
+            auto read_group = [&](int g, u32x4* ad, u32x4& bd) {
+                bd = *reinterpret_cast<const u32x4*>(sb + b_off + g * 4096);
 #pragma unroll
                 for (int b = 0; b < 4; ++b)
-                    a[b] = *reinterpret_cast<const u32x4*>(sa + a_row + b * 32 * kWideTileBytes + (((2 * g + h) ^ a_swz) << 4));
+                    ad[b] = *reinterpret_cast<const u32x4*>(sa + a_row + b * 32 * kWideTileBytes + (((2 * g + h) ^ a_swz) << 4));
+            };
+            read_group(0, a[0], bf[0]);
 #pragma unroll
-                for (int b = 0; b < 4; ++b) acc[b] = mma_k16<DT>(a[b], bf, acc[b]);
-                if (g == colblk && half == 0) {    // this wave's share of its rows' sums of squares
+            for (int g = 0; g < kGroups; ++g) {
+                const u32x4* cur = a[g & 1];
+                if (g + 1 < kGroups) read_group(g + 1, a[(g + 1) & 1], bf[(g + 1) & 1]);
 #pragma unroll
-                    for (int b = 0; b < 4; ++b) ssq[b] = chunk_sumsq<DT>(a[b], ssq[b]);
+                for (int b = 0; b < 4; ++b) acc[b] = mma_k16<DT>(cur[b], bf[g & 1], acc[b]);
+                if (g == colblk_u && half_u == 0) {    // this wave's share of its rows' sums of squares
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) ssq[b] = chunk_sumsq<DT>(cur[b], ssq[b]);
                 }
             }
             ++stage;
