@@ -67,8 +67,9 @@ struct Workspace {
 std::mutex g_mu;
 Workspace g_ws[kMaxDevices];
 int g_variant = TIDE_VARIANT_AUTO;
-int g_prefill_form = 0;   // 0 auto; 1 / 2: streaming form with 64 / 128 rows per workgroup; 3: register-ring form;
-                          // 4: wide-tile form (256 rows) wherever it applies, on as many workgroups as there are whole tiles
+int g_prefill_form = 0;   // a form word (see valid_form_word): 0 auto; 1 / 2: streaming form with 64 / 128 rows per workgroup;
+                          // 3: register-ring form; 4: wide-tile form wherever it applies, on as many workgroups as there are
+                          // whole tiles; 5: split-k pair (optionally with a forced shape); 6: one-tile form
 
 // Grow-only device buffer.  Re-allocation frees the old block, which waits for the device.
 int reserve(Buffer& b, size_t bytes, bool zero) {
