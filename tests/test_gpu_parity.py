@@ -517,6 +517,16 @@ def test_one_checkpoint_calls_take_the_shape_the_plan_names(tr, C, T, dtype, d, 
     run_and_compare(tr, w, w.name, rt=rt, packed=True)
 
 
+@pytest.mark.parametrize("T", [64, 256, 16384])
+def test_one_checkpoint_calls_at_the_other_measured_sizes(tr, T):
+    """The remaining sizes of the one-checkpoint measurements (C = 1, bf16, d = 4096, packed weights, automatic
+    choice): 32-row split-k tiles at 64 and 256 rows, the 64-row streaming kernel at 16384."""
+    w = synth.Workload(f"one_ckpt_T{T}", 61, "bf16", 4096, 4, 4, T, None)
+    rt = w.routers()
+    rt.b2[:] = -0.1
+    run_and_compare(tr, w, w.name, rt=rt, packed=True)
+
+
 def test_thresholds_off_and_always_and_min_layer(tr):
     import torch
     w = synth.Workload("theta_edges", 23, "bf16", 1024, 16, 4, 200, None)
