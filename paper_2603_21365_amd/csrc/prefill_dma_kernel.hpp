@@ -331,6 +331,28 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
 #pragma unroll
                         for (int b = 0; b < kActive; ++b) ssq[b] = chunk_sumsq<DT>(a[b], ssq[b]);
                     }
+                } else if constexpr (kBlocks == 2) {
+                    // 64-row kernel: the next group's fragments are read before this group's (one or two)
+                    // matrix instructions are issued, as in the pieces of the 128-row kernel above
+                    if (g == 0) {
+#pragma unroll
+                        for (int b = 0; b < kActive; ++b)
+                            a_pipe[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + y16);
+                    }
+                    u32x4 a[kActive];
+#pragma unroll
+                    for (int b = 0; b < kActive; ++b) a[b] = a_pipe[b];
+                    if (g + 1 < kMmaGroups) {
+#pragma unroll
+                        for (int b = 0; b < kActive; ++b)
+                            a_pipe[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + (y16 ^ ((g + 1) << 5)));
+                    }
+#pragma unroll
+                    for (int b = 0; b < kActive; ++b) acc[b] = mma_k16<DT>(a[b], bf[g], acc[b]);
+                    if ((g & 3) == wave) {             // this wave's share of the sums of squares
+#pragma unroll
+                        for (int b = 0; b < kActive; ++b) ssq[b] = chunk_sumsq<DT>(a[b], ssq[b]);
+                    }
                 } else {
                     u32x4 a[kActive];
 #pragma unroll

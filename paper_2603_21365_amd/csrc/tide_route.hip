@@ -332,11 +332,12 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
     const bool generic_d = d % 128 != 0;           // the fallback: register-ring form, whatever form is forced
     // Rows per workgroup (streaming form).  128 rows fetch each W1' fragment once per 128 rows and
     // is the choice whenever the tiles fill most of the chip.  With few tiles it wins again, because
-    // every CU is launched and the tiles are cut into 64- or 32-row pieces (up to 80 tiles of 128
-    // rows: measured against the 64-row kernel on a 256-CU device); in between, 64-row tiles on two
-    // workgroups per CU are faster.  `form` overrides for tests and tuning.
+    // every CU is launched and the tiles are cut into 32-row pieces (up to 64 tiles of 128 rows, a
+    // quarter of a 256-CU device: 25.7 against 29.6 us at 64 tiles, measured); from there up to the
+    // one-tile kernel's range 64-row tiles on two workgroups per CU are faster (30.3 against 32.8 us
+    // at 80 tiles, 32.9 against 39.5 us at 128).  `form` overrides for tests and tuning.
     const int64_t tiles128 = C * ((T + 127) / 128);
-    int rows_per_wg = (tiles128 <= 80 || tiles128 >= 144) ? 128 : 64;
+    int rows_per_wg = (tiles128 <= 64 || tiles128 >= 144) ? 128 : 64;
     if (form == 1) rows_per_wg = 64;
     if (form == 2 || form == 6) rows_per_wg = 128;
     // fp32 rows are split into bf16 terms before the matrix cores: the register-ring form does
@@ -412,7 +413,13 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
             plan.launch[plan.count++] = PlannedLaunch{wide16 ? kKernelWide : kKernelWideF32, (int)wrows, (int)tpcw, (int)wide_tiles, 0, 1, wgrid};
             if (wide_tiles == tilesw) return plan;
             const int64_t c0 = wide_tiles / tpcw, j0 = wide_tiles % tpcw;      // first row left: wrows * j0 of checkpoint c0
-            if (wide16) rows_per_wg = (int)(wrows / 2);
+            if (wide16) {
+                rows_per_wg = (int)(wrows / 2);
+                if (rows_per_wg == 128 && form == 0) {         // what is left, by the rule at the top
+                    const int64_t tpc128 = (T + 127) / 128, left128 = C * tpc128 - (c0 * tpc128 + 2 * j0);
+                    if (left128 > 64 && left128 < 144) rows_per_wg = 64;
+                }
+            }
             tiles_per_ckpt = (T + rows_per_wg - 1) / rows_per_wg;
             total_tiles = C * tiles_per_ckpt;
             tile_begin = c0 * tiles_per_ckpt + (wrows / rows_per_wg) * j0;

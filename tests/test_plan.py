@@ -149,7 +149,8 @@ def test_the_choices_on_the_named_workloads():
     """What the automatic choice is on a 256-CU device for the workloads the measurements quote."""
     kinds = lambda plan: [(L["kernel"], L["rows_per_tile"]) for L in plan]
     assert kinds(tr.prefill_plan(tr.BF16, 8, 4096, 4096)) == [(TILE, 128)]                       # one tile per CU
-    assert kinds(tr.prefill_plan(tr.BF16, 9, 16384, 4096)) == [(WIDE, 256), (STREAM128, 128)]    # two wide rounds + the rest
+    assert kinds(tr.prefill_plan(tr.BF16, 9, 16384, 4096)) == [(WIDE, 256), (STREAM64, 64)]      # two wide rounds + the rest (128 tiles of 128 rows)
+    assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096)) == [(WIDE, 256), (TILE, 128)]        # ... + a full round of 128-row tiles
     assert kinds(tr.prefill_plan(tr.BF16, 8, 8192, 4096)) == [(WIDE, 256)]                        # exactly one wide round
     assert kinds(tr.prefill_plan(tr.F32, 10, 16384, 4096)) == [(WIDE_F32, 256), (RING, 64)]
     assert kinds(tr.prefill_plan(tr.F16, 8, 8, 4096)) == [(SPLITK, 32)]                           # a decode step on packed weights
