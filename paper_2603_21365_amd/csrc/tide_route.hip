@@ -332,12 +332,13 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
     const bool generic_d = d % 128 != 0;           // the fallback: register-ring form, whatever form is forced
     // Rows per workgroup (streaming form).  128 rows fetch each W1' fragment once per 128 rows and
     // is the choice whenever the tiles fill most of the chip.  With few tiles it wins again, because
-    // every CU is launched and the tiles are cut into 32-row pieces (up to 64 tiles of 128 rows, a
-    // quarter of a 256-CU device: 25.7 against 29.6 us at 64 tiles, measured); from there up to the
-    // one-tile kernel's range 64-row tiles on two workgroups per CU are faster (30.3 against 32.8 us
-    // at 80 tiles, 32.9 against 39.5 us at 128).  `form` overrides for tests and tuning.
-    const int64_t tiles128 = C * ((T + 127) / 128);
-    int rows_per_wg = (tiles128 <= 64 || tiles128 >= 144) ? 128 : 64;
+    // every CU is launched and the tiles are cut into 32-row pieces (up to a quarter as many tiles of
+    // 128 rows as CUs: 25.7 against 29.6 us at 64 tiles on 256 CUs, measured); from there on 64-row
+    // tiles are faster as long as every CU holds at most one (30.3 against 32.8 us at 80 tiles of 128
+    // rows, 32.9 against 39.5 us at 128; with a second workgroup on some CUs 55 us at 129, where the
+    // one-tile kernel takes 43.6 us).  `form` overrides for tests and tuning.
+    const int64_t tiles128 = C * ((T + 127) / 128), tiles64 = C * ((T + 63) / 64);
+    int rows_per_wg = (4 * tiles128 > (int64_t)cus && tiles64 <= (int64_t)cus) ? 64 : 128;
     if (form == 1) rows_per_wg = 64;
     if (form == 2 || form == 6) rows_per_wg = 128;
     // fp32 rows are split into bf16 terms before the matrix cores: the register-ring form does
@@ -417,7 +418,8 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
                 rows_per_wg = (int)(wrows / 2);
                 if (rows_per_wg == 128 && form == 0) {         // what is left, by the rule at the top
                     const int64_t tpc128 = (T + 127) / 128, left128 = C * tpc128 - (c0 * tpc128 + 2 * j0);
-                    if (left128 > 64 && left128 < 144) rows_per_wg = 64;
+                    const int64_t tpc64 = (T + 63) / 64, left64 = C * tpc64 - (c0 * tpc64 + 4 * j0);
+                    if (4 * left128 > (int64_t)cus && left64 <= (int64_t)cus) rows_per_wg = 64;
                 }
             }
             tiles_per_ckpt = (T + rows_per_wg - 1) / rows_per_wg;
