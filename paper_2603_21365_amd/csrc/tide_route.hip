@@ -409,6 +409,12 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
         const int64_t tpcw = (T + wrows - 1) / wrows, tilesw = C * tpcw;
         unsigned wgrid = cus;
         if (form == 4 && tilesw < (int64_t)cus) wgrid = (unsigned)(tilesw & ~(int64_t)7);
+        // Less than one round, but more than half of one and a whole number of tiles per XCD: a wide tile on
+        // each of that many CUs still beats 128-row tiles in one round and a bit (measured on 256 CUs, 16-bit
+        // rows, width 128: 78.6 against 86.6 us at 192 wide tiles, 84.4 against 98.8 us at 224, 69.7 against
+        // 71.9 us at 144; below that, or with a few tiles left for a second launch, it does not).
+        if (form == 0 && wide16 && !two_halves && tilesw < (int64_t)cus && tilesw % 8 == 0 && 16 * tilesw >= 9 * (int64_t)cus)
+            wgrid = (unsigned)tilesw;
         const int64_t wide_tiles = wgrid >= 8 ? tilesw / wgrid * wgrid : 0;
         if (wide_tiles > 0) {
             plan.launch[plan.count++] = PlannedLaunch{wide16 ? kKernelWide : kKernelWideF32, (int)wrows, (int)tpcw, (int)wide_tiles, 0, 1, wgrid};
