@@ -27,8 +27,9 @@ constexpr int kWide32PlaneBytes = (kWideTileBytes / 4 / 16) * 4096;       // one
 constexpr int kWide32BBytes = 2 * kWide32PlaneBytes;                      // 16 KiB
 constexpr int kWide32LdsBytes = kWide32Stages * (kWide32ABytes + kWide32BBytes) + kWideConsumers * 32 * (int)sizeof(float);
 
-// p.total_tiles counts tiles of 256 rows and is a multiple of the grid size (the host hands the rest of
-// the batch to the register-ring kernel); p.tiles_per_ckpt = ceil(T / 256).
+// p.total_tiles counts tiles of 256 rows: the first p.total_tiles of the checkpoint-major list (the host hands
+// the rest of the batch, if any, to the register-ring kernel); the last round may be partly filled, and a
+// workgroup without a tile exits at once.  p.tiles_per_ckpt = ceil(T / 256).
 __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_f32_kernel(const PrefillParams p) {
     typedef __attribute__((address_space(3))) char lds_char;
     typedef __attribute__((address_space(1))) const char glb_char;
@@ -41,9 +42,11 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_f32_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nstage = p.d * 4 / kWideTileBytes;                 // k-tiles of a row
-    const int per_xcd = p.total_tiles >> 3, g = gridDim.x >> 3;
+    const int per_xcd = (p.total_tiles + 7) >> 3, g = gridDim.x >> 3;
     const int lo = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    const int count = per_xcd / g;                               // tiles of this workgroup
+    const int slice_end = ((blockIdx.x & 7) + 1) * per_xcd < p.total_tiles ? ((blockIdx.x & 7) + 1) * per_xcd : p.total_tiles;   // of this XCD's slice
+    const int count = lo < slice_end ? (slice_end - lo + g - 1) / g : 0;   // tiles of this workgroup: lo, lo + g, ... below slice_end
+    if (count == 0) return;                                         // (the whole workgroup, before any barrier)
     auto tile_of = [&](int i) { return lo + i * g; };
     auto first_stage = [&](int tile) { return (int)(((unsigned)tile * 5u) % (unsigned)nstage); };
     const size_t plane_chunks = (size_t)p.d * 16;                // 16-byte chunks of one plane of a checkpoint's W1'

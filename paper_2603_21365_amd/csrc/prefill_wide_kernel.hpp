@@ -53,8 +53,9 @@ constexpr int wide_scratch_bytes(int kHalves) { return (4 + 4 * kHalves + 1) * w
 static_assert(wide_lds_bytes(1) <= 160 * 1024 && wide_lds_bytes(2) <= 160 * 1024, "LDS of a CU");
 static_assert(wide_scratch_bytes(1) <= wide_b_bytes(1) && wide_scratch_bytes(2) <= wide_b_bytes(2), "the scratch arrays fit a W1' slot");
 
-// p.total_tiles counts tiles of wide_rows(kHalves) rows here and is a multiple of the grid size (the
-// host hands the rest of the batch to the streaming kernel); p.tiles_per_ckpt = ceil(T / rows).
+// p.total_tiles counts tiles of wide_rows(kHalves) rows here: the first p.total_tiles of the checkpoint-major
+// list (the host hands the rest of the batch, if any, to the streaming kernel); the last round may
+// be partly filled, and a workgroup without a tile exits at once.  p.tiles_per_ckpt = ceil(T / rows).
 template <int DT, int kHalves>
 __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(const PrefillParams p) {
     static_assert(DT != kF32, "16-bit storage types only");
@@ -78,9 +79,11 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
     const int nstage = p.d * Storage<DT>::kBytes / kWideTileBytes;      // k-tiles of a row
     // XCD x (workgroup id mod 8) walks the x-th eighth of the checkpoint-major tile list, its
     // workgroups round-robin: an XCD's L2 holds one W1' at a time.
-    const int per_xcd = p.total_tiles >> 3, g = gridDim.x >> 3;
+    const int per_xcd = (p.total_tiles + 7) >> 3, g = gridDim.x >> 3;
     const int lo = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    const int count = per_xcd / g;                                       // tiles of this workgroup
+    const int slice_end = ((blockIdx.x & 7) + 1) * per_xcd < p.total_tiles ? ((blockIdx.x & 7) + 1) * per_xcd : p.total_tiles;   // of this XCD's slice
+    const int count = lo < slice_end ? (slice_end - lo + g - 1) / g : 0;   // tiles of this workgroup: lo, lo + g, ... below slice_end
+    if (count == 0) return;                                         // (the whole workgroup, before any barrier)
     auto tile_of = [&](int i) { return lo + i * g; };
     auto first_stage = [&](int tile) { return (int)(((unsigned)tile * 5u) % (unsigned)nstage); };
     const size_t ckpt_chunks = (size_t)p.d * kBottleneck / Storage<DT>::kElems;   // of one column half

@@ -366,6 +366,7 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
     //   streaming, few tiles:  5.7 + 0.48 n   (width 256: 7.0 + 1.17 n; fp32 rows: 5.7 + 0.7 n)
     //   split-k pair:          a_B + c_B ceil(n / S) ceil(W / CUs) + (0.011 + 0.009 S) R
     //                          with (a_B, c_B) = (8.5, 0.50), (8.9, 0.60), (9.6, 0.92) for B = 1, 2, 4
+    //                          (fp32 rows: c_B = 0.65, 0.90, 1.61)
     // Forced (form 5) the cheapest shape is taken whatever the streaming estimate says, and the form
     // word may fix the tile height (bits 8-15) and the slice count (bits 16-23).
     if (!generic_d && (form == 0 || form == 5)) {
@@ -378,7 +379,9 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
             if (force_rows ? rows != force_rows : (rows > 32 && 2 * T <= rows)) continue;   // never a tile that is mostly padding
             const int64_t tiles = C * ((T + rows - 1) / rows);
             const double B = rows / 32, R = (double)(tiles * halves) * B;
-            const double launch_cost = rows == 32 ? 8.5 : rows == 64 ? 8.9 : 9.6, chain_cost = rows == 32 ? 0.50 : rows == 64 ? 0.60 : 0.92;
+            const double launch_cost = rows == 32 ? 8.5 : rows == 64 ? 8.9 : 9.6;
+            const double chain_cost = dtype == TIDE_F32 ? (rows == 32 ? 0.65 : rows == 64 ? 0.90 : 1.61)     // three matrix steps per value
+                                                        : (rows == 32 ? 0.50 : rows == 64 ? 0.60 : 0.92);
             if (tiles * halves * (rows / 32) > max_blocks) continue;
             for (int64_t s = kSplitkMaxSlices; s >= 2; s /= 2) {
                 const int64_t S = std::min<int64_t>(ntile, s);
@@ -407,15 +410,21 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
     if (wide16 || wide32) {
         const int64_t wrows = two_halves ? kWideRows / 2 : kWideRows;
         const int64_t tpcw = (T + wrows - 1) / wrows, tilesw = C * tpcw;
-        unsigned wgrid = cus;
-        if (form == 4 && tilesw < (int64_t)cus) wgrid = (unsigned)(tilesw & ~(int64_t)7);
-        // Less than one round, but more than half of one and a whole number of tiles per XCD: a wide tile on
-        // each of that many CUs still beats 128-row tiles in one round and a bit (measured on 256 CUs, 16-bit
-        // rows, width 128: 78.6 against 86.6 us at 192 wide tiles, 84.4 against 98.8 us at 224, 69.7 against
-        // 71.9 us at 144; below that, or with a few tiles left for a second launch, it does not).
-        if (form == 0 && wide16 && !two_halves && tilesw < (int64_t)cus && tilesw % 8 == 0 && 16 * tilesw >= 9 * (int64_t)cus)
-            wgrid = (unsigned)tilesw;
-        const int64_t wide_tiles = wgrid >= 8 ? tilesw / wgrid * wgrid : 0;
+        // Whole rounds always; the tiles of a last, partly filled round too if they are many enough (the
+        // CUs without a tile idle meanwhile), else they go to a kernel with smaller tiles behind this one.
+        // Measured on 256 CUs against the best other form, less than one round in all:
+        //   16-bit rows, width 128: 78.6 against 86.6 us at 192 wide tiles, 84.4 against 98.8 us at 224, a draw
+        //     at 144-160 (d = 8192: 3 % behind) -- from 11/16 of the CUs on;
+        //   width 256 (128-row tiles): 60.9 against 92 us at 136, 66.6 against 94.4 us at 192, but 59.8 against
+        //     51.6 us at 128, where the 64-row kernel still has one workgroup per CU -- from half the CUs + 1 on;
+        //   fp32 rows: 157 against 169 us at 132 (264 tiles of 128 rows), 208 against 238 us at 224, nothing to
+        //     gain at 128 and below -- from half the CUs + 1 on.
+        // Forced (form 4): every tile of the list, whatever their number.
+        const int64_t rem = tilesw % (int64_t)cus;
+        const bool last_round_too = form == 4 || rem == 0 ||
+                                    (wide16 && !two_halves ? 16 * rem >= 11 * (int64_t)cus : 2 * rem > (int64_t)cus);
+        const int64_t wide_tiles = last_round_too ? tilesw : tilesw - rem;
+        const unsigned wgrid = wide_tiles >= (int64_t)cus ? cus : 8u * (unsigned)((wide_tiles + 7) / 8);
         if (wide_tiles > 0) {
             plan.launch[plan.count++] = PlannedLaunch{wide16 ? kKernelWide : kKernelWideF32, (int)wrows, (int)tpcw, (int)wide_tiles, 0, 1, wgrid};
             if (wide_tiles == tilesw) return plan;

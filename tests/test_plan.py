@@ -51,7 +51,8 @@ def check_plan(dtype, C, T, d, b, cus, form):
         if k in (WIDE, WIDE_F32):
             assert i == 0 and L["tile_begin"] == 0 and d % 128 == 0, what
             assert R == (128 if halves == 2 else 256), what
-            assert wg % 8 == 0 and wg <= cus and L["total_tiles"] % wg == 0, what   # whole rounds, one slice per XCD
+            assert wg % 8 == 0 and wg <= cus, what                                   # one slice of the list per XCD
+            assert wg == (cus if L["total_tiles"] >= cus else 8 * -(-L["total_tiles"] // 8)), what   # rounds of one tile per CU; the last may be partly filled
             assert (dtype == tr.F32) == (k == WIDE_F32), what
             assert not (k == WIDE_F32 and halves == 2), what
         if k == TILE:
@@ -162,7 +163,16 @@ def test_the_choices_on_the_named_workloads():
     assert kinds(tr.prefill_plan(tr.BF16, 1, 6144, 4096)) == [(STREAM128, 128)]                   # 48 tiles: pieces of the persistent kernel
     assert kinds(tr.prefill_plan(tr.BF16, 1, 1024, 1024)) == [(STREAM128, 128)]                   # short rows: the chain is short already
     assert kinds(tr.prefill_plan(tr.BF16, 8, 4096, 4096, 256)) == [(WIDE, 128)]                   # width 256: one round of 128-row tiles
-    assert kinds(tr.prefill_plan(tr.BF16, 8, 2048, 4096)) == [(STREAM64, 64)]                     # 128 tiles of 128 rows: two 64-row workgroups per CU
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 2048, 4096)) == [(STREAM64, 64)]                     # 128 tiles of 128 rows: a 64-row workgroup per CU
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 2080, 4096)) == [(TILE, 128)]                        # 136 tiles: the 64-row kernel would need two per CU
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 6144, 4096)) == [(WIDE, 256)]                        # 192 wide tiles: three quarters of a round
+    assert tr.prefill_plan(tr.BF16, 8, 6144, 4096)[0]["workgroups"] == 192
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 4608, 4096)) == [(STREAM128, 128)]                   # 144 wide tiles: too few for that
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 3072, 4096, 256)) == [(WIDE, 128)]                   # width 256: 192 tiles of 128 rows on 192 CUs
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 7168, 4096, 256)) == [(WIDE, 128)]                   # ... and 448: a round and three quarters
+    assert kinds(tr.prefill_plan(tr.F32, 8, 7168, 4096)) == [(WIDE_F32, 256)]                     # fp32 rows: 224 wide tiles
+    assert kinds(tr.prefill_plan(tr.F32, 1, 9216, 4096)) == [(RING, 64)]                          # fp32, 72 tiles: the split-k chain is too long
+    assert kinds(tr.prefill_plan(tr.F32, 1, 8192, 4096)) == [(SPLITK, 64)]
 
 
 def test_a_forced_split_k_shape_is_taken_as_given():
