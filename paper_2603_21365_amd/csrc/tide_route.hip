@@ -363,7 +363,7 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
     // measurements on a 256-CU device (d = 1024 ... 8192, 32 ... 8192 rows, widths 128 and 256), with
     // n = k-tiles of a row, B = 32-row blocks per tile, S = slices, R = 32-row blocks of the whole call
     // (x 2 at width 256), W = workgroups:
-    //   streaming, few tiles:  5.7 + 0.48 n   (width 256: 7.0 + 1.17 n; fp32 rows: 5.7 + 0.7 n)
+    //   streaming, few tiles:  5.7 + 0.48 n   (width 256: 7.0 + 1.17 n; fp32 rows, register-ring form: 8.5 + 0.75 n)
     //   split-k pair:          a_B + c_B ceil(n / S) ceil(W / CUs) + (0.011 + 0.009 S) R
     //                          with (a_B, c_B) = (8.5, 0.50), (8.9, 0.60), (9.6, 0.92) for B = 1, 2, 4
     //                          (fp32 rows: c_B = 0.65, 0.90, 1.61)
@@ -392,7 +392,7 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
                 if (t < best) { best = t; best_rows = rows; best_S = S; }
             }
         }
-        const double t_stream = dtype == TIDE_F32 ? 5.7 + 0.7 * (double)ntile      // the register-ring form
+        const double t_stream = dtype == TIDE_F32 ? 8.5 + 0.75 * (double)ntile     // the register-ring form
                               : halves == 1 ? 5.7 + 0.48 * (double)ntile : 7.0 + 1.17 * (double)ntile;
         if (best_rows && (form == 5 || best + 0.3 < t_stream)) {
             const int64_t tpc = (T + best_rows - 1) / best_rows, tiles = C * tpc;
@@ -413,8 +413,9 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
         // Whole rounds always; the tiles of a last, partly filled round too if they are many enough (the
         // CUs without a tile idle meanwhile), else they go to a kernel with smaller tiles behind this one.
         // Measured on 256 CUs against the best other form, less than one round in all:
-        //   16-bit rows, width 128: 78.6 against 86.6 us at 192 wide tiles, 84.4 against 98.8 us at 224, a draw
-        //     at 144-160 (d = 8192: 3 % behind) -- from 11/16 of the CUs on;
+        //   16-bit rows, width 128: 78.6 against 86.6 us at 192 wide tiles, 84.4 against 98.8 us at 224; at 129-160
+        //     d = 1024 / 2048 gain 5-10 % (23 against 25.5 us, 39 against 41.5 us), d = 4096 1-6 %, d = 8192 loses
+        //     3-5 % -- from half the CUs + 1 on, beyond d = 4096 from 11/16 of them on;
         //   width 256 (128-row tiles): 60.9 against 92 us at 136, 66.6 against 94.4 us at 192, but 59.8 against
         //     51.6 us at 128, where the 64-row kernel still has one workgroup per CU -- from half the CUs + 1 on;
         //   fp32 rows: 157 against 169 us at 132 (264 tiles of 128 rows), 208 against 238 us at 224, nothing to
@@ -422,7 +423,7 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
         // Forced (form 4): every tile of the list, whatever their number.
         const int64_t rem = tilesw % (int64_t)cus;
         const bool last_round_too = form == 4 || rem == 0 ||
-                                    (wide16 && !two_halves ? 16 * rem >= 11 * (int64_t)cus : 2 * rem > (int64_t)cus);
+                                    (wide16 && !two_halves && d > 4096 ? 16 * rem >= 11 * (int64_t)cus : 2 * rem > (int64_t)cus);
         const int64_t wide_tiles = last_round_too ? tilesw : tilesw - rem;
         const unsigned wgrid = wide_tiles >= (int64_t)cus ? cus : 8u * (unsigned)((wide_tiles + 7) / 8);
         if (wide_tiles > 0) {

@@ -167,7 +167,9 @@ def test_the_choices_on_the_named_workloads():
     assert kinds(tr.prefill_plan(tr.BF16, 8, 2080, 4096)) == [(TILE, 128)]                        # 136 tiles: the 64-row kernel would need two per CU
     assert kinds(tr.prefill_plan(tr.BF16, 8, 6144, 4096)) == [(WIDE, 256)]                        # 192 wide tiles: three quarters of a round
     assert tr.prefill_plan(tr.BF16, 8, 6144, 4096)[0]["workgroups"] == 192
-    assert kinds(tr.prefill_plan(tr.BF16, 8, 4608, 4096)) == [(STREAM128, 128)]                   # 144 wide tiles: too few for that
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 4608, 4096)) == [(WIDE, 256)]                        # 144 wide tiles: still more than half a round
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 4608, 8192)) == [(STREAM128, 128)]                   # ... which at d = 8192 is too few (from 176 on)
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 4096 + 128, 4096)) == [(WIDE, 256)]                  # 136 wide tiles, the last of each checkpoint half empty
     assert kinds(tr.prefill_plan(tr.BF16, 8, 3072, 4096, 256)) == [(WIDE, 128)]                   # width 256: 192 tiles of 128 rows on 192 CUs
     assert kinds(tr.prefill_plan(tr.BF16, 8, 7168, 4096, 256)) == [(WIDE, 128)]                   # ... and 448: a round and three quarters
     assert kinds(tr.prefill_plan(tr.F32, 8, 7168, 4096)) == [(WIDE_F32, 256)]                     # fp32 rows: 224 wide tiles
