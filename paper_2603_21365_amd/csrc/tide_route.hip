@@ -364,7 +364,7 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
     // n = k-tiles of a row, B = 32-row blocks per tile, S = slices, R = 32-row blocks of the whole call
     // (x 2 at width 256), W = workgroups:
     //   streaming, few tiles:  5.7 + 0.48 n   (width 256: 7.0 + 1.17 n; fp32 rows, register-ring form: 8.5 + 0.75 n)
-    //   split-k pair:          a_B + c_B ceil(n / S) ceil(W / CUs) + (0.011 + 0.009 S) R
+    //   split-k pair:          a_B + c_B ceil(n / S) ceil(W / CUs) + (0.011 + 0.009 S) R min(1, n / 32)   (fp32 rows: no min)
     //                          with (a_B, c_B) = (8.5, 0.50), (8.9, 0.60), (9.6, 0.92) for B = 1, 2, 4
     //                          (fp32 rows: c_B = 0.65, 0.90, 1.61)
     // Forced (form 5) the cheapest shape is taken whatever the streaming estimate says, and the form
@@ -380,6 +380,8 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
             const int64_t tiles = C * ((T + rows - 1) / rows);
             const double B = rows / 32, R = (double)(tiles * halves) * B;
             const double launch_cost = rows == 32 ? 8.5 : rows == 64 ? 8.9 : 9.6;
+            // (16-bit rows: the per-block cost halves at d = 2048 and is flat from 4096 on; fp32 rows: flat)
+            const double short_rows = dtype != TIDE_F32 && ntile < 32 ? (double)ntile / 32.0 : 1.0;
             const double chain_cost = dtype == TIDE_F32 ? (rows == 32 ? 0.65 : rows == 64 ? 0.90 : 1.61)     // three matrix steps per value
                                                         : (rows == 32 ? 0.50 : rows == 64 ? 0.60 : 0.92);
             if (tiles * halves * (rows / 32) > max_blocks) continue;
@@ -388,7 +390,7 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
                 if (S < 2 || (force_slices && s != force_slices)) continue;
                 const int64_t W = tiles * halves * S;
                 const double t = launch_cost + chain_cost * (double)((ntile + S - 1) / S) * (double)((W + cus - 1) / cus) +
-                                 (0.011 + 0.009 * (double)S) * R;
+                                 (0.011 + 0.009 * (double)S) * R * short_rows;
                 if (t < best) { best = t; best_rows = rows; best_S = S; }
             }
         }
