@@ -267,7 +267,7 @@ def main() -> int:
         _, ev3 = timed(lambda i: c3[i & 1](), n3, 5)
         by3 = w3.C * w3.T * d * esz + w3.C * d * 128 * esz + w3.T * 8 + w3.C * w3.T * 4
         result["large_batch"] = {"workload": "configs[3]: bf16, d=4096, 36 layers, C=9, T=16384 (8 x 2048), packed weights; "
-                                             "wide-tile kernel for two rounds of 256-row tiles + 128-row kernel for the rest",
+                                             "wide-tile kernel for two rounds of 256-row tiles + 64-row kernel for the rest",
                                  "us_per_call": round(ev3 / n3 * 1e6, 2), "tokens_per_s": round(w3.T / (ev3 / n3), 1),
                                  "algorithmic_bytes": by3, "gbs": round(by3 / (ev3 / n3) / 1e9, 1),
                                  "frac_of_hbm_peak": round(by3 / (ev3 / n3) / 1e9 / HBM_PEAK_GBS, 4)}
