@@ -409,10 +409,20 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
                         for (int b = 0; b < kActive; ++b) ssq[b] += sq[b];
                     }
                 } else {
+                    // the next group's fragments are read before this group's matrix instructions are issued
+                    if (g == 0) {
+#pragma unroll
+                        for (int b = 0; b < kActive; ++b)
+                            a_pipe[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + y16);
+                    }
                     u32x4 a[kActive];
 #pragma unroll
-                    for (int b = 0; b < kActive; ++b)
-                        a[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + (y16 ^ (g << 5)));
+                    for (int b = 0; b < kActive; ++b) a[b] = a_pipe[b];
+                    if (g + 1 < kMmaGroups) {
+#pragma unroll
+                        for (int b = 0; b < kActive; ++b)
+                            a_pipe[b] = *reinterpret_cast<const u32x4*>(st + b * 32 * kTileBytes + (y16 ^ ((g + 1) << 5)));
+                    }
 #pragma unroll
                     for (int b = 0; b < kActive; ++b) {
                         acc[b] = mma_k16<DT>(a[b], bh0[slot], acc[b]);
