@@ -241,6 +241,11 @@ __global__ __launch_bounds__(kFinishThreads * kHalves) void tide_splitk_finish_k
     const int row0 = (tile - c * p.tiles_per_ckpt) * kRowsM + 32 * blk;
     if (row0 >= p.T) return;                       // a block of padding rows only
     const int S = p.k_slices;
+    // this lane's column of the second layer, fetched first so that the epilogue does not wait for it
+    // (columns at and beyond the bottleneck width are zero padding: their w2 is zero)
+    const int col = kBottleneck * half + 32 * w + (lane & 31);
+    const float b1c = (p.b1 && col < p.b) ? p.b1[c * p.b + col] : 0.0f;
+    const float w2c = col < p.b ? p.w2[c * p.b + col] : 0.0f;
 
     // partial sums of squares (those of column half 0; every half computed the same ones): thread
     // (row, j) adds the four waves' values of slices j, j+8, ...; the eight results per row are
@@ -285,10 +290,6 @@ __global__ __launch_bounds__(kFinishThreads * kHalves) void tide_splitk_finish_k
         for (int q = 0; q < 4; ++q)
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc[0][4 * q + e] = sum[q][e];
-        // (columns at and beyond the bottleneck width are zero padding: their w2 is zero)
-        const int col = kBottleneck * half + 32 * w + (lane & 31);
-        const float b1c = (p.b1 && col < p.b) ? p.b1[c * p.b + col] : 0.0f;
-        const float w2c = col < p.b ? p.w2[c * p.b + col] : 0.0f;
         router_epilogue<1>(acc, inv_rms, z_part[wave], b1c, w2c, lane);
     }
     __syncthreads();

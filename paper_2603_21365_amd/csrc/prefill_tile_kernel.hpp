@@ -96,6 +96,11 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
     const int y16 = ((lane >> 5) ^ (r & 15)) << 4;               // see prefill_dma_kernel.hpp
     const size_t ckpt_chunks = (size_t)p.d * kBottleneck / Storage<DT>::kElems;
     const u32x4* bptr = p.packed + (size_t)c * ckpt_chunks + wave * 64 + lane;
+    // this lane's column of the second layer, fetched now so that the epilogue does not wait for it
+    // (columns at and beyond the bottleneck width are zero padding: their w2 is zero)
+    const int col = 32 * wave + (lane & 31);
+    const float b1c = (p.b1 && col < p.b) ? p.b1[c * p.b + col] : 0.0f;
+    const float w2c = col < p.b ? p.w2[c * p.b + col] : 0.0f;
     constexpr int kGroups = Compute<DT>::kMmaGroups;             // 8
     u32x4 breg[kGroups];                                         // W1' fragments, one k-tile ahead
 #pragma unroll
@@ -149,13 +154,7 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
         inv_rms[tid] = inv_rms_f32(ss, 1.0f / (float)p.d, p.eps);
     }
     __syncthreads();
-    {
-        // (columns at and beyond the bottleneck width are zero padding: their w2 is zero)
-        const int col = 32 * wave + (lane & 31);
-        const float b1c = (p.b1 && col < p.b) ? p.b1[c * p.b + col] : 0.0f;
-        const float w2c = col < p.b ? p.w2[c * p.b + col] : 0.0f;
-        router_epilogue<kBlocks>(acc, inv_rms, z_part + wave * kRowsM, b1c, w2c, lane);
-    }
+    router_epilogue<kBlocks>(acc, inv_rms, z_part + wave * kRowsM, b1c, w2c, lane);
     __syncthreads();
     if (tid < kRowsM) {
         const int t = row0 + tid;
