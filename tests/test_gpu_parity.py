@@ -527,6 +527,30 @@ def test_one_checkpoint_calls_at_the_other_measured_sizes(tr, T):
     run_and_compare(tr, w, w.name, rt=rt, packed=True)
 
 
+def test_random_shapes_on_the_automatic_choice(tr):
+    """Seeded random (type, C, T, d, width) on the automatic choice, sized so that every kind of launch
+    the plan knows comes up -- split-k shapes, pieces, the 64-row and one-tile kernels, wide rounds with
+    a partly filled last round, wide rounds + a second launch -- each against the oracle."""
+    rng = np.random.default_rng(0xA070)
+    seen = set()
+    for n in range(36):
+        dtype = ["bf16", "f16", "f32"][int(rng.integers(0, 3))]
+        d = int(rng.choice([128, 256, 384, 512, 1024]))
+        b = int(rng.choice([64, 128, 128, 256]))
+        C = int(rng.integers(1, 13))
+        rows = int(rng.choice([rng.integers(1, 200), rng.integers(200, 5000), rng.integers(5000, 30000), rng.integers(30000, 90000)]))
+        T = max(1, rows // C)
+        plan = tr.prefill_plan(tr.DTYPE_CODES[dtype], C, T, d, b)
+        kinds = tuple((L["kernel"], L["rows_per_tile"]) for L in plan)
+        seen.add(kinds)
+        w = synth.Workload(f"fuzz{n}_{dtype}_C{C}_T{T}_d{d}_b{b}_{kinds}", 67 + n, dtype, d, 4 * C, 4, T, None, b=b)
+        rt = w.routers()
+        rt.b2[:] = np.linspace(-0.2, 0.2, C) if C > 1 else 0.05
+        run_and_compare(tr, w, w.name, rt=rt, packed=bool(n & 1))
+    say(f"launch kinds seen: {sorted(seen)}")
+    assert len(seen) >= 8
+
+
 def test_thresholds_off_and_always_and_min_layer(tr):
     import torch
     w = synth.Workload("theta_edges", 23, "bf16", 1024, 16, 4, 200, None)
