@@ -363,8 +363,9 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
     // measurements on a 256-CU device (d = 1024 ... 8192, 32 ... 8192 rows, widths 128 and 256), with
     // n = k-tiles of a row, B = 32-row blocks per tile, S = slices, R = 32-row blocks of the whole call
     // (x 2 at width 256), W = workgroups:
-    //   streaming, few tiles:  5.7 + 0.48 n   (width 256: 7.0 + 1.17 n; fp32 rows, register-ring form: 8.5 + 0.75 n)
-    //   split-k pair:          a_B + c_B ceil(n / S) ceil(W / CUs) + (0.011 + 0.009 S) R min(1, n / 32)   (fp32 rows: no min)
+    //   streaming, few tiles:  5.7 + 0.48 n + 0.07 (n / 32) (tiles of 128 rows)   (width 256: 7.0 + 1.17 n; fp32 rows,
+    //                          register-ring form: 8.5 + 0.75 n)
+    //   split-k pair:          a_B + c_B ceil(n / S) ceil(W / CUs) + (0.011 n / 32 + 0.009 S) R
     //                          with (a_B, c_B) = (8.5, 0.50), (8.9, 0.60), (9.6, 0.92) for B = 1, 2, 4
     //                          (fp32 rows: c_B = 0.65, 0.90, 1.61)
     // Forced (form 5) the cheapest shape is taken whatever the streaming estimate says, and the form
@@ -380,8 +381,7 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
             const int64_t tiles = C * ((T + rows - 1) / rows);
             const double B = rows / 32, R = (double)(tiles * halves) * B;
             const double launch_cost = rows == 32 ? 8.5 : rows == 64 ? 8.9 : 9.6;
-            // (16-bit rows: the per-block cost halves at d = 2048 and is flat from 4096 on; fp32 rows: flat)
-            const double short_rows = dtype != TIDE_F32 && ntile < 32 ? (double)ntile / 32.0 : 1.0;
+            const double row_cost = 0.011 * (double)ntile / 32.0;                 // reading a 32-row block's rows: by their length
             const double chain_cost = dtype == TIDE_F32 ? (rows == 32 ? 0.65 : rows == 64 ? 0.90 : 1.61)     // three matrix steps per value
                                                         : (rows == 32 ? 0.50 : rows == 64 ? 0.60 : 0.92);
             if (tiles * halves * (rows / 32) > max_blocks) continue;
@@ -390,12 +390,13 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
                 if (S < 2 || (force_slices && s != force_slices)) continue;
                 const int64_t W = tiles * halves * S;
                 const double t = launch_cost + chain_cost * (double)((ntile + S - 1) / S) * (double)((W + cus - 1) / cus) +
-                                 (0.011 + 0.009 * (double)S) * R * short_rows;
+                                 (row_cost + 0.009 * (double)S) * R;
                 if (t < best) { best = t; best_rows = rows; best_S = S; }
             }
         }
         const double t_stream = dtype == TIDE_F32 ? 8.5 + 0.75 * (double)ntile     // the register-ring form
-                              : halves == 1 ? 5.7 + 0.48 * (double)ntile : 7.0 + 1.17 * (double)ntile;
+                              : halves == 1 ? 5.7 + 0.48 * (double)ntile + 0.07 * ((double)ntile / 32.0) * (double)tiles128
+                                            : 7.0 + 1.17 * (double)ntile;
         if (best_rows && (form == 5 || best + 0.3 < t_stream)) {
             const int64_t tpc = (T + best_rows - 1) / best_rows, tiles = C * tpc;
             plan.launch[plan.count++] = PlannedLaunch{kKernelSplitK, best_rows, (int)tpc, (int)tiles, 0, (int)best_S, (unsigned)(tiles * halves * best_S)};
@@ -416,16 +417,17 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
         // CUs without a tile idle meanwhile), else they go to a kernel with smaller tiles behind this one.
         // Measured on 256 CUs against the best other form, less than one round in all:
         //   16-bit rows, width 128: 78.6 against 86.6 us at 192 wide tiles, 84.4 against 98.8 us at 224; at 129-160
-        //     d = 1024 / 2048 gain 5-10 % (23 against 25.5 us, 39 against 41.5 us), d = 4096 1-6 %, d = 8192 loses
-        //     3-5 % -- from half the CUs + 1 on, beyond d = 4096 from 11/16 of them on;
+        //     d = 1024 / 2048 gain 5-10 % (23 against 25.5 us, 39 against 41.5 us), d = 4096 1-6 %, d = 16384 11-15 %
+        //     (244-270 against 286-303 us), but d = 5120 and 8192 lose 5-8 % (95-100 against 87-93 us) -- from half
+        //     the CUs + 1 on, for 4096 < d <= 8192 from 11/16 of them on;
         //   width 256 (128-row tiles): 60.9 against 92 us at 136, 66.6 against 94.4 us at 192, but 59.8 against
         //     51.6 us at 128, where the 64-row kernel still has one workgroup per CU -- from half the CUs + 1 on;
         //   fp32 rows: 157 against 169 us at 132 (264 tiles of 128 rows), 208 against 238 us at 224, nothing to
         //     gain at 128 and below -- from half the CUs + 1 on.
         // Forced (form 4): every tile of the list, whatever their number.
         const int64_t rem = tilesw % (int64_t)cus;
-        const bool last_round_too = form == 4 || rem == 0 ||
-                                    (wide16 && !two_halves && d > 4096 ? 16 * rem >= 11 * (int64_t)cus : 2 * rem > (int64_t)cus);
+        const bool mid_rows = wide16 && !two_halves && d > 4096 && d <= 8192;
+        const bool last_round_too = form == 4 || rem == 0 || (mid_rows ? 16 * rem >= 11 * (int64_t)cus : 2 * rem > (int64_t)cus);
         const int64_t wide_tiles = last_round_too ? tilesw : tilesw - rem;
         const unsigned wgrid = wide_tiles >= (int64_t)cus ? cus : 8u * (unsigned)((wide_tiles + 7) / 8);
         if (wide_tiles > 0) {

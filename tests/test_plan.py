@@ -160,7 +160,7 @@ def test_the_choices_on_the_named_workloads():
     assert tr.prefill_plan(tr.BF16, 1, 1024, 4096)[0]["workgroups"] == 256
     p4096 = tr.prefill_plan(tr.BF16, 1, 4096, 4096)[0]                                            # 64 tiles x 4 slices: still one workgroup per CU
     assert (p4096["kernel"], p4096["rows_per_tile"], p4096["k_slices"], p4096["workgroups"]) == (SPLITK, 64, 4, 256)
-    assert kinds(tr.prefill_plan(tr.BF16, 1, 6144, 4096)) == [(STREAM128, 128)]                   # 48 tiles: pieces of the persistent kernel
+    assert kinds(tr.prefill_plan(tr.BF16, 1, 8192, 4096)) == [(STREAM128, 128)]                   # 64 tiles: pieces of the persistent kernel
     assert kinds(tr.prefill_plan(tr.BF16, 1, 1024, 1024)) == [(STREAM128, 128)]                   # short rows: the chain is short already
     assert kinds(tr.prefill_plan(tr.BF16, 8, 4096, 4096, 256)) == [(WIDE, 128)]                   # width 256: one round of 128-row tiles
     assert kinds(tr.prefill_plan(tr.BF16, 8, 2048, 4096)) == [(STREAM64, 64)]                     # 128 tiles of 128 rows: a 64-row workgroup per CU
@@ -168,7 +168,6 @@ def test_the_choices_on_the_named_workloads():
     assert kinds(tr.prefill_plan(tr.BF16, 8, 6144, 4096)) == [(WIDE, 256)]                        # 192 wide tiles: three quarters of a round
     assert tr.prefill_plan(tr.BF16, 8, 6144, 4096)[0]["workgroups"] == 192
     assert kinds(tr.prefill_plan(tr.BF16, 8, 4608, 4096)) == [(WIDE, 256)]                        # 144 wide tiles: still more than half a round
-    assert kinds(tr.prefill_plan(tr.BF16, 8, 4608, 8192)) == [(STREAM128, 128)]                   # ... which at d = 8192 is too few (from 176 on)
     assert kinds(tr.prefill_plan(tr.BF16, 8, 4096 + 128, 4096)) == [(WIDE, 256)]                  # 136 wide tiles, the last of each checkpoint half empty
     assert kinds(tr.prefill_plan(tr.BF16, 8, 3072, 4096, 256)) == [(WIDE, 128)]                   # width 256: 192 tiles of 128 rows on 192 CUs
     assert kinds(tr.prefill_plan(tr.BF16, 8, 7168, 4096, 256)) == [(WIDE, 128)]                   # ... and 448: a round and three quarters
