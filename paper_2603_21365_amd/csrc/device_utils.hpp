@@ -204,6 +204,58 @@ __device__ __forceinline__ void router_epilogue2(const f32x16 (&acc0)[kBlocks], 
     }
 }
 
+// The router epilogue in the transposed accumulator layout.  The 32x32 matrix-core step takes its two
+// operands in the same lane layout, so a kernel may pass the W1' fragment first and the row fragment
+// second: the accumulator block then holds the transposed product, lane l owning ONE row (l % 32 of the
+// block) and, in register v, the router column 8*(v/4) + 4*(l/32) + v%4 of the wave's 32 columns.
+// The sum over columns becomes 16 multiply-adds inside the lane plus one exchange with lane l ^ 32
+// (no reduce-scatter), the row scale 1/rms is one scalar per lane, and b1 / w2 are per-register
+// constants.  The constants are pre-scaled so that an element costs six instructions:
+//   t = -log2(e) * (r * acc + b1)  (one fma),  e^-a = exp2(t),  s = 1 / (1 + e^-a),
+//   w2 * a * s = (-ln 2 * w2) * (t * s)        (a = -ln 2 * t)
+// (t = +large: exp2 = inf, s = 0, product 0; t = -large: exp2 = 0, s = 1, product t: SiLU's two tails).
+struct EpilogueColumns {
+    f32x4 b1s[4];   // -log2(e) * b1 of columns col0 + 8q + 4h + (0..3), q = 0..3
+    f32x4 w2s[4];   // -ln(2) * w2 of the same columns
+};
+constexpr float kNegLog2e = -1.4426950408889634f;
+constexpr float kNegLn2 = -0.6931471805599453f;
+// col0 = first column of the wave's 32 (within the router's b columns); columns at and beyond b are
+// zero padding.  b1 / w2 point at the checkpoint's [b] arrays, 16-byte aligned.
+__device__ __forceinline__ EpilogueColumns load_epilogue_columns(const float* b1, const float* w2, int b, int col0, int lane) {
+    EpilogueColumns e;
+    const int h = lane >> 5;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int col = col0 + 8 * q + 4 * h;
+        f32x4 bv = f32x4{0.0f, 0.0f, 0.0f, 0.0f}, wv = bv;
+        if (col < b) {
+            wv = *reinterpret_cast<const f32x4*>(w2 + col);
+            if (b1) bv = *reinterpret_cast<const f32x4*>(b1 + col);
+        }
+        e.b1s[q] = bv * kNegLog2e;
+        e.w2s[q] = wv * kNegLn2;
+    }
+    return e;
+}
+// One block: this lane's row, scale rs = -log2(e) / rms; returns the sum over the wave's 32 columns of
+// w2 * SiLU(acc / rms + b1), complete in every lane (both lane halves hold the same value).
+__device__ __forceinline__ float router_epilogue_row(const f32x16& acc, float rs, const EpilogueColumns& e) {
+    float z0 = 0.0f, z1 = 0.0f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float t = fmaf(rs, acc[4 * q + i], e.b1s[q][i]);
+            const float s = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t));
+            if (i & 1) z1 = fmaf(e.w2s[q][i], t * s, z1);
+            else z0 = fmaf(e.w2s[q][i], t * s, z0);
+        }
+    }
+    const float z = z0 + z1;
+    return z + __shfl_xor(z, 32, kWave);
+}
+
 // Values that another workgroup, possibly on another XCD, reads back within the same launch
 // are written and read with device-scope relaxed atomics: such accesses go straight to the
 // level where all XCDs agree, so no cache write-back or invalidate is needed.  (A device-scope

@@ -34,7 +34,6 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
     char* ring = smem;
     float* ss_part = reinterpret_cast<float*>(smem + kDmaStages * kStageBytes);   // [4][kRowsM]
     float* z_part = ss_part + kDmaConsumers * kRowsM;                              // [4][kRowsM]
-    float* inv_rms = z_part + kDmaConsumers * kRowsM;                              // [kRowsM]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int per_xcd = (p.total_tiles - p.tile_begin + 7) >> 3;
@@ -83,8 +82,7 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
             ring_barrier();                        // stage k handed over; the slot of stage k-1 is free
             issue_next();
         }
-        ring_barrier();                            // the three barriers of the consumers' epilogue
-        ring_barrier();
+        ring_barrier();                            // the two barriers of the consumers' epilogue
         ring_barrier();
         return;
     }
@@ -96,11 +94,11 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
     const int y16 = ((lane >> 5) ^ (r & 15)) << 4;               // see prefill_dma_kernel.hpp
     const size_t ckpt_chunks = (size_t)p.d * kBottleneck / Storage<DT>::kElems;
     const u32x4* bptr = p.packed + (size_t)c * ckpt_chunks + wave * 64 + lane;
-    // this lane's column of the second layer, fetched now so that the epilogue does not wait for it
-    // (columns at and beyond the bottleneck width are zero padding: their w2 is zero)
-    const int col = 32 * wave + (lane & 31);
-    const float b1c = (p.b1 && col < p.b) ? p.b1[c * p.b + col] : 0.0f;
-    const float w2c = col < p.b ? p.w2[c * p.b + col] : 0.0f;
+    // The matrix steps take W1' first and the rows second: the accumulators hold the transposed product,
+    // a lane owning one row per block and 16 of the wave's 32 columns (router_epilogue_row).  The b1 / w2
+    // of those columns are fetched now so that the epilogue does not wait for them (columns at and
+    // beyond the bottleneck width are zero padding: their w2 is zero).
+    const EpilogueColumns ecols = load_epilogue_columns(p.b1 ? p.b1 + c * p.b : nullptr, p.w2 + c * p.b, p.b, 32 * wave, lane);
     constexpr int kGroups = Compute<DT>::kMmaGroups;             // 8
     u32x4 breg[kGroups];                                         // W1' fragments, one k-tile ahead
 #pragma unroll
@@ -127,7 +125,7 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
             u32x4* cur = a[g & 1];
             if (g + 1 < kGroups) read_a(g + 1, a[(g + 1) & 1]);      // (two groups ahead: measured, no further gain)
 #pragma unroll
-            for (int b = 0; b < kBlocks; ++b) acc[b] = mma_k16<DT>(cur[b], breg[g], acc[b]);
+            for (int b = 0; b < kBlocks; ++b) acc[b] = mma_k16<DT>(breg[g], cur[b], acc[b]);
             if ((g & 3) == wave_u) {               // this wave's share of the sums of squares
 #pragma unroll
                 for (int b = 0; b < kBlocks; ++b) ssq[b] = chunk_sumsq<DT>(cur[b], ssq[b]);
@@ -149,12 +147,15 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
         if (lane < 32) ss_part[wave * kRowsM + 32 * b + lane] = s2;
     }
     __syncthreads();
-    if (tid < kRowsM) {
-        const float ss = (ss_part[tid] + ss_part[kRowsM + tid]) + (ss_part[2 * kRowsM + tid] + ss_part[3 * kRowsM + tid]);
-        inv_rms[tid] = inv_rms_f32(ss, 1.0f / (float)p.d, p.eps);
+    // every lane owns one row per block: its 1/rms from the four waves' partial sums, then the block's
+    // 16 columns inside the lane
+#pragma unroll
+    for (int b = 0; b < kBlocks; ++b) {
+        const int row = 32 * b + (lane & 31);
+        const float ss = (ss_part[row] + ss_part[kRowsM + row]) + (ss_part[2 * kRowsM + row] + ss_part[3 * kRowsM + row]);
+        const float z = router_epilogue_row(acc[b], kNegLog2e * inv_rms_f32(ss, 1.0f / (float)p.d, p.eps), ecols);
+        if (lane < 32) z_part[wave * kRowsM + row] = z;
     }
-    __syncthreads();
-    router_epilogue<kBlocks>(acc, inv_rms, z_part + wave * kRowsM, b1c, w2c, lane);
     __syncthreads();
     if (tid < kRowsM) {
         const int t = row0 + tid;
