@@ -33,12 +33,25 @@
  *  - T == 0 is a successful no-op.  1 <= C <= 32.
  *  - The threshold test is taken on the logit: z > ln(theta/(1-theta)) for 0 < theta < 1,
  *    never for theta >= 1 (the paper's "1.0 (off)", Table 4), always for theta <= 0.
- *  - The router entry points (raw or packed weights) use a per-device workspace that the
- *    library allocates (hipMalloc) on first use and when a larger problem arrives; calls that
- *    share it on one device must be ordered on one stream.  tide_release() frees it.
- *    Once the workspace is large enough a call only enqueues kernels, so it can be captured in
- *    a HIP graph; the graph holds the workspace's addresses, so make one eager call of the
- *    largest shape first and neither outgrow nor release the workspace while the graph lives.
+ *  - Scratch memory.  The router entry points need some device memory of their own: a counter per
+ *    checkpoint and one 64-bit arrival word per token (state: zero between calls), and for some
+ *    shapes packed weights or partial results (data).  Two sources:
+ *      (1) the plain entry points use a per-device workspace that the library allocates (hipMalloc)
+ *          on first use and when a larger problem arrives -- always before the call's first kernel
+ *          is enqueued.  It is shared by every stream of the device: calls that use it must be
+ *          ordered on one stream, and a call on another stream while the last one's stream is still
+ *          busy is refused with TIDE_ERR_WORKSPACE.  tide_release() frees it.  Once it is large
+ *          enough a call only enqueues kernels, so it can be captured in a HIP graph; the graph
+ *          holds the workspace's addresses, so make one eager call of the largest shape on the
+ *          capturing stream first and neither outgrow nor release the workspace while the graph lives;
+ *      (2) the _ws entry points take a caller-owned workspace (tide_workspace_bytes,
+ *          tide_workspace_init): nothing is allocated, and calls on different workspaces may run
+ *          concurrently on different streams.
+ *  - On error nothing is enqueued, with one exception: if a kernel launch itself fails
+ *    (TIDE_ERR_HIP) after an earlier kernel of the same call was enqueued, that earlier work stays
+ *    enqueued; the scratch memory is then marked and re-initialised by the next call that uses it
+ *    (a caller-owned workspace: by the caller's next tide_workspace_init).
+ *  - W1 / packed, w2, and gamma / b1 when given, must be 16-byte aligned (TIDE_ERR_ALIGNMENT).
  *  - Small batches (a decode step, or one checkpoint's call on a few hundred rows) run on kernels
  *    that split each router's contraction over the whole chip: a matrix-core split-k pair for
  *    packed weights, an fp32 latency kernel for raw weights up to 8 rows per checkpoint and, up
@@ -64,8 +77,8 @@ typedef enum {
     TIDE_OK = 0,
     TIDE_ERR_INVALID_ARG = -1, /* NULL where data is required, negative size, bad enum, unsorted layer_ids */
     TIDE_ERR_UNSUPPORTED = -2, /* d or b outside the supported set, C > 32 */
-    TIDE_ERR_ALIGNMENT = -3,   /* hidden base or strides not 16-byte aligned */
-    TIDE_ERR_WORKSPACE = -4,   /* workspace allocation failed */
+    TIDE_ERR_ALIGNMENT = -3,   /* hidden base or strides, a parameter array or a workspace misaligned */
+    TIDE_ERR_WORKSPACE = -4,   /* workspace allocation failed, or a workspace too small, busy or in the wrong state */
     TIDE_ERR_HIP = -5          /* a HIP runtime call failed; see tide_last_error() */
 } tide_status_t;
 
@@ -136,6 +149,40 @@ int tide_select_exit_packed(const void* hidden, int dtype, int64_t C, int64_t T,
                             const float* threshold, const int32_t* layer_ids, int32_t min_layer,
                             int32_t no_exit_layer, int32_t* exit_layer, float* logits,
                             uint32_t* fire_mask, void* stream);
+
+/* ---- Caller-owned workspaces: the same two calls with the scratch memory supplied by the caller
+ * (Eq. (2) / Fig. 1 step 3 as above; nothing is allocated, and each stream can have its own).
+ *
+ * tide_workspace_bytes: bytes a call of this shape needs on the current device under the current
+ *   variant / prefill-form settings (raw_weights != 0: the call takes W1 and packs it inside the
+ *   call).  A multiple of 256; 0 with tide_last_error() set if the shape is unsupported.  On a
+ *   machine without a GPU the answer is that for a 256-CU device.  Host arithmetic only.
+ * tide_workspace_init: zero-fills `workspace` (device, 256-byte aligned, workspace_bytes >= 256) on
+ *   `stream` with a kernel and registers it with the library.  Call it once after allocating the
+ *   workspace, and again before a call that keeps MORE state at the start of the workspace than
+ *   the calls since the last init (more tokens, or an exit_layer output after calls without one);
+ *   the library tracks this per workspace and returns TIDE_ERR_WORKSPACE instead of computing on a
+ *   workspace in the wrong state.  Calls of one and the same shape never need a second init.
+ *   Calls sharing one workspace must be ordered on one stream (the workspace carries their state);
+ *   the library does not check this for caller-owned workspaces.
+ * tide_workspace_forget: drops the library's record of a workspace (before freeing it); optional,
+ *   the library keeps at most 64 records and replaces the least recently used.
+ * The _ws calls: exactly one of W1 (raw fp32 weights, with optional gamma) and packed is non-NULL;
+ *   workspace_bytes >= tide_workspace_bytes(...) and <= what tide_workspace_init was given.      */
+size_t tide_workspace_bytes(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int raw_weights);
+int tide_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+int tide_workspace_forget(void* workspace);
+int tide_router_eval_ws(const void* hidden, int dtype, int64_t T, int64_t d, int64_t b,
+                        int64_t row_stride, const float* gamma, float eps, const float* W1,
+                        const void* packed, const float* b1, const float* w2, float b2,
+                        float threshold, float* prob, uint8_t* fire, float* logit, void* workspace,
+                        size_t workspace_bytes, void* stream);
+int tide_select_exit_ws(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b,
+                        int64_t ckpt_stride, int64_t row_stride, const float* gamma, float eps,
+                        const float* W1, const void* packed, const float* b1, const float* w2,
+                        const float* b2, const float* threshold, const int32_t* layer_ids,
+                        int32_t min_layer, int32_t no_exit_layer, int32_t* exit_layer, float* logits,
+                        uint32_t* fire_mask, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Exit projection: the rows the LM head consumes (Fig. 1 "LMHead(Norm(h_k))", Alg. 1 line 5,
  * Sec. 3.4 kernels 3-4).  out[t,:] = RMSNorm(src_t) * norm_gain, computed in fp32 and rounded

@@ -60,8 +60,26 @@ struct Buffer {
     size_t bytes = 0;
 };
 
+// ---- Scratch memory of a router call (device memory beyond the caller's inputs and outputs).
+// Two kinds.  STATE words -- the decode kernel's per-checkpoint counters and one arrival word per
+// token -- must be zero when a call starts, and every kernel that uses them leaves them zero (the
+// last arriver resets them).  DATA -- the packed weights of a raw-weight call and the partial
+// results of the split-k pair / the latency kernel -- is written before it is read within the call.
+struct Scratch {
+    uint32_t* counters = nullptr;   // kCounterSlots words (state)
+    uint64_t* arrive = nullptr;     // [T] arrival words (state), null when no exit_layer is asked for
+    void* packed = nullptr;         // C packed routers (data), raw-weight prefill calls only
+    float* part = nullptr;          // partial results (data)
+};
+
+// The library's own workspace: one per device, grow-only, shared by every call that does not bring
+// a workspace of its own.  `last_stream` / `used` remember where its last call was enqueued, `dirty`
+// that a launch failed after an earlier one of the same call had been enqueued (the state words
+// may then be non-zero: the next call clears them first).
 struct Workspace {
     Buffer counters, arrive, packed, part, batch, compact;
+    hipStream_t last_stream = nullptr;
+    bool used = false, dirty = false;
 };
 
 std::mutex g_mu;
@@ -70,6 +88,19 @@ int g_variant = TIDE_VARIANT_AUTO;
 int g_prefill_form = 0;   // a form word (see valid_form_word): 0 auto; 1 / 2: streaming form with 64 / 128 rows per workgroup;
                           // 3: register-ring form; 4: wide-tile form wherever it applies, on as many workgroups as there are
                           // whole tiles; 5: split-k pair (optionally with a forced shape); 6: one-tile form
+
+// Caller-owned workspaces (the _ws entry points) are single blocks laid out per call: state words first, data behind them.  A call with more
+// state words than an earlier one would find that call's data where it needs zeros, so the library
+// keeps, per block, how many leading bytes are known to hold zero state (`clean`): the whole block
+// after tide_workspace_init, at most the call's state bytes after a call that wrote data.
+struct BlockRecord {
+    void* ptr = nullptr;
+    size_t bytes = 0, clean = 0;
+    uint64_t stamp = 0;             // for replacing the least recently used record
+};
+constexpr int kMaxBlockRecords = 64;
+BlockRecord g_blocks[kMaxBlockRecords];
+uint64_t g_block_clock = 0;
 
 // Grow-only device buffer.  Re-allocation frees the old block, which waits for the device.
 int reserve(Buffer& b, size_t bytes, bool zero) {
@@ -94,11 +125,39 @@ int reserve(Buffer& b, size_t bytes, bool zero) {
     return TIDE_OK;
 }
 
+int current_device(int* dev) {
+    TIDE_HIP(hipGetDevice(dev));
+    if (*dev < 0 || *dev >= kMaxDevices) return fail(TIDE_ERR_UNSUPPORTED, "device index %d out of range", *dev);
+    return TIDE_OK;
+}
+
 int current_workspace(Workspace** out) {
     int dev = 0;
-    TIDE_HIP(hipGetDevice(&dev));
-    if (dev < 0 || dev >= kMaxDevices) return fail(TIDE_ERR_UNSUPPORTED, "device index %d out of range", dev);
+    int rc = current_device(&dev);
+    if (rc) return rc;
     *out = &g_ws[dev];
+    return TIDE_OK;
+}
+
+// The library's workspace is shared by every stream of the device, and its state words carry a
+// call's progress: two calls in flight on different streams would corrupt each other.  A call on
+// another stream than the last one is accepted only when that stream has drained.  (Skipped while
+// `st` is being captured into a graph -- queries are not allowed then; a captured call must follow
+// an eager one on the same stream anyway, which is what sizes the workspace.)
+int claim_workspace(Workspace& ws, hipStream_t st) {
+    if (ws.used && ws.last_stream != st) {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(st, &cap) != hipSuccess) (void)hipGetLastError();
+        if (cap == hipStreamCaptureStatusNone) {
+            const hipError_t q = hipStreamQuery(ws.last_stream);
+            if (q == hipErrorNotReady)
+                return fail(TIDE_ERR_WORKSPACE, "the library workspace is still in use by a call on another stream: order the "
+                            "calls on one stream, or give each stream a workspace of its own (the _ws entry points)");
+            if (q != hipSuccess) (void)hipGetLastError();   // e.g. the stream no longer exists: nothing of ours is pending on it
+        }
+    }
+    ws.last_stream = st;
+    ws.used = true;
     return TIDE_OK;
 }
 
@@ -152,6 +211,14 @@ int check_common(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d,
     const size_t eb = elem_bytes(dtype);
     if (((uintptr_t)hidden & 15) || ((size_t)row_stride * eb & 15) || (C > 1 && ((size_t)ckpt_stride * eb & 15)))
         return fail(TIDE_ERR_ALIGNMENT, "hidden base and strides must be multiples of 16 bytes");
+    if (((uintptr_t)weights & 15) || ((uintptr_t)w2 & 15))
+        return fail(TIDE_ERR_ALIGNMENT, "W1 / packed and w2 must be 16-byte aligned");
+    return TIDE_OK;
+}
+
+// gamma and b1 are optional; when given they are read with 16-byte loads like the other parameter arrays.
+int check_optional_arrays(const float* gamma, const float* b1) {
+    if (((uintptr_t)gamma & 15) || ((uintptr_t)b1 & 15)) return fail(TIDE_ERR_ALIGNMENT, "gamma and b1 must be 16-byte aligned");
     return TIDE_OK;
 }
 
@@ -226,8 +293,13 @@ template <int DT, int kHalves> int launch_wide(unsigned grid, hipStream_t st, co
 }
 
 // The split-k pair: `tiles` tiles of kBlocks*32 rows times p.k_slices workgroups leave their partial
-// results in the workspace, then one small workgroup per 32-row block adds them and finishes the router.
-template <int DT, int kBlocks> int launch_splitk(Workspace& ws, int64_t tiles, hipStream_t st, PrefillParams& p) {
+// results in `part`, then one small workgroup per 32-row block adds them and finishes the router.
+// Bytes of partial results the pair leaves for `tiles` tiles of kBlocks*32 rows in `halves` column halves and S slices.
+size_t splitk_part_bytes(int blocks, int64_t tiles, int halves, int64_t S) {
+    const size_t items = (size_t)tiles * halves * S;
+    return items * ((size_t)blocks * 32 * kBottleneck + (size_t)kDmaConsumers * blocks * 32) * sizeof(float);
+}
+template <int DT, int kBlocks> int launch_splitk(float* part, int64_t tiles, hipStream_t st, PrefillParams& p) {
     static bool raised[kMaxDevices] = {};
     int dev = 0;
     TIDE_HIP(hipGetDevice(&dev));
@@ -240,10 +312,8 @@ template <int DT, int kBlocks> int launch_splitk(Workspace& ws, int64_t tiles, h
     const int halves = halves_of(p.b);
     const size_t items = (size_t)tiles * halves * p.k_slices;
     const size_t z_bytes = items * splitk_part_floats<kBlocks>() * sizeof(float);
-    int rc = reserve(ws.part, z_bytes + items * kDmaConsumers * kBlocks * 32 * sizeof(float), false);
-    if (rc) return rc;
-    p.zpart = (float*)ws.part.ptr;
-    p.sspart = (float*)((char*)ws.part.ptr + z_bytes);
+    p.zpart = part;
+    p.sspart = (float*)((char*)part + z_bytes);
     hipLaunchKernelGGL((tide_prefill_splitk_kernel<DT, kBlocks>), dim3((unsigned)items), dim3(kDmaThreads), lds, st, p);
     if (halves == 2)
         hipLaunchKernelGGL((tide_splitk_finish_kernel<kBlocks, 2>), dim3((unsigned)(tiles * kBlocks)), dim3(2 * kFinishThreads), 0, st, p);
@@ -471,8 +541,8 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
     return plan;
 }
 
-int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int64_t ckpt_stride,
-                   int64_t row_stride, const void* packed, float eps, const float* b1, const float* w2,
+int launch_prefill(const Scratch& sc, const PrefillPlan& plan, const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b,
+                   int64_t ckpt_stride, int64_t row_stride, const void* packed, float eps, const float* b1, const float* w2,
                    const CheckpointTable& tab, int32_t min_layer, int32_t no_exit, const Outputs& o, hipStream_t st) {
     PrefillParams p;
     std::memset(&p, 0, sizeof(p));
@@ -497,18 +567,11 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
     p.exit_layer = o.exit_layer;
     p.fire_mask = o.fire_mask;
     p.tab = tab;
-    if (o.exit_layer) {
-        int rc0 = reserve(ws.arrive, (size_t)T * sizeof(uint64_t), true);
-        if (rc0) return rc0;
-        p.arrive = (uint64_t*)ws.arrive.ptr;
-    }
-    unsigned cus = 0;
-    int rc = resident_cus(&cus);
-    if (rc) return rc;
+    p.arrive = o.exit_layer ? sc.arrive : nullptr;
+    int rc = TIDE_OK;
     const bool two_halves = halves_of(b) == 2;
     const int ntile = (int)(p.dpad * (int64_t)eb / kTileBytes);
     const bool ragged = p.dpad != p.d;
-    const PrefillPlan plan = plan_prefill(dtype, C, T, d, b, cus, g_prefill_form);
     for (int i = 0; i < plan.count; ++i) {
         const PlannedLaunch& L = plan.launch[i];
         p.tiles_per_ckpt = L.tiles_per_ckpt;
@@ -519,8 +582,8 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
             constexpr int DT = decltype(dt)::value;
             switch (L.kernel) {
             case kKernelSplitK:
-                rc = L.rows_per_tile == 32 ? launch_splitk<DT, 1>(ws, L.total_tiles, st, p)
-                   : L.rows_per_tile == 64 ? launch_splitk<DT, 2>(ws, L.total_tiles, st, p) : launch_splitk<DT, 4>(ws, L.total_tiles, st, p);
+                rc = L.rows_per_tile == 32 ? launch_splitk<DT, 1>(sc.part, L.total_tiles, st, p)
+                   : L.rows_per_tile == 64 ? launch_splitk<DT, 2>(sc.part, L.total_tiles, st, p) : launch_splitk<DT, 4>(sc.part, L.total_tiles, st, p);
                 break;
             case kKernelWide:
                 if constexpr (DT != kF32) rc = two_halves ? launch_wide<DT, 2>(L.grid, st, p) : launch_wide<DT, 1>(L.grid, st, p);
@@ -559,7 +622,7 @@ int launch_prefill(Workspace& ws, const void* hidden, int dtype, int64_t C, int6
     return TIDE_OK;
 }
 
-int launch_decode(Workspace& ws, const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int64_t ckpt_stride,
+int launch_decode(const Scratch& sc, const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int64_t ckpt_stride,
                   int64_t row_stride, const float* gamma, const float* W1, const void* packed, float eps, const float* b1, const float* w2,
                   const CheckpointTable& tab, int32_t min_layer, int32_t no_exit, const Outputs& o, hipStream_t st) {
     DecodeParams p;
@@ -589,17 +652,9 @@ int launch_decode(Workspace& ws, const void* hidden, int dtype, int64_t C, int64
     p.exit_layer = o.exit_layer;
     p.fire_mask = o.fire_mask;
     p.tab = tab;
-    int rc = reserve(ws.counters, kCounterSlots * sizeof(uint32_t), true);
-    if (rc) return rc;
-    p.counter = (uint32_t*)ws.counters.ptr;
-    rc = reserve(ws.part, (size_t)C * p.S * T * (p.halves * kBottleneck + kPartPad) * sizeof(float), false);
-    if (rc) return rc;
-    p.part = (float*)ws.part.ptr;
-    if (o.exit_layer) {
-        rc = reserve(ws.arrive, (size_t)T * sizeof(uint64_t), true);
-        if (rc) return rc;
-        p.arrive = (uint64_t*)ws.arrive.ptr;
-    }
+    p.counter = sc.counters;
+    p.part = sc.part;
+    p.arrive = o.exit_layer ? sc.arrive : nullptr;
     const int nblk = p.C * p.S * p.halves;
     const unsigned grid = 8u * (unsigned)((nblk + 7) / 8);
     by_dtype(dtype, [&](auto dt) {
@@ -625,37 +680,152 @@ int launch_decode(Workspace& ws, const void* hidden, int dtype, int64_t C, int64
 // T = 8).  With raw weights that form needs the packing pass first (7.5 us at C = 8), so the latency
 // kernel, which reads W1 as it is, keeps T <= 8 (11-15 us against 17 us); it also keeps, up to
 // T = 32, what the split-k form does not cover (hidden sizes that are not multiples of 128).
-bool use_decode(int64_t T, int dtype, int64_t d, int64_t b, bool packed_given) {
-    if (g_variant == TIDE_VARIANT_DECODE) return T <= kDecodeMaxT;
-    if (g_variant == TIDE_VARIANT_PREFILL) return false;
+bool use_decode(int64_t T, int dtype, int64_t d, int64_t b, bool packed_given, int variant, int form_word) {
+    if (variant == TIDE_VARIANT_DECODE) return T <= kDecodeMaxT;
+    if (variant == TIDE_VARIANT_PREFILL) return false;
     const bool split_k = d % 128 == 0 && d >= 256 &&
-                         ((g_prefill_form & 0xff) == 0 || (g_prefill_form & 0xff) == 5);
+                         ((form_word & 0xff) == 0 || (form_word & 0xff) == 5);
     if (!split_k) return T <= kDecodeAutoMaxT;
     return !packed_given && T <= kDecodeRawMaxT;
 }
 
-// Shared body of the four compute entry points.  Exactly one of (W1) / (packed) is given.
+// ---- What a router call needs of scratch memory, and which path it takes: host arithmetic only.
+struct CallNeed {
+    bool decode = false;            // the latency kernel takes the call, else the prefill path with `plan`
+    PrefillPlan plan;
+    size_t state_bytes = 0;         // counters + arrival words, a multiple of 256
+    size_t packed_bytes = 0;        // a multiple of 256
+    size_t part_bytes = 0;          // a multiple of 256
+    size_t total() const { return state_bytes + packed_bytes + part_bytes; }
+};
+size_t round256(size_t n) { return (n + 255) & ~size_t(255); }
+
+CallNeed call_need(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, bool raw_weights, bool want_exit, unsigned cus, int variant,
+                   int form_word) {
+    CallNeed n;
+    n.state_bytes = round256(kCounterSlots * sizeof(uint32_t)) + (want_exit ? round256((size_t)T * sizeof(uint64_t)) : 0);
+    n.decode = use_decode(T, dtype, d, b, !raw_weights, variant, form_word);
+    const int halves = halves_of(b);
+    if (n.decode) {
+        const size_t S = (size_t)((d + kDecodeSlice - 1) / kDecodeSlice);
+        n.part_bytes = round256((size_t)C * S * (size_t)T * (size_t)(halves * kBottleneck + kPartPad) * sizeof(float));
+        return n;
+    }
+    if (raw_weights) n.packed_bytes = round256((size_t)C * tide_packed_router_bytes(dtype, d, b));
+    n.plan = plan_prefill(dtype, C, T, d, b, cus, form_word);
+    for (int i = 0; i < n.plan.count; ++i) {
+        const PlannedLaunch& L = n.plan.launch[i];
+        if (L.kernel == kKernelSplitK) n.part_bytes = round256(splitk_part_bytes(L.rows_per_tile / 32, L.total_tiles, halves, L.k_slices));
+    }
+    return n;
+}
+
+// Zero-fill for state words (a kernel, not a memset: calls may be captured into HIP graphs).
+__global__ void tide_clear_kernel(u32x4* p, size_t chunks) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < chunks; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = u32x4{0u, 0u, 0u, 0u};
+}
+int launch_clear(void* ptr, size_t bytes, hipStream_t st) {      // ptr 16-byte aligned, bytes a multiple of 16
+    if (bytes == 0) return TIDE_OK;
+    const size_t chunks = bytes / 16;
+    const unsigned grid = (unsigned)std::min<size_t>((chunks + 255) / 256, 2048);
+    hipLaunchKernelGGL(tide_clear_kernel, dim3(grid), dim3(256), 0, st, (u32x4*)ptr, chunks);
+    TIDE_HIP(hipGetLastError());
+    return TIDE_OK;
+}
+
+// One block (a caller's workspace) laid out for a call: state first, data behind.
+Scratch carve(void* block, const CallNeed& n, bool want_exit) {
+    Scratch sc;
+    char* base = (char*)block;
+    sc.counters = (uint32_t*)base;
+    sc.arrive = want_exit ? (uint64_t*)(base + round256(kCounterSlots * sizeof(uint32_t))) : nullptr;
+    sc.packed = n.packed_bytes ? base + n.state_bytes : nullptr;
+    sc.part = n.part_bytes ? (float*)(base + n.state_bytes + n.packed_bytes) : nullptr;
+    return sc;
+}
+
+BlockRecord* find_block(void* ptr) {
+    for (BlockRecord& r : g_blocks)
+        if (r.ptr == ptr) return &r;
+    return nullptr;
+}
+
+// Where a call's scratch memory comes from.
+enum ScratchSource { kScratchLibrary, kScratchCaller };
+
+// Shared body of the compute entry points.  Exactly one of (W1) / (packed) is given.  Everything that
+// can fail for lack of memory or for a misused workspace happens before the first kernel is enqueued.
 int run(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int64_t ckpt_stride, int64_t row_stride,
         const float* gamma, const float* W1, const void* packed, float eps, const float* b1, const float* w2,
-        const CheckpointTable& tab, int32_t min_layer, int32_t no_exit, const Outputs& o, void* stream) {
+        const CheckpointTable& tab, int32_t min_layer, int32_t no_exit, const Outputs& o, void* stream,
+        ScratchSource source = kScratchLibrary, void* block = nullptr, size_t block_bytes = 0) {
     if (T == 0) return TIDE_OK;
     hipStream_t st = (hipStream_t)stream;
     std::lock_guard<std::mutex> lock(g_mu);
-    Workspace* ws = nullptr;
-    int rc = current_workspace(&ws);
+    int dev = 0;
+    int rc = current_device(&dev);
     if (rc) return rc;
-    if (use_decode(T, dtype, d, b, packed != nullptr))
-        return launch_decode(*ws, hidden, dtype, C, T, d, b, ckpt_stride, row_stride, gamma, W1, packed, eps, b1, w2, tab,
-                             min_layer, no_exit, o, st);
-    if (W1) {
-        rc = reserve(ws->packed, (size_t)C * tide_packed_router_bytes(dtype, d, b), false);
+    unsigned cus = 0;
+    rc = resident_cus(&cus);
+    if (rc) return rc;
+    const bool want_exit = o.exit_layer != nullptr;
+    const CallNeed need = call_need(dtype, C, T, d, b, W1 != nullptr, want_exit, cus, g_variant, g_prefill_form);
+
+    Scratch sc;
+    Workspace* ws = nullptr;        // library workspace, if that is the source
+    size_t* clean = nullptr;        // else: the block's count of leading zero-state bytes
+    if (source == kScratchLibrary) {
+        ws = &g_ws[dev];
+        rc = claim_workspace(*ws, st);
         if (rc) return rc;
-        rc = launch_pack(dtype, C, d, b, gamma, W1, ws->packed.ptr, st);
-        if (rc) return rc;
-        packed = ws->packed.ptr;
+        if ((rc = reserve(ws->counters, kCounterSlots * sizeof(uint32_t), true))) return rc;
+        if (want_exit && (rc = reserve(ws->arrive, (size_t)T * sizeof(uint64_t), true))) return rc;
+        if (need.packed_bytes && (rc = reserve(ws->packed, need.packed_bytes, false))) return rc;
+        if (need.part_bytes && (rc = reserve(ws->part, need.part_bytes, false))) return rc;
+        if (ws->dirty) {            // an earlier call broke off between two launches: its state words may be set
+            if ((rc = launch_clear(ws->counters.ptr, ws->counters.bytes, st))) return rc;
+            if (ws->arrive.ptr && (rc = launch_clear(ws->arrive.ptr, ws->arrive.bytes, st))) return rc;
+            ws->dirty = false;
+        }
+        sc.counters = (uint32_t*)ws->counters.ptr;
+        sc.arrive = want_exit ? (uint64_t*)ws->arrive.ptr : nullptr;
+        sc.packed = ws->packed.ptr;
+        sc.part = (float*)ws->part.ptr;
+    } else if (source == kScratchCaller) {
+        BlockRecord* rec = find_block(block);
+        if (!rec) return fail(TIDE_ERR_WORKSPACE, "unknown workspace %p: call tide_workspace_init on it first", block);
+        if (block_bytes > rec->bytes)
+            return fail(TIDE_ERR_WORKSPACE, "workspace_bytes %zu exceeds the %zu bytes tide_workspace_init was given", block_bytes, rec->bytes);
+        if (need.total() > block_bytes)
+            return fail(TIDE_ERR_WORKSPACE, "this call needs %zu bytes of workspace (tide_workspace_bytes), %zu given", need.total(), block_bytes);
+        if (need.state_bytes > rec->clean)
+            return fail(TIDE_ERR_WORKSPACE, "this call keeps %zu bytes of state at the start of the workspace, where an earlier call of "
+                        "another shape left data (or a launch failed): call tide_workspace_init again first", need.state_bytes);
+        rec->stamp = ++g_block_clock;
+        clean = &rec->clean;
+        sc = carve(block, need, want_exit);
     }
-    return launch_prefill(*ws, hidden, dtype, C, T, d, b, ckpt_stride, row_stride, packed, eps, b1, w2, tab, min_layer,
-                          no_exit, o, st);
+    // the data regions of this call overwrite whatever zero state lay behind its own state words
+    if (clean && need.packed_bytes + need.part_bytes > 0 && *clean > need.state_bytes) *clean = need.state_bytes;
+
+    if (need.decode) {
+        rc = launch_decode(sc, hidden, dtype, C, T, d, b, ckpt_stride, row_stride, gamma, W1, packed, eps, b1, w2, tab,
+                           min_layer, no_exit, o, st);
+    } else {
+        if (W1) {
+            rc = launch_pack(dtype, C, d, b, gamma, W1, sc.packed, st);
+            packed = sc.packed;
+        }
+        if (!rc)
+            rc = launch_prefill(sc, need.plan, hidden, dtype, C, T, d, b, ckpt_stride, row_stride, packed, eps, b1, w2, tab,
+                                min_layer, no_exit, o, st);
+    }
+    if (rc) {                       // a launch failed, possibly after an earlier one of this call was enqueued
+        if (ws) ws->dirty = true;
+        if (clean) *clean = 0;
+    }
+    return rc;
 }
 
 }  // namespace
@@ -682,33 +852,73 @@ int tide_router_pack(int dtype, int64_t C, int64_t d, int64_t b, const float* ga
     return launch_pack(dtype, C, d, b, gamma, W1, packed, (hipStream_t)stream);
 }
 
-int tide_router_eval(const void* hidden, int dtype, int64_t T, int64_t d, int64_t b, int64_t row_stride, const float* gamma,
-                     float eps, const float* W1, const float* b1, const float* w2, float b2, float threshold,
-                     float* prob, uint8_t* fire, float* logit, void* stream) {
+namespace {
+// Front end of the router_eval family: one router (C = 1), exactly one of W1 / packed.
+int eval_front(const void* hidden, int dtype, int64_t T, int64_t d, int64_t b, int64_t row_stride, const float* gamma, float eps,
+               const float* W1, const void* packed, const float* b1, const float* w2, float b2, float threshold, float* prob,
+               uint8_t* fire, float* logit, void* stream, ScratchSource source, void* block, size_t block_bytes) {
     g_err[0] = 0;
-    int rc = check_common(hidden, dtype, 1, T, d, b, 0, row_stride, W1, w2, eps);
+    int rc = check_common(hidden, dtype, 1, T, d, b, 0, row_stride, W1 ? (const void*)W1 : packed, w2, eps);
     if (rc) return rc;
+    if ((rc = check_optional_arrays(gamma, b1))) return rc;
     CheckpointTable tab;
     const int32_t id0 = 0;
     rc = fill_table(tab, 1, &b2, &threshold, &id0);
     if (rc) return rc;
     Outputs o{prob, fire, logit, nullptr, nullptr};
-    return run(hidden, dtype, 1, T, d, b, 0, row_stride, gamma, W1, nullptr, eps, b1, w2, tab, 0, 0, o, stream);
+    return run(hidden, dtype, 1, T, d, b, 0, row_stride, gamma, W1, packed, eps, b1, w2, tab, 0, 0, o, stream, source, block, block_bytes);
+}
+// Front end of the select_exit family.
+int select_front(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int64_t ckpt_stride, int64_t row_stride,
+                 const float* gamma, float eps, const float* W1, const void* packed, const float* b1, const float* w2,
+                 const float* b2, const float* threshold, const int32_t* layer_ids, int32_t min_layer, int32_t no_exit_layer,
+                 int32_t* exit_layer, float* logits, uint32_t* fire_mask, void* stream, ScratchSource source, void* block,
+                 size_t block_bytes) {
+    g_err[0] = 0;
+    int rc = check_common(hidden, dtype, C, T, d, b, ckpt_stride, row_stride, W1 ? (const void*)W1 : packed, w2, eps);
+    if (rc) return rc;
+    if ((rc = check_optional_arrays(gamma, b1))) return rc;
+    CheckpointTable tab;
+    rc = fill_table(tab, C, b2, threshold, layer_ids);
+    if (rc) return rc;
+    if (T > 0 && !exit_layer) return fail(TIDE_ERR_INVALID_ARG, "exit_layer must not be NULL");
+    Outputs o{nullptr, nullptr, logits, exit_layer, fire_mask};
+    return run(hidden, dtype, C, T, d, b, ckpt_stride, row_stride, gamma, W1, packed, eps, b1, w2, tab, min_layer, no_exit_layer, o,
+               stream, source, block, block_bytes);
+}
+// A caller's workspace argument, checked before anything else is looked at.
+int check_block(const void* W1, const void* packed, const float* gamma, void* workspace, size_t workspace_bytes) {
+    g_err[0] = 0;
+    if ((W1 != nullptr) == (packed != nullptr)) return fail(TIDE_ERR_INVALID_ARG, "give exactly one of W1 (raw weights) and packed");
+    if (packed && gamma) return fail(TIDE_ERR_INVALID_ARG, "gamma is folded into packed weights: pass gamma = NULL with packed");
+    if (!workspace || workspace_bytes == 0) return fail(TIDE_ERR_INVALID_ARG, "workspace must not be NULL or empty");
+    if ((uintptr_t)workspace & 255) return fail(TIDE_ERR_ALIGNMENT, "workspace must be 256-byte aligned");
+    return TIDE_OK;
+}
+}  // namespace
+
+int tide_router_eval(const void* hidden, int dtype, int64_t T, int64_t d, int64_t b, int64_t row_stride, const float* gamma,
+                     float eps, const float* W1, const float* b1, const float* w2, float b2, float threshold,
+                     float* prob, uint8_t* fire, float* logit, void* stream) {
+    return eval_front(hidden, dtype, T, d, b, row_stride, gamma, eps, W1, nullptr, b1, w2, b2, threshold, prob, fire, logit, stream,
+                      kScratchLibrary, nullptr, 0);
 }
 
 int tide_router_eval_packed(const void* hidden, int dtype, int64_t T, int64_t d, int64_t b, int64_t row_stride,
                             const void* packed, float eps, const float* b1, const float* w2, float b2,
                             float threshold, float* prob, uint8_t* fire, float* logit, void* stream) {
-    g_err[0] = 0;
-    int rc = check_common(hidden, dtype, 1, T, d, b, 0, row_stride, packed, w2, eps);
+    return eval_front(hidden, dtype, T, d, b, row_stride, nullptr, eps, nullptr, packed, b1, w2, b2, threshold, prob, fire, logit,
+                      stream, kScratchLibrary, nullptr, 0);
+}
+
+int tide_router_eval_ws(const void* hidden, int dtype, int64_t T, int64_t d, int64_t b, int64_t row_stride, const float* gamma,
+                        float eps, const float* W1, const void* packed, const float* b1, const float* w2, float b2,
+                        float threshold, float* prob, uint8_t* fire, float* logit, void* workspace, size_t workspace_bytes,
+                        void* stream) {
+    int rc = check_block(W1, packed, gamma, workspace, workspace_bytes);
     if (rc) return rc;
-    if ((uintptr_t)packed & 15) return fail(TIDE_ERR_ALIGNMENT, "packed must be 16-byte aligned");
-    CheckpointTable tab;
-    const int32_t id0 = 0;
-    rc = fill_table(tab, 1, &b2, &threshold, &id0);
-    if (rc) return rc;
-    Outputs o{prob, fire, logit, nullptr, nullptr};
-    return run(hidden, dtype, 1, T, d, b, 0, row_stride, nullptr, nullptr, packed, eps, b1, w2, tab, 0, 0, o, stream);
+    return eval_front(hidden, dtype, T, d, b, row_stride, gamma, eps, W1, packed, b1, w2, b2, threshold, prob, fire, logit, stream,
+                      kScratchCaller, workspace, workspace_bytes);
 }
 
 int tide_select_exit(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int64_t ckpt_stride,
@@ -716,16 +926,8 @@ int tide_select_exit(const void* hidden, int dtype, int64_t C, int64_t T, int64_
                      const float* w2, const float* b2, const float* threshold, const int32_t* layer_ids,
                      int32_t min_layer, int32_t no_exit_layer, int32_t* exit_layer, float* logits,
                      uint32_t* fire_mask, void* stream) {
-    g_err[0] = 0;
-    int rc = check_common(hidden, dtype, C, T, d, b, ckpt_stride, row_stride, W1, w2, eps);
-    if (rc) return rc;
-    CheckpointTable tab;
-    rc = fill_table(tab, C, b2, threshold, layer_ids);
-    if (rc) return rc;
-    if (T > 0 && !exit_layer) return fail(TIDE_ERR_INVALID_ARG, "exit_layer must not be NULL");
-    Outputs o{nullptr, nullptr, logits, exit_layer, fire_mask};
-    return run(hidden, dtype, C, T, d, b, ckpt_stride, row_stride, gamma, W1, nullptr, eps, b1, w2, tab, min_layer,
-               no_exit_layer, o, stream);
+    return select_front(hidden, dtype, C, T, d, b, ckpt_stride, row_stride, gamma, eps, W1, nullptr, b1, w2, b2, threshold, layer_ids,
+                        min_layer, no_exit_layer, exit_layer, logits, fire_mask, stream, kScratchLibrary, nullptr, 0);
 }
 
 int tide_select_exit_packed(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int64_t ckpt_stride,
@@ -733,17 +935,70 @@ int tide_select_exit_packed(const void* hidden, int dtype, int64_t C, int64_t T,
                             const float* b2, const float* threshold, const int32_t* layer_ids, int32_t min_layer,
                             int32_t no_exit_layer, int32_t* exit_layer, float* logits, uint32_t* fire_mask,
                             void* stream) {
+    return select_front(hidden, dtype, C, T, d, b, ckpt_stride, row_stride, nullptr, eps, nullptr, packed, b1, w2, b2, threshold,
+                        layer_ids, min_layer, no_exit_layer, exit_layer, logits, fire_mask, stream, kScratchLibrary, nullptr, 0);
+}
+
+int tide_select_exit_ws(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int64_t ckpt_stride,
+                        int64_t row_stride, const float* gamma, float eps, const float* W1, const void* packed,
+                        const float* b1, const float* w2, const float* b2, const float* threshold,
+                        const int32_t* layer_ids, int32_t min_layer, int32_t no_exit_layer, int32_t* exit_layer,
+                        float* logits, uint32_t* fire_mask, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_block(W1, packed, gamma, workspace, workspace_bytes);
+    if (rc) return rc;
+    return select_front(hidden, dtype, C, T, d, b, ckpt_stride, row_stride, gamma, eps, W1, packed, b1, w2, b2, threshold, layer_ids,
+                        min_layer, no_exit_layer, exit_layer, logits, fire_mask, stream, kScratchCaller, workspace, workspace_bytes);
+}
+
+size_t tide_workspace_bytes(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int raw_weights) {
     g_err[0] = 0;
-    int rc = check_common(hidden, dtype, C, T, d, b, ckpt_stride, row_stride, packed, w2, eps);
+    if ((dtype != TIDE_F32 && dtype != TIDE_F16 && dtype != TIDE_BF16) || C < 1 || C > TIDE_MAX_CHECKPOINTS || T < 0 ||
+        C * T > (int64_t)1 << 30 || tide_packed_router_bytes(dtype, d, b) == 0) {
+        fail(TIDE_ERR_UNSUPPORTED, "unsupported dtype %d, C %lld, T %lld, d %lld or b %lld", dtype, (long long)C, (long long)T,
+             (long long)d, (long long)b);
+        return 0;
+    }
+    unsigned cus = 256;             // without a device: the answer for a 256-CU one
+    int dev = 0;
+    if (hipGetDevice(&dev) == hipSuccess) {
+        if (resident_cus(&cus) != TIDE_OK) cus = 256;
+    } else {
+        (void)hipGetLastError();
+    }
+    std::lock_guard<std::mutex> lock(g_mu);
+    return call_need(dtype, C, T > 0 ? T : 1, d, b, raw_weights != 0, true, cus, g_variant, g_prefill_form).total();
+}
+
+int tide_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+    g_err[0] = 0;
+    if (!workspace || workspace_bytes < 256) return fail(TIDE_ERR_INVALID_ARG, "workspace must not be NULL and hold at least 256 bytes");
+    if ((uintptr_t)workspace & 255) return fail(TIDE_ERR_ALIGNMENT, "workspace must be 256-byte aligned");
+    const size_t bytes = workspace_bytes & ~size_t(255);
+    std::lock_guard<std::mutex> lock(g_mu);
+    int rc = launch_clear(workspace, bytes, (hipStream_t)stream);
     if (rc) return rc;
-    if ((uintptr_t)packed & 15) return fail(TIDE_ERR_ALIGNMENT, "packed must be 16-byte aligned");
-    CheckpointTable tab;
-    rc = fill_table(tab, C, b2, threshold, layer_ids);
-    if (rc) return rc;
-    if (T > 0 && !exit_layer) return fail(TIDE_ERR_INVALID_ARG, "exit_layer must not be NULL");
-    Outputs o{nullptr, nullptr, logits, exit_layer, fire_mask};
-    return run(hidden, dtype, C, T, d, b, ckpt_stride, row_stride, nullptr, nullptr, packed, eps, b1, w2, tab, min_layer,
-               no_exit_layer, o, stream);
+    BlockRecord* rec = find_block(workspace);
+    if (!rec) {                     // a free record, else the least recently used one
+        rec = &g_blocks[0];
+        for (BlockRecord& r : g_blocks) {
+            if (!r.ptr) { rec = &r; break; }
+            if (r.stamp < rec->stamp) rec = &r;
+        }
+    }
+    rec->ptr = workspace;
+    rec->bytes = bytes;
+    rec->clean = bytes;
+    rec->stamp = ++g_block_clock;
+    return TIDE_OK;
+}
+
+int tide_workspace_forget(void* workspace) {
+    g_err[0] = 0;
+    std::lock_guard<std::mutex> lock(g_mu);
+    BlockRecord* rec = find_block(workspace);
+    if (!rec) return fail(TIDE_ERR_INVALID_ARG, "unknown workspace %p", workspace);
+    *rec = BlockRecord{};
+    return TIDE_OK;
 }
 
 int tide_exit_project(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t ckpt_stride,
@@ -824,6 +1079,7 @@ int tide_batch_compact(const int32_t* exit_layer, int64_t T, int32_t layer, int3
     Workspace* ws = nullptr;
     int rc = current_workspace(&ws);
     if (rc) return rc;
+    if ((rc = claim_workspace(*ws, st))) return rc;
     constexpr int kMaxBlocks = 1024;
     rc = reserve(ws->compact, kMaxBlocks * sizeof(uint32_t), true);
     if (rc) return rc;
@@ -917,6 +1173,7 @@ int tide_batch_exit(const uint32_t* fire_mask, int64_t T, int64_t C, const int32
     Workspace* ws = nullptr;
     int rc = current_workspace(&ws);
     if (rc) return rc;
+    if ((rc = claim_workspace(*ws, (hipStream_t)stream))) return rc;
     constexpr unsigned kMaxBlocks = 256;
     rc = reserve(ws->batch, (kMaxBlocks * 32 + 1) * sizeof(uint32_t), true);
     if (rc) return rc;
@@ -1014,6 +1271,8 @@ int tide_release(void) {
         b->ptr = nullptr;
         b->bytes = 0;
     }
+    ws->used = false;
+    ws->dirty = false;
     return TIDE_OK;
 }
 

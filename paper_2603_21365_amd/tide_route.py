@@ -26,6 +26,7 @@ EXPORTS = (
     "tide_version", "tide_last_error", "tide_router_eval", "tide_select_exit",
     "tide_packed_router_bytes", "tide_router_pack", "tide_router_eval_packed",
     "tide_select_exit_packed", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_batch_compact", "tide_set_variant", "tide_set_prefill_form", "tide_prefill_plan", "tide_stream_schedule", "tide_release",
+    "tide_workspace_bytes", "tide_workspace_init", "tide_workspace_forget", "tide_router_eval_ws", "tide_select_exit_ws",
 )
 
 _lib = None
@@ -54,6 +55,14 @@ def load_library() -> ctypes.CDLL:
                                      vp, vp, vp, vp]
     lib.tide_select_exit_packed.argtypes = [vp, ci, i64, i64, i64, i64, i64, i64, vp, f32, vp, vp, vp, vp, vp, i32, i32,
                                             vp, vp, vp, vp]
+    sz = ctypes.c_size_t
+    lib.tide_router_eval_ws.argtypes = [vp, ci, i64, i64, i64, i64, vp, f32, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp, sz, vp]
+    lib.tide_select_exit_ws.argtypes = [vp, ci, i64, i64, i64, i64, i64, i64, vp, f32, vp, vp, vp, vp, vp, vp, vp, i32, i32,
+                                        vp, vp, vp, vp, sz, vp]
+    lib.tide_workspace_bytes.argtypes = [ci, i64, i64, i64, i64, ci]
+    lib.tide_workspace_bytes.restype = sz
+    lib.tide_workspace_init.argtypes = [vp, sz, vp]
+    lib.tide_workspace_forget.argtypes = [vp]
     lib.tide_packed_router_bytes.argtypes = [ci, i64, i64]
     lib.tide_packed_router_bytes.restype = ctypes.c_size_t
     lib.tide_router_pack.argtypes = [ci, i64, i64, i64, vp, vp, vp, vp]
@@ -66,7 +75,8 @@ def load_library() -> ctypes.CDLL:
     lib.tide_prefill_plan.argtypes = [ci, i64, i64, i64, i64, ci, ci, vp]
     lib.tide_stream_schedule.argtypes = [ci, i64, i64, ci, ci, ci, ci, vp, ci]
     for name in ("tide_router_eval", "tide_router_eval_packed", "tide_select_exit", "tide_select_exit_packed",
-                 "tide_router_pack", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_batch_compact", "tide_set_variant", "tide_set_prefill_form", "tide_release"):
+                 "tide_router_pack", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_batch_compact", "tide_set_variant", "tide_set_prefill_form", "tide_release",
+                 "tide_router_eval_ws", "tide_select_exit_ws", "tide_workspace_init", "tide_workspace_forget"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -278,6 +288,52 @@ def select_exit_packed(hidden, packed, eps, b1, w2, b2, threshold, layer_ids, mi
                                                   _ptr(packed), float(eps), _ptr(b1), _ptr(w2), b2p, thp, idp,
                                                   int(min_layer), int(no_exit_layer), _ptr(exit_layer), _ptr(logits),
                                                   _ptr(mask), _stream()))
+    del keep
+    return exit_layer, logits, mask
+
+
+def workspace_bytes(dtype: int, C: int, T: int, d: int, b: int = BOTTLENECK, *, raw_weights: bool = False) -> int:
+    """Bytes of caller-owned workspace a router call of this shape needs (0 and last_error() if unsupported)."""
+    return int(load_library().tide_workspace_bytes(int(dtype), int(C), int(T), int(d), int(b), 1 if raw_weights else 0))
+
+
+def workspace_init(workspace: torch.Tensor) -> None:
+    """Zero-fill a workspace (a CUDA uint8 tensor, 256-byte aligned) on the current stream and register it."""
+    _check(load_library().tide_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def workspace_forget(workspace: torch.Tensor) -> None:
+    _check(load_library().tide_workspace_forget(_ptr(workspace)))
+
+
+def router_eval_ws(hidden, gamma, eps, W1, packed, b1, w2, b2, threshold, workspace, *, d, want_prob=True, want_fire=True,
+                   want_logit=True):
+    """router_eval / router_eval_packed (exactly one of W1 and packed) on a caller-owned workspace."""
+    (T, width), (rs, _) = _rows(hidden, 2)
+    b = int(w2.shape[0])
+    _f32dev(b1, (b,), "b1"), _f32dev(w2, (b,), "w2")
+    if width < d:
+        raise ValueError("hidden rows are shorter than d")
+    prob, fire, logit = _eval_outputs(T, hidden.device, want_prob, want_fire, want_logit)
+    _check(load_library().tide_router_eval_ws(_ptr(hidden), _dtype_code(hidden), T, int(d), b, rs if T > 1 else max(rs, d),
+                                              _ptr(gamma), float(eps), _ptr(W1), _ptr(packed), _ptr(b1), _ptr(w2), float(b2),
+                                              float(threshold), _ptr(prob), _ptr(fire), _ptr(logit), _ptr(workspace),
+                                              workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                                              _stream()))
+    return prob, fire, logit
+
+
+def select_exit_ws(hidden, gamma, eps, W1, packed, b1, w2, b2, threshold, layer_ids, min_layer, no_exit_layer, workspace, *, d,
+                   want_logits=True, want_mask=True, out=None):
+    """select_exit / select_exit_packed (exactly one of W1 and packed) on a caller-owned workspace."""
+    C, T, cs, rs, b2p, thp, idp, exit_layer, logits, mask, keep = _select_common(
+        hidden, int(d), b1, w2, b2, threshold, layer_ids, want_logits, want_mask, out)
+    _check(load_library().tide_select_exit_ws(_ptr(hidden), _dtype_code(hidden), C, T, int(d), keep[3], cs, rs, _ptr(gamma),
+                                              float(eps), _ptr(W1), _ptr(packed), _ptr(b1), _ptr(w2), b2p, thp, idp,
+                                              int(min_layer), int(no_exit_layer), _ptr(exit_layer), _ptr(logits), _ptr(mask),
+                                              _ptr(workspace),
+                                              workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                                              _stream()))
     del keep
     return exit_layer, logits, mask
 

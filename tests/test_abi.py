@@ -167,3 +167,54 @@ def test_exit_statistics_reproduce_fig3(golden_dir):
     hist = stats.exit_histogram(ex, [int(x) for x in g["router_layers"]], int(g["n_layers"][0]))
     assert hist == {"L8": 1, "L16": 1, "none": 1}
     assert stats.exit_rate(ex, 32) == pytest.approx(2 / 3)
+
+
+def test_workspace_size_query():
+    """Host arithmetic of tide_workspace_bytes: state words (a counter block + 8 bytes per token), the packed
+    weights of a raw-weight prefill call, the partial results of the split-k pair / the latency kernel."""
+    # one 128-row tile per CU (the 8B-shaped prefill): state only
+    assert tr.workspace_bytes(tr.BF16, 8, 4096, 4096) == 256 + 4096 * 8
+    # the same call on raw weights packs 8 routers inside the call
+    assert tr.workspace_bytes(tr.BF16, 8, 4096, 4096, raw_weights=True) == 256 + 4096 * 8 + 8 * tr.packed_router_bytes(tr.BF16, 4096)
+    # a decode step on packed weights: split-k pair, 32-row tiles x 8 slices -> 16.5 KiB per workgroup
+    assert tr.workspace_bytes(tr.F16, 8, 8, 4096) == 256 + 256 + 8 * 8 * (32 * 128 + 4 * 32) * 4
+    # ... on raw weights: the latency kernel, d/128 slices of 128 + 4 floats per row
+    assert tr.workspace_bytes(tr.F16, 8, 1, 4096, raw_weights=True) == 256 + 256 + 8 * 32 * 1 * 132 * 4
+    # multiples of 256, monotone in T for a fixed path, zero for unsupported shapes
+    for T in (1, 33, 500, 4096, 16384):
+        assert tr.workspace_bytes(tr.BF16, 9, T, 4096) % 256 == 0
+    assert tr.workspace_bytes(tr.BF16, 8, 4096, 100) == 0 and "unsupported" in tr.last_error()
+    assert tr.workspace_bytes(tr.BF16, 0, 4096, 4096) == 0 and tr.workspace_bytes(9, 8, 64, 4096) == 0
+
+
+def test_ws_entry_points_reject_bad_arguments():
+    lib = tr.load_library()
+    b2a, tha, ida = np.zeros(2, np.float32), np.full(2, .5, np.float32), np.asarray([3, 7], np.int32)
+    p = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+
+    def sel(W1=None, packed=FAKE, gamma=None, ws=0x20000, ws_bytes=1 << 20, exit_ptr=FAKE, T=4):
+        return lib.tide_select_exit_ws(FAKE, 2, 2, T, 256, 128, 1024, 256, gamma, 1e-6, W1, packed, None, FAKE, p(b2a), p(tha),
+                                       p(ida), 0, 32, exit_ptr, None, None, ws, ws_bytes, None)
+
+    def ev(W1=None, packed=FAKE, gamma=None, ws=0x20000, ws_bytes=1 << 20, T=4, rs=256):
+        return lib.tide_router_eval_ws(FAKE, 2, T, 256, 128, rs, gamma, 1e-6, W1, packed, None, FAKE, 0.0, 0.5, None, None, None,
+                                       ws, ws_bytes, None)
+
+    for call in (sel, ev):
+        assert call(W1=FAKE, packed=FAKE) == -1 and "exactly one" in tr.last_error()
+        assert call(W1=None, packed=None) == -1
+        assert call(gamma=FAKE) == -1 and "gamma" in tr.last_error()
+        assert call(ws=None) == -1 and call(ws_bytes=0) == -1
+        assert call(ws=0x20010) == -3 and "256" in tr.last_error()
+    assert sel(exit_ptr=None) == -1
+    assert ev(rs=128) == -1
+    # parameter arrays are read with 16-byte loads
+    assert lib.tide_router_eval(FAKE, 2, 4, 256, 128, 256, None, 1e-6, FAKE + 4, None, FAKE, 0.0, 0.5, None, None, None, None) == -3
+    assert lib.tide_router_eval(FAKE, 2, 4, 256, 128, 256, None, 1e-6, FAKE, None, FAKE + 8, 0.0, 0.5, None, None, None, None) == -3
+    assert lib.tide_router_eval(FAKE, 2, 4, 256, 128, 256, FAKE + 4, 1e-6, FAKE, None, FAKE, 0.0, 0.5, None, None, None, None) == -3
+    assert lib.tide_router_eval(FAKE, 2, 4, 256, 128, 256, None, 1e-6, FAKE, FAKE + 12, FAKE, 0.0, 0.5, None, None, None, None) == -3
+    # workspace registration
+    assert lib.tide_workspace_init(None, 4096, None) == -1
+    assert lib.tide_workspace_init(0x20000, 100, None) == -1
+    assert lib.tide_workspace_init(0x20010, 4096, None) == -3
+    assert lib.tide_workspace_forget(0x30000) == -1
