@@ -35,7 +35,7 @@
  *    never for theta >= 1 (the paper's "1.0 (off)", Table 4), always for theta <= 0.
  *  - Scratch memory.  The router entry points need some device memory of their own: a counter per
  *    checkpoint and one 64-bit arrival word per token (state: zero between calls), and for some
- *    shapes packed weights or partial results (data).  Two sources:
+ *    shapes packed weights or partial results (data).  Three sources:
  *      (1) the plain entry points use a per-device workspace that the library allocates (hipMalloc)
  *          on first use and when a larger problem arrives -- always before the call's first kernel
  *          is enqueued.  It is shared by every stream of the device: calls that use it must be
@@ -46,7 +46,8 @@
  *          capturing stream first and neither outgrow nor release the workspace while the graph lives;
  *      (2) the _ws entry points take a caller-owned workspace (tide_workspace_bytes,
  *          tide_workspace_init): nothing is allocated, and calls on different workspaces may run
- *          concurrently on different streams.
+ *          concurrently on different streams;
+ *      (3) tide_select_exit_packed_noalloc uses a fixed array inside the library.
  *  - On error nothing is enqueued, with one exception: if a kernel launch itself fails
  *    (TIDE_ERR_HIP) after an earlier kernel of the same call was enqueued, that earlier work stays
  *    enqueued; the scratch memory is then marked and re-initialised by the next call that uses it
@@ -183,6 +184,25 @@ int tide_select_exit_ws(const void* hidden, int dtype, int64_t C, int64_t T, int
                         const float* b2, const float* threshold, const int32_t* layer_ids,
                         int32_t min_layer, int32_t no_exit_layer, int32_t* exit_layer, float* logits,
                         uint32_t* fire_mask, void* workspace, size_t workspace_bytes, void* stream);
+
+/* tide_select_exit_packed for callers that cannot allocate: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same results, same kernels; the
+ * scratch memory is a fixed array of TIDE_NOALLOC_SCRATCH_BYTES inside the library (every GPU the
+ * library runs on holds its own copy until the process ends), and the call makes no allocating
+ * HIP or library call.  A shape that needs more scratch memory than the array holds
+ * (tide_workspace_bytes(..., 0) > tide_noalloc_scratch_bytes()) is refused with
+ * TIDE_ERR_WORKSPACE.  All calls on one GPU share that GPU's array: they must be ordered on one
+ * stream -- calls that overlap on one GPU race.  The array keeps the last call's contents; the
+ * state words a call needs to start from zero are cleared by a small kernel on `stream` whenever
+ * an earlier call may have left data there.                                                  */
+#define TIDE_NOALLOC_SCRATCH_BYTES (32u << 20)
+int tide_select_exit_packed_noalloc(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d,
+                                    int64_t b, int64_t ckpt_stride, int64_t row_stride,
+                                    const void* packed, float eps, const float* b1, const float* w2,
+                                    const float* b2, const float* threshold, const int32_t* layer_ids,
+                                    int32_t min_layer, int32_t no_exit_layer, int32_t* exit_layer,
+                                    float* logits, uint32_t* fire_mask, void* stream);
+size_t tide_noalloc_scratch_bytes(void);
 
 /* Exit projection: the rows the LM head consumes (Fig. 1 "LMHead(Norm(h_k))", Alg. 1 line 5,
  * Sec. 3.4 kernels 3-4).  out[t,:] = RMSNorm(src_t) * norm_gain, computed in fp32 and rounded

@@ -89,7 +89,8 @@ int g_prefill_form = 0;   // a form word (see valid_form_word): 0 auto; 1 / 2: s
                           // 3: register-ring form; 4: wide-tile form wherever it applies, on as many workgroups as there are
                           // whole tiles; 5: split-k pair (optionally with a forced shape); 6: one-tile form
 
-// Caller-owned workspaces (the _ws entry points) are single blocks laid out per call: state words first, data behind them.  A call with more
+// Caller-owned workspaces (the _ws entry points) and the static array of the no-allocation entry
+// point are single blocks laid out per call: state words first, data behind them.  A call with more
 // state words than an earlier one would find that call's data where it needs zeros, so the library
 // keeps, per block, how many leading bytes are known to hold zero state (`clean`): the whole block
 // after tide_workspace_init, at most the call's state bytes after a call that wrote data.
@@ -101,6 +102,17 @@ struct BlockRecord {
 constexpr int kMaxBlockRecords = 64;
 BlockRecord g_blocks[kMaxBlockRecords];
 uint64_t g_block_clock = 0;
+
+// The no-allocation entry point's scratch memory: every GPU the library runs on holds its own copy
+// of this array until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the address kernels and fills use is the per-device pointer kept below.
+constexpr size_t kStaticScratchBytes = (size_t)TIDE_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticScratchBytes];
+struct StaticScratch {
+    void* ptr = nullptr;            // device address of this device's copy
+    size_t clean = 0;               // as BlockRecord::clean (the array starts zero-filled)
+};
+StaticScratch g_static[kMaxDevices];
 
 // Grow-only device buffer.  Re-allocation frees the old block, which waits for the device.
 int reserve(Buffer& b, size_t bytes, bool zero) {
@@ -734,7 +746,7 @@ int launch_clear(void* ptr, size_t bytes, hipStream_t st) {      // ptr 16-byte 
     return TIDE_OK;
 }
 
-// One block (a caller's workspace) laid out for a call: state first, data behind.
+// One block (a caller's workspace or the static array) laid out for a call: state first, data behind.
 Scratch carve(void* block, const CallNeed& n, bool want_exit) {
     Scratch sc;
     char* base = (char*)block;
@@ -752,7 +764,7 @@ BlockRecord* find_block(void* ptr) {
 }
 
 // Where a call's scratch memory comes from.
-enum ScratchSource { kScratchLibrary, kScratchCaller };
+enum ScratchSource { kScratchLibrary, kScratchCaller, kScratchStatic };
 
 // Shared body of the compute entry points.  Exactly one of (W1) / (packed) is given.  Everything that
 // can fail for lack of memory or for a misused workspace happens before the first kernel is enqueued.
@@ -805,6 +817,23 @@ int run(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t 
         rec->stamp = ++g_block_clock;
         clean = &rec->clean;
         sc = carve(block, need, want_exit);
+    } else {
+        StaticScratch& ss = g_static[dev];
+        if (!ss.ptr) {              // once per device, with that device current
+            void* addr = nullptr;
+            TIDE_HIP(hipGetSymbolAddress(&addr, HIP_SYMBOL(g_static_scratch)));
+            ss.ptr = addr;
+            ss.clean = kStaticScratchBytes;          // device globals start zero-filled
+        }
+        if (need.total() > kStaticScratchBytes)
+            return fail(TIDE_ERR_WORKSPACE, "this call needs %zu bytes of scratch memory; the no-allocation entry point holds %zu "
+                        "(use the entry point with a caller-supplied workspace)", need.total(), kStaticScratchBytes);
+        if (need.state_bytes > ss.clean) {           // an earlier call's data lies where this one keeps state: clear it
+            if ((rc = launch_clear(ss.ptr, need.state_bytes, st))) return rc;
+            ss.clean = need.state_bytes;
+        }
+        clean = &ss.clean;
+        sc = carve(ss.ptr, need, want_exit);
     }
     // the data regions of this call overwrite whatever zero state lay behind its own state words
     if (clean && need.packed_bytes + need.part_bytes > 0 && *clean > need.state_bytes) *clean = need.state_bytes;
@@ -1000,6 +1029,17 @@ int tide_workspace_forget(void* workspace) {
     *rec = BlockRecord{};
     return TIDE_OK;
 }
+
+int tide_select_exit_packed_noalloc(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b,
+                                    int64_t ckpt_stride, int64_t row_stride, const void* packed, float eps, const float* b1,
+                                    const float* w2, const float* b2, const float* threshold, const int32_t* layer_ids,
+                                    int32_t min_layer, int32_t no_exit_layer, int32_t* exit_layer, float* logits,
+                                    uint32_t* fire_mask, void* stream) {
+    return select_front(hidden, dtype, C, T, d, b, ckpt_stride, row_stride, nullptr, eps, nullptr, packed, b1, w2, b2, threshold,
+                        layer_ids, min_layer, no_exit_layer, exit_layer, logits, fire_mask, stream, kScratchStatic, nullptr, 0);
+}
+
+size_t tide_noalloc_scratch_bytes(void) { return kStaticScratchBytes; }
 
 int tide_exit_project(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t ckpt_stride,
                       int64_t row_stride, const void* final_hidden, int64_t final_row_stride,

@@ -27,6 +27,7 @@ EXPORTS = (
     "tide_packed_router_bytes", "tide_router_pack", "tide_router_eval_packed",
     "tide_select_exit_packed", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_batch_compact", "tide_set_variant", "tide_set_prefill_form", "tide_prefill_plan", "tide_stream_schedule", "tide_release",
     "tide_workspace_bytes", "tide_workspace_init", "tide_workspace_forget", "tide_router_eval_ws", "tide_select_exit_ws",
+    "tide_select_exit_packed_noalloc", "tide_noalloc_scratch_bytes",
 )
 
 _lib = None
@@ -59,10 +60,12 @@ def load_library() -> ctypes.CDLL:
     lib.tide_router_eval_ws.argtypes = [vp, ci, i64, i64, i64, i64, vp, f32, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp, sz, vp]
     lib.tide_select_exit_ws.argtypes = [vp, ci, i64, i64, i64, i64, i64, i64, vp, f32, vp, vp, vp, vp, vp, vp, vp, i32, i32,
                                         vp, vp, vp, vp, sz, vp]
+    lib.tide_select_exit_packed_noalloc.argtypes = lib.tide_select_exit_packed.argtypes
     lib.tide_workspace_bytes.argtypes = [ci, i64, i64, i64, i64, ci]
     lib.tide_workspace_bytes.restype = sz
     lib.tide_workspace_init.argtypes = [vp, sz, vp]
     lib.tide_workspace_forget.argtypes = [vp]
+    lib.tide_noalloc_scratch_bytes.restype = sz
     lib.tide_packed_router_bytes.argtypes = [ci, i64, i64]
     lib.tide_packed_router_bytes.restype = ctypes.c_size_t
     lib.tide_router_pack.argtypes = [ci, i64, i64, i64, vp, vp, vp, vp]
@@ -76,7 +79,7 @@ def load_library() -> ctypes.CDLL:
     lib.tide_stream_schedule.argtypes = [ci, i64, i64, ci, ci, ci, ci, vp, ci]
     for name in ("tide_router_eval", "tide_router_eval_packed", "tide_select_exit", "tide_select_exit_packed",
                  "tide_router_pack", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_batch_compact", "tide_set_variant", "tide_set_prefill_form", "tide_release",
-                 "tide_router_eval_ws", "tide_select_exit_ws", "tide_workspace_init", "tide_workspace_forget"):
+                 "tide_router_eval_ws", "tide_select_exit_ws", "tide_select_exit_packed_noalloc", "tide_workspace_init", "tide_workspace_forget"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -297,6 +300,10 @@ def workspace_bytes(dtype: int, C: int, T: int, d: int, b: int = BOTTLENECK, *, 
     return int(load_library().tide_workspace_bytes(int(dtype), int(C), int(T), int(d), int(b), 1 if raw_weights else 0))
 
 
+def noalloc_scratch_bytes() -> int:
+    return int(load_library().tide_noalloc_scratch_bytes())
+
+
 def workspace_init(workspace: torch.Tensor) -> None:
     """Zero-fill a workspace (a CUDA uint8 tensor, 256-byte aligned) on the current stream and register it."""
     _check(load_library().tide_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
@@ -334,6 +341,19 @@ def select_exit_ws(hidden, gamma, eps, W1, packed, b1, w2, b2, threshold, layer_
                                               _ptr(workspace),
                                               workspace.numel() * workspace.element_size() if workspace is not None else 0,
                                               _stream()))
+    del keep
+    return exit_layer, logits, mask
+
+
+def select_exit_packed_noalloc(hidden, packed, eps, b1, w2, b2, threshold, layer_ids, min_layer, no_exit_layer, *, d, out):
+    """select_exit_packed on the library's fixed scratch array; `out` = (exit_layer, logits | None, fire_mask | None) must be
+    given (this binding allocates nothing either)."""
+    C, T, cs, rs, b2p, thp, idp, exit_layer, logits, mask, keep = _select_common(
+        hidden, int(d), b1, w2, b2, threshold, layer_ids, False, False, out)
+    _check(load_library().tide_select_exit_packed_noalloc(_ptr(hidden), _dtype_code(hidden), C, T, int(d), keep[3], cs, rs,
+                                                          _ptr(packed), float(eps), _ptr(b1), _ptr(w2), b2p, thp, idp,
+                                                          int(min_layer), int(no_exit_layer), _ptr(exit_layer), _ptr(logits),
+                                                          _ptr(mask), _stream()))
     del keep
     return exit_layer, logits, mask
 

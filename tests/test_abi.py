@@ -185,6 +185,7 @@ def test_workspace_size_query():
         assert tr.workspace_bytes(tr.BF16, 9, T, 4096) % 256 == 0
     assert tr.workspace_bytes(tr.BF16, 8, 4096, 100) == 0 and "unsupported" in tr.last_error()
     assert tr.workspace_bytes(tr.BF16, 0, 4096, 4096) == 0 and tr.workspace_bytes(9, 8, 64, 4096) == 0
+    assert tr.noalloc_scratch_bytes() == 32 << 20
 
 
 def test_ws_entry_points_reject_bad_arguments():
