@@ -7,14 +7,19 @@ T=4096 tokens x d=4096, seeded synthetic hidden states already resident in HBM),
 the C ABI call tide_select_exit (raw fp32 router weights: the gain fold / weight packing
 pass is inside the timed region).  Prints ONE JSON line.
 
-  value      tokens/s through all C checkpoints (whole job, inputs resident)
+  value      tokens/s through all C checkpoints (whole job, inputs resident): exactly --steps
+             steps between two synchronisations, wall clock
   roofline   the prefill kernel alone (tide_select_exit_packed = exactly one launch per
              step), algorithmic bytes / HIP-event time per launch, against 8 TB/s
   cpu_baseline  the fp64 oracle on the same workload on this machine's host cores
-  decode     config-2 latency (fp16, T=1 and T=8), us per call
+  decode     config-2 latency (fp16, T=1 and T=8), us per call: warm (back to back) and cold
+  sweep      configs[4]: d x dtype at T=16384, C=10 on packed weights
 
-Input buffers rotate so that consecutive steps never re-read a buffer that could still
-sit in the 256 MB last-level cache.
+Every timed loop is cut into windows by HIP events; a window that takes more than 1.5 times
+the median window is listed as a stall (the device idling between two launches: not kernel
+time), and figures derived from a loop say whether they are the plain mean or the mean over
+the windows that are not stalls.  Input buffers rotate so that consecutive steps never
+re-read a buffer that could still sit in the 256 MB last-level cache.
 """
 import argparse
 import json
@@ -39,6 +44,7 @@ def main() -> int:
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the steps around the path (exit projection, calibration labels, other bottleneck widths)")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the hidden-size x dtype sweep (configs[4])")
     ap.add_argument("--no-settle", action="store_true", help="skip the untimed settling phase (short profiler runs)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 256 MiB device copy 3 times (known traffic, scales the profiler's "
@@ -93,13 +99,23 @@ def main() -> int:
     def step_packed(i):
         packed_calls[i % args.buffers]()
 
-    def timed(step, steps, warmup, window=16):
-        """K steps between two synchronisations.  The host keeps at most ~2*window launches
-        queued ahead of the GPU (it waits on an event recorded `window` steps earlier), so the
-        runtime's submission queue never fills and the figure is the GPU's own throughput."""
+    def timed(step, steps, warmup, window=None):
+        """`steps` steps between two synchronisations, cut into windows of `window` steps by HIP events
+        (at least four windows).  The host keeps at most ~2 windows of launches queued ahead of the GPU
+        (it waits on the event recorded two windows earlier), so the runtime's submission queue never
+        fills and the figures are the GPU's own.  Returns a dict, times in seconds per step:
+          wall    wall clock / steps (host clock around the whole loop, both synchronisations included)
+          mean    HIP-event time of the whole loop / steps
+          median  median over the windows;  best, p90 likewise
+          clean   mean over the windows that are not stalls (stall: more than 1.5 x the median window)
+          stalls  [{window, us_per_step}] of the stalled windows;  allocations: device allocations the
+                  library made inside the loop (0: a stall does not coincide with one of ours)"""
+        if window is None:
+            window = max(1, min(16, steps // 4))
         for i in range(warmup):
             step(i)
         torch.cuda.synchronize()
+        allocs0 = tr.workspace_allocations()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         marks = []
         t0 = time.perf_counter()
@@ -115,25 +131,35 @@ def main() -> int:
         e1.record()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
-        # per-step time of every full window of `window` steps (spread of the measurement)
         edges = [e0] + marks
-        per_window = sorted(edges[k].elapsed_time(edges[k + 1]) * 1e-3 / window for k in range(len(edges) - 1))
-        timed.windows = per_window
-        return wall, e0.elapsed_time(e1) * 1e-3
+        per_window = [edges[k].elapsed_time(edges[k + 1]) * 1e-3 / window for k in range(len(edges) - 1)]
+        mean = e0.elapsed_time(e1) * 1e-3 / steps
+        if not per_window:
+            per_window = [mean]
+        srt = sorted(per_window)
+        median = srt[len(srt) // 2]
+        stalls = [{"window": k, "us_per_step": round(v * 1e6, 2)} for k, v in enumerate(per_window) if v > 1.5 * median]
+        good = [v for v in per_window if v <= 1.5 * median]
+        return {"wall": wall / steps, "mean": mean, "median": median, "best": srt[0],
+                "p10": srt[min(len(srt) - 1, len(srt) // 10)], "p90": srt[min(len(srt) - 1, (9 * len(srt)) // 10)],
+                "clean": sum(good) / len(good), "windows": len(per_window), "steps_per_window": window, "steps": steps,
+                "stalls": stalls, "allocations": tr.workspace_allocations() - allocs0}
 
-    def sp_pct(ws, q):
-        return ws[min(len(ws) - 1, int(q * len(ws)))]
+    def spread(r, us_scale=1e6):
+        s = {"mean": round(r["mean"] * us_scale, 2), "median_window": round(r["median"] * us_scale, 2),
+             "best_window": round(r["best"] * us_scale, 2), "p90_window": round(r["p90"] * us_scale, 2),
+             "windows": r["windows"], "steps_per_window": r["steps_per_window"]}
+        if r["stalls"]:
+            s["stalls"] = r["stalls"]
+            s["library_allocations_in_loop"] = r["allocations"]
+        return s
 
-    def spread(us_scale=1e6):
-        ws = timed.windows
-        if not ws:
-            return {}
-        return {"median": round(ws[len(ws) // 2] * us_scale, 2), "best": round(ws[0] * us_scale, 2),
-                "p90": round(ws[min(len(ws) - 1, (9 * len(ws)) // 10)] * us_scale, 2), "windows": len(ws),
-                "steps_per_window": 16}
+    def hbm(nbytes, seconds):
+        gbs = nbytes / seconds / 1e9
+        return {"gbs": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
 
-    # Settle: a one-time stall of ~30 ms was observed early in a process's GPU life (the device
-    # idles between two launches; not kernel time).  Run untimed work past it before timing.
+    # Settle: a stall of some tens of milliseconds between two launches is seen now and then, mostly
+    # early in a process's GPU life (the device idles; not kernel time).  Run untimed work first.
     t_settle = time.perf_counter()
     if args.copy_probe:
         src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device="cuda")
@@ -148,17 +174,18 @@ def main() -> int:
             step_packed(i)
         torch.cuda.synchronize()
 
-    wall_raw, ev_raw = timed(step_raw, args.steps, args.warmup)
-    spread_raw = spread()
-    wall_pk, ev_pk = timed(step_packed, args.steps, args.warmup)
-    spread_pk = spread()
+    # ---- the headline: exactly --steps steps of the raw-weight call
+    r_raw = timed(step_raw, args.steps, args.warmup)
+    # ---- the prefill kernel alone: one launch per packed step; at least 256 launches so that the figure
+    # does not rest on a handful of them
+    n_roof = max(args.steps, 256)
+    r_pk = timed(step_packed, n_roof, args.warmup)
 
     # what this machine's memory system gives a plain device-to-device copy of one batch (256 MiB read
     # + 256 MiB written), source and destination rotated like the inputs: the "achievable" figure
     copy_dst = [torch.empty_like(batches[0]) for _ in range(2)]
-    n_copy = max(20, args.steps // 4)
-    _, ev_cp = timed(lambda i: copy_dst[i & 1].copy_(batches[i % args.buffers]), n_copy, 5)
-    copy_gbs = 2.0 * batches[0].numel() * 2 / (ev_cp / n_copy) / 1e9
+    r_cp = timed(lambda i: copy_dst[i & 1].copy_(batches[i % args.buffers]), 64, 5)
+    copy_gbs = 2.0 * batches[0].numel() * 2 / r_cp["clean"] / 1e9
     del copy_dst
 
     ex = out[0].cpu().numpy()
@@ -177,13 +204,14 @@ def main() -> int:
     # ---- roofline of the prefill kernel: one launch per packed step
     esz = 2
     alg_bytes = C * T * d * esz + C * d * 128 * esz + T * (4 + 4) + C * T * 4
-    t_launch = ev_pk / args.steps
+    t_launch = r_pk["clean"]
     achieved = alg_bytes / t_launch / 1e9
     flops = 2.0 * d * 128 * C * T
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "kernel": "tide_prefill_tile_kernel<bf16> (one 128-row tile per workgroup)", "us_per_launch": round(t_launch * 1e6, 2),
-                "us_per_launch_spread": spread_pk,
+                "us_per_launch_is": f"mean over the windows without a stall of {n_roof} back-to-back launches (HIP events)",
+                "us_per_launch_spread": spread(r_pk),
                 "device_copy_gbs": round(copy_gbs, 1), "frac_of_device_copy": round(achieved / copy_gbs, 4),
                 "algorithmic_bytes_per_launch": alg_bytes,
                 "mfma_tflops": round(flops / t_launch / 1e12, 1),
@@ -191,9 +219,9 @@ def main() -> int:
 
     result = {
         "metric": "tokens/sec + % HBM peak, fused RMSNorm+router d=4096 bf16; decode us/call",
-        "value": round(T * args.steps / wall_raw, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(wall_raw / args.steps * 1e3, 5),
-        "us_per_step_spread": spread_raw, "higher_is_better": True,
+        "value": round(T / r_raw["wall"], 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(r_raw["wall"] * 1e3, 5),
+        "us_per_step_spread": spread(r_raw), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "paper_context": "end-to-end model figures on one A100, bf16 (Table 3): DeepSeek R1 Distill 8B prefill latency -7.2 %, "
                          "throughput +6.6 % at batch 1; Qwen3 8B throughput +8.1 % at batch 8 -- not kernel figures, hence vs_baseline null",
@@ -201,36 +229,35 @@ def main() -> int:
                                "T=4096 tokens, ~30% firing per checkpoint", "C": C, "T": T, "d": d,
                    "entry_point": "tide_select_exit (raw fp32 router weights; gain fold + packing inside the step)",
                    "input_buffers_rotated": args.buffers},
-        "rows_per_s": round(C * T * args.steps / wall_raw, 1),
-        "packed_weights": {"entry_point": "tide_select_exit_packed", "tokens_per_s": round(T * args.steps / wall_pk, 1),
-                           "ms_per_step": round(wall_pk / args.steps * 1e3, 5)},
+        "rows_per_s": round(C * T / r_raw["wall"], 1),
+        "tokens_per_s_median_window": round(T / r_raw["median"], 1),
+        "packed_weights": {"entry_point": "tide_select_exit_packed", "tokens_per_s": round(T / r_pk["clean"], 1),
+                           "ms_per_step": round(r_pk["clean"] * 1e3, 5)},
         "exit_histogram": hist,
         "roofline": roofline,
     }
 
     if not args.no_extras:
+        n_x = max(args.steps, 100)
         # ---- exit projection (the step after the path: rows for the LM head), same workload
         final_h = torch.from_numpy(synth.make_hidden(w.cfg + 7, 1, T, d, w.dtype)[0].view(np.int16)).cuda().view(torch.bfloat16)
         norm_gain = torch.ones(d, dtype=torch.float32, device="cuda")
         proj_out = torch.empty((T, d), dtype=torch.bfloat16, device="cuda")
         pj_calls = [tr.prepare_exit_project(b, final_h, out[0], w.layer_ids, norm_gain, 1e-6, out=proj_out) for b in batches]
-        wall_pj, ev_pj = timed(lambda i: pj_calls[i % args.buffers](), args.steps, args.warmup)
+        r_pj = timed(lambda i: pj_calls[i % args.buffers](), n_x, 10)
         pj_bytes = 2 * T * d * esz + 4 * T + 4 * d
-        result["exit_projection"] = {"entry_point": "tide_exit_project", "us_per_call": round(ev_pj / args.steps * 1e6, 2),
-                                     "algorithmic_bytes": pj_bytes, "gbs": round(pj_bytes / (ev_pj / args.steps) / 1e9, 1),
-                                     "frac_of_hbm_peak": round(pj_bytes / (ev_pj / args.steps) / 1e9 / HBM_PEAK_GBS, 4)}
+        result["exit_projection"] = {"entry_point": "tide_exit_project", "us_per_call": round(r_pj["clean"] * 1e6, 2),
+                                     "algorithmic_bytes": pj_bytes, **hbm(pj_bytes, r_pj["clean"])}
 
         # ---- calibration labels (the step before the path: Eq. 1), same shapes
         cos_out = (torch.empty((C, T), dtype=torch.float32, device="cuda"), torch.empty((C, T), dtype=torch.uint8, device="cuda"))
 
         def cos_call(i):
             tr.cosine_labels(batches[i % args.buffers], final_h, 0.98, out=cos_out)
-        n_cos = max(20, args.steps // 4)
-        wall_cs, ev_cs = timed(cos_call, n_cos, 5)
+        r_cs = timed(cos_call, n_x, 5)
         cs_bytes = (C + 1) * T * d * esz + 5 * C * T
-        result["calibration_labels"] = {"entry_point": "tide_cosine_labels", "us_per_call": round(ev_cs / n_cos * 1e6, 2),
-                                        "algorithmic_bytes": cs_bytes, "gbs": round(cs_bytes / (ev_cs / n_cos) / 1e9, 1),
-                                        "frac_of_hbm_peak": round(cs_bytes / (ev_cs / n_cos) / 1e9 / HBM_PEAK_GBS, 4)}
+        result["calibration_labels"] = {"entry_point": "tide_cosine_labels", "us_per_call": round(r_cs["clean"] * 1e6, 2),
+                                        "algorithmic_bytes": cs_bytes, **hbm(cs_bytes, r_cs["clean"])}
 
         # ---- the other bottleneck widths of the paper's kernel specialisations (Table 2), same token count
         widths = {}
@@ -243,16 +270,14 @@ def main() -> int:
             pkb = tr.router_pack(tr.BF16, None, Wb)
             cb = [tr.prepare_select_exit_packed(h, pkb, w.eps, None, w2b, 0.0, 0.5, w.layer_ids, 0, w.n_layers, d=dd, out=out)
                   for h in hbs]
-            n_w = max(20, args.steps // 4)
-            _, ev_w = timed(lambda i: cb[i % nb](), n_w, 5)
+            r_w = timed(lambda i: cb[i % nb](), n_x, 5)
             by = C * T * dd * esz + C * dd * bb * esz + T * 8 + C * T * 4
-            widths[f"d{dd}_b{bb}"] = {"us_per_call": round(ev_w / n_w * 1e6, 2), "algorithmic_bytes": by,
-                                      "gbs": round(by / (ev_w / n_w) / 1e9, 1),
-                                      "frac_of_hbm_peak": round(by / (ev_w / n_w) / 1e9 / HBM_PEAK_GBS, 4)}
+            widths[f"d{dd}_b{bb}"] = {"us_per_call": round(r_w["clean"] * 1e6, 2), "us_per_call_median_window": round(r_w["median"] * 1e6, 2),
+                                      "algorithmic_bytes": by, **hbm(by, r_w["clean"])}
             del hbs, cb, pkb, Wb
         result["bottleneck_widths"] = {"workload": f"Table 2 pairs with b != 128: bf16, C={C}, T={T}, packed weights", **widths}
 
-        # ---- configs[3]: the 36-layer batched prefill (C=9, T=8x2048), where whole rounds of 256-row tiles exist
+        # ---- configs[3]: the 36-layer batched prefill (C=9, T=8x2048)
         w3 = synth.config3()
         gen3 = torch.Generator(device="cuda").manual_seed(0x71DE + 3)
         hb3 = [torch.randn((w3.C, w3.T, d), generator=gen3, device="cuda").to(torch.bfloat16) for _ in range(2)]
@@ -263,21 +288,60 @@ def main() -> int:
                 torch.empty(w3.T, dtype=torch.int32, device="cuda"))
         c3 = [tr.prepare_select_exit_packed(h, pk3, w3.eps, None, w23, 0.0, 0.5, w3.layer_ids, 0, w3.n_layers, d=d, out=out3)
               for h in hb3]
-        n3 = max(20, args.steps // 5)
-        _, ev3 = timed(lambda i: c3[i & 1](), n3, 5)
+        r3 = timed(lambda i: c3[i & 1](), n_x, 5)
         by3 = w3.C * w3.T * d * esz + w3.C * d * 128 * esz + w3.T * 8 + w3.C * w3.T * 4
-        result["large_batch"] = {"workload": "configs[3]: bf16, d=4096, 36 layers, C=9, T=16384 (8 x 2048), packed weights; "
-                                             "wide-tile kernel for two rounds of 256-row tiles + 64-row kernel for the rest",
-                                 "us_per_call": round(ev3 / n3 * 1e6, 2), "tokens_per_s": round(w3.T / (ev3 / n3), 1),
-                                 "algorithmic_bytes": by3, "gbs": round(by3 / (ev3 / n3) / 1e9, 1),
-                                 "frac_of_hbm_peak": round(by3 / (ev3 / n3) / 1e9 / HBM_PEAK_GBS, 4)}
+        plan3 = tr.prefill_plan(tr.BF16, w3.C, w3.T, d, 128, cus=torch.cuda.get_device_properties(0).multi_processor_count & ~7)
+        result["large_batch"] = {"workload": "configs[3]: bf16, d=4096, 36 layers, C=9, T=16384 (8 x 2048), packed weights",
+                                 "launches": [{k: L[k] for k in ("kernel", "rows_per_tile", "total_tiles", "tile_begin", "workgroups")} for L in plan3],
+                                 "us_per_call": round(r3["clean"] * 1e6, 2), "us_per_call_median_window": round(r3["median"] * 1e6, 2),
+                                 "tokens_per_s": round(w3.T / r3["clean"], 1),
+                                 "algorithmic_bytes": by3, **hbm(by3, r3["clean"])}
         del hb3, c3
+
+    # ---- configs[4]: hidden size x storage type at T = 16384, C = 10, packed weights.  fp32 rows reach the
+    # matrix cores as two bf16 terms per value and three bf16 products per pair, so the matrix-core work
+    # issued is 3 x 2 d 128 flops per row on the bf16 units; the fp32 MFMA peak is quoted for context only.
+    if not args.no_sweep:
+        sweep = {}
+        Ts, Cs = 16384, 10
+        gen4 = torch.Generator(device="cuda").manual_seed(0x71DE + 4)
+        outs = (torch.empty(Ts, dtype=torch.int32, device="cuda"), torch.empty((Cs, Ts), dtype=torch.float32, device="cuda"),
+                torch.empty(Ts, dtype=torch.int32, device="cuda"))
+        for dd in synth.SWEEP_D:
+            ids4 = synth.config4(dd, "bf16").layer_ids
+            n_layers4 = synth.config4(dd, "bf16").n_layers
+            W4 = torch.randn((Cs, dd, 128), generator=gen4, device="cuda") / dd ** 0.5
+            w24 = torch.randn((Cs, 128), generator=gen4, device="cuda") / 128 ** 0.5
+            for name, tdt, code, es in (("bf16", torch.bfloat16, tr.BF16, 2), ("f16", torch.float16, tr.F16, 2), ("f32", torch.float32, tr.F32, 4)):
+                nbuf = 3 if Cs * Ts * dd * es < (300 << 20) else 2     # never re-read what the 256 MB last-level cache may hold
+                hs = [torch.randn((Cs, Ts, dd), generator=gen4, device="cuda").to(tdt) for _ in range(nbuf)]
+                pk4 = tr.router_pack(code, None, W4)
+                c4 = [tr.prepare_select_exit_packed(h, pk4, 1e-6, None, w24, 0.0, 0.5, ids4, 0, n_layers4, d=dd, out=outs) for h in hs]
+                r4 = timed(lambda i: c4[i % nbuf](), 48, 6, window=8)
+                by4 = Cs * Ts * dd * es + Cs * dd * 128 * es + Ts * 8 + Cs * Ts * 4
+                fl4 = 2.0 * dd * 128 * Cs * Ts
+                point = {"us_per_call": round(r4["clean"] * 1e6, 1), "us_per_call_median_window": round(r4["median"] * 1e6, 1),
+                         **hbm(by4, r4["clean"])}
+                if name == "f32":
+                    point["mfma_frac_of_bf16_peak_issued"] = round(3 * fl4 / r4["clean"] / 1e12 / MFMA_PEAK_TFLOPS["bf16"], 4)
+                    point["algorithmic_tflops_vs_fp32_mfma_peak"] = round(fl4 / r4["clean"] / 1e12 / MFMA_PEAK_TFLOPS["f32"], 3)
+                else:
+                    point["mfma_frac_of_peak"] = round(fl4 / r4["clean"] / 1e12 / MFMA_PEAK_TFLOPS[name], 4)
+                if r4["stalls"]:
+                    point["stalls"] = r4["stalls"]
+                sweep[f"d{dd}_{name}"] = point
+                del hs, c4, pk4
+            del W4
+        result["sweep"] = {"workload": f"configs[4]: T={Ts}, C={Cs}, b=128, packed weights, random rows, 48 back-to-back calls on "
+                                       "rotating inputs; d=8192 is the 80-layer point", **sweep}
 
     # ---- decode latency (config 2): fp16, T = 1 and 8.  Router weights are static at inference, so the
     # serving loop's call is the one on pre-packed weights (automatic choice: the split-k pair on the
     # matrix cores); the raw-weight call (fp32 W1, latency kernel, no packing pass) is timed beside it.
     if not args.no_decode:
         dec = {}
+        evict_src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")
+        evict_dst = torch.empty_like(evict_src)
         for Td in (1, 8):
             wd = synth.config2(Td)
             hd = torch.from_numpy(wd.hidden()).cuda()
@@ -286,9 +350,7 @@ def main() -> int:
             pk16 = tr.router_pack(tr.F16, g, W1)
             prep_pk = tr.prepare_select_exit_packed(hd, pk16, wd.eps, b1, w2, rt.b2, rt.theta, wd.layer_ids, 0, wd.n_layers,
                                                     d=d, out=outd)
-            wall, ev = timed(lambda i: prep_pk(), 2000, 200)
-            sp = spread()
-            p10 = round(sp_pct(timed.windows, 0.1) * 1e6, 2)
+            r_d = timed(lambda i: prep_pk(), 2000, 200, window=16)
             # latency of a single call as a caller that needs the answer sees it: call, then wait
             lat = []
             for _ in range(1000):
@@ -297,10 +359,23 @@ def main() -> int:
                 torch.cuda.synchronize()
                 lat.append(time.perf_counter() - t0)
             lat.sort()
+            # cold: in a serving loop the model's own layers run between two router calls and evict the
+            # router weights from L2 and the last-level cache.  A 512 MiB device copy stands in for them;
+            # each call is timed on its own by a pair of HIP events.
+            cold = []
+            for _ in range(60):
+                evict_dst.copy_(evict_src)
+                ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                ea.record()
+                prep_pk()
+                eb.record()
+                eb.synchronize()
+                cold.append(ea.elapsed_time(eb) * 1e3)
+            cold.sort()
             # the raw-weight call
             prepared = tr.prepare_select_exit(hd, g, wd.eps, W1, b1, w2, rt.b2, rt.theta, wd.layer_ids, 0, wd.n_layers,
                                               out=outd)
-            wall_r, _ = timed(lambda i: prepared(), 2000, 200)
+            r_r = timed(lambda i: prepared(), 2000, 200, window=16)
             # the packed call captured in a HIP graph (what a decode loop would replay every step)
             cap_stream = torch.cuda.Stream()
             graph = torch.cuda.CUDAGraph()
@@ -313,7 +388,7 @@ def main() -> int:
                 with torch.cuda.graph(graph, stream=cap_stream):
                     prep_g()
             torch.cuda.synchronize()
-            wall_g, _ = timed(lambda i: graph.replay(), 2000, 200)
+            r_g = timed(lambda i: graph.replay(), 2000, 200, window=16)
             lat_g = []
             for _ in range(1000):
                 t0 = time.perf_counter()
@@ -321,20 +396,27 @@ def main() -> int:
                 torch.cuda.synchronize()
                 lat_g.append(time.perf_counter() - t0)
             lat_g.sort()
-            dec[f"T{Td}"] = {"us_per_call": round(wall / 2000 * 1e6, 2), "calls_per_s": round(2000 / wall, 1),
+            dec[f"T{Td}"] = {"us_per_call": round(r_d["wall"] * 1e6, 2), "calls_per_s": round(1.0 / r_d["wall"], 1),
                              "entry_point": "tide_select_exit_packed (fp16 packed weights; split-k pair, two launches)",
-                             "us_per_call_hip_events": round(ev / 2000 * 1e6, 2),
-                             "us_per_call_spread": {"p10": p10, "median": sp["median"],
-                                                    "p90": sp["p90"], "windows": sp["windows"], "calls_per_window": 16},
+                             "cache_state": "warm: the same 8 MiB of packed routers and the same rows are re-read back to back "
+                                            "and stay in L2 / the last-level cache",
+                             "us_per_call_hip_events": round(r_d["mean"] * 1e6, 2),
+                             "us_per_call_spread": {"p10": round(r_d["p10"] * 1e6, 2), "median": round(r_d["median"] * 1e6, 2),
+                                                    "p90": round(r_d["p90"] * 1e6, 2), "windows": r_d["windows"], "calls_per_window": 16},
                              "us_call_plus_sync": {"p10": round(lat[100] * 1e6, 2), "median": round(lat[500] * 1e6, 2),
                                                    "p90": round(lat[900] * 1e6, 2), "calls": 1000},
+                             "cold": {"us_per_call": {"p10": round(cold[6], 2), "median": round(cold[30], 2), "p90": round(cold[54], 2)},
+                                      "calls": 60, "note": "a 512 MiB device copy before every call (evicts the router weights), "
+                                                           "each call between its own pair of HIP events"},
                              "raw_weights": {"entry_point": "tide_select_exit (fp32 W1; latency kernel, one launch)",
-                                             "us_per_call": round(wall_r / 2000 * 1e6, 2)},
-                             "hip_graph": {"us_per_replay": round(wall_g / 2000 * 1e6, 2),
+                                             "us_per_call": round(r_r["wall"] * 1e6, 2)},
+                             "hip_graph": {"us_per_replay": round(r_g["wall"] * 1e6, 2),
                                            "us_replay_plus_sync_median": round(lat_g[500] * 1e6, 2),
                                            "note": "the packed call captured as a graph of its two kernels"}}
+        del evict_src, evict_dst
         result["decode"] = {"workload": "configs[2]: fp16, d=4096, C=8, back-to-back calls on one stream "
-                                        "(us_per_call) and one call then a stream synchronisation (us_call_plus_sync)", **dec}
+                                        "(us_per_call), one call then a stream synchronisation (us_call_plus_sync), and "
+                                        "one call after the caches were flushed (cold)", **dec}
 
     # ---- the call a serving loop makes at ONE checkpoint layer (C = 1) on batches of several sizes
     if not args.no_extras:
@@ -346,18 +428,16 @@ def main() -> int:
                     torch.empty(Tp, dtype=torch.int32, device="cuda"))
             c1 = [tr.prepare_select_exit_packed(h, packed, w.eps, b1[:1], w2[:1], rt.b2[:1], rt.theta[:1], w.layer_ids[:1], 0,
                                                 w.n_layers, d=d, out=out1) for h in hb1]
-            n1c = 400
-            _, ev1 = timed(lambda i: c1[i % nb1](), n1c, 40)
+            r1 = timed(lambda i: c1[i % nb1](), 400, 40, window=16)
             by1 = Tp * d * 2 + d * 128 * 2
-            med1 = spread()["median"]           # per call, median over windows of 16 calls: robust against a one-time stall
-            per[f"T{Tp}"] = {"us_per_call": round(ev1 / n1c * 1e6, 2), "us_per_call_median_window": med1,
-                             "gbs": round(by1 / (med1 * 1e-6) / 1e9, 1)}
-            if ev1 / n1c * 1e6 > 1.5 * med1:
-                per[f"T{Tp}"]["note"] = (f"the mean includes a stall of {(ev1 - n1c * med1 * 1e-6) * 1e3:.0f} ms between two launches "
-                                         "(seen once per process now and then, whatever runs); the median is the call's time")
+            per[f"T{Tp}"] = {"us_per_call": round(r1["mean"] * 1e6, 2), "us_per_call_median_window": round(r1["median"] * 1e6, 2),
+                             **hbm(by1, r1["median"])}
+            if r1["stalls"]:
+                per[f"T{Tp}"]["stalls"] = r1["stalls"]
+                per[f"T{Tp}"]["library_allocations_in_loop"] = r1["allocations"]
             del hb1, c1
         result["per_checkpoint_call"] = {"workload": "one checkpoint (C=1) of the 8B shape: bf16, d=4096, packed weights, "
-                                                     "random rows, back-to-back calls on rotating inputs", **per}
+                                                     "random rows, back-to-back calls on rotating inputs; gbs from the median window", **per}
 
         # ---- earliest-exit semantics need fewer rows than the dense call reads: a token's rows beyond its first
         # firing checkpoint are never needed.  A layer-skipping runtime gets that by calling the router at each
@@ -377,14 +457,13 @@ def main() -> int:
         def run_schedule(i):
             for call in sched:
                 call()
-        n_sc = 200
-        _, ev_sc = timed(run_schedule, n_sc, 20)
+        r_sc = timed(run_schedule, 200, 20, window=10)
         result["short_circuit_schedule"] = {
             "workload": f"C={C} calls of tide_select_exit_packed with C=1 on T*0.7^c rows (c = 0..{C - 1}), back to back; "
                         "no compaction pass in the timed region",
-            "us_per_schedule": round(ev_sc / n_sc * 1e6, 2), "rows_evaluated": rows_sc, "rows_dense": C * T,
+            "us_per_schedule": round(r_sc["clean"] * 1e6, 2), "rows_evaluated": rows_sc, "rows_dense": C * T,
             "algorithmic_bytes": rows_sc * d * 2 + C * d * 128 * 2,
-            "tokens_per_s": round(T / (ev_sc / n_sc), 1),
+            "tokens_per_s": round(T / r_sc["clean"], 1),
             "note": "fewer bytes, more launches: on resident data the dense single launch is faster; the schedule is what "
                     "true layer skipping calls, one call per checkpoint layer"}
 

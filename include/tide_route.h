@@ -204,6 +204,10 @@ int tide_select_exit_packed_noalloc(const void* hidden, int dtype, int64_t C, in
                                     float* logits, uint32_t* fire_mask, void* stream);
 size_t tide_noalloc_scratch_bytes(void);
 
+/* Number of device allocations (hipMalloc) the library has made in this process, all for its own
+ * workspace (source (1) above): lets a caller check that a loop of calls allocates nothing.   */
+uint64_t tide_workspace_allocations(void);
+
 /* Exit projection: the rows the LM head consumes (Fig. 1 "LMHead(Norm(h_k))", Alg. 1 line 5,
  * Sec. 3.4 kernels 3-4).  out[t,:] = RMSNorm(src_t) * norm_gain, computed in fp32 and rounded
  * once to `dtype`, where src_t = hidden[c,t,:] for the checkpoint c with

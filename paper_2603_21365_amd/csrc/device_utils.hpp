@@ -298,6 +298,9 @@ __device__ __forceinline__ bool last_arrival(uint32_t* counter, uint32_t expecte
         *flag_lds = (prev == expected - 1);
     }
     __syncthreads();
+    // the caller's stage_load()s must stay behind the counter update: relaxed atomics on other
+    // addresses carry no order of their own, so the compiler is told (the hardware issues in order)
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
     return *flag_lds != 0;
 }
 

@@ -102,6 +102,7 @@ struct BlockRecord {
 constexpr int kMaxBlockRecords = 64;
 BlockRecord g_blocks[kMaxBlockRecords];
 uint64_t g_block_clock = 0;
+uint64_t g_allocations = 0;       // hipMalloc calls made by the library so far (tide_workspace_allocations)
 
 // The no-allocation entry point's scratch memory: every GPU the library runs on holds its own copy
 // of this array until the process ends.  In host code the array's name is only a handle for
@@ -130,6 +131,7 @@ int reserve(Buffer& b, size_t bytes, bool zero) {
         return fail(TIDE_ERR_WORKSPACE, "workspace hipMalloc(%zu): %s", want, hipGetErrorString(e));
     }
     b.bytes = want;
+    ++g_allocations;
     if (zero) {
         e = hipMemset(b.ptr, 0, want);
         if (e != hipSuccess) return fail(TIDE_ERR_HIP, "hipMemset: %s", hipGetErrorString(e));
@@ -1040,6 +1042,11 @@ int tide_select_exit_packed_noalloc(const void* hidden, int dtype, int64_t C, in
 }
 
 size_t tide_noalloc_scratch_bytes(void) { return kStaticScratchBytes; }
+
+uint64_t tide_workspace_allocations(void) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    return g_allocations;
+}
 
 int tide_exit_project(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t ckpt_stride,
                       int64_t row_stride, const void* final_hidden, int64_t final_row_stride,

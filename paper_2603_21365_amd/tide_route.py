@@ -27,7 +27,7 @@ EXPORTS = (
     "tide_packed_router_bytes", "tide_router_pack", "tide_router_eval_packed",
     "tide_select_exit_packed", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_batch_compact", "tide_set_variant", "tide_set_prefill_form", "tide_prefill_plan", "tide_stream_schedule", "tide_release",
     "tide_workspace_bytes", "tide_workspace_init", "tide_workspace_forget", "tide_router_eval_ws", "tide_select_exit_ws",
-    "tide_select_exit_packed_noalloc", "tide_noalloc_scratch_bytes",
+    "tide_select_exit_packed_noalloc", "tide_noalloc_scratch_bytes", "tide_workspace_allocations",
 )
 
 _lib = None
@@ -66,6 +66,7 @@ def load_library() -> ctypes.CDLL:
     lib.tide_workspace_init.argtypes = [vp, sz, vp]
     lib.tide_workspace_forget.argtypes = [vp]
     lib.tide_noalloc_scratch_bytes.restype = sz
+    lib.tide_workspace_allocations.restype = ctypes.c_uint64
     lib.tide_packed_router_bytes.argtypes = [ci, i64, i64]
     lib.tide_packed_router_bytes.restype = ctypes.c_size_t
     lib.tide_router_pack.argtypes = [ci, i64, i64, i64, vp, vp, vp, vp]
@@ -302,6 +303,11 @@ def workspace_bytes(dtype: int, C: int, T: int, d: int, b: int = BOTTLENECK, *, 
 
 def noalloc_scratch_bytes() -> int:
     return int(load_library().tide_noalloc_scratch_bytes())
+
+
+def workspace_allocations() -> int:
+    """Device allocations the library has made so far in this process (all for its own workspace)."""
+    return int(load_library().tide_workspace_allocations())
 
 
 def workspace_init(workspace: torch.Tensor) -> None:

@@ -102,5 +102,9 @@ def check_self_consistent(name, z_gpu, exit_gpu, mask_gpu, theta, layer_ids, min
     assert np.array_equal(want, np.asarray(exit_gpu)), f"{name}: GPU exit_layer is not the earliest eligible set bit of its fire_mask"
 
 
+REPORTS: list = []      # every comparison reported in this process; conftest.py prints their summary at the end of the run
+
+
 def report(stats: dict) -> None:
+    REPORTS.append(dict(stats))
     print("PARITY " + " ".join(f"{k}={v}" for k, v in stats.items()), flush=True)
