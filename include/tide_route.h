@@ -26,10 +26,17 @@
  *  - Return value: TIDE_OK (0) or a negative tide_status_t.  On error nothing is enqueued,
  *    outputs are untouched and tide_last_error() describes the cause.  No call aborts.
  *  - hidden rows are d elements of `dtype`, row r of checkpoint c starting at element
- *    c*ckpt_stride + r*row_stride.  Requirements: 16 <= d <= 16384 with d*sizeof(dtype) a
- *    multiple of 16, row_stride >= d, base address and both strides (in bytes) multiples of 16.
- *    Hidden sizes that are multiples of 128 (every model of the paper's Table 2) run on the
- *    tuned kernels; any other size on a generic fallback (Sec. 3.4), bottleneck 64 or 128 only.
+ *    c*ckpt_stride + r*row_stride.  1 <= d <= 16384, row_stride >= d.  When d*sizeof(dtype) is a
+ *    multiple of 16 the base address and both strides (in bytes) must be multiples of 16
+ *    (TIDE_ERR_ALIGNMENT otherwise); for other hidden sizes rows cannot be aligned like that and
+ *    only element alignment is required.
+ *    Hidden sizes that are multiples of 128 (every model of the paper's Table 2) run on the tuned
+ *    kernels; any other size on a generic fallback (Sec. 3.4): at widths 64 / 128 and rows of whole
+ *    16-byte chunks, kernels that zero-fill the last partial tile; otherwise (rows that are not
+ *    whole chunks, or width 256) the rows are first copied into aligned, zero-padded rows in the
+ *    scratch memory -- C*T*roundup(d,128) elements -- and the tuned kernels run on the copy.
+ *    tide_exit_project and tide_cosine_labels read rows in 16-byte chunks and accept only hidden
+ *    sizes with d*sizeof(dtype) a multiple of 16 (TIDE_ERR_UNSUPPORTED otherwise).
  *  - T == 0 is a successful no-op.  1 <= C <= 32.
  *  - The threshold test is taken on the logit: z > ln(theta/(1-theta)) for 0 < theta < 1,
  *    never for theta >= 1 (the paper's "1.0 (off)", Table 4), always for theta <= 0.
@@ -52,7 +59,7 @@
  *    (TIDE_ERR_HIP) after an earlier kernel of the same call was enqueued, that earlier work stays
  *    enqueued; the scratch memory is then marked and re-initialised by the next call that uses it
  *    (a caller-owned workspace: by the caller's next tide_workspace_init).
- *  - W1 / packed, w2, and gamma / b1 when given, must be 16-byte aligned (TIDE_ERR_ALIGNMENT).
+ *  - W1 / packed, w2, and b1 when given, must be 16-byte aligned (TIDE_ERR_ALIGNMENT).
  *  - Small batches (a decode step, or one checkpoint's call on a few hundred rows) run on kernels
  *    that split each router's contraction over the whole chip: a matrix-core split-k pair for
  *    packed weights, an fp32 latency kernel for raw weights up to 8 rows per checkpoint and, up
@@ -130,7 +137,8 @@ int tide_select_exit(const void* hidden, int dtype, int64_t C, int64_t T, int64_
  * gain can be folded into the projection ahead of time: W1'[i][j] = gamma_i * W1[i][j],
  * rounded to `dtype` and stored in the order the matrix-core kernel consumes it.
  * tide_packed_router_bytes: bytes of one checkpoint's packed weights (0 if unsupported; width 64
- *   is stored padded to 128 columns, width 256 as two 128-column halves).
+ *   is stored padded to 128 columns, width 256 as two 128-column halves, d padded with zero rows
+ *   to a multiple of 128).
  * tide_router_pack: device gamma [C,d] or NULL, device W1 [C,d,b] -> device packed
  *   [C * tide_packed_router_bytes] (16-byte aligned).  The packed layout is private to the
  *   library version that wrote it.                                                      */

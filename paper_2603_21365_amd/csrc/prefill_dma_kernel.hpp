@@ -533,7 +533,7 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_dma_kernel(const 
         // ---- one inverse RMS per row, computed once ----
         if (tid < kActive * 32) {
             const float ss = (ss_part[tid] + ss_part[kRowsM + tid]) + (ss_part[2 * kRowsM + tid] + ss_part[3 * kRowsM + tid]);
-            inv_rms[tid] = inv_rms_f32(ss, 1.0f / (float)p.d, p.eps);
+            inv_rms[tid] = inv_rms_f32(ss, p.inv_d, p.eps);
         }
         __syncthreads();
 

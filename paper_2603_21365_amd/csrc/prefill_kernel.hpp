@@ -39,6 +39,7 @@ struct PrefillParams {
     int tile_begin;            // first tile of the checkpoint-major list this launch covers (the tiles before it
                                // went to a wide-tile kernel), else 0
     float eps;
+    float inv_d;               // 1 / (the hidden size of Eq. (2)'s mean): the true d also where p.d is a padded row length
     int32_t min_layer, no_exit;
     // outputs (each may be null)
     float* prob;               // [C][T]
@@ -229,7 +230,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void tide_prefill_kernel(const 
         if (kt + j < ntile) do_tile(j, kt + j, false);
 
     // ---- row scale: the 16 lanes that share a row hold its partial sums of squares ----
-    const float inv_d = 1.0f / (float)p.d;
+    const float inv_d = p.inv_d;
 #pragma unroll
     for (int i = 0; i < kChunksPerThread; ++i) {
         const float s = xor_reduce_sum<4>(ss[i]);

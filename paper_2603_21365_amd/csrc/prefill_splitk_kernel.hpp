@@ -281,7 +281,7 @@ __global__ __launch_bounds__(kFinishThreads * kHalves) void tide_splitk_finish_k
     if (tid < 32) {
         const float ss = ((ss_part[0][tid] + ss_part[1][tid]) + (ss_part[2][tid] + ss_part[3][tid])) +
                          ((ss_part[4][tid] + ss_part[5][tid]) + (ss_part[6][tid] + ss_part[7][tid]));
-        inv_rms[tid] = inv_rms_f32(ss, 1.0f / (float)p.d, p.eps);
+        inv_rms[tid] = inv_rms_f32(ss, p.inv_d, p.eps);
     }
     __syncthreads();
     {

@@ -153,7 +153,7 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
     for (int b = 0; b < kBlocks; ++b) {
         const int row = 32 * b + (lane & 31);
         const float ss = (ss_part[row] + ss_part[kRowsM + row]) + (ss_part[2 * kRowsM + row] + ss_part[3 * kRowsM + row]);
-        const float z = router_epilogue_row(acc[b], kNegLog2e * inv_rms_f32(ss, 1.0f / (float)p.d, p.eps), ecols);
+        const float z = router_epilogue_row(acc[b], kNegLog2e * inv_rms_f32(ss, p.inv_d, p.eps), ecols);
         if (lane < 32) z_part[wave * kRowsM + row] = z;
     }
     __syncthreads();

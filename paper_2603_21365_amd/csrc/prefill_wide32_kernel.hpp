@@ -195,7 +195,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_f32_kernel(
 
         // ---- epilogue, all within the wave: lanes l and l^32 hold the two halves of row l%32's sum of squares
         const float s2 = ssq + __shfl_xor(ssq, 32, kWave);
-        if (lane < 32) my_rms[lane] = inv_rms_f32(s2, 1.0f / (float)p.d, p.eps);
+        if (lane < 32) my_rms[lane] = inv_rms_f32(s2, p.inv_d, p.eps);
         float xs[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) xs[v] = 0.0f;

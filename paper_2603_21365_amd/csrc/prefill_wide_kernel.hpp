@@ -274,7 +274,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void tide_prefill_wide_kernel(cons
         __syncthreads();
         if (tid < kRowsW) {
             const float ss = (ss_part[tid] + ss_part[kRowsW + tid]) + (ss_part[2 * kRowsW + tid] + ss_part[3 * kRowsW + tid]);
-            inv_rms[tid] = inv_rms_f32(ss, 1.0f / (float)p.d, p.eps);
+            inv_rms[tid] = inv_rms_f32(ss, p.inv_d, p.eps);
         }
         __syncthreads();
         {

@@ -25,6 +25,7 @@
 #include "prefill_wide_kernel.hpp"
 #include "prefill_wide32_kernel.hpp"
 #include "project_kernel.hpp"
+#include "repack_kernel.hpp"
 
 namespace {
 
@@ -70,6 +71,7 @@ struct Scratch {
     uint64_t* arrive = nullptr;     // [T] arrival words (state), null when no exit_layer is asked for
     void* packed = nullptr;         // C packed routers (data), raw-weight prefill calls only
     float* part = nullptr;          // partial results (data)
+    void* rows = nullptr;           // re-aligned, zero-padded copy of the hidden rows (data), generic fallback only
 };
 
 // The library's own workspace: one per device, grow-only, shared by every call that does not bring
@@ -77,7 +79,7 @@ struct Scratch {
 // that a launch failed after an earlier one of the same call had been enqueued (the state words
 // may then be non-zero: the next call clears them first).
 struct Workspace {
-    Buffer counters, arrive, packed, part, batch, compact;
+    Buffer counters, arrive, packed, part, rows, batch, compact;
     hipStream_t last_stream = nullptr;
     bool used = false, dirty = false;
 };
@@ -187,32 +189,37 @@ float threshold_logit(float theta) {
 // Everything both entry points must check before anything is enqueued.
 bool supported_bottleneck(int64_t b) { return b == 64 || b == 128 || b == 256; }
 
-// Hidden sizes: rows of whole 16-byte chunks.  Multiples of 128 run on the streaming kernels; any
-// other size on the generic fallback (register-ring prefill form with a zero-filled last k-tile,
-// decode kernel with a partial last slice).
+// Hidden sizes.  Multiples of 128 run on the tuned kernels.  Other sizes whose rows are whole 16-byte
+// chunks run, at widths 64 / 128, on the register-ring prefill form with a zero-filled last k-tile and on
+// the latency kernel with a partial last slice.  Everything else -- rows that are not whole chunks, or
+// width 256 at a hidden size that is not a multiple of 128 -- is first copied into aligned, zero-padded
+// rows (repack_kernel.hpp) and then takes the tuned kernels.
 bool supported_hidden(int dtype, int64_t d) {
-    return d >= 16 && d <= 16384 && (d * (int64_t)(dtype == TIDE_F32 ? 4 : 2)) % 16 == 0;
+    (void)dtype;
+    return d >= 1 && d <= 16384;
 }
+bool chunked_rows(int dtype, int64_t d) { return (d * (int64_t)(dtype == TIDE_F32 ? 4 : 2)) % 16 == 0; }
+bool needs_repack(int dtype, int64_t d, int64_t b) { return !chunked_rows(dtype, d) || (d % 128 != 0 && b == 256); }
 
-// d rounded up to whole k-tiles of the prefill kernels (256 bytes of a row).
+// d rounded up to a multiple of 128 elements: whole k-tiles of the prefill kernels (256 bytes of a row)
+// for every storage type, and the row length the tuned kernels accept.
 int64_t padded_hidden(int dtype, int64_t d) {
-    const int64_t tile = 256 / (dtype == TIDE_F32 ? 4 : 2);
-    return (d + tile - 1) / tile * tile;
+    (void)dtype;
+    return (d + 127) / 128 * 128;
 }
 
+// chunked_only: the entry point reads rows in 16-byte chunks and has no fallback for other hidden sizes.
 int check_common(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int64_t ckpt_stride,
-                 int64_t row_stride, const void* weights, const float* w2, float eps) {
+                 int64_t row_stride, const void* weights, const float* w2, float eps, bool chunked_only = false) {
     if (dtype != TIDE_F32 && dtype != TIDE_F16 && dtype != TIDE_BF16)
         return fail(TIDE_ERR_INVALID_ARG, "dtype %d is not a tide_dtype_t", dtype);
     if (C < 1) return fail(TIDE_ERR_INVALID_ARG, "C = %lld must be at least 1", (long long)C);
     if (C > TIDE_MAX_CHECKPOINTS) return fail(TIDE_ERR_UNSUPPORTED, "C = %lld exceeds %d", (long long)C, TIDE_MAX_CHECKPOINTS);
     if (T < 0) return fail(TIDE_ERR_INVALID_ARG, "T = %lld is negative", (long long)T);
     if (d <= 0) return fail(TIDE_ERR_INVALID_ARG, "d = %lld must be positive", (long long)d);
-    if (!supported_hidden(dtype, d))
-        return fail(TIDE_ERR_UNSUPPORTED, "d = %lld: rows must be a multiple of 16 bytes and d in [16, 16384] "
-                    "(multiples of 128 take the fast kernels)", (long long)d);
-    if (d % 128 != 0 && b == 256)
-        return fail(TIDE_ERR_UNSUPPORTED, "bottleneck width 256 needs d %% 128 == 0 (d = %lld)", (long long)d);
+    if (!supported_hidden(dtype, d)) return fail(TIDE_ERR_UNSUPPORTED, "d = %lld: hidden sizes from 1 to 16384", (long long)d);
+    if (chunked_only && !chunked_rows(dtype, d))
+        return fail(TIDE_ERR_UNSUPPORTED, "d = %lld: rows must be a multiple of 16 bytes for this entry point", (long long)d);
     if (!supported_bottleneck(b))
         return fail(TIDE_ERR_UNSUPPORTED, "bottleneck width b = %lld: supported widths are 64, 128 and 256", (long long)b);
     if (C * T > (int64_t)1 << 30)
@@ -223,16 +230,22 @@ int check_common(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d,
     if (T == 0) return TIDE_OK;
     if (!hidden || !weights || !w2) return fail(TIDE_ERR_INVALID_ARG, "hidden, W1/packed and w2 must not be NULL");
     const size_t eb = elem_bytes(dtype);
-    if (((uintptr_t)hidden & 15) || ((size_t)row_stride * eb & 15) || (C > 1 && ((size_t)ckpt_stride * eb & 15)))
-        return fail(TIDE_ERR_ALIGNMENT, "hidden base and strides must be multiples of 16 bytes");
+    if (chunked_rows(dtype, d)) {
+        if (((uintptr_t)hidden & 15) || ((size_t)row_stride * eb & 15) || (C > 1 && ((size_t)ckpt_stride * eb & 15)))
+            return fail(TIDE_ERR_ALIGNMENT, "hidden base and strides must be multiples of 16 bytes");
+    } else if ((uintptr_t)hidden & (eb - 1)) {      // rows that cannot be 16-byte aligned: elements must be
+        return fail(TIDE_ERR_ALIGNMENT, "hidden must be aligned to its element size");
+    }
     if (((uintptr_t)weights & 15) || ((uintptr_t)w2 & 15))
         return fail(TIDE_ERR_ALIGNMENT, "W1 / packed and w2 must be 16-byte aligned");
     return TIDE_OK;
 }
 
-// gamma and b1 are optional; when given they are read with 16-byte loads like the other parameter arrays.
+// gamma and b1 are optional.  b1 is read with 16-byte loads like w2; gamma element by element (a
+// checkpoint's row of gamma starts d floats after the previous one: no alignment beyond a float for general d).
 int check_optional_arrays(const float* gamma, const float* b1) {
-    if (((uintptr_t)gamma & 15) || ((uintptr_t)b1 & 15)) return fail(TIDE_ERR_ALIGNMENT, "gamma and b1 must be 16-byte aligned");
+    if ((uintptr_t)b1 & 15) return fail(TIDE_ERR_ALIGNMENT, "b1 must be 16-byte aligned");
+    if ((uintptr_t)gamma & 3) return fail(TIDE_ERR_ALIGNMENT, "gamma must be aligned to a float");
     return TIDE_OK;
 }
 
@@ -555,8 +568,8 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
     return plan;
 }
 
-int launch_prefill(const Scratch& sc, const PrefillPlan& plan, const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t b,
-                   int64_t ckpt_stride, int64_t row_stride, const void* packed, float eps, const float* b1, const float* w2,
+int launch_prefill(const Scratch& sc, const PrefillPlan& plan, const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t d_mean,
+                   int64_t b, int64_t ckpt_stride, int64_t row_stride, const void* packed, float eps, const float* b1, const float* w2,
                    const CheckpointTable& tab, int32_t min_layer, int32_t no_exit, const Outputs& o, hipStream_t st) {
     PrefillParams p;
     std::memset(&p, 0, sizeof(p));
@@ -573,6 +586,7 @@ int launch_prefill(const Scratch& sc, const PrefillPlan& plan, const void* hidde
     p.dpad = (int)padded_hidden(dtype, d);
     p.b = (int)b;
     p.eps = eps;
+    p.inv_d = 1.0f / (float)d_mean;
     p.min_layer = min_layer;
     p.no_exit = no_exit;
     p.prob = o.prob;
@@ -710,7 +724,10 @@ struct CallNeed {
     size_t state_bytes = 0;         // counters + arrival words, a multiple of 256
     size_t packed_bytes = 0;        // a multiple of 256
     size_t part_bytes = 0;          // a multiple of 256
-    size_t total() const { return state_bytes + packed_bytes + part_bytes; }
+    size_t rows_bytes = 0;          // generic fallback: the re-aligned copy of the hidden rows; a multiple of 256
+    int64_t d_run = 0;              // the row length the kernels run on: d, or d padded to a multiple of 128 with rows_bytes
+    size_t data_bytes() const { return packed_bytes + part_bytes + rows_bytes; }
+    size_t total() const { return state_bytes + data_bytes(); }
 };
 size_t round256(size_t n) { return (n + 255) & ~size_t(255); }
 
@@ -718,7 +735,11 @@ CallNeed call_need(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, bool r
                    int form_word) {
     CallNeed n;
     n.state_bytes = round256(kCounterSlots * sizeof(uint32_t)) + (want_exit ? round256((size_t)T * sizeof(uint64_t)) : 0);
-    n.decode = use_decode(T, dtype, d, b, !raw_weights, variant, form_word);
+    const bool repack = needs_repack(dtype, d, b);
+    n.d_run = repack ? padded_hidden(dtype, d) : d;
+    if (repack) n.rows_bytes = round256((size_t)C * (size_t)T * (size_t)n.d_run * elem_bytes(dtype));
+    // (the latency kernel reads raw W1 rows by the true d and hidden rows in 16-byte chunks: never after a repack)
+    n.decode = !repack && use_decode(T, dtype, d, b, !raw_weights, variant, form_word);
     const int halves = halves_of(b);
     if (n.decode) {
         const size_t S = (size_t)((d + kDecodeSlice - 1) / kDecodeSlice);
@@ -726,7 +747,7 @@ CallNeed call_need(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, bool r
         return n;
     }
     if (raw_weights) n.packed_bytes = round256((size_t)C * tide_packed_router_bytes(dtype, d, b));
-    n.plan = plan_prefill(dtype, C, T, d, b, cus, form_word);
+    n.plan = plan_prefill(dtype, C, T, n.d_run, b, cus, form_word);
     for (int i = 0; i < n.plan.count; ++i) {
         const PlannedLaunch& L = n.plan.launch[i];
         if (L.kernel == kKernelSplitK) n.part_bytes = round256(splitk_part_bytes(L.rows_per_tile / 32, L.total_tiles, halves, L.k_slices));
@@ -756,6 +777,7 @@ Scratch carve(void* block, const CallNeed& n, bool want_exit) {
     sc.arrive = want_exit ? (uint64_t*)(base + round256(kCounterSlots * sizeof(uint32_t))) : nullptr;
     sc.packed = n.packed_bytes ? base + n.state_bytes : nullptr;
     sc.part = n.part_bytes ? (float*)(base + n.state_bytes + n.packed_bytes) : nullptr;
+    sc.rows = n.rows_bytes ? base + n.state_bytes + n.packed_bytes + n.part_bytes : nullptr;
     return sc;
 }
 
@@ -797,6 +819,7 @@ int run(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t 
         if (want_exit && (rc = reserve(ws->arrive, (size_t)T * sizeof(uint64_t), true))) return rc;
         if (need.packed_bytes && (rc = reserve(ws->packed, need.packed_bytes, false))) return rc;
         if (need.part_bytes && (rc = reserve(ws->part, need.part_bytes, false))) return rc;
+        if (need.rows_bytes && (rc = reserve(ws->rows, need.rows_bytes, false))) return rc;
         if (ws->dirty) {            // an earlier call broke off between two launches: its state words may be set
             if ((rc = launch_clear(ws->counters.ptr, ws->counters.bytes, st))) return rc;
             if (ws->arrive.ptr && (rc = launch_clear(ws->arrive.ptr, ws->arrive.bytes, st))) return rc;
@@ -806,6 +829,7 @@ int run(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t 
         sc.arrive = want_exit ? (uint64_t*)ws->arrive.ptr : nullptr;
         sc.packed = ws->packed.ptr;
         sc.part = (float*)ws->part.ptr;
+        sc.rows = ws->rows.ptr;
     } else if (source == kScratchCaller) {
         BlockRecord* rec = find_block(block);
         if (!rec) return fail(TIDE_ERR_WORKSPACE, "unknown workspace %p: call tide_workspace_init on it first", block);
@@ -838,19 +862,42 @@ int run(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t 
         sc = carve(ss.ptr, need, want_exit);
     }
     // the data regions of this call overwrite whatever zero state lay behind its own state words
-    if (clean && need.packed_bytes + need.part_bytes > 0 && *clean > need.state_bytes) *clean = need.state_bytes;
+    if (clean && need.data_bytes() > 0 && *clean > need.state_bytes) *clean = need.state_bytes;
 
     if (need.decode) {
         rc = launch_decode(sc, hidden, dtype, C, T, d, b, ckpt_stride, row_stride, gamma, W1, packed, eps, b1, w2, tab,
                            min_layer, no_exit, o, st);
     } else {
-        if (W1) {
+        if (need.rows_bytes) {      // generic fallback: aligned, zero-padded rows for the tuned kernels
+            RepackParams rp;
+            const int64_t eb = (int64_t)elem_bytes(dtype);
+            rp.hidden = (const char*)hidden;
+            rp.ckpt_stride_bytes = ckpt_stride * eb;
+            rp.row_stride_bytes = row_stride * eb;
+            rp.out = (u32x4*)sc.rows;
+            rp.C = (int)C;
+            rp.T = (int)T;
+            rp.d = (int)d;
+            rp.dpad = (int)need.d_run;
+            const int64_t chunks = C * T * (need.d_run * eb / 16);
+            const unsigned grid = (unsigned)std::min<int64_t>((chunks + kRepackThreads - 1) / kRepackThreads, 1 << 20);
+            by_dtype(dtype, [&](auto dt) {
+                hipLaunchKernelGGL((tide_repack_rows_kernel<decltype(dt)::value>), dim3(grid), dim3(kRepackThreads), 0, st, rp);
+                return 0;
+            });
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) rc = fail(TIDE_ERR_HIP, "row repack launch: %s", hipGetErrorString(e));
+            hidden = sc.rows;
+            ckpt_stride = T * need.d_run;
+            row_stride = need.d_run;
+        }
+        if (!rc && W1) {
             rc = launch_pack(dtype, C, d, b, gamma, W1, sc.packed, st);
             packed = sc.packed;
         }
         if (!rc)
-            rc = launch_prefill(sc, need.plan, hidden, dtype, C, T, d, b, ckpt_stride, row_stride, packed, eps, b1, w2, tab,
-                                min_layer, no_exit, o, st);
+            rc = launch_prefill(sc, need.plan, hidden, dtype, C, T, need.d_run, d, b, ckpt_stride, row_stride, packed, eps, b1, w2,
+                                tab, min_layer, no_exit, o, st);
     }
     if (rc) {                       // a launch failed, possibly after an earlier one of this call was enqueued
         if (ws) ws->dirty = true;
@@ -869,7 +916,7 @@ const char* tide_last_error(void) { return g_err; }
 
 size_t tide_packed_router_bytes(int dtype, int64_t d, int64_t b) {
     if ((dtype != TIDE_F32 && dtype != TIDE_F16 && dtype != TIDE_BF16) || !supported_hidden(dtype, d)) return 0;
-    if (!supported_bottleneck(b) || (d % 128 != 0 && b == 256)) return 0;
+    if (!supported_bottleneck(b)) return 0;
     return (size_t)halves_of(b) * (size_t)padded_hidden(dtype, d) * kBottleneck * elem_bytes(dtype);
 }
 
@@ -1053,7 +1100,7 @@ int tide_exit_project(const void* hidden, int dtype, int64_t C, int64_t T, int64
                       const int32_t* exit_layer, const int32_t* layer_ids, const float* norm_gain, float eps,
                       void* out, int64_t out_row_stride, void* stream) {
     g_err[0] = 0;
-    int rc = check_common(hidden, dtype, C, T, d, kBottleneck, ckpt_stride, row_stride, hidden, reinterpret_cast<const float*>(hidden), eps);
+    int rc = check_common(hidden, dtype, C, T, d, kBottleneck, ckpt_stride, row_stride, hidden, reinterpret_cast<const float*>(hidden), eps, true);
     if (rc) return rc;
     if (T == 0) return TIDE_OK;
     if (!exit_layer || !layer_ids || !out) return fail(TIDE_ERR_INVALID_ARG, "exit_layer, layer_ids (host) and out must not be NULL");
@@ -1153,7 +1200,7 @@ int tide_cosine_labels(const void* hidden, int dtype, int64_t C, int64_t T, int6
                        int64_t row_stride, const void* final_hidden, int64_t final_row_stride, float tau, float* sim,
                        uint8_t* label, void* stream) {
     g_err[0] = 0;
-    int rc = check_common(hidden, dtype, C, T, d, kBottleneck, ckpt_stride, row_stride, hidden, reinterpret_cast<const float*>(hidden), 0.0f);
+    int rc = check_common(hidden, dtype, C, T, d, kBottleneck, ckpt_stride, row_stride, hidden, reinterpret_cast<const float*>(hidden), 0.0f, true);
     if (rc) return rc;
     if (T == 0) return TIDE_OK;
     if (!final_hidden) return fail(TIDE_ERR_INVALID_ARG, "final_hidden must not be NULL");
@@ -1264,7 +1311,8 @@ bool valid_form_word(int w) {
 int tide_prefill_plan(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int cus, int form, int32_t* out) {
     if (dtype != TIDE_F32 && dtype != TIDE_F16 && dtype != TIDE_BF16) return fail(TIDE_ERR_INVALID_ARG, "dtype %d is not a tide_dtype_t", dtype);
     if (C < 1 || C > TIDE_MAX_CHECKPOINTS || T < 1 || C * T > (int64_t)1 << 30) return fail(TIDE_ERR_INVALID_ARG, "C = %lld, T = %lld out of range", (long long)C, (long long)T);
-    if (!supported_hidden(dtype, d) || !supported_bottleneck(b) || (d % 128 != 0 && b == 256)) return fail(TIDE_ERR_UNSUPPORTED, "d = %lld, b = %lld unsupported", (long long)d, (long long)b);
+    if (!supported_hidden(dtype, d) || !supported_bottleneck(b)) return fail(TIDE_ERR_UNSUPPORTED, "d = %lld, b = %lld unsupported", (long long)d, (long long)b);
+    if (needs_repack(dtype, d, b)) d = padded_hidden(dtype, d);      // such calls run the tuned kernels on zero-padded rows
     if (cus < 8 || cus % 8 != 0) return fail(TIDE_ERR_INVALID_ARG, "cus = %d must be a positive multiple of 8", cus);
     if (!valid_form_word(form)) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d: a form in [0, 6], with form 5 optionally rows << 8 | slices << 16", form);
     if (!out) return fail(TIDE_ERR_INVALID_ARG, "out must not be NULL");
@@ -1313,7 +1361,7 @@ int tide_release(void) {
     int rc = current_workspace(&ws);
     if (rc) return rc;
     TIDE_HIP(hipDeviceSynchronize());
-    for (Buffer* b : {&ws->counters, &ws->arrive, &ws->packed, &ws->part, &ws->batch, &ws->compact}) {
+    for (Buffer* b : {&ws->counters, &ws->arrive, &ws->packed, &ws->part, &ws->rows, &ws->batch, &ws->compact}) {
         if (b->ptr) TIDE_HIP(hipFree(b->ptr));
         b->ptr = nullptr;
         b->bytes = 0;

@@ -34,7 +34,10 @@ def test_library_exports_every_declared_symbol():
 def test_packed_size_query():
     assert tr.packed_router_bytes(tr.BF16, 4096) == 4096 * 128 * 2
     assert tr.packed_router_bytes(tr.F32, 768) == 768 * 128 * 4
-    assert tr.packed_router_bytes(tr.F16, 100) == 0
+    # any hidden size up to 16384: packed with zero rows up to the next multiple of 128 (the generic fallback)
+    assert tr.packed_router_bytes(tr.F16, 100) == 128 * 128 * 2
+    assert tr.packed_router_bytes(tr.F32, 333) == 384 * 128 * 4 and tr.packed_router_bytes(tr.BF16, 1001, 256) == 1024 * 256 * 2
+    assert tr.packed_router_bytes(tr.F16, 0) == 0 and tr.packed_router_bytes(tr.F16, 16385) == 0
     assert tr.packed_router_bytes(7, 4096) == 0
     # width 64 is stored padded to 128 columns, width 256 as two 128-column halves (Table 2's widths)
     assert tr.packed_router_bytes(tr.BF16, 2048, 64) == 2048 * 128 * 2
@@ -54,8 +57,7 @@ def test_router_eval_rejects_bad_arguments():
     assert _eval(lib, dtype=5) == -1 and "dtype" in tr.last_error()
     assert _eval(lib, T=-1) == -1
     assert _eval(lib, d=0) == -1
-    assert _eval(lib, d=100, rs=100) == -2 and "128" in tr.last_error()
-    assert _eval(lib, d=32768, rs=32768) == -2
+    assert _eval(lib, d=32768, rs=32768) == -2 and "16384" in tr.last_error()
     assert _eval(lib, b=96) == -2 and "bottleneck" in tr.last_error()
     assert _eval(lib, b=0) == -2 and _eval(lib, b=512) == -2
     assert _eval(lib, rs=128) == -1
@@ -65,6 +67,7 @@ def test_router_eval_rejects_bad_arguments():
     assert _eval(lib, eps=-1.0) == -1
     assert _eval(lib, eps=float("nan")) == -1
     assert _eval(lib, hidden=FAKE + 2) == -3
+    assert _eval(lib, hidden=FAKE + 1, d=100, rs=100) == -3 and "element" in tr.last_error()   # rows that cannot be chunk-aligned: elements must be
     assert _eval(lib, rs=260) == -3            # 260 bf16 = 520 bytes: not a multiple of 16
     assert _eval(lib, T=0, hidden=None, W1=None, w2=None) == 0   # empty input: successful no-op
 
@@ -183,7 +186,10 @@ def test_workspace_size_query():
     # multiples of 256, monotone in T for a fixed path, zero for unsupported shapes
     for T in (1, 33, 500, 4096, 16384):
         assert tr.workspace_bytes(tr.BF16, 9, T, 4096) % 256 == 0
-    assert tr.workspace_bytes(tr.BF16, 8, 4096, 100) == 0 and "unsupported" in tr.last_error()
+    assert tr.workspace_bytes(tr.BF16, 8, 4096, 20000) == 0 and "unsupported" in tr.last_error()
+    # the generic fallback's aligned copy of the rows: C x T x (d rounded up to 128) elements
+    assert tr.workspace_bytes(tr.F16, 2, 4096, 100) >= 2 * 4096 * 128 * 2
+    assert tr.workspace_bytes(tr.BF16, 2, 4096, 200, 256) >= 2 * 4096 * 256 * 2 and tr.workspace_bytes(tr.BF16, 2, 4096, 200, 128) < 4096 * 256
     assert tr.workspace_bytes(tr.BF16, 0, 4096, 4096) == 0 and tr.workspace_bytes(9, 8, 64, 4096) == 0
     assert tr.noalloc_scratch_bytes() == 32 << 20
 
@@ -212,7 +218,7 @@ def test_ws_entry_points_reject_bad_arguments():
     # parameter arrays are read with 16-byte loads
     assert lib.tide_router_eval(FAKE, 2, 4, 256, 128, 256, None, 1e-6, FAKE + 4, None, FAKE, 0.0, 0.5, None, None, None, None) == -3
     assert lib.tide_router_eval(FAKE, 2, 4, 256, 128, 256, None, 1e-6, FAKE, None, FAKE + 8, 0.0, 0.5, None, None, None, None) == -3
-    assert lib.tide_router_eval(FAKE, 2, 4, 256, 128, 256, FAKE + 4, 1e-6, FAKE, None, FAKE, 0.0, 0.5, None, None, None, None) == -3
+    assert lib.tide_router_eval(FAKE, 2, 4, 256, 128, 256, FAKE + 2, 1e-6, FAKE, None, FAKE, 0.0, 0.5, None, None, None, None) == -3
     assert lib.tide_router_eval(FAKE, 2, 4, 256, 128, 256, None, 1e-6, FAKE, FAKE + 12, FAKE, 0.0, 0.5, None, None, None, None) == -3
     # workspace registration
     assert lib.tide_workspace_init(None, 4096, None) == -1

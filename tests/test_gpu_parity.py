@@ -367,13 +367,48 @@ def test_generic_fallback_for_other_hidden_sizes(tr, dtype, d, b):
         report(st)
 
 
-def test_generic_hidden_size_rejects_width_256(tr):
+@pytest.mark.parametrize("dtype,d,b", [("f16", 100, 128), ("bf16", 1001, 128), ("f32", 333, 128), ("f16", 100, 256), ("bf16", 1001, 64),
+                                       ("f32", 333, 256), ("bf16", 200, 256), ("f16", 4104, 256), ("f32", 708, 256), ("bf16", 7, 128),
+                                       ("f32", 1, 64)])
+def test_generic_fallback_for_unaligned_rows_and_width_256(tr, dtype, d, b):
+    """The rest of the generic fallback (Sec. 3.4): hidden sizes whose rows are not whole 16-byte chunks
+    (contiguous rows of d = 100 fp16, 1001 bf16, 333 fp32 elements start on no 16-byte boundary), and
+    bottleneck width 256 at hidden sizes that are not multiples of 128.  The library copies the rows into
+    aligned, zero-padded ones and runs the tuned kernels on the copy.  Prefill- and decode-sized batches,
+    raw and packed weights, contiguous rows and rows inside a wider buffer whose padding holds NaN."""
     import torch
-    h = torch.zeros((1, 4, 200), dtype=torch.bfloat16, device="cuda")
-    W1 = torch.zeros((1, 200, 256), device="cuda")
-    w2 = torch.zeros((1, 256), device="cuda")
-    with pytest.raises(tr.TideError):
-        tr.select_exit(h, None, 1e-6, W1, None, w2, 0.0, 0.5, [3], 0, 4)
+    C, T = 3, 333
+    w = synth.Workload(f"unaligned_{dtype}_d{d}_b{b}", 47, dtype, d, 12, 4, T, None, b=b)
+    rt = w.routers()
+    rt.b2[:] = [0.1, -0.2, 0.0]
+    hb = w.hidden()
+    ex_o, z_o, m_o = oracle_select(w, rt, hb)
+    store = np.float32 if dtype == "f32" else (np.float16 if dtype == "f16" else np.uint16)
+    nan = np.array(np.nan, dtype=np.float32).astype(store) if dtype != "bf16" else np.uint16(0x7FC0)
+    esz = 4 if dtype == "f32" else 2
+    # rows that cannot be chunk-aligned sit d + 3 elements apart (no alignment beyond an element); the others keep 16-byte alignment
+    pad = 3 if (d * esz) % 16 else (24 if dtype == "f32" else 40)
+    wide = np.full((C, T + 2, d + pad), nan, dtype=store)
+    wide[:, :T, :d] = hb
+    dev_wide = to_device(wide, dtype)
+    dev_tight = to_device(np.ascontiguousarray(hb), dtype)
+    g, W1, b1, w2 = routers_to_device(rt)
+    pk = tr.router_pack(tr.DTYPE_CODES[dtype], g, W1)
+    for label, dev, Tn, use_packed in (("tight_raw", dev_tight, T, False), ("wide_packed", dev_wide[:, :T, :d], T, True),
+                                       ("wide_raw_small", dev_wide[:, :5, :d], 5, False), ("tight_packed_small", dev_tight[:, :21], 21, True)):
+        say(f"{w.name} {label}")
+        if use_packed:
+            ex, z, m = tr.select_exit_packed(dev, pk, w.eps, b1, w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers, d=d)
+        else:
+            ex, z, m = tr.select_exit(dev, g, w.eps, W1, b1, w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers)
+        torch.cuda.synchronize()
+        st = compare_select(f"{w.name}_{label}", dtype, z.cpu().numpy(), ex.cpu().numpy(), m.cpu().numpy(),
+                            z_o[:, :Tn], ex_o[:Tn], m_o[:Tn], rt.theta, w.layer_ids, 0, w.n_layers)
+        report(st)
+    # router_eval on one checkpoint of the same rows
+    prob, fire, logit = tr.router_eval(dev_tight[1], g[1], w.eps, W1[1], b1[1], w2[1], float(rt.b2[1]), 0.5)
+    torch.cuda.synchronize()
+    assert np.abs(logit.cpu().numpy() - z_o[1]).max() <= TOL[dtype]
 
 
 # ------------------------------------------------------------------ every element counts

@@ -189,8 +189,10 @@ def test_a_forced_split_k_shape_is_taken_as_given():
 
 
 def test_plan_rejects_bad_arguments():
-    bad = [dict(dtype=9), dict(C=0), dict(C=33), dict(T=0), dict(d=100000), dict(d=130), dict(b=96), dict(cus=100), dict(cus=0), dict(form=7),
-           dict(d=200, b=256)]
+    bad = [dict(dtype=9), dict(C=0), dict(C=33), dict(T=0), dict(d=100000), dict(d=0), dict(b=96), dict(cus=100), dict(cus=0), dict(form=7)]
+    # hidden sizes of the generic fallback that are copied into zero-padded rows first are planned at the padded size
+    assert tr.prefill_plan(tr.BF16, 4, 1000, 130) == tr.prefill_plan(tr.BF16, 4, 1000, 131)[:] == tr.prefill_plan(tr.BF16, 4, 1000, 256)
+    assert tr.prefill_plan(tr.BF16, 4, 1000, 200, 256) == tr.prefill_plan(tr.BF16, 4, 1000, 256, 256)
     for kw in bad:
         args = dict(dtype=tr.BF16, C=4, T=100, d=1024, b=128, cus=256, form=0)
         args.update(kw)
