@@ -24,8 +24,9 @@ _lib = None
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (plain -O2, OpenMP over tokens only)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        # TIDE_ORACLE_CFLAGS: extra compiler flags, e.g. the sanitizer build of tests/test_sanitizers.py
         cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-               "-o", _LIB, _SRC, "-lm"]
+               *os.environ.get("TIDE_ORACLE_CFLAGS", "").split(), "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 

@@ -44,9 +44,10 @@ def load_library() -> ctypes.CDLL:
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
+    path = os.environ.get("TIDE_ROUTE_LIB") or LIB_PATH      # the override is for instrumented builds of the same sources (tests)
+    if path == LIB_PATH and not os.path.exists(LIB_PATH):
         build_library()
-    lib = ctypes.CDLL(LIB_PATH)
+    lib = ctypes.CDLL(path)
     vp, i64, i32, f32, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_int
     lib.tide_version.restype = ci
     lib.tide_last_error.restype = ctypes.c_char_p
