@@ -17,20 +17,21 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile every HIP source into libtide_route.so; always recompiles."""
+def build_library(verbose: bool = False, *, out: str = LIB_PATH, defines: tuple = ()) -> str:
+    """Compile every HIP source into libtide_route.so; always recompiles.  `out` / `defines` make an
+    instrumented build beside it (timeline.py)."""
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
     if not os.path.exists(hipcc):
         raise RuntimeError("hipcc not found: libtide_route cannot be built on this machine")
-    tmp = LIB_PATH + ".tmp"
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", INCLUDE, "-o", tmp, os.path.join(CSRC, "tide_route.hip")]
+    tmp = out + ".tmp"
+    cmd = [hipcc, *HIPCC_FLAGS, *[f"-D{d}" for d in defines], "-I", INCLUDE, "-o", tmp, os.path.join(CSRC, "tide_route.hip")]
     run = subprocess.run(cmd, capture_output=True, text=True)
     if verbose or run.returncode:
         print(run.stdout + run.stderr)
     if run.returncode:
         raise RuntimeError(f"hipcc failed ({run.returncode}): {' '.join(cmd)}")
-    os.replace(tmp, LIB_PATH)
-    return LIB_PATH
+    os.replace(tmp, out)
+    return out
 
 
 if __name__ == "__main__":

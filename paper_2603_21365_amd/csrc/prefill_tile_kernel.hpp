@@ -17,6 +17,22 @@
 
 namespace tide {
 
+// Timeline builds (-DTIDE_TILE_TIMELINE; see timeline.py): thread 0 of every workgroup -- lane 0 of consumer
+// wave 0 -- notes the 100 MHz real-time counter at its start, at every ring hand-over, at the end of its k
+// loop, after the first epilogue barrier, after its share of the epilogue, after the last barrier and once
+// its results are acknowledged: kTimelineStamps 64-bit values per workgroup in the buffer tide_debug_timeline set.
+#ifdef TIDE_TILE_TIMELINE
+constexpr int kTimelineStamps = 48;
+__device__ unsigned long long* g_tile_timeline = nullptr;
+#define TIDE_STAMP()                                                                              \
+    do {                                                                                          \
+        if (tid == 0 && tl_base && tl_n < kTimelineStamps) tl_base[tl_n] = __builtin_amdgcn_s_memrealtime(); \
+        ++tl_n;                                                                                   \
+    } while (0)
+#else
+#define TIDE_STAMP() do { } while (0)
+#endif
+
 constexpr int kTileRows = 128;
 constexpr int kTileLdsBytes = dma_lds_bytes<kTileRows>();
 
@@ -36,6 +52,11 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
     float* z_part = ss_part + kDmaConsumers * kRowsM;                              // [4][kRowsM]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+#ifdef TIDE_TILE_TIMELINE
+    unsigned long long* tl_base = g_tile_timeline ? g_tile_timeline + (size_t)blockIdx.x * kTimelineStamps : nullptr;
+    int tl_n = 0;
+#endif
+    TIDE_STAMP();
     const int per_xcd = (p.total_tiles - p.tile_begin + 7) >> 3;
     const int tile = p.tile_begin + (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if ((int)(blockIdx.x >> 3) >= per_xcd || tile >= p.total_tiles) return;
@@ -135,10 +156,13 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
     };
     for (int k = 0; k + 1 < ntile; ++k) {
         ring_barrier();
+        TIDE_STAMP();
         k_tile(ring + (k % kDmaStages) * kStageBytes + a_base, kt_of(k + 1), std::true_type{});
     }
     ring_barrier();
+    TIDE_STAMP();
     k_tile(ring + ((ntile - 1) % kDmaStages) * kStageBytes + a_base, 0, std::false_type{});
+    TIDE_STAMP();
 
     // ---- row sums of squares: lanes l and l^32 hold the two chunk phases; the 4 waves the rest
 #pragma unroll
@@ -147,6 +171,7 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
         if (lane < 32) ss_part[wave * kRowsM + 32 * b + lane] = s2;
     }
     __syncthreads();
+    TIDE_STAMP();
     // every lane owns one row per block: its 1/rms from the four waves' partial sums, then the block's
     // 16 columns inside the lane
 #pragma unroll
@@ -156,7 +181,9 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
         const float z = router_epilogue_row(acc[b], kNegLog2e * inv_rms_f32(ss, p.inv_d, p.eps), ecols);
         if (lane < 32) z_part[wave * kRowsM + row] = z;
     }
+    TIDE_STAMP();
     __syncthreads();
+    TIDE_STAMP();
     if (tid < kRowsM) {
         const int t = row0 + tid;
         if (t < p.T) {
@@ -164,6 +191,10 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
             emit_router_result(p, c, t, z);
         }
     }
+#ifdef TIDE_TILE_TIMELINE
+    __builtin_amdgcn_s_waitcnt(0);
+    TIDE_STAMP();
+#endif
 }
 
 }  // namespace tide

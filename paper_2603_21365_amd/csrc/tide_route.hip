@@ -1090,6 +1090,17 @@ int tide_select_exit_packed_noalloc(const void* hidden, int dtype, int64_t C, in
 
 size_t tide_noalloc_scratch_bytes(void) { return kStaticScratchBytes; }
 
+#ifdef TIDE_TILE_TIMELINE
+// Timeline builds only (timeline.py): where the one-tile prefill kernel leaves its per-workgroup time stamps
+// (device memory, kTimelineStamps x 8 bytes per workgroup of the largest launch; NULL switches them off).
+int tide_debug_timeline(void* buffer) {
+    g_err[0] = 0;
+    unsigned long long* b = (unsigned long long*)buffer;
+    TIDE_HIP(hipMemcpyToSymbol(HIP_SYMBOL(g_tile_timeline), &b, sizeof(b)));
+    return kTimelineStamps;
+}
+#endif
+
 uint64_t tide_workspace_allocations(void) {
     std::lock_guard<std::mutex> lock(g_mu);
     return g_allocations;
