@@ -272,7 +272,9 @@ int tide_set_variant(int variant);
  * form (256 rows per workgroup, 16-bit types) for as many whole tiles as there are workgroups,
  * 5 = split-k form (several workgroups share a tile's hidden dimension and a second launch adds
  * their partial results) with at least two slices, 6 = one 128-row tile per workgroup
- * without the persistent schedule (16-bit types, widths 64 / 128).  With form 5 the word may also
+ * without the persistent schedule (16-bit types, widths 64 / 128), 7 = band form (one launch, every
+ * workgroup an equal share of the 32-row blocks, tiles of up to 288 rows; 16-bit types, widths
+ * 64 / 128).  With form 5 the word may also
  * fix the split-k tile height and slice count: 5 | rows << 8 | slices << 16 with rows in {0, 32, 64,
  * 128} and slices in {0, 2, 4, 8}, 0 = chosen by the library.  A form that does
  * not apply to a call (storage type, width, hidden size) falls back to one that does.
@@ -286,7 +288,8 @@ int tide_set_prefill_form(int form);
  * tile_begin, k_slices, workgroups}: the launch covers tiles tile_begin .. total_tiles-1 of the
  * checkpoint-major list of tiles of rows_per_tile rows (tiles_per_ckpt per checkpoint, the last one
  * of a checkpoint possibly ragged).  kernel: 1 split-k pair, 2 wide-tile, 3 wide-tile fp32, 4 one-tile,
- * 5 / 6 streaming with 128 / 64 rows, 7 register-ring.  Returns the number of launches (1 or 2) or a
+ * 5 / 6 streaming with 128 / 64 rows, 7 register-ring, 8 band (rows_per_tile = 32: the blocks its
+ * bands are counted in, see tide_band_schedule).  Returns the number of launches (1 or 2) or a
  * negative tide_status_t.  Calls with at most 32 rows per checkpoint may take the latency kernel
  * instead (see the conventions); this function describes the prefill path only.              */
 int tide_prefill_plan(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int cus, int form, int32_t* out);
@@ -300,6 +303,14 @@ int tide_prefill_plan(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int
  * negative tide_status_t.                                                                      */
 int tide_stream_schedule(int rows_per_tile, int64_t b, int64_t k_tiles, int grid, int block, int tile_begin,
                          int total_tiles, int32_t* out, int max_items);
+
+/* The band kernel's schedule, for tests (host arithmetic, no GPU needed; the very code the kernel
+ * runs): the tiles of workgroup `block` of a launch of `grid` workgroups (a multiple of 8) over C
+ * checkpoints of blocks_per_ckpt = ceil(T / 32) blocks of 32 rows each (a tide_prefill_plan launch of
+ * kernel 8).  out: HOST int32 [max_items][3] = {checkpoint, first block within the checkpoint,
+ * blocks}; a tile has 1 to 9 blocks and lies within one checkpoint.  Returns the number of tiles
+ * (only the first max_items are written) or a negative tide_status_t.                          */
+int tide_band_schedule(int64_t C, int64_t blocks_per_ckpt, int grid, int block, int32_t* out, int max_items);
 
 /* Free the current device's workspace (synchronises that device).                       */
 int tide_release(void);

@@ -23,6 +23,7 @@
 #include "prefill_splitk_kernel.hpp"
 #include "prefill_tile_kernel.hpp"
 #include "prefill_wide_kernel.hpp"
+#include "prefill_band_kernel.hpp"
 #include "prefill_wide32_kernel.hpp"
 #include "project_kernel.hpp"
 #include "repack_kernel.hpp"
@@ -319,6 +320,21 @@ template <int DT, int kHalves> int launch_wide(unsigned grid, hipStream_t st, co
     return TIDE_OK;
 }
 
+// The band kernel: `grid` workgroups (a multiple of 8), each a contiguous band of the checkpoint-major list of
+// 32-row blocks; p.tiles_per_ckpt = blocks per checkpoint.
+template <int DT> int launch_band(unsigned grid, hipStream_t st, const PrefillParams& p) {
+    static bool raised[kMaxDevices] = {};
+    int dev = 0;
+    TIDE_HIP(hipGetDevice(&dev));
+    if (!raised[dev]) {
+        TIDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&tide_prefill_band_kernel<DT>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, kBandLdsBytes));
+        raised[dev] = true;
+    }
+    hipLaunchKernelGGL((tide_prefill_band_kernel<DT>), dim3(grid), dim3(kBandThreads), kBandLdsBytes, st, p);
+    return TIDE_OK;
+}
+
 // The split-k pair: `tiles` tiles of kBlocks*32 rows times p.k_slices workgroups leave their partial
 // results in `part`, then one small workgroup per 32-row block adds them and finishes the router.
 // Bytes of partial results the pair leaves for `tiles` tiles of kBlocks*32 rows in `halves` column halves and S slices.
@@ -404,7 +420,8 @@ enum PrefillKernel : int {
     kKernelTile = 4,       // prefill_tile_kernel.hpp
     kKernelStream128 = 5,  // prefill_dma_kernel.hpp, 128 rows per workgroup
     kKernelStream64 = 6,   // prefill_dma_kernel.hpp, 64 rows per workgroup (width 256: both column halves per wave)
-    kKernelRing = 7        // prefill_kernel.hpp
+    kKernelRing = 7,       // prefill_kernel.hpp
+    kKernelBand = 8        // prefill_band_kernel.hpp: rows_per_tile = 32 (the unit its bands are counted in)
 };
 struct PlannedLaunch {
     int kernel;            // PrefillKernel
@@ -499,6 +516,18 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
             plan.launch[plan.count++] = PlannedLaunch{kKernelSplitK, best_rows, (int)tpc, (int)tiles, 0, (int)best_S, (unsigned)(tiles * halves * best_S)};
             return plan;
         }
+    }
+    // Band form: one launch, every workgroup an equal share of the checkpoint-major list of 32-row blocks, cut
+    // into tiles of up to 288 rows by the kernel itself (16-bit rows, widths 64 / 128).
+    // It is the automatic choice from six blocks per CU on -- measured on 256 CUs against the wide-tile kernel and what
+    // it leaves to a second launch: 212-219 against 224-226 us on the 36-layer batched prefill (C = 9, T = 16384,
+    // d = 4096: 18 blocks per CU), 78 against 90 us at 6 per CU (C = 8, T = 6144), 59.5 against 63.5 us at d = 768,
+    // level where the batch is whole rounds of 256-row tiles anyway; at 5 blocks per CU it loses (90 against 83 us).
+    const int64_t blocks32 = C * ((T + 31) / 32);
+    if (!ring_form && dtype != TIDE_F32 && !two_halves && (form == 7 || (form == 0 && blocks32 >= 6 * (int64_t)cus))) {
+        const int64_t U = (T + 31) / 32;
+        plan.launch[plan.count++] = PlannedLaunch{kKernelBand, 32, (int)U, (int)(C * U), 0, 1, cus};
+        return plan;
     }
     // Wide-tile forms: whole rounds of wide tiles (256 rows, or 128 rows at width 256; one per CU and
     // round) go to a wide kernel, what is left of the checkpoint-major row list to a kernel with
@@ -621,6 +650,9 @@ int launch_prefill(const Scratch& sc, const PrefillPlan& plan, const void* hidde
                 break;
             case kKernelTile:
                 if constexpr (DT != kF32) rc = launch_tile<DT>(st, p);
+                break;
+            case kKernelBand:
+                if constexpr (DT != kF32) rc = launch_band<DT>(L.grid, st, p);
                 break;
             case kKernelStream128:
                 rc = launch_dma<DT, 128, 1>(L.grid, st, p);
@@ -1313,7 +1345,7 @@ namespace {
 // (bits 8-15: 0, 32, 64 or 128) and slice count (bits 16-23: 0, 2, 4 or 8).
 bool valid_form_word(int w) {
     const int form = w & 0xff, rows = (w >> 8) & 0xff, slices = (w >> 16) & 0xff;
-    if (w < 0 || (w >> 24) != 0 || form > 6) return false;
+    if (w < 0 || (w >> 24) != 0 || form > 7) return false;
     if ((rows || slices) && form != 5) return false;
     return (rows == 0 || rows == 32 || rows == 64 || rows == 128) && (slices == 0 || slices == 2 || slices == 4 || slices == 8);
 }
@@ -1325,7 +1357,7 @@ int tide_prefill_plan(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int
     if (!supported_hidden(dtype, d) || !supported_bottleneck(b)) return fail(TIDE_ERR_UNSUPPORTED, "d = %lld, b = %lld unsupported", (long long)d, (long long)b);
     if (needs_repack(dtype, d, b)) d = padded_hidden(dtype, d);      // such calls run the tuned kernels on zero-padded rows
     if (cus < 8 || cus % 8 != 0) return fail(TIDE_ERR_INVALID_ARG, "cus = %d must be a positive multiple of 8", cus);
-    if (!valid_form_word(form)) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d: a form in [0, 6], with form 5 optionally rows << 8 | slices << 16", form);
+    if (!valid_form_word(form)) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d: a form in [0, 7], with form 5 optionally rows << 8 | slices << 16", form);
     if (!out) return fail(TIDE_ERR_INVALID_ARG, "out must not be NULL");
     const PrefillPlan plan = plan_prefill(dtype, C, T, d, b, (unsigned)cus, form);
     for (int i = 0; i < plan.count; ++i) {
@@ -1357,8 +1389,22 @@ int tide_stream_schedule(int rows_per_tile, int64_t b, int64_t k_tiles, int grid
     return n;
 }
 
+int tide_band_schedule(int64_t C, int64_t blocks_per_ckpt, int grid, int block, int32_t* out, int max_items) {
+    if (C < 1 || C > TIDE_MAX_CHECKPOINTS || blocks_per_ckpt < 1 || C * blocks_per_ckpt > (int64_t)1 << 30)
+        return fail(TIDE_ERR_INVALID_ARG, "C = %lld, blocks_per_ckpt = %lld out of range", (long long)C, (long long)blocks_per_ckpt);
+    if (grid < 8 || grid % 8 != 0 || block < 0 || block >= grid) return fail(TIDE_ERR_INVALID_ARG, "grid = %d (a multiple of 8), block = %d", grid, block);
+    if (!out || max_items < 0) return fail(TIDE_ERR_INVALID_ARG, "out / max_items");
+    int n = 0;
+    for (BandWalk w(block, grid, (int)C, (int)blocks_per_ckpt); w.valid(); w.advance()) {
+        const BandTile t = w.current();
+        if (n < max_items) { out[3 * n] = t.c; out[3 * n + 1] = t.block0; out[3 * n + 2] = t.blocks; }
+        ++n;
+    }
+    return n;
+}
+
 int tide_set_prefill_form(int form) {
-    if (!valid_form_word(form)) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d: a form in [0, 6], with form 5 optionally rows << 8 | slices << 16", form);
+    if (!valid_form_word(form)) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d: a form in [0, 7], with form 5 optionally rows << 8 | slices << 16", form);
     std::lock_guard<std::mutex> lock(g_mu);
     int prev = g_prefill_form;
     g_prefill_form = form;

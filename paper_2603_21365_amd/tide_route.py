@@ -25,7 +25,7 @@ DTYPE_CODES = {"f32": F32, "f16": F16, "bf16": BF16}
 EXPORTS = (
     "tide_version", "tide_last_error", "tide_router_eval", "tide_select_exit",
     "tide_packed_router_bytes", "tide_router_pack", "tide_router_eval_packed",
-    "tide_select_exit_packed", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_batch_compact", "tide_set_variant", "tide_set_prefill_form", "tide_prefill_plan", "tide_stream_schedule", "tide_release",
+    "tide_select_exit_packed", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_batch_compact", "tide_set_variant", "tide_set_prefill_form", "tide_prefill_plan", "tide_stream_schedule", "tide_band_schedule", "tide_release",
     "tide_workspace_bytes", "tide_workspace_init", "tide_workspace_forget", "tide_router_eval_ws", "tide_select_exit_ws",
     "tide_select_exit_packed_noalloc", "tide_noalloc_scratch_bytes", "tide_workspace_allocations",
 )
@@ -79,6 +79,7 @@ def load_library() -> ctypes.CDLL:
     lib.tide_set_prefill_form.argtypes = [ci]
     lib.tide_prefill_plan.argtypes = [ci, i64, i64, i64, i64, ci, ci, vp]
     lib.tide_stream_schedule.argtypes = [ci, i64, i64, ci, ci, ci, ci, vp, ci]
+    lib.tide_band_schedule.argtypes = [i64, i64, ci, ci, vp, ci]
     for name in ("tide_router_eval", "tide_router_eval_packed", "tide_select_exit", "tide_select_exit_packed",
                  "tide_router_pack", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_batch_compact", "tide_set_variant", "tide_set_prefill_form", "tide_release",
                  "tide_router_eval_ws", "tide_select_exit_ws", "tide_select_exit_packed_noalloc", "tide_workspace_init", "tide_workspace_forget"):
@@ -159,6 +160,19 @@ def set_prefill_form(form: int) -> int:
     if prev < 0:
         _check(prev)
     return prev
+
+
+def band_schedule(C: int, blocks_per_ckpt: int, grid: int, block: int) -> list:
+    """Tiles (checkpoint, first 32-row block, blocks) of one workgroup of a band-kernel launch (host arithmetic)."""
+    cap = 64
+    while True:
+        out = (ctypes.c_int32 * (3 * cap))()
+        n = load_library().tide_band_schedule(int(C), int(blocks_per_ckpt), int(grid), int(block), out, cap)
+        if n < 0:
+            _check(n)
+        if n <= cap:
+            return [tuple(out[3 * i:3 * i + 3]) for i in range(n)]
+        cap = n
 
 
 PLAN_FIELDS = ("kernel", "rows_per_tile", "tiles_per_ckpt", "total_tiles", "tile_begin", "k_slices", "workgroups")

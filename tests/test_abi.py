@@ -149,7 +149,7 @@ def test_set_prefill_form_validates():
     prev = tr.set_prefill_form(0)
     assert prev & 0xff in (0, 1, 2, 3, 4, 5, 6)
     with pytest.raises(tr.TideError):
-        tr.set_prefill_form(7)
+        tr.set_prefill_form(8)
     # form 5 may carry a forced split-k shape (rows << 8 | slices << 16); no other form may, and only the shapes that exist
     word = tr.splitk_form(64, 4)
     assert word == 5 | 64 << 8 | 4 << 16

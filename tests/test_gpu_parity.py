@@ -107,11 +107,11 @@ def test_config1_full(tr, packed):
     assert st["max_abs_err"] < 1e-2                      # bf16 W1' rounding: well inside the 2e-2 bar
 
 
-@pytest.mark.parametrize("form", [1, 2, 3, 4, 5, 6, 0])
+@pytest.mark.parametrize("form", [1, 2, 3, 4, 5, 6, 7, 0])
 @pytest.mark.parametrize("dtype,T,d", [("bf16", 300, 1024), ("f16", 129, 768), ("f32", 257, 512), ("bf16", 64, 128), ("f16", 1100, 384)])
 def test_every_prefill_form_computes_the_same_function(tr, form, dtype, T, d):
     """Streaming form with 64 / 128 rows per workgroup, the register-ring form, the wide-tile form,
-    the split-k form, the one-tile form and the automatic choice, in turn, on ragged token counts and on a hidden
+    the split-k form, the one-tile form, the band form and the automatic choice, in turn, on ragged token counts and on a hidden
     size with a single k-tile (forms that do not apply to a case fall back to one that does)."""
     w = synth.Workload(f"form{form}_{dtype}_T{T}_d{d}", 29, dtype, d, 12, 4, T, None)
     rt = w.routers()
@@ -139,6 +139,10 @@ def test_every_prefill_form_computes_the_same_function(tr, form, dtype, T, d):
     (0, "f32", 20, 16384 + 77, 128, "fp32 rows, 325 tiles: one wide round, 69 left; two k-tiles of the ring kernel, four stages of the wide one"),
     (6, "bf16", 20, 8155, 256, "one-tile form: 320 tiles of 128 rows, a workgroup each (more than the CUs hold at once); ragged"),
     (0, "f16", 24, 4000, 384, "automatic choice at 192 tiles of 128 rows: the one-tile form; ragged"),
+    (7, "bf16", 36, 16384, 256, "band form: 9 x 512 blocks, 18 per workgroup: two tiles of 9, three where a checkpoint ends inside a band"),
+    (7, "f16", 12, 8155, 384, "band form: 3 x 255 blocks, 2 or 3 per workgroup; ragged last block"),
+    (7, "bf16", 40, 16384 + 77, 128, "band form: 10 x 515 blocks, 20 or 21 per workgroup: three tiles; single 128-byte k-tile pair"),
+    (7, "f16", 8, 100, 512, "band form: 8 blocks on 256 workgroups, most without a block"),
 ])
 def test_uneven_tile_counts_split_the_last_round(tr, form, dtype, layers, T, d, what):
     """Tile counts that do not divide among the persistent workgroups: the tiles of the last
@@ -246,11 +250,17 @@ def test_config2_decode(tr, T):
 
 # ------------------------------------------------------------------ config 3: 36-layer batched prefill, bf16, full size
 
-def test_config3_full(tr):
+@pytest.mark.parametrize("form", [0, 7])
+def test_config3_full(tr, form):
+    """The automatic choice, and the band form forced (whichever of the two the automatic choice is not)."""
     w = synth.config3()
     t0 = time.time()
-    st, (ex_o, _, m_o), _ = run_and_compare(tr, w, "config3", packed=True)
-    say(f"config3 done in {time.time() - t0:.1f}s")
+    tr.set_prefill_form(form)
+    try:
+        st, (ex_o, _, m_o), _ = run_and_compare(tr, w, f"config3_form{form}", packed=True)
+    finally:
+        tr.set_prefill_form(0)
+    say(f"config3 form {form} done in {time.time() - t0:.1f}s")
     assert [(int(((m_o >> c) & 1).sum())) for c in range(w.C)] == [round(0.20 * w.T)] * w.C
 
 
@@ -431,7 +441,7 @@ def test_every_element_enters_the_sum_of_squares(tr, dtype, d):
     ex_o, z_o, m_o = oracle_select(w, rt, hb)
     dev = to_device(hb, dtype)
     g, W1, b1, w2 = routers_to_device(rt)
-    for form in (1, 2, 3, 4):
+    for form in (1, 2, 3, 4, 7):
         tr.set_prefill_form(form)
         tr.set_variant(tr.VARIANT_PREFILL)
         try:

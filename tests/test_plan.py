@@ -8,7 +8,7 @@ import pytest
 
 from paper_2603_21365_amd import tide_route as tr
 
-SPLITK, WIDE, WIDE_F32, TILE, STREAM128, STREAM64, RING = 1, 2, 3, 4, 5, 6, 7
+SPLITK, WIDE, WIDE_F32, TILE, STREAM128, STREAM64, RING, BAND = 1, 2, 3, 4, 5, 6, 7, 8
 ELEM = {tr.F32: 4, tr.F16: 2, tr.BF16: 2}
 
 
@@ -64,6 +64,8 @@ def check_plan(dtype, C, T, d, b, cus, form):
             assert halves == 1 or k == STREAM64, what
         if k == RING:
             assert R == 64 and halves == 1, what
+        if k == BAND:
+            assert len(plan) == 1 and R == 32 and dtype != tr.F32 and halves == 1 and d % 128 == 0 and wg == cus, what
         if d % 128 != 0:
             assert k == RING and len(plan) == 1, what
     if len(plan) == 2:
@@ -76,7 +78,7 @@ SHAPES = [(8, 4096, 4096), (9, 16384, 4096), (10, 16384, 768), (10, 16384, 8192)
           (7, 2049, 3072), (2, 12345, 5120), (8, 2048, 4096), (8, 3072, 4096), (8, 1536, 4096), (1, 16384, 4096)]
 
 
-@pytest.mark.parametrize("form", [0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("form", [0, 1, 2, 3, 4, 5, 6, 7])
 @pytest.mark.parametrize("dtype", [tr.BF16, tr.F16, tr.F32])
 def test_every_row_is_in_exactly_one_tile(dtype, form):
     for C, T, d in SHAPES:
@@ -96,7 +98,7 @@ def test_every_row_is_in_exactly_one_tile_on_random_shapes():
         d = int(rng.choice([128, 256, 384, 768, 1024, 2048, 2560, 4096, 5120, 8192, 16384]))
         b = int(rng.choice([64, 128, 256]))
         cus = int(rng.choice([8, 64, 128, 256, 304]))
-        form = int(rng.integers(0, 7))
+        form = int(rng.integers(0, 8))
         check_plan(dtype, C, T, d, b, cus, form)
 
 
@@ -138,9 +140,57 @@ def test_the_persistent_schedule_covers_every_tile_once():
     assert checked > 60
 
 
+def check_band_schedule(C, U, grid):
+    """Every 32-row block of every checkpoint lies in exactly one tile of exactly one workgroup; a tile has 1 to 9
+    blocks of one checkpoint; the workgroups' shares differ by at most one block; XCD x (workgroup id mod 8) owns
+    a contiguous eighth of the list."""
+    seen = np.zeros((C, U), np.uint8)
+    share = []
+    first = {}
+    for block in range(grid):
+        tiles = tr.band_schedule(C, U, grid, block)
+        n = 0
+        pos = None
+        for c, b0, nb in tiles:
+            assert 0 <= c < C and 1 <= nb <= 9 and 0 <= b0 and b0 + nb <= U, (C, U, grid, block, tiles)
+            assert pos is None or pos == c * U + b0, "a workgroup's tiles are contiguous in the checkpoint-major list"
+            pos = c * U + b0 + nb
+            seen[c, b0:b0 + nb] += 1
+            n += nb
+        # as few tiles as cover each piece of the band: a piece of L blocks within one checkpoint takes ceil(L / 9)
+        pieces = {}
+        for c, b0, nb in tiles:
+            pieces.setdefault(c, []).append(nb)
+        for c, sizes in pieces.items():
+            assert len(sizes) == -(-sum(sizes) // 9) and max(sizes) - min(sizes) <= 1, (C, U, grid, block, tiles)
+        share.append(n)
+        if tiles:
+            first[block] = tiles[0][0] * U + tiles[0][1]
+    assert seen.min() == 1 and seen.max() == 1, (C, U, grid)
+    assert max(share) - min(share) <= 1, (C, U, grid, share)
+    for x in range(8):                      # XCD x: workgroups x, x + 8, ... take ascending, adjacent bands
+        starts = [first[b] for b in range(x, grid, 8) if b in first]
+        assert starts == sorted(starts)
+        if x and starts:
+            prev = [first[b] for b in range(x - 1, grid, 8) if b in first]
+            assert not prev or max(prev) < min(starts)
+
+
+def test_the_band_schedule_covers_every_block_once():
+    rng = np.random.default_rng(11)
+    cases = [(9, 512, 256), (10, 512, 256), (8, 128, 256), (1, 1, 8), (1, 7, 256), (3, 1000, 304), (32, 17, 64), (2, 5000, 8)]
+    for _ in range(200):
+        cases.append((int(rng.integers(1, 33)), int(rng.choice([rng.integers(1, 40), rng.integers(1, 2000)])), int(rng.choice([8, 64, 256, 304]))))
+    for C, U, grid in cases:
+        check_band_schedule(C, U, grid)
+    # the 36-layer batched prefill on 256 CUs: 18 blocks per workgroup, two tiles of 9 unless a checkpoint ends inside the band
+    counts = [len(tr.band_schedule(9, 512, 256, block)) for block in range(256)]
+    assert sorted(set(counts)) == [2, 3] and counts.count(3) == 8
+
+
 def test_generic_hidden_sizes_take_the_register_ring_kernel():
     for dtype, d in ((tr.BF16, 200), (tr.F16, 72), (tr.F32, 100), (tr.BF16, 4104), (tr.F32, 708)):
-        for form in range(7):
+        for form in range(8):
             for C, T in ((1, 1), (4, 300), (10, 16384)):
                 plan = check_plan(dtype, C, T, d, 128, 256, form)
                 assert [L["kernel"] for L in plan] == [RING]
@@ -150,9 +200,11 @@ def test_the_choices_on_the_named_workloads():
     """What the automatic choice is on a 256-CU device for the workloads the measurements quote."""
     kinds = lambda plan: [(L["kernel"], L["rows_per_tile"]) for L in plan]
     assert kinds(tr.prefill_plan(tr.BF16, 8, 4096, 4096)) == [(TILE, 128)]                       # one tile per CU
-    assert kinds(tr.prefill_plan(tr.BF16, 9, 16384, 4096)) == [(WIDE, 256), (STREAM64, 64)]      # two wide rounds + the rest (128 tiles of 128 rows)
-    assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096)) == [(WIDE, 256), (TILE, 128)]        # ... + a full round of 128-row tiles
-    assert kinds(tr.prefill_plan(tr.BF16, 8, 8192, 4096)) == [(WIDE, 256)]                        # exactly one wide round
+    assert kinds(tr.prefill_plan(tr.BF16, 9, 16384, 4096)) == [(BAND, 32)]                        # 18 blocks of 32 rows per CU: the band form
+    assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096)) == [(BAND, 32)]                       # 20 per CU
+    assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256)) == [(WIDE, 128)]                 # width 256: five rounds of 128-row tiles; the band form has no such width
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 8192, 4096)) == [(BAND, 32)]                         # 8 per CU (= one round of 256-row tiles)
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 5120, 4096)) == [(WIDE, 256)]                        # 5 per CU: 160 wide tiles on 160 CUs
     assert kinds(tr.prefill_plan(tr.F32, 10, 16384, 4096)) == [(WIDE_F32, 256), (RING, 64)]
     assert kinds(tr.prefill_plan(tr.F16, 8, 8, 4096)) == [(SPLITK, 32)]                           # a decode step on packed weights
     assert tr.prefill_plan(tr.F16, 8, 8, 4096)[0]["k_slices"] == 8
@@ -165,8 +217,9 @@ def test_the_choices_on_the_named_workloads():
     assert kinds(tr.prefill_plan(tr.BF16, 8, 4096, 4096, 256)) == [(WIDE, 128)]                   # width 256: one round of 128-row tiles
     assert kinds(tr.prefill_plan(tr.BF16, 8, 2048, 4096)) == [(STREAM64, 64)]                     # 128 tiles of 128 rows: a 64-row workgroup per CU
     assert kinds(tr.prefill_plan(tr.BF16, 8, 2080, 4096)) == [(TILE, 128)]                        # 136 tiles: the 64-row kernel would need two per CU
-    assert kinds(tr.prefill_plan(tr.BF16, 8, 6144, 4096)) == [(WIDE, 256)]                        # 192 wide tiles: three quarters of a round
-    assert tr.prefill_plan(tr.BF16, 8, 6144, 4096)[0]["workgroups"] == 192
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 6144, 4096)) == [(BAND, 32)]                         # 6 blocks per CU
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 6144, 4096, form=4)) == [(WIDE, 256)]                # 192 wide tiles: three quarters of a round
+    assert tr.prefill_plan(tr.BF16, 8, 6144, 4096, form=4)[0]["workgroups"] == 192
     assert kinds(tr.prefill_plan(tr.BF16, 8, 4608, 4096)) == [(WIDE, 256)]                        # 144 wide tiles: still more than half a round
     assert kinds(tr.prefill_plan(tr.BF16, 8, 4096 + 128, 4096)) == [(WIDE, 256)]                  # 136 wide tiles, the last of each checkpoint half empty
     assert kinds(tr.prefill_plan(tr.BF16, 8, 3072, 4096, 256)) == [(WIDE, 128)]                   # width 256: 192 tiles of 128 rows on 192 CUs
@@ -188,8 +241,20 @@ def test_a_forced_split_k_shape_is_taken_as_given():
             tr.prefill_plan(tr.BF16, 1, 100, 512, form=word)
 
 
+def test_the_band_form_is_one_launch_over_all_blocks():
+    for dtype in (tr.BF16, tr.F16):
+        for C, T, d, b in ((9, 16384, 4096, 128), (10, 16384, 768, 64), (3, 1000, 1024, 128), (1, 1, 128, 128)):
+            (L,) = tr.prefill_plan(dtype, C, T, d, b, form=7)
+            assert (L["kernel"], L["rows_per_tile"], L["tiles_per_ckpt"], L["total_tiles"], L["tile_begin"], L["workgroups"]) == \
+                   (BAND, 32, -(-T // 32), C * -(-T // 32), 0, 256)
+    # fp32 rows, width 256 and other hidden sizes fall back to forms that apply
+    assert BAND not in [L["kernel"] for L in tr.prefill_plan(tr.F32, 9, 16384, 4096, form=7)]
+    assert BAND not in [L["kernel"] for L in tr.prefill_plan(tr.BF16, 9, 16384, 4096, 256, form=7)]
+    assert [L["kernel"] for L in tr.prefill_plan(tr.BF16, 9, 16384, 200, form=7)] == [RING]
+
+
 def test_plan_rejects_bad_arguments():
-    bad = [dict(dtype=9), dict(C=0), dict(C=33), dict(T=0), dict(d=100000), dict(d=0), dict(b=96), dict(cus=100), dict(cus=0), dict(form=7)]
+    bad = [dict(dtype=9), dict(C=0), dict(C=33), dict(T=0), dict(d=100000), dict(d=0), dict(b=96), dict(cus=100), dict(cus=0), dict(form=8)]
     # hidden sizes of the generic fallback that are copied into zero-padded rows first are planned at the padded size
     assert tr.prefill_plan(tr.BF16, 4, 1000, 130) == tr.prefill_plan(tr.BF16, 4, 1000, 131)[:] == tr.prefill_plan(tr.BF16, 4, 1000, 256)
     assert tr.prefill_plan(tr.BF16, 4, 1000, 200, 256) == tr.prefill_plan(tr.BF16, 4, 1000, 256, 256)
