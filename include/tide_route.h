@@ -272,7 +272,7 @@ int tide_set_variant(int variant);
  * form (256 rows per workgroup, 16-bit types) for as many whole tiles as there are workgroups,
  * 5 = split-k form (several workgroups share a tile's hidden dimension and a second launch adds
  * their partial results) with at least two slices, 6 = one 128-row tile per workgroup
- * without the persistent schedule (16-bit types, widths 64 / 128), 7 = band form (one launch, every
+ * without the persistent schedule (16-bit types; at width 256 with eight consumer waves), 7 = band form (one launch, every
  * workgroup an equal share of the 32-row blocks, tiles of up to 288 rows; 16-bit types, widths
  * 64 / 128).  With form 5 the word may also
  * fix the split-k tile height and slice count: 5 | rows << 8 | slices << 16 with rows in {0, 32, 64,

@@ -34,12 +34,20 @@ __device__ unsigned long long* g_tile_timeline = nullptr;
 #endif
 
 constexpr int kTileRows = 128;
-constexpr int kTileLdsBytes = dma_lds_bytes<kTileRows>();
+// kHalves = 128-column halves of the bottleneck (2 at width 256): 4 consumer waves per half, wave w owning columns
+// 32 (w % 4) .. + 31 of half w / 4.  Every wave has columns of its own, so its W1' fragments still come straight from
+// L2, once per workgroup; the ring holds rows only (three stages of 32 KiB in flight whatever the width).
+constexpr int tile_consumers(int kHalves) { return kDmaConsumers * kHalves; }
+constexpr int tile_threads(int kHalves) { return (tile_consumers(kHalves) + kDmaProducers) * kWave; }          // 384 / 640
+constexpr int tile_lds_bytes(int kHalves) {
+    // ring + per-wave row sums of squares (the waves of half 0) + per-wave logit partials
+    return kDmaStages * kTileRows * kTileBytes + (kDmaConsumers + tile_consumers(kHalves)) * kTileRows * (int)sizeof(float);
+}
 
 // blockIdx.x -> tile as in the other forms: XCD x (workgroup id mod 8) takes the x-th eighth of the
 // checkpoint-major tile list from p.tile_begin on, so that an XCD's L2 holds one W1' at a time.
-template <int DT>
-__global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const PrefillParams p) {
+template <int DT, int kHalves>
+__global__ __launch_bounds__(tile_threads(kHalves), 1) void tide_prefill_tile_kernel(const PrefillParams p) {
     static_assert(DT != kF32, "16-bit storage types only");
     typedef __attribute__((address_space(3))) char lds_char;
     typedef __attribute__((address_space(1))) const char glb_char;
@@ -48,8 +56,9 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
     constexpr int kStageBytes = kRowsM * kTileBytes;
     constexpr int kInstrPerProducer = kRowsM / 4 / kDmaProducers;   // one transfer = 4 rows x 256 B
     char* ring = smem;
+    constexpr int kConsumers = tile_consumers(kHalves);
     float* ss_part = reinterpret_cast<float*>(smem + kDmaStages * kStageBytes);   // [4][kRowsM]
-    float* z_part = ss_part + kDmaConsumers * kRowsM;                              // [4][kRowsM]
+    float* z_part = ss_part + kDmaConsumers * kRowsM;                              // [kConsumers][kRowsM]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 #ifdef TIDE_TILE_TIMELINE
@@ -68,9 +77,9 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
     const int c = tile / p.tiles_per_ckpt;
     const int row0 = (tile - c * p.tiles_per_ckpt) * kRowsM;
 
-    if (wave >= kDmaConsumers) {
+    if (wave >= kConsumers) {
         // ------------------------------------------------------------------ producers
-        const int pw = wave - kDmaConsumers;
+        const int pw = wave - kConsumers;
         const int rl = lane >> 4, slot = lane & 15;
         const char* base = p.hidden + (int64_t)c * p.ckpt_stride_bytes;
         const char* gp[kInstrPerProducer];
@@ -109,17 +118,23 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
     }
 
     // ---------------------------------------------------------------------- consumers
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave);     // uniform: branches on it are scalar
+    const int half = wave >> 2, cw = wave & 3;                   // column half, column block within it
+    const int wave_u = __builtin_amdgcn_readfirstlane(cw);       // uniform: branches on it are scalar
+    const int half_u = __builtin_amdgcn_readfirstlane(half);
     const int r = lane & 31;
     const int a_base = r * kTileBytes;
     const int y16 = ((lane >> 5) ^ (r & 15)) << 4;               // see prefill_dma_kernel.hpp
     const size_t ckpt_chunks = (size_t)p.d * kBottleneck / Storage<DT>::kElems;
-    const u32x4* bptr = p.packed + (size_t)c * ckpt_chunks + wave * 64 + lane;
+    const u32x4* bptr = p.packed + ((size_t)c * kHalves + half) * ckpt_chunks + cw * 64 + lane;
     // The matrix steps take W1' first and the rows second: the accumulators hold the transposed product,
     // a lane owning one row per block and 16 of the wave's 32 columns (router_epilogue_row).  The b1 / w2
     // of those columns are fetched now so that the epilogue does not wait for them (columns at and
     // beyond the bottleneck width are zero padding: their w2 is zero).
-    const EpilogueColumns ecols = load_epilogue_columns(p.b1 ? p.b1 + c * p.b : nullptr, p.w2 + c * p.b, p.b, 32 * wave, lane);
+    // (With eight consumer waves there are 168 registers per wave and the k loop needs them: there the 32 registers
+    // of these constants are fetched after the loop, and the first epilogue barrier covers most of the round trip.)
+    auto fetch_ecols = [&]() { return load_epilogue_columns(p.b1 ? p.b1 + c * p.b : nullptr, p.w2 + c * p.b, p.b, kBottleneck * half + 32 * cw, lane); };
+    EpilogueColumns ecols;
+    if constexpr (kHalves == 1) ecols = fetch_ecols();
     constexpr int kGroups = Compute<DT>::kMmaGroups;             // 8
     u32x4 breg[kGroups];                                         // W1' fragments, one k-tile ahead
 #pragma unroll
@@ -147,7 +162,7 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
             if (g + 1 < kGroups) read_a(g + 1, a[(g + 1) & 1]);      // (two groups ahead: measured, no further gain)
 #pragma unroll
             for (int b = 0; b < kBlocks; ++b) acc[b] = mma_k16<DT>(breg[g], cur[b], acc[b]);
-            if ((g & 3) == wave_u) {               // this wave's share of the sums of squares
+            if ((g & 3) == wave_u && half_u == 0) {   // this wave's share of the sums of squares (the waves of half 0 cover every chunk)
 #pragma unroll
                 for (int b = 0; b < kBlocks; ++b) ssq[b] = chunk_sumsq<DT>(cur[b], ssq[b]);
             }
@@ -164,11 +179,12 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
     k_tile(ring + ((ntile - 1) % kDmaStages) * kStageBytes + a_base, 0, std::false_type{});
     TIDE_STAMP();
 
+    if constexpr (kHalves == 2) ecols = fetch_ecols();
     // ---- row sums of squares: lanes l and l^32 hold the two chunk phases; the 4 waves the rest
 #pragma unroll
     for (int b = 0; b < kBlocks; ++b) {
         const float s2 = ssq[b] + __shfl_xor(ssq[b], 32, kWave);
-        if (lane < 32) ss_part[wave * kRowsM + 32 * b + lane] = s2;
+        if (lane < 32 && half == 0) ss_part[cw * kRowsM + 32 * b + lane] = s2;
     }
     __syncthreads();
     TIDE_STAMP();
@@ -187,8 +203,10 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_tile_kernel(const
     if (tid < kRowsM) {
         const int t = row0 + tid;
         if (t < p.T) {
-            const float z = p.tab.b2[c] + ((z_part[tid] + z_part[kRowsM + tid]) + (z_part[2 * kRowsM + tid] + z_part[3 * kRowsM + tid]));
-            emit_router_result(p, c, t, z);
+            float zsum = (z_part[tid] + z_part[kRowsM + tid]) + (z_part[2 * kRowsM + tid] + z_part[3 * kRowsM + tid]);
+            if constexpr (kHalves == 2)
+                zsum += (z_part[4 * kRowsM + tid] + z_part[5 * kRowsM + tid]) + (z_part[6 * kRowsM + tid] + z_part[7 * kRowsM + tid]);
+            emit_router_result(p, c, t, p.tab.b2[c] + zsum);
         }
     }
 #ifdef TIDE_TILE_TIMELINE

@@ -380,17 +380,17 @@ int launch_wide_f32(unsigned grid, hipStream_t st, const PrefillParams& p) {
 }
 
 // The one-tile kernel: a workgroup per 128-row tile from p.tile_begin on.
-template <int DT> int launch_tile(hipStream_t st, const PrefillParams& p) {
+template <int DT, int kHalves> int launch_tile(hipStream_t st, const PrefillParams& p) {
     static bool raised[kMaxDevices] = {};
     int dev = 0;
     TIDE_HIP(hipGetDevice(&dev));
     if (!raised[dev]) {
-        TIDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&tide_prefill_tile_kernel<DT>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, kTileLdsBytes));
+        TIDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&tide_prefill_tile_kernel<DT, kHalves>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, tile_lds_bytes(kHalves)));
         raised[dev] = true;
     }
     const unsigned grid = 8u * (unsigned)((p.total_tiles - p.tile_begin + 7) / 8);
-    hipLaunchKernelGGL((tide_prefill_tile_kernel<DT>), dim3(grid), dim3(kDmaThreads), kTileLdsBytes, st, p);
+    hipLaunchKernelGGL((tide_prefill_tile_kernel<DT, kHalves>), dim3(grid), dim3(tile_threads(kHalves)), tile_lds_bytes(kHalves), st, p);
     return TIDE_OK;
 }
 
@@ -464,7 +464,14 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
     // k-tile of W1' in flight, too little to cover the L2 round trip: measured slower.
     const bool ring_form = generic_d || (!two_halves && (form == 3 || (form == 0 && dtype == TIDE_F32)));
     if (ring_form) rows_per_wg = kRows;
-    if (two_halves) rows_per_wg = 64;
+    // Width 256 from more than half as many 128-row tiles as CUs on: the one-tile kernel with eight consumer waves, a
+    // workgroup per tile however many rounds that makes -- the rows have the whole ring (three stages of 32 KiB in flight;
+    // the wide-tile kernel, which also sends W1' through LDS, has 32 KiB) and every wave fetches the W1' of its own
+    // columns straight from L2.  Measured against the wide-tile kernel (bf16, C = 8, d = 4096): 77-83 against 85.5 us at
+    // T = 4096, 66 against 73.5 us at 3072, 59 against 66 us at 2304, 309 against 322 us at 16384; d = 8192: 149 against
+    // 167 us; at 128 tiles the 64-row kernel's one workgroup per CU still wins (52.7 against 59.9 us).
+    const bool tile256 = two_halves && dtype != TIDE_F32 && !generic_d && (form == 6 || (form == 0 && 2 * tiles128 > (int64_t)cus));
+    if (two_halves) rows_per_wg = tile256 ? 128 : 64;
     int64_t tiles_per_ckpt = (T + rows_per_wg - 1) / rows_per_wg;
     int64_t total_tiles = C * tiles_per_ckpt, tile_begin = 0;
 
@@ -534,7 +541,7 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
     // smaller tiles behind it on the same stream (the arrival words carry the per-token state across
     // the two launches): 16-bit rows to the streaming kernel with half as many rows per tile, fp32
     // rows to the register-ring kernel.
-    const bool wide16 = !ring_form && dtype != TIDE_F32 && (form == 0 || form == 4);
+    const bool wide16 = !ring_form && dtype != TIDE_F32 && !tile256 && (form == 0 || form == 4);
     const bool wide32 = dtype == TIDE_F32 && !generic_d && !two_halves && (form == 0 || form == 4);
     if (wide16 || wide32) {
         const int64_t wrows = two_halves ? kWideRows / 2 : kWideRows;
@@ -579,8 +586,8 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
     if (!ring_form) {
         // One whole 128-row tile for every CU or none (more than half as many tiles as CUs, at most as
         // many): the one-tile kernel, 1-3 % faster than the persistent one on such batches.
-        const bool one_tile_each = !two_halves && dtype != TIDE_F32 && rows_per_wg == 128 &&
-                                   (form == 6 || (form == 0 && 2 * left > (int64_t)cus && left <= (int64_t)cus));
+        const bool one_tile_each = dtype != TIDE_F32 && rows_per_wg == 128 &&
+                                   (form == 6 || tile256 || (form == 0 && !two_halves && 2 * left > (int64_t)cus && left <= (int64_t)cus));
         kernel = one_tile_each ? kKernelTile : rows_per_wg == 128 ? kKernelStream128 : kKernelStream64;
         if (!one_tile_each) {
             // The streaming kernels are persistent: at most one (128-row; width 256: the two-halves
@@ -649,7 +656,7 @@ int launch_prefill(const Scratch& sc, const PrefillPlan& plan, const void* hidde
                 rc = launch_wide_f32(L.grid, st, p);
                 break;
             case kKernelTile:
-                if constexpr (DT != kF32) rc = launch_tile<DT>(st, p);
+                if constexpr (DT != kF32) rc = two_halves ? launch_tile<DT, 2>(st, p) : launch_tile<DT, 1>(st, p);
                 break;
             case kKernelBand:
                 if constexpr (DT != kF32) rc = launch_band<DT>(L.grid, st, p);

@@ -306,6 +306,16 @@ def test_table2_pairs_prefill(tr, d, b):
     assert st["max_abs_err"] < 1e-2
 
 
+@pytest.mark.parametrize("d,T", [(4096, 4096), (2048, 2500)])
+def test_width_256_at_the_measured_size(tr, d, T):
+    """Width 256 at the batch sizes whose timing the bench quotes (one 128-row tile per CU, a ragged case with
+    fewer): the automatic choice there is the one-tile kernel with eight consumer waves."""
+    w = synth.table2(d, 256, "bf16", T=T)
+    assert [L["kernel"] for L in tr.prefill_plan(tr.BF16, w.C, T, d, 256)] == [4]
+    st, _, _ = run_and_compare(tr, w, f"{w.name}_T{T}", packed=True)
+    assert st["max_abs_err"] < 1e-2
+
+
 @pytest.mark.parametrize("b", [64, 256])
 @pytest.mark.parametrize("dtype,T,d", [("bf16", 300, 1024), ("f16", 129, 768), ("f32", 257, 512), ("bf16", 4100, 256),
                                        ("f16", 1100, 384)])
@@ -317,7 +327,7 @@ def test_bottleneck_widths_every_dtype_and_form(tr, b, dtype, T, d):
     rt.b2[:] = [0.2, -0.1, 0.0]
     hb = w.hidden()
     run_and_compare(tr, w, w.name + "_raw", rt=rt, hidden_bits=hb, variant=tr.VARIANT_PREFILL)
-    for form in (1, 2, 3, 4):
+    for form in (1, 2, 3, 4, 6, 7):
         tr.set_prefill_form(form)
         try:
             run_and_compare(tr, w, f"{w.name}_form{form}", rt=rt, hidden_bits=hb, packed=True, variant=tr.VARIANT_PREFILL)
@@ -441,7 +451,7 @@ def test_every_element_enters_the_sum_of_squares(tr, dtype, d):
     ex_o, z_o, m_o = oracle_select(w, rt, hb)
     dev = to_device(hb, dtype)
     g, W1, b1, w2 = routers_to_device(rt)
-    for form in (1, 2, 3, 4, 7):
+    for form in (1, 2, 3, 4, 6, 7):
         tr.set_prefill_form(form)
         tr.set_variant(tr.VARIANT_PREFILL)
         try:

@@ -56,7 +56,7 @@ def check_plan(dtype, C, T, d, b, cus, form):
             assert (dtype == tr.F32) == (k == WIDE_F32), what
             assert not (k == WIDE_F32 and halves == 2), what
         if k == TILE:
-            assert R == 128 and dtype != tr.F32 and halves == 1 and d % 128 == 0, what
+            assert R == 128 and dtype != tr.F32 and d % 128 == 0, what
             assert wg == 8 * -(-(L["total_tiles"] - L["tile_begin"]) // 8), what
         if k in (STREAM128, STREAM64):
             assert R == (128 if k == STREAM128 else 64) and d % 128 == 0, what
@@ -202,7 +202,9 @@ def test_the_choices_on_the_named_workloads():
     assert kinds(tr.prefill_plan(tr.BF16, 8, 4096, 4096)) == [(TILE, 128)]                       # one tile per CU
     assert kinds(tr.prefill_plan(tr.BF16, 9, 16384, 4096)) == [(BAND, 32)]                        # 18 blocks of 32 rows per CU: the band form
     assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096)) == [(BAND, 32)]                       # 20 per CU
-    assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256)) == [(WIDE, 128)]                 # width 256: five rounds of 128-row tiles; the band form has no such width
+    assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256)) == [(TILE, 128)]                 # width 256: the one-tile kernel, five rounds of workgroups; the band form has no such width
+    assert tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256)[0]["workgroups"] == 1280
+    assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256, form=4)) == [(WIDE, 128)]         # ... the wide-tile kernel when forced
     assert kinds(tr.prefill_plan(tr.BF16, 8, 8192, 4096)) == [(BAND, 32)]                         # 8 per CU (= one round of 256-row tiles)
     assert kinds(tr.prefill_plan(tr.BF16, 8, 5120, 4096)) == [(WIDE, 256)]                        # 5 per CU: 160 wide tiles on 160 CUs
     assert kinds(tr.prefill_plan(tr.F32, 10, 16384, 4096)) == [(WIDE_F32, 256), (RING, 64)]
@@ -214,7 +216,8 @@ def test_the_choices_on_the_named_workloads():
     assert (p4096["kernel"], p4096["rows_per_tile"], p4096["k_slices"], p4096["workgroups"]) == (SPLITK, 64, 4, 256)
     assert kinds(tr.prefill_plan(tr.BF16, 1, 8192, 4096)) == [(STREAM128, 128)]                   # 64 tiles: pieces of the persistent kernel
     assert kinds(tr.prefill_plan(tr.BF16, 1, 1024, 1024)) == [(STREAM128, 128)]                   # short rows: the chain is short already
-    assert kinds(tr.prefill_plan(tr.BF16, 8, 4096, 4096, 256)) == [(WIDE, 128)]                   # width 256: one round of 128-row tiles
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 4096, 4096, 256)) == [(TILE, 128)]                   # width 256: one 128-row tile per CU, eight consumer waves
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 2048, 4096, 256)) == [(STREAM64, 64)]                # ... 128 tiles: a 64-row workgroup per CU
     assert kinds(tr.prefill_plan(tr.BF16, 8, 2048, 4096)) == [(STREAM64, 64)]                     # 128 tiles of 128 rows: a 64-row workgroup per CU
     assert kinds(tr.prefill_plan(tr.BF16, 8, 2080, 4096)) == [(TILE, 128)]                        # 136 tiles: the 64-row kernel would need two per CU
     assert kinds(tr.prefill_plan(tr.BF16, 8, 6144, 4096)) == [(BAND, 32)]                         # 6 blocks per CU
@@ -222,8 +225,8 @@ def test_the_choices_on_the_named_workloads():
     assert tr.prefill_plan(tr.BF16, 8, 6144, 4096, form=4)[0]["workgroups"] == 192
     assert kinds(tr.prefill_plan(tr.BF16, 8, 4608, 4096)) == [(WIDE, 256)]                        # 144 wide tiles: still more than half a round
     assert kinds(tr.prefill_plan(tr.BF16, 8, 4096 + 128, 4096)) == [(WIDE, 256)]                  # 136 wide tiles, the last of each checkpoint half empty
-    assert kinds(tr.prefill_plan(tr.BF16, 8, 3072, 4096, 256)) == [(WIDE, 128)]                   # width 256: 192 tiles of 128 rows on 192 CUs
-    assert kinds(tr.prefill_plan(tr.BF16, 8, 7168, 4096, 256)) == [(WIDE, 128)]                   # ... and 448: a round and three quarters
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 3072, 4096, 256)) == [(TILE, 128)]                   # width 256: 192 tiles of 128 rows on 192 CUs
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 7168, 4096, 256)) == [(TILE, 128)]                   # ... and 448: a round and three quarters
     assert kinds(tr.prefill_plan(tr.F32, 8, 7168, 4096)) == [(WIDE_F32, 256)]                     # fp32 rows: 224 wide tiles
     assert kinds(tr.prefill_plan(tr.F32, 1, 9216, 4096)) == [(RING, 64)]                          # fp32, 72 tiles: the split-k chain is too long
     assert kinds(tr.prefill_plan(tr.F32, 1, 8192, 4096)) == [(SPLITK, 64)]
