@@ -34,6 +34,31 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}
 
 
+def pmc_shapes(tr) -> int:
+    """Three shapes, ten launches each on two rotating batches of random bf16 rows, nothing timed: each runs on one
+    kernel of its own, so a counter run's per-kernel means are per shape (profiles/per_cu_load_path_pmc.txt)."""
+    import numpy as np
+    import torch
+    gen = torch.Generator(device="cuda").manual_seed(0x71DE)
+    shapes = []
+    for C, T, d, b in ((8, 4096, 4096, 128), (9, 16384, 4096, 128), (8, 4096, 4096, 256)):
+        rows = [torch.randn((C, T, d), generator=gen, device="cuda").to(torch.bfloat16) for _ in range(2)]
+        W1 = torch.randn((C, d, b), generator=gen, device="cuda") / d ** 0.5
+        w2 = torch.randn((C, b), generator=gen, device="cuda") / b ** 0.5
+        packed = tr.router_pack(tr.BF16, None, W1)
+        out = (torch.empty(T, dtype=torch.int32, device="cuda"), torch.empty((C, T), dtype=torch.float32, device="cuda"),
+               torch.empty(T, dtype=torch.int32, device="cuda"))
+        ids = np.arange(3, 4 * C, 4, dtype=np.int32)
+        for k in range(10):
+            tr.select_exit_packed(rows[k % 2], packed, 1e-6, None, w2, np.zeros(C, np.float32), np.full(C, 0.5, np.float32), ids, 0,
+                                  4 * C, d=d, out=out)
+        torch.cuda.synchronize()
+        shapes.append({"C": C, "T": T, "d": d, "b": b, "plan": tr.prefill_plan(tr.BF16, C, T, d, b)})
+        del rows, W1, packed
+    print(json.dumps({"pmc_shapes": shapes}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -46,6 +71,9 @@ def main() -> int:
                     help="skip the steps around the path (exit projection, calibration labels, other bottleneck widths)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the hidden-size x dtype sweep (configs[4])")
     ap.add_argument("--no-settle", action="store_true", help="skip the untimed settling phase (short profiler runs)")
+    ap.add_argument("--pmc-shapes", action="store_true",
+                    help="only launch three shapes ten times each, untimed, for rocprofv3 --pmc runs: configs[1] (one-tile kernel), "
+                         "configs[3] (band kernel) and width 256 at C=8, T=4096, d=4096 (one-tile kernel, eight consumer waves)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 256 MiB device copy 3 times (known traffic, scales the profiler's "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -65,6 +93,8 @@ def main() -> int:
 
     from paper_2603_21365_amd import synth
     from paper_2603_21365_amd import tide_route as tr
+    if args.pmc_shapes:
+        return pmc_shapes(tr)
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
@@ -98,6 +128,18 @@ def main() -> int:
     packed_calls = [tr.prepare_select_exit_packed(b, packed, w.eps, b1, w2, rt.b2, rt.theta, w.layer_ids, 0,
                                                   w.n_layers, d=d, out=out) for b in batches]
 
+    def cgroup_throttled_us():
+        """Microseconds this container's processes have been held back by its CPU quota so far (0 if unknown)."""
+        for path, key, scale in (("/sys/fs/cgroup/cpu.stat", "throttled_usec", 1.0), ("/sys/fs/cgroup/cpu/cpu.stat", "throttled_time", 1e-3)):
+            try:
+                with open(path) as f:
+                    for line in f:
+                        if line.startswith(key):
+                            return int(float(line.split()[1]) * scale)
+            except OSError:
+                pass
+        return 0
+
     def step_raw(i):
         raw_calls[i % args.buffers]()
 
@@ -121,18 +163,26 @@ def main() -> int:
             step(i)
         torch.cuda.synchronize()
         allocs0 = tr.workspace_allocations()
+        throttled0 = cgroup_throttled_us()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         marks = []
+        host_pause, host_pause_window = 0.0, -1          # the host's longest pause between two launches, and where
         t0 = time.perf_counter()
+        t_prev = t0
         e0.record()
         for i in range(steps):
             step(i)
+            t_now = time.perf_counter()
+            if t_now - t_prev > host_pause:
+                host_pause, host_pause_window = t_now - t_prev, i // window
+            t_prev = t_now
             if i % window == window - 1:
                 m = torch.cuda.Event(enable_timing=True)
                 m.record()
                 marks.append(m)
                 if len(marks) > 2:
                     marks[-3].synchronize()
+                t_prev = time.perf_counter()              # (waiting for the GPU here is not a pause of the host's)
         e1.record()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
@@ -148,16 +198,26 @@ def main() -> int:
         return {"wall": wall / steps, "mean": mean, "median": median, "best": srt[0],
                 "p10": srt[min(len(srt) - 1, len(srt) // 10)], "p90": srt[min(len(srt) - 1, (9 * len(srt)) // 10)],
                 "clean": sum(good) / len(good), "windows": len(per_window), "steps_per_window": window, "steps": steps,
-                "stalls": stalls, "allocations": tr.workspace_allocations() - allocs0}
+                "stalls": stalls, "allocations": tr.workspace_allocations() - allocs0,
+                "host_pause_us": round(host_pause * 1e6, 1), "host_pause_window": host_pause_window,
+                "cgroup_throttled_us": cgroup_throttled_us() - throttled0}
 
     def spread(r, us_scale=1e6):
         s = {"mean": round(r["mean"] * us_scale, 2), "median_window": round(r["median"] * us_scale, 2),
              "best_window": round(r["best"] * us_scale, 2), "p90_window": round(r["p90"] * us_scale, 2),
              "windows": r["windows"], "steps_per_window": r["steps_per_window"]}
-        if r["stalls"]:
-            s["stalls"] = r["stalls"]
-            s["library_allocations_in_loop"] = r["allocations"]
+        s.update(stall_record(r))
         return s
+
+    def stall_record(r):
+        """What a stall coincides with: a device allocation by the library (never, by construction), the host not
+        submitting (its longest pause between two launches, and the window it fell into), the container's CPU quota
+        throttling the process -- or none of these, and then the device itself idled."""
+        if not r["stalls"]:
+            return {}
+        return {"stalls": r["stalls"], "library_allocations_in_loop": r["allocations"],
+                "host_longest_pause_us": r["host_pause_us"], "host_longest_pause_in_window": r["host_pause_window"],
+                "cgroup_throttled_us_in_loop": r["cgroup_throttled_us"]}
 
     def hbm(nbytes, seconds):
         gbs = nbytes / seconds / 1e9
@@ -333,8 +393,7 @@ def main() -> int:
                     point["algorithmic_tflops_vs_fp32_mfma_peak"] = round(fl4 / r4["clean"] / 1e12 / MFMA_PEAK_TFLOPS["f32"], 3)
                 else:
                     point["mfma_frac_of_peak"] = round(fl4 / r4["clean"] / 1e12 / MFMA_PEAK_TFLOPS[name], 4)
-                if r4["stalls"]:
-                    point["stalls"] = r4["stalls"]
+                point.update(stall_record(r4))
                 sweep[f"d{dd}_{name}"] = point
                 del hs, c4, pk4
             del W4
@@ -438,9 +497,7 @@ def main() -> int:
             by1 = Tp * d * 2 + d * 128 * 2
             per[f"T{Tp}"] = {"us_per_call": round(r1["mean"] * 1e6, 2), "us_per_call_median_window": round(r1["median"] * 1e6, 2),
                              **hbm(by1, r1["median"])}
-            if r1["stalls"]:
-                per[f"T{Tp}"]["stalls"] = r1["stalls"]
-                per[f"T{Tp}"]["library_allocations_in_loop"] = r1["allocations"]
+            per[f"T{Tp}"].update(stall_record(r1))
             del hb1, c1
         result["per_checkpoint_call"] = {"workload": "one checkpoint (C=1) of the 8B shape: bf16, d=4096, packed weights, "
                                                      "random rows, back-to-back calls on rotating inputs; gbs from the median window", **per}

@@ -294,7 +294,9 @@ __device__ __forceinline__ void stage_writes_done() {
 __device__ __forceinline__ bool last_arrival(uint32_t* counter, uint32_t expected, int* flag_lds) {
     __syncthreads();
     if (threadIdx.x == 0) {
-        const uint32_t prev = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // acquire: the loads of whoever arrives last may not be moved, by compiler or hardware, ahead of this
+        // update (an invalidate of the wave's non-coherent cache lines; no write-back sweep)
+        const uint32_t prev = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
         *flag_lds = (prev == expected - 1);
     }
     __syncthreads();

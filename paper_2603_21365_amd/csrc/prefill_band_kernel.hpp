@@ -272,11 +272,7 @@ __global__ __launch_bounds__(kBandThreads, 1) void tide_prefill_band_kernel(cons
         const int a_row = (first_block * 32 + r) * kWideTileBytes;
         for (int k = 0; k < nstage; ++k) {
             ring_barrier();
-#ifdef TIDE_BAND_NO_CONSUME
-            if constexpr (false) {
-#else
             if constexpr (kA > 0) {
-#endif
                 const char* sa = a_ring + (stage % kBandStages) * kBandABytes;
                 const char* sb = b_ring + (stage % kBandStages) * kBandBBytes;
                 // the fragments of group g+1 are read before the matrix steps of group g are issued
