@@ -526,12 +526,14 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
     }
     // Band form: one launch, every workgroup an equal share of the checkpoint-major list of 32-row blocks, cut
     // into tiles of up to 288 rows by the kernel itself (16-bit rows, widths 64 / 128).
-    // It is the automatic choice from six blocks per CU on -- measured on 256 CUs against the wide-tile kernel and what
-    // it leaves to a second launch: 212-219 against 224-226 us on the 36-layer batched prefill (C = 9, T = 16384,
-    // d = 4096: 18 blocks per CU), 78 against 90 us at 6 per CU (C = 8, T = 6144), 59.5 against 63.5 us at d = 768,
-    // level where the batch is whole rounds of 256-row tiles anyway; at 5 blocks per CU it loses (90 against 83 us).
+    // It is the automatic choice as soon as the batch is more than one 128-row tile per CU (more than four blocks per CU)
+    // -- measured on 256 CUs against the best of the other forms (bf16, C = 8; us): d = 4096: 63.5 against 74.3 at
+    // T = 4608, 71.4 against 75.1 at 5632, 75.0 against 76.8 at 6144, level at 5120, 7168 and where the batch is whole rounds
+    // of 256-row tiles; d = 1024: 23.5 against 26.9 at 4608, 24.6 against 27.4 at 5120; d = 8192: 114 against 131 at 4608, 123
+    // against 138 at 5120, 136 against 144 at 6144; the 36-layer batched prefill (C = 9, T = 16384, d = 4096: 18 blocks per
+    // CU) 212-219 against 224-226.  At four blocks per CU and below the one-tile kernel is faster (W1' straight from L2).
     const int64_t blocks32 = C * ((T + 31) / 32);
-    if (!ring_form && dtype != TIDE_F32 && !two_halves && (form == 7 || (form == 0 && blocks32 >= 6 * (int64_t)cus))) {
+    if (!ring_form && dtype != TIDE_F32 && !two_halves && (form == 7 || (form == 0 && blocks32 > 4 * (int64_t)cus))) {
         const int64_t U = (T + 31) / 32;
         plan.launch[plan.count++] = PlannedLaunch{kKernelBand, 32, (int)U, (int)(C * U), 0, 1, cus};
         return plan;

@@ -206,7 +206,8 @@ def test_the_choices_on_the_named_workloads():
     assert tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256)[0]["workgroups"] == 1280
     assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256, form=4)) == [(WIDE, 128)]         # ... the wide-tile kernel when forced
     assert kinds(tr.prefill_plan(tr.BF16, 8, 8192, 4096)) == [(BAND, 32)]                         # 8 per CU (= one round of 256-row tiles)
-    assert kinds(tr.prefill_plan(tr.BF16, 8, 5120, 4096)) == [(WIDE, 256)]                        # 5 per CU: 160 wide tiles on 160 CUs
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 5120, 4096)) == [(BAND, 32)]                         # 5 per CU
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 5120, 4096, form=4)) == [(WIDE, 256)]                # ... forced: 160 wide tiles on 160 CUs
     assert kinds(tr.prefill_plan(tr.F32, 10, 16384, 4096)) == [(WIDE_F32, 256), (RING, 64)]
     assert kinds(tr.prefill_plan(tr.F16, 8, 8, 4096)) == [(SPLITK, 32)]                           # a decode step on packed weights
     assert tr.prefill_plan(tr.F16, 8, 8, 4096)[0]["k_slices"] == 8
@@ -223,8 +224,10 @@ def test_the_choices_on_the_named_workloads():
     assert kinds(tr.prefill_plan(tr.BF16, 8, 6144, 4096)) == [(BAND, 32)]                         # 6 blocks per CU
     assert kinds(tr.prefill_plan(tr.BF16, 8, 6144, 4096, form=4)) == [(WIDE, 256)]                # 192 wide tiles: three quarters of a round
     assert tr.prefill_plan(tr.BF16, 8, 6144, 4096, form=4)[0]["workgroups"] == 192
-    assert kinds(tr.prefill_plan(tr.BF16, 8, 4608, 4096)) == [(WIDE, 256)]                        # 144 wide tiles: still more than half a round
-    assert kinds(tr.prefill_plan(tr.BF16, 8, 4096 + 128, 4096)) == [(WIDE, 256)]                  # 136 wide tiles, the last of each checkpoint half empty
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 4608, 4096)) == [(BAND, 32)]                         # 4.5 blocks per CU
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 4608, 4096, form=4)) == [(WIDE, 256)]                # ... forced: 144 wide tiles
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 4096 + 128, 4096)) == [(BAND, 32)]                   # one block more than a 128-row tile per CU
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 4096, 4096)) == [(TILE, 128)]                        # exactly four blocks per CU: the one-tile kernel
     assert kinds(tr.prefill_plan(tr.BF16, 8, 3072, 4096, 256)) == [(TILE, 128)]                   # width 256: 192 tiles of 128 rows on 192 CUs
     assert kinds(tr.prefill_plan(tr.BF16, 8, 7168, 4096, 256)) == [(TILE, 128)]                   # ... and 448: a round and three quarters
     assert kinds(tr.prefill_plan(tr.F32, 8, 7168, 4096)) == [(WIDE_F32, 256)]                     # fp32 rows: 224 wide tiles
