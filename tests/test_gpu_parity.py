@@ -584,8 +584,8 @@ def test_one_checkpoint_calls_at_the_other_measured_sizes(tr, T):
 
 def test_random_shapes_on_the_automatic_choice(tr):
     """Seeded random (type, C, T, d, width) on the automatic choice, sized so that every kind of launch
-    the plan knows comes up -- split-k shapes, pieces, the 64-row and one-tile kernels, wide rounds with
-    a partly filled last round, wide rounds + a second launch -- each against the oracle."""
+    the plan knows comes up -- split-k shapes, pieces, the 64-row and one-tile kernels (the latter at width 256
+    too), the band kernel, fp32 wide rounds + a second launch -- each against the oracle."""
     rng = np.random.default_rng(0xA070)
     seen = set()
     for n in range(36):
@@ -603,7 +603,7 @@ def test_random_shapes_on_the_automatic_choice(tr):
         rt.b2[:] = np.linspace(-0.2, 0.2, C) if C > 1 else 0.05
         run_and_compare(tr, w, w.name, rt=rt, packed=bool(n & 1))
     say(f"launch kinds seen: {sorted(seen)}")
-    assert len(seen) >= 8
+    assert len(seen) >= 7
 
 
 def test_thresholds_off_and_always_and_min_layer(tr):
