@@ -53,6 +53,7 @@ struct PrefillParams {
     int k_slices;              // workgroups that share a tile's k range
     float* zpart;              // [total_tiles][k_slices][rows per tile * 128] partial accumulators
     float* sspart;             // [total_tiles][k_slices][4 waves][rows per tile] partial sums of squares
+    uint32_t* counters;        // single-launch split-k form: one arrival counter per tile (state words: zero between calls)
     CheckpointTable tab;
 };
 

@@ -32,6 +32,7 @@
 namespace tide {
 
 constexpr int kFinishThreads = 256;
+constexpr int kSplitkMaxS = 8;           // most workgroups that share a tile's k range (the single-launch form unrolls over them)
 
 template <int kBlocks> constexpr int splitk_lds_bytes() { return kDmaStages * kBlocks * 32 * kTileBytes; }   // the ring
 // floats a workgroup leaves in p.zpart: kBlocks*32 rows x 128 columns, in the order
@@ -43,8 +44,16 @@ template <int kBlocks> constexpr int splitk_part_floats() { return kBlocks * 32 
 // checkpoint-major (p.tiles_per_ckpt per checkpoint); half = which 128 columns of the bottleneck
 // (halves = 2 at width 256, else 1); slice s covers k-tiles [s*n/S, (s+1)*n/S) of the n = d/128
 // k-tiles of a row (S <= n, so every slice has at least one).
-template <int DT, int kBlocks>
+// kFused (32-row tiles, widths 64 / 128, at most as many tiles as the scratch memory has counters): ONE launch.  Every
+// workgroup leaves its partial results with device-scope stores -- only the register quads that hold rows in use: a
+// decode step of up to 8 rows per checkpoint writes 4 KiB per workgroup instead of 16 -- and ticks the tile's counter;
+// the workgroup that ticks last adds the S partial results in ascending slice order (its own included: the result does
+// not depend on who is last) and finishes the router.  An earlier version of this hand-over read whole 16 KiB blocks,
+// 8 bytes at a time, and lost to the second launch; with the rows in use only it wins at decode sizes (see the host's
+// choice).  Ordering is by completion, as in the latency kernel (device_utils.hpp: stage_store / last_arrival).
+template <int DT, int kBlocks, bool kFused = false>
 __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_splitk_kernel(const PrefillParams p) {
+    static_assert(!kFused || kBlocks == 1, "the single-launch form has 32-row tiles");
     typedef __attribute__((address_space(3))) char lds_char;
     typedef __attribute__((address_space(1))) const char glb_char;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -215,11 +224,95 @@ __global__ __launch_bounds__(kDmaThreads, 1) void tide_prefill_splitk_kernel(con
         // partial sum of squares per row (lanes l and l^32 hold the two chunk phases)
 #pragma unroll
         for (int b = 0; b < kBlocks; ++b) {
+            const float s2 = ssq[b] + __shfl_xor(ssq[b], 32, kWave);
+            if constexpr (kFused) {
+                // register quad q holds rows 8 q + 4 (lane / 32) + (0..3): the quads below the tile's last row in use
+                const int quads = (min(p.T - row0, 32) + 7) >> 3;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (q < quads) stage_store4(zmine + q * 256, f32x4{acc[b][4 * q], acc[b][4 * q + 1], acc[b][4 * q + 2], acc[b][4 * q + 3]});
+                if (lane < 32) stage_store(p.sspart + ((size_t)item * kDmaConsumers + wave) * kRowsM + lane, s2);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<f32x4*>(zmine + (b * 4 + q) * 256) = f32x4{acc[b][4 * q], acc[b][4 * q + 1], acc[b][4 * q + 2], acc[b][4 * q + 3]};
+                if (lane < 32) p.sspart[((size_t)item * kDmaConsumers + wave) * kRowsM + 32 * b + lane] = s2;
+            }
+        }
+    }
+    if constexpr (kFused) {
+        // ---- the workgroup that completes the tile's count finishes it (every wave of the workgroup takes part in
+        // the barriers; the ring is no longer in use, its memory holds the exchange arrays)
+        float* inv_rms = reinterpret_cast<float*>(smem);          // [32], 16-byte aligned
+        float* z_part = inv_rms + 32;                             // [4][32]
+        int* flag = reinterpret_cast<int*>(z_part + 4 * 32);
+        stage_writes_done();
+        if (!last_arrival(p.counters + tile, (uint32_t)S, flag)) return;
+        const int quads = (min(p.T - row0, 32) + 7) >> 3;
+        const size_t first_item = (size_t)tile * S;
+        if (wave < kDmaConsumers) {
+            // this lane's column of the second layer, fetched first so that the epilogue does not wait for it
+            const int col = 32 * wave + (lane & 31);
+            const float b1c = (p.b1 && col < p.b) ? p.b1[c * p.b + col] : 0.0f;
+            const float w2c = col < p.b ? p.w2[c * p.b + col] : 0.0f;
+            // sums of squares: lane (h, r) takes waves 2h, 2h+1 of every slice (surplus loads re-read the last slice)
+            const float* sp = p.sspart + first_item * kDmaConsumers * kRowsM + (size_t)(2 * (lane >> 5)) * kRowsM + (lane & 31);
+            float sa[kSplitkMaxS], sb[kSplitkMaxS];
+#pragma unroll
+            for (int j = 0; j < kSplitkMaxS; ++j) {
+                const size_t o = (size_t)(j < S ? j : S - 1) * kDmaConsumers * kRowsM;
+                sa[j] = stage_load(sp + o);
+                sb[j] = stage_load(sp + o + kRowsM);
+            }
+            // this wave's 32 columns: the S partial accumulators of its lane position, all loads in flight; one
+            // straight-line version per number of register quads in use (a branch around a load makes the compiler wait)
+            const float* zp = p.zpart + first_item * kPartFloats + (size_t)wave * 1024 + lane * 4;
+            f32x4 sum[4] = {f32x4{0}, f32x4{0}, f32x4{0}, f32x4{0}};
+            auto add_slices = [&](auto quads_tag) {
+                constexpr int kQ = decltype(quads_tag)::value;
+                f32x4 v[kSplitkMaxS][kQ];
+#pragma unroll
+                for (int j = 0; j < kSplitkMaxS; ++j) {
+                    const size_t o = (size_t)(j < S ? j : S - 1) * kPartFloats;
+#pragma unroll
+                    for (int q = 0; q < kQ; ++q) v[j][q] = stage_load4(zp + o + q * 256);
+                }
+#pragma unroll
+                for (int j = 0; j < kSplitkMaxS; ++j) {
+                    const bool keep = j < S;
+#pragma unroll
+                    for (int q = 0; q < kQ; ++q) sum[q] += keep ? v[j][q] : f32x4{0};
+                }
+            };
+            switch (quads) {
+            case 1: add_slices(std::integral_constant<int, 1>{}); break;
+            case 2: add_slices(std::integral_constant<int, 2>{}); break;
+            case 3: add_slices(std::integral_constant<int, 3>{}); break;
+            default: add_slices(std::integral_constant<int, 4>{}); break;
+            }
+            float ss = 0.0f;
+#pragma unroll
+            for (int j = 0; j < kSplitkMaxS; ++j) ss += j < S ? sa[j] + sb[j] : 0.0f;
+            ss += __shfl_xor(ss, 32, kWave);
+            if (wave == 0 && lane < 32) inv_rms[lane] = inv_rms_f32(ss, p.inv_d, p.eps);
+            __syncthreads();
+            f32x16 facc[1];
 #pragma unroll
             for (int q = 0; q < 4; ++q)
-                *reinterpret_cast<f32x4*>(zmine + (b * 4 + q) * 256) = f32x4{acc[b][4 * q], acc[b][4 * q + 1], acc[b][4 * q + 2], acc[b][4 * q + 3]};
-            const float s2 = ssq[b] + __shfl_xor(ssq[b], 32, kWave);
-            if (lane < 32) p.sspart[((size_t)item * kDmaConsumers + wave) * kRowsM + 32 * b + lane] = s2;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) facc[0][4 * q + e] = sum[q][e];
+            router_epilogue<1>(facc, inv_rms, z_part + wave * 32, b1c, w2c, lane);
+        } else {
+            __syncthreads();
+        }
+        __syncthreads();
+        if (tid == 0) __hip_atomic_store(p.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // zero for the next call
+        if (tid < 32) {
+            const int t = row0 + tid;
+            if (t < p.T) {
+                const float z = p.tab.b2[c] + ((z_part[tid] + z_part[32 + tid]) + (z_part[64 + tid] + z_part[96 + tid]));
+                emit_router_result(p, c, t, z);
+            }
         }
     }
 }

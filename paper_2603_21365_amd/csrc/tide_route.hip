@@ -365,6 +365,18 @@ template <int DT, int kBlocks> int launch_splitk(float* part, int64_t tiles, hip
     return TIDE_OK;
 }
 
+// The split-k form in one launch (32-row tiles, widths 64 / 128, at most kCounterSlots tiles): the workgroup that
+// completes a tile's count finishes it.
+template <int DT> int launch_splitk_fused(float* part, uint32_t* counters, int64_t tiles, hipStream_t st, PrefillParams& p) {
+    static_assert(kSplitkMaxSlices == kSplitkMaxS, "the kernel unrolls over the slices");
+    const size_t items = (size_t)tiles * p.k_slices;
+    p.zpart = part;
+    p.sspart = (float*)((char*)part + items * splitk_part_floats<1>() * sizeof(float));
+    p.counters = counters;
+    hipLaunchKernelGGL((tide_prefill_splitk_kernel<DT, 1, true>), dim3((unsigned)items), dim3(kDmaThreads), splitk_lds_bytes<1>(), st, p);
+    return TIDE_OK;
+}
+
 // The wide-tile kernel for fp32 rows: as launch_wide.
 int launch_wide_f32(unsigned grid, hipStream_t st, const PrefillParams& p) {
     static bool raised[kMaxDevices] = {};
@@ -421,7 +433,8 @@ enum PrefillKernel : int {
     kKernelStream128 = 5,  // prefill_dma_kernel.hpp, 128 rows per workgroup
     kKernelStream64 = 6,   // prefill_dma_kernel.hpp, 64 rows per workgroup (width 256: both column halves per wave)
     kKernelRing = 7,       // prefill_kernel.hpp
-    kKernelBand = 8        // prefill_band_kernel.hpp: rows_per_tile = 32 (the unit its bands are counted in)
+    kKernelBand = 8,       // prefill_band_kernel.hpp: rows_per_tile = 32 (the unit its bands are counted in)
+    kKernelSplitKFused = 9 // prefill_splitk_kernel.hpp in one launch: 32-row tiles, the last workgroup of a tile finishes it
 };
 struct PlannedLaunch {
     int kernel;            // PrefillKernel
@@ -491,13 +504,14 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
     //                          (fp32 rows: c_B = 0.65, 0.90, 1.61)
     // Forced (form 5) the cheapest shape is taken whatever the streaming estimate says, and the form
     // word may fix the tile height (bits 8-15) and the slice count (bits 16-23).
-    if (!generic_d && (form == 0 || form == 5)) {
+    if (!generic_d && (form == 0 || form == 5 || form == 8)) {
         const int64_t ntile = d * eb / kTileBytes;
         const int64_t max_blocks = form == 5 ? (int64_t)kSplitkForcedMaxTiles * 4 : (int64_t)kSplitkMaxTiles * 4;
         double best = 1e30;
         int best_rows = 0;
         int64_t best_S = 0;
         for (int rows = 32; rows <= 128; rows *= 2) {
+            if (form == 8 && rows != 32) continue;                                         // the single-launch form has 32-row tiles
             if (force_rows ? rows != force_rows : (rows > 32 && 2 * T <= rows)) continue;   // never a tile that is mostly padding
             const int64_t tiles = C * ((T + rows - 1) / rows);
             const double B = rows / 32, R = (double)(tiles * halves) * B;
@@ -518,9 +532,16 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
         const double t_stream = dtype == TIDE_F32 ? 8.5 + 0.75 * (double)ntile     // the register-ring form
                               : halves == 1 ? 5.7 + 0.48 * (double)ntile + 0.07 * ((double)ntile / 32.0) * (double)tiles128
                                             : 7.0 + 1.17 * (double)ntile;
-        if (best_rows && (form == 5 || best + 0.3 < t_stream)) {
+        if (best_rows && (form == 5 || form == 8 || best + 0.3 < t_stream)) {
             const int64_t tpc = (T + best_rows - 1) / best_rows, tiles = C * tpc;
-            plan.launch[plan.count++] = PlannedLaunch{kKernelSplitK, best_rows, (int)tpc, (int)tiles, 0, (int)best_S, (unsigned)(tiles * halves * best_S)};
+            // One launch instead of two where the kernel has it (32-row tiles, one column half, a counter per tile) and
+            // where it is faster: the finishing workgroup reads the partial results past every cache, so it wins while
+            // few rows are in use -- measured (fp16, C = 8, d = 4096; pair against one launch, us): 10.15 / 8.5 up to 8 rows
+            // per checkpoint, 10.25 / 9.2 up to 16, 10.3 / 10.2 up to 24, 10.4 / 11.3 at 32; a full 32-row tile per checkpoint
+            // and more (C = 1, T = 64 ... 2048) loses 0.9-1.9 us.  Forced (form 8): whenever the kernel has it.
+            const bool fused = form != 5 && best_rows == 32 && halves == 1 && tiles <= (int64_t)kCounterSlots && (form == 8 || T <= 16);
+            plan.launch[plan.count++] = PlannedLaunch{fused ? kKernelSplitKFused : kKernelSplitK, best_rows, (int)tpc, (int)tiles, 0, (int)best_S,
+                                                      (unsigned)(tiles * halves * best_S)};
             return plan;
         }
     }
@@ -651,6 +672,9 @@ int launch_prefill(const Scratch& sc, const PrefillPlan& plan, const void* hidde
                 rc = L.rows_per_tile == 32 ? launch_splitk<DT, 1>(sc.part, L.total_tiles, st, p)
                    : L.rows_per_tile == 64 ? launch_splitk<DT, 2>(sc.part, L.total_tiles, st, p) : launch_splitk<DT, 4>(sc.part, L.total_tiles, st, p);
                 break;
+            case kKernelSplitKFused:
+                rc = launch_splitk_fused<DT>(sc.part, sc.counters, L.total_tiles, st, p);
+                break;
             case kKernelWide:
                 if constexpr (DT != kF32) rc = two_halves ? launch_wide<DT, 2>(L.grid, st, p) : launch_wide<DT, 1>(L.grid, st, p);
                 break;
@@ -753,7 +777,7 @@ bool use_decode(int64_t T, int dtype, int64_t d, int64_t b, bool packed_given, i
     if (variant == TIDE_VARIANT_DECODE) return T <= kDecodeMaxT;
     if (variant == TIDE_VARIANT_PREFILL) return false;
     const bool split_k = d % 128 == 0 && d >= 256 &&
-                         ((form_word & 0xff) == 0 || (form_word & 0xff) == 5);
+                         ((form_word & 0xff) == 0 || (form_word & 0xff) == 5 || (form_word & 0xff) == 8);
     if (!split_k) return T <= kDecodeAutoMaxT;
     return !packed_given && T <= kDecodeRawMaxT;
 }
@@ -791,7 +815,7 @@ CallNeed call_need(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, bool r
     n.plan = plan_prefill(dtype, C, T, n.d_run, b, cus, form_word);
     for (int i = 0; i < n.plan.count; ++i) {
         const PlannedLaunch& L = n.plan.launch[i];
-        if (L.kernel == kKernelSplitK) n.part_bytes = round256(splitk_part_bytes(L.rows_per_tile / 32, L.total_tiles, halves, L.k_slices));
+        if (L.kernel == kKernelSplitK || L.kernel == kKernelSplitKFused) n.part_bytes = round256(splitk_part_bytes(L.rows_per_tile / 32, L.total_tiles, halves, L.k_slices));
     }
     return n;
 }
@@ -1354,8 +1378,9 @@ namespace {
 // (bits 8-15: 0, 32, 64 or 128) and slice count (bits 16-23: 0, 2, 4 or 8).
 bool valid_form_word(int w) {
     const int form = w & 0xff, rows = (w >> 8) & 0xff, slices = (w >> 16) & 0xff;
-    if (w < 0 || (w >> 24) != 0 || form > 7) return false;
-    if ((rows || slices) && form != 5) return false;
+    if (w < 0 || (w >> 24) != 0 || form > 8) return false;
+    if ((rows || slices) && form != 5 && form != 8) return false;
+    if (form == 8 && rows != 0 && rows != 32) return false;
     return (rows == 0 || rows == 32 || rows == 64 || rows == 128) && (slices == 0 || slices == 2 || slices == 4 || slices == 8);
 }
 }  // namespace
@@ -1366,7 +1391,7 @@ int tide_prefill_plan(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int
     if (!supported_hidden(dtype, d) || !supported_bottleneck(b)) return fail(TIDE_ERR_UNSUPPORTED, "d = %lld, b = %lld unsupported", (long long)d, (long long)b);
     if (needs_repack(dtype, d, b)) d = padded_hidden(dtype, d);      // such calls run the tuned kernels on zero-padded rows
     if (cus < 8 || cus % 8 != 0) return fail(TIDE_ERR_INVALID_ARG, "cus = %d must be a positive multiple of 8", cus);
-    if (!valid_form_word(form)) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d: a form in [0, 7], with form 5 optionally rows << 8 | slices << 16", form);
+    if (!valid_form_word(form)) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d: a form in [0, 8], with forms 5 and 8 optionally rows << 8 | slices << 16", form);
     if (!out) return fail(TIDE_ERR_INVALID_ARG, "out must not be NULL");
     const PrefillPlan plan = plan_prefill(dtype, C, T, d, b, (unsigned)cus, form);
     for (int i = 0; i < plan.count; ++i) {
@@ -1413,7 +1438,7 @@ int tide_band_schedule(int64_t C, int64_t blocks_per_ckpt, int grid, int block, 
 }
 
 int tide_set_prefill_form(int form) {
-    if (!valid_form_word(form)) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d: a form in [0, 7], with form 5 optionally rows << 8 | slices << 16", form);
+    if (!valid_form_word(form)) return fail(TIDE_ERR_INVALID_ARG, "prefill form %d: a form in [0, 8], with forms 5 and 8 optionally rows << 8 | slices << 16", form);
     std::lock_guard<std::mutex> lock(g_mu);
     int prev = g_prefill_form;
     g_prefill_form = form;

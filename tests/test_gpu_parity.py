@@ -107,7 +107,7 @@ def test_config1_full(tr, packed):
     assert st["max_abs_err"] < 1e-2                      # bf16 W1' rounding: well inside the 2e-2 bar
 
 
-@pytest.mark.parametrize("form", [1, 2, 3, 4, 5, 6, 7, 0])
+@pytest.mark.parametrize("form", [1, 2, 3, 4, 5, 6, 7, 8, 0])
 @pytest.mark.parametrize("dtype,T,d", [("bf16", 300, 1024), ("f16", 129, 768), ("f32", 257, 512), ("bf16", 64, 128), ("f16", 1100, 384)])
 def test_every_prefill_form_computes_the_same_function(tr, form, dtype, T, d):
     """Streaming form with 64 / 128 rows per workgroup, the register-ring form, the wide-tile form,
@@ -193,6 +193,52 @@ def test_split_k_form_for_batches_with_few_tiles(tr, C, dtype, T, d, b, what):
         run_and_compare(tr, w, w.name + "_own_shape", rt=rt, packed=True, variant=tr.VARIANT_PREFILL)
     finally:
         tr.set_prefill_form(0)
+
+
+@pytest.mark.parametrize("C,dtype,T,d,b,slices,what", [
+    (8, "f16", 1, 4096, 128, 8, "a decode step, one row per checkpoint: one register quad of partial results per lane"),
+    (8, "f16", 8, 4096, 128, 8, "a decode step, eight rows: still one quad"),
+    (8, "bf16", 13, 2048, 128, 4, "two quads, four slices"),
+    (5, "f16", 19, 1408, 128, 8, "three quads; 11 k-tiles in 8 slices of 1 and 2"),
+    (32, "f16", 32, 1024, 128, 8, "the most checkpoints, every row of the tile in use: four quads"),
+    (1, "bf16", 1000, 4096, 128, 8, "32 tiles of one checkpoint, the last ragged: one counter per tile"),
+    (2, "bf16", 1024, 512, 128, 2, "64 tiles: as many as there are counters; two slices of one k-tile"),
+    (4, "f32", 8, 4096, 128, 8, "fp32 rows (two bf16 terms per value)"),
+    (3, "f16", 40, 768, 64, 2, "width 64; two tiles per checkpoint, the second with 8 rows in use"),
+])
+def test_split_k_in_one_launch(tr, C, dtype, T, d, b, slices, what):
+    """The single-launch split-k form (the automatic choice for decode steps of up to 16 rows per checkpoint; forced
+    here so that larger cases run on it too): the workgroup that completes a tile's count adds the partial results
+    and finishes the router.  Against the oracle, packed and raw weights, and three times in a row with identical
+    bits (the counters return to zero; the sum does not depend on which workgroup is last)."""
+    import torch
+    w = synth.Workload(f"fused_{dtype}_C{C}_T{T}_d{d}_b{b}_S{slices}", 41, dtype, d, 4 * C, 4, T, None, b=b)
+    say(what)
+    rt = w.routers()
+    rt.b2[:] = np.linspace(-0.2, 0.2, w.C) if C > 1 else 0.05
+    form = 8 | 32 << 8 | slices << 16
+    plan = tr.prefill_plan(tr.DTYPE_CODES[dtype], C, T, d, b, form=form)
+    assert [(L["kernel"], L["rows_per_tile"], L["k_slices"]) for L in plan] == [(9, 32, slices)], plan
+    tr.set_prefill_form(form)
+    try:
+        run_and_compare(tr, w, w.name, rt=rt, packed=True, variant=tr.VARIANT_PREFILL)
+        run_and_compare(tr, w, w.name + "_raw", rt=rt, packed=False, variant=tr.VARIANT_PREFILL)
+        hb = w.hidden()
+        dev = to_device(hb, dtype)
+        g, W1, b1, w2 = routers_to_device(rt)
+        tr.set_variant(tr.VARIANT_PREFILL)
+        first = None
+        for rep in range(3):
+            ex, z, m = tr.select_exit(dev, g, w.eps, W1, b1, w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers)
+            torch.cuda.synchronize()
+            got = (ex.cpu().numpy().copy(), z.cpu().numpy().copy(), m.cpu().numpy().copy())
+            if first is None:
+                first = got
+            else:
+                assert all(np.array_equal(a, b_) for a, b_ in zip(first, got)), f"call {rep} differs from the first"
+    finally:
+        tr.set_prefill_form(0)
+        tr.set_variant(tr.VARIANT_AUTO)
 
 
 @pytest.mark.parametrize("slices", [2, 4, 8])

@@ -8,7 +8,7 @@ import pytest
 
 from paper_2603_21365_amd import tide_route as tr
 
-SPLITK, WIDE, WIDE_F32, TILE, STREAM128, STREAM64, RING, BAND = 1, 2, 3, 4, 5, 6, 7, 8
+SPLITK, WIDE, WIDE_F32, TILE, STREAM128, STREAM64, RING, BAND, SPLITK_FUSED = 1, 2, 3, 4, 5, 6, 7, 8, 9
 ELEM = {tr.F32: 4, tr.F16: 2, tr.BF16: 2}
 
 
@@ -41,7 +41,9 @@ def check_plan(dtype, C, T, d, b, cus, form):
     for i, L in enumerate(plan):
         k, R, wg = L["kernel"], L["rows_per_tile"], L["workgroups"]
         assert wg >= 1, what
-        if k == SPLITK:
+        if k == SPLITK_FUSED:
+            assert R == 32 and halves == 1 and L["total_tiles"] <= 64 and (form & 0xff) in (0, 8) and ((form & 0xff) == 8 or T <= 16), what
+        if k in (SPLITK, SPLITK_FUSED):
             assert len(plan) == 1 and d % 128 == 0, what
             assert R in (32, 64, 128) and (form >> 8 or R == 32 or T > R // 2), what   # its own choice: never a tile that is mostly padding
             assert L["k_slices"] in (2, 4, 8, ntile) and 2 <= L["k_slices"] <= min(8, ntile), what
@@ -78,7 +80,7 @@ SHAPES = [(8, 4096, 4096), (9, 16384, 4096), (10, 16384, 768), (10, 16384, 8192)
           (7, 2049, 3072), (2, 12345, 5120), (8, 2048, 4096), (8, 3072, 4096), (8, 1536, 4096), (1, 16384, 4096)]
 
 
-@pytest.mark.parametrize("form", [0, 1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("form", [0, 1, 2, 3, 4, 5, 6, 7, 8])
 @pytest.mark.parametrize("dtype", [tr.BF16, tr.F16, tr.F32])
 def test_every_row_is_in_exactly_one_tile(dtype, form):
     for C, T, d in SHAPES:
@@ -98,7 +100,7 @@ def test_every_row_is_in_exactly_one_tile_on_random_shapes():
         d = int(rng.choice([128, 256, 384, 768, 1024, 2048, 2560, 4096, 5120, 8192, 16384]))
         b = int(rng.choice([64, 128, 256]))
         cus = int(rng.choice([8, 64, 128, 256, 304]))
-        form = int(rng.integers(0, 8))
+        form = int(rng.integers(0, 9))
         check_plan(dtype, C, T, d, b, cus, form)
 
 
@@ -190,7 +192,7 @@ def test_the_band_schedule_covers_every_block_once():
 
 def test_generic_hidden_sizes_take_the_register_ring_kernel():
     for dtype, d in ((tr.BF16, 200), (tr.F16, 72), (tr.F32, 100), (tr.BF16, 4104), (tr.F32, 708)):
-        for form in range(8):
+        for form in range(9):
             for C, T in ((1, 1), (4, 300), (10, 16384)):
                 plan = check_plan(dtype, C, T, d, 128, 256, form)
                 assert [L["kernel"] for L in plan] == [RING]
@@ -209,8 +211,14 @@ def test_the_choices_on_the_named_workloads():
     assert kinds(tr.prefill_plan(tr.BF16, 8, 5120, 4096)) == [(BAND, 32)]                         # 5 per CU
     assert kinds(tr.prefill_plan(tr.BF16, 8, 5120, 4096, form=4)) == [(WIDE, 256)]                # ... forced: 160 wide tiles on 160 CUs
     assert kinds(tr.prefill_plan(tr.F32, 10, 16384, 4096)) == [(WIDE_F32, 256), (RING, 64)]
-    assert kinds(tr.prefill_plan(tr.F16, 8, 8, 4096)) == [(SPLITK, 32)]                           # a decode step on packed weights
+    assert kinds(tr.prefill_plan(tr.F16, 8, 8, 4096)) == [(SPLITK_FUSED, 32)]                     # a decode step on packed weights: split-k in one launch
     assert tr.prefill_plan(tr.F16, 8, 8, 4096)[0]["k_slices"] == 8
+    assert kinds(tr.prefill_plan(tr.F16, 8, 16, 4096)) == [(SPLITK_FUSED, 32)]
+    assert kinds(tr.prefill_plan(tr.F16, 8, 17, 4096)) == [(SPLITK, 32)]                          # more rows in use: the pair
+    assert kinds(tr.prefill_plan(tr.F16, 8, 8, 4096, 256)) == [(SPLITK, 32)]                      # width 256: the pair
+    assert kinds(tr.prefill_plan(tr.F16, 8, 8, 4096, form=5)) == [(SPLITK, 32)]                   # the pair when forced
+    assert kinds(tr.prefill_plan(tr.BF16, 1, 1024, 4096, form=8)) == [(SPLITK_FUSED, 32)]         # one launch when forced: 32 tiles
+    assert kinds(tr.prefill_plan(tr.BF16, 1, 4096, 4096, form=8)) == [(SPLITK, 32)]               # ... 128 tiles: more than there are counters
     assert kinds(tr.prefill_plan(tr.BF16, 1, 1024, 4096)) == [(SPLITK, 32)]                       # one checkpoint's call: 32 tiles x 8 slices
     assert tr.prefill_plan(tr.BF16, 1, 1024, 4096)[0]["workgroups"] == 256
     p4096 = tr.prefill_plan(tr.BF16, 1, 4096, 4096)[0]                                            # 64 tiles x 4 slices: still one workgroup per CU
@@ -260,7 +268,7 @@ def test_the_band_form_is_one_launch_over_all_blocks():
 
 
 def test_plan_rejects_bad_arguments():
-    bad = [dict(dtype=9), dict(C=0), dict(C=33), dict(T=0), dict(d=100000), dict(d=0), dict(b=96), dict(cus=100), dict(cus=0), dict(form=8)]
+    bad = [dict(dtype=9), dict(C=0), dict(C=33), dict(T=0), dict(d=100000), dict(d=0), dict(b=96), dict(cus=100), dict(cus=0), dict(form=9)]
     # hidden sizes of the generic fallback that are copied into zero-padded rows first are planned at the padded size
     assert tr.prefill_plan(tr.BF16, 4, 1000, 130) == tr.prefill_plan(tr.BF16, 4, 1000, 131)[:] == tr.prefill_plan(tr.BF16, 4, 1000, 256)
     assert tr.prefill_plan(tr.BF16, 4, 1000, 200, 256) == tr.prefill_plan(tr.BF16, 4, 1000, 256, 256)
