@@ -83,11 +83,6 @@ def main() -> int:
               "exchange; no multi-GPU run exists to measure). Use --gpus 1.", file=sys.stderr)
         return 2
 
-    # Kernel arguments in device memory: the HIP runtime otherwise keeps them in host memory, and the first workgroups of
-    # every launch wait for them across PCIe (measured on this workload: 0.8 us per launch, 1.5 us per two-launch step).
-    # It is read when the runtime starts, so it is set before anything touches the GPU; an exported value wins.
-    os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")
-
     import numpy as np
     import torch
 
@@ -294,6 +289,8 @@ def main() -> int:
                                "T=4096 tokens, ~30% firing per checkpoint", "C": C, "T": T, "d": d,
                    "entry_point": "tide_select_exit (raw fp32 router weights; gain fold + packing inside the step)",
                    "input_buffers_rotated": args.buffers,
+                   # (unset = kernel arguments in device memory on this runtime; 0 would cost 0.8 us per launch here
+                   # and 4 us per decode call)
                    "runtime_env": {"HIP_FORCE_DEV_KERNARG": os.environ.get("HIP_FORCE_DEV_KERNARG")}},
         "rows_per_s": round(C * T / r_raw["wall"], 1),
         "tokens_per_s_median_window": round(T / r_raw["median"], 1),
@@ -401,8 +398,8 @@ def main() -> int:
                                        "rotating inputs; d=8192 is the 80-layer point", **sweep}
 
     # ---- decode latency (config 2): fp16, T = 1 and 8.  Router weights are static at inference, so the
-    # serving loop's call is the one on pre-packed weights (automatic choice: the split-k pair on the
-    # matrix cores); the raw-weight call (fp32 W1, latency kernel, no packing pass) is timed beside it.
+    # serving loop's call is the one on pre-packed weights (automatic choice: the split-k form on the
+    # matrix cores, in one launch); the raw-weight call (fp32 W1, latency kernel, no packing pass) is timed beside it.
     if not args.no_decode:
         dec = {}
         evict_src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")
@@ -462,7 +459,8 @@ def main() -> int:
                 lat_g.append(time.perf_counter() - t0)
             lat_g.sort()
             dec[f"T{Td}"] = {"us_per_call": round(r_d["wall"] * 1e6, 2), "calls_per_s": round(1.0 / r_d["wall"], 1),
-                             "entry_point": "tide_select_exit_packed (fp16 packed weights; split-k pair, two launches)",
+                             "entry_point": "tide_select_exit_packed (fp16 packed weights; split-k form in one launch: 64 workgroups, "
+                                            "the last of each checkpoint's eight finishes its router)",
                              "cache_state": "warm: the same 8 MiB of packed routers and the same rows are re-read back to back "
                                             "and stay in L2 / the last-level cache",
                              "us_per_call_hip_events": round(r_d["mean"] * 1e6, 2),
@@ -477,7 +475,7 @@ def main() -> int:
                                              "us_per_call": round(r_r["wall"] * 1e6, 2)},
                              "hip_graph": {"us_per_replay": round(r_g["wall"] * 1e6, 2),
                                            "us_replay_plus_sync_median": round(lat_g[500] * 1e6, 2),
-                                           "note": "the packed call captured as a graph of its two kernels"}}
+                                           "note": "the packed call captured as a graph (one kernel)"}}
         del evict_src, evict_dst
         result["decode"] = {"workload": "configs[2]: fp16, d=4096, C=8, back-to-back calls on one stream "
                                         "(us_per_call), one call then a stream synchronisation (us_call_plus_sync), and "
