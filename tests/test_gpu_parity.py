@@ -241,6 +241,29 @@ def test_split_k_in_one_launch(tr, C, dtype, T, d, b, slices, what):
         tr.set_variant(tr.VARIANT_AUTO)
 
 
+@pytest.mark.parametrize("T", [1, 5, 16])
+def test_router_eval_of_a_few_rows_on_packed_weights(tr, T):
+    """tide_router_eval_packed on a handful of rows: the single-launch split-k form without exit selection (no arrival
+    words, only the tile's counter), every optional output."""
+    import torch
+    w = synth.Workload(f"eval_few_T{T}", 53, "f16", 2048, 4, 4, T, None)
+    h = w.hidden()
+    rt = w.routers()
+    z_o, p_o, f_o = oracle.router_eval(h[0], "f16", rt.gamma[0], w.eps, rt.W1[0], rt.b1[0], rt.w2[0], 0.1, 0.5)
+    g, W1, b1, w2 = routers_to_device(rt)
+    assert [L["kernel"] for L in tr.prefill_plan(tr.F16, 1, T, 2048)] == [9]
+    packed = tr.router_pack(tr.F16, g[:1], W1[:1])
+    for rep in range(2):
+        prob, fire, logit = tr.router_eval_packed(to_device(h[0], "f16"), packed, w.eps, b1[0], w2[0], 0.1, 0.5, d=2048)
+        torch.cuda.synchronize()
+        z_g, p_g, f_g = logit.cpu().numpy(), prob.cpu().numpy(), fire.cpu().numpy()
+        err = np.abs(z_g - z_o).max()
+        print(f"PARITY name=eval_few_T{T}_call{rep} rows={T} max_abs_err={err:.3e}", flush=True)
+        assert err <= TOL["f16"] and np.abs(p_g - p_o).max() <= TOL["f16"]
+        near = np.abs(z_o) <= TOL["f16"]
+        assert np.array_equal(f_g[~near], f_o[~near])
+
+
 @pytest.mark.parametrize("slices", [2, 4, 8])
 @pytest.mark.parametrize("rows", [32, 64, 128])
 @pytest.mark.parametrize("C,dtype,T,d,b", [(3, "bf16", 333, 1408, 128), (2, "f16", 200, 1024, 256), (2, "f32", 150, 512, 128),
