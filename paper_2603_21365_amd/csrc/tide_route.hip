@@ -90,7 +90,8 @@ Workspace g_ws[kMaxDevices];
 int g_variant = TIDE_VARIANT_AUTO;
 int g_prefill_form = 0;   // a form word (see valid_form_word): 0 auto; 1 / 2: streaming form with 64 / 128 rows per workgroup;
                           // 3: register-ring form; 4: wide-tile form wherever it applies, on as many workgroups as there are
-                          // whole tiles; 5: split-k pair (optionally with a forced shape); 6: one-tile form
+                          // whole tiles; 5: split-k pair (optionally with a forced shape); 6: one-tile form; 7: band form;
+                          // 8: split-k in one launch (optionally with a forced slice count)
 
 // Caller-owned workspaces (the _ws entry points) and the static array of the no-allocation entry
 // point are single blocks laid out per call: state words first, data behind them.  A call with more
@@ -1374,8 +1375,8 @@ int tide_set_variant(int variant) {
 }
 
 namespace {
-// A prefill form word: the form in bits 0-7; with form 5, optionally a forced split-k tile height
-// (bits 8-15: 0, 32, 64 or 128) and slice count (bits 16-23: 0, 2, 4 or 8).
+// A prefill form word: the form in bits 0-7; with forms 5 and 8, optionally a forced split-k tile height
+// (bits 8-15: 0, 32, 64 or 128; form 8: 0 or 32) and slice count (bits 16-23: 0, 2, 4 or 8).
 bool valid_form_word(int w) {
     const int form = w & 0xff, rows = (w >> 8) & 0xff, slices = (w >> 16) & 0xff;
     if (w < 0 || (w >> 24) != 0 || form > 8) return false;
