@@ -976,7 +976,7 @@ int run(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t 
 
 extern "C" {
 
-int tide_version(void) { return 100; }
+int tide_version(void) { return 110; }
 
 const char* tide_last_error(void) { return g_err; }
 
