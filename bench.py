@@ -506,22 +506,36 @@ def main() -> int:
         # checkpoint c on T * 0.7^c rows (30 % of the running tokens exit at every checkpoint, as in this
         # workload); in a model these calls are a layer stack apart, so what matters there is each call's latency.
         nbytes_pk = tr.packed_router_bytes(tr.BF16, d)
-        sched, rows_sc = [], 0
+        sched, sched_out, rows_sc = [], [], 0
         for c in range(C):
             Tc = max(1, int(round(T * 0.7 ** c)))
             rows_sc += Tc
             outc = (torch.empty(Tc, dtype=torch.int32, device="cuda"), torch.empty((1, Tc), dtype=torch.float32, device="cuda"),
                     torch.empty(Tc, dtype=torch.int32, device="cuda"))
+            sched_out.append(outc)
             sched.append(tr.prepare_select_exit_packed(batches[c % len(batches)][c:c + 1, :Tc], packed[c * nbytes_pk:(c + 1) * nbytes_pk],
                                                        w.eps, b1[c:c + 1], w2[c:c + 1], rt.b2[c:c + 1], rt.theta[c:c + 1],
                                                        w.layer_ids[c:c + 1], 0, w.n_layers, d=d, out=outc))
+        # ... each followed by the compaction of the running batch's token ids (Sec. 3.4 kernel 2) that the runtime gathers
+        # the continuing tokens' rows by; the gather itself belongs to the model's layers, not to this library
+        import ctypes
+        lib_sc = tr.load_library()
+        stream_sc = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        compact_args = []
+        for c in range(C):
+            Tc = max(1, int(round(T * 0.7 ** c)))
+            ids = (torch.empty(Tc, dtype=torch.int32, device="cuda"), torch.empty(Tc, dtype=torch.int32, device="cuda"),
+                   torch.zeros(2, dtype=torch.int32, device="cuda"))
+            compact_args.append((sched_out[c][0], Tc, int(w.layer_ids[c]), ids))
         def run_schedule(i):
-            for call in sched:
+            for call, (ex_c, Tc, layer_c, ids) in zip(sched, compact_args):
                 call()
+                lib_sc.tide_batch_compact(ctypes.c_void_p(ex_c.data_ptr()), Tc, layer_c, ctypes.c_void_p(ids[0].data_ptr()),
+                                          ctypes.c_void_p(ids[1].data_ptr()), ctypes.c_void_p(ids[2].data_ptr()), stream_sc)
         r_sc = timed(run_schedule, 200, 20, window=10)
         result["short_circuit_schedule"] = {
-            "workload": f"C={C} calls of tide_select_exit_packed with C=1 on T*0.7^c rows (c = 0..{C - 1}), back to back; "
-                        "no compaction pass in the timed region",
+            "workload": f"C={C} x (tide_select_exit_packed with C=1 on T*0.7^c rows, then tide_batch_compact of the call's exit "
+                        f"layers), c = 0..{C - 1}, back to back",
             "us_per_schedule": round(r_sc["clean"] * 1e6, 2), "rows_evaluated": rows_sc, "rows_dense": C * T,
             "algorithmic_bytes": rows_sc * d * 2 + C * d * 128 * 2,
             "tokens_per_s": round(T / r_sc["clean"], 1),
