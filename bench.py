@@ -336,9 +336,27 @@ def main() -> int:
             r_w = timed(lambda i: cb[i % nb](), n_x, 5)
             by = C * T * dd * esz + C * dd * bb * esz + T * 8 + C * T * 4
             widths[f"d{dd}_b{bb}"] = {"us_per_call": round(r_w["clean"] * 1e6, 2), "us_per_call_median_window": round(r_w["median"] * 1e6, 2),
-                                      "algorithmic_bytes": by, **hbm(by, r_w["clean"])}
+                                      "algorithmic_bytes": by, **hbm(by, r_w["clean"]),
+                                      "mfma_frac_of_bf16_peak": round(2.0 * C * T * dd * bb / r_w["clean"] / (MFMA_PEAK_TFLOPS["bf16"] * 1e12), 4)}
             del hbs, cb, pkb, Wb
-        result["bottleneck_widths"] = {"workload": f"Table 2 pairs with b != 128: bf16, C={C}, T={T}, packed weights", **widths}
+        # width 256 on larger batches (256 rows per CU and more: the square form, 256 x 256 tiles)
+        for TT in (8192, 16384):
+            dd, bb, nb = 4096, 256, 2
+            hbs = [torch.randn((C, TT, dd), generator=gen, device="cuda").to(torch.bfloat16) for _ in range(nb)]
+            Wb = torch.randn((C, dd, bb), generator=gen, device="cuda") / dd ** 0.5
+            w2b = torch.randn((C, bb), generator=gen, device="cuda") / bb ** 0.5
+            pkb = tr.router_pack(tr.BF16, None, Wb)
+            out_t = (torch.empty(TT, dtype=torch.int32, device="cuda"), torch.empty((C, TT), dtype=torch.float32, device="cuda"),
+                     torch.empty(TT, dtype=torch.int32, device="cuda"))
+            cb = [tr.prepare_select_exit_packed(h, pkb, w.eps, None, w2b, 0.0, 0.5, w.layer_ids, 0, w.n_layers, d=dd, out=out_t)
+                  for h in hbs]
+            r_w = timed(lambda i: cb[i % nb](), max(40, n_x // 2), 5)
+            by = C * TT * dd * esz + C * dd * bb * esz + TT * 8 + C * TT * 4
+            widths[f"d{dd}_b{bb}_T{TT}"] = {"us_per_call": round(r_w["clean"] * 1e6, 2), "us_per_call_median_window": round(r_w["median"] * 1e6, 2),
+                                            "algorithmic_bytes": by, **hbm(by, r_w["clean"]),
+                                            "mfma_frac_of_bf16_peak": round(2.0 * C * TT * dd * bb / r_w["clean"] / (MFMA_PEAK_TFLOPS["bf16"] * 1e12), 4)}
+            del hbs, cb, pkb, Wb, out_t
+        result["bottleneck_widths"] = {"workload": f"Table 2 pairs with b != 128: bf16, C={C}, T={T} (or the T a key names), packed weights", **widths}
 
         # ---- configs[3]: the 36-layer batched prefill (C=9, T=8x2048)
         w3 = synth.config3()

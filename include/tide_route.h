@@ -275,7 +275,8 @@ int tide_set_variant(int variant);
  * without the persistent schedule (16-bit types; at width 256 with eight consumer waves), 7 = band form (one launch, every
  * workgroup an equal share of the 32-row blocks, tiles of up to 288 rows; 16-bit types, widths
  * 64 / 128), 8 = the split-k form in ONE launch (32-row tiles; the workgroup that completes a tile's
- * count finishes it; widths 64 / 128, at most 64 tiles -- otherwise as form 5).  With forms 5 and 8 the word may also
+ * count finishes it; widths 64 / 128, at most 64 tiles -- otherwise as form 5), 9 = square form (width 256, 16-bit
+ * types: a workgroup of four waves per tile of 256 rows x 256 columns).  With forms 5 and 8 the word may also
  * fix the split-k tile height and slice count: 5 | rows << 8 | slices << 16 with rows in {0, 32, 64,
  * 128} and slices in {0, 2, 4, 8}, 0 = chosen by the library.  A form that does
  * not apply to a call (storage type, width, hidden size) falls back to one that does.
@@ -290,7 +291,7 @@ int tide_set_prefill_form(int form);
  * checkpoint-major list of tiles of rows_per_tile rows (tiles_per_ckpt per checkpoint, the last one
  * of a checkpoint possibly ragged).  kernel: 1 split-k pair, 2 wide-tile, 3 wide-tile fp32, 4 one-tile,
  * 5 / 6 streaming with 128 / 64 rows, 7 register-ring, 8 band (rows_per_tile = 32: the blocks its
- * bands are counted in, see tide_band_schedule), 9 split-k in one launch.  Returns the number of launches (1 or 2) or a
+ * bands are counted in, see tide_band_schedule), 9 split-k in one launch, 10 square.  Returns the number of launches (1 or 2) or a
  * negative tide_status_t.  Calls with at most 32 rows per checkpoint may take the latency kernel
  * instead (see the conventions); this function describes the prefill path only.              */
 int tide_prefill_plan(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, int cus, int form, int32_t* out);

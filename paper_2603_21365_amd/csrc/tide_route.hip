@@ -24,6 +24,7 @@
 #include "prefill_tile_kernel.hpp"
 #include "prefill_wide_kernel.hpp"
 #include "prefill_band_kernel.hpp"
+#include "prefill_square_kernel.hpp"
 #include "prefill_wide32_kernel.hpp"
 #include "project_kernel.hpp"
 #include "repack_kernel.hpp"
@@ -91,7 +92,7 @@ int g_variant = TIDE_VARIANT_AUTO;
 int g_prefill_form = 0;   // a form word (see valid_form_word): 0 auto; 1 / 2: streaming form with 64 / 128 rows per workgroup;
                           // 3: register-ring form; 4: wide-tile form wherever it applies, on as many workgroups as there are
                           // whole tiles; 5: split-k pair (optionally with a forced shape); 6: one-tile form; 7: band form;
-                          // 8: split-k in one launch (optionally with a forced slice count)
+                          // 8: split-k in one launch (optionally with a forced slice count); 9: square form (width 256)
 
 // Caller-owned workspaces (the _ws entry points) and the static array of the no-allocation entry
 // point are single blocks laid out per call: state words first, data behind them.  A call with more
@@ -378,6 +379,21 @@ template <int DT> int launch_splitk_fused(float* part, uint32_t* counters, int64
     return TIDE_OK;
 }
 
+// The square kernel (width 256, 16-bit rows): a workgroup per 256-row tile.
+template <int DT> int launch_square(hipStream_t st, const PrefillParams& p) {
+    static bool raised[kMaxDevices] = {};
+    int dev = 0;
+    TIDE_HIP(hipGetDevice(&dev));
+    if (!raised[dev]) {
+        TIDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&tide_prefill_square_kernel<DT>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, kSquareLdsBytes));
+        raised[dev] = true;
+    }
+    const unsigned grid = 8u * (unsigned)((p.total_tiles + 7) / 8);
+    hipLaunchKernelGGL((tide_prefill_square_kernel<DT>), dim3(grid), dim3(kSquareThreads), kSquareLdsBytes, st, p);
+    return TIDE_OK;
+}
+
 // The wide-tile kernel for fp32 rows: as launch_wide.
 int launch_wide_f32(unsigned grid, hipStream_t st, const PrefillParams& p) {
     static bool raised[kMaxDevices] = {};
@@ -435,7 +451,8 @@ enum PrefillKernel : int {
     kKernelStream64 = 6,   // prefill_dma_kernel.hpp, 64 rows per workgroup (width 256: both column halves per wave)
     kKernelRing = 7,       // prefill_kernel.hpp
     kKernelBand = 8,       // prefill_band_kernel.hpp: rows_per_tile = 32 (the unit its bands are counted in)
-    kKernelSplitKFused = 9 // prefill_splitk_kernel.hpp in one launch: 32-row tiles, the last workgroup of a tile finishes it
+    kKernelSplitKFused = 9,// prefill_splitk_kernel.hpp in one launch: 32-row tiles, the last workgroup of a tile finishes it
+    kKernelSquare = 10     // prefill_square_kernel.hpp (width 256, 16-bit rows: 256-row tiles)
 };
 struct PlannedLaunch {
     int kernel;            // PrefillKernel
@@ -543,6 +560,23 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
             const bool fused = form != 5 && best_rows == 32 && halves == 1 && tiles <= (int64_t)kCounterSlots && (form == 8 || T <= 16);
             plan.launch[plan.count++] = PlannedLaunch{fused ? kKernelSplitKFused : kKernelSplitK, best_rows, (int)tpc, (int)tiles, 0, (int)best_S,
                                                       (unsigned)(tiles * halves * best_S)};
+            return plan;
+        }
+    }
+    // Square form (width 256, 16-bit rows): 256-row tiles on four waves, a workgroup per tile, as many rounds as that
+    // makes.  Half the W1' traffic and half the LDS reads per row of the 128-row tiles below, but twice the work per
+    // workgroup: it is the automatic choice when more than half the CUs get a tile and the last round is not mostly idle
+    // CUs -- at most one round, whole rounds, a last round at least 0.6 full, or two rounds and more.  Measured on 256 CUs
+    // against the 128-row tiles (bf16, C = 8, d = 4096; us): 102 / 119 at T = 4352 (136 tiles), 107 / 123 at 4608, 126 / 145 at
+    // 7168, 135-143 / 150 at 8192 (one round), 273 / 300 at 16384, 341 / 352 at C = 9 (2.25 rounds); d = 1024: 36 / 42 at 4608,
+    // 43 / 52 at 8192; d = 8192: 195 / 230 at 4608, 268 / 297 at 8192; but 209 / 188 at T = 8448 (1.03 rounds), 210 / 193 at 9216,
+    // 225 / 220 at 12288 (1.5), and 98 / 77 at 4096, where the 128-row tiles give every CU one.
+    const bool square_fits = two_halves && dtype != TIDE_F32 && !generic_d && d / kSquareStageK >= kSquareMinStages;
+    if (square_fits && (form == 0 || form == 9)) {
+        const int64_t tpc = (T + kSquareRows - 1) / kSquareRows, tiles = C * tpc, rem = tiles % (int64_t)cus;
+        const bool even_rounds = tiles <= (int64_t)cus || rem == 0 || 5 * rem >= 3 * (int64_t)cus || tiles >= 2 * (int64_t)cus;
+        if (form == 9 || (2 * tiles > (int64_t)cus && even_rounds)) {
+            plan.launch[plan.count++] = PlannedLaunch{kKernelSquare, kSquareRows, (int)tpc, (int)tiles, 0, 1, 8u * (unsigned)((tiles + 7) / 8)};
             return plan;
         }
     }
@@ -687,6 +721,9 @@ int launch_prefill(const Scratch& sc, const PrefillPlan& plan, const void* hidde
                 break;
             case kKernelBand:
                 if constexpr (DT != kF32) rc = launch_band<DT>(L.grid, st, p);
+                break;
+            case kKernelSquare:
+                if constexpr (DT != kF32) rc = launch_square<DT>(st, p);
                 break;
             case kKernelStream128:
                 rc = launch_dma<DT, 128, 1>(L.grid, st, p);
@@ -1379,7 +1416,7 @@ namespace {
 // (bits 8-15: 0, 32, 64 or 128; form 8: 0 or 32) and slice count (bits 16-23: 0, 2, 4 or 8).
 bool valid_form_word(int w) {
     const int form = w & 0xff, rows = (w >> 8) & 0xff, slices = (w >> 16) & 0xff;
-    if (w < 0 || (w >> 24) != 0 || form > 8) return false;
+    if (w < 0 || (w >> 24) != 0 || form > 9) return false;
     if ((rows || slices) && form != 5 && form != 8) return false;
     if (form == 8 && rows != 0 && rows != 32) return false;
     return (rows == 0 || rows == 32 || rows == 64 || rows == 128) && (slices == 0 || slices == 2 || slices == 4 || slices == 8);

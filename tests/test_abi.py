@@ -147,9 +147,9 @@ def test_set_variant_validates():
 
 def test_set_prefill_form_validates():
     prev = tr.set_prefill_form(0)
-    assert prev & 0xff in (0, 1, 2, 3, 4, 5, 6, 7, 8)
+    assert prev & 0xff in (0, 1, 2, 3, 4, 5, 6, 7, 8, 9)
     with pytest.raises(tr.TideError):
-        tr.set_prefill_form(9)
+        tr.set_prefill_form(10)
     # forms 5 and 8 may carry a forced split-k shape (rows << 8 | slices << 16); no other form may, and only the shapes that exist
     # (the single-launch form 8 has 32-row tiles)
     word = tr.splitk_form(64, 4)
@@ -158,7 +158,7 @@ def test_set_prefill_form_validates():
     assert tr.set_prefill_form(0) == word
     assert tr.set_prefill_form(8 | 32 << 8 | 4 << 16) == 0
     assert tr.set_prefill_form(0) == 8 | 32 << 8 | 4 << 16
-    for bad in (2 | 64 << 8, 5 | 48 << 8, 5 | 16 << 16, 5 | 1 << 24, 8 | 64 << 8, -1):
+    for bad in (2 | 64 << 8, 5 | 48 << 8, 5 | 16 << 16, 5 | 1 << 24, 8 | 64 << 8, 9 | 2 << 16, -1):
         with pytest.raises(tr.TideError):
             tr.set_prefill_form(bad)
     assert tr.set_prefill_form(prev) == 0

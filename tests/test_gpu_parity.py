@@ -107,7 +107,7 @@ def test_config1_full(tr, packed):
     assert st["max_abs_err"] < 1e-2                      # bf16 W1' rounding: well inside the 2e-2 bar
 
 
-@pytest.mark.parametrize("form", [1, 2, 3, 4, 5, 6, 7, 8, 0])
+@pytest.mark.parametrize("form", [1, 2, 3, 4, 5, 6, 7, 8, 9, 0])
 @pytest.mark.parametrize("dtype,T,d", [("bf16", 300, 1024), ("f16", 129, 768), ("f32", 257, 512), ("bf16", 64, 128), ("f16", 1100, 384)])
 def test_every_prefill_form_computes_the_same_function(tr, form, dtype, T, d):
     """Streaming form with 64 / 128 rows per workgroup, the register-ring form, the wide-tile form,
@@ -385,6 +385,58 @@ def test_width_256_at_the_measured_size(tr, d, T):
     assert st["max_abs_err"] < 1e-2
 
 
+@pytest.mark.parametrize("dtype,C,T,d,forced,what", [
+    ("bf16", 8, 8192, 4096, False, "one 256-row tile per CU: the automatic choice, at the size whose timing the bench quotes"),
+    ("f16", 8, 4400, 1024, False, "138 tiles on 138 CUs, the last tile of every checkpoint ragged (48 rows)"),
+    ("bf16", 8, 8300, 512, True, "264 tiles: a full round and 8 more workgroups; ragged (108 rows)"),
+    ("bf16", 5, 77, 192, True, "three stages, the fewest the kernel takes: no steady-state stage at all; tiles of 77 rows"),
+    ("f16", 3, 1000, 320, True, "five stages: one steady-state pair, then three of the last kind"),
+    ("bf16", 2, 515, 448, True, "seven stages: an odd count"),
+])
+def test_width_256_square_form(tr, dtype, C, T, d, forced, what):
+    """The square form (256 x 256 tiles on four waves that issue their own transfers) where it is the automatic
+    choice and, forced, on stage counts that exercise each way its k loop can end."""
+    w = synth.Workload(f"square_{dtype}_C{C}_T{T}_d{d}", 61, dtype, d, 4 * C, 4, T, None, b=256)
+    assert w.C == C
+    assert [L["kernel"] for L in tr.prefill_plan(tr.DTYPE_CODES[dtype], C, T, d, 256, form=9 if forced else 0)] == [10], what
+    rt = w.routers()
+    rt.b2[:] = np.linspace(-0.2, 0.2, C)
+    tr.set_prefill_form(9 if forced else 0)
+    try:
+        st, _, _ = run_and_compare(tr, w, w.name, rt=rt, packed=True, variant=tr.VARIANT_PREFILL)
+    finally:
+        tr.set_prefill_form(0)
+    assert st["max_abs_err"] < (1e-2 if dtype == "bf16" else 2e-3)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("d", [192, 256, 448])
+def test_square_form_sums_every_element(tr, dtype, d):
+    """As test_every_element_enters_the_sum_of_squares, for the square form, whose waves share out the sums of squares
+    by row block: row t carries a spike of 40 at element t (mod d)."""
+    import torch
+    T = 2 * d + 37
+    w = synth.Workload(f"square_spike_{dtype}_d{d}", 67, dtype, d, 8, 4, T, None, trajectory=False, b=256)
+    rt = w.routers()
+    h = np.random.default_rng(d).standard_normal((w.C, T, d)).astype(np.float32)
+    for t in range(T):
+        h[:, t, t % d] = 40.0
+    hb = synth.to_storage(h, dtype)
+    ex_o, z_o, m_o = oracle_select(w, rt, hb)
+    dev = to_device(hb, dtype)
+    g, W1, b1, w2 = routers_to_device(rt)
+    tr.set_prefill_form(9)
+    tr.set_variant(tr.VARIANT_PREFILL)
+    try:
+        assert [L["kernel"] for L in tr.prefill_plan(tr.DTYPE_CODES[dtype], w.C, T, d, 256, form=9)] == [10]
+        ex, z, m = tr.select_exit(dev, g, w.eps, W1, b1, w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers)
+        torch.cuda.synchronize()
+    finally:
+        tr.set_prefill_form(0)
+        tr.set_variant(tr.VARIANT_AUTO)
+    report(compare_select(w.name, dtype, z.cpu().numpy(), ex.cpu().numpy(), m.cpu().numpy(), z_o, ex_o, m_o, rt.theta, w.layer_ids, 0, w.n_layers))
+
+
 @pytest.mark.parametrize("b", [64, 256])
 @pytest.mark.parametrize("dtype,T,d", [("bf16", 300, 1024), ("f16", 129, 768), ("f32", 257, 512), ("bf16", 4100, 256),
                                        ("f16", 1100, 384)])
@@ -396,7 +448,7 @@ def test_bottleneck_widths_every_dtype_and_form(tr, b, dtype, T, d):
     rt.b2[:] = [0.2, -0.1, 0.0]
     hb = w.hidden()
     run_and_compare(tr, w, w.name + "_raw", rt=rt, hidden_bits=hb, variant=tr.VARIANT_PREFILL)
-    for form in (1, 2, 3, 4, 6, 7):
+    for form in (1, 2, 3, 4, 6, 7, 9):
         tr.set_prefill_form(form)
         try:
             run_and_compare(tr, w, f"{w.name}_form{form}", rt=rt, hidden_bits=hb, packed=True, variant=tr.VARIANT_PREFILL)

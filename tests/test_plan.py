@@ -8,7 +8,7 @@ import pytest
 
 from paper_2603_21365_amd import tide_route as tr
 
-SPLITK, WIDE, WIDE_F32, TILE, STREAM128, STREAM64, RING, BAND, SPLITK_FUSED = 1, 2, 3, 4, 5, 6, 7, 8, 9
+SPLITK, WIDE, WIDE_F32, TILE, STREAM128, STREAM64, RING, BAND, SPLITK_FUSED, SQUARE = 1, 2, 3, 4, 5, 6, 7, 8, 9, 10
 ELEM = {tr.F32: 4, tr.F16: 2, tr.BF16: 2}
 
 
@@ -57,6 +57,13 @@ def check_plan(dtype, C, T, d, b, cus, form):
             assert wg == (cus if L["total_tiles"] >= cus else 8 * -(-L["total_tiles"] // 8)), what   # rounds of one tile per CU; the last may be partly filled
             assert (dtype == tr.F32) == (k == WIDE_F32), what
             assert not (k == WIDE_F32 and halves == 2), what
+        if k == SQUARE:
+            assert len(plan) == 1 and R == 256 and halves == 2 and dtype != tr.F32 and d % 128 == 0 and d >= 192, what
+            assert L["tile_begin"] == 0 and wg == 8 * -(-L["total_tiles"] // 8), what
+            assert (form & 0xff) in (0, 9), what
+            if form == 0:      # its own choice: more than half the CUs get a tile, and no last round of mostly idle CUs
+                n, rem = L["total_tiles"], L["total_tiles"] % cus
+                assert 2 * n > cus and (n <= cus or rem == 0 or 5 * rem >= 3 * cus or n >= 2 * cus), what
         if k == TILE:
             assert R == 128 and dtype != tr.F32 and d % 128 == 0, what
             assert wg == 8 * -(-(L["total_tiles"] - L["tile_begin"]) // 8), what
@@ -80,7 +87,7 @@ SHAPES = [(8, 4096, 4096), (9, 16384, 4096), (10, 16384, 768), (10, 16384, 8192)
           (7, 2049, 3072), (2, 12345, 5120), (8, 2048, 4096), (8, 3072, 4096), (8, 1536, 4096), (1, 16384, 4096)]
 
 
-@pytest.mark.parametrize("form", [0, 1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("form", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9])
 @pytest.mark.parametrize("dtype", [tr.BF16, tr.F16, tr.F32])
 def test_every_row_is_in_exactly_one_tile(dtype, form):
     for C, T, d in SHAPES:
@@ -100,7 +107,7 @@ def test_every_row_is_in_exactly_one_tile_on_random_shapes():
         d = int(rng.choice([128, 256, 384, 768, 1024, 2048, 2560, 4096, 5120, 8192, 16384]))
         b = int(rng.choice([64, 128, 256]))
         cus = int(rng.choice([8, 64, 128, 256, 304]))
-        form = int(rng.integers(0, 9))
+        form = int(rng.integers(0, 10))
         check_plan(dtype, C, T, d, b, cus, form)
 
 
@@ -192,7 +199,7 @@ def test_the_band_schedule_covers_every_block_once():
 
 def test_generic_hidden_sizes_take_the_register_ring_kernel():
     for dtype, d in ((tr.BF16, 200), (tr.F16, 72), (tr.F32, 100), (tr.BF16, 4104), (tr.F32, 708)):
-        for form in range(9):
+        for form in range(10):
             for C, T in ((1, 1), (4, 300), (10, 16384)):
                 plan = check_plan(dtype, C, T, d, 128, 256, form)
                 assert [L["kernel"] for L in plan] == [RING]
@@ -204,9 +211,11 @@ def test_the_choices_on_the_named_workloads():
     assert kinds(tr.prefill_plan(tr.BF16, 8, 4096, 4096)) == [(TILE, 128)]                       # one tile per CU
     assert kinds(tr.prefill_plan(tr.BF16, 9, 16384, 4096)) == [(BAND, 32)]                        # 18 blocks of 32 rows per CU: the band form
     assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096)) == [(BAND, 32)]                       # 20 per CU
-    assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256)) == [(TILE, 128)]                 # width 256: the one-tile kernel, five rounds of workgroups; the band form has no such width
-    assert tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256)[0]["workgroups"] == 1280
-    assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256, form=4)) == [(WIDE, 128)]         # ... the wide-tile kernel when forced
+    assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256)) == [(SQUARE, 256)]               # width 256: the square form, two and a half rounds of 256-row tiles
+    assert tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256)[0]["workgroups"] == 640
+    assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256, form=6)) == [(TILE, 128)]         # ... the one-tile kernel when forced: five rounds of 128-row tiles
+    assert tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256, form=6)[0]["workgroups"] == 1280
+    assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256, form=4)) == [(WIDE, 128)]         # ... or the wide-tile kernel
     assert kinds(tr.prefill_plan(tr.BF16, 8, 8192, 4096)) == [(BAND, 32)]                         # 8 per CU (= one round of 256-row tiles)
     assert kinds(tr.prefill_plan(tr.BF16, 8, 5120, 4096)) == [(BAND, 32)]                         # 5 per CU
     assert kinds(tr.prefill_plan(tr.BF16, 8, 5120, 4096, form=4)) == [(WIDE, 256)]                # ... forced: 160 wide tiles on 160 CUs
@@ -237,7 +246,16 @@ def test_the_choices_on_the_named_workloads():
     assert kinds(tr.prefill_plan(tr.BF16, 8, 4096 + 128, 4096)) == [(BAND, 32)]                   # one block more than a 128-row tile per CU
     assert kinds(tr.prefill_plan(tr.BF16, 8, 4096, 4096)) == [(TILE, 128)]                        # exactly four blocks per CU: the one-tile kernel
     assert kinds(tr.prefill_plan(tr.BF16, 8, 3072, 4096, 256)) == [(TILE, 128)]                   # width 256: 192 tiles of 128 rows on 192 CUs
-    assert kinds(tr.prefill_plan(tr.BF16, 8, 7168, 4096, 256)) == [(TILE, 128)]                   # ... and 448: a round and three quarters
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 4352, 4096, 256)) == [(SQUARE, 256)]                 # ... 136 tiles of 256 rows: the square form from more than half the CUs on
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 7168, 4096, 256)) == [(SQUARE, 256)]                 # ... 224
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 8192, 4096, 256)) == [(SQUARE, 256)]                 # ... one round
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 8448, 4096, 256)) == [(TILE, 128)]                   # ... one round and 8 tiles: a second round would be mostly idle CUs
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 12288, 4096, 256)) == [(TILE, 128)]                  # ... a round and a half
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 13312, 4096, 256)) == [(SQUARE, 256)]                # ... 1.625 rounds
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 16384, 4096, 256)) == [(SQUARE, 256)]                # ... two rounds
+    assert kinds(tr.prefill_plan(tr.F16, 9, 16384, 4096, 256)) == [(SQUARE, 256)]                 # ... 2.25
+    assert kinds(tr.prefill_plan(tr.F32, 8, 8192, 4096, 256)) != [(SQUARE, 256)]                  # (16-bit rows only)
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 8192, 128, 256)) != [(SQUARE, 256)]                  # (two 64-value stages: too short a row)
     assert kinds(tr.prefill_plan(tr.F32, 8, 7168, 4096)) == [(WIDE_F32, 256)]                     # fp32 rows: 224 wide tiles
     assert kinds(tr.prefill_plan(tr.F32, 1, 9216, 4096)) == [(RING, 64)]                          # fp32, 72 tiles: the split-k chain is too long
     assert kinds(tr.prefill_plan(tr.F32, 1, 8192, 4096)) == [(SPLITK, 64)]
@@ -268,7 +286,7 @@ def test_the_band_form_is_one_launch_over_all_blocks():
 
 
 def test_plan_rejects_bad_arguments():
-    bad = [dict(dtype=9), dict(C=0), dict(C=33), dict(T=0), dict(d=100000), dict(d=0), dict(b=96), dict(cus=100), dict(cus=0), dict(form=9)]
+    bad = [dict(dtype=9), dict(C=0), dict(C=33), dict(T=0), dict(d=100000), dict(d=0), dict(b=96), dict(cus=100), dict(cus=0), dict(form=10)]
     # hidden sizes of the generic fallback that are copied into zero-padded rows first are planned at the padded size
     assert tr.prefill_plan(tr.BF16, 4, 1000, 130) == tr.prefill_plan(tr.BF16, 4, 1000, 131)[:] == tr.prefill_plan(tr.BF16, 4, 1000, 256)
     assert tr.prefill_plan(tr.BF16, 4, 1000, 200, 256) == tr.prefill_plan(tr.BF16, 4, 1000, 256, 256)
