@@ -35,13 +35,13 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}
 
 
 def pmc_shapes(tr) -> int:
-    """Three shapes, ten launches each on two rotating batches of random bf16 rows, nothing timed: each runs on one
+    """Four shapes, ten launches each on two rotating batches of random bf16 rows, nothing timed: each runs on one
     kernel of its own, so a counter run's per-kernel means are per shape (profiles/per_cu_load_path_pmc.txt)."""
     import numpy as np
     import torch
     gen = torch.Generator(device="cuda").manual_seed(0x71DE)
     shapes = []
-    for C, T, d, b in ((8, 4096, 4096, 128), (9, 16384, 4096, 128), (8, 4096, 4096, 256)):
+    for C, T, d, b in ((8, 4096, 4096, 128), (9, 16384, 4096, 128), (8, 4096, 4096, 256), (8, 8192, 4096, 256)):
         rows = [torch.randn((C, T, d), generator=gen, device="cuda").to(torch.bfloat16) for _ in range(2)]
         W1 = torch.randn((C, d, b), generator=gen, device="cuda") / d ** 0.5
         w2 = torch.randn((C, b), generator=gen, device="cuda") / b ** 0.5
@@ -59,6 +59,20 @@ def pmc_shapes(tr) -> int:
     return 0
 
 
+def mfma_rate(tr) -> int:
+    """The matrix instruction's sustained rate: 3 runs of 20 launches per case, 256 CUs x 4 or 8 waves x 4096 instructions each."""
+    cases = {}
+    for zero in (False, True):
+        for waves in (4, 8):
+            runs = [tr.mfma_probe(waves, 512, 20, zero) for _ in range(3)]
+            cases[f"{'zero' if zero else 'random'}_operands_{waves}_waves_per_cu"] = {
+                "tflops": [round(r["tflops"], 1) for r in runs], "us_per_launch": [round(r["us_per_launch"], 1) for r in runs],
+                "clock_ghz": [round(r["clock_ghz"], 3) for r in runs],
+                "cycles_per_instruction_and_wave": round(runs[-1]["cycles_per_instruction_and_wave"], 1)}
+    print(json.dumps({"mfma_rate": {"instruction": "v_mfma_f32_32x32x16_bf16", "nominal_peak_tflops": MFMA_PEAK_TFLOPS["bf16"], **cases}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -72,8 +86,12 @@ def main() -> int:
     ap.add_argument("--no-sweep", action="store_true", help="skip the hidden-size x dtype sweep (configs[4])")
     ap.add_argument("--no-settle", action="store_true", help="skip the untimed settling phase (short profiler runs)")
     ap.add_argument("--pmc-shapes", action="store_true",
-                    help="only launch three shapes ten times each, untimed, for rocprofv3 --pmc runs: configs[1] (one-tile kernel), "
-                         "configs[3] (band kernel) and width 256 at C=8, T=4096, d=4096 (one-tile kernel, eight consumer waves)")
+                    help="only launch four shapes ten times each, untimed, for rocprofv3 --pmc runs: configs[1] (one-tile kernel), "
+                         "configs[3] (band kernel), width 256 at C=8, T=4096, d=4096 (one-tile kernel, eight consumer waves) and at "
+                         "T=8192 (square kernel)")
+    ap.add_argument("--mfma-rate", action="store_true",
+                    help="only measure the sustained rate of the prefill kernels' matrix instruction (random and all-zero operands, "
+                         "one and two waves per SIMD) and print it as one JSON line (profiles/mfma_sustained_rate.txt)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 256 MiB device copy 3 times (known traffic, scales the profiler's "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -90,6 +108,8 @@ def main() -> int:
     from paper_2603_21365_amd import tide_route as tr
     if args.pmc_shapes:
         return pmc_shapes(tr)
+    if args.mfma_rate:
+        return mfma_rate(tr)
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)

@@ -216,6 +216,16 @@ size_t tide_noalloc_scratch_bytes(void);
  * workspace (source (1) above): lets a caller check that a loop of calls allocates nothing.   */
 uint64_t tide_workspace_allocations(void);
 
+/* Measurement helper for benchmarks, not part of the router path: the rate at which this device sustains the
+ * matrix instruction the prefill kernels use for the d x b projection of Eq. (2) (32 x 32 x 16, bf16 operands, fp32
+ * accumulators) when every wave issues it back to back from registers.  One workgroup of waves_per_cu waves (4 or 8:
+ * one or two per SIMD) per compute unit, iters x 8 instructions per wave and launch, `launches` timed launches on the
+ * default stream after one untimed; zero_operands != 0 runs it on all-zero operands (the clock then stays up: the
+ * difference is the power the arithmetic draws).  out: HOST double [4] = {microseconds per launch, TFLOP/s, shader
+ * clock in GHz during one workgroup's loop, shader cycles per instruction and wave}.  Allocates and frees its own few
+ * KiB of device memory and synchronises the device.  Returns TIDE_OK or a negative tide_status_t.            */
+int tide_mfma_probe(int waves_per_cu, int iters, int launches, int zero_operands, double* out);
+
 /* Exit projection: the rows the LM head consumes (Fig. 1 "LMHead(Norm(h_k))", Alg. 1 line 5,
  * Sec. 3.4 kernels 3-4).  out[t,:] = RMSNorm(src_t) * norm_gain, computed in fp32 and rounded
  * once to `dtype`, where src_t = hidden[c,t,:] for the checkpoint c with

@@ -12,6 +12,7 @@
 #include <cstring>
 #include <limits>
 #include <mutex>
+#include <vector>
 
 #include "batch_kernel.hpp"
 #include "compact_kernel.hpp"
@@ -25,6 +26,7 @@
 #include "prefill_wide_kernel.hpp"
 #include "prefill_band_kernel.hpp"
 #include "prefill_square_kernel.hpp"
+#include "mfma_probe_kernel.hpp"
 #include "prefill_wide32_kernel.hpp"
 #include "project_kernel.hpp"
 #include "repack_kernel.hpp"
@@ -1013,7 +1015,7 @@ int run(const void* hidden, int dtype, int64_t C, int64_t T, int64_t d, int64_t 
 
 extern "C" {
 
-int tide_version(void) { return 110; }
+int tide_version(void) { return 111; }
 
 const char* tide_last_error(void) { return g_err; }
 
@@ -1203,6 +1205,72 @@ int tide_debug_timeline(void* buffer) {
     return kTimelineStamps;
 }
 #endif
+
+// Measurement helper (not part of the router path): see the header.
+int tide_mfma_probe(int waves_per_cu, int iters, int launches, int zero_operands, double* out) {
+    g_err[0] = 0;
+    if (!out || (waves_per_cu != 4 && waves_per_cu != 8) || iters < 1 || iters > (1 << 20) || launches < 1 || launches > 1000)
+        return fail(TIDE_ERR_INVALID_ARG, "tide_mfma_probe: waves_per_cu 4 or 8, 1 <= iters <= 2^20, 1 <= launches <= 1000, out not NULL");
+    unsigned cus = 0;
+    int rc = resident_cus(&cus);
+    if (rc) return rc;
+    // operand bits: pairs of bf16 values of magnitude 1 .. 2 with pseudo-random mantissas and signs, or zeros
+    std::vector<uint32_t> bits(4096 * 4, 0u);
+    if (!zero_operands) {
+        uint32_t x = 0x71DEu;
+        for (uint32_t& w : bits) {
+            uint32_t h[2];
+            for (uint32_t& v : h) {
+                x = x * 1664525u + 1013904223u;
+                v = 0x3f80u | ((x >> 9) & 0x7fu) | (((x >> 20) & 1u) << 15);
+            }
+            w = h[0] | (h[1] << 16);
+        }
+    }
+    void *in = nullptr, *sums = nullptr, *clk = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    auto cleanup = [&]() {
+        if (in) (void)hipFree(in);
+        if (sums) (void)hipFree(sums);
+        if (clk) (void)hipFree(clk);
+        if (e0) (void)hipEventDestroy(e0);
+        if (e1) (void)hipEventDestroy(e1);
+    };
+    auto step = [&](hipError_t e, const char* what) {
+        if (e == hipSuccess) return 0;
+        cleanup();
+        return fail(TIDE_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    };
+    const unsigned threads = (unsigned)waves_per_cu * kWave;
+    if ((rc = step(hipMalloc(&in, bits.size() * 4), "hipMalloc"))) return rc;
+    if ((rc = step(hipMalloc(&sums, (size_t)cus * threads * sizeof(float)), "hipMalloc"))) return rc;
+    if ((rc = step(hipMalloc(&clk, 16), "hipMalloc"))) return rc;
+    if ((rc = step(hipMemcpy(in, bits.data(), bits.size() * 4, hipMemcpyHostToDevice), "hipMemcpy"))) return rc;
+    if ((rc = step(hipMemset(clk, 0, 16), "hipMemset"))) return rc;
+    if ((rc = step(hipEventCreate(&e0), "hipEventCreate"))) return rc;
+    if ((rc = step(hipEventCreate(&e1), "hipEventCreate"))) return rc;
+    auto launch = [&]() {
+        hipLaunchKernelGGL(tide_mfma_probe_kernel, dim3(cus), dim3(threads), 0, nullptr, (const u32x4*)in, (float*)sums, iters, (unsigned long long*)clk);
+    };
+    launch();                                                     // (untimed: code load, clocks)
+    if ((rc = step(hipDeviceSynchronize(), "hipDeviceSynchronize"))) return rc;
+    if ((rc = step(hipEventRecord(e0, nullptr), "hipEventRecord"))) return rc;
+    for (int l = 0; l < launches; ++l) launch();
+    if ((rc = step(hipEventRecord(e1, nullptr), "hipEventRecord"))) return rc;
+    if ((rc = step(hipDeviceSynchronize(), "hipDeviceSynchronize"))) return rc;
+    float ms = 0.0f;
+    if ((rc = step(hipEventElapsedTime(&ms, e0, e1), "hipEventElapsedTime"))) return rc;
+    unsigned long long c[2] = {0, 0};
+    if ((rc = step(hipMemcpy(c, clk, 16, hipMemcpyDeviceToHost), "hipMemcpy"))) return rc;
+    cleanup();
+    const double us = (double)ms * 1e3 / launches;
+    const double flop = (double)cus * waves_per_cu * (double)iters * kMfmaProbeAcc * 32768.0;      // 2 x 32 x 32 x 16 per instruction
+    out[0] = us;
+    out[1] = flop / us / 1e6;                                    // TFLOP/s
+    out[2] = c[1] ? (double)c[0] / (double)c[1] / 10.0 : 0.0;     // GHz
+    out[3] = (double)c[0] / ((double)iters * kMfmaProbeAcc);     // cycles per instruction and wave
+    return TIDE_OK;
+}
 
 uint64_t tide_workspace_allocations(void) {
     std::lock_guard<std::mutex> lock(g_mu);

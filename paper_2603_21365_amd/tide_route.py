@@ -27,7 +27,7 @@ EXPORTS = (
     "tide_packed_router_bytes", "tide_router_pack", "tide_router_eval_packed",
     "tide_select_exit_packed", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_batch_compact", "tide_set_variant", "tide_set_prefill_form", "tide_prefill_plan", "tide_stream_schedule", "tide_band_schedule", "tide_release",
     "tide_workspace_bytes", "tide_workspace_init", "tide_workspace_forget", "tide_router_eval_ws", "tide_select_exit_ws",
-    "tide_select_exit_packed_noalloc", "tide_noalloc_scratch_bytes", "tide_workspace_allocations",
+    "tide_select_exit_packed_noalloc", "tide_noalloc_scratch_bytes", "tide_workspace_allocations", "tide_mfma_probe",
 )
 
 _lib = None
@@ -80,6 +80,8 @@ def load_library() -> ctypes.CDLL:
     lib.tide_prefill_plan.argtypes = [ci, i64, i64, i64, i64, ci, ci, vp]
     lib.tide_stream_schedule.argtypes = [ci, i64, i64, ci, ci, ci, ci, vp, ci]
     lib.tide_band_schedule.argtypes = [i64, i64, ci, ci, vp, ci]
+    lib.tide_mfma_probe.argtypes = [ci, ci, ci, ci, vp]
+    lib.tide_mfma_probe.restype = ci
     for name in ("tide_router_eval", "tide_router_eval_packed", "tide_select_exit", "tide_select_exit_packed",
                  "tide_router_pack", "tide_exit_project", "tide_batch_exit", "tide_cosine_labels", "tide_batch_compact", "tide_set_variant", "tide_set_prefill_form", "tide_release",
                  "tide_router_eval_ws", "tide_select_exit_ws", "tide_select_exit_packed_noalloc", "tide_workspace_init", "tide_workspace_forget"):
@@ -173,6 +175,13 @@ def band_schedule(C: int, blocks_per_ckpt: int, grid: int, block: int) -> list:
         if n <= cap:
             return [tuple(out[3 * i:3 * i + 3]) for i in range(n)]
         cap = n
+
+
+def mfma_probe(waves_per_cu: int = 4, iters: int = 512, launches: int = 20, zero_operands: bool = False) -> dict:
+    """Sustained rate of the prefill kernels' matrix instruction on this device (a measurement helper, see the header)."""
+    out = (ctypes.c_double * 4)()
+    _check(load_library().tide_mfma_probe(int(waves_per_cu), int(iters), int(launches), int(bool(zero_operands)), out))
+    return {"us_per_launch": out[0], "tflops": out[1], "clock_ghz": out[2], "cycles_per_instruction_and_wave": out[3]}
 
 
 PLAN_FIELDS = ("kernel", "rows_per_tile", "tiles_per_ckpt", "total_tiles", "tile_begin", "k_slices", "workgroups")

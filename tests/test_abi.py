@@ -164,6 +164,14 @@ def test_set_prefill_form_validates():
     assert tr.set_prefill_form(prev) == 0
 
 
+def test_mfma_probe_validates_its_arguments():
+    lib = tr.load_library()
+    out = (ctypes.c_double * 4)()
+    for waves, iters, launches, outp in ((3, 16, 1, out), (4, 0, 1, out), (4, 16, 0, out), (8, 1 << 21, 1, out), (4, 16, 1001, out), (4, 16, 1, None)):
+        assert lib.tide_mfma_probe(waves, iters, launches, 0, outp) == -1, (waves, iters, launches)
+        assert "tide_mfma_probe" in tr.last_error()
+
+
 def test_exit_statistics_reproduce_fig3(golden_dir):
     g = read_golden(os.path.join(golden_dir, "fig3_exit_example.txt"))
     ex = [int(x) for x in g["exit_layers"]]
