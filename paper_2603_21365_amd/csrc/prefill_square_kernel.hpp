@@ -50,8 +50,8 @@ constexpr int kSquareRowBytes = kSquareStageK * 2;                    // bytes o
 constexpr int kSquareStageBytes = kSquareRows * kSquareRowBytes;      // 32 KiB
 constexpr int kSquareStages = 4;
 constexpr int kSquareMinStages = 3;                                   // the prologue fills three slots unconditionally
-// ring + logit partials per wave [4][256] + row scales [256]
-constexpr int kSquareLdsBytes = kSquareStages * kSquareStageBytes + (kSquareWaves + 1) * kSquareRows * (int)sizeof(float);
+// ring + sums of squares per k-group [4][256] + logit partials per wave [4][256] + row scales [256]
+constexpr int kSquareLdsBytes = kSquareStages * kSquareStageBytes + (4 + kSquareWaves + 1) * kSquareRows * (int)sizeof(float);
 static_assert(kSquareLdsBytes <= 160 * 1024, "LDS of a CU");
 
 // Four fragments (row blocks kOff / 4096 .. + 3 of the stage at addr) into a.
@@ -88,6 +88,40 @@ template <int v> __device__ __forceinline__ void square_load_w(u32x4 (&w)[8], ui
         asm volatile("global_load_dwordx4 %0, %1, %2" : "+v"(w[v]) : "v"(lane_off), "s"(sb + (v >> 1) * 4096) : "memory");
 }
 
+// Sums of squares on the matrix cores.  With one wave per SIMD nothing runs beside a wave's own instructions: every
+// vector-ALU instruction in the k loop is time the matrix core idles (dot products and the selects that picked a wave's
+// share cost 720 of a stage's 3180 cycles).  The 4 x 4 x 4 matrix instruction works on 16 independent groups of four
+// lanes: D_b[i][j] += sum_k A_b[i][k] B_b[k][j], lane 4 b + i supplying row i of A_b and column i of B_b as four 16-bit
+// values.  Given the SAME register for both operands it accumulates the Gram matrix of the group's four lanes, whose
+// diagonal element (i, i) -- lane 4 b + i, accumulator register i -- is that lane's own sum of squares: eight
+// cycles for four k values of all 64 lanes, and exact products as with the dot-product instruction.  A row
+// fragment (8 k values per lane) takes two of them.
+// It is inline assembly: the accumulators of the 32 x 32 steps fill the accumulation registers, and the compiler, which keeps
+// every matrix instruction's result there once a kernel uses them at all, would move blocks in and out around each of these
+// (the instruction itself takes ordinary vector registers).  The eight instructions of four fragments go round the four
+// accumulators, so that one that reads an accumulator is three instructions (24 cycles) behind the one that wrote it:
+// more than the wait states the hardware asks for between dependent matrix instructions, which the compiler cannot
+// insert inside an asm statement.
+template <int DT> __device__ __forceinline__ void square_sumsq4(const u32x4 (&a)[4], f32x4 (&acc)[4]) {
+    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+    const u32x2 l0 = {a[0][0], a[0][1]}, l1 = {a[1][0], a[1][1]}, l2 = {a[2][0], a[2][1]}, l3 = {a[3][0], a[3][1]};
+    const u32x2 h0 = {a[0][2], a[0][3]}, h1 = {a[1][2], a[1][3]}, h2 = {a[2][2], a[2][3]}, h3 = {a[3][2], a[3][3]};
+    if constexpr (DT == kBF16)
+        asm("v_mfma_f32_4x4x4_16b_bf16 %0, %4, %4, %0\n\tv_mfma_f32_4x4x4_16b_bf16 %1, %5, %5, %1\n\t"
+            "v_mfma_f32_4x4x4_16b_bf16 %2, %6, %6, %2\n\tv_mfma_f32_4x4x4_16b_bf16 %3, %7, %7, %3\n\t"
+            "v_mfma_f32_4x4x4_16b_bf16 %0, %8, %8, %0\n\tv_mfma_f32_4x4x4_16b_bf16 %1, %9, %9, %1\n\t"
+            "v_mfma_f32_4x4x4_16b_bf16 %2, %10, %10, %2\n\tv_mfma_f32_4x4x4_16b_bf16 %3, %11, %11, %3"
+            : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3])
+            : "v"(l0), "v"(l1), "v"(l2), "v"(l3), "v"(h0), "v"(h1), "v"(h2), "v"(h3));
+    else
+        asm("v_mfma_f32_4x4x4_16b_f16 %0, %4, %4, %0\n\tv_mfma_f32_4x4x4_16b_f16 %1, %5, %5, %1\n\t"
+            "v_mfma_f32_4x4x4_16b_f16 %2, %6, %6, %2\n\tv_mfma_f32_4x4x4_16b_f16 %3, %7, %7, %3\n\t"
+            "v_mfma_f32_4x4x4_16b_f16 %0, %8, %8, %0\n\tv_mfma_f32_4x4x4_16b_f16 %1, %9, %9, %1\n\t"
+            "v_mfma_f32_4x4x4_16b_f16 %2, %10, %10, %2\n\tv_mfma_f32_4x4x4_16b_f16 %3, %11, %11, %3"
+            : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3])
+            : "v"(l0), "v"(l1), "v"(l2), "v"(l3), "v"(h0), "v"(h1), "v"(h2), "v"(h3));
+}
+
 // grid = 8 * ceil(p.total_tiles / 8); p.tiles_per_ckpt = ceil(T / 256).
 template <int DT>
 __global__ __launch_bounds__(kSquareThreads, 1) void tide_prefill_square_kernel(const PrefillParams p) {
@@ -96,7 +130,8 @@ __global__ __launch_bounds__(kSquareThreads, 1) void tide_prefill_square_kernel(
     typedef __attribute__((address_space(1))) const char glb_char;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     char* ring = smem;
-    float* z_part = reinterpret_cast<float*>(smem + kSquareStages * kSquareStageBytes);    // [4][256]
+    float* ss_part = reinterpret_cast<float*>(smem + kSquareStages * kSquareStageBytes);   // [4][256]
+    float* z_part = ss_part + 4 * kSquareRows;                                             // [4][256]
     float* row_scale = z_part + kSquareWaves * kSquareRows;                                // [256]
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);    // uniform: addresses built on it are scalar
@@ -173,20 +208,12 @@ __global__ __launch_bounds__(kSquareThreads, 1) void tide_prefill_square_kernel(
         acc[0][b] = f32x16{0};
         acc[1][b] = f32x16{0};
     }
-    // This wave's share of the sums of squares: row blocks `wave` and 4 + wave, every k-group.  The fragment is picked
-    // with selects on the (uniform) wave number rather than with branches: see the end of `stage` on why no two paths
-    // may meet while fragments are on their way.
-    float ssq[2] = {0.0f, 0.0f};
-    const bool ss_bit0 = (wave & 1) != 0, ss_bit1 = (wave & 2) != 0;
-    auto own_fragment = [&](const u32x4 (&a)[4]) {
-        u32x4 f;
+    // This wave's share of the sums of squares: of a stage's eight half k-groups (k-group g, row blocks 0..3 or 4..7) those
+    // numbered `wave` and 7 - wave, one on either side of the stage's barrier, so that the four waves stay level.  The
+    // branch is uniform and changes these accumulators only.
+    f32x4 sq[2][4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const uint32_t lo = ss_bit0 ? a[1][e] : a[0][e], hi = ss_bit0 ? a[3][e] : a[2][e];
-            f[e] = ss_bit1 ? hi : lo;
-        }
-        return f;
-    };
+    for (int i = 0; i < 4; ++i) sq[0][i] = sq[1][i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
     // One stage: the matrix steps on stage k (W1' fragments in cur, first four row fragments in a0: both arrived
     // before the stage begins) and, spread between them, the stage's 16 memory operations in their fixed order -- the 8
@@ -225,7 +252,9 @@ __global__ __launch_bounds__(kSquareThreads, 1) void tide_prefill_square_kernel(
                 if (i == 0) memory_op(std::integral_constant<int, 2 * hg>{});
                 if (i == 2) memory_op(std::integral_constant<int, 2 * hg + 1>{});
             }
-            ssq[hg & 1] = chunk_sumsq<DT>(own_fragment(a), ssq[hg & 1]);
+            if (wave == (hg < 4 ? hg : 7 - hg)) {
+                square_sumsq4<DT>(a, sq[hg < 4 ? 0 : 1]);
+            }
         };
         // group 0
         square_read4(a1, sb + kUpperBlocks + aoff[0]);
@@ -285,14 +314,25 @@ __global__ __launch_bounds__(kSquareThreads, 1) void tide_prefill_square_kernel(
         if (k + 1 < ns) stage(std::false_type{}, wb, wa, k + 1);
     }
 
-    // ---- epilogue: each wave has the complete sums of squares of 64 rows; every lane owns one row per block
+    // ---- epilogue: the rows' sums of squares (a lane's own is register lane % 4 of its accumulator; lanes l and l ^ 32
+    // hold the two halves of every k-group), then every lane owns one row per block
     lane = lane_id();
     const int tid = wave * kWave + lane;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const float s2 = ssq[i] + __shfl_xor(ssq[i], 32, kWave);
-        if (lane < 32) row_scale[32 * (4 * i + wave) + lane] = kNegLog2e * inv_rms_f32(s2, p.inv_d, p.eps);
+    for (int set = 0; set < 2; ++set) {
+        const int hg = set == 0 ? wave : 7 - wave;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const f32x4 v = sq[set][i];
+            const float lo = (lane & 1) ? v[1] : v[0], hi = (lane & 1) ? v[3] : v[2];
+            const float own = (lane & 2) ? hi : lo;
+            const float s2 = own + __shfl_xor(own, 32, kWave);
+            if (lane < 32) ss_part[(hg >> 1) * kSquareRows + 32 * (4 * (hg & 1) + i) + lane] = s2;
+        }
     }
+    __syncthreads();
+    row_scale[tid] = kNegLog2e * inv_rms_f32((ss_part[tid] + ss_part[kSquareRows + tid]) + (ss_part[2 * kSquareRows + tid] + ss_part[3 * kSquareRows + tid]),
+                                              p.inv_d, p.eps);
     __syncthreads();
     float z[8];
 #pragma unroll
