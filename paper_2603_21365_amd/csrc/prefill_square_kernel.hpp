@@ -18,8 +18,8 @@
 //     that the stage before this one has been read by every wave (its slot takes the transfers issued in the second
 //     half), so a wave runs from the last matrix step of a stage into the first of the next without a barrier
 //     and reads the next stage's first fragments while the last steps of this one execute;
-//   - every wave adds up the sums of squares of two of the eight row blocks in every k-group, so that the four
-//     waves do the same work between two barriers.
+//   - the rows' sums of squares run on the matrix cores too (square_sumsq4 below), two of a stage's eight half k-groups
+//     per wave, one on either side of the barrier: with one wave per SIMD there is nothing to hide vector-ALU work behind.
 // Wave w owns columns 64 w .. 64 w + 63 (two column blocks) of all 256 rows; its W1' fragments come straight
 // from L2 into registers, two stages ahead.  A ring stage is 64 k values (128 bytes of each row: 32 KiB), four
 // slots, up to three stages in flight; wave w transfers rows 64 w .. 64 w + 63 of each stage.
