@@ -625,6 +625,36 @@ def test_prefill_ragged_tail_and_padded_strides(tr, T, dtype):
                           w.layer_ids, 0, w.n_layers))
 
 
+@pytest.mark.parametrize("T,dtype", [(1, "f16"), (255, "bf16"), (257, "bf16"), (600, "f16")])
+def test_square_form_on_padded_strides(tr, T, dtype):
+    """The square form on row and checkpoint strides larger than the data, padding filled with NaN, gain and biases in
+    use: the clamped re-reads of a ragged tile's missing rows must not reach any output."""
+    import torch
+    d, C, pad_cols, pad_rows = 448, 3, 8, 5
+    w = synth.Workload(f"square_edge_T{T}_{dtype}", 71, dtype, d, 12, 4, T, None, b=256)
+    say(f"{w.name}: square form, row_stride={d + pad_cols}, ckpt_stride=(T+{pad_rows})*row_stride")
+    hb = w.hidden()
+    rt = w.routers()
+    rt.b2[:] = [0.1, -0.1, 0.0]
+    ex_o, z_o, m_o = oracle_select(w, rt, hb)
+    tdt = {"bf16": torch.bfloat16, "f16": torch.float16}[dtype]
+    big = torch.full((C, T + pad_rows, d + pad_cols), float("nan"), dtype=tdt, device="cuda")
+    big[:, :T, :d] = to_device(hb, dtype)
+    view = big[:, :T, :]
+    g, W1, b1, w2 = routers_to_device(rt)
+    tr.set_variant(tr.VARIANT_PREFILL)
+    tr.set_prefill_form(9)
+    try:
+        assert [L["kernel"] for L in tr.prefill_plan(tr.DTYPE_CODES[dtype], C, T, d, 256, form=9)] == [10]
+        ex, z, m = tr.select_exit(view, g, w.eps, W1, b1, w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers)
+        torch.cuda.synchronize()
+    finally:
+        tr.set_prefill_form(0)
+        tr.set_variant(tr.VARIANT_AUTO)
+    report(compare_select(w.name, dtype, z.cpu().numpy(), ex.cpu().numpy(), m.cpu().numpy(), z_o, ex_o, m_o, rt.theta,
+                          w.layer_ids, 0, w.n_layers))
+
+
 @pytest.mark.parametrize("rows,slices", [(32, 8), (64, 4), (128, 2)])
 @pytest.mark.parametrize("T,dtype", [(1, "f16"), (97, "bf16"), (300, "f32")])
 def test_split_k_pair_on_padded_strides(tr, rows, slices, T, dtype):
