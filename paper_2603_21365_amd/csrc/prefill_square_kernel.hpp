@@ -3,7 +3,7 @@
 //
 // Why another form.  At width 256 the router is 256 flop per hidden byte, four fifths of what the chip's
 // nominal matrix rate allows per HBM byte, and the matrix cores do not sustain that rate: with random operands
-// the clock falls to 1.5 GHz (1.4-1.65 PFLOP/s of the nominal 2.5).  The call is bound by matrix work, by the
+// the clock falls to 1.5-1.9 GHz (1.4-1.8 PFLOP/s of the nominal 2.5).  The call is bound by matrix work, by the
 // bytes a CU draws through its own load path and by LDS, all at once, so this form spends as little as it can
 // of each: four waves, one per SIMD with the whole register file -- 256 accumulator registers for 256 rows x
 // 64 columns, 16 blocks -- so that W1' is fetched once per 256 rows (2 bytes through L2 -> CU per hidden byte
@@ -21,17 +21,19 @@
 //   - the rows' sums of squares run on the matrix cores too (square_sumsq4 below), two of a stage's eight half k-groups
 //     per wave, one on either side of the barrier: with one wave per SIMD there is nothing to hide vector-ALU work behind.
 // Wave w owns columns 64 w .. 64 w + 63 (two column blocks) of all 256 rows; its W1' fragments come straight
-// from L2 into registers, two stages ahead.  A ring stage is 64 k values (128 bytes of each row: 32 KiB), four
+// from L2 into registers, one stage ahead.  A ring stage is 64 k values (128 bytes of each row: 32 KiB), four
 // slots, up to three stages in flight; wave w transfers rows 64 w .. 64 w + 63 of each stage.
 //
 // Loads that the same wave both issues and, as LDS data, consumes: the compiler would make every LDS read
 // wait for ALL outstanding global->LDS transfers (it cannot tell the ring slots apart), which would leave
 // nothing in flight.  The k loop therefore reads LDS and W1' with inline assembly and waits with explicit
 // counts, each wait tied to the registers it covers so that no matrix step is scheduled ahead of it:
-//   vmcnt: per stage and wave 8 W1' loads (first half of the stage), then 8 transfers (second half); memory
-//     operations complete in issue order, so "at most 24 outstanding" at the top of stage s means W1'(s) has
-//     arrived, and the same count in the middle of stage s that this wave's transfers of stage s + 1 have landed;
+//   vmcnt: per stage and wave the 8 loads of W1'(s + 1) in the first half of stage s, then, behind the barrier, the 8
+//     transfers of stage s + 3; memory operations complete in issue order, so "at most 8 outstanding" at the END of
+//     stage s means that W1'(s + 1) has arrived and that this wave's transfers of stage s + 2 have landed (what the
+//     barrier of stage s + 1 promises the other waves);
 //   lgkmcnt: LDS reads return in order; the loop holds no scalar loads (checked in the generated code).
+// Nothing is on its way into a register when a stage ends (see `stage` on why).
 // 16-bit storage types, width 256, d a multiple of 64 with at least 3 stages.  A workgroup per tile: a batch fills
 // the chip from 256 rows per CU on (with fewer, the 128-row tiles of prefill_tile_kernel.hpp keep every CU busy).
 #pragma once
@@ -54,7 +56,7 @@ constexpr int kSquareMinStages = 3;                                   // the pro
 constexpr int kSquareLdsBytes = kSquareStages * kSquareStageBytes + (4 + kSquareWaves + 1) * kSquareRows * (int)sizeof(float);
 static_assert(kSquareLdsBytes <= 160 * 1024, "LDS of a CU");
 
-// Four fragments (row blocks kOff / 4096 .. + 3 of the stage at addr) into a.
+// Four fragments into a: this lane's chunk of four consecutive row blocks of a stage, the first at addr.
 __device__ __forceinline__ void square_read4(u32x4 (&a)[4], uint32_t addr) {
     asm volatile("ds_read_b128 %0, %1" : "=v"(a[0]) : "v"(addr) : "memory");
     asm volatile("ds_read_b128 %0, %1 offset:4096" : "=v"(a[1]) : "v"(addr) : "memory");
@@ -101,7 +103,8 @@ template <int v> __device__ __forceinline__ void square_load_w(u32x4 (&w)[8], ui
 // (the instruction itself takes ordinary vector registers).  The eight instructions of four fragments go round the four
 // accumulators, so that one that reads an accumulator is three instructions (24 cycles) behind the one that wrote it:
 // more than the wait states the hardware asks for between dependent matrix instructions, which the compiler cannot
-// insert inside an asm statement.
+// insert inside an asm statement; the trailing s_nop covers those it asks for before a vector-ALU instruction may touch
+// a result (the compiler does not know what the asm wrote with).
 template <int DT> __device__ __forceinline__ void square_sumsq4(const u32x4 (&a)[4], f32x4 (&acc)[4]) {
     typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
     const u32x2 l0 = {a[0][0], a[0][1]}, l1 = {a[1][0], a[1][1]}, l2 = {a[2][0], a[2][1]}, l3 = {a[3][0], a[3][1]};
@@ -110,14 +113,14 @@ template <int DT> __device__ __forceinline__ void square_sumsq4(const u32x4 (&a)
         asm("v_mfma_f32_4x4x4_16b_bf16 %0, %4, %4, %0\n\tv_mfma_f32_4x4x4_16b_bf16 %1, %5, %5, %1\n\t"
             "v_mfma_f32_4x4x4_16b_bf16 %2, %6, %6, %2\n\tv_mfma_f32_4x4x4_16b_bf16 %3, %7, %7, %3\n\t"
             "v_mfma_f32_4x4x4_16b_bf16 %0, %8, %8, %0\n\tv_mfma_f32_4x4x4_16b_bf16 %1, %9, %9, %1\n\t"
-            "v_mfma_f32_4x4x4_16b_bf16 %2, %10, %10, %2\n\tv_mfma_f32_4x4x4_16b_bf16 %3, %11, %11, %3"
+            "v_mfma_f32_4x4x4_16b_bf16 %2, %10, %10, %2\n\tv_mfma_f32_4x4x4_16b_bf16 %3, %11, %11, %3\n\ts_nop 7"
             : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3])
             : "v"(l0), "v"(l1), "v"(l2), "v"(l3), "v"(h0), "v"(h1), "v"(h2), "v"(h3));
     else
         asm("v_mfma_f32_4x4x4_16b_f16 %0, %4, %4, %0\n\tv_mfma_f32_4x4x4_16b_f16 %1, %5, %5, %1\n\t"
             "v_mfma_f32_4x4x4_16b_f16 %2, %6, %6, %2\n\tv_mfma_f32_4x4x4_16b_f16 %3, %7, %7, %3\n\t"
             "v_mfma_f32_4x4x4_16b_f16 %0, %8, %8, %0\n\tv_mfma_f32_4x4x4_16b_f16 %1, %9, %9, %1\n\t"
-            "v_mfma_f32_4x4x4_16b_f16 %2, %10, %10, %2\n\tv_mfma_f32_4x4x4_16b_f16 %3, %11, %11, %3"
+            "v_mfma_f32_4x4x4_16b_f16 %2, %10, %10, %2\n\tv_mfma_f32_4x4x4_16b_f16 %3, %11, %11, %3\n\ts_nop 7"
             : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3])
             : "v"(l0), "v"(l1), "v"(l2), "v"(l3), "v"(h0), "v"(h1), "v"(h2), "v"(h3));
 }
