@@ -845,6 +845,27 @@ def test_repeated_and_interleaved_calls_are_deterministic(tr):
     assert z is None and m is None and np.array_equal(ex.cpu().numpy(), first_a[0])
 
 
+def test_square_form_is_deterministic_and_leaves_the_arrival_words_clear(tr):
+    """The square form alternating with another shape on the same workspace: bit-identical results run to run."""
+    ws_ = synth.Workload("rep_square", 73, "bf16", 512, 16, 4, 700, None, b=256)
+    wt = synth.Workload("rep_other", 74, "bf16", 512, 16, 4, 90, None, b=256)
+    hs, ht = to_device(ws_.hidden(), "bf16"), to_device(wt.hidden(), "bf16")
+    rs, rt_ = ws_.routers(), wt.routers()
+    say("repeat/interleave, square form")
+
+    def square():
+        tr.set_prefill_form(9)
+        try:
+            return gpu_select(tr, ws_, rs, hs, packed=True, variant=tr.VARIANT_PREFILL)
+        finally:
+            tr.set_prefill_form(0)
+    first_s, first_t = square(), gpu_select(tr, wt, rt_, ht, packed=True, variant=tr.VARIANT_PREFILL)
+    for i in range(3):
+        again_s, again_t = square(), gpu_select(tr, wt, rt_, ht, packed=True, variant=tr.VARIANT_PREFILL)
+        for x, y in zip(first_s + first_t, again_s + again_t):
+            assert np.array_equal(x, y)
+
+
 def test_largest_hidden_size_and_side_stream(tr):
     import torch
     w = synth.Workload("d16384", 27, "bf16", 16384, 8, 4, 192, None)
