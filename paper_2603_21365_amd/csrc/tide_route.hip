@@ -567,20 +567,32 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
     }
     // Square form (width 256, 16-bit rows): 256-row tiles on four waves, a workgroup per tile, as many rounds as that
     // makes.  Half the W1' traffic and half the LDS reads per row of the 128-row tiles below, but twice the work per
-    // workgroup: it is the automatic choice when more than half the CUs get a tile and the last round is not mostly idle
-    // CUs -- at most one round, whole rounds, a last round at least 0.6 full, or two rounds and more.  Measured on 256 CUs
+    // workgroup: it is the automatic choice when more than half the CUs get a tile, for the whole rounds and for a last round
+    // that is more than half full.  Measured on 256 CUs
     // against the 128-row tiles (bf16, C = 8, d = 4096; us): 102 / 119 at T = 4352 (136 tiles), 107 / 123 at 4608, 126 / 145 at
     // 7168, 135-143 / 150 at 8192 (one round), 273 / 300 at 16384, 341 / 352 at C = 9 (2.25 rounds); d = 1024: 36 / 42 at 4608,
     // 43 / 52 at 8192; d = 8192: 195 / 230 at 4608, 268 / 297 at 8192; but 209 / 188 at T = 8448 (1.03 rounds), 210 / 193 at 9216,
     // 225 / 220 at 12288 (1.5), and 98 / 77 at 4096, where the 128-row tiles give every CU one.
     const bool square_fits = two_halves && dtype != TIDE_F32 && !generic_d && d / kSquareStageK >= kSquareMinStages;
+    // Beyond one round, what the whole rounds leave over goes to the 128-row one-tile kernel behind the square launch
+    // (the arrival words carry the per-token state across the two launches) if it is at most half a round: that is one
+    // round of the small tiles, which costs 0.6 of a round of 256-row tiles; more than half a round takes another round
+    // of the square form.  Just above a whole number of rounds (less than 0.175 of one left, below two rounds) the small
+    // tiles take the whole call, as they do below half a round.  Measured (bf16, C = 8, d = 4096; this rule / all 128-row
+    // tiles / all 256-row tiles, us): 190 / 190 / 198 at T = 8448, 193 / 203 / 205 at 10240, 197 / 212 / 211 at 11264,
+    // 209 / 231 / 219 at 12288, 226 / 263 / 226 at 13312, 240 / 274 / 240 at 14336, 250 / 292 / 255 at 15360; C = 9,
+    // T = 16384: 316 / 353 / 327; C = 10: 345 / 378 / 357.
+    int64_t square_tiles = 0, square_tpc = 0;
     if (square_fits && (form == 0 || form == 9)) {
-        const int64_t tpc = (T + kSquareRows - 1) / kSquareRows, tiles = C * tpc, rem = tiles % (int64_t)cus;
-        const bool even_rounds = tiles <= (int64_t)cus || rem == 0 || 5 * rem >= 3 * (int64_t)cus || tiles >= 2 * (int64_t)cus;
-        if (form == 9 || (2 * tiles > (int64_t)cus && even_rounds)) {
-            plan.launch[plan.count++] = PlannedLaunch{kKernelSquare, kSquareRows, (int)tpc, (int)tiles, 0, 1, 8u * (unsigned)((tiles + 7) / 8)};
-            return plan;
-        }
+        const int64_t tpc = (T + kSquareRows - 1) / kSquareRows, tiles = C * tpc, rem = tiles % (int64_t)cus, whole = tiles - rem;
+        square_tpc = tpc;
+        if (form == 9 || (tiles <= (int64_t)cus && 2 * tiles > (int64_t)cus) || (whole > 0 && (rem == 0 || 2 * rem > (int64_t)cus)))
+            square_tiles = tiles;
+        else if (whole >= 2 * (int64_t)cus || (whole > 0 && 40 * rem > 7 * (int64_t)cus))
+            square_tiles = whole;
+        if (square_tiles > 0)
+            plan.launch[plan.count++] = PlannedLaunch{kKernelSquare, kSquareRows, (int)tpc, (int)square_tiles, 0, 1, 8u * (unsigned)((square_tiles + 7) / 8)};
+        if (square_tiles == tiles) return plan;
     }
     // Band form: one launch, every workgroup an equal share of the checkpoint-major list of 32-row blocks, cut
     // into tiles of up to 288 rows by the kernel itself (16-bit rows, widths 64 / 128).
@@ -638,6 +650,14 @@ PrefillPlan plan_prefill(int dtype, int64_t C, int64_t T, int64_t d, int64_t b, 
             tiles_per_ckpt = (T + rows_per_wg - 1) / rows_per_wg;
             total_tiles = C * tiles_per_ckpt;
             tile_begin = c0 * tiles_per_ckpt + (wrows / rows_per_wg) * j0;
+        }
+    }
+    if (square_tiles > 0) {                        // behind whole rounds of the square form: the 128-row tiles of the rest
+        if (rows_per_wg == 128 && tile256) {
+            const int64_t c0 = square_tiles / square_tpc, j0 = square_tiles % square_tpc;
+            tile_begin = c0 * tiles_per_ckpt + 2 * j0;
+        } else {
+            plan.count = 0;                        // (never: such a batch is many 128-row tiles of a 16-bit type)
         }
     }
     const int64_t left = total_tiles - tile_begin;

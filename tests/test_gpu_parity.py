@@ -409,6 +409,27 @@ def test_width_256_square_form(tr, dtype, C, T, d, forced, what):
     assert st["max_abs_err"] < (1e-2 if dtype == "bf16" else 2e-3)
 
 
+@pytest.mark.parametrize("dtype,C,T,d,begin,what", [
+    ("bf16", 8, 12288, 256, 512, "384 tiles, 48 a checkpoint: the second launch starts a third of the way into checkpoint 5"),
+    ("f16", 6, 13000, 192, 512, "306 tiles, 51 a checkpoint (the last of 200 rows): the second launch starts one tile into checkpoint 5"),
+    ("bf16", 10, 8100, 320, 512, "320 tiles, 32 a checkpoint (the last of 164 rows): checkpoints 8 and 9 on the small tiles"),
+])
+def test_width_256_split_plan(tr, dtype, C, T, d, begin, what):
+    """Beyond one round of 256-row tiles the automatic plan is two launches: whole rounds on the square form, the
+    rest on 128-row tiles, with the per-token state carried across in the arrival words."""
+    import torch
+    if torch.cuda.get_device_properties(0).multi_processor_count != 256:
+        pytest.skip("the tile counts are chosen for 256 CUs")
+    w = synth.Workload(f"split_{dtype}_C{C}_T{T}_d{d}", 71, dtype, d, 4 * C, 4, T, None, b=256)
+    assert w.C == C
+    plan = tr.prefill_plan(tr.DTYPE_CODES[dtype], C, T, d, 256)
+    assert [L["kernel"] for L in plan] == [10, 4] and plan[0]["total_tiles"] == 256 and plan[1]["tile_begin"] == begin, what
+    rt = w.routers()
+    rt.b2[:] = np.linspace(-0.2, 0.2, C)
+    st, _, _ = run_and_compare(tr, w, w.name, rt=rt, packed=True, variant=tr.VARIANT_PREFILL)
+    assert st["max_abs_err"] < (1e-2 if dtype == "bf16" else 2e-3)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("d", [192, 256, 448])
 def test_square_form_sums_every_element(tr, dtype, d):

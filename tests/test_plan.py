@@ -58,12 +58,18 @@ def check_plan(dtype, C, T, d, b, cus, form):
             assert (dtype == tr.F32) == (k == WIDE_F32), what
             assert not (k == WIDE_F32 and halves == 2), what
         if k == SQUARE:
-            assert len(plan) == 1 and R == 256 and halves == 2 and dtype != tr.F32 and d % 128 == 0 and d >= 192, what
+            assert i == 0 and R == 256 and halves == 2 and dtype != tr.F32 and d % 128 == 0 and d >= 192, what
             assert L["tile_begin"] == 0 and wg == 8 * -(-L["total_tiles"] // 8), what
             assert (form & 0xff) in (0, 9), what
-            if form == 0:      # its own choice: more than half the CUs get a tile, and no last round of mostly idle CUs
-                n, rem = L["total_tiles"], L["total_tiles"] % cus
-                assert 2 * n > cus and (n <= cus or rem == 0 or 5 * rem >= 3 * cus or n >= 2 * cus), what
+            all_tiles = C * L["tiles_per_ckpt"]
+            if len(plan) == 2:  # whole rounds here, the rest on 128-row tiles behind it: at most half a round
+                assert form == 0 and L["total_tiles"] % cus == 0 and 0 < all_tiles - L["total_tiles"] < cus, what
+                assert 2 * (all_tiles - L["total_tiles"]) <= cus and plan[1]["kernel"] == TILE, what
+            else:
+                assert L["total_tiles"] == all_tiles, what
+                if form == 0:   # its own choice: more than half the CUs get a tile, and a last round more than half full
+                    rem = all_tiles % cus
+                    assert 2 * all_tiles > cus and (all_tiles <= cus or rem == 0 or 2 * rem > cus), what
         if k == TILE:
             assert R == 128 and dtype != tr.F32 and d % 128 == 0, what
             assert wg == 8 * -(-(L["total_tiles"] - L["tile_begin"]) // 8), what
@@ -78,7 +84,7 @@ def check_plan(dtype, C, T, d, b, cus, form):
         if d % 128 != 0:
             assert k == RING and len(plan) == 1, what
     if len(plan) == 2:
-        assert plan[0]["kernel"] in (WIDE, WIDE_F32) and plan[1]["kernel"] not in (WIDE, WIDE_F32, SPLITK), what
+        assert plan[0]["kernel"] in (WIDE, WIDE_F32, SQUARE) and plan[1]["kernel"] not in (WIDE, WIDE_F32, SPLITK, SQUARE), what
     return plan
 
 
@@ -211,8 +217,8 @@ def test_the_choices_on_the_named_workloads():
     assert kinds(tr.prefill_plan(tr.BF16, 8, 4096, 4096)) == [(TILE, 128)]                       # one tile per CU
     assert kinds(tr.prefill_plan(tr.BF16, 9, 16384, 4096)) == [(BAND, 32)]                        # 18 blocks of 32 rows per CU: the band form
     assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096)) == [(BAND, 32)]                       # 20 per CU
-    assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256)) == [(SQUARE, 256)]               # width 256: the square form, two and a half rounds of 256-row tiles
-    assert tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256)[0]["workgroups"] == 640
+    assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256)) == [(SQUARE, 256), (TILE, 128)]  # width 256: two rounds of 256-row tiles, the other half round as 128-row tiles
+    assert [L["workgroups"] for L in tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256)] == [512, 256]
     assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256, form=6)) == [(TILE, 128)]         # ... the one-tile kernel when forced: five rounds of 128-row tiles
     assert tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256, form=6)[0]["workgroups"] == 1280
     assert kinds(tr.prefill_plan(tr.BF16, 10, 16384, 4096, 256, form=4)) == [(WIDE, 128)]         # ... or the wide-tile kernel
@@ -249,11 +255,13 @@ def test_the_choices_on_the_named_workloads():
     assert kinds(tr.prefill_plan(tr.BF16, 8, 4352, 4096, 256)) == [(SQUARE, 256)]                 # ... 136 tiles of 256 rows: the square form from more than half the CUs on
     assert kinds(tr.prefill_plan(tr.BF16, 8, 7168, 4096, 256)) == [(SQUARE, 256)]                 # ... 224
     assert kinds(tr.prefill_plan(tr.BF16, 8, 8192, 4096, 256)) == [(SQUARE, 256)]                 # ... one round
-    assert kinds(tr.prefill_plan(tr.BF16, 8, 8448, 4096, 256)) == [(TILE, 128)]                   # ... one round and 8 tiles: a second round would be mostly idle CUs
-    assert kinds(tr.prefill_plan(tr.BF16, 8, 12288, 4096, 256)) == [(TILE, 128)]                  # ... a round and a half
-    assert kinds(tr.prefill_plan(tr.BF16, 8, 13312, 4096, 256)) == [(SQUARE, 256)]                # ... 1.625 rounds
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 8448, 4096, 256)) == [(TILE, 128)]                   # ... one round and 8 tiles: the small tiles take it all
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 12288, 4096, 256)) == [(SQUARE, 256), (TILE, 128)]   # ... a round and a half: one round, then 256 small tiles
+    assert [L["tile_begin"] for L in tr.prefill_plan(tr.BF16, 8, 12288, 4096, 256)] == [0, 512]
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 13312, 4096, 256)) == [(SQUARE, 256)]                # ... 1.625 rounds: two rounds
+    assert kinds(tr.prefill_plan(tr.BF16, 8, 15360, 4096, 256)) == [(SQUARE, 256)]                # ... 1.875
     assert kinds(tr.prefill_plan(tr.BF16, 8, 16384, 4096, 256)) == [(SQUARE, 256)]                # ... two rounds
-    assert kinds(tr.prefill_plan(tr.F16, 9, 16384, 4096, 256)) == [(SQUARE, 256)]                 # ... 2.25
+    assert kinds(tr.prefill_plan(tr.F16, 9, 16384, 4096, 256)) == [(SQUARE, 256), (TILE, 128)]    # ... 2.25
     assert kinds(tr.prefill_plan(tr.F32, 8, 8192, 4096, 256)) != [(SQUARE, 256)]                  # (16-bit rows only)
     assert kinds(tr.prefill_plan(tr.BF16, 8, 8192, 128, 256)) != [(SQUARE, 256)]                  # (two 64-value stages: too short a row)
     assert kinds(tr.prefill_plan(tr.F32, 8, 7168, 4096)) == [(WIDE_F32, 256)]                     # fp32 rows: 224 wide tiles
