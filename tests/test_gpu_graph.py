@@ -21,13 +21,20 @@ def tr():
     tide_route.set_variant(tide_route.VARIANT_AUTO)
 
 
-@pytest.mark.parametrize("case", ["decode_T8_raw", "decode_T8_packed", "prefill_T600_packed_then_project"])
+@pytest.mark.parametrize("case", ["decode_T8_raw", "decode_T8_packed", "prefill_T600_packed_then_project",
+                                  "prefill_width256_two_launches_then_project"])
 def test_captured_calls_replay_like_eager_calls(tr, case):
     import torch
     decode = case.startswith("decode")
-    T = 8 if decode else 600
+    two_launches = "two_launches" in case                      # width 256 beyond one round of 256-row tiles: the square
+    T = 8 if decode else 4100 if two_launches else 600         # form, then 128-row tiles; the arrival words carry the state
     dtype = "f16" if decode else "bf16"
-    w = synth.Workload(f"graph_{case}", 53, dtype, 1024, 16, 4, T, None)
+    if two_launches:
+        w = synth.Workload(f"graph_{case}", 53, dtype, 320, 40, 2, T, None, b=256)
+        if torch.cuda.get_device_properties(0).multi_processor_count == 256:
+            assert [L["kernel"] for L in tr.prefill_plan(tr.BF16, w.C, T, w.d, 256)] == [10, 4]
+    else:
+        w = synth.Workload(f"graph_{case}", 53, dtype, 1024, 16, 4, T, None)
     rt = w.routers()
     rt.b2[:] = np.linspace(-0.2, 0.2, w.C)
     g, W1, b1, w2 = routers_to_device(rt)

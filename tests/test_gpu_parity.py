@@ -412,7 +412,7 @@ def test_width_256_square_form(tr, dtype, C, T, d, forced, what):
 @pytest.mark.parametrize("dtype,C,T,d,begin,what", [
     ("bf16", 8, 12288, 256, 512, "384 tiles, 48 a checkpoint: the second launch starts a third of the way into checkpoint 5"),
     ("f16", 6, 13000, 192, 512, "306 tiles, 51 a checkpoint (the last of 200 rows): the second launch starts one tile into checkpoint 5"),
-    ("bf16", 10, 8100, 320, 512, "320 tiles, 32 a checkpoint (the last of 164 rows): checkpoints 8 and 9 on the small tiles"),
+    ("bf16", 10, 8100, 320, 512, "320 tiles, 32 a checkpoint (the last of 164 rows): checkpoints 8 and 9 on the small tiles; rows re-aligned to d = 384 first"),
 ])
 def test_width_256_split_plan(tr, dtype, C, T, d, begin, what):
     """Beyond one round of 256-row tiles the automatic plan is two launches: whole rounds on the square form, the

@@ -98,6 +98,40 @@ def test_router_eval_ws_matches_router_eval(tr):
     tr.workspace_forget(ws)
 
 
+def test_two_launch_plan_on_every_kind_of_scratch_memory(tr):
+    """Width 256 beyond one round of 256-row tiles is two launches that hand the per-token state on in the arrival
+    words: the library workspace, a caller-owned workspace and the fixed scratch array give the same bits, twice in a
+    row each (the words are back at zero after a call), and they match the oracle."""
+    import torch
+    w = synth.Workload("ws_two_launches", 47, "bf16", 384, 40, 2, 4100, None, b=256)      # C=20: 340 tiles of 256 rows
+    if torch.cuda.get_device_properties(0).multi_processor_count == 256:
+        assert [L["kernel"] for L in tr.prefill_plan(tr.BF16, w.C, w.T, w.d, 256)] == [10, 4]
+    hb = w.hidden()
+    rt = w.routers()
+    rt.b2[:] = np.linspace(-0.2, 0.2, w.C)
+    h = to_device(hb, "bf16")
+    g, W1, b1, w2 = routers_to_device(rt)
+    pk = tr.router_pack(tr.BF16, g, W1)
+    say("two launches: library workspace, caller's workspace, fixed scratch array")
+    args = (w.eps, b1, w2, rt.b2, rt.theta, w.layer_ids, 0, w.n_layers)
+    ws = new_workspace(tr, tr.workspace_bytes(tr.BF16, w.C, w.T, w.d, 256))
+    results = []
+    for _ in range(2):
+        results.append(tr.select_exit_packed(h, pk, *args, d=w.d))
+        results.append(tr.select_exit_ws(h, None, w.eps, None, pk, *args[1:], ws, d=w.d))
+        out = (torch.empty(w.T, dtype=torch.int32, device="cuda"), torch.empty((w.C, w.T), dtype=torch.float32, device="cuda"),
+               torch.empty(w.T, dtype=torch.int32, device="cuda"))
+        tr.select_exit_packed_noalloc(h, pk, *args, d=w.d, out=out)
+        results.append(out)
+    torch.cuda.synchronize()
+    ex0, z0, m0 = (o.cpu().numpy() for o in results[0])
+    for ex, z, m in results[1:]:
+        assert np.array_equal(ex.cpu().numpy(), ex0) and np.array_equal(z.cpu().numpy(), z0) and np.array_equal(m.cpu().numpy(), m0)
+    ex_o, z_o, m_o = oracle_select(w, rt, hb)
+    report(compare_select(w.name, "bf16", z0, ex0, m0, z_o, ex_o, m_o, rt.theta, w.layer_ids, 0, w.n_layers))
+    tr.workspace_forget(ws)
+
+
 def test_workspace_state_is_tracked(tr):
     """A workspace is laid out per call, state words first: a call that keeps more state than the calls since
     the last tide_workspace_init would find their data where it needs zeros.  The library refuses it
