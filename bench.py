@@ -359,8 +359,9 @@ def main() -> int:
                                       "algorithmic_bytes": by, **hbm(by, r_w["clean"]),
                                       "mfma_frac_of_bf16_peak": round(2.0 * C * T * dd * bb / r_w["clean"] / (MFMA_PEAK_TFLOPS["bf16"] * 1e12), 4)}
             del hbs, cb, pkb, Wb
-        # width 256 on larger batches (256 rows per CU and more: the square form, 256 x 256 tiles)
-        for TT in (8192, 16384):
+        # width 256 on larger batches (256 rows per CU and more: the square form, 256 x 256 tiles; at T = 12288, a round and
+        # a half, the second half round goes to 128-row tiles in a second launch)
+        for TT in (8192, 12288, 16384):
             dd, bb, nb = 4096, 256, 2
             hbs = [torch.randn((C, TT, dd), generator=gen, device="cuda").to(torch.bfloat16) for _ in range(nb)]
             Wb = torch.randn((C, dd, bb), generator=gen, device="cuda") / dd ** 0.5
@@ -374,7 +375,9 @@ def main() -> int:
             by = C * TT * dd * esz + C * dd * bb * esz + TT * 8 + C * TT * 4
             widths[f"d{dd}_b{bb}_T{TT}"] = {"us_per_call": round(r_w["clean"] * 1e6, 2), "us_per_call_median_window": round(r_w["median"] * 1e6, 2),
                                             "algorithmic_bytes": by, **hbm(by, r_w["clean"]),
-                                            "mfma_frac_of_bf16_peak": round(2.0 * C * TT * dd * bb / r_w["clean"] / (MFMA_PEAK_TFLOPS["bf16"] * 1e12), 4)}
+                                            "mfma_frac_of_bf16_peak": round(2.0 * C * TT * dd * bb / r_w["clean"] / (MFMA_PEAK_TFLOPS["bf16"] * 1e12), 4),
+                                            "launches": [{k: L[k] for k in ("kernel", "rows_per_tile", "total_tiles", "tile_begin", "workgroups")}
+                                                         for L in tr.prefill_plan(tr.BF16, C, TT, dd, bb, cus=torch.cuda.get_device_properties(0).multi_processor_count & ~7)]}
             del hbs, cb, pkb, Wb, out_t
         result["bottleneck_widths"] = {"workload": f"Table 2 pairs with b != 128: bf16, C={C}, T={T} (or the T a key names), packed weights", **widths}
 
